@@ -1,0 +1,132 @@
+"""CPU oracle for the schedule-evaluation path -- TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, single-threaded reference written from the paper.  Only the tests, the
+smoke check and the benchmark's CPU-baseline leg may import this package; the GPU
+library and its Python binding never do, and share no code with it.
+
+  kvsched_oracle.c : Phase 2 of Algorithm 1 (literal and array-profile forms), sorted-prefix
+                     Phase 1 with the F-metric, position moves, best neighbour.
+  exact.py         : Algorithm 2 (exact DP), subset / permutation / start-time brute force,
+                     lower bound -- tiny instances only.
+  check.py         : direct-definition schedule checker (memory per round, greedy-earliest).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvsched_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (a second or so)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", tmp])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a, typ):
+    return a.ctypes.data_as(typ) if a is not None else None
+
+
+class OracleError(ValueError):
+    pass
+
+
+def _check(rc):
+    if rc != 0:
+        raise OracleError(f"oracle rejected the input (code {rc})")
+
+
+def check_instance(s, o, M) -> bool:
+    s, o = _i32(s), _i32(o)
+    return _load().oracle_check_instance(ctypes.c_int32(len(s)), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M))) == 0
+
+
+def simulate(s, o, M, order, literal: bool = True):
+    """One order -> (start rounds p[n], completion rounds c[n], TEL); indexed by request id."""
+    s, o, order = _i32(s), _i32(o), _i32(order)
+    n = len(s)
+    if len(o) != n or len(order) != n:
+        raise OracleError("length mismatch")
+    p = np.zeros(n, dtype=np.int32)
+    c = np.zeros(n, dtype=np.int32)
+    tel = ctypes.c_int64(0)
+    fn = _load().oracle_simulate_literal if literal else _load().oracle_simulate_profile
+    _check(fn(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)), _ptr(order, _i32p),
+              _ptr(p, _i32p), _ptr(c, _i32p), ctypes.byref(tel)))
+    return p, c, int(tel.value)
+
+
+def simulate_many(s, o, M, orders, literal: bool = False, completions: bool = True):
+    """Rows of `orders` [C, n] -> (tel[C] int64, completion[C, n] int32 or None)."""
+    s, o, orders = _i32(s), _i32(o), _i32(orders)
+    C, n = orders.shape
+    if len(s) != n or len(o) != n:
+        raise OracleError("length mismatch")
+    tel = np.zeros(C, dtype=np.int64)
+    comp = np.zeros((C, n), dtype=np.int32) if completions else None
+    _check(_load().oracle_simulate_many(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                        _ptr(orders, _i32p), ctypes.c_int32(C), ctypes.c_int32(1 if literal else 0),
+                                        _ptr(tel, _i64p), _ptr(comp, _i32p)))
+    return tel, comp
+
+
+def sortedF(s, o, M, tie_rule: int = 0):
+    """-> (order[n], batch_end[num_batches], F[num_batches])."""
+    s, o = _i32(s), _i32(o)
+    n = len(s)
+    order = np.zeros(n, dtype=np.int32)
+    ends = np.zeros(max(n, 1), dtype=np.int32)
+    F = np.zeros(max(n, 1), dtype=np.float64)
+    nb = ctypes.c_int32(0)
+    _check(_load().oracle_sortedF(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                  ctypes.c_int32(tie_rule), _ptr(order, _i32p), _ptr(ends, _i32p), _ptr(F, _f64p),
+                                  ctypes.byref(nb)))
+    return order, ends[: nb.value].copy(), F[: nb.value].copy()
+
+
+def apply_move(base, move):
+    base = _i32(base)
+    out = np.zeros_like(base)
+    _check(_load().oracle_apply_move(ctypes.c_int32(len(base)), _ptr(base, _i32p), ctypes.c_int32(int(move[0])),
+                                     ctypes.c_int32(int(move[1])), ctypes.c_int32(int(move[2])), _ptr(out, _i32p)))
+    return out
+
+
+def best_neighbor(s, o, M, base, moves, literal: bool = False):
+    """-> (tel[K], (best_move_index, best_tel, base_tel)); ties -> lowest move index."""
+    s, o, base = _i32(s), _i32(o), _i32(base)
+    moves = _i32(moves).reshape(-1, 3)
+    K = moves.shape[0]
+    tel = np.zeros(K, dtype=np.int64)
+    res = np.zeros(3, dtype=np.int64)
+    _check(_load().oracle_best_neighbor(ctypes.c_int32(len(s)), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                        _ptr(base, _i32p), _ptr(moves, _i32p), ctypes.c_int32(K),
+                                        ctypes.c_int32(1 if literal else 0), _ptr(tel, _i64p), _ptr(res, _i64p)))
+    return tel, (int(res[0]), int(res[1]), int(res[2]))

@@ -1,0 +1,316 @@
+/*
+ * CPU oracle for the schedule-evaluation path.  TEST INFRASTRUCTURE ONLY: slow, single
+ * threaded, written from the paper; the GPU library shares no code with it and must
+ * never call it.
+ *
+ * Model (Section 2, "Batch Processing and Memory Constraint"; Optimal-IP of Section 6):
+ * rounds are 0,1,2,...; a request started at round p occupies s + j tokens of KV memory at
+ * round p + j for j = 1..o and completes at round c = p + o; at every round the occupied
+ * memory of all running requests must not exceed M.  The paper's pseudo-code (Algorithm 1)
+ * counts rounds from 1 and keeps a request for o + 1 rounds, which contradicts both the
+ * integer program and the worked Example 1 (TEL 64 / 45); the integer program's convention
+ * is the one used here.
+ *
+ * Functions
+ *   oracle_check_instance     Theorem 1's preconditions: s,o >= 1, s + o <= M.
+ *   oracle_simulate_literal   Algorithm 1, Phase 2, with the feasibility predicate of Eq. (1)
+ *                             re-evaluated from the set of running requests for every
+ *                             future round.  This is the reference semantics.
+ *   oracle_simulate_profile   The same procedure with the running set's future memory kept
+ *                             in an array instead of being re-summed (must equal the literal
+ *                             one; the tests check that).  Used where the literal form is
+ *                             too slow, and timed as the CPU baseline.
+ *   oracle_sortedF            Algorithm 1, Phase 1, with the batch chosen among the feasible
+ *                             prefixes of the requests sorted by (s+o, o, id); F of Section 4.
+ *   oracle_apply_move / oracle_best_neighbor
+ *                             position-level swap / insert neighbours of an order, scored by
+ *                             total end-to-end latency (Section 2, "Objective").
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_EINVAL (-1)
+#define ORACLE_ENOMEM (-2)
+
+/* ------------------------------------------------------------------ instance checks */
+
+int oracle_check_instance(int32_t n, const int32_t *s, const int32_t *o, int64_t M)
+{
+    if (n < 0 || M < 1) return ORACLE_EINVAL;
+    for (int32_t i = 0; i < n; ++i) {
+        if (s[i] < 1 || o[i] < 1) return ORACLE_EINVAL;
+        if ((int64_t)s[i] + (int64_t)o[i] > M) return ORACLE_EINVAL;
+    }
+    return ORACLE_OK;
+}
+
+static int is_permutation(int32_t n, const int32_t *order)
+{
+    unsigned char *seen = (unsigned char *)calloc((size_t)n + 1, 1);
+    if (!seen) return 0;
+    int ok = 1;
+    for (int32_t k = 0; k < n && ok; ++k) {
+        int32_t r = order[k];
+        if (r < 0 || r >= n || seen[r]) ok = 0;
+        else seen[r] = 1;
+    }
+    free(seen);
+    return ok;
+}
+
+/* --------------------------------------------------- Phase 2, literal (Eq. 1 re-summed) */
+
+/* Memory held at round tq by request (s, o) started at round p: the summand of
+ * M(X, t*) in Section 4, with the indicator taken inclusively and first use at p + 1. */
+static int64_t held(int32_t s, int32_t o, int64_t p, int64_t tq)
+{
+    int64_t a = tq - p;
+    return (a >= 1 && a <= (int64_t)o) ? (int64_t)s + a : 0;
+}
+
+int oracle_simulate_literal(int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                            const int32_t *order, int32_t *p_out, int32_t *c_out,
+                            int64_t *tel_out)
+{
+    if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if (!is_permutation(n, order)) return ORACLE_EINVAL;
+    int32_t *V = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1)); /* running requests */
+    int64_t *p = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!V || !p) { free(V); free(p); return ORACLE_ENOMEM; }
+    int32_t nV = 0, next = 0;
+    int64_t tel = 0;
+    for (int64_t t = 0; next < n; ++t) {
+        /* (i) requests whose last token was produced at a round <= t have left */
+        int32_t w = 0;
+        for (int32_t a = 0; a < nV; ++a)
+            if (p[V[a]] + o[V[a]] > t) V[w++] = V[a];
+        nV = w;
+        /* (ii) admit pending requests in order until the first one that does not fit */
+        while (next < n) {
+            int32_t r = order[next];
+            p[r] = t; /* tentative */
+            V[nV] = r;
+            int64_t tmax = 0;
+            for (int32_t a = 0; a <= nV; ++a) {
+                int64_t cj = p[V[a]] + o[V[a]];
+                if (cj > tmax) tmax = cj;
+            }
+            int feasible = 1;
+            for (int64_t tq = t + 1; tq <= tmax && feasible; ++tq) {
+                int64_t sum = 0;
+                for (int32_t a = 0; a <= nV; ++a)
+                    sum += held(s[V[a]], o[V[a]], p[V[a]], tq);
+                if (sum > M) feasible = 0;
+            }
+            if (!feasible) break;
+            ++nV;
+            ++next;
+            if (p_out) p_out[r] = (int32_t)t;
+            if (c_out) c_out[r] = (int32_t)(t + o[r]);
+            tel += t + o[r];
+        }
+        /* (iii) every running request produces one token; next round */
+    }
+    if (tel_out) *tel_out = tel;
+    free(V);
+    free(p);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------- Phase 2 with the future memory in an array */
+
+typedef struct {
+    int64_t *P; /* P[tq] = memory held at round tq by everything admitted so far */
+    int64_t cap;
+} profile_t;
+
+static int profile_reserve(profile_t *pf, int64_t need)
+{
+    if (need <= pf->cap) return 1;
+    int64_t cap = pf->cap ? pf->cap : 1024;
+    while (cap < need) cap *= 2;
+    int64_t *q = (int64_t *)realloc(pf->P, sizeof(int64_t) * (size_t)cap);
+    if (!q) return 0;
+    memset(q + pf->cap, 0, sizeof(int64_t) * (size_t)(cap - pf->cap));
+    pf->P = q;
+    pf->cap = cap;
+    return 1;
+}
+
+int oracle_simulate_profile(int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                            const int32_t *order, int32_t *p_out, int32_t *c_out,
+                            int64_t *tel_out)
+{
+    if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if (!is_permutation(n, order)) return ORACLE_EINVAL;
+    profile_t pf = {0, 0};
+    int64_t tel = 0, t = 0;
+    int32_t next = 0;
+    while (next < n) {
+        int32_t r = order[next];
+        if (!profile_reserve(&pf, t + o[r] + 2)) { free(pf.P); return ORACLE_ENOMEM; }
+        int feasible = 1;
+        for (int64_t j = 1; j <= o[r]; ++j)
+            if (pf.P[t + j] + s[r] + j > M) { feasible = 0; break; }
+        if (!feasible) { ++t; continue; } /* nothing more is admitted this round */
+        for (int64_t j = 1; j <= o[r]; ++j) pf.P[t + j] += s[r] + j;
+        if (p_out) p_out[r] = (int32_t)t;
+        if (c_out) c_out[r] = (int32_t)(t + o[r]);
+        tel += t + o[r];
+        ++next;
+    }
+    if (tel_out) *tel_out = tel;
+    free(pf.P);
+    return ORACLE_OK;
+}
+
+/* -------------------------------------------------------------- Phase 1 (sorted prefix) */
+
+typedef struct { int64_t w; int32_t o; int32_t id; } skey_t;
+
+static int cmp_size_o_id(const void *a, const void *b)
+{
+    const skey_t *x = (const skey_t *)a, *y = (const skey_t *)b;
+    if (x->w != y->w) return x->w < y->w ? -1 : 1;
+    if (x->o != y->o) return x->o < y->o ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+static int cmp_o_id(const void *a, const void *b)
+{
+    const skey_t *x = (const skey_t *)a, *y = (const skey_t *)b;
+    if (x->o != y->o) return x->o < y->o ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+/* sign of F(Sa, ka) - F(Sb, kb) with F = S / k^2, in exact integers */
+static int cmp_F(int64_t Sa, int64_t ka, int64_t Sb, int64_t kb)
+{
+    unsigned __int128 lhs = (unsigned __int128)Sa * (unsigned __int128)kb * (unsigned __int128)kb;
+    unsigned __int128 rhs = (unsigned __int128)Sb * (unsigned __int128)ka * (unsigned __int128)ka;
+    return (lhs > rhs) - (lhs < rhs);
+}
+
+/*
+ * tie_rule 0: among equal F take the larger batch (the text of Section 4: minimise
+ *             (F, -|X|)); tie_rule 1: take the smaller batch (the first minimum met when
+ *             scanning k upward, as Algorithm 2's final loop does).
+ * Batch feasibility is the sum of peaks, sum (s_i + o_i) <= M, as in Algorithms 2-4.
+ * Outputs: order_out[n]; batch_end_out[b] = number of requests in batches 0..b;
+ *          F_out[b] = F of batch b (one IEEE division of exact integers); *nb_out.
+ */
+int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
+                   int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *nb_out)
+{
+    if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if (tie_rule != 0 && tie_rule != 1) return ORACLE_EINVAL;
+    skey_t *rem = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
+    if (!rem) return ORACLE_ENOMEM;
+    for (int32_t i = 0; i < n; ++i) {
+        rem[i].w = (int64_t)s[i] + o[i];
+        rem[i].o = o[i];
+        rem[i].id = i;
+    }
+    qsort(rem, (size_t)n, sizeof(skey_t), cmp_size_o_id);
+    int32_t a = 0, nb = 0;
+    while (a < n) {
+        int64_t W = 0, S = 0, bestS = 0, bestk = 0;
+        for (int64_t k = 1; a + k <= n; ++k) {
+            W += rem[a + k - 1].w;
+            if (W > M) break;
+            S += rem[a + k - 1].o;
+            int better;
+            if (bestk == 0) better = 1;
+            else {
+                int c = cmp_F(S, k, bestS, bestk);
+                better = (c < 0) || (c == 0 && tie_rule == 0);
+            }
+            if (better) { bestS = S; bestk = k; }
+        }
+        /* the chosen batch runs shortest-output first */
+        qsort(rem + a, (size_t)bestk, sizeof(skey_t), cmp_o_id);
+        for (int64_t k = 0; k < bestk; ++k) order_out[a + k] = rem[a + k].id;
+        a += (int32_t)bestk;
+        if (batch_end_out) batch_end_out[nb] = a;
+        if (F_out) F_out[nb] = (double)bestS / ((double)bestk * (double)bestk);
+        ++nb;
+    }
+    if (nb_out) *nb_out = nb;
+    free(rem);
+    return ORACLE_OK;
+}
+
+/* ----------------------------------------------------------------- neighbourhood moves */
+
+/* type 0: exchange positions i and j.  type 1: take the entry at position i out and put it
+ * back so that it lands at position j.  out may not alias base. */
+int oracle_apply_move(int32_t n, const int32_t *base, int32_t type, int32_t i, int32_t j,
+                      int32_t *out)
+{
+    if (i < 0 || j < 0 || i >= n || j >= n) return ORACLE_EINVAL;
+    if (type == 0) {
+        memcpy(out, base, sizeof(int32_t) * (size_t)n);
+        out[i] = base[j];
+        out[j] = base[i];
+        return ORACLE_OK;
+    }
+    if (type == 1) {
+        int32_t w = 0;
+        for (int32_t k = 0; k < n; ++k) { /* base without position i ... */
+            if (k == i) continue;
+            if (w == j) out[w++] = base[i]; /* ... with base[i] placed at j */
+            out[w++] = base[k];
+        }
+        if (w == j) out[w++] = base[i];
+        return ORACLE_OK;
+    }
+    return ORACLE_EINVAL;
+}
+
+/* result_out = { index of the best move (lowest index among equal TEL), its TEL, TEL of base }.
+ * literal != 0 scores with oracle_simulate_literal, else with oracle_simulate_profile. */
+int oracle_best_neighbor(int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                         const int32_t *base, const int32_t *moves, int32_t K, int32_t literal,
+                         int64_t *tel_out, int64_t *result_out)
+{
+    int32_t *cand = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
+    if (!cand) return ORACLE_ENOMEM;
+    int rc;
+    int64_t base_tel = 0, best_tel = -1, best = -1;
+    rc = literal ? oracle_simulate_literal(n, s, o, M, base, 0, 0, &base_tel)
+                 : oracle_simulate_profile(n, s, o, M, base, 0, 0, &base_tel);
+    for (int32_t m = 0; m < K && rc == ORACLE_OK; ++m) {
+        rc = oracle_apply_move(n, base, moves[3 * m], moves[3 * m + 1], moves[3 * m + 2], cand);
+        if (rc != ORACLE_OK) break;
+        int64_t tel = 0;
+        rc = literal ? oracle_simulate_literal(n, s, o, M, cand, 0, 0, &tel)
+                     : oracle_simulate_profile(n, s, o, M, cand, 0, 0, &tel);
+        if (tel_out) tel_out[m] = tel;
+        if (best < 0 || tel < best_tel) { best = m; best_tel = tel; }
+    }
+    if (rc == ORACLE_OK && result_out) {
+        result_out[0] = best;
+        result_out[1] = best_tel;
+        result_out[2] = base_tel;
+    }
+    free(cand);
+    return rc;
+}
+
+/* Many orders in a row (row-major [C][n]); rows are independent.  tel_out[C];
+ * c_out is [C][n] by request id or NULL. */
+int oracle_simulate_many(int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                         const int32_t *orders, int32_t C, int32_t literal, int64_t *tel_out,
+                         int32_t *c_out)
+{
+    for (int32_t k = 0; k < C; ++k) {
+        const int32_t *row = orders + (size_t)k * (size_t)n;
+        int32_t *crow = c_out ? c_out + (size_t)k * (size_t)n : 0;
+        int rc = literal ? oracle_simulate_literal(n, s, o, M, row, 0, crow, tel_out + k)
+                         : oracle_simulate_profile(n, s, o, M, row, 0, crow, tel_out + k);
+        if (rc != ORACLE_OK) return rc;
+    }
+    return ORACLE_OK;
+}

@@ -1,0 +1,194 @@
+"""Seeded synthetic instances and candidate-order sets.
+
+The paper evaluates on LMSYS-Chat-1M conversations mixed with Arxiv long-document
+summarisation (Section 7, "Dataset Overview"); neither is available offline, so these
+generators stand in for them with the same structure: many short chat requests plus a
+minority of long-prompt requests, one KV budget M, all requests present at round 0.
+
+Nothing in this module computes anything of the scheduling method itself: it draws
+request lengths and builds candidate orders from a *given* base order by index moves.
+Both the CPU oracle's tests and the GPU path's tests/bench use it.
+"""
+from __future__ import annotations
+
+import itertools
+from dataclasses import dataclass
+
+import numpy as np
+
+SEED0 = 20250806
+
+MOVE_SWAP = 0
+MOVE_INSERT = 1
+
+
+@dataclass(frozen=True)
+class Instance:
+    name: str
+    s: np.ndarray  # int32 [n] prompt lengths
+    o: np.ndarray  # int32 [n] decode lengths
+    M: int  # KV budget in tokens
+
+    @property
+    def n(self) -> int:
+        return int(self.s.shape[0])
+
+
+def _rng(cfg: int, stream: int = 0) -> np.random.Generator:
+    return np.random.default_rng(SEED0 + cfg + 1000 * stream)
+
+
+def _chat_lengths(rng: np.random.Generator, n: int):
+    s = np.clip(np.rint(rng.lognormal(np.log(128.0), 0.8, n)), 4, 2048)
+    o = np.clip(np.rint(rng.lognormal(np.log(200.0), 0.9, n)), 1, 2048)
+    return s.astype(np.int32), o.astype(np.int32)
+
+
+def _mixed_lengths(rng: np.random.Generator, n: int):
+    s, o = _chat_lengths(rng, n)
+    is_long = rng.random(n) < 0.3
+    s_long = rng.integers(2048, 8193, n).astype(np.int32)
+    o_long = rng.integers(100, 501, n).astype(np.int32)
+    return np.where(is_long, s_long, s).astype(np.int32), np.where(is_long, o_long, o).astype(np.int32)
+
+
+def instance(cfg: int, n: int | None = None, M: int | None = None) -> Instance:
+    """The five workload configurations; `n` / `M` override the size for scaled-down tests."""
+    rng = _rng(cfg)
+    if cfg == 1:  # tiny exact
+        n = 8 if n is None else n
+        s = rng.integers(1, 9, n).astype(np.int32)
+        o = rng.integers(1, 9, n).astype(np.int32)
+        return Instance("tiny-exact", s, o, 48 if M is None else M)
+    if cfg == 2:  # short conversations
+        n = 200 if n is None else n
+        s, o = _chat_lengths(rng, n)
+        return Instance("short-conversation", s, o, 16384 if M is None else M)
+    if cfg == 3:  # mixed chat + long-document summarisation
+        n = 2000 if n is None else n
+        s, o = _mixed_lengths(rng, n)
+        return Instance("mixed-chat-summarization", s, o, 131072 if M is None else M)
+    if cfg == 4:  # receding-horizon scale
+        n = 10000 if n is None else n
+        s, o = _mixed_lengths(rng, n)
+        return Instance("receding-horizon", s, o, 1048576 if M is None else M)
+    if cfg == 5:  # adversarial bimodal
+        n = 100000 if n is None else n
+        s = np.where(rng.random(n) < 0.5, 1, 4096).astype(np.int32)
+        o = np.where(rng.random(n) < 0.5, 4096, 1).astype(np.int32)
+        return Instance("adversarial-bimodal", s, o, 2097152 if M is None else M)
+    raise ValueError(f"unknown config {cfg}")
+
+
+# ----------------------------------------------------------------------------- moves
+
+def apply_move(order: np.ndarray, move) -> np.ndarray:
+    """Position-level neighbour of a priority order.
+
+    swap(i, j): exchange the entries at positions i and j.
+    insert(i, j): take the entry at position i out and put it back so that it ends up at
+    position j; the entries in between shift by one.  i == j is the identity for both.
+    """
+    kind, i, j = int(move[0]), int(move[1]), int(move[2])
+    out = np.array(order, dtype=np.int32, copy=True)
+    if kind == MOVE_SWAP:
+        out[i], out[j] = order[j], order[i]
+    elif kind == MOVE_INSERT:
+        out = np.insert(np.delete(out, i), j, order[i]).astype(np.int32)
+    else:
+        raise ValueError("move type must be 0 (swap) or 1 (insert)")
+    return out
+
+
+def random_swap_moves(rng: np.random.Generator, count: int, lo: int, hi: int, distinct: bool = False) -> np.ndarray:
+    """`count` swap moves with both positions in [lo, hi), i != j; optionally distinct pairs."""
+    moves = np.zeros((count, 3), dtype=np.int32)
+    seen = set()
+    k = 0
+    while k < count:
+        i, j = (int(x) for x in rng.integers(lo, hi, 2))
+        if i == j:
+            continue
+        a, b = min(i, j), max(i, j)
+        if distinct:
+            if (a, b) in seen:
+                continue
+            seen.add((a, b))
+        moves[k] = (MOVE_SWAP, a, b)
+        k += 1
+    return moves
+
+
+def window_moves(rng: np.random.Generator, count: int, lo: int, hi: int) -> np.ndarray:
+    """Move 0 is the identity; the rest are half swaps, half inserts inside [lo, hi)."""
+    moves = np.zeros((count, 3), dtype=np.int32)
+    moves[0] = (MOVE_SWAP, lo, lo)
+    if hi - lo < 2:
+        moves[:, 1] = lo
+        moves[:, 2] = lo
+        return moves
+    k = 1
+    while k < count:
+        i, j = (int(x) for x in rng.integers(lo, hi, 2))
+        if i == j:
+            continue
+        moves[k] = (MOVE_SWAP if k % 2 else MOVE_INSERT, i, j)
+        k += 1
+    return moves
+
+
+def orders_from_moves(base: np.ndarray, moves: np.ndarray) -> np.ndarray:
+    rows = np.empty((moves.shape[0], base.shape[0]), dtype=np.int32)
+    for k in range(moves.shape[0]):
+        rows[k] = apply_move(base, moves[k])
+    return rows
+
+
+# ------------------------------------------------------------------------ candidates
+
+def all_permutations(n: int) -> np.ndarray:
+    """All n! orders in lexicographic order, int32 [n!, n]."""
+    return np.array(list(itertools.permutations(range(n))), dtype=np.int32)
+
+
+def candidates(cfg: int, base: np.ndarray, count: int | None = None) -> np.ndarray:
+    """Candidate order matrix [C, n] for configurations 1, 2, 3 and 5 given the base order.
+
+    cfg 1: every permutation of the n requests (lexicographic) followed by the base order.
+    cfg 2: row 0 = base; the rest = base with one random position pair exchanged.
+    cfg 3: row 0 = base; then distinct random 1-swap neighbours; the last 256 rows
+           (count // 64 when scaled down) are uniform random permutations (restarts).
+    cfg 5: row 0 = base; the rest = base with 64 random position pairs exchanged in turn.
+    """
+    base = np.asarray(base, dtype=np.int32)
+    n = base.shape[0]
+    rng = _rng(cfg, stream=1)
+    if cfg == 1:
+        return np.concatenate([all_permutations(n), base[None, :]], axis=0)
+    if cfg == 2:
+        C = 4096 if count is None else count
+        moves = random_swap_moves(rng, C - 1, 0, n)
+        return np.concatenate([base[None, :], orders_from_moves(base, moves)], axis=0)
+    if cfg == 3:
+        C = 16384 if count is None else count
+        restarts = 256 if count is None else max(1, C // 64)
+        moves = random_swap_moves(rng, C - 1 - restarts, 0, n, distinct=True)
+        rows = np.empty((C, n), dtype=np.int32)
+        rows[0] = base
+        rows[1 : C - restarts] = np.broadcast_to(base, (C - 1 - restarts, n))
+        idx = np.arange(C - 1 - restarts)
+        a, b = moves[:, 1], moves[:, 2]
+        rows[1 + idx, a] = base[b]
+        rows[1 + idx, b] = base[a]
+        for k in range(restarts):
+            rows[C - restarts + k] = rng.permutation(n).astype(np.int32)
+        return rows
+    if cfg == 5:
+        C = 1025 if count is None else count
+        rows = np.broadcast_to(base, (C, n)).copy()
+        for k in range(1, C):
+            for _ in range(64):
+                i, j = (int(x) for x in rng.integers(0, n, 2))
+                rows[k, i], rows[k, j] = rows[k, j], rows[k, i]
+        return rows
+    raise ValueError("config 4 draws its candidates per re-planning window; see window_moves()")

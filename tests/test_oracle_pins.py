@@ -1,0 +1,359 @@
+"""Pins of the CPU oracle to what the paper and the mathematics fix (no GPU)."""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import check, exact
+from paper_2508_06133_amd import workloads
+from conftest import read_golden
+
+
+def _ints(txt):
+    return [int(x) for x in txt.split()]
+
+
+def _example1(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "example1.txt"))
+    s1, o1, n1 = _ints(g["type1"])
+    s2, o2, n2 = _ints(g["type2"])
+    s = np.array([s1] * n1 + [s2] * n2, dtype=np.int32)
+    o = np.array([o1] * n1 + [o2] * n2, dtype=np.int32)
+    return g, s, o, int(g["M"])
+
+
+# ------------------------------------------------------------------ worked Example 1
+
+@pytest.mark.parametrize("literal", [True, False])
+def test_example1_tel(golden_dir, literal):
+    g, s, o, M = _example1(golden_dir)
+    mcsf = np.argsort(o, kind="stable")  # shortest output first
+    assert oracle.simulate(s, o, M, mcsf, literal=literal)[2] == int(g["tel_mcsf"])
+    order, ends, F = oracle.sortedF(s, o, M)
+    assert oracle.simulate(s, o, M, order, literal=literal)[2] == int(g["tel_sortedF"])
+
+
+def test_example1_batches_and_F(golden_dir):
+    g, s, o, M = _example1(golden_dir)
+    order, ends, F = oracle.sortedF(s, o, M)
+    assert list(ends) == [21, 22]
+    assert sorted(order[:21]) == list(range(1, 22)) and order[21] == 0
+    assert F[0] == float(Fraction(g["F_type2"])) and F[1] == float(Fraction(g["F_type1"]))
+
+
+def test_example1_start_rounds(golden_dir):
+    # "Type 2 completes at t=2, after which Type 1 is processed at t=3"
+    g, s, o, M = _example1(golden_dir)
+    order, _, _ = oracle.sortedF(s, o, M)
+    p, c, _ = oracle.simulate(s, o, M, order)
+    assert (c[1:] == 2).all() and c[0] == 3 and p[0] == 2
+
+
+# ------------------------------------------------------------ Theorem 1's instance
+
+@pytest.mark.parametrize("literal", [True, False])
+def test_theorem1_closed_form(golden_dir, literal):
+    g = read_golden(os.path.join(golden_dir, "theorem1_instance.txt"))
+    M, X, Y = int(g["M"]), int(g["X"]), int(g["Y"])
+    r = int(round(M ** 0.5))
+    assert r * r == M and Y == round(M ** 1.25)
+    s = np.array([r - 1] * X + [1] * Y, dtype=np.int32)
+    o = np.array([1] * X + [2] * Y, dtype=np.int32)
+    closed = r * sum(range(1, X // r + 1)) + X * Y // r + (2 * M // 3) * sum(range(1, 3 * Y // M + 1))
+    assert closed == int(g["tel_mcsf"])
+    order = np.arange(X + Y, dtype=np.int32)  # all of type 1, then type 2
+    assert oracle.simulate(s, o, M, order, literal=literal)[2] == closed
+
+
+def test_theorem1_reverse_order_bound():
+    # type 2 first: the proof's expression for that schedule is an upper bound on what
+    # continuous batching achieves (the type switch overlaps), and it beats MC-SF.
+    M, X, Y, r = 6561, 6561, 59049, 81
+    s = np.array([r - 1] * X + [1] * Y, dtype=np.int32)
+    o = np.array([1] * X + [2] * Y, dtype=np.int32)
+    order = np.concatenate([np.arange(X, X + Y), np.arange(X)]).astype(np.int32)
+    tel = oracle.simulate(s, o, M, order, literal=False)[2]
+    bound = (2 * M // 3) * sum(range(1, 3 * Y // M + 1)) + 6 * X * Y // M + r * sum(range(1, X // r + 1))
+    assert tel <= bound < 6705342
+
+
+# ------------------------------------------------------------ 3-Partition reduction
+
+def _has_partition(xs, T):
+    xs = list(xs)
+    if not xs:
+        return True
+    first = xs[0]
+    for a, b in itertools.combinations(range(1, len(xs)), 2):
+        if first + xs[a] + xs[b] == T:
+            rest = [x for k, x in enumerate(xs) if k not in (0, a, b)]
+            if _has_partition(rest, T):
+                return True
+    return False
+
+
+@pytest.mark.parametrize("key,m", [("yes_m2", 2), ("no_m2", 2)])
+def test_three_partition_all_orders(golden_dir, key, m):
+    g = read_golden(os.path.join(golden_dir, "three_partition.txt"))
+    T = int(g["T"])
+    xs = _ints(g[key])
+    assert sum(xs) == m * T and all(T / 4 < x < T / 2 for x in xs)
+    s = np.array(xs, dtype=np.int32)
+    o = np.ones(len(xs), dtype=np.int32)
+    perms = workloads.all_permutations(len(xs))
+    tel, _ = oracle.simulate_many(s, o, T + 3, perms, literal=True, completions=False)
+    target = 3 * m * (m + 1) // 2
+    assert target == int(g["opt_m2"])
+    assert (tel.min() == target) == _has_partition(xs, T)
+    assert tel.min() >= target
+
+
+def test_three_partition_m3(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "three_partition.txt"))
+    T = int(g["T"])
+    xs = _ints(g["yes_m3"])
+    s = np.array(xs, dtype=np.int32)
+    o = np.ones(9, dtype=np.int32)
+    assert oracle.simulate(s, o, T + 3, np.arange(9))[2] == int(g["opt_m3"]) == 18
+    # an order that splits the triples needs a fourth round
+    bad = np.array([0, 1, 3, 2, 4, 5, 6, 7, 8])
+    assert oracle.simulate(s, o, T + 3, bad)[2] > 18
+    # never four in one round (four requests need more than T + 3)
+    _, c, _ = oracle.simulate(s, o, T + 3, bad)
+    assert np.bincount(c).max() <= 3
+
+
+# ------------------------------------------------- Example 2 (two homogeneous batches)
+
+@pytest.mark.parametrize("sa,oa,na,sb,ob,nb", [(3, 2, 12, 2, 4, 10), (5, 1, 10, 1, 3, 15), (1, 5, 4, 4, 2, 4)])
+def test_example2_two_batches(sa, oa, na, sb, ob, nb):
+    # equal total memory n_A (s_A+o_A) = n_B (s_B+o_B) = M.  Run back to back, "X then Y" costs
+    # n_X o_X + n_Y (o_X + o_Y); the two orders differ by n_B o_A - n_A o_B, so the batch with
+    # the smaller o/n goes first.  Under continuous batching the second batch cannot start
+    # before the first completes when its requests are at least as long (they would still be
+    # running at the first batch's peak round, where no memory is free); shorter ones may
+    # slip in earlier, so there the expression is an upper bound.
+    M = na * (sa + oa)
+    assert M == nb * (sb + ob)
+    s = np.array([sa] * na + [sb] * nb, dtype=np.int32)
+    o = np.array([oa] * na + [ob] * nb, dtype=np.int32)
+    ab = np.arange(na + nb)
+    ba = np.concatenate([np.arange(na, na + nb), np.arange(na)])
+    tel_ab = oracle.simulate(s, o, M, ab)[2]
+    tel_ba = oracle.simulate(s, o, M, ba)[2]
+    form_ab = na * oa + nb * (oa + ob)
+    form_ba = nb * ob + na * (oa + ob)
+    assert form_ab - form_ba == nb * oa - na * ob
+    assert tel_ab == form_ab if ob >= oa else tel_ab <= form_ab
+    assert tel_ba == form_ba if oa >= ob else tel_ba <= form_ba
+    assert (tel_ab == form_ab) or (tel_ba == form_ba)
+
+
+# -------------------------------------------- literal == array-profile, direct checker
+
+def _random_instance(rng, n, smax, omax, M):
+    s = rng.integers(1, smax + 1, n).astype(np.int32)
+    o = rng.integers(1, omax + 1, n).astype(np.int32)
+    return s, o, max(M, int((s + o).max()))
+
+
+def test_literal_equals_profile_random():
+    rng = np.random.default_rng(11)
+    for trial in range(300):
+        n = int(rng.integers(1, 13))
+        s, o, M = _random_instance(rng, n, 12, 12, int(rng.integers(8, 60)))
+        order = rng.permutation(n).astype(np.int32)
+        a = oracle.simulate(s, o, M, order, literal=True)
+        b = oracle.simulate(s, o, M, order, literal=False)
+        assert (a[0] == b[0]).all() and (a[1] == b[1]).all() and a[2] == b[2]
+
+
+def test_literal_equals_profile_config2_sample():
+    inst = workloads.instance(2)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(2, base, count=6)
+    t1, c1 = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=True)
+    t2, c2 = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    assert (t1 == t2).all() and (c1 == c2).all()
+
+
+@pytest.mark.parametrize("literal", [True, False])
+def test_direct_definition_checker(literal):
+    rng = np.random.default_rng(5)
+    for trial in range(120):
+        n = int(rng.integers(1, 10))
+        s, o, M = _random_instance(rng, n, 9, 9, int(rng.integers(6, 40)))
+        order = rng.permutation(n).astype(np.int32)
+        p, c, tel = oracle.simulate(s, o, M, order, literal=literal)
+        assert (c == p + o).all() and tel == int(c.sum())
+        assert check.is_feasible(s, o, p, M)
+        assert check.is_greedy_in_order(s, o, M, order, p)
+
+
+def test_checker_rejects_planted_mistakes():
+    # the checker itself must notice a start that is one round early or late
+    s = np.array([5, 5, 5], dtype=np.int32)
+    o = np.array([3, 3, 3], dtype=np.int32)
+    M = 16
+    order = np.arange(3)
+    p, c, _ = oracle.simulate(s, o, M, order)
+    assert list(p) == [0, 0, 3]  # two fit (peak 16); the third waits for a completion
+    assert check.is_greedy_in_order(s, o, M, order, p)
+    assert not check.is_greedy_in_order(s, o, M, order, p + np.array([0, 0, 1]))
+    assert not check.is_feasible(s, o, p - np.array([0, 0, 1]), M)
+
+
+def test_admission_is_not_monotone_in_time():
+    # running (s=1,o=10) from round 0, M=12: (s=5,o=3) fits at round 0, not at 1..9, again at 10
+    s = np.array([1, 5], dtype=np.int32)
+    o = np.array([10, 3], dtype=np.int32)
+    ok = [check.fits(s, o, [0], [0], 1, t, 12) for t in range(12)]
+    assert ok == [True] + [False] * 9 + [True, True]
+    assert list(oracle.simulate(s, o, 12, [0, 1])[0]) == [0, 0]
+
+
+def test_break_on_first_miss_no_backfill():
+    # the third request would fit at round 0 but must wait behind the second
+    s = np.array([6, 6, 1], dtype=np.int32)
+    o = np.array([2, 2, 1], dtype=np.int32)
+    p, c, tel = oracle.simulate(s, o, 10, [0, 1, 2])
+    assert list(p) == [0, 2, 2] and tel == 2 + 4 + 3
+
+
+def test_instance_rules():
+    assert not oracle.check_instance([5], [6], 10)  # s + o > M can never run
+    assert not oracle.check_instance([0], [1], 10)
+    assert not oracle.check_instance([1], [0], 10)
+    with pytest.raises(oracle.OracleError):
+        oracle.simulate([5], [6], 10, [0])
+    with pytest.raises(oracle.OracleError):
+        oracle.simulate([1, 1], [1, 1], 10, [0, 0])  # not a permutation
+
+
+# ------------------------------------------- lower bound, true optimum, all 8! orders
+
+def test_config1_all_orders_bounds():
+    inst = workloads.instance(1)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(1, base)
+    assert rows.shape == (40321, 8)
+    tel, comp = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=True)
+    lb = exact.lower_bound(inst.s, inst.o, inst.M)
+    assert tel.min() >= lb
+    assert (comp >= inst.o[None, :]).all()
+    assert tel[-1] >= tel.min()
+    # a sample of rows against the direct-definition checker
+    for k in range(0, 40321, 2017):
+        p = comp[k] - inst.o
+        assert check.is_feasible(inst.s, inst.o, p, inst.M)
+        assert check.is_greedy_in_order(inst.s, inst.o, inst.M, rows[k], p)
+
+
+def test_true_optimum_small():
+    rng = np.random.default_rng(3)
+    for trial in range(12):
+        n = 4
+        s = rng.integers(1, 6, n).astype(np.int32)
+        o = rng.integers(1, 4, n).astype(np.int32)
+        M = max(int((s + o).max()), int(rng.integers(6, 14)))
+        opt, _ = exact.optimal_start_times(s, o, M)
+        perms = workloads.all_permutations(n)
+        tel, _ = oracle.simulate_many(s, o, M, perms, literal=True, completions=False)
+        assert exact.lower_bound(s, o, M) <= opt <= tel.min()
+
+
+def test_lower_bound_on_workloads():
+    for cfg, n in [(2, 200), (3, 300)]:
+        inst = workloads.instance(cfg, n=n)
+        base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+        assert oracle.simulate(inst.s, inst.o, inst.M, base, literal=False)[2] >= exact.lower_bound(inst.s, inst.o, inst.M)
+
+
+# ---------------------------------------------------------------- Phase 1 and F-metric
+
+def test_dp_equals_subset_bruteforce_and_lemma1():
+    rng = np.random.default_rng(8)
+    cases = [workloads.instance(1)]
+    for trial in range(25):
+        n = int(rng.integers(2, 9))
+        s = rng.integers(1, 9, n).astype(np.int32)
+        o = rng.integers(1, 9, n).astype(np.int32)
+        cases.append(workloads.Instance("rnd", s, o, int(rng.integers(16, 49))))
+    for inst in cases:
+        F_dp, ks_dp, subs = exact.dp_best_batch(inst.s, inst.o, inst.M)
+        F_bf, ks_bf = exact.brute_best_batch(inst.s, inst.o, inst.M)
+        assert F_dp == F_bf and ks_dp == ks_bf
+        # Lemma 1 (output balance) on the batch the text selects: the largest minimiser
+        X = sorted(subs[max(ks_dp)])
+        oo = inst.o[X]
+        assert oo.mean() > 0.5 * oo.max()
+        # the sorted-prefix batch is a feasible subset, so it cannot beat the exact optimum
+        _, ends, F = oracle.sortedF(inst.s, inst.o, inst.M)
+        k = int(ends[0])
+        assert Fraction(int(inst.o[oracle.sortedF(inst.s, inst.o, inst.M)[0][:k]].sum()), k * k) >= F_dp
+
+
+def test_sortedF_structure_random():
+    rng = np.random.default_rng(21)
+    for trial in range(60):
+        n = int(rng.integers(1, 40))
+        s = rng.integers(1, 30, n).astype(np.int32)
+        o = rng.integers(1, 12, n).astype(np.int32)
+        M = int(rng.integers(int((s + o).max()), 200))
+        for tie in (0, 1):
+            order, ends, F = oracle.sortedF(s, o, M, tie)
+            assert sorted(order) == list(range(n)) and ends[-1] == n
+            a = 0
+            for b, e in enumerate(ends):
+                batch = order[a:e]
+                assert int((s[batch] + o[batch]).sum()) <= M
+                key = list(zip(o[batch], batch))
+                assert key == sorted(key)  # shortest output first, ties by id
+                assert F[b] == int(o[batch].sum()) / float(len(batch) ** 2)
+                a = e
+
+
+def test_tie_rule():
+    # o = {1, 3}: F({first}) = 1 = F({both}) = 4/4
+    s = np.array([1, 1], dtype=np.int32)
+    o = np.array([1, 3], dtype=np.int32)
+    _, ends0, F0 = oracle.sortedF(s, o, 100, 0)
+    _, ends1, F1 = oracle.sortedF(s, o, 100, 1)
+    assert list(ends0) == [2] and F0[0] == 1.0  # the text: prefer the larger batch
+    assert list(ends1) == [1, 2] and list(F1) == [1.0, 3.0]  # first minimum when scanning k upward
+
+
+def test_sort_key_is_size_then_output_then_id():
+    s = np.array([4, 2, 3, 3], dtype=np.int32)
+    o = np.array([1, 3, 2, 2], dtype=np.int32)  # every s + o = 5
+    order, ends, _ = oracle.sortedF(s, o, 5, 0)  # one request per batch
+    assert list(order) == [0, 2, 3, 1] and list(ends) == [1, 2, 3, 4]
+
+
+# --------------------------------------------------------------------- neighbourhood
+
+def test_apply_move_matches_numpy():
+    rng = np.random.default_rng(2)
+    base = rng.permutation(9).astype(np.int32)
+    for kind in (0, 1):
+        for i in range(9):
+            for j in range(9):
+                assert (oracle.apply_move(base, (kind, i, j)) == workloads.apply_move(base, (kind, i, j))).all()
+    assert list(workloads.apply_move(np.arange(5), (1, 1, 3))) == [0, 2, 3, 1, 4]
+    assert list(workloads.apply_move(np.arange(5), (1, 3, 0))) == [3, 0, 1, 2, 4]
+    assert list(workloads.apply_move(np.arange(5), (0, 1, 3))) == [0, 3, 2, 1, 4]
+
+
+def test_best_neighbor_bruteforce():
+    inst = workloads.instance(1)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    moves = np.array([(k, i, j) for k in (0, 1) for i in range(8) for j in range(8)], dtype=np.int32)
+    tel, (best, best_tel, base_tel) = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=True)
+    rows = workloads.orders_from_moves(base, moves)
+    ref, _ = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=True, completions=False)
+    assert (tel == ref).all()
+    assert best == int(np.argmin(ref)) and best_tel == int(ref.min())  # argmin = first minimum
+    assert base_tel == oracle.simulate(inst.s, inst.o, inst.M, base)[2] == tel[0]  # move 0 is swap(0,0)
