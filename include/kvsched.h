@@ -1,0 +1,137 @@
+/*
+ * libkvsched -- batched evaluation of candidate schedules for LLM serving under a KV-cache
+ * budget (offline, backlogged model of "LLM Serving Optimization with Variable Prefill and
+ * Decode Lengths").  C ABI; every entry point runs hand-written HIP kernels for gfx950 on
+ * one GPU.  There is no CPU fallback.
+ *
+ * Model (Section 2, "Batch Processing and Memory Constraint", with the timing of the
+ * integer program Optimal-IP in Section 6): rounds are 0,1,2,...; request i has prompt
+ * length s_i and decode length o_i; started at round p it holds s_i + j tokens of KV memory
+ * at round p + j (j = 1..o_i) and completes at round c_i = p + o_i; the memory held by all
+ * running requests may not exceed M at any round.  All n requests are present at round 0.
+ *
+ * Conventions common to all entry points
+ *   - Every array argument is a DEVICE pointer owned by the caller (for instance the
+ *     data_ptr() of a torch tensor on the context's device), contiguous, row-major.
+ *     The library neither frees nor keeps them after the call's work has run.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *     enqueued on it; outputs are valid once the caller has synchronised the stream.  A call
+ *     blocks the host only for the short length scan described at kvsched_set_o_max().
+ *   - Return value: KVSCHED_OK or a negative KVSCHED_E* code for errors the host can see
+ *     (null pointers, sizes, unsupported ranges, HIP runtime failures).  Faults only the
+ *     device can see (a length < 1, s_i + o_i > M, an order row that is not a permutation,
+ *     a malformed move) set bits in a device status word, readable with
+ *     kvsched_device_status(); the affected candidates get tel = -1.
+ *   - int32 for lengths, ids, orders, rounds; int64 for M and total latencies.
+ *   - A context is bound to one device and may be used by one host thread at a time.
+ */
+#ifndef KVSCHED_H
+#define KVSCHED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvsched_ctx kvsched_ctx;
+
+#define KVSCHED_OK 0
+#define KVSCHED_EINVAL (-1)  /* null pointer, non-positive size, bad enum value            */
+#define KVSCHED_ERANGE (-2)  /* a size beyond what the kernels support (see each call)     */
+#define KVSCHED_EHIP (-3)    /* a HIP runtime call failed                                  */
+#define KVSCHED_ENOMEM (-4)  /* device scratch could not be allocated                      */
+
+/* bits of the device status word */
+#define KVSCHED_DEV_BAD_LENGTH 1 /* some s_i < 1, o_i < 1 or s_i + o_i > M (Theorem 1's premise) */
+#define KVSCHED_DEV_BAD_ORDER 2  /* an order row is not a permutation of 0..n-1               */
+#define KVSCHED_DEV_BAD_MOVE 4   /* a move has type outside {0,1} or a position outside [0,n) */
+#define KVSCHED_DEV_O_MAX 8      /* a decode length exceeds the bound given to kvsched_set_o_max() */
+
+#define KVSCHED_MOVE_SWAP 0   /* exchange the entries at positions i and j                  */
+#define KVSCHED_MOVE_INSERT 1 /* take the entry at position i out, put it back at position j */
+
+#define KVSCHED_TIE_LARGER 0  /* equal F: the larger batch (Section 4: minimise (F, -|X|))   */
+#define KVSCHED_TIE_SMALLER 1 /* equal F: the smaller batch (first minimum scanning k upward) */
+
+/* largest supported decode length (slots of the per-timeline future-memory ring) */
+#define KVSCHED_MAX_O 16384
+
+/* Create / destroy a context on HIP device `device_id`.  The context owns a few KB of device
+ * and pinned host scratch plus buffers that grow with the largest n / K seen. */
+int kvsched_create(kvsched_ctx **out, int device_id);
+void kvsched_destroy(kvsched_ctx *ctx);
+
+/* Static description of a return code. */
+const char *kvsched_strerror(int status);
+
+/* The kernels size their future-memory ring from the largest decode length.  By default
+ * every call first scans o[] on the device and waits for that one number (the only host
+ * synchronisation a call makes).  A caller that knows an upper bound on o_i can set it here
+ * (1..KVSCHED_MAX_O) to make calls fully asynchronous; 0 restores the scan.  A length above
+ * the bound is reported as KVSCHED_DEV_O_MAX and the affected candidates get tel = -1. */
+int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound);
+
+/* Wait for `stream` and return (in *status_out) the device status word of the last call
+ * made on this context: an OR of KVSCHED_DEV_* bits, 0 when the data was well-formed. */
+int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out);
+
+/*
+ * Phase 2 of Algorithm 1 ("Scheduling Execution") for C candidate priority orders at once.
+ * Each row of `orders` is turned into a continuous-batching timeline: at every round the
+ * pending requests are admitted in row order for as long as the memory check of Eq. (1)
+ * (peak over all future rounds) holds, stopping at the first request that does not fit.
+ *
+ *   orders          [C][n] int32, each row a permutation of 0..n-1
+ *   s, o            [n]    int32, 1 <= s_i, 1 <= o_i <= KVSCHED_MAX_O, s_i + o_i <= M
+ *   M               KV budget, 1 <= M < 2^30
+ *   tel_out         [C]    int64: total end-to-end latency sum_i c_i of each row (Section 2,
+ *                   "Objective"), or -1 for a faulty row
+ *   completion_out  [C][n] int32 or NULL: c_i, indexed by REQUEST ID (not by position)
+ *   common_prefix   hint: the first common_prefix positions are identical in all rows
+ *                   (0 = no hint).  Never changes results; a wrong hint is detected and
+ *                   reported as KVSCHED_DEV_BAD_ORDER.
+ * ERANGE: n * (ring size) >= 2^31 (round counters are int32), M >= 2^30, o_max bound too large.
+ */
+int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n,
+                     const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out,
+                     int32_t *completion_out, int32_t common_prefix, void *stream);
+
+/*
+ * Phase 1 of Algorithm 1 ("Batch Construction") with the batch chosen among the feasible
+ * prefixes of the remaining requests sorted by (s_i + o_i, o_i, i): for prefix length k with
+ * sum_{first k}(s_i + o_i) <= M, F(k) = sum_{first k} o_i / k^2 (Section 4); the batch is the
+ * prefix of least F (ties per `tie_rule`), emitted in nondecreasing o_i (ties by id); repeat
+ * on what remains.  F is compared in exact integers; reported as one IEEE double division.
+ *
+ *   order_out        [n] int32: the Sorted-F priority order
+ *   batch_end_out    [n] int32: batch_end_out[b] = number of requests in batches 0..b; only
+ *                    the first *num_batches_out entries are written
+ *   F_out            [n] double: F of batch b; same extent
+ *   num_batches_out  [1] int32
+ */
+int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                    int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                    int32_t *num_batches_out, void *stream);
+
+/*
+ * Local-search step on a priority order: every move is applied to `base_order` on the fly
+ * (no [K][n] matrix is materialised), the resulting order is run through Phase 2 exactly
+ * as in kvsched_simulate, and the move of least total latency is returned, the lowest move
+ * index among equals.
+ *
+ *   base_order  [n]    int32 permutation
+ *   moves       [K][3] int32 {type, i, j}: KVSCHED_MOVE_SWAP / KVSCHED_MOVE_INSERT on
+ *               positions i, j in [0, n); i == j is the identity
+ *   tel_out     [K]    int64 or NULL: latency of every neighbour (-1 for a malformed move)
+ *   result_out  [3]    int64: {index of the best move or -1 if none is valid, its total
+ *               latency, total latency of base_order itself}
+ */
+int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n,
+                          const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o,
+                          int64_t M, int64_t *tel_out, int64_t *result_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVSCHED_H */

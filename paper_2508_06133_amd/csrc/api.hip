@@ -1,0 +1,228 @@
+// C ABI of libkvsched: argument checks, context and scratch management, kernel sequencing.
+// All arithmetic of the method runs in the kernels of simulate.hip and sortedf.hip.
+#include "kvsched_internal.h"
+
+#include <new>
+
+namespace {
+
+constexpr int64_t kMaxM = (int64_t)1 << 30;
+
+int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
+{
+    if (bytes <= ctx->scratch_bytes) return KVSCHED_OK;
+    if (ctx->d_scratch) {
+        // kernels of earlier calls may still be reading the old buffer
+        if (hipDeviceSynchronize() != hipSuccess) return KVSCHED_EHIP;
+        (void)hipFree(ctx->d_scratch);
+        ctx->d_scratch = nullptr;
+        ctx->scratch_bytes = 0;
+    }
+    size_t cap = (bytes + ((size_t)1 << 20)) & ~(((size_t)1 << 20) - 1);
+    if (hipMalloc(&ctx->d_scratch, cap) != hipSuccess) return KVSCHED_ENOMEM;
+    ctx->scratch_bytes = cap;
+    return KVSCHED_OK;
+}
+
+int32_t ring_slots_for(int32_t o_max)
+{
+    int32_t h = 64;
+    while (h < o_max) h <<= 1;
+    return h;
+}
+
+// Enqueue the length scan; unless the caller supplied a bound, wait for the largest decode
+// length.  *o_bound_out is what the timeline kernels size their ring from.
+int scan_and_bound(kvsched_ctx *ctx, const int32_t *s, const int32_t *o, int32_t n, int64_t M, hipStream_t st,
+                   int32_t *o_bound_out)
+{
+    int rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, ctx->o_max_bound, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    if (ctx->o_max_bound > 0) {
+        *o_bound_out = ctx->o_max_bound;
+        return KVSCHED_OK;
+    }
+    if (hipMemcpyAsync(ctx->h_words, ctx->d_words, sizeof(int32_t) * KVS_W_COUNT, hipMemcpyDeviceToHost, st) !=
+        hipSuccess)
+        return KVSCHED_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return KVSCHED_EHIP;
+    int32_t omax = ctx->h_words[KVS_W_OMAX];
+    if (omax > KVSCHED_MAX_O) return KVSCHED_ERANGE;
+    *o_bound_out = omax < 1 ? 1 : omax;
+    return KVSCHED_OK;
+}
+
+int check_common(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M)
+{
+    if (!ctx || !s || !o || n < 1 || M < 1) return KVSCHED_EINVAL;
+    if (M >= kMaxM) return KVSCHED_ERANGE;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    return KVSCHED_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvsched_create(kvsched_ctx **out, int device_id)
+{
+    if (!out) return KVSCHED_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess) return KVSCHED_EHIP;
+    if (device_id < 0 || device_id >= count) return KVSCHED_EINVAL;
+    if (hipSetDevice(device_id) != hipSuccess) return KVSCHED_EHIP;
+    kvsched_ctx *ctx = new (std::nothrow) kvsched_ctx();
+    if (!ctx) return KVSCHED_ENOMEM;
+    ctx->device = device_id;
+    ctx->o_max_bound = 0;
+    ctx->d_words = nullptr;
+    ctx->h_words = nullptr;
+    ctx->d_scratch = nullptr;
+    ctx->scratch_bytes = 0;
+    if (hipMalloc((void **)&ctx->d_words, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess ||
+        hipHostMalloc((void **)&ctx->h_words, sizeof(int32_t) * KVS_W_COUNT, hipHostMallocDefault) != hipSuccess ||
+        hipMemset(ctx->d_words, 0, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess) {
+        kvsched_destroy(ctx);
+        return KVSCHED_ENOMEM;
+    }
+    *out = ctx;
+    return KVSCHED_OK;
+}
+
+void kvsched_destroy(kvsched_ctx *ctx)
+{
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    if (ctx->d_words) (void)hipFree(ctx->d_words);
+    if (ctx->h_words) (void)hipHostFree(ctx->h_words);
+    if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+    delete ctx;
+}
+
+const char *kvsched_strerror(int status)
+{
+    switch (status) {
+        case KVSCHED_OK: return "ok";
+        case KVSCHED_EINVAL: return "invalid argument (null pointer, non-positive size or bad enum)";
+        case KVSCHED_ERANGE: return "size outside the supported range";
+        case KVSCHED_EHIP: return "HIP runtime call failed";
+        case KVSCHED_ENOMEM: return "out of device or host memory";
+        default: return "unknown status";
+    }
+}
+
+int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound)
+{
+    if (!ctx || o_max_bound < 0) return KVSCHED_EINVAL;
+    if (o_max_bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
+    ctx->o_max_bound = o_max_bound;
+    return KVSCHED_OK;
+}
+
+int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out)
+{
+    if (!ctx || !status_out) return KVSCHED_EINVAL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(ctx->h_words, ctx->d_words, sizeof(int32_t) * KVS_W_COUNT, hipMemcpyDeviceToHost, st) !=
+        hipSuccess)
+        return KVSCHED_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return KVSCHED_EHIP;
+    *status_out = ctx->h_words[KVS_W_STATUS];
+    return KVSCHED_OK;
+}
+
+int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n, const int32_t *s,
+                     const int32_t *o, int64_t M, int64_t *tel_out, int32_t *completion_out, int32_t common_prefix,
+                     void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!orders || !tel_out || C < 1 || common_prefix < 0 || common_prefix > n) return KVSCHED_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    int32_t o_bound = 0;
+    rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound);
+    if (rc != KVSCHED_OK) return rc;
+    const int32_t H = ring_slots_for(o_bound);
+    if ((int64_t)n * (int64_t)H >= kMaxM) return KVSCHED_ERANGE;  // rounds are int32
+    SimParams p;
+    p.src.orders = orders;
+    p.src.base = nullptr;
+    p.src.moves = nullptr;
+    p.C = C;
+    p.n = n;
+    p.s = s;
+    p.o = o;
+    p.M = (int32_t)M;
+    p.tel_out = tel_out;
+    p.completion_out = completion_out;
+    p.d_words = ctx->d_words;
+    p.o_bound = o_bound;
+    rc = kvs_launch_simulate(p, H, st);
+    if (rc != KVSCHED_OK) return rc;
+    return kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
+}
+
+int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
+                    int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
+                    void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!order_out || !batch_end_out || !F_out || !num_batches_out) return KVSCHED_EINVAL;
+    if (tie_rule != KVSCHED_TIE_LARGER && tie_rule != KVSCHED_TIE_SMALLER) return KVSCHED_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    rc = ensure_scratch(ctx, kvs_sortedF_scratch_bytes(n));
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    return kvs_launch_sortedF(n, s, o, (int32_t)M, tie_rule, order_out, batch_end_out, F_out, num_batches_out,
+                              ctx->d_scratch, ctx->d_words, st);
+}
+
+int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,
+                          const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out, int64_t *result_out,
+                          void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    rc = ensure_scratch(ctx, sizeof(int64_t) * ((size_t)K + 1));
+    if (rc != KVSCHED_OK) return rc;
+    int64_t *tel = (int64_t *)ctx->d_scratch;  // [K] neighbours, then the base order itself
+    int32_t o_bound = 0;
+    rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound);
+    if (rc != KVSCHED_OK) return rc;
+    const int32_t H = ring_slots_for(o_bound);
+    if ((int64_t)n * (int64_t)H >= kMaxM) return KVSCHED_ERANGE;
+    SimParams p;
+    p.src.orders = nullptr;
+    p.src.base = base_order;
+    p.src.moves = moves;
+    p.C = K + 1;
+    p.n = n;
+    p.s = s;
+    p.o = o;
+    p.M = (int32_t)M;
+    p.tel_out = tel;
+    p.completion_out = nullptr;
+    p.d_words = ctx->d_words;
+    p.o_bound = o_bound;
+    rc = kvs_launch_simulate(p, H, st);
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_check_moves(moves, K, n, tel, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_check_orders(base_order, 1, n, tel + K, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_argmin(tel, K, result_out, st);
+    if (rc != KVSCHED_OK) return rc;
+    if (tel_out &&
+        hipMemcpyAsync(tel_out, tel, sizeof(int64_t) * (size_t)K, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return KVSCHED_EHIP;
+    return KVSCHED_OK;
+}
+
+}  // extern "C"

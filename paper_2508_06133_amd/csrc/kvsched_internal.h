@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libkvsched.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/kvsched.h"
+
+// Device-side scratch words owned by a context (int32 each).
+enum {
+    KVS_W_STATUS = 0,  // OR of KVSCHED_DEV_* bits for the call in flight
+    KVS_W_OMAX = 1,    // largest decode length found by the length scan
+    KVS_W_COUNT = 8
+};
+
+struct kvsched_ctx {
+    int device;
+    int32_t o_max_bound;   // 0 = scan o[] on every call
+    int32_t *d_words;      // [KVS_W_COUNT] device
+    int32_t *h_words;      // [KVS_W_COUNT] pinned host mirror
+    void *d_scratch;       // grows on demand
+    size_t scratch_bytes;
+};
+
+// How a candidate's order is presented to the timeline kernel.
+struct OrderSource {
+    const int32_t *orders;  // [C][n] explicit rows, or NULL
+    const int32_t *base;    // [n] base order when moves are applied on the fly
+    const int32_t *moves;   // [K][3]; candidate K (one past the last move) is the base itself
+};
+
+struct SimParams {
+    OrderSource src;
+    int32_t C;  // number of timelines to run
+    int32_t n;
+    const int32_t *s;
+    const int32_t *o;
+    int32_t M;
+    int64_t *tel_out;         // [C]
+    int32_t *completion_out;  // [C][n] or NULL
+    int32_t *d_words;
+    int32_t o_bound;          // lengths above this are reported, not simulated
+};
+
+// simulate.hip
+int kvs_launch_scan_lengths(const int32_t *s, const int32_t *o, int32_t n, int32_t M, int32_t o_bound,
+                            int32_t *d_words, hipStream_t st);
+int kvs_launch_simulate(const SimParams &p, int32_t ring_slots, hipStream_t st);
+int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t *tel_out, int32_t *d_words,
+                            hipStream_t st);
+int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *tel_out, int32_t *d_words,
+                           hipStream_t st);
+int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, hipStream_t st);
+
+// sortedf.hip
+size_t kvs_sortedF_scratch_bytes(int32_t n);
+int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule,
+                       int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
+                       void *scratch, int32_t *d_words, hipStream_t st);

@@ -1,0 +1,290 @@
+// Sorted-F order construction: Phase 1 of Algorithm 1 ("Batch Construction") with the batch
+// taken among the feasible prefixes of the remaining requests sorted by (s+o, o, id), scored
+// by the F-metric of Section 4, F(X) = sum o_i / |X|^2.
+//
+// Since every batch is a prefix of what remains, the remaining requests stay sorted: one key
+// sort serves all batches, and batch b is the segment [a_b, a_b + k*) of the sorted array.
+// One workgroup does the whole construction:
+//   1. stable LSD radix sort of the ids by o            -> requests in (o, id) order
+//   2. continue the same sort on s+o                    -> requests in (s+o, o, id) order
+//   3. prefix sums W (of s+o) and S (of o) over that order
+//   4. per batch: feasible extent K by a two-level search on W, argmin over k <= K of S_k / k^2
+//      compared in exact 128-bit integers, tie rule applied; F reported as one fp64 division
+//   5. stable sort of the (o, id)-ordered ids by batch number -> each batch in nondecreasing o
+#include "kvsched_internal.h"
+
+namespace {
+
+constexpr int TPB = 1024;
+constexpr int NWAVES = TPB / 64;
+
+struct Lds {
+    int hist[256];
+    int wcount[NWAVES][256];  // per tile: lanes of wave w holding digit d
+    int woff[NWAVES][256];    // per tile: output offset of wave w's first lane with digit d
+    long long scan_a[NWAVES];
+    long long scan_b[NWAVES];
+    long long carry_a, carry_b;
+    long long red_S[NWAVES];
+    int red_k[NWAVES];
+    long long best_S;
+    int best_k;
+    int flag;
+};
+
+__device__ __forceinline__ unsigned long long lanemask_lt()
+{
+    return (1ull << (threadIdx.x & 63)) - 1ull;
+}
+
+// One stable counting pass on an 8-bit digit of key(id).  in/out: [n] ids.
+template <class KeyFn>
+__device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key, Lds &L)
+{
+    const int tid = threadIdx.x, wave = tid >> 6;
+    if (tid < 256) L.hist[tid] = 0;
+    for (int i = tid; i < NWAVES * 256; i += TPB) (&L.wcount[0][0])[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += TPB) atomicAdd(&L.hist[(key(in[i]) >> shift) & 255], 1);
+    __syncthreads();
+    if (tid == 0) {  // exclusive scan of the 256 digit counts -> running output base per digit
+        int run = 0;
+        for (int d = 0; d < 256; ++d) {
+            const int c = L.hist[d];
+            L.hist[d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (int tile = 0; tile < n; tile += TPB) {
+        const int i = tile + tid;
+        const bool valid = i < n;
+        const int id = valid ? in[i] : 0;
+        const int d = valid ? ((key(id) >> shift) & 255) : 256;
+        // lanes of this wave holding the same digit
+        unsigned long long peers = ~0ull;
+#pragma unroll
+        for (int b = 0; b < 9; ++b) {
+            const unsigned long long bal = __builtin_amdgcn_ballot_w64((d >> b) & 1);
+            peers &= ((d >> b) & 1) ? bal : ~bal;
+        }
+        const int rank = __popcll(peers & lanemask_lt());
+        if (valid && rank == 0) L.wcount[wave][d] = __popcll(peers);
+        __syncthreads();
+        if (tid < 256) {  // per digit: offsets of the waves in order, advance the running base
+            int off = L.hist[tid];
+            for (int w = 0; w < NWAVES; ++w) {
+                const int c = L.wcount[w][tid];
+                L.wcount[w][tid] = 0;  // ready for the next tile
+                L.woff[w][tid] = off;
+                off += c;
+            }
+            L.hist[tid] = off;
+        }
+        __syncthreads();
+        if (valid) out[L.woff[wave][d] + rank] = id;
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ int bits_of(long long v)
+{
+    return v <= 0 ? 1 : 64 - __clzll(v);
+}
+
+// sign of Sa/ka^2 - Sb/kb^2 in exact integers (Sa, Sb < 2^63; ka, kb < 2^31)
+__device__ __forceinline__ int cmp_F(long long Sa, int ka, long long Sb, int kb)
+{
+    const unsigned long long qa = (unsigned long long)ka * (unsigned long long)ka;
+    const unsigned long long qb = (unsigned long long)kb * (unsigned long long)kb;
+    const unsigned long long l_hi = __umul64hi((unsigned long long)Sa, qb), l_lo = (unsigned long long)Sa * qb;
+    const unsigned long long r_hi = __umul64hi((unsigned long long)Sb, qa), r_lo = (unsigned long long)Sb * qa;
+    if (l_hi != r_hi) return l_hi < r_hi ? -1 : 1;
+    if (l_lo != r_lo) return l_lo < r_lo ? -1 : 1;
+    return 0;
+}
+
+// is prefix (Sa, ka) a better batch than (Sb, kb)?  kb == 0 means "none yet".
+__device__ __forceinline__ bool better(long long Sa, int ka, long long Sb, int kb, int tie_rule)
+{
+    if (ka == 0) return false;
+    if (kb == 0) return true;
+    const int c = cmp_F(Sa, ka, Sb, kb);
+    if (c != 0) return c < 0;
+    return tie_rule == KVSCHED_TIE_LARGER ? ka > kb : ka < kb;
+}
+
+__global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
+                                                      int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out,
+                                                      double *F_out, int32_t *num_batches_out, int *buf0, int *buf1,
+                                                      int *by_o, long long *cumW, long long *cumS, int *batch_of,
+                                                      int32_t *words)
+{
+    __shared__ Lds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // ---- well-formedness and key widths
+    int omax = 0, wmax = 0, bad = 0;
+    for (int i = tid; i < n; i += TPB) {
+        const int sv = s[i], ov = o[i];
+        if (sv < 1 || ov < 1 || (long long)sv + ov > (long long)M) bad = 1;
+        omax = max(omax, ov);
+        wmax = max(wmax, (sv < 1 || ov < 1) ? 0 : (int)min((long long)sv + ov, (long long)M));
+    }
+    if (tid == 0) L.flag = 0;
+    __syncthreads();
+    if (bad) atomicOr(&L.flag, 1);
+    if (tid < 2) L.hist[tid] = 0;
+    __syncthreads();
+    atomicMax(&L.hist[0], omax);
+    atomicMax(&L.hist[1], wmax);
+    __syncthreads();
+    omax = L.hist[0];
+    wmax = L.hist[1];
+    const bool any_bad = L.flag != 0;
+    __syncthreads();
+    if (any_bad) {  // a request that can never run: report, emit no batches
+        if (tid == 0) {
+            atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+            *num_batches_out = 0;
+        }
+        return;
+    }
+
+    // ---- 1/2: key sorts (ids start in id order, every pass is stable)
+    for (int i = tid; i < n; i += TPB) buf0[i] = i;
+    __syncthreads();
+    int *cur = buf0, *alt = buf1;
+    auto key_o = [o](int id) { return o[id]; };
+    auto key_w = [s, o](int id) { return s[id] + o[id]; };
+    for (int shift = 0; shift < bits_of(omax); shift += 8) {
+        radix_pass(cur, alt, n, shift, key_o, L);
+        int *t = cur; cur = alt; alt = t;
+    }
+    for (int i = tid; i < n; i += TPB) by_o[i] = cur[i];
+    __syncthreads();
+    for (int shift = 0; shift < bits_of(wmax); shift += 8) {
+        radix_pass(cur, alt, n, shift, key_w, L);
+        int *t = cur; cur = alt; alt = t;
+    }
+    const int *sorted = cur;  // (s+o, o, id) ascending
+
+    // ---- 3: inclusive prefix sums over the sorted order; cumW[0] = cumS[0] = 0
+    if (tid == 0) {
+        L.carry_a = 0;
+        L.carry_b = 0;
+        cumW[0] = 0;
+        cumS[0] = 0;
+    }
+    __syncthreads();
+    for (int tile = 0; tile < n; tile += TPB) {
+        const int i = tile + tid;
+        long long w = 0, q = 0;
+        if (i < n) {
+            const int id = sorted[i];
+            q = o[id];
+            w = (long long)s[id] + q;
+        }
+        for (int d = 1; d < 64; d <<= 1) {
+            const long long uw = __shfl_up(w, d), uq = __shfl_up(q, d);
+            if (lane >= d) { w += uw; q += uq; }
+        }
+        if (lane == 63) { L.scan_a[wave] = w; L.scan_b[wave] = q; }
+        __syncthreads();
+        long long offw = L.carry_a, offq = L.carry_b;
+        for (int v = 0; v < wave; ++v) { offw += L.scan_a[v]; offq += L.scan_b[v]; }
+        if (i < n) { cumW[i + 1] = w + offw; cumS[i + 1] = q + offq; }
+        __syncthreads();
+        if (tid == TPB - 1) { L.carry_a = w + offw; L.carry_b = q + offq; }
+        __syncthreads();
+    }
+    __threadfence_block();
+
+    // ---- 4: batches
+    int a = 0, nb = 0;
+    while (a < n) {
+        const int rem = n - a;
+        const long long W0 = cumW[a], S0 = cumS[a];
+        // feasible extent K = max{k : W_k <= M}; W is increasing, so count the feasible probes
+        const int stride = (rem + TPB - 1) / TPB;
+        const long long k1 = (long long)(tid + 1) * stride;  // coarse probes, a prefix of them fits
+        const bool ok1 = k1 <= rem && (cumW[a + k1] - W0 <= (long long)M);
+        int K = __syncthreads_count(ok1) * stride;
+        {
+            const long long k2 = (long long)K + tid + 1;  // fine probes inside the next stride
+            const bool ok2 = tid < stride && k2 <= rem && (cumW[a + k2] - W0 <= (long long)M);
+            K += __syncthreads_count(ok2);
+        }
+        if (K < 1) {  // cannot happen for well-formed input; never spin
+            if (tid == 0) atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+            break;
+        }
+        long long bS = 0;
+        int bk = 0;
+        for (int k = tid + 1; k <= K; k += TPB) {
+            const long long Sk = cumS[a + k] - S0;
+            if (better(Sk, k, bS, bk, tie_rule)) { bS = Sk; bk = k; }
+        }
+        for (int d = 32; d > 0; d >>= 1) {
+            const long long oS = __shfl_down(bS, d);
+            const int ok = __shfl_down(bk, d);
+            if (better(oS, ok, bS, bk, tie_rule)) { bS = oS; bk = ok; }
+        }
+        if (lane == 0) { L.red_S[wave] = bS; L.red_k[wave] = bk; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int v = 1; v < NWAVES; ++v)
+                if (better(L.red_S[v], L.red_k[v], bS, bk, tie_rule)) { bS = L.red_S[v]; bk = L.red_k[v]; }
+            L.best_S = bS;
+            L.best_k = bk;
+            batch_end_out[nb] = a + bk;
+            F_out[nb] = (double)bS / ((double)bk * (double)bk);
+        }
+        __syncthreads();
+        const int kstar = L.best_k;
+        for (int i = tid; i < kstar; i += TPB) batch_of[sorted[a + i]] = nb;
+        __syncthreads();
+        a += kstar;
+        ++nb;
+    }
+    if (tid == 0) *num_batches_out = nb;
+    __threadfence_block();
+    __syncthreads();
+
+    // ---- 5: order the (o, id)-sorted ids by batch number (stable)
+    int *src = by_o;
+    int *dst = (cur == buf0) ? buf1 : buf0;  // `sorted` is no longer needed after step 4, but keep it intact
+    int *other = (int *)cur;
+    auto key_b = [batch_of](int id) { return batch_of[id]; };
+    bool first = true;
+    for (int shift = 0; shift < bits_of(nb - 1); shift += 8) {
+        radix_pass(src, dst, n, shift, key_b, L);
+        if (first) { src = dst; dst = other; first = false; }
+        else { int *t = src; src = dst; dst = t; }
+    }
+    for (int i = tid; i < n; i += TPB) order_out[i] = src[i];
+}
+
+}  // namespace
+
+size_t kvs_sortedF_scratch_bytes(int32_t n)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    return np * (4 * sizeof(int) + 2 * sizeof(long long)) + 256;
+}
+
+int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule,
+                       int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
+                       void *scratch, int32_t *d_words, hipStream_t st)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    long long *cumW = (long long *)scratch;
+    long long *cumS = cumW + np;
+    int *buf0 = (int *)(cumS + np);
+    int *buf1 = buf0 + np;
+    int *by_o = buf1 + np;
+    int *batch_of = by_o + np;
+    hipLaunchKernelGGL(sortedF_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, tie_rule, order_out, batch_end_out,
+                       F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, batch_of, d_words);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}

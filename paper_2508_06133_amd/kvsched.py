@@ -1,0 +1,143 @@
+"""ctypes binding over libkvsched.so -- argument marshalling only.
+
+Same names as the C ABI (see include/kvsched.h).  Inputs and outputs are torch tensors on
+the context's GPU; torch is used for device memory and the current stream, nothing else.
+Importing this module loads the shared library and raises if it has not been built:
+there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+OK = 0
+TIE_LARGER, TIE_SMALLER = 0, 1
+MOVE_SWAP, MOVE_INSERT = 0, 1
+DEV_BAD_LENGTH, DEV_BAD_ORDER, DEV_BAD_MOVE, DEV_O_MAX = 1, 2, 4, 8
+
+
+class KvschedError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what} failed: {code} ({strerror(code)})")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    path = _build.lib_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it with `python -m paper_2508_06133_amd.build` "
+            "(hipcc, gfx950); libkvsched has no CPU fallback"
+        )
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.kvsched_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+    lib.kvsched_destroy.argtypes = [vp]
+    lib.kvsched_destroy.restype = None
+    lib.kvsched_strerror.argtypes = [ctypes.c_int]
+    lib.kvsched_strerror.restype = ctypes.c_char_p
+    lib.kvsched_set_o_max.argtypes = [vp, i32]
+    lib.kvsched_device_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
+    lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, vp, vp, vp, vp, vp]
+    lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def strerror(code: int) -> str:
+    return _lib.kvsched_strerror(int(code)).decode()
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what}: expected a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Context:
+    """Owns a kvsched_ctx on one device; methods mirror the C entry points."""
+
+    def __init__(self, device: int = 0):
+        self._h = ctypes.c_void_p()
+        self.device = int(device)
+        rc = _lib.kvsched_create(ctypes.byref(self._h), self.device)
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_create")
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            _lib.kvsched_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def set_o_max(self, bound: int):
+        rc = _lib.kvsched_set_o_max(self._h, int(bound))
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_set_o_max")
+
+    def device_status(self) -> int:
+        out = ctypes.c_int32(0)
+        rc = _lib.kvsched_device_status(self._h, _stream(), ctypes.byref(out))
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_device_status")
+        return int(out.value)
+
+    def simulate(self, orders, s, o, M, completions: bool = True, common_prefix: int = 0, tel_out=None,
+                 completion_out=None):
+        """orders [C, n] -> (tel [C] int64, completion [C, n] int32 by request id or None)."""
+        C, n = orders.shape
+        dev = orders.device
+        tel = torch.empty(C, dtype=torch.int64, device=dev) if tel_out is None else tel_out
+        comp = None
+        if completions:
+            comp = torch.empty((C, n), dtype=torch.int32, device=dev) if completion_out is None else completion_out
+        rc = _lib.kvsched_simulate(self._h, _dev(orders, torch.int32, "orders"), C, n, _dev(s, torch.int32, "s"),
+                                   _dev(o, torch.int32, "o"), int(M), _dev(tel, torch.int64, "tel_out"),
+                                   _dev(comp, torch.int32, "completion_out") if comp is not None else None,
+                                   int(common_prefix), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_simulate")
+        return tel, comp
+
+    def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER):
+        """-> (order [n] int32, batch_end [n] int32, F [n] float64, num_batches [1] int32); the first
+        num_batches entries of batch_end / F are meaningful."""
+        n = s.shape[0]
+        dev = s.device
+        order = torch.empty(n, dtype=torch.int32, device=dev)
+        ends = torch.zeros(n, dtype=torch.int32, device=dev)
+        F = torch.zeros(n, dtype=torch.float64, device=dev)
+        nb = torch.zeros(1, dtype=torch.int32, device=dev)
+        rc = _lib.kvsched_sortedF(self._h, n, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
+                                  int(tie_rule), order.data_ptr(), ends.data_ptr(), F.data_ptr(), nb.data_ptr(),
+                                  _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_sortedF")
+        return order, ends, F, nb
+
+    def best_neighbor(self, base_order, moves, s, o, M, want_tel: bool = True):
+        """-> (tel [K] int64 or None, result [3] int64 = {best move, its TEL, TEL of base})."""
+        n = base_order.shape[0]
+        K = moves.shape[0]
+        dev = base_order.device
+        tel = torch.empty(K, dtype=torch.int64, device=dev) if want_tel else None
+        res = torch.empty(3, dtype=torch.int64, device=dev)
+        rc = _lib.kvsched_best_neighbor(self._h, _dev(base_order, torch.int32, "base_order"), n,
+                                        _dev(moves, torch.int32, "moves"), K, _dev(s, torch.int32, "s"),
+                                        _dev(o, torch.int32, "o"), int(M),
+                                        tel.data_ptr() if tel is not None else None, res.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_best_neighbor")
+        return tel, res

@@ -1,0 +1,45 @@
+"""The C-ABI library loads and exports every symbol the header declares (no compute calls)."""
+import ctypes
+import os
+import re
+
+from conftest import ROOT
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvsched.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvsched_[a-zA-Z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_calls():
+    names = _declared_functions()
+    for must in ("kvsched_simulate", "kvsched_sortedF", "kvsched_best_neighbor", "kvsched_create", "kvsched_destroy"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2508_06133_amd import build
+
+    assert os.path.exists(build.lib_path()), "libkvsched.so has not been built"
+    lib = ctypes.CDLL(build.lib_path())
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_strerror_needs_no_gpu():
+    from paper_2508_06133_amd import build
+
+    lib = ctypes.CDLL(build.lib_path())
+    lib.kvsched_strerror.restype = ctypes.c_char_p
+    assert lib.kvsched_strerror(0) == b"ok"
+    assert b"range" in lib.kvsched_strerror(-2)
+
+
+def test_product_path_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2508_06133_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in src and "from oracle" not in src, f

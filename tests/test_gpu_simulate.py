@@ -1,0 +1,194 @@
+"""GPU parity of kvsched_simulate with the CPU oracle: bit-exact completion rounds and TEL."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2508_06133_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    from paper_2508_06133_amd import kvsched
+
+    assert torch.cuda.is_available()
+    c = kvsched.Context(0)
+    yield c
+    c.close()
+
+
+def _gpu_simulate(ctx, inst_s, inst_o, M, rows, completions=True):
+    import torch
+
+    dev = torch.device("cuda:0")
+    s = torch.from_numpy(np.ascontiguousarray(inst_s, dtype=np.int32)).to(dev)
+    o = torch.from_numpy(np.ascontiguousarray(inst_o, dtype=np.int32)).to(dev)
+    orders = torch.from_numpy(np.ascontiguousarray(rows, dtype=np.int32)).to(dev)
+    tel, comp = ctx.simulate(orders, s, o, M, completions=completions)
+    torch.cuda.synchronize()
+    return tel.cpu().numpy(), (comp.cpu().numpy() if comp is not None else None), ctx.device_status()
+
+
+def _assert_equal(tel_g, comp_g, tel_o, comp_o, what):
+    bad = np.nonzero(tel_g != tel_o)[0]
+    assert bad.size == 0, f"{what}: TEL differs at rows {bad[:8]} gpu={tel_g[bad[:8]]} oracle={tel_o[bad[:8]]}"
+    if comp_g is not None:
+        assert (comp_g == comp_o).all(), f"{what}: completion rounds differ"
+
+
+def test_config1_all_orders(ctx):
+    inst = workloads.instance(1)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(1, base)
+    print(f"config 1: n={inst.n} C={rows.shape[0]}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=True)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 1")
+
+
+def test_config2_full(ctx):
+    inst = workloads.instance(2)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(2, base)
+    print(f"config 2: n={inst.n} C={rows.shape[0]}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 2")
+    # a few rows against the literal form of the algorithm as well
+    tel_l, comp_l = oracle.simulate_many(inst.s, inst.o, inst.M, rows[:4], literal=True)
+    _assert_equal(tel_g[:4], comp_g[:4], tel_l, comp_l, "config 2 literal")
+
+
+def test_config3_scaled_full(ctx):
+    inst = workloads.instance(3, n=333)  # ragged: 5 blocks of 64 + 13
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(3, base, count=640)
+    print(f"config 3 scaled: n={inst.n} C={rows.shape[0]}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 3 scaled")
+
+
+def test_config3_full_size_sampled(ctx):
+    # the launch the benchmark times: n = 2000, C = 16384; the oracle checks a sample of rows
+    inst = workloads.instance(3)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(3, base)
+    print(f"config 3: n={inst.n} C={rows.shape[0]}", flush=True)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert status == 0
+    sample = np.unique(np.concatenate([np.arange(0, 16384, 128), np.arange(16384 - 256, 16384, 16), [0, 1, 16383]]))
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows[sample], literal=False)
+    _assert_equal(tel_g[sample], comp_g[sample], tel_o, comp_o, "config 3 sample")
+    # properties that hold for every row at any size
+    assert (comp_g >= inst.o[None, :]).all()
+    assert (tel_g == comp_g.astype(np.int64).sum(axis=1)).all()
+    lb = oracle.exact.lower_bound(inst.s, inst.o, inst.M) if hasattr(oracle, "exact") else None
+    from oracle import exact
+
+    assert tel_g.min() >= exact.lower_bound(inst.s, inst.o, inst.M)
+
+
+def test_config5_scaled_and_full_rows(ctx):
+    inst = workloads.instance(5, n=3000)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(5, base, count=24)
+    print(f"config 5 scaled: n={inst.n} C={rows.shape[0]}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 5 scaled")
+
+
+@pytest.mark.parametrize("n,omax,smax,M,C", [
+    (1, 5, 5, 10, 3), (2, 64, 10, 80, 5), (63, 64, 40, 600, 33), (64, 65, 40, 700, 17), (65, 130, 300, 3000, 40),
+    (200, 9, 9, 60, 257), (130, 1000, 2000, 20000, 20), (97, 2048, 512, 30000, 12), (50, 4096, 100, 50000, 9),
+    (40, 5000, 100, 60000, 5),
+])
+def test_random_instances_across_ring_sizes(ctx, n, omax, smax, M, C):
+    rng = np.random.default_rng(1000 + n + omax)
+    s = rng.integers(1, smax + 1, n).astype(np.int32)
+    o = rng.integers(1, omax + 1, n).astype(np.int32)
+    o[rng.integers(0, n)] = omax  # the ring size is decided by the longest decode
+    M = max(M, int((s.astype(np.int64) + o).max()))
+    rows = np.stack([rng.permutation(n).astype(np.int32) for _ in range(C)])
+    print(f"random: n={n} omax={omax} M={M} C={C}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(s, o, M, rows, literal=(n <= 100 and omax <= 200))
+    tel_g, comp_g, status = _gpu_simulate(ctx, s, o, M, rows)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o, "random")
+    tel_g2, none, _ = _gpu_simulate(ctx, s, o, M, rows, completions=False)
+    assert none is None and (tel_g2 == tel_o).all()
+
+
+def test_paper_example1_on_gpu(ctx):
+    s = np.array([63] + [1] * 21, dtype=np.int32)
+    o = np.array([1] + [2] * 21, dtype=np.int32)
+    rows = np.stack([np.arange(22), np.concatenate([np.arange(1, 22), [0]])]).astype(np.int32)
+    tel_g, comp_g, status = _gpu_simulate(ctx, s, o, 64, rows)
+    assert status == 0 and list(tel_g) == [64, 45]  # shortest-output-first vs Sorted-F order
+
+
+def test_faulty_rows_and_lengths(ctx):
+    from paper_2508_06133_amd import kvsched
+
+    s = np.array([3, 4, 5, 6], dtype=np.int32)
+    o = np.array([2, 2, 3, 1], dtype=np.int32)
+    rows = np.array([[0, 1, 2, 3], [0, 0, 2, 3], [3, 2, 1, 0], [0, 1, 2, 7]], dtype=np.int32)
+    tel_g, comp_g, status = _gpu_simulate(ctx, s, o, 12, rows)
+    assert status == kvsched.DEV_BAD_ORDER
+    assert tel_g[1] == -1 and tel_g[3] == -1
+    ref, _ = oracle.simulate_many(s, o, 12, rows[[0, 2]], literal=True)
+    assert tel_g[0] == ref[0] and tel_g[2] == ref[1]
+    # a request that can never run (s + o > M): every row is rejected, nothing hangs
+    tel_g, _, status = _gpu_simulate(ctx, s, o, 6, rows[[0, 2]])
+    assert status & kvsched.DEV_BAD_LENGTH and (tel_g == -1).all()
+    o0 = o.copy()
+    o0[2] = 0
+    tel_g, _, status = _gpu_simulate(ctx, s, o0, 12, rows[[0, 2]])
+    assert status & kvsched.DEV_BAD_LENGTH and (tel_g == -1).all()
+
+
+def test_o_max_bound_makes_calls_asynchronous_and_is_checked(ctx):
+    from paper_2508_06133_amd import kvsched
+
+    inst = workloads.instance(2, n=100)
+    rows = np.stack([np.random.default_rng(k).permutation(100).astype(np.int32) for k in range(8)])
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    try:
+        ctx.set_o_max(2048)
+        tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o, "bounded")
+        ctx.set_o_max(int(inst.o.max()) - 1)  # too small: reported, not simulated
+        tel_g, _, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+        assert status & kvsched.DEV_O_MAX and (tel_g == -1).all()
+    finally:
+        ctx.set_o_max(0)
+
+
+def test_host_side_errors(ctx):
+    import torch
+    from paper_2508_06133_amd import kvsched
+
+    dev = torch.device("cuda:0")
+    s = torch.ones(4, dtype=torch.int32, device=dev)
+    o = torch.ones(4, dtype=torch.int32, device=dev)
+    orders = torch.arange(4, dtype=torch.int32, device=dev)[None, :].contiguous()
+    with pytest.raises(kvsched.KvschedError) as e:
+        ctx.simulate(orders, s, o, 0)
+    assert e.value.code == -1
+    with pytest.raises(kvsched.KvschedError) as e:
+        ctx.simulate(orders, s, o, 1 << 31)
+    assert e.value.code == -2
+    o_big = torch.full((4,), 20000, dtype=torch.int32, device=dev)
+    with pytest.raises(kvsched.KvschedError) as e:
+        ctx.simulate(orders, s, o_big, 1 << 20)
+    assert e.value.code == -2  # longest decode beyond the supported ring
+    with pytest.raises(TypeError):
+        ctx.simulate(orders.to(torch.int64), s, o, 10)

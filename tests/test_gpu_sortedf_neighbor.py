@@ -1,0 +1,138 @@
+"""GPU parity of kvsched_sortedF and kvsched_best_neighbor with the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2508_06133_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    from paper_2508_06133_amd import kvsched
+
+    assert torch.cuda.is_available()
+    c = kvsched.Context(0)
+    yield c
+    c.close()
+
+
+def _to_dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda:0")
+
+
+def _gpu_sortedF(ctx, s, o, M, tie):
+    import torch
+
+    order, ends, F, nb = ctx.sortedF(_to_dev(s), _to_dev(o), M, tie)
+    torch.cuda.synchronize()
+    k = int(nb.item())
+    return order.cpu().numpy(), ends.cpu().numpy()[:k], F.cpu().numpy()[:k]
+
+
+def _check_sortedF(ctx, s, o, M, what):
+    for tie in (0, 1):
+        print(f"sortedF {what}: n={len(s)} M={M} tie={tie}", flush=True)
+        order_o, ends_o, F_o = oracle.sortedF(s, o, M, tie)
+        order_g, ends_g, F_g = _gpu_sortedF(ctx, s, o, M, tie)
+        assert len(ends_g) == len(ends_o) and (ends_g == ends_o).all(), what
+        assert (order_g == order_o).all(), what
+        assert np.allclose(F_g, F_o, rtol=1e-12, atol=0.0), what  # one IEEE division of exact integers
+        assert ctx.device_status() == 0
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_sortedF_configs(ctx, cfg):
+    inst = workloads.instance(cfg)
+    _check_sortedF(ctx, inst.s, inst.o, inst.M, f"config {cfg}")
+
+
+@pytest.mark.parametrize("n,smax,omax,M", [(1, 3, 3, 6), (2, 1, 3, 100), (64, 20, 6, 90), (65, 20, 6, 2000),
+                                           (1023, 50, 4, 300), (1024, 50, 300, 5000), (1025, 3, 2, 40),
+                                           (5000, 2, 2, 64), (3000, 4000, 4000, 9000), (2500, 1, 1, 1 << 20)])
+def test_sortedF_random_and_tie_heavy(ctx, n, smax, omax, M):
+    rng = np.random.default_rng(n * 7 + omax)
+    s = rng.integers(1, smax + 1, n).astype(np.int32)
+    o = rng.integers(1, omax + 1, n).astype(np.int32)
+    M = max(M, int((s.astype(np.int64) + o).max()))
+    _check_sortedF(ctx, s, o, M, "random")
+
+
+def test_sortedF_example1(ctx):
+    s = np.array([63] + [1] * 21, dtype=np.int32)
+    o = np.array([1] + [2] * 21, dtype=np.int32)
+    order, ends, F = _gpu_sortedF(ctx, s, o, 64, 0)
+    assert list(ends) == [21, 22] and order[21] == 0
+    assert F[0] == 42 / 441 and F[1] == 1.0
+
+
+def test_sortedF_bad_lengths(ctx):
+    from paper_2508_06133_amd import kvsched
+
+    s = np.array([3, 9], dtype=np.int32)
+    o = np.array([2, 4], dtype=np.int32)
+    order, ends, F = _gpu_sortedF(ctx, s, o, 12, 0)
+    assert len(ends) == 0 and ctx.device_status() & kvsched.DEV_BAD_LENGTH
+
+
+def _gpu_best(ctx, s, o, M, base, moves):
+    import torch
+
+    tel, res = ctx.best_neighbor(_to_dev(base), _to_dev(moves), _to_dev(s), _to_dev(o), M)
+    torch.cuda.synchronize()
+    return tel.cpu().numpy(), tuple(int(x) for x in res.cpu().numpy())
+
+
+def test_best_neighbor_config1_every_move(ctx):
+    inst = workloads.instance(1)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    moves = np.array([(k, i, j) for k in (0, 1) for i in range(8) for j in range(8)], dtype=np.int32)
+    tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=True)
+    tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+    assert (tel_g == tel_o).all() and res_g == res_o
+
+
+@pytest.mark.parametrize("cfg,n,K", [(2, 200, 1500), (3, 450, 700), (5, 1000, 40)])
+def test_best_neighbor_windows(ctx, cfg, n, K):
+    inst = workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rng = np.random.default_rng(cfg)
+    lo = n // 5
+    moves = workloads.window_moves(rng, K, lo, min(n, lo + 512))
+    moves[-1] = (1, 0, n - 1)  # the longest shifts
+    moves[-2] = (1, n - 1, 0)
+    moves[-3] = (0, 0, n - 1)
+    print(f"best_neighbor config {cfg}: n={n} K={K}", flush=True)
+    tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=False)
+    tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+    assert (tel_g == tel_o).all() and res_g == res_o
+    assert ctx.device_status() == 0
+
+
+def test_best_neighbor_ties_take_lowest_index(ctx):
+    # identical requests: every move gives the same TEL, so move 0 must win
+    s = np.full(10, 3, dtype=np.int32)
+    o = np.full(10, 2, dtype=np.int32)
+    moves = workloads.window_moves(np.random.default_rng(0), 50, 0, 10)[1:]
+    tel_o, res_o = oracle.best_neighbor(s, o, 12, np.arange(10), moves, literal=True)
+    tel_g, res_g = _gpu_best(ctx, s, o, 12, np.arange(10, dtype=np.int32), moves)
+    assert res_o[0] == 0 and res_g == res_o and (tel_g == tel_o).all()
+
+
+def test_best_neighbor_bad_moves(ctx):
+    from paper_2508_06133_amd import kvsched
+
+    inst = workloads.instance(2, n=40)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    moves = np.array([(0, 1, 2), (2, 1, 2), (0, -1, 3), (1, 5, 40), (1, 5, 39)], dtype=np.int32)
+    tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+    assert ctx.device_status() == kvsched.DEV_BAD_MOVE
+    assert list(tel_g[1:4]) == [-1, -1, -1]
+    good = moves[[0, 4]]
+    tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, good, literal=False)
+    assert tel_g[0] == tel_o[0] and tel_g[4] == tel_o[1]
+    assert res_g[0] == (0, 4)[res_o[0]] and res_g[1] == res_o[1] and res_g[2] == res_o[2]
