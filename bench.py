@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the schedule-evaluation hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input, everything already
+resident in HBM: Sorted-F order construction (Phase 1), evaluation of the C candidate orders
+(Phase 2: timelines, total latency and completion rounds per candidate), argmin over the
+candidates.  Workload: configuration 3 ("mixed chat + summarisation": n = 2000 requests,
+M = 131072 tokens, C = 16384 candidates = Sorted-F order, 16127 distinct 1-swap neighbours,
+256 random restarts).
+
+Prints ONE JSON line:  candidate schedules evaluated per second, the roofline object of the
+dominant kernel (integer-VALU bound; algorithmic lane-ops from the outputs of the run) and the
+CPU oracle timed on the same rows on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Peak plain-ALU rate of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one int32 op per
+# lane per clock (the fp32 vector peak of 157.3 TFLOP/s counts an FMA as two and packs two).
+PEAK_INT32_LANE_OPS = 256 * 4 * 16 * 2.4e9
+PEAK_HBM_BYTES = 8.0e12
+OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for one request
+CFG = 3
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="candidate rows the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build evaluates schedules on ONE GPU; --gpus must be 1 "
+              "(candidates would shard across GPUs, see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2508_06133_amd import kvsched, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libkvsched has no CPU path", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ctx = kvsched.Context(0)
+
+    inst = workloads.instance(CFG)
+    n, M = inst.n, inst.M
+    s = torch.from_numpy(inst.s).to(dev)
+    o = torch.from_numpy(inst.o).to(dev)
+
+    # The candidate set is built around the Sorted-F order; that order comes from the library.
+    order_d, ends_d, F_d, nb_d = ctx.sortedF(s, o, M)
+    torch.cuda.synchronize()
+    base = order_d.cpu().numpy()
+    rows_h = workloads.candidates(CFG, base)
+    C = rows_h.shape[0]
+    orders = torch.from_numpy(rows_h).to(dev)
+    tel = torch.empty(C, dtype=torch.int64, device=dev)
+    comp = torch.empty((C, n), dtype=torch.int32, device=dev)
+    best = torch.empty(2, dtype=torch.int64, device=dev)
+
+    ctx.enable_timing(True)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ctx.sortedF(s, o, M)
+        ctx.simulate(orders, s, o, M, tel_out=tel, completion_out=comp)
+        ctx.argmin(tel, result_out=best)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    kernel_ms = []
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+        kernel_ms.append(ctx.last_timeline_ms())  # events on the stream the kernel ran on
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    status = ctx.device_status()
+    if status != 0:
+        print(f"bench.py: device status {status}", file=sys.stderr)
+        return 1
+
+    # ---- accounting from the outputs of the run (outside the timed region)
+    tel_h = tel.cpu().numpy()
+    o64 = o.to(torch.int64)
+    sum_o = int(o64.sum().item())
+    last_req = orders[:, -1].to(torch.int64)
+    p_last = comp.gather(1, last_req[:, None]).squeeze(1).to(torch.int64) - o64[last_req]
+    visits = int((p_last + 2 * sum_o).sum().item())  # rounds waited through + window checked + window updated
+    lane_ops = OPS_PER_VISIT * visits
+    k_ms = float(np.mean(kernel_ms))
+    achieved = lane_ops / (k_ms * 1e-3)
+    hbm_bytes = C * (4 * n + 4 * n + 8) + 8 * n
+    result = {
+        "metric": "candidate schedules evaluated/s (n=2000 mixed)",
+        "value": C * args.steps / wall,
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "config 3: mixed chat+summarization, n=2000, M=131072, C=16384 "
+                               "(Sorted-F order + 16127 1-swap neighbours + 256 random restarts)",
+                   "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item())},
+        "request_rounds_per_s": C * sum_o * args.steps / wall,
+        "gpu_ms_per_step": gpu_ms / args.steps,
+        "timeline_kernel_ms": k_ms,
+        "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
+        "roofline": {
+            "bound": "alu",
+            "kernel": "timeline_kernel<2048,4,false>",
+            "achieved": achieved / 1e12,
+            "peak": PEAK_INT32_LANE_OPS / 1e12,
+            "unit": "Tlane-op/s (int32)",
+            "frac": achieved / PEAK_INT32_LANE_OPS,
+            "traffic": None,
+            "visits_per_launch": visits,
+            "ops_per_visit": OPS_PER_VISIT,
+            "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / (k_ms * 1e-3) / 1e9,
+                    "frac_of_8TBps": hbm_bytes / (k_ms * 1e-3) / PEAK_HBM_BYTES},
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure; only this baseline leg uses it
+
+        rows_cpu = rows_h[: max(1, min(args.cpu_rows, C))]
+        t0 = time.perf_counter()
+        tel_o, _ = oracle.simulate_many(inst.s, inst.o, M, rows_cpu, literal=False, completions=True)
+        cpu_s = time.perf_counter() - t0
+        if not (tel_o == tel_h[: rows_cpu.shape[0]]).all():
+            print("bench.py: GPU and oracle disagree on the sampled rows", file=sys.stderr)
+            return 1
+        result["cpu_baseline"] = {
+            "value": rows_cpu.shape[0] / cpu_s,
+            "unit": "candidates/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": f"first {rows_cpu.shape[0]} of the {C} candidate rows, array-profile oracle "
+                      f"(oracle_simulate_profile), single thread, {cpu_s:.1f} s",
+        }
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

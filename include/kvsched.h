@@ -72,6 +72,13 @@ const char *kvsched_strerror(int status);
  * the bound is reported as KVSCHED_DEV_O_MAX and the affected candidates get tel = -1. */
 int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound);
 
+/* Optional kernel timing.  With `on` != 0 every later kvsched_simulate / kvsched_best_neighbor
+ * call records a pair of HIP events around its timeline kernel on the caller's stream;
+ * kvsched_last_timeline_ms() waits for the second event and returns the kernel's duration in
+ * milliseconds (EINVAL if timing is off or no call was made). */
+int kvsched_enable_timing(kvsched_ctx *ctx, int on);
+int kvsched_last_timeline_ms(kvsched_ctx *ctx, float *ms_out);
+
 /* Wait for `stream` and return (in *status_out) the device status word of the last call
  * made on this context: an OR of KVSCHED_DEV_* bits, 0 when the data was well-formed. */
 int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out);
@@ -130,6 +137,16 @@ int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n,
                           const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o,
                           int64_t M, int64_t *tel_out, int64_t *result_out, void *stream);
+
+/*
+ * Candidate scoring step for explicit order rows (Section 2, "Objective": the score of a
+ * candidate is its total end-to-end latency): index of the least non-negative entry of
+ * tel[0..C), the lowest index among equals.  Deterministic (fixed reduction order).
+ *
+ *   tel         [C] int64 as written by kvsched_simulate (-1 marks a faulty row, skipped)
+ *   result_out  [2] int64: {index of the best row or -1 if none is valid, its total latency}
+ */
+int kvsched_argmin(kvsched_ctx *ctx, const int64_t *tel, int32_t C, int64_t *result_out, void *stream);
 
 #ifdef __cplusplus
 }

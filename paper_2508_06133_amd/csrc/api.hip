@@ -24,6 +24,19 @@ int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
     return KVSCHED_OK;
 }
 
+// The timeline kernel, bracketed by the context's events when timing is on.
+int run_timelines(kvsched_ctx *ctx, const SimParams &p, int32_t H, hipStream_t st)
+{
+    if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
+    int rc = kvs_launch_simulate(p, H, st);
+    if (rc != KVSCHED_OK) return rc;
+    if (ctx->timing) {
+        if (hipEventRecord(ctx->ev1, st) != hipSuccess) return KVSCHED_EHIP;
+        ctx->timed = 1;
+    }
+    return KVSCHED_OK;
+}
+
 int32_t ring_slots_for(int32_t o_max)
 {
     int32_t h = 64;
@@ -80,6 +93,10 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->h_words = nullptr;
     ctx->d_scratch = nullptr;
     ctx->scratch_bytes = 0;
+    ctx->timing = 0;
+    ctx->timed = 0;
+    ctx->ev0 = nullptr;
+    ctx->ev1 = nullptr;
     if (hipMalloc((void **)&ctx->d_words, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess ||
         hipHostMalloc((void **)&ctx->h_words, sizeof(int32_t) * KVS_W_COUNT, hipHostMallocDefault) != hipSuccess ||
         hipMemset(ctx->d_words, 0, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess) {
@@ -98,6 +115,8 @@ void kvsched_destroy(kvsched_ctx *ctx)
     if (ctx->d_words) (void)hipFree(ctx->d_words);
     if (ctx->h_words) (void)hipHostFree(ctx->h_words);
     if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+    if (ctx->ev0) (void)hipEventDestroy(ctx->ev0);
+    if (ctx->ev1) (void)hipEventDestroy(ctx->ev1);
     delete ctx;
 }
 
@@ -118,6 +137,26 @@ int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound)
     if (!ctx || o_max_bound < 0) return KVSCHED_EINVAL;
     if (o_max_bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
     ctx->o_max_bound = o_max_bound;
+    return KVSCHED_OK;
+}
+
+int kvsched_enable_timing(kvsched_ctx *ctx, int on)
+{
+    if (!ctx) return KVSCHED_EINVAL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    if (on && !ctx->ev0) {
+        if (hipEventCreate(&ctx->ev0) != hipSuccess || hipEventCreate(&ctx->ev1) != hipSuccess) return KVSCHED_EHIP;
+    }
+    ctx->timing = on ? 1 : 0;
+    ctx->timed = 0;
+    return KVSCHED_OK;
+}
+
+int kvsched_last_timeline_ms(kvsched_ctx *ctx, float *ms_out)
+{
+    if (!ctx || !ms_out || !ctx->timing || !ctx->timed) return KVSCHED_EINVAL;
+    if (hipEventSynchronize(ctx->ev1) != hipSuccess) return KVSCHED_EHIP;
+    if (hipEventElapsedTime(ms_out, ctx->ev0, ctx->ev1) != hipSuccess) return KVSCHED_EHIP;
     return KVSCHED_OK;
 }
 
@@ -160,7 +199,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     p.completion_out = completion_out;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
-    rc = kvs_launch_simulate(p, H, st);
+    rc = run_timelines(ctx, p, H, st);
     if (rc != KVSCHED_OK) return rc;
     return kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
 }
@@ -211,18 +250,25 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     p.completion_out = nullptr;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
-    rc = kvs_launch_simulate(p, H, st);
+    rc = run_timelines(ctx, p, H, st);
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_check_moves(moves, K, n, tel, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_check_orders(base_order, 1, n, tel + K, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
-    rc = kvs_launch_argmin(tel, K, result_out, st);
+    rc = kvs_launch_argmin(tel, K, result_out, 1, st);
     if (rc != KVSCHED_OK) return rc;
     if (tel_out &&
         hipMemcpyAsync(tel_out, tel, sizeof(int64_t) * (size_t)K, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return KVSCHED_EHIP;
     return KVSCHED_OK;
+}
+
+int kvsched_argmin(kvsched_ctx *ctx, const int64_t *tel, int32_t C, int64_t *result_out, void *stream)
+{
+    if (!ctx || !tel || !result_out || C < 1) return KVSCHED_EINVAL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    return kvs_launch_argmin(tel, C, result_out, 0, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -20,6 +20,9 @@ struct kvsched_ctx {
     int32_t *h_words;      // [KVS_W_COUNT] pinned host mirror
     void *d_scratch;       // grows on demand
     size_t scratch_bytes;
+    int timing;            // record events around the timeline kernel
+    int timed;             // a pair of events has been recorded
+    hipEvent_t ev0, ev1;
 };
 
 // How a candidate's order is presented to the timeline kernel.
@@ -50,7 +53,7 @@ int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t
                             hipStream_t st);
 int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *tel_out, int32_t *d_words,
                            hipStream_t st);
-int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, hipStream_t st);
+int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, int32_t with_base, hipStream_t st);
 
 // sortedf.hip
 size_t kvs_sortedF_scratch_bytes(int32_t n);

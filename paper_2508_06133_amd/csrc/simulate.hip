@@ -226,9 +226,11 @@ __global__ __launch_bounds__(256) void check_moves_kernel(const int32_t *moves, 
     }
 }
 
-// One block: index of the least non-negative tel[0..K), lowest index among equals; tel[K] is
-// the base order's own latency.  Fixed reduction order, so the result is deterministic.
-__global__ __launch_bounds__(1024) void argmin_kernel(const int64_t *tel, int32_t K, int64_t *result_out)
+// One block: index of the least non-negative tel[0..K), lowest index among equals.  With
+// with_base, tel[K] is the base order's own latency and becomes the third result.  Fixed
+// reduction order, so the result is deterministic.
+__global__ __launch_bounds__(1024) void argmin_kernel(const int64_t *tel, int32_t K, int64_t *result_out,
+                                                      int32_t with_base)
 {
     __shared__ long long sh_tel[1024];
     __shared__ int sh_idx[1024];
@@ -258,10 +260,10 @@ __global__ __launch_bounds__(1024) void argmin_kernel(const int64_t *tel, int32_
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        const bool base_ok = tel[K] >= 0;  // a faulty base order makes every neighbour faulty
+        const bool base_ok = !with_base || tel[K] >= 0;  // a faulty base order makes every neighbour faulty
         result_out[0] = base_ok ? sh_idx[0] : -1;
         result_out[1] = (base_ok && sh_idx[0] >= 0) ? sh_tel[0] : -1;
-        result_out[2] = tel[K];
+        if (with_base) result_out[2] = tel[K];
     }
 }
 
@@ -324,8 +326,8 @@ int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
-int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, hipStream_t st)
+int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, int32_t with_base, hipStream_t st)
 {
-    hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, st, tel, K, result_out);
+    hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, st, tel, K, result_out, with_base);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

@@ -42,6 +42,9 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_strerror.restype = ctypes.c_char_p
     lib.kvsched_set_o_max.argtypes = [vp, i32]
     lib.kvsched_device_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.kvsched_enable_timing.argtypes = [vp, ctypes.c_int]
+    lib.kvsched_last_timeline_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.kvsched_argmin.argtypes = [vp, vp, i32, vp, vp]
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
@@ -86,6 +89,27 @@ class Context:
         rc = _lib.kvsched_set_o_max(self._h, int(bound))
         if rc != OK:
             raise KvschedError(rc, "kvsched_set_o_max")
+
+    def enable_timing(self, on: bool = True):
+        rc = _lib.kvsched_enable_timing(self._h, 1 if on else 0)
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_enable_timing")
+
+    def last_timeline_ms(self) -> float:
+        out = ctypes.c_float(0.0)
+        rc = _lib.kvsched_last_timeline_ms(self._h, ctypes.byref(out))
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_last_timeline_ms")
+        return float(out.value)
+
+    def argmin(self, tel, result_out=None):
+        """tel [C] int64 -> result [2] int64 = {index of the least valid entry, its value}."""
+        res = torch.empty(2, dtype=torch.int64, device=tel.device) if result_out is None else result_out
+        rc = _lib.kvsched_argmin(self._h, _dev(tel, torch.int64, "tel"), tel.shape[0], _dev(res, torch.int64, "result"),
+                                 _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_argmin")
+        return res
 
     def device_status(self) -> int:
         out = ctypes.c_int32(0)
