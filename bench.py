@@ -138,7 +138,7 @@ def main() -> int:
         "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
         "roofline": {
             "bound": "alu",
-            "kernel": "timeline_kernel<2048,4,false>",
+            "kernel": "timeline_reg_kernel<33,4,false>",
             "achieved": achieved / 1e12,
             "peak": PEAK_INT32_LANE_OPS / 1e12,
             "unit": "Tlane-op/s (int32)",

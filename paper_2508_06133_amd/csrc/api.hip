@@ -28,7 +28,8 @@ int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
 int run_timelines(kvsched_ctx *ctx, const SimParams &p, int32_t H, hipStream_t st)
 {
     if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
-    int rc = kvs_launch_simulate(p, H, st);
+    // profile in registers when the longest decode fits there, else the LDS ring
+    int rc = p.o_bound <= KVS_REG_MAX_O ? kvs_launch_simulate_reg(p, st) : kvs_launch_simulate(p, H, st);
     if (rc != KVSCHED_OK) return rc;
     if (ctx->timing) {
         if (hipEventRecord(ctx->ev1, st) != hipSuccess) return KVSCHED_EHIP;

@@ -49,6 +49,10 @@ struct SimParams {
 int kvs_launch_scan_lengths(const int32_t *s, const int32_t *o, int32_t n, int32_t M, int32_t o_bound,
                             int32_t *d_words, hipStream_t st);
 int kvs_launch_simulate(const SimParams &p, int32_t ring_slots, hipStream_t st);
+// timeline_reg.hip (decode lengths up to KVS_REG_MAX_O)
+constexpr int32_t KVS_REG_MAX_O = 4096;
+int kvs_launch_simulate_reg(const SimParams &p, hipStream_t st);
+
 int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t *tel_out, int32_t *d_words,
                             hipStream_t st);
 int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *tel_out, int32_t *d_words,

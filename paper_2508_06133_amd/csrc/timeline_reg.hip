@@ -1,0 +1,325 @@
+// Timeline kernel with the future-memory profile held in vector registers.
+//
+// Phase 2 of Algorithm 1 ("Scheduling Execution"), one wavefront per candidate order, same
+// search as the LDS-ring kernel (see simulate.hip): the k-th request of the order starts at
+// the smallest round t >= the previous start at which P(tau) + s + (tau - t) <= M for all
+// tau in (t, t + o]  (Eq. 1), P being the memory already committed to round tau.
+//
+// Layout.  The profile of rounds 64*B .. 64*(B+NR)-1 lives in NR vector registers: register
+// r of lane l belongs to round 64*(B+r) + l and holds Q = P + 64*r.  B is kept equal to
+// floor((t+1)/64), so the window (t, t+o] of the request being placed always starts in
+// register 0 and, with NR = ceil(o_max/64) + 1, always ends inside the file.  When t crosses
+// a multiple of 64 the file moves down by one register (NR subtract-64 moves per 64 rounds
+// of simulated time) and an empty row enters at the top.  There is no LDS traffic, no
+// address arithmetic and no memory wait in the hot loops:
+//   check   per row:  y = Q_r + (s - M);  c = min(y, 64 r);  acc = max(acc, c)
+//           c is the least admissible start that the row's round imposes, relative to the
+//           lane's round in row 0.  Rounds at or before t yield at most their own index, i.e.
+//           nothing above t, so the dead lanes in front of the window need no mask.
+//   update  per row:  Q_r += s + (tau - t)
+//   Only the last row of a window is lane-masked (rounds beyond t + o).
+//
+// The row loops are hand-written gfx950 assembly: the register file is a fixed block of
+// physical VGPRs (v32 upward) that only these assembly blocks touch; full rows run as an
+// unrolled chain with one scalar compare-and-branch per row, the last (masked) row is reached
+// through VGPR index mode.  The compiler-generated part of the kernel needs fewer than 32
+// VGPRs, so it never allocates the block; the clobber lists keep the block out of its hands
+// across the assembly statements.
+#include "kvsched_internal.h"
+#include "device_util.h"
+
+#include <limits.h>
+
+namespace {
+
+#define KVS_CLOB_9 "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40"
+#define KVS_CLOB_33                                                                                               \
+    KVS_CLOB_9, "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", \
+        "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64"
+#define KVS_CLOB_65                                                                                                \
+    KVS_CLOB_33, "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", \
+        "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93",   \
+        "v94", "v95", "v96"
+
+// gfx950 needs a wait state between s_set_gpr_idx_on and the first VALU instruction that uses
+// the index: issued back to back, about 0.3 % of the timelines of a fully occupied GPU came
+// out wrong (never on a lightly loaded one); a single s_nop removed every mismatch.  Two wait
+// states are inserted.
+#define KVS_IDX_WAIT "s_nop 1\n"
+
+// First register of the profile block; the KVS_CLOB_* lists start there.
+#define KVS_PB "32"
+
+// Expands STMT(clobber-list) for the instantiated file size.
+#define KVS_FOR_NR(STMT)                        \
+    do {                                        \
+        if constexpr (NR == 9) {                \
+            STMT(KVS_CLOB_9);                   \
+        } else if constexpr (NR == 33) {        \
+            STMT(KVS_CLOB_33);                  \
+        } else {                                \
+            static_assert(NR == 9 || NR == 33 || NR == 65, "profile file sizes: 9, 33 or 65 rows"); \
+            STMT(KVS_CLOB_65);                  \
+        }                                       \
+    } while (0)
+
+// Q_r = 64 r for all rows: nothing committed.
+template <int NR>
+__device__ __forceinline__ void prof_init()
+{
+#define KVS_STMT(CLOB)                                         \
+    asm volatile(".set kvs_r, 0\n"                             \
+                 ".rept %c[nr]\n"                              \
+                 "  v_mov_b32 v[" KVS_PB "+kvs_r], 64*kvs_r\n" \
+                 "  .set kvs_r, kvs_r+1\n"                     \
+                 ".endr\n"                                     \
+                 :                                             \
+                 : [nr] "n"(NR)                                \
+                 : CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
+// Rows move down by one: row r takes over the rounds of row r + 1 (whose offset was 64 more);
+// the top row becomes empty.
+template <int NR>
+__device__ __forceinline__ void prof_rotate1()
+{
+#define KVS_STMT(CLOB)                                                                  \
+    asm volatile(".set kvs_r, 0\n"                                                      \
+                 ".rept %c[nrm1]\n"                                                     \
+                 "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n"      \
+                 "  .set kvs_r, kvs_r+1\n"                                              \
+                 ".endr\n"                                                              \
+                 "v_mov_b32 v[" KVS_PB "+%c[nrm1]], 64*%c[nrm1]\n"                      \
+                 :                                                                      \
+                 : [nrm1] "n"(NR - 1)                                                   \
+                 : CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
+// The last row `re` of a window, common tail of both checks: acc = max(acc, c) on the lanes
+// of `lm` only.
+#define KVS_CHECK_LAST_ROW                             \
+    "s_set_gpr_idx_on %[re], gpr_idx(SRC0)\n" KVS_IDX_WAIT         \
+    "v_mov_b32 %[y], v[" KVS_PB "]\n"                  \
+    "s_set_gpr_idx_off\n"                              \
+    "s_lshl_b32 %[t0], %[re], 6\n"                     \
+    "v_add_u32 %[y], %[sb], %[y]\n"                    \
+    "v_min_i32 %[y], %[t0], %[y]\n"                    \
+    "s_and_saveexec_b64 %[sv], %[lm]\n"                \
+    "v_max_i32 %[acc], %[acc], %[y]\n"                 \
+    "s_mov_b64 exec, %[sv]\n"
+
+// Rows 0..re (row 0 holds round t + 1): per lane, the largest over its rounds of the least
+// admissible start, relative to the lane's round in row 0.  lm = lanes of row re inside the
+// window; sb = s - M.
+template <int NR>
+__device__ __forceinline__ int prof_check_from0(int re, int sb, unsigned long long lm)
+{
+    int acc, y, t0;
+    unsigned long long sv;
+#define KVS_STMT(CLOB)                                                                        \
+    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                    \
+                 ".set kvs_r, 0\n"                                                            \
+                 ".rept %c[nrm1]\n"                                                           \
+                 "  s_cmp_le_u32 %[re], kvs_r\n"                                              \
+                 "  s_cbranch_scc1 1f\n"                                                      \
+                 "  v_add_u32 %[y], %[sb], v[" KVS_PB "+kvs_r]\n"                             \
+                 "  v_min_i32 %[y], 64*kvs_r, %[y]\n"                                         \
+                 "  v_max_i32 %[acc], %[acc], %[y]\n"                                         \
+                 "  .set kvs_r, kvs_r+1\n"                                                    \
+                 ".endr\n"                                                                    \
+                 "1:\n" KVS_CHECK_LAST_ROW                                                    \
+                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [sv] "=&s"(sv)             \
+                 : [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm), [nrm1] "n"(NR - 1)               \
+                 : "scc", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+    return acc;
+}
+
+// The same over rows rs..re with rs > 0 unknown at compile time (the rounds that entered the
+// window after t moved): short scalar loop through VGPR index mode.
+template <int NR>
+__device__ __forceinline__ int prof_check_from(int rs, int re, int sb, unsigned long long lm)
+{
+    int acc, y, t0, t1;
+    unsigned long long sv;
+#define KVS_STMT(CLOB)                                                                                 \
+    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                             \
+                 "s_mov_b32 %[t1], %[rs]\n"                                                            \
+                 "s_cmp_ge_u32 %[t1], %[re]\n"                                                         \
+                 "s_cbranch_scc1 2f\n"                                                                 \
+                 "1:\n"                                                                                \
+                 "s_set_gpr_idx_on %[t1], gpr_idx(SRC0)\n" KVS_IDX_WAIT                                         \
+                 "v_mov_b32 %[y], v[" KVS_PB "]\n"                                                     \
+                 "s_set_gpr_idx_off\n"                                                                 \
+                 "s_lshl_b32 %[t0], %[t1], 6\n"                                                        \
+                 "v_add_u32 %[y], %[sb], %[y]\n"                                                       \
+                 "v_min_i32 %[y], %[t0], %[y]\n"                                                       \
+                 "v_max_i32 %[acc], %[acc], %[y]\n"                                                    \
+                 "s_add_u32 %[t1], %[t1], 1\n"                                                         \
+                 "s_cmp_lt_u32 %[t1], %[re]\n"                                                         \
+                 "s_cbranch_scc1 1b\n"                                                                 \
+                 "2:\n" KVS_CHECK_LAST_ROW                                                             \
+                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [t1] "=&s"(t1), [sv] "=&s"(sv)      \
+                 : [rs] "s"(rs), [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm)                              \
+                 : "scc", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+    return acc;
+}
+
+// Admit: rows 0..re get the request's ramp.  ramp = s + (tau - t) for the lane's round in row 0.
+template <int NR>
+__device__ __forceinline__ void prof_update(int re, unsigned long long lm, int ramp)
+{
+    unsigned long long sv;
+#define KVS_STMT(CLOB)                                                                   \
+    asm volatile(".set kvs_r, 0\n"                                                       \
+                 ".rept %c[nrm1]\n"                                                      \
+                 "  s_cmp_le_u32 %[re], kvs_r\n"                                         \
+                 "  s_cbranch_scc1 1f\n"                                                 \
+                 "  v_add_u32 v[" KVS_PB "+kvs_r], %[ramp], v[" KVS_PB "+kvs_r]\n"       \
+                 "  v_add_u32 %[ramp], 64, %[ramp]\n"                                    \
+                 "  .set kvs_r, kvs_r+1\n"                                               \
+                 ".endr\n"                                                               \
+                 "1:\n"                                                                  \
+                 "s_and_saveexec_b64 %[sv], %[lm]\n"                                     \
+                 "s_set_gpr_idx_on %[re], gpr_idx(SRC0,DST)\n" KVS_IDX_WAIT                         \
+                 "v_add_u32 v[" KVS_PB "], v[" KVS_PB "], %[ramp]\n"                     \
+                 "s_set_gpr_idx_off\n"                                                   \
+                 "s_mov_b64 exec, %[sv]\n"                                               \
+                 : [ramp] "+v"(ramp), [sv] "=&s"(sv)                                     \
+                 : [re] "s"(re), [lm] "s"(lm), [nrm1] "n"(NR - 1)                        \
+                 : "scc", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_perm(int v)
+{
+    return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, 0xf, true);
+}
+
+__device__ __forceinline__ int wave_max_dpp(int v)
+{
+    v = max(v, dpp_perm<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = max(v, dpp_perm<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = max(v, dpp_perm<0x141>(v));  // row_half_mirror
+    v = max(v, dpp_perm<0x140>(v));  // row_mirror
+    const int a = __builtin_amdgcn_readlane(v, 0);
+    const int b = __builtin_amdgcn_readlane(v, 16);
+    const int c = __builtin_amdgcn_readlane(v, 32);
+    const int d = __builtin_amdgcn_readlane(v, 48);
+    return max(max(a, b), max(c, d));
+}
+
+template <int NR, int WPB, bool MOVES>
+__global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int cand = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + (threadIdx.x >> 6));
+    if (cand >= p.C) return;
+
+    const int n = p.n;
+    const int M = p.M;
+    OrderReader<MOVES> rd;
+    if (MOVES) {
+        rd.row = p.src.base;
+        rd.mt = KVSCHED_MOVE_SWAP;
+        rd.mi = rd.mj = 0;
+        if (cand < p.C - 1) {  // the last timeline is the base order itself
+            rd.mt = p.src.moves[3 * (size_t)cand];
+            rd.mi = min(max(p.src.moves[3 * (size_t)cand + 1], 0), n - 1);
+            rd.mj = min(max(p.src.moves[3 * (size_t)cand + 2], 0), n - 1);
+        }
+    } else {
+        rd.row = p.src.orders + (size_t)cand * (size_t)n;
+        rd.mt = rd.mi = rd.mj = 0;
+    }
+    int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n : nullptr;
+
+    prof_init<NR>();
+    int B = 0;  // row r of lane l is round 64 * (B + r) + l
+    long long tel = 0;
+    int t = 0;  // start round of the previous request in the order
+
+    for (int k0 = 0; k0 < n; k0 += WAVE) {
+        // 64 positions of the order at a time: ids read coalesced, lengths gathered
+        const int k = k0 + lane;
+        int rq = 0, sv = 1, ov = 1;
+        if (k < n) {
+            rq = min(max(rd.at(k), 0), n - 1);
+            sv = p.s[rq];
+            ov = p.o[rq];
+        }
+        const bool bad = (sv < 1) | (ov < 1) | (ov > p.o_bound) | ((long long)sv + (long long)ov > (long long)M);
+        if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever
+            if (lane == 0) p.tel_out[cand] = -1;
+            return;
+        }
+        const int cnt = min(WAVE, n - k0);
+        int cv = 0;  // completion round of position k0 + lane
+        for (int j = 0; j < cnt; ++j) {
+            const int sj = __builtin_amdgcn_readlane(sv, j);
+            const int oj = __builtin_amdgcn_readlane(ov, j);
+            const int sb = sj - M;
+            int hi = t + oj;
+            int re = (hi >> 6) - B;
+            unsigned long long lm = (2ull << (hi & 63)) - 1ull;  // lanes of row re up to round hi
+            int acc = prof_check_from0<NR>(re, sb, lm);
+            for (;;) {
+                const int need = acc + ((B << 6) + lane);  // least start this lane's rounds allow
+                if (__builtin_amdgcn_ballot_w64(need > t) == 0) break;
+                t = wave_max_dpp(need);
+                const int lo = hi + 1;  // rounds up to hi have been accounted for
+                // keep register 0 on the row of round t + 1
+                const int Bn = (t + 1) >> 6;
+                int shift = Bn - B;
+                B = Bn;
+                if (shift >= NR) {
+                    prof_init<NR>();
+                } else {
+                    for (; shift > 0; --shift) prof_rotate1<NR>();
+                }
+                hi = t + oj;
+                re = (hi >> 6) - B;
+                lm = (2ull << (hi & 63)) - 1ull;
+                acc = prof_check_from<NR>((lo >> 6) - B, re, sb, lm);
+            }
+            // admitted at round t: holds sj + a tokens at round t + a
+            prof_update<NR>(re, lm, lane + (sj - t + (B << 6)));
+            tel += hi;
+            cv = (lane == j) ? hi : cv;
+        }
+        if (crow && k < n) crow[rq] = cv;
+    }
+    if (lane == 0) p.tel_out[cand] = tel;
+}
+
+template <int NR, int WPB>
+int launch_reg(const SimParams &p, hipStream_t st)
+{
+    const unsigned blocks = (unsigned)((p.C + WPB - 1) / WPB);
+    if (p.src.orders)
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    else
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+}  // namespace
+
+// o_bound <= KVS_REG_MAX_O.  Rows needed: ceil(o_bound / 64) + 1.
+int kvs_launch_simulate_reg(const SimParams &p, hipStream_t st)
+{
+    const int rows = (p.o_bound + 63) / 64 + 1;
+    if (rows <= 9) return launch_reg<9, 4>(p, st);
+    if (rows <= 33) return launch_reg<33, 4>(p, st);
+    if (rows <= 65) return launch_reg<65, 4>(p, st);
+    return KVSCHED_ERANGE;
+}

@@ -74,23 +74,24 @@ def test_config3_scaled_full(ctx):
     _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 3 scaled")
 
 
-def test_config3_full_size_sampled(ctx):
-    # the launch the benchmark times: n = 2000, C = 16384; the oracle checks a sample of rows
+def test_config3_full_size(ctx):
+    # the launch the benchmark times: n = 2000, C = 16384, the GPU fully occupied.  Every row
+    # is compared (the array-profile oracle needs a few seconds for all of them), on two
+    # launches: a timing-dependent fault shows up as a handful of rows that differ.
+    from oracle import exact
+
     inst = workloads.instance(3)
     base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
     rows = workloads.candidates(3, base)
     print(f"config 3: n={inst.n} C={rows.shape[0]}", flush=True)
-    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
-    assert status == 0
-    sample = np.unique(np.concatenate([np.arange(0, 16384, 128), np.arange(16384 - 256, 16384, 16), [0, 1, 16383]]))
-    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows[sample], literal=False)
-    _assert_equal(tel_g[sample], comp_g[sample], tel_o, comp_o, "config 3 sample")
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    for launch in range(2):
+        tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o, f"config 3, launch {launch}")
     # properties that hold for every row at any size
     assert (comp_g >= inst.o[None, :]).all()
     assert (tel_g == comp_g.astype(np.int64).sum(axis=1)).all()
-    lb = oracle.exact.lower_bound(inst.s, inst.o, inst.M) if hasattr(oracle, "exact") else None
-    from oracle import exact
-
     assert tel_g.min() >= exact.lower_bound(inst.s, inst.o, inst.M)
 
 
