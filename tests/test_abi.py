@@ -43,3 +43,26 @@ def test_product_path_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src, f
+
+
+def test_reserved_vgpr_scan_of_the_build():
+    # host logic of the build: compiler-generated lines inside a timeline_reg_kernel may not
+    # name a VGPR of the block its inline assembly owns (v32 upward); asm blocks and other
+    # functions are not looked at
+    from paper_2508_06133_amd import build
+
+    text = "\n".join([
+        "_ZN12_GLOBAL__N_119timeline_reg_kernelILi33ELi4ELb0EEEv9SimParams: ; @x",
+        "\tv_add_u32_e32 v31, v1, v2",
+        "\t;APP",
+        "  v_mov_b32 v[32+kvs_r], 64*kvs_r",
+        "v_mov_b32 v40, 0",
+        "\t;NO_APP",
+        "\tv_add_u32_e32 v33, v1, v2",
+        "\tv_mov_b64_e32 v[30:33], 0",
+        "\ts_endpgm",
+        "_Z5otherv:",
+        "\tv_mov_b32_e32 v50, 0",
+    ])
+    assert build.reserved_vgpr_violations(text) == ["v_add_u32_e32 v33, v1, v2", "v_mov_b64_e32 v[30:33], 0"]
+    assert build.reserved_vgpr_violations(text.replace("v33", "v3").replace("v[30:33]", "v[28:31]")) == []
