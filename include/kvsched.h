@@ -139,6 +139,32 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
                           int64_t M, int64_t *tel_out, int64_t *result_out, void *stream);
 
 /*
+ * One re-planning step of receding-horizon scheduling (Section 6, "Heuristics under Online
+ * Arrival": plan on a look-ahead window of the pending order, admit what the live memory
+ * profile allows, plan again), in its offline form with every request present at round 0:
+ *   1. kvsched_best_neighbor over `moves` (the caller draws them inside its look-ahead window
+ *      and includes an identity move, so the result is never worse than `order` itself);
+ *   2. the best move is applied to `order` IN PLACE;
+ *   3. the new order is run through Phase 2 (one timeline, completion rounds);
+ *   4. T = the round by which min(n, completed_in + complete_every) requests have completed
+ *      (that order statistic of the completion rounds); every position started by round T is
+ *      committed -- start rounds are nondecreasing along the order, so they form a prefix that
+ *      later moves beyond it can no longer influence.
+ *
+ *   order           [n]    int32 permutation, updated in place
+ *   moves, K, tel_out      as for kvsched_best_neighbor
+ *   completed_in    requests completed at the previous step's T (0 at the start)
+ *   complete_every  >= 1: completions to wait for before re-planning
+ *   completion_out  [n]    int32 or NULL: completion rounds of the new order, by request id
+ *   result_out      [6]    int64: {best move, its total latency, latency of the order before
+ *                   the move, committed positions, requests completed by T, T}
+ */
+int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int32_t *moves, int32_t K,
+                         const int32_t *s, const int32_t *o, int64_t M, int64_t completed_in,
+                         int32_t complete_every, int64_t *tel_out, int32_t *completion_out,
+                         int64_t *result_out, void *stream);
+
+/*
  * Candidate scoring step for explicit order rows (Section 2, "Objective": the score of a
  * candidate is its total end-to-end latency): index of the least non-negative entry of
  * tel[0..C), the lowest index among equals.  Deterministic (fixed reduction order).

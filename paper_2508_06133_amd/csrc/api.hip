@@ -265,6 +265,52 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     return KVSCHED_OK;
 }
 
+int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int32_t *moves, int32_t K,
+                         const int32_t *s, const int32_t *o, int64_t M, int64_t completed_in, int32_t complete_every,
+                         int64_t *tel_out, int32_t *completion_out, int64_t *result_out, void *stream)
+{
+    if (!order || !result_out || completed_in < 0 || complete_every < 1) return KVSCHED_EINVAL;
+    if (K < 1 || K == INT32_MAX || n < 1) return KVSCHED_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    // scratch: [K+1] latencies of best_neighbor | new order [n] | completion rounds [n] | one latency
+    const size_t tel_bytes = (sizeof(int64_t) * ((size_t)K + 1) + 255) & ~(size_t)255;
+    const size_t row_bytes = (sizeof(int32_t) * (size_t)n + 255) & ~(size_t)255;
+    int rc = ctx ? ensure_scratch(ctx, tel_bytes + 2 * row_bytes + 256) : KVSCHED_EINVAL;
+    if (rc != KVSCHED_OK) return rc;
+    // 1. best move of the window (result_out[0..2])
+    rc = kvsched_best_neighbor(ctx, order, n, moves, K, s, o, M, tel_out, result_out, stream);
+    if (rc != KVSCHED_OK) return rc;
+    char *base = (char *)ctx->d_scratch;
+    int32_t *new_order = (int32_t *)(base + tel_bytes);
+    int32_t *comp = completion_out ? completion_out : (int32_t *)(base + tel_bytes + row_bytes);
+    int64_t *tel1 = (int64_t *)(base + tel_bytes + 2 * row_bytes);
+    // 2. take it
+    rc = kvs_launch_apply_best_move(order, n, moves, result_out, new_order, st);
+    if (rc != KVSCHED_OK) return rc;
+    if (hipMemcpyAsync(order, new_order, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return KVSCHED_EHIP;
+    // 3. the chosen timeline, 4. how far it gets
+    const int32_t o_bound = ctx->o_max_bound > 0 ? ctx->o_max_bound
+                                                 : (ctx->h_words[KVS_W_OMAX] < 1 ? 1 : ctx->h_words[KVS_W_OMAX]);
+    SimParams p;
+    p.src.orders = order;
+    p.src.base = nullptr;
+    p.src.moves = nullptr;
+    p.C = 1;
+    p.n = n;
+    p.s = s;
+    p.o = o;
+    p.M = (int32_t)M;
+    p.tel_out = tel1;
+    p.completion_out = comp;
+    p.d_words = ctx->d_words;
+    p.o_bound = o_bound;
+    rc = p.o_bound <= KVS_REG_MAX_O ? kvs_launch_simulate_reg(p, st)
+                                    : kvs_launch_simulate(p, ring_slots_for(o_bound), st);
+    if (rc != KVSCHED_OK) return rc;
+    return kvs_launch_horizon_advance(order, comp, o, n, completed_in, complete_every, result_out + 3, st);
+}
+
 int kvsched_argmin(kvsched_ctx *ctx, const int64_t *tel, int32_t C, int64_t *result_out, void *stream)
 {
     if (!ctx || !tel || !result_out || C < 1) return KVSCHED_EINVAL;

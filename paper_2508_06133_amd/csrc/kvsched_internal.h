@@ -64,3 +64,9 @@ size_t kvs_sortedF_scratch_bytes(int32_t n);
 int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule,
                        int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
                        void *scratch, int32_t *d_words, hipStream_t st);
+
+// horizon.hip
+int kvs_launch_apply_best_move(const int32_t *order, int32_t n, const int32_t *moves, const int64_t *result,
+                               int32_t *order_out, hipStream_t st);
+int kvs_launch_horizon_advance(const int32_t *order, const int32_t *completion, const int32_t *o, int32_t n,
+                               int64_t completed_in, int32_t complete_every, int64_t *result_out, hipStream_t st);

@@ -48,6 +48,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
+    lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     return lib
 
 
@@ -164,4 +165,25 @@ class Context:
                                         tel.data_ptr() if tel is not None else None, res.data_ptr(), _stream())
         if rc != OK:
             raise KvschedError(rc, "kvsched_best_neighbor")
+        return tel, res
+
+    def horizon_step(self, order, moves, s, o, M, completed_in: int, complete_every: int, want_tel: bool = False,
+                     completion_out=None):
+        """One re-planning step; `order` [n] is updated in place.
+        -> (tel [K] or None, result [6] int64 = {best move, its TEL, TEL before, committed positions,
+        requests completed by T, T})."""
+        n = order.shape[0]
+        K = moves.shape[0]
+        dev = order.device
+        tel = torch.empty(K, dtype=torch.int64, device=dev) if want_tel else None
+        res = torch.empty(6, dtype=torch.int64, device=dev)
+        rc = _lib.kvsched_horizon_step(self._h, _dev(order, torch.int32, "order"), n, _dev(moves, torch.int32, "moves"),
+                                       K, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
+                                       int(completed_in), int(complete_every),
+                                       tel.data_ptr() if tel is not None else None,
+                                       _dev(completion_out, torch.int32, "completion_out")
+                                       if completion_out is not None else None,
+                                       res.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_horizon_step")
         return tel, res

@@ -357,3 +357,29 @@ def test_best_neighbor_bruteforce():
     assert (tel == ref).all()
     assert best == int(np.argmin(ref)) and best_tel == int(ref.min())  # argmin = first minimum
     assert base_tel == oracle.simulate(inst.s, inst.o, inst.M, base)[2] == tel[0]  # move 0 is swap(0,0)
+
+
+# ------------------------------------------------------------- receding-horizon driver
+
+def test_receding_horizon_oracle_invariants():
+    from oracle import horizon as ohorizon
+
+    inst = workloads.instance(4, n=120)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rng = np.random.default_rng(1)
+    order, c, log = ohorizon.receding_horizon(inst.s, inst.o, inst.M, base,
+                                              lambda lo, hi: workloads.window_moves(rng, 60, lo, hi), 16, 8)
+    assert sorted(order) == list(range(120)) and log[-1]["committed"] == 120
+    committed = [r["committed"] for r in log]
+    assert all(a < b for a, b in zip(committed, committed[1:]))  # every step commits something new
+    tels = [r["best_tel"] for r in log]
+    assert all(a >= b for a, b in zip(tels, tels[1:]))  # the identity move is always available
+    assert tels[-1] == int(c.sum()) <= oracle.simulate(inst.s, inst.o, inst.M, base, literal=False)[2]
+    # committed positions are frozen: later steps only move positions at or beyond `lo`
+    for r in log:
+        assert r["lo"] <= r["hi"] and (r["tel"][0] == r["base_tel"])
+    # one step against the literal form of the algorithm
+    moves = workloads.window_moves(np.random.default_rng(2), 30, 0, 16)
+    a = ohorizon.horizon_step(inst.s, inst.o, inst.M, base, moves, 0, 8, literal=True)
+    b = ohorizon.horizon_step(inst.s, inst.o, inst.M, base, moves, 0, 8, literal=False)
+    assert a[3] == b[3] and (a[0] == b[0]).all() and (a[1] == b[1]).all()
