@@ -33,6 +33,24 @@ PEAK_HBM_BYTES = 8.0e12
 OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for one request
 CFG = 3
 
+# HBM traffic of one launch of the dominant kernel on this workload, from rocprofv3 counters
+# (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 64666 KiB x 1.9997 (what a plain
+# 256 MiB copy reads per KiB moved) + WRITE_SIZE 128214 KiB x 1.0.  Valid only for the kernel
+# sources it was measured on; reported as null once they change.
+TRAFFIC_BYTES = int((64666 * 1.9997 + 128214 * 1.0) * 1024)
+TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
+TRAFFIC_SOURCES_SHA256 = "c17f02d98744f8f2"
+
+
+def measured_traffic():
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, "paper_2508_06133_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return TRAFFIC_BYTES if h.hexdigest()[:16] == TRAFFIC_SOURCES_SHA256 else None
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -41,6 +59,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="candidate rows the CPU oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, the yardstick for FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build evaluates schedules on ONE GPU; --gpus must be 1 "
@@ -105,6 +125,14 @@ def main() -> int:
         print(f"bench.py: device status {status}", file=sys.stderr)
         return 1
 
+    if args.calibrate_copy:  # 2^26 int32 = 256 MiB read + 256 MiB written by one elementwise kernel
+        src = torch.arange(1 << 26, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- accounting from the outputs of the run (outside the timed region)
     tel_h = tel.cpu().numpy()
     o64 = o.to(torch.int64)
@@ -143,7 +171,7 @@ def main() -> int:
             "peak": PEAK_INT32_LANE_OPS / 1e12,
             "unit": "Tlane-op/s (int32)",
             "frac": achieved / PEAK_INT32_LANE_OPS,
-            "traffic": None,
+            "traffic": measured_traffic(),
             "visits_per_launch": visits,
             "ops_per_visit": OPS_PER_VISIT,
             "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / (k_ms * 1e-3) / 1e9,

@@ -198,10 +198,18 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     p.M = (int32_t)M;
     p.tel_out = tel_out;
     p.completion_out = completion_out;
+    // Completion rounds leave the timeline kernel in position order (coalesced stores); a second
+    // kernel permutes each row to request-id order through LDS.  Rows too long for LDS are
+    // scattered by the timeline kernel itself.
+    p.completion_by_position = (completion_out && n <= KVS_PERMUTE_MAX_N) ? 1 : 0;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
     rc = run_timelines(ctx, p, H, st);
     if (rc != KVSCHED_OK) return rc;
+    if (p.completion_by_position) {
+        rc = kvs_launch_permute_rows(orders, C, n, completion_out, st);
+        if (rc != KVSCHED_OK) return rc;
+    }
     return kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
 }
 
@@ -249,6 +257,7 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     p.M = (int32_t)M;
     p.tel_out = tel;
     p.completion_out = nullptr;
+    p.completion_by_position = 0;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
     rc = run_timelines(ctx, p, H, st);
@@ -303,6 +312,7 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     p.M = (int32_t)M;
     p.tel_out = tel1;
     p.completion_out = comp;
+    p.completion_by_position = 0;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
     rc = p.o_bound <= KVS_REG_MAX_O ? kvs_launch_simulate_reg(p, st)

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_kernel(SimParams p)
             tel += c;
             cv = (lane == j) ? c : cv;
         }
-        if (crow && k < n) crow[r] = cv;
+        if (crow && k < n) crow[p.completion_by_position ? k : r] = cv;
     }
     if (lane == 0) p.tel_out[cand] = tel;
 }

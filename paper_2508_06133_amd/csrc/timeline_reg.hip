@@ -296,7 +296,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             tel += hi;
             cv = (lane == j) ? hi : cv;
         }
-        if (crow && k < n) crow[rq] = cv;
+        if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
     if (lane == 0) p.tel_out[cand] = tel;
 }
