@@ -2,9 +2,9 @@
 
 hipcc cross-compiles without a GPU, so this runs anywhere the ROCm toolchain is installed.
 
-timeline_reg.hip keeps per-timeline state in a block of physical VGPRs (v32 upward) that only
+timeline_reg.hip keeps per-timeline state in a block of physical VGPRs (v24 upward) that only
 its inline-assembly blocks touch.  That is sound only while the compiler-generated part of those
-kernels stays below v32, so the build emits the device assembly of that file and fails if any
+kernels stays below v24, so the build emits the device assembly of that file and fails if any
 compiler-generated instruction of a timeline_reg_kernel names a VGPR of the block.
 """
 from __future__ import annotations
@@ -27,7 +27,7 @@ DEVICE_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 FLAGS = DEVICE_FLAGS + ["-fPIC", "-shared", "-Wall", "-Wno-unused-function"]
-RESERVED_VGPR_BASE = 32  # KVS_PB in timeline_reg.hip
+RESERVED_VGPR_BASE = 24  # KVS_PB in timeline_reg.hip
 
 
 def lib_path() -> str:

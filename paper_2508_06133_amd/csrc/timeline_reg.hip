@@ -20,11 +20,12 @@
 //   Only the last row of a window is lane-masked (rounds beyond t + o).
 //
 // The row loops are hand-written gfx950 assembly: the register file is a fixed block of
-// physical VGPRs (v32 upward) that only these assembly blocks touch; full rows run as an
-// unrolled chain with one scalar compare-and-branch per row, the last (masked) row is reached
-// through VGPR index mode.  The compiler-generated part of the kernel needs fewer than 32
-// VGPRs, so it never allocates the block; the clobber lists keep the block out of its hands
-// across the assembly statements.
+// physical VGPRs (v24 upward) that only these assembly blocks touch; full rows run as an
+// unrolled chain with one scalar compare-and-branch per row (rows are paired so that two
+// rows cost five vector instructions in the check and three in the update), the last (masked)
+// row is reached through VGPR index mode.  The compiler-generated part of the kernel needs
+// fewer than 24 VGPRs, so it never allocates the block (the build verifies that); the clobber
+// lists keep the block out of its hands across the assembly statements.
 #include "kvsched_internal.h"
 #include "device_util.h"
 
@@ -32,14 +33,17 @@
 
 namespace {
 
-#define KVS_CLOB_9 "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40"
+// First register of the profile block; the KVS_CLOB_* lists start there.
+#define KVS_PB "24"
+
+#define KVS_CLOB_9 "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32"
 #define KVS_CLOB_33                                                                                               \
-    KVS_CLOB_9, "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", \
-        "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64"
+    KVS_CLOB_9, "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", \
+        "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56"
 #define KVS_CLOB_65                                                                                                \
-    KVS_CLOB_33, "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", \
-        "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93",   \
-        "v94", "v95", "v96"
+    KVS_CLOB_33, "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", \
+        "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85",   \
+        "v86", "v87", "v88"
 
 // gfx950 needs a wait state between s_set_gpr_idx_on and the first VALU instruction that uses
 // the index: issued back to back, about 0.3 % of the timelines of a fully occupied GPU came
@@ -47,20 +51,18 @@ namespace {
 // states are inserted.
 #define KVS_IDX_WAIT "s_nop 1\n"
 
-// First register of the profile block; the KVS_CLOB_* lists start there.
-#define KVS_PB "32"
-
-// Expands STMT(clobber-list) for the instantiated file size.
-#define KVS_FOR_NR(STMT)                        \
-    do {                                        \
-        if constexpr (NR == 9) {                \
-            STMT(KVS_CLOB_9);                   \
-        } else if constexpr (NR == 33) {        \
-            STMT(KVS_CLOB_33);                  \
-        } else {                                \
+// Expands STMT(clobber-list) for the instantiated file size (NR - 1 must be even: the row
+// chains process rows in pairs).
+#define KVS_FOR_NR(STMT)                                                                            \
+    do {                                                                                            \
+        if constexpr (NR == 9) {                                                                    \
+            STMT(KVS_CLOB_9);                                                                       \
+        } else if constexpr (NR == 33) {                                                            \
+            STMT(KVS_CLOB_33);                                                                      \
+        } else {                                                                                    \
             static_assert(NR == 9 || NR == 33 || NR == 65, "profile file sizes: 9, 33 or 65 rows"); \
-            STMT(KVS_CLOB_65);                  \
-        }                                       \
+            STMT(KVS_CLOB_65);                                                                      \
+        }                                                                                           \
     } while (0)
 
 // Q_r = 64 r for all rows: nothing committed.
@@ -85,15 +87,15 @@ __device__ __forceinline__ void prof_init()
 template <int NR>
 __device__ __forceinline__ void prof_rotate1()
 {
-#define KVS_STMT(CLOB)                                                                  \
-    asm volatile(".set kvs_r, 0\n"                                                      \
-                 ".rept %c[nrm1]\n"                                                     \
-                 "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n"      \
-                 "  .set kvs_r, kvs_r+1\n"                                              \
-                 ".endr\n"                                                              \
-                 "v_mov_b32 v[" KVS_PB "+%c[nrm1]], 64*%c[nrm1]\n"                      \
-                 :                                                                      \
-                 : [nrm1] "n"(NR - 1)                                                   \
+#define KVS_STMT(CLOB)                                                             \
+    asm volatile(".set kvs_r, 0\n"                                                 \
+                 ".rept %c[nrm1]\n"                                                \
+                 "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n" \
+                 "  .set kvs_r, kvs_r+1\n"                                         \
+                 ".endr\n"                                                         \
+                 "v_mov_b32 v[" KVS_PB "+%c[nrm1]], 64*%c[nrm1]\n"                 \
+                 :                                                                 \
+                 : [nrm1] "n"(NR - 1)                                              \
                  : CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
@@ -101,39 +103,49 @@ __device__ __forceinline__ void prof_rotate1()
 
 // The last row `re` of a window, common tail of both checks: acc = max(acc, c) on the lanes
 // of `lm` only.
-#define KVS_CHECK_LAST_ROW                             \
-    "s_set_gpr_idx_on %[re], gpr_idx(SRC0)\n" KVS_IDX_WAIT         \
-    "v_mov_b32 %[y], v[" KVS_PB "]\n"                  \
-    "s_set_gpr_idx_off\n"                              \
-    "s_lshl_b32 %[t0], %[re], 6\n"                     \
-    "v_add_u32 %[y], %[sb], %[y]\n"                    \
-    "v_min_i32 %[y], %[t0], %[y]\n"                    \
-    "s_and_saveexec_b64 %[sv], %[lm]\n"                \
-    "v_max_i32 %[acc], %[acc], %[y]\n"                 \
+#define KVS_CHECK_LAST_ROW                                 \
+    "s_set_gpr_idx_on %[re], gpr_idx(SRC0)\n" KVS_IDX_WAIT \
+    "v_mov_b32 %[y], v[" KVS_PB "]\n"                      \
+    "s_set_gpr_idx_off\n"                                  \
+    "s_lshl_b32 %[t0], %[re], 6\n"                         \
+    "v_add_u32 %[y], %[sb], %[y]\n"                        \
+    "v_min_i32 %[y], %[t0], %[y]\n"                        \
+    "s_and_saveexec_b64 %[sv], %[lm]\n"                    \
+    "v_max_i32 %[acc], %[acc], %[y]\n"                     \
     "s_mov_b64 exec, %[sv]\n"
 
 // Rows 0..re (row 0 holds round t + 1): per lane, the largest over its rounds of the least
 // admissible start, relative to the lane's round in row 0.  lm = lanes of row re inside the
-// window; sb = s - M.
+// window; sb = s - M.  Full rows are taken two at a time (one three-input max per pair); an
+// exit after an odd number of rows first folds the pending row in (label 2).
 template <int NR>
 __device__ __forceinline__ int prof_check_from0(int re, int sb, unsigned long long lm)
 {
-    int acc, y, t0;
+    int acc, y, z, t0;
     unsigned long long sv;
-#define KVS_STMT(CLOB)                                                                        \
-    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                    \
-                 ".set kvs_r, 0\n"                                                            \
-                 ".rept %c[nrm1]\n"                                                           \
-                 "  s_cmp_le_u32 %[re], kvs_r\n"                                              \
-                 "  s_cbranch_scc1 1f\n"                                                      \
-                 "  v_add_u32 %[y], %[sb], v[" KVS_PB "+kvs_r]\n"                             \
-                 "  v_min_i32 %[y], 64*kvs_r, %[y]\n"                                         \
-                 "  v_max_i32 %[acc], %[acc], %[y]\n"                                         \
-                 "  .set kvs_r, kvs_r+1\n"                                                    \
-                 ".endr\n"                                                                    \
-                 "1:\n" KVS_CHECK_LAST_ROW                                                    \
-                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [sv] "=&s"(sv)             \
-                 : [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm), [nrm1] "n"(NR - 1)               \
+#define KVS_STMT(CLOB)                                                                                  \
+    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                              \
+                 ".set kvs_r, 0\n"                                                                      \
+                 ".rept %c[nrm1]\n"                                                                     \
+                 "  s_cmp_le_u32 %[re], kvs_r\n"                                                        \
+                 "  .if (kvs_r & 1) == 0\n"                                                             \
+                 "    s_cbranch_scc1 1f\n"                                                              \
+                 "    v_add_u32 %[y], %[sb], v[" KVS_PB "+kvs_r]\n"                                     \
+                 "    v_min_i32 %[y], 64*kvs_r, %[y]\n"                                                 \
+                 "  .else\n"                                                                            \
+                 "    s_cbranch_scc1 2f\n"                                                              \
+                 "    v_add_u32 %[z], %[sb], v[" KVS_PB "+kvs_r]\n"                                     \
+                 "    v_min_i32 %[z], 64*kvs_r, %[z]\n"                                                 \
+                 "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                          \
+                 "  .endif\n"                                                                           \
+                 "  .set kvs_r, kvs_r+1\n"                                                              \
+                 ".endr\n"                                                                              \
+                 "s_branch 1f\n"                                                                        \
+                 "2:\n"                                                                                 \
+                 "v_max_i32 %[acc], %[acc], %[y]\n"                                                     \
+                 "1:\n" KVS_CHECK_LAST_ROW                                                              \
+                 : [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [t0] "=&s"(t0), [sv] "=&s"(sv)         \
+                 : [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm), [nrm1] "n"(NR - 1)                         \
                  : "scc", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
@@ -147,75 +159,90 @@ __device__ __forceinline__ int prof_check_from(int rs, int re, int sb, unsigned 
 {
     int acc, y, t0, t1;
     unsigned long long sv;
-#define KVS_STMT(CLOB)                                                                                 \
-    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                             \
-                 "s_mov_b32 %[t1], %[rs]\n"                                                            \
-                 "s_cmp_ge_u32 %[t1], %[re]\n"                                                         \
-                 "s_cbranch_scc1 2f\n"                                                                 \
-                 "1:\n"                                                                                \
-                 "s_set_gpr_idx_on %[t1], gpr_idx(SRC0)\n" KVS_IDX_WAIT                                         \
-                 "v_mov_b32 %[y], v[" KVS_PB "]\n"                                                     \
-                 "s_set_gpr_idx_off\n"                                                                 \
-                 "s_lshl_b32 %[t0], %[t1], 6\n"                                                        \
-                 "v_add_u32 %[y], %[sb], %[y]\n"                                                       \
-                 "v_min_i32 %[y], %[t0], %[y]\n"                                                       \
-                 "v_max_i32 %[acc], %[acc], %[y]\n"                                                    \
-                 "s_add_u32 %[t1], %[t1], 1\n"                                                         \
-                 "s_cmp_lt_u32 %[t1], %[re]\n"                                                         \
-                 "s_cbranch_scc1 1b\n"                                                                 \
-                 "2:\n" KVS_CHECK_LAST_ROW                                                             \
-                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [t1] "=&s"(t1), [sv] "=&s"(sv)      \
-                 : [rs] "s"(rs), [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm)                              \
+#define KVS_STMT(CLOB)                                                                            \
+    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                        \
+                 "s_mov_b32 %[t1], %[rs]\n"                                                       \
+                 "s_cmp_ge_u32 %[t1], %[re]\n"                                                    \
+                 "s_cbranch_scc1 2f\n"                                                            \
+                 "1:\n"                                                                           \
+                 "s_set_gpr_idx_on %[t1], gpr_idx(SRC0)\n" KVS_IDX_WAIT                           \
+                 "v_mov_b32 %[y], v[" KVS_PB "]\n"                                                \
+                 "s_set_gpr_idx_off\n"                                                            \
+                 "s_lshl_b32 %[t0], %[t1], 6\n"                                                   \
+                 "v_add_u32 %[y], %[sb], %[y]\n"                                                  \
+                 "v_min_i32 %[y], %[t0], %[y]\n"                                                  \
+                 "v_max_i32 %[acc], %[acc], %[y]\n"                                               \
+                 "s_add_u32 %[t1], %[t1], 1\n"                                                    \
+                 "s_cmp_lt_u32 %[t1], %[re]\n"                                                    \
+                 "s_cbranch_scc1 1b\n"                                                            \
+                 "2:\n" KVS_CHECK_LAST_ROW                                                        \
+                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [t1] "=&s"(t1), [sv] "=&s"(sv) \
+                 : [rs] "s"(rs), [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm)                         \
                  : "scc", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
     return acc;
 }
 
-// Admit: rows 0..re get the request's ramp.  ramp = s + (tau - t) for the lane's round in row 0.
+// Admit: rows 0..re get the request's ramp.  ramp = s + (tau - t) for the lane's round in row 0;
+// it advances by 64 per row, once per pair of rows (an exit after an odd number of rows makes
+// up for the missing step at label 2).
 template <int NR>
 __device__ __forceinline__ void prof_update(int re, unsigned long long lm, int ramp)
 {
     unsigned long long sv;
-#define KVS_STMT(CLOB)                                                                   \
-    asm volatile(".set kvs_r, 0\n"                                                       \
-                 ".rept %c[nrm1]\n"                                                      \
-                 "  s_cmp_le_u32 %[re], kvs_r\n"                                         \
-                 "  s_cbranch_scc1 1f\n"                                                 \
-                 "  v_add_u32 v[" KVS_PB "+kvs_r], %[ramp], v[" KVS_PB "+kvs_r]\n"       \
-                 "  v_add_u32 %[ramp], 64, %[ramp]\n"                                    \
-                 "  .set kvs_r, kvs_r+1\n"                                               \
-                 ".endr\n"                                                               \
-                 "1:\n"                                                                  \
-                 "s_and_saveexec_b64 %[sv], %[lm]\n"                                     \
-                 "s_set_gpr_idx_on %[re], gpr_idx(SRC0,DST)\n" KVS_IDX_WAIT                         \
-                 "v_add_u32 v[" KVS_PB "], v[" KVS_PB "], %[ramp]\n"                     \
-                 "s_set_gpr_idx_off\n"                                                   \
-                 "s_mov_b64 exec, %[sv]\n"                                               \
-                 : [ramp] "+v"(ramp), [sv] "=&s"(sv)                                     \
-                 : [re] "s"(re), [lm] "s"(lm), [nrm1] "n"(NR - 1)                        \
+#define KVS_STMT(CLOB)                                                                            \
+    asm volatile(".set kvs_r, 0\n"                                                                \
+                 ".rept %c[nrm1]\n"                                                               \
+                 "  s_cmp_le_u32 %[re], kvs_r\n"                                                  \
+                 "  .if (kvs_r & 1) == 0\n"                                                       \
+                 "    s_cbranch_scc1 1f\n"                                                        \
+                 "    v_add_u32 v[" KVS_PB "+kvs_r], %[ramp], v[" KVS_PB "+kvs_r]\n"              \
+                 "  .else\n"                                                                      \
+                 "    s_cbranch_scc1 2f\n"                                                        \
+                 "    v_add3_u32 v[" KVS_PB "+kvs_r], v[" KVS_PB "+kvs_r], %[ramp], 64\n"         \
+                 "    v_add_u32 %[ramp], 0x80, %[ramp]\n"                                         \
+                 "  .endif\n"                                                                     \
+                 "  .set kvs_r, kvs_r+1\n"                                                        \
+                 ".endr\n"                                                                        \
+                 "s_branch 1f\n"                                                                  \
+                 "2:\n"                                                                           \
+                 "v_add_u32 %[ramp], 64, %[ramp]\n"                                               \
+                 "1:\n"                                                                           \
+                 "s_and_saveexec_b64 %[sv], %[lm]\n"                                              \
+                 "s_set_gpr_idx_on %[re], gpr_idx(SRC0,DST)\n" KVS_IDX_WAIT                       \
+                 "v_add_u32 v[" KVS_PB "], v[" KVS_PB "], %[ramp]\n"                              \
+                 "s_set_gpr_idx_off\n"                                                            \
+                 "s_mov_b64 exec, %[sv]\n"                                                        \
+                 : [ramp] "+v"(ramp), [sv] "=&s"(sv)                                              \
+                 : [re] "s"(re), [lm] "s"(lm), [nrm1] "n"(NR - 1)                                 \
                  : "scc", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
 }
 
-template <int CTRL>
-__device__ __forceinline__ int dpp_perm(int v)
-{
-    return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, 0xf, true);
-}
-
+// Maximum over the 64 lanes (all active).  Four DPP steps give every lane of a 16-lane row the
+// row's maximum; two row broadcasts carry it to lane 63.  A DPP read of a register written by
+// the previous instruction needs two wait states.
 __device__ __forceinline__ int wave_max_dpp(int v)
 {
-    v = max(v, dpp_perm<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = max(v, dpp_perm<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = max(v, dpp_perm<0x141>(v));  // row_half_mirror
-    v = max(v, dpp_perm<0x140>(v));  // row_mirror
-    const int a = __builtin_amdgcn_readlane(v, 0);
-    const int b = __builtin_amdgcn_readlane(v, 16);
-    const int c = __builtin_amdgcn_readlane(v, 32);
-    const int d = __builtin_amdgcn_readlane(v, 48);
-    return max(max(a, b), max(c, d));
+    int out;
+    asm volatile("s_nop 1\n"
+                 "v_max_i32_dpp %[v], %[v], %[v] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
+                 "s_nop 1\n"
+                 "v_max_i32_dpp %[v], %[v], %[v] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n"
+                 "s_nop 1\n"
+                 "v_max_i32_dpp %[v], %[v], %[v] row_half_mirror row_mask:0xf bank_mask:0xf\n"
+                 "s_nop 1\n"
+                 "v_max_i32_dpp %[v], %[v], %[v] row_mirror row_mask:0xf bank_mask:0xf\n"
+                 "s_nop 1\n"
+                 "v_max_i32_dpp %[v], %[v], %[v] row_bcast:15 row_mask:0xa bank_mask:0xf\n"
+                 "s_nop 1\n"
+                 "v_max_i32_dpp %[v], %[v], %[v] row_bcast:31 row_mask:0xc bank_mask:0xf\n"
+                 "s_nop 1\n"
+                 "v_readlane_b32 %[out], %[v], 63\n"
+                 : [v] "+v"(v), [out] "=s"(out));
+    return out;
 }
 
 template <int NR, int WPB, bool MOVES>
@@ -248,14 +275,22 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     long long tel = 0;
     int t = 0;  // start round of the previous request in the order
 
+    // 64 positions of the order at a time: ids read coalesced, lengths gathered; the next
+    // block is fetched while the current one is being placed
+    int rq_n = 0, sv_n = 1, ov_n = 1;
+    if (lane < n) {
+        rq_n = min(max(rd.at(lane), 0), n - 1);
+        sv_n = p.s[rq_n];
+        ov_n = p.o[rq_n];
+    }
     for (int k0 = 0; k0 < n; k0 += WAVE) {
-        // 64 positions of the order at a time: ids read coalesced, lengths gathered
         const int k = k0 + lane;
-        int rq = 0, sv = 1, ov = 1;
-        if (k < n) {
-            rq = min(max(rd.at(k), 0), n - 1);
-            sv = p.s[rq];
-            ov = p.o[rq];
+        const int rq = rq_n, sv = sv_n, ov = ov_n;
+        rq_n = 0, sv_n = 1, ov_n = 1;
+        if (k + WAVE < n) {
+            rq_n = min(max(rd.at(k + WAVE), 0), n - 1);
+            sv_n = p.s[rq_n];
+            ov_n = p.o[rq_n];
         }
         const bool bad = (sv < 1) | (ov < 1) | (ov > p.o_bound) | ((long long)sv + (long long)ov > (long long)M);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever

@@ -47,7 +47,7 @@ def test_product_path_does_not_touch_the_oracle():
 
 def test_reserved_vgpr_scan_of_the_build():
     # host logic of the build: compiler-generated lines inside a timeline_reg_kernel may not
-    # name a VGPR of the block its inline assembly owns (v32 upward); asm blocks and other
+    # name a VGPR of the block its inline assembly owns (v24 upward); asm blocks and other
     # functions are not looked at
     from paper_2508_06133_amd import build
 
@@ -64,5 +64,5 @@ def test_reserved_vgpr_scan_of_the_build():
         "_Z5otherv:",
         "\tv_mov_b32_e32 v50, 0",
     ])
-    assert build.reserved_vgpr_violations(text) == ["v_add_u32_e32 v33, v1, v2", "v_mov_b64_e32 v[30:33], 0"]
-    assert build.reserved_vgpr_violations(text.replace("v33", "v3").replace("v[30:33]", "v[28:31]")) == []
+    assert build.reserved_vgpr_violations(text, base=32) == ["v_add_u32_e32 v33, v1, v2", "v_mov_b64_e32 v[30:33], 0"]
+    assert build.reserved_vgpr_violations(text.replace("v33", "v3").replace("v[30:33]", "v[28:31]"), base=32) == []
