@@ -48,13 +48,19 @@ int32_t ring_slots_for(int32_t o_max)
 // Enqueue the length scan; unless the caller supplied a bound, wait for the largest decode
 // length.  *o_bound_out is what the timeline kernels size their ring from.
 int scan_and_bound(kvsched_ctx *ctx, const int32_t *s, const int32_t *o, int32_t n, int64_t M, hipStream_t st,
-                   int32_t *o_bound_out)
+                   int32_t *o_bound_out, const int32_t *moves = nullptr, int32_t K = 0,
+                   int32_t *min_position_out = nullptr)
 {
     int rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, ctx->o_max_bound, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
+    if (min_position_out) *min_position_out = 0;
     if (ctx->o_max_bound > 0) {
         *o_bound_out = ctx->o_max_bound;
         return KVSCHED_OK;
+    }
+    if (moves && min_position_out) {  // rides on the same read-back: first position any move touches
+        rc = kvs_launch_moves_min_position(moves, K, n, ctx->d_words, st);
+        if (rc != KVSCHED_OK) return rc;
     }
     if (hipMemcpyAsync(ctx->h_words, ctx->d_words, sizeof(int32_t) * KVS_W_COUNT, hipMemcpyDeviceToHost, st) !=
         hipSuccess)
@@ -63,7 +69,42 @@ int scan_and_bound(kvsched_ctx *ctx, const int32_t *s, const int32_t *o, int32_t
     int32_t omax = ctx->h_words[KVS_W_OMAX];
     if (omax > KVSCHED_MAX_O) return KVSCHED_ERANGE;
     *o_bound_out = omax < 1 ? 1 : omax;
+    if (moves && min_position_out) {
+        const int32_t mp = ctx->h_words[KVS_W_MINPOS];
+        *min_position_out = (mp < 0 || mp > n) ? 0 : mp;  // INT_MAX: no move changes the order
+        if (mp == INT32_MAX) *min_position_out = n;
+    }
     return KVSCHED_OK;
+}
+
+constexpr int32_t kMinSharedPrefix = 64;  // shorter shared prefixes are not worth a launch
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+size_t state_bytes() { return align256(sizeof(int32_t) * KVS_STATE_MAX_WORDS); }
+
+// Run positions [0, cp) of `row0` once and leave the timeline state in `state`;
+// completion rounds of those positions (position order) go to prefix_completion if not NULL.
+int run_shared_prefix(const int32_t *row0, int32_t cp, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                      int32_t o_bound, int32_t *d_words, int32_t *state, int32_t *prefix_completion, hipStream_t st)
+{
+    SimParams q;
+    q.src.orders = row0;
+    q.src.base = nullptr;
+    q.src.moves = nullptr;
+    q.C = 1;
+    q.n = n;
+    q.s = s;
+    q.o = o;
+    q.M = (int32_t)M;
+    q.tel_out = nullptr;
+    q.completion_out = prefix_completion;
+    q.completion_by_position = 1;
+    q.d_words = d_words;
+    q.o_bound = o_bound;
+    q.k_begin = 0;
+    q.k_end = cp;
+    q.state_out = state;
+    return kvs_launch_simulate_reg(q, st);
 }
 
 int check_common(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M)
@@ -204,13 +245,34 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     p.completion_by_position = (completion_out && n <= KVS_PERMUTE_MAX_N) ? 1 : 0;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
+    // Declared common prefix: run it once (row 0), resume every row from its state.
+    int32_t cp = 0;
+    int32_t *prefix_comp = nullptr;
+    if (common_prefix >= kMinSharedPrefix && C > 1 && o_bound <= KVS_REG_MAX_O &&
+        (!completion_out || p.completion_by_position)) {
+        cp = common_prefix;
+        rc = ensure_scratch(ctx, state_bytes() + align256(sizeof(int32_t) * (size_t)cp));
+        if (rc != KVSCHED_OK) return rc;
+        int32_t *state = (int32_t *)ctx->d_scratch;
+        if (completion_out) prefix_comp = (int32_t *)((char *)ctx->d_scratch + state_bytes());
+        rc = run_shared_prefix(orders, cp, n, s, o, M, o_bound, ctx->d_words, state, prefix_comp, st);
+        if (rc != KVSCHED_OK) return rc;
+        p.k_begin = cp;
+        p.state_in = state;
+    }
     rc = run_timelines(ctx, p, H, st);
     if (rc != KVSCHED_OK) return rc;
+    if (prefix_comp) {
+        rc = kvs_launch_broadcast_prefix(prefix_comp, cp, C, n, completion_out, st);
+        if (rc != KVSCHED_OK) return rc;
+    }
     if (p.completion_by_position) {
         rc = kvs_launch_permute_rows(orders, C, n, completion_out, st);
         if (rc != KVSCHED_OK) return rc;
     }
-    return kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
+    rc = kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
+    if (rc != KVSCHED_OK || cp == 0) return rc;
+    return kvs_launch_check_prefix(orders, C, n, cp, tel_out, ctx->d_words, st);
 }
 
 int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
@@ -238,11 +300,14 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     if (rc != KVSCHED_OK) return rc;
     if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    rc = ensure_scratch(ctx, sizeof(int64_t) * ((size_t)K + 1));
+    // scratch: [K+1] latencies (neighbours, then the base order) | state of the shared prefix
+    const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1));
+    rc = ensure_scratch(ctx, tel_bytes + state_bytes());
     if (rc != KVSCHED_OK) return rc;
-    int64_t *tel = (int64_t *)ctx->d_scratch;  // [K] neighbours, then the base order itself
-    int32_t o_bound = 0;
-    rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound);
+    int64_t *tel = (int64_t *)ctx->d_scratch;
+    int32_t *state = (int32_t *)((char *)ctx->d_scratch + tel_bytes);
+    int32_t o_bound = 0, min_pos = 0;
+    rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound, moves, K, &min_pos);
     if (rc != KVSCHED_OK) return rc;
     const int32_t H = ring_slots_for(o_bound);
     if ((int64_t)n * (int64_t)H >= kMaxM) return KVSCHED_ERANGE;
@@ -260,6 +325,14 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     p.completion_by_position = 0;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
+    // No move touches a position before min_pos: that prefix of the base order is common to
+    // every neighbour, so it is placed once and all timelines resume from its state.
+    if (min_pos >= kMinSharedPrefix && o_bound <= KVS_REG_MAX_O) {
+        rc = run_shared_prefix(base_order, min_pos, n, s, o, M, o_bound, ctx->d_words, state, nullptr, st);
+        if (rc != KVSCHED_OK) return rc;
+        p.k_begin = min_pos;
+        p.state_in = state;
+    }
     rc = run_timelines(ctx, p, H, st);
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_check_moves(moves, K, n, tel, ctx->d_words, st);
@@ -282,8 +355,8 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     if (K < 1 || K == INT32_MAX || n < 1) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     // scratch: [K+1] latencies of best_neighbor | new order [n] | completion rounds [n] | one latency
-    const size_t tel_bytes = (sizeof(int64_t) * ((size_t)K + 1) + 255) & ~(size_t)255;
-    const size_t row_bytes = (sizeof(int32_t) * (size_t)n + 255) & ~(size_t)255;
+    const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1)) + state_bytes();  // best_neighbor's part
+    const size_t row_bytes = align256(sizeof(int32_t) * (size_t)n);
     int rc = ctx ? ensure_scratch(ctx, tel_bytes + 2 * row_bytes + 256) : KVSCHED_EINVAL;
     if (rc != KVSCHED_OK) return rc;
     // 1. best move of the window (result_out[0..2])

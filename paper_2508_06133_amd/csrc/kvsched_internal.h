@@ -10,6 +10,7 @@
 enum {
     KVS_W_STATUS = 0,  // OR of KVSCHED_DEV_* bits for the call in flight
     KVS_W_OMAX = 1,    // largest decode length found by the length scan
+    KVS_W_MINPOS = 2,  // smallest position any move touches (best_neighbor)
     KVS_W_COUNT = 8
 };
 
@@ -44,7 +45,15 @@ struct SimParams {
     int32_t completion_by_position;  // 1: row entry k = completion of position k (a later pass permutes)
     int32_t *d_words;
     int32_t o_bound;          // lengths above this are reported, not simulated
+    // Register kernel only: simulate positions [k_begin, k_end) (k_end == 0: up to n), starting
+    // from / leaving behind a timeline state of KVS_STATE_WORDS(NR) int32 words:
+    // {B, t, tel low, tel high, 60 unused, then the NR x 64 profile registers}.
+    int32_t k_begin = 0;
+    int32_t k_end = 0;
+    const int32_t *state_in = nullptr;
+    int32_t *state_out = nullptr;
 };
+constexpr size_t KVS_STATE_MAX_WORDS = 64 + 65 * 64;
 
 // simulate.hip
 int kvs_launch_scan_lengths(const int32_t *s, const int32_t *o, int32_t n, int32_t M, int32_t o_bound,
@@ -75,3 +84,10 @@ int kvs_launch_apply_best_move(const int32_t *order, int32_t n, const int32_t *m
                                int32_t *order_out, hipStream_t st);
 int kvs_launch_horizon_advance(const int32_t *order, const int32_t *completion, const int32_t *o, int32_t n,
                                int64_t completed_in, int32_t complete_every, int64_t *result_out, hipStream_t st);
+
+// prefix.hip
+int kvs_launch_moves_min_position(const int32_t *moves, int32_t K, int32_t n, int32_t *d_words, hipStream_t st);
+int kvs_launch_check_prefix(const int32_t *orders, int32_t C, int32_t n, int32_t cp, int64_t *tel_out,
+                            int32_t *d_words, hipStream_t st);
+int kvs_launch_broadcast_prefix(const int32_t *prefix, int32_t cp, int32_t C, int32_t n, int32_t *completion,
+                                hipStream_t st);

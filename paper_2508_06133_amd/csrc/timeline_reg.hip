@@ -82,6 +82,46 @@ __device__ __forceinline__ void prof_init()
 #undef KVS_STMT
 }
 
+// The register file to / from memory (row r of lane l at word 64 r + l): a timeline that has
+// placed a common prefix of the order is saved once and resumed by every candidate.
+template <int NR>
+__device__ __forceinline__ void prof_store(int32_t *rows, int lane)
+{
+    int voff = lane * 4;
+#define KVS_STMT(CLOB)                                                            \
+    asm volatile(".set kvs_r, 0\n"                                                \
+                 ".rept %c[nr]\n"                                                 \
+                 "  global_store_dword %[voff], v[" KVS_PB "+kvs_r], %[base]\n"   \
+                 "  v_add_u32 %[voff], 0x100, %[voff]\n"                          \
+                 "  .set kvs_r, kvs_r+1\n"                                        \
+                 ".endr\n"                                                        \
+                 "s_waitcnt vmcnt(0)\n"                                           \
+                 : [voff] "+v"(voff)                                              \
+                 : [base] "s"(rows), [nr] "n"(NR)                                 \
+                 : "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
+template <int NR>
+__device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
+{
+    int voff = lane * 4;
+#define KVS_STMT(CLOB)                                                            \
+    asm volatile(".set kvs_r, 0\n"                                                \
+                 ".rept %c[nr]\n"                                                 \
+                 "  global_load_dword v[" KVS_PB "+kvs_r], %[voff], %[base]\n"    \
+                 "  v_add_u32 %[voff], 0x100, %[voff]\n"                          \
+                 "  .set kvs_r, kvs_r+1\n"                                        \
+                 ".endr\n"                                                        \
+                 "s_waitcnt vmcnt(0)\n"                                           \
+                 : [voff] "+v"(voff)                                              \
+                 : [base] "s"(rows), [nr] "n"(NR)                                 \
+                 : "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
 // Rows move down by one: row r takes over the rounds of row r + 1 (whose offset was 64 more);
 // the top row becomes empty.
 template <int NR>
@@ -252,7 +292,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     const int cand = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + (threadIdx.x >> 6));
     if (cand >= p.C) return;
 
-    const int n = p.n;
+    const int n_all = p.n;
     const int M = p.M;
     OrderReader<MOVES> rd;
     if (MOVES) {
@@ -261,40 +301,58 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         rd.mi = rd.mj = 0;
         if (cand < p.C - 1) {  // the last timeline is the base order itself
             rd.mt = p.src.moves[3 * (size_t)cand];
-            rd.mi = min(max(p.src.moves[3 * (size_t)cand + 1], 0), n - 1);
-            rd.mj = min(max(p.src.moves[3 * (size_t)cand + 2], 0), n - 1);
+            rd.mi = min(max(p.src.moves[3 * (size_t)cand + 1], 0), n_all - 1);
+            rd.mj = min(max(p.src.moves[3 * (size_t)cand + 2], 0), n_all - 1);
         }
     } else {
-        rd.row = p.src.orders + (size_t)cand * (size_t)n;
+        rd.row = p.src.orders + (size_t)cand * (size_t)n_all;
         rd.mt = rd.mi = rd.mj = 0;
     }
-    int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n : nullptr;
+    int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n_all : nullptr;
 
-    prof_init<NR>();
+    // positions [k_first, n) of the order are placed; the state after the first k_first ones
+    // (a prefix shared by all candidates) comes from memory when there is one
+    const int k_first = p.k_begin;
+    const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
     int B = 0;  // row r of lane l is round 64 * (B + r) + l
     long long tel = 0;
     int t = 0;  // start round of the previous request in the order
+    if (p.state_in) {
+        if (p.state_in[1] < 0) {  // the shared prefix could not be scheduled
+            if (lane == 0 && p.tel_out) p.tel_out[cand] = -1;
+            return;
+        }
+        B = p.state_in[0];
+        t = p.state_in[1];
+        tel = (long long)(((unsigned long long)(unsigned)p.state_in[3] << 32) | (unsigned)p.state_in[2]);
+        prof_load<NR>(p.state_in + 64, lane);
+    } else {
+        prof_init<NR>();
+    }
 
     // 64 positions of the order at a time: ids read coalesced, lengths gathered; the next
     // block is fetched while the current one is being placed
     int rq_n = 0, sv_n = 1, ov_n = 1;
-    if (lane < n) {
-        rq_n = min(max(rd.at(lane), 0), n - 1);
+    if (k_first + lane < n) {
+        rq_n = min(max(rd.at(k_first + lane), 0), n_all - 1);
         sv_n = p.s[rq_n];
         ov_n = p.o[rq_n];
     }
-    for (int k0 = 0; k0 < n; k0 += WAVE) {
+    for (int k0 = k_first; k0 < n; k0 += WAVE) {
         const int k = k0 + lane;
         const int rq = rq_n, sv = sv_n, ov = ov_n;
         rq_n = 0, sv_n = 1, ov_n = 1;
         if (k + WAVE < n) {
-            rq_n = min(max(rd.at(k + WAVE), 0), n - 1);
+            rq_n = min(max(rd.at(k + WAVE), 0), n_all - 1);
             sv_n = p.s[rq_n];
             ov_n = p.o[rq_n];
         }
         const bool bad = (sv < 1) | (ov < 1) | (ov > p.o_bound) | ((long long)sv + (long long)ov > (long long)M);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever
-            if (lane == 0) p.tel_out[cand] = -1;
+            if (lane == 0) {
+                if (p.tel_out) p.tel_out[cand] = -1;
+                if (p.state_out) p.state_out[1] = -1;  // poisons every timeline that resumes from it
+            }
             return;
         }
         const int cnt = min(WAVE, n - k0);
@@ -333,7 +391,16 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         }
         if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
-    if (lane == 0) p.tel_out[cand] = tel;
+    if (p.state_out) {
+        if (lane == 0) {
+            p.state_out[0] = B;
+            p.state_out[1] = t;
+            p.state_out[2] = (int)(unsigned)((unsigned long long)tel & 0xffffffffull);
+            p.state_out[3] = (int)(unsigned)((unsigned long long)tel >> 32);
+        }
+        prof_store<NR>(p.state_out + 64, lane);
+    }
+    if (lane == 0 && p.tel_out) p.tel_out[cand] = tel;
 }
 
 template <int NR, int WPB>

@@ -207,3 +207,46 @@ def test_host_side_errors(ctx):
     assert e.value.code == -2  # longest decode beyond the supported ring
     with pytest.raises(TypeError):
         ctx.simulate(orders.to(torch.int64), s, o, 10)
+
+
+def _gpu_simulate_hint(ctx, s_h, o_h, M, rows, cp, completions=True):
+    import torch
+
+    dev = torch.device("cuda:0")
+    s = torch.from_numpy(np.ascontiguousarray(s_h, dtype=np.int32)).to(dev)
+    o = torch.from_numpy(np.ascontiguousarray(o_h, dtype=np.int32)).to(dev)
+    orders = torch.from_numpy(np.ascontiguousarray(rows, dtype=np.int32)).to(dev)
+    tel, comp = ctx.simulate(orders, s, o, M, completions=completions, common_prefix=cp)
+    torch.cuda.synchronize()
+    return tel.cpu().numpy(), (comp.cpu().numpy() if comp is not None else None), ctx.device_status()
+
+
+@pytest.mark.parametrize("cfg,n,cp,C", [(3, 500, 200, 300), (2, 200, 64, 50), (3, 333, 333, 5), (5, 1500, 1000, 20)])
+def test_common_prefix_hint_never_changes_results(ctx, cfg, n, cp, C):
+    inst = workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rng = np.random.default_rng(cfg * 100 + cp)
+    rows = np.broadcast_to(base, (C, n)).copy()
+    for c in range(1, C):  # rows agree on the first cp positions, the rest is shuffled
+        rows[c, cp:] = rng.permutation(rows[c, cp:])
+    print(f"common prefix: config {cfg} n={n} cp={cp} C={C}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    for completions in (True, False):
+        tel_g, comp_g, status = _gpu_simulate_hint(ctx, inst.s, inst.o, inst.M, rows, cp, completions)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o, "common prefix")
+
+
+def test_wrong_common_prefix_hint_is_reported(ctx):
+    from paper_2508_06133_amd import kvsched
+
+    inst = workloads.instance(2, n=200)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = np.broadcast_to(base, (6, 200)).copy()
+    rows[3, [10, 150]] = rows[3, [150, 10]]  # row 3 differs at position 10, inside the declared prefix
+    rows[5, [120, 180]] = rows[5, [180, 120]]
+    tel_o, _ = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    tel_g, _, status = _gpu_simulate_hint(ctx, inst.s, inst.o, inst.M, rows, 100)
+    assert status == kvsched.DEV_BAD_ORDER and tel_g[3] == -1
+    keep = [0, 1, 2, 4, 5]
+    assert (tel_g[keep] == tel_o[keep]).all()

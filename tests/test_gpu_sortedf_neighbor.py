@@ -136,3 +136,27 @@ def test_best_neighbor_bad_moves(ctx):
     tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, good, literal=False)
     assert tel_g[0] == tel_o[0] and tel_g[4] == tel_o[1]
     assert res_g[0] == (0, 4)[res_o[0]] and res_g[1] == res_o[1] and res_g[2] == res_o[2]
+
+
+@pytest.mark.parametrize("cfg,n,lo,width,K", [(3, 700, 300, 200, 500), (2, 200, 64, 100, 300), (4, 1500, 1333, 167, 256),
+                                              (5, 2000, 1500, 400, 64)])
+def test_best_neighbor_shared_prefix(ctx, cfg, n, lo, width, K):
+    # every move lies at or beyond position lo >= 64: the library places the common prefix once and
+    # resumes all neighbours from its state; results must not change
+    inst = workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    moves = workloads.window_moves(np.random.default_rng(cfg + 10), K, lo, min(n, lo + width))
+    print(f"best_neighbor shared prefix config {cfg}: n={n} window [{lo},{lo + width}) K={K}", flush=True)
+    tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=False)
+    tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+    assert (tel_g == tel_o).all() and res_g == res_o
+    assert ctx.device_status() == 0
+
+
+def test_best_neighbor_only_identity_moves(ctx):
+    inst = workloads.instance(2, n=130)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    moves = np.array([(0, 5, 5), (1, 70, 70), (0, 129, 129)], dtype=np.int32)
+    tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=False)
+    tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+    assert (tel_g == tel_o).all() and res_g == res_o and res_g[0] == 0 and res_g[1] == res_g[2]
