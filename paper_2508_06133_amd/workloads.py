@@ -120,20 +120,19 @@ def random_swap_moves(rng: np.random.Generator, count: int, lo: int, hi: int, di
 
 
 def window_moves(rng: np.random.Generator, count: int, lo: int, hi: int) -> np.ndarray:
-    """Move 0 is the identity; the rest are half swaps, half inserts inside [lo, hi)."""
+    """Move 0 is the identity; the rest alternate swaps (odd index) and inserts (even index) on two
+    different positions drawn uniformly inside [lo, hi)."""
     moves = np.zeros((count, 3), dtype=np.int32)
-    moves[0] = (MOVE_SWAP, lo, lo)
-    if hi - lo < 2:
-        moves[:, 1] = lo
-        moves[:, 2] = lo
+    moves[:, 1] = lo
+    moves[:, 2] = lo
+    if hi - lo < 2 or count < 2:
         return moves
-    k = 1
-    while k < count:
-        i, j = (int(x) for x in rng.integers(lo, hi, 2))
-        if i == j:
-            continue
-        moves[k] = (MOVE_SWAP if k % 2 else MOVE_INSERT, i, j)
-        k += 1
+    i = rng.integers(lo, hi, count - 1)
+    j = rng.integers(lo, hi - 1, count - 1)
+    j = j + (j >= i)  # uniform over the positions other than i
+    moves[1:, 0] = np.where(np.arange(1, count) % 2 == 1, MOVE_SWAP, MOVE_INSERT)
+    moves[1:, 1] = i
+    moves[1:, 2] = j
     return moves
 
 
