@@ -5,9 +5,9 @@
 // the smallest round t >= the previous start at which P(tau) + s + (tau - t) <= M for all
 // tau in (t, t + o]  (Eq. 1), P being the memory already committed to round tau.
 //
-// Layout.  The profile of rounds 64*B .. 64*(B+NR)-1 lives in NR vector registers: register
-// r of lane l belongs to round 64*(B+r) + l and holds Q = P + 64*r.  B is kept equal to
-// floor((t+1)/64), so the window (t, t+o] of the request being placed always starts in
+// Layout.  The profile of rounds b64 .. b64 + 64 NR - 1 lives in NR vector registers: register
+// r of lane l belongs to round b64 + 64 r + l and holds Q = P + 64 r.  b64 is kept equal to
+// 64 floor((t+1)/64), so the window (t, t+o] of the request being placed always starts in
 // register 0 and, with NR = ceil(o_max/64) + 1, always ends inside the file.  When t crosses
 // a multiple of 64 the file moves down by one register (NR subtract-64 moves per 64 rounds
 // of simulated time) and an empty row enters at the top.  There is no LDS traffic, no
@@ -17,15 +17,21 @@
 //           lane's round in row 0.  Rounds at or before t yield at most their own index, i.e.
 //           nothing above t, so the dead lanes in front of the window need no mask.
 //   update  per row:  Q_r += s + (tau - t)
-//   Only the last row of a window is lane-masked (rounds beyond t + o).
+//   Only the last row of a window is lane-masked (rounds beyond t + o), by value.
 //
-// The row loops are hand-written gfx950 assembly: the register file is a fixed block of
-// physical VGPRs (v24 upward) that only these assembly blocks touch; full rows run as an
-// unrolled chain with one scalar compare-and-branch per row (rows are paired so that two
-// rows cost five vector instructions in the check and three in the update), the last (masked)
-// row is reached through VGPR index mode.  The compiler-generated part of the kernel needs
-// fewer than 24 VGPRs, so it never allocates the block (the build verifies that); the clobber
-// lists keep the block out of its hands across the assembly statements.
+// The row loops are hand-written gfx950 assembly over a fixed block of physical VGPRs (v24
+// upward) that only these assembly blocks touch.  The kernel is bound by the scalar unit (one per
+// compute unit, shared by its four SIMDs: adding eight scalar instructions per request cost
+// 11 % of the run time, eight vector instructions 1.6 %), so the loops are laid out to need
+// almost no scalar work: a pass over rows 0..re is entered by one computed jump
+// (s_getpc / s_setpc, 64-byte slots) to a stub that handles the masked last row `re` with
+// constant register numbers and then branches into a descending chain of full rows re-1..0,
+// which runs to its end without a single compare or branch.  Rows are paired (five vector
+// instructions per two rows in the check, three in the update).  Only the rounds that enter
+// the window after t has moved are reached through VGPR index mode.
+// The compiler-generated part of the kernel needs fewer than 24 VGPRs, so it never allocates
+// the block (the build verifies that); the clobber lists keep the block, s98, s99 and vcc out
+// of its hands across the assembly statements.
 #include "kvsched_internal.h"
 #include "device_util.h"
 
@@ -45,23 +51,32 @@ namespace {
         "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85",   \
         "v86", "v87", "v88"
 
+// Row numbers as the assembler's .irp wants them: all rows ascending (one stub each), and the
+// rows that can be the last row of a window with at least one full row below, descending.
+#define KVS_ASC_9 "0,1,2,3,4,5,6,7,8"
+#define KVS_DESC_9 "8,7,6,5,4,3,2,1"
+#define KVS_ASC_33 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32"
+#define KVS_DESC_33 "32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
+#define KVS_ASC_65 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63,64"
+#define KVS_DESC_65 "64,63,62,61,60,59,58,57,56,55,54,53,52,51,50,49,48,47,46,45,44,43,42,41,40,39,38,37,36,35,34,33,32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
+
 // gfx950 needs a wait state between s_set_gpr_idx_on and the first VALU instruction that uses
 // the index: issued back to back, about 0.3 % of the timelines of a fully occupied GPU came
 // out wrong (never on a lightly loaded one); a single s_nop removed every mismatch.  Two wait
 // states are inserted.
 #define KVS_IDX_WAIT "s_nop 1\n"
 
-// Expands STMT(clobber-list) for the instantiated file size (NR - 1 must be even: the row
-// chains process rows in pairs).
+// Expands STMT(clobber-list, rows ascending, rows descending) for the instantiated file size
+// (NR - 1 must be even: the row chains process rows in pairs).
 #define KVS_FOR_NR(STMT)                                                                            \
     do {                                                                                            \
         if constexpr (NR == 9) {                                                                    \
-            STMT(KVS_CLOB_9);                                                                       \
+            STMT(KVS_CLOB_9, KVS_ASC_9, KVS_DESC_9);                                                \
         } else if constexpr (NR == 33) {                                                            \
-            STMT(KVS_CLOB_33);                                                                      \
+            STMT(KVS_CLOB_33, KVS_ASC_33, KVS_DESC_33);                                             \
         } else {                                                                                    \
             static_assert(NR == 9 || NR == 33 || NR == 65, "profile file sizes: 9, 33 or 65 rows"); \
-            STMT(KVS_CLOB_65);                                                                      \
+            STMT(KVS_CLOB_65, KVS_ASC_65, KVS_DESC_65);                                             \
         }                                                                                           \
     } while (0)
 
@@ -69,7 +84,7 @@ namespace {
 template <int NR>
 __device__ __forceinline__ void prof_init()
 {
-#define KVS_STMT(CLOB)                                         \
+#define KVS_STMT(CLOB, ASC, DESC)                                        \
     asm volatile(".set kvs_r, 0\n"                             \
                  ".rept %c[nr]\n"                              \
                  "  v_mov_b32 v[" KVS_PB "+kvs_r], 64*kvs_r\n" \
@@ -88,7 +103,7 @@ template <int NR>
 __device__ __forceinline__ void prof_store(int32_t *rows, int lane)
 {
     int voff = lane * 4;
-#define KVS_STMT(CLOB)                                                            \
+#define KVS_STMT(CLOB, ASC, DESC)                                                           \
     asm volatile(".set kvs_r, 0\n"                                                \
                  ".rept %c[nr]\n"                                                 \
                  "  global_store_dword %[voff], v[" KVS_PB "+kvs_r], %[base]\n"   \
@@ -107,7 +122,7 @@ template <int NR>
 __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 {
     int voff = lane * 4;
-#define KVS_STMT(CLOB)                                                            \
+#define KVS_STMT(CLOB, ASC, DESC)                                                           \
     asm volatile(".set kvs_r, 0\n"                                                \
                  ".rept %c[nr]\n"                                                 \
                  "  global_load_dword v[" KVS_PB "+kvs_r], %[voff], %[base]\n"    \
@@ -127,7 +142,7 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 template <int NR>
 __device__ __forceinline__ void prof_rotate1()
 {
-#define KVS_STMT(CLOB)                                                             \
+#define KVS_STMT(CLOB, ASC, DESC)                                                            \
     asm volatile(".set kvs_r, 0\n"                                                 \
                  ".rept %c[nrm1]\n"                                                \
                  "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n" \
@@ -141,52 +156,59 @@ __device__ __forceinline__ void prof_rotate1()
 #undef KVS_STMT
 }
 
-// The last row `re` of a window, common tail of both checks: acc = max(acc, c) on the lanes
-// of `lm` only.
-#define KVS_CHECK_LAST_ROW                                 \
-    "s_set_gpr_idx_on %[re], gpr_idx(SRC0)\n" KVS_IDX_WAIT \
-    "v_mov_b32 %[y], v[" KVS_PB "]\n"                      \
-    "s_set_gpr_idx_off\n"                                  \
-    "s_lshl_b32 %[t0], %[re], 6\n"                         \
-    "v_add_u32 %[y], %[sb], %[y]\n"                        \
-    "v_min_i32 %[y], %[t0], %[y]\n"                        \
-    "s_and_saveexec_b64 %[sv], %[lm]\n"                    \
-    "v_max_i32 %[acc], %[acc], %[y]\n"                     \
-    "s_mov_b64 exec, %[sv]\n"
+// Computed jump to the 64-byte slot of row re = x64/64 - 1: the slots start 64 bytes after the
+// instruction that follows s_getpc_b64 (four 4-byte instructions, then padding).
+#define KVS_DISPATCH                      \
+    "s_getpc_b64 s[98:99]\n"              \
+    "s_andn2_b32 %[t0], %[x64], 63\n"     \
+    "s_add_u32 s98, s98, %[t0]\n"         \
+    "s_addc_u32 s99, s99, 0\n"            \
+    "s_setpc_b64 s[98:99]\n"              \
+    ".fill 12, 4, 0xbf800000\n"
+
+// Pads the slot that began at the last label 7 to 64 bytes (never executed: slots end in a branch).
+#define KVS_SLOT_END "  .fill (64-(.-7b))/4, 4, 0xbf800000\n"
 
 // Rows 0..re (row 0 holds round t + 1): per lane, the largest over its rounds of the least
-// admissible start, relative to the lane's round in row 0.  lm = lanes of row re inside the
-// window; sb = s - M.  Full rows are taken two at a time (one three-input max per pair); an
-// exit after an odd number of rows first folds the pending row in (label 2).
+// admissible start, relative to the lane's round in row 0.  x64 = (t + o - b64) + 64, so that
+// re = x64/64 - 1 and the last round of the window sits in lane x64 & 63 of row re; sb = s - M;
+// vmin = INT_MIN in every lane.
 template <int NR>
-__device__ __forceinline__ int prof_check_from0(int re, int sb, unsigned long long lm)
+__device__ __forceinline__ int prof_check_from0(int x64, int sb, int lane, int vmin)
 {
     int acc, y, z, t0;
-    unsigned long long sv;
-#define KVS_STMT(CLOB)                                                                                  \
-    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                              \
-                 ".set kvs_r, 0\n"                                                                      \
-                 ".rept %c[nrm1]\n"                                                                     \
-                 "  s_cmp_le_u32 %[re], kvs_r\n"                                                        \
-                 "  .if (kvs_r & 1) == 0\n"                                                             \
-                 "    s_cbranch_scc1 1f\n"                                                              \
-                 "    v_add_u32 %[y], %[sb], v[" KVS_PB "+kvs_r]\n"                                     \
-                 "    v_min_i32 %[y], 64*kvs_r, %[y]\n"                                                 \
-                 "  .else\n"                                                                            \
-                 "    s_cbranch_scc1 2f\n"                                                              \
-                 "    v_add_u32 %[z], %[sb], v[" KVS_PB "+kvs_r]\n"                                     \
-                 "    v_min_i32 %[z], 64*kvs_r, %[z]\n"                                                 \
-                 "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                          \
-                 "  .endif\n"                                                                           \
-                 "  .set kvs_r, kvs_r+1\n"                                                              \
-                 ".endr\n"                                                                              \
-                 "s_branch 1f\n"                                                                        \
-                 "2:\n"                                                                                 \
-                 "v_max_i32 %[acc], %[acc], %[y]\n"                                                     \
-                 "1:\n" KVS_CHECK_LAST_ROW                                                              \
-                 : [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [t0] "=&s"(t0), [sv] "=&s"(sv)         \
-                 : [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm), [nrm1] "n"(NR - 1)                         \
-                 : "scc", CLOB)
+#define KVS_STMT(CLOB, ASC, DESC)                                                              \
+    asm volatile("s_and_b32 %[t0], %[x64], 63\n"                                               \
+                 "v_cmp_ge_u32 vcc, %[t0], %[lane]\n" KVS_DISPATCH                             \
+                 ".irp r," ASC "\n"                                                            \
+                 "7:\n"                                                                        \
+                 "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                \
+                 "  v_min_i32 %[y], 64*\\r, %[y]\n"                                            \
+                 "  v_cndmask_b32 %[acc], %[vmin], %[y], vcc\n"                                \
+                 "  .if \\r == 0\n"                                                            \
+                 "    s_branch 9f\n"                                                           \
+                 "  .else\n"                                                                   \
+                 "    .if (\\r & 1) == 1\n"                                                    \
+                 "      v_mov_b32 %[z], %[acc]\n"                                              \
+                 "    .endif\n"                                                                \
+                 "    s_branch 20\\r\\()f\n"                                                   \
+                 "  .endif\n" KVS_SLOT_END                                                     \
+                 ".endr\n"                                                                     \
+                 ".irp r," DESC "\n"                                                           \
+                 "20\\r:\n"                                                                    \
+                 "  .if ((\\r-1) & 1) == 1\n"                                                  \
+                 "    v_add_u32 %[z], %[sb], v[" KVS_PB "+\\r-1]\n"                            \
+                 "    v_min_i32 %[z], 64*(\\r-1), %[z]\n"                                      \
+                 "  .else\n"                                                                   \
+                 "    v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r-1]\n"                            \
+                 "    v_min_i32 %[y], 64*(\\r-1), %[y]\n"                                      \
+                 "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                 \
+                 "  .endif\n"                                                                  \
+                 ".endr\n"                                                                     \
+                 "9:\n"                                                                        \
+                 : [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [t0] "=&s"(t0)                \
+                 : [x64] "s"(x64), [sb] "s"(sb), [lane] "v"(lane), [vmin] "v"(vmin)            \
+                 : "scc", "vcc", "s98", "s99", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
     return acc;
@@ -195,12 +217,13 @@ __device__ __forceinline__ int prof_check_from0(int re, int sb, unsigned long lo
 // The same over rows rs..re with rs > 0 unknown at compile time (the rounds that entered the
 // window after t moved): short scalar loop through VGPR index mode.
 template <int NR>
-__device__ __forceinline__ int prof_check_from(int rs, int re, int sb, unsigned long long lm)
+__device__ __forceinline__ int prof_check_from(int rs, int x64, int sb, int lane, int vmin)
 {
-    int acc, y, t0, t1;
-    unsigned long long sv;
-#define KVS_STMT(CLOB)                                                                            \
-    asm volatile("v_bfrev_b32 %[acc], 1\n"                                                        \
+    int acc, y, t0, t1, re;
+#define KVS_STMT(CLOB, ASC, DESC)                                                                 \
+    asm volatile("v_mov_b32 %[acc], %[vmin]\n"                                                    \
+                 "s_lshr_b32 %[re], %[x64], 6\n"                                                  \
+                 "s_sub_u32 %[re], %[re], 1\n"                                                    \
                  "s_mov_b32 %[t1], %[rs]\n"                                                       \
                  "s_cmp_ge_u32 %[t1], %[re]\n"                                                    \
                  "s_cbranch_scc1 2f\n"                                                            \
@@ -215,48 +238,74 @@ __device__ __forceinline__ int prof_check_from(int rs, int re, int sb, unsigned 
                  "s_add_u32 %[t1], %[t1], 1\n"                                                    \
                  "s_cmp_lt_u32 %[t1], %[re]\n"                                                    \
                  "s_cbranch_scc1 1b\n"                                                            \
-                 "2:\n" KVS_CHECK_LAST_ROW                                                        \
-                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [t1] "=&s"(t1), [sv] "=&s"(sv) \
-                 : [rs] "s"(rs), [re] "s"(re), [sb] "s"(sb), [lm] "s"(lm)                         \
-                 : "scc", CLOB)
+                 "2:\n"                                                                           \
+                 "s_set_gpr_idx_on %[re], gpr_idx(SRC0)\n" KVS_IDX_WAIT                           \
+                 "v_mov_b32 %[y], v[" KVS_PB "]\n"                                                \
+                 "s_set_gpr_idx_off\n"                                                            \
+                 "s_lshl_b32 %[t0], %[re], 6\n"                                                   \
+                 "v_add_u32 %[y], %[sb], %[y]\n"                                                  \
+                 "v_min_i32 %[y], %[t0], %[y]\n"                                                  \
+                 "s_and_b32 %[t0], %[x64], 63\n"                                                  \
+                 "v_cmp_ge_u32 vcc, %[t0], %[lane]\n"                                             \
+                 "v_cndmask_b32 %[y], %[vmin], %[y], vcc\n"                                       \
+                 "v_max_i32 %[acc], %[acc], %[y]\n"                                               \
+                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [t1] "=&s"(t1), [re] "=&s"(re) \
+                 : [rs] "s"(rs), [x64] "s"(x64), [sb] "s"(sb), [lane] "v"(lane), [vmin] "v"(vmin) \
+                 : "scc", "vcc", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
     return acc;
 }
 
-// Admit: rows 0..re get the request's ramp.  ramp = s + (tau - t) for the lane's round in row 0;
-// it advances by 64 per row, once per pair of rows (an exit after an odd number of rows makes
-// up for the missing step at label 2).
+// Admit: rows 0..re get the request's ramp.  ramp = s + (tau - t) for the lane's round in row 0.
+// The chain of full rows runs downwards with a running ramp `e` (the ramp of the even row of
+// the current pair) that steps by -128 per pair; the lowest pair uses `ramp` itself.
 template <int NR>
-__device__ __forceinline__ void prof_update(int re, unsigned long long lm, int ramp)
+__device__ __forceinline__ void prof_update(int x64, int ramp, int lane)
 {
-    unsigned long long sv;
-#define KVS_STMT(CLOB)                                                                            \
-    asm volatile(".set kvs_r, 0\n"                                                                \
-                 ".rept %c[nrm1]\n"                                                               \
-                 "  s_cmp_le_u32 %[re], kvs_r\n"                                                  \
-                 "  .if (kvs_r & 1) == 0\n"                                                       \
-                 "    s_cbranch_scc1 1f\n"                                                        \
-                 "    v_add_u32 v[" KVS_PB "+kvs_r], %[ramp], v[" KVS_PB "+kvs_r]\n"              \
-                 "  .else\n"                                                                      \
-                 "    s_cbranch_scc1 2f\n"                                                        \
-                 "    v_add3_u32 v[" KVS_PB "+kvs_r], v[" KVS_PB "+kvs_r], %[ramp], 64\n"         \
-                 "    v_add_u32 %[ramp], 0x80, %[ramp]\n"                                         \
-                 "  .endif\n"                                                                     \
-                 "  .set kvs_r, kvs_r+1\n"                                                        \
-                 ".endr\n"                                                                        \
-                 "s_branch 1f\n"                                                                  \
-                 "2:\n"                                                                           \
-                 "v_add_u32 %[ramp], 64, %[ramp]\n"                                               \
-                 "1:\n"                                                                           \
-                 "s_and_saveexec_b64 %[sv], %[lm]\n"                                              \
-                 "s_set_gpr_idx_on %[re], gpr_idx(SRC0,DST)\n" KVS_IDX_WAIT                       \
-                 "v_add_u32 v[" KVS_PB "], v[" KVS_PB "], %[ramp]\n"                              \
-                 "s_set_gpr_idx_off\n"                                                            \
-                 "s_mov_b64 exec, %[sv]\n"                                                        \
-                 : [ramp] "+v"(ramp), [sv] "=&s"(sv)                                              \
-                 : [re] "s"(re), [lm] "s"(lm), [nrm1] "n"(NR - 1)                                 \
-                 : "scc", CLOB)
+    int y, e, t0;
+#define KVS_STMT(CLOB, ASC, DESC)                                                              \
+    asm volatile("s_and_b32 %[t0], %[x64], 63\n"                                               \
+                 "v_cmp_ge_u32 vcc, %[t0], %[lane]\n" KVS_DISPATCH                             \
+                 ".irp r," ASC "\n"                                                            \
+                 "7:\n"                                                                        \
+                 "  .if \\r == 0\n"                                                            \
+                 "    v_cndmask_b32 %[y], 0, %[ramp], vcc\n"                                   \
+                 "  .else\n"                                                                   \
+                 "    v_add_u32 %[y], 64*\\r, %[ramp]\n"                                       \
+                 "    v_cndmask_b32 %[y], 0, %[y], vcc\n"                                      \
+                 "  .endif\n"                                                                  \
+                 "  v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                    \
+                 "  .if \\r >= 3\n"                                                            \
+                 "    v_add_u32 %[e], 128*((\\r-1)/2), %[ramp]\n"                              \
+                 "  .endif\n"                                                                  \
+                 "  .if \\r == 0\n"                                                            \
+                 "    s_branch 8f\n"                                                           \
+                 "  .else\n"                                                                   \
+                 "    s_branch 30\\r\\()f\n"                                                   \
+                 "  .endif\n" KVS_SLOT_END                                                     \
+                 ".endr\n"                                                                     \
+                 ".irp r," DESC "\n"                                                           \
+                 "30\\r:\n"                                                                    \
+                 "  .if (\\r-1) >= 2\n"                                                        \
+                 "    .if ((\\r-1) & 1) == 1\n"                                                \
+                 "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[e], 64\n"       \
+                 "    .else\n"                                                                 \
+                 "      v_add_u32 v[" KVS_PB "+\\r-1], %[e], v[" KVS_PB "+\\r-1]\n"            \
+                 "      v_add_u32 %[e], 0xffffff80, %[e]\n"                                    \
+                 "    .endif\n"                                                                \
+                 "  .else\n"                                                                   \
+                 "    .if ((\\r-1) & 1) == 1\n"                                                \
+                 "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[ramp], 64\n"    \
+                 "    .else\n"                                                                 \
+                 "      v_add_u32 v[" KVS_PB "+\\r-1], %[ramp], v[" KVS_PB "+\\r-1]\n"         \
+                 "    .endif\n"                                                                \
+                 "  .endif\n"                                                                  \
+                 ".endr\n"                                                                     \
+                 "8:\n"                                                                        \
+                 : [y] "=&v"(y), [e] "=&v"(e), [t0] "=&s"(t0)                                  \
+                 : [x64] "s"(x64), [ramp] "v"(ramp), [lane] "v"(lane)                          \
+                 : "scc", "vcc", "s98", "s99", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
 }
@@ -314,21 +363,24 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     // (a prefix shared by all candidates) comes from memory when there is one
     const int k_first = p.k_begin;
     const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
-    int B = 0;  // row r of lane l is round 64 * (B + r) + l
-    long long tel = 0;
-    int t = 0;  // start round of the previous request in the order
+    int b64 = 0;             // round of lane 0 of register 0: 64 * floor((t + 1) / 64)
+    int t = 0;               // start round of the previous request in the order
+    long long tel_lane = 0;  // completion rounds summed per lane; added up over the lanes at the end
     if (p.state_in) {
         if (p.state_in[1] < 0) {  // the shared prefix could not be scheduled
             if (lane == 0 && p.tel_out) p.tel_out[cand] = -1;
             return;
         }
-        B = p.state_in[0];
+        b64 = p.state_in[0];
         t = p.state_in[1];
-        tel = (long long)(((unsigned long long)(unsigned)p.state_in[3] << 32) | (unsigned)p.state_in[2]);
+        if (lane == 0)
+            tel_lane = (long long)(((unsigned long long)(unsigned)p.state_in[3] << 32) | (unsigned)p.state_in[2]);
         prof_load<NR>(p.state_in + 64, lane);
     } else {
         prof_init<NR>();
     }
+    int u64 = t - b64 + 64;  // x64 of a request is its decode length plus this
+    const int vmin = INT_MIN;
 
     // 64 positions of the order at a time: ids read coalesced, lengths gathered; the next
     // block is fetched while the current one is being placed
@@ -361,39 +413,37 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             const int sj = __builtin_amdgcn_readlane(sv, j);
             const int oj = __builtin_amdgcn_readlane(ov, j);
             const int sb = sj - M;
-            int hi = t + oj;
-            int re = (hi >> 6) - B;
-            unsigned long long lm = (2ull << (hi & 63)) - 1ull;  // lanes of row re up to round hi
-            int acc = prof_check_from0<NR>(re, sb, lm);
-            for (;;) {
-                const int need = acc + ((B << 6) + lane);  // least start this lane's rounds allow
-                if (__builtin_amdgcn_ballot_w64(need > t) == 0) break;
+            int x64 = oj + u64;  // (t + oj - b64) + 64: row and lane of the window's last round
+            int need = prof_check_from0<NR>(x64, sb, lane, vmin) + (lane + b64);  // least start the lane's rounds allow
+            while (__builtin_amdgcn_ballot_w64(need > t) != 0) {
                 t = wave_max_dpp(need);
-                const int lo = hi + 1;  // rounds up to hi have been accounted for
+                const int lo = x64 + b64 - 63;  // first round not looked at yet
                 // keep register 0 on the row of round t + 1
-                const int Bn = (t + 1) >> 6;
-                int shift = Bn - B;
-                B = Bn;
+                const int b64n = (t + 1) & ~63;
+                int shift = (b64n - b64) >> 6;
+                b64 = b64n;
+                u64 = t - b64 + 64;
+                x64 = oj + u64;
                 if (shift >= NR) {
                     prof_init<NR>();
                 } else {
                     for (; shift > 0; --shift) prof_rotate1<NR>();
                 }
-                hi = t + oj;
-                re = (hi >> 6) - B;
-                lm = (2ull << (hi & 63)) - 1ull;
-                acc = prof_check_from<NR>((lo >> 6) - B, re, sb, lm);
+                need = prof_check_from<NR>((lo - b64) >> 6, x64, sb, lane, vmin) + (lane + b64);
             }
-            // admitted at round t: holds sj + a tokens at round t + a
-            prof_update<NR>(re, lm, lane + (sj - t + (B << 6)));
-            tel += hi;
-            cv = (lane == j) ? hi : cv;
+            // admitted at round t: holds sj + a tokens at round t + a, i.e. sj - t + b64 + l in lane l of row 0
+            prof_update<NR>(x64, lane + (sj + 64 - u64), lane);
+            const int hi = t + oj;
+            cv = (lane == j) ? hi : cv;  // vector compare + select: the scalar unit is the scarce one
         }
+        tel_lane += cv;
         if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
+    for (int d = 32; d > 0; d >>= 1) tel_lane += __shfl_down(tel_lane, d);
+    const long long tel = tel_lane;  // lane 0 holds the total
     if (p.state_out) {
         if (lane == 0) {
-            p.state_out[0] = B;
+            p.state_out[0] = b64;
             p.state_out[1] = t;
             p.state_out[2] = (int)(unsigned)((unsigned long long)tel & 0xffffffffull);
             p.state_out[3] = (int)(unsigned)((unsigned long long)tel >> 32);
