@@ -30,7 +30,7 @@
 // instructions per two rows in the check, three in the update).  Only the rounds that enter
 // the window after t has moved are reached through VGPR index mode.
 // The compiler-generated part of the kernel needs fewer than 24 VGPRs, so it never allocates
-// the block (the build verifies that); the clobber lists keep the block, s98, s99 and vcc out
+// the block (the build verifies that); the clobber lists keep the block, s72, s73 and vcc out
 // of its hands across the assembly statements.
 #include "kvsched_internal.h"
 #include "device_util.h"
@@ -159,11 +159,11 @@ __device__ __forceinline__ void prof_rotate1()
 // Computed jump to the 64-byte slot of row re = x64/64 - 1: the slots start 64 bytes after the
 // instruction that follows s_getpc_b64 (four 4-byte instructions, then padding).
 #define KVS_DISPATCH                      \
-    "s_getpc_b64 s[98:99]\n"              \
+    "s_getpc_b64 s[72:73]\n"              \
     "s_andn2_b32 %[t0], %[x64], 63\n"     \
-    "s_add_u32 s98, s98, %[t0]\n"         \
-    "s_addc_u32 s99, s99, 0\n"            \
-    "s_setpc_b64 s[98:99]\n"              \
+    "s_add_u32 s72, s72, %[t0]\n"         \
+    "s_addc_u32 s73, s73, 0\n"            \
+    "s_setpc_b64 s[72:73]\n"              \
     ".fill 12, 4, 0xbf800000\n"
 
 // Pads the slot that began at the last label 7 to 64 bytes (never executed: slots end in a branch).
@@ -208,7 +208,7 @@ __device__ __forceinline__ int prof_check_from0(int x64, int sb, int lane, int v
                  "9:\n"                                                                        \
                  : [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [t0] "=&s"(t0)                \
                  : [x64] "s"(x64), [sb] "s"(sb), [lane] "v"(lane), [vmin] "v"(vmin)            \
-                 : "scc", "vcc", "s98", "s99", CLOB)
+                 : "scc", "vcc", "s72", "s73", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
     return acc;
@@ -305,7 +305,7 @@ __device__ __forceinline__ void prof_update(int x64, int ramp, int lane)
                  "8:\n"                                                                        \
                  : [y] "=&v"(y), [e] "=&v"(e), [t0] "=&s"(t0)                                  \
                  : [x64] "s"(x64), [ramp] "v"(ramp), [lane] "v"(lane)                          \
-                 : "scc", "vcc", "s98", "s99", CLOB)
+                 : "scc", "vcc", "s72", "s73", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
 }
