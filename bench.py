@@ -34,12 +34,12 @@ OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for on
 CFG = 3
 
 # HBM traffic of one launch of the dominant kernel on this workload, from rocprofv3 counters
-# (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 64666 KiB x 1.9997 (what a plain
-# 256 MiB copy reads per KiB moved) + WRITE_SIZE 128214 KiB x 1.0.  Valid only for the kernel
+# (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 64855 KiB x 1.9997 (what a plain
+# 256 MiB copy reads per KiB moved) + WRITE_SIZE 128445 KiB x 1.0.  Valid only for the kernel
 # sources it was measured on; reported as null once they change.
-TRAFFIC_BYTES = int((64666 * 1.9997 + 128214 * 1.0) * 1024)
+TRAFFIC_BYTES = int((64855 * 1.9997 + 128445 * 1.0) * 1024)
 TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
-TRAFFIC_SOURCES_SHA256 = "c17f02d98744f8f2"
+TRAFFIC_SOURCES_SHA256 = "6484ac64260b01ea"
 
 
 def measured_traffic():
