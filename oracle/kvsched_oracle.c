@@ -22,6 +22,12 @@
  *                             too slow, and timed as the CPU baseline.
  *   oracle_sortedF            Algorithm 1, Phase 1, with the batch chosen among the feasible
  *                             prefixes of the requests sorted by (s+o, o, id); F of Section 4.
+ *   oracle_local_swap         Algorithm 1, Phase 1, with every batch chosen by Local Swap Search
+ *                             (the appendix algorithm of that name): greedy fill in ascending
+ *                             s+o, then first-improving single exchanges.  Two forms: the literal
+ *                             double scan, and one that leaves the inner scan at the first
+ *                             request that no longer fits (the list is sorted by s+o, so none
+ *                             after it fits either); the tests check that they agree.
  *   oracle_apply_move / oracle_best_neighbor
  *                             position-level swap / insert neighbours of an order, scored by
  *                             total end-to-end latency (Section 2, "Objective").
@@ -239,6 +245,107 @@ int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int
     }
     if (nb_out) *nb_out = nb;
     free(rem);
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------- Phase 1 (Local Swap Search) */
+
+/*
+ * One batch by Local Swap Search over the m requests rem[0..m), which are sorted by
+ * (s+o, o, id).  inX[i] = 1 marks membership.  The member set and its complement are both
+ * visited in that sorted order; a request swapped in is visited at its own sorted place.
+ *   1. greedy fill: walk the list, add a request whenever it still fits (sum of peaks <= M);
+ *   2. repeat: scan members r_out in order, for each scan non-members r_in in order; skip pairs
+ *      with mem + (w_in - w_out) > M; take the first pair whose F is smaller.  |X| does not
+ *      change in an exchange, so "F smaller" is decided exactly as S + (o_in - o_out) < S.
+ *      After an exchange both scans start again; stop when a full scan finds nothing.
+ * early_exit != 0 leaves the inner scan at the first r_in that does not fit.
+ */
+static int64_t local_swap_batch(const skey_t *rem, int32_t m, int64_t M, int early_exit,
+                                unsigned char *inX, int64_t *S_out, int64_t *K_out)
+{
+    int64_t mem = 0, S = 0, K = 0, swaps = 0;
+    for (int32_t r = 0; r < m; ++r) {
+        inX[r] = 0;
+        if (mem + rem[r].w <= M) {
+            inX[r] = 1;
+            mem += rem[r].w;
+            S += rem[r].o;
+            ++K;
+        }
+    }
+    int improved = 1;
+    while (improved) {
+        improved = 0;
+        for (int32_t a = 0; a < m && !improved; ++a) {
+            if (!inX[a]) continue;
+            for (int32_t b = 0; b < m; ++b) {
+                if (inX[b]) continue;
+                const int64_t dm = rem[b].w - rem[a].w;
+                if (mem + dm > M) {
+                    if (early_exit) break;
+                    continue;
+                }
+                const int64_t d_o = (int64_t)rem[b].o - rem[a].o;
+                if (S + d_o < S) {  /* newF < currentF, same |X| on both sides */
+                    inX[a] = 0;
+                    inX[b] = 1;
+                    mem += dm;
+                    S += d_o;
+                    ++swaps;
+                    improved = 1;
+                    break;
+                }
+            }
+        }
+    }
+    *S_out = S;
+    *K_out = K;
+    return swaps;
+}
+
+/*
+ * Phase 1 of Algorithm 1 with Local Swap Search as the batch solver: choose a batch from the
+ * remaining requests, append it in nondecreasing o (ties by id), remove it, repeat.
+ * Outputs as oracle_sortedF, plus swaps_out[b] = exchanges made while forming batch b.
+ */
+int oracle_local_swap(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t early_exit,
+                      int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
+                      int32_t *nb_out)
+{
+    if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    skey_t *rem = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
+    skey_t *batch = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
+    unsigned char *inX = (unsigned char *)malloc((size_t)n + 1);
+    if (!rem || !batch || !inX) { free(rem); free(batch); free(inX); return ORACLE_ENOMEM; }
+    for (int32_t i = 0; i < n; ++i) {
+        rem[i].w = (int64_t)s[i] + o[i];
+        rem[i].o = o[i];
+        rem[i].id = i;
+    }
+    qsort(rem, (size_t)n, sizeof(skey_t), cmp_size_o_id);
+    int32_t m = n, done = 0, nb = 0;
+    while (m > 0) {
+        int64_t S = 0, K = 0;
+        const int64_t swaps = local_swap_batch(rem, m, M, early_exit, inX, &S, &K);
+        int32_t nbatch = 0, keep = 0;
+        for (int32_t r = 0; r < m; ++r) {
+            if (inX[r]) batch[nbatch++] = rem[r];
+            else rem[keep++] = rem[r];  /* what remains stays sorted */
+        }
+        qsort(batch, (size_t)nbatch, sizeof(skey_t), cmp_o_id);
+        for (int32_t k = 0; k < nbatch; ++k) order_out[done + k] = batch[k].id;
+        done += nbatch;
+        m = keep;
+        if (batch_end_out) batch_end_out[nb] = done;
+        if (F_out) F_out[nb] = (double)S / ((double)K * (double)K);
+        if (swaps_out) swaps_out[nb] = (int32_t)swaps;
+        ++nb;
+    }
+    if (nb_out) *nb_out = nb;
+    free(rem);
+    free(batch);
+    free(inX);
     return ORACLE_OK;
 }
 
