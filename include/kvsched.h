@@ -122,6 +122,22 @@ int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t
                     int32_t *num_batches_out, void *stream);
 
 /*
+ * Phase 1 of Algorithm 1 ("Batch Construction") with every batch chosen by Local Swap Search
+ * (the appendix algorithm "Local Swap Search"): the remaining requests are sorted by
+ * (s_i + o_i, o_i, i); the batch X starts as the greedy fill in that order (sum of s_i + o_i
+ * <= M); then, repeatedly, members r_out and non-members r_in are scanned in the sorted order
+ * and the first pair with sum(s+o) still <= M after the exchange and a smaller F is exchanged
+ * (|X| is unchanged by an exchange, so F falls exactly when o_in < o_out); when a full scan
+ * finds no such pair the batch is emitted in nondecreasing o_i (ties by id) and removed.
+ *
+ *   order_out, batch_end_out, F_out, num_batches_out   as for kvsched_sortedF
+ *   swaps_out        [n] int32 or NULL: exchanges made while forming batch b; same extent
+ */
+int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                       int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                       int32_t *swaps_out, int32_t *num_batches_out, void *stream);
+
+/*
  * Local-search step on a priority order: every move is applied to `base_order` on the fly
  * (no [K][n] matrix is materialised), the resulting order is run through Phase 2 exactly
  * as in kvsched_simulate, and the move of least total latency is returned, the lowest move

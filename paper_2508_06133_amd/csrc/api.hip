@@ -292,6 +292,22 @@ int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t
                               ctx->d_scratch, ctx->d_words, st);
 }
 
+int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                       int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
+                       int32_t *num_batches_out, void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!order_out || !batch_end_out || !F_out || !num_batches_out) return KVSCHED_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    rc = ensure_scratch(ctx, kvs_local_swap_scratch_bytes(n));
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    return kvs_launch_local_swap(n, s, o, (int32_t)M, order_out, batch_end_out, F_out, swaps_out, num_batches_out,
+                                 ctx->d_scratch, ctx->d_words, st);
+}
+
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,
                           const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out, int64_t *result_out,
                           void *stream)

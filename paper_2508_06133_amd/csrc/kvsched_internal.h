@@ -69,6 +69,12 @@ int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *
                            hipStream_t st);
 int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, int32_t with_base, hipStream_t st);
 
+// localswap.hip
+size_t kvs_local_swap_scratch_bytes(int32_t n);
+int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t *order_out,
+                          int32_t *batch_end_out, double *F_out, int32_t *swaps_out, int32_t *num_batches_out,
+                          void *scratch, int32_t *d_words, hipStream_t st);
+
 // sortedf.hip
 size_t kvs_sortedF_scratch_bytes(int32_t n);
 int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule,

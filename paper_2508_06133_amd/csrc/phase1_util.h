@@ -1,0 +1,78 @@
+// Block-level building blocks of the Phase 1 kernels (one workgroup of 1024 threads builds the
+// whole order): a stable 8-bit LSD radix pass over request ids and small wavefront scans.
+#pragma once
+
+#include "kvsched_internal.h"
+
+namespace {
+
+constexpr int TPB = 1024;
+constexpr int NWAVES = TPB / 64;
+
+struct RadixLds {
+    int hist[256];
+    int wcount[NWAVES][256];  // per tile: lanes of wave w holding digit d
+    int woff[NWAVES][256];    // per tile: output offset of wave w's first lane with digit d
+};
+
+__device__ __forceinline__ unsigned long long lanemask_lt()
+{
+    return (1ull << (threadIdx.x & 63)) - 1ull;
+}
+
+// One stable counting pass on an 8-bit digit of key(id).  in/out: [n] ids.
+template <class KeyFn>
+__device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key, RadixLds &L)
+{
+    const int tid = threadIdx.x, wave = tid >> 6;
+    if (tid < 256) L.hist[tid] = 0;
+    for (int i = tid; i < NWAVES * 256; i += TPB) (&L.wcount[0][0])[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += TPB) atomicAdd(&L.hist[(key(in[i]) >> shift) & 255], 1);
+    __syncthreads();
+    if (tid == 0) {  // exclusive scan of the 256 digit counts -> running output base per digit
+        int run = 0;
+        for (int d = 0; d < 256; ++d) {
+            const int c = L.hist[d];
+            L.hist[d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (int tile = 0; tile < n; tile += TPB) {
+        const int i = tile + tid;
+        const bool valid = i < n;
+        const int id = valid ? in[i] : 0;
+        const int d = valid ? ((key(id) >> shift) & 255) : 256;
+        // lanes of this wave holding the same digit
+        unsigned long long peers = ~0ull;
+#pragma unroll
+        for (int b = 0; b < 9; ++b) {
+            const unsigned long long bal = __builtin_amdgcn_ballot_w64((d >> b) & 1);
+            peers &= ((d >> b) & 1) ? bal : ~bal;
+        }
+        const int rank = __popcll(peers & lanemask_lt());
+        if (valid && rank == 0) L.wcount[wave][d] = __popcll(peers);
+        __syncthreads();
+        if (tid < 256) {  // per digit: offsets of the waves in order, advance the running base
+            int off = L.hist[tid];
+            for (int w = 0; w < NWAVES; ++w) {
+                const int c = L.wcount[w][tid];
+                L.wcount[w][tid] = 0;  // ready for the next tile
+                L.woff[w][tid] = off;
+                off += c;
+            }
+            L.hist[tid] = off;
+        }
+        __syncthreads();
+        if (valid) out[L.woff[wave][d] + rank] = id;
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ int bits_of(long long v)
+{
+    return v <= 0 ? 1 : 64 - __clzll(v);
+}
+
+}  // namespace

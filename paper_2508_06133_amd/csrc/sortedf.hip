@@ -11,17 +11,13 @@
 //   4. per batch: feasible extent K by a two-level search on W, argmin over k <= K of S_k / k^2
 //      compared in exact 128-bit integers, tie rule applied; F reported as one fp64 division
 //   5. stable sort of the (o, id)-ordered ids by batch number -> each batch in nondecreasing o
-#include "kvsched_internal.h"
+#include "phase1_util.h"
 
 namespace {
 
-constexpr int TPB = 1024;
-constexpr int NWAVES = TPB / 64;
-
 struct Lds {
-    int hist[256];
-    int wcount[NWAVES][256];  // per tile: lanes of wave w holding digit d
-    int woff[NWAVES][256];    // per tile: output offset of wave w's first lane with digit d
+    RadixLds radix;
+    int hist[2];
     long long scan_a[NWAVES];
     long long scan_b[NWAVES];
     long long carry_a, carry_b;
@@ -31,66 +27,6 @@ struct Lds {
     int best_k;
     int flag;
 };
-
-__device__ __forceinline__ unsigned long long lanemask_lt()
-{
-    return (1ull << (threadIdx.x & 63)) - 1ull;
-}
-
-// One stable counting pass on an 8-bit digit of key(id).  in/out: [n] ids.
-template <class KeyFn>
-__device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key, Lds &L)
-{
-    const int tid = threadIdx.x, wave = tid >> 6;
-    if (tid < 256) L.hist[tid] = 0;
-    for (int i = tid; i < NWAVES * 256; i += TPB) (&L.wcount[0][0])[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += TPB) atomicAdd(&L.hist[(key(in[i]) >> shift) & 255], 1);
-    __syncthreads();
-    if (tid == 0) {  // exclusive scan of the 256 digit counts -> running output base per digit
-        int run = 0;
-        for (int d = 0; d < 256; ++d) {
-            const int c = L.hist[d];
-            L.hist[d] = run;
-            run += c;
-        }
-    }
-    __syncthreads();
-    for (int tile = 0; tile < n; tile += TPB) {
-        const int i = tile + tid;
-        const bool valid = i < n;
-        const int id = valid ? in[i] : 0;
-        const int d = valid ? ((key(id) >> shift) & 255) : 256;
-        // lanes of this wave holding the same digit
-        unsigned long long peers = ~0ull;
-#pragma unroll
-        for (int b = 0; b < 9; ++b) {
-            const unsigned long long bal = __builtin_amdgcn_ballot_w64((d >> b) & 1);
-            peers &= ((d >> b) & 1) ? bal : ~bal;
-        }
-        const int rank = __popcll(peers & lanemask_lt());
-        if (valid && rank == 0) L.wcount[wave][d] = __popcll(peers);
-        __syncthreads();
-        if (tid < 256) {  // per digit: offsets of the waves in order, advance the running base
-            int off = L.hist[tid];
-            for (int w = 0; w < NWAVES; ++w) {
-                const int c = L.wcount[w][tid];
-                L.wcount[w][tid] = 0;  // ready for the next tile
-                L.woff[w][tid] = off;
-                off += c;
-            }
-            L.hist[tid] = off;
-        }
-        __syncthreads();
-        if (valid) out[L.woff[wave][d] + rank] = id;
-        __syncthreads();
-    }
-}
-
-__device__ __forceinline__ int bits_of(long long v)
-{
-    return v <= 0 ? 1 : 64 - __clzll(v);
-}
 
 // sign of Sa/ka^2 - Sb/kb^2 in exact integers (Sa, Sb < 2^63; ka, kb < 2^31)
 __device__ __forceinline__ int cmp_F(long long Sa, int ka, long long Sb, int kb)
@@ -158,13 +94,13 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
     auto key_o = [o](int id) { return o[id]; };
     auto key_w = [s, o](int id) { return s[id] + o[id]; };
     for (int shift = 0; shift < bits_of(omax); shift += 8) {
-        radix_pass(cur, alt, n, shift, key_o, L);
+        radix_pass(cur, alt, n, shift, key_o, L.radix);
         int *t = cur; cur = alt; alt = t;
     }
     for (int i = tid; i < n; i += TPB) by_o[i] = cur[i];
     __syncthreads();
     for (int shift = 0; shift < bits_of(wmax); shift += 8) {
-        radix_pass(cur, alt, n, shift, key_w, L);
+        radix_pass(cur, alt, n, shift, key_w, L.radix);
         int *t = cur; cur = alt; alt = t;
     }
     const int *sorted = cur;  // (s+o, o, id) ascending
@@ -258,7 +194,7 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
     auto key_b = [batch_of](int id) { return batch_of[id]; };
     bool first = true;
     for (int shift = 0; shift < bits_of(nb - 1); shift += 8) {
-        radix_pass(src, dst, n, shift, key_b, L);
+        radix_pass(src, dst, n, shift, key_b, L.radix);
         if (first) { src = dst; dst = other; first = false; }
         else { int *t = src; src = dst; dst = t; }
     }

@@ -47,6 +47,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_argmin.argtypes = [vp, vp, i32, vp, vp]
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, vp, vp, vp, vp, vp]
+    lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
     lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     return lib
@@ -151,6 +152,22 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_sortedF")
         return order, ends, F, nb
+
+    def local_swap(self, s, o, M):
+        """Phase 1 with Local Swap Search -> (order [n], batch_end [n], F [n], swaps [n], num_batches [1])."""
+        n = s.shape[0]
+        dev = s.device
+        order = torch.empty(n, dtype=torch.int32, device=dev)
+        ends = torch.zeros(n, dtype=torch.int32, device=dev)
+        F = torch.zeros(n, dtype=torch.float64, device=dev)
+        swaps = torch.zeros(n, dtype=torch.int32, device=dev)
+        nb = torch.zeros(1, dtype=torch.int32, device=dev)
+        rc = _lib.kvsched_local_swap(self._h, n, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
+                                     order.data_ptr(), ends.data_ptr(), F.data_ptr(), swaps.data_ptr(),
+                                     nb.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_local_swap")
+        return order, ends, F, swaps, nb
 
     def best_neighbor(self, base_order, moves, s, o, M, want_tel: bool = True):
         """-> (tel [K] int64 or None, result [3] int64 = {best move, its TEL, TEL of base})."""
