@@ -10,35 +10,54 @@
 //     r_out has an improving partner   <=>   pm[ub(out)] < o_out,
 // the pair the double scan meets first is the first such member, and its partner is the first
 // non-member with o < o_out (it lies before ub(out) because one such non-member does).
-// One step = one exclusive prefix-minimum scan, one binary search per member, two block-wide
-// minimum reductions; the whole construction runs in one workgroup, the working set in LDS once
-// at most LS_CAP requests remain.
+// One step = one exclusive prefix-minimum scan, one ub() per member, two block-wide reductions.
+//
+// The step is a chain of dependent wave operations and barriers, so the whole construction runs in
+// ONE small workgroup (LS_T threads = one wavefront per SIMD of a compute unit: with more waves the
+// instructions every wave repeats share the issue ports and the step gets slower), each thread
+// owning LS_E consecutive places of a tile and keeping its places of the first tile in registers.
+// Once at most LS_CAP requests remain the working set lives in LDS, and while the sizes stay below
+// LS_TABLE ub() is one read of a table rank[v] = number of remaining requests with w <= v (the
+// arrangement is fixed within a batch, so the table is built once per batch); otherwise ub() is a
+// binary search.
 #include "phase1_util.h"
 
 namespace {
 
-constexpr int LS_CAP = 8192;             // remaining requests held in LDS
+constexpr int LS_T = 256;                // threads of the workgroup
+constexpr int LS_E = 4;                  // consecutive places per thread in a tile
+constexpr int LS_TILE = LS_T * LS_E;
+constexpr int LS_NW = LS_T / 64;
+constexpr int LS_CAP = 10240;            // remaining requests held in LDS (3 x 40 KB + the 32 KB table)
+constexpr int LS_TABLE = 16384;          // sizes covered by the rank table
 constexpr int LS_INF = 0x7fffffff;
 constexpr unsigned LS_MEMBER = 0x80000000u;  // membership flag kept in the sign bit of the o entry
 constexpr int LS_NONE = 0x7fffffff;
+constexpr unsigned long long LS_NO_KEY = ~0ull;
+
+typedef __attribute__((address_space(3))) int lds_int;
+typedef __attribute__((address_space(3))) const unsigned short lds_rank;
 
 struct SwapLds {
-    int wave_min[NWAVES];
-    int first_out[2];  // alternating slots: least place of a member that has a partner
-    int first_in[2];   //                    least place of its partner
-    unsigned long long acc_mem, acc_S;
-    long long scan_w[NWAVES];
-    int scan_c[NWAVES];
+    int wave_min[LS_NW];
+    unsigned long long first_out[2];  // alternating slots: (place << 32 | o) of the first member that has a partner
+    unsigned first_key[2];            // the same as place << 15 | o (small case)
+    int first_in[2][4];               //                    {place, o, w} of that partner
+    long long scan_w[LS_NW];
+    long long scan_o[LS_NW];
+    int scan_c[LS_NW];
+    long long fill_mem, fill_S;
 };
 
 struct WorkLds {
     int w[LS_CAP];
     int o[LS_CAP];
-    int pm[LS_CAP + 1];
+    int pm[LS_CAP + LS_E];  // LS_CAP is a multiple of the tile: whole-tile stores of a tile that holds place m - 1 < LS_CAP stay inside
+    unsigned short rank[LS_TABLE];
 };
 
 union PhaseLds {
-    RadixLds radix;
+    RadixLds<LS_T> radix;
     WorkLds work;
 };
 
@@ -48,33 +67,31 @@ __device__ __forceinline__ int dpp_else(int keep, int v)
     return __builtin_amdgcn_update_dpp(keep, v, CTRL, ROW_MASK, 0xf, false);
 }
 
-// inclusive prefix minimum over the 64 lanes (all lanes active)
-__device__ __forceinline__ int wave_scan_min(int v)
+// inclusive prefix minimum (MAX: maximum of non-negative values) over the 64 lanes, all active
+template <bool MAX>
+__device__ __forceinline__ int wave_scan(int v)
 {
-    v = min(v, dpp_else<0x111, 0xf>(LS_INF, v));  // row_shr:1
-    v = min(v, dpp_else<0x112, 0xf>(LS_INF, v));  // row_shr:2
-    v = min(v, dpp_else<0x114, 0xf>(LS_INF, v));  // row_shr:4
-    v = min(v, dpp_else<0x118, 0xf>(LS_INF, v));  // row_shr:8
-    v = min(v, dpp_else<0x142, 0xa>(LS_INF, v));  // row_bcast15 into rows 1 and 3
-    v = min(v, dpp_else<0x143, 0xc>(LS_INF, v));  // row_bcast31 into rows 2 and 3
+    constexpr int ID = MAX ? 0 : LS_INF;
+    auto op = [](int x, int y) { return MAX ? max(x, y) : min(x, y); };
+    v = op(v, dpp_else<0x111, 0xf>(ID, v));  // row_shr:1
+    v = op(v, dpp_else<0x112, 0xf>(ID, v));  // row_shr:2
+    v = op(v, dpp_else<0x114, 0xf>(ID, v));  // row_shr:4
+    v = op(v, dpp_else<0x118, 0xf>(ID, v));  // row_shr:8
+    v = op(v, dpp_else<0x142, 0xa>(ID, v));  // row_bcast15 into rows 1 and 3
+    v = op(v, dpp_else<0x143, 0xc>(ID, v));  // row_bcast31 into rows 2 and 3
     return v;
 }
 
-__device__ __forceinline__ int wave_min_i32(int v)
+// the value of the lane below (the identity in lane 0)
+template <bool MAX>
+__device__ __forceinline__ int wave_prev(int v)
 {
-    v = min(v, dpp_else<0xB1, 0xf>(v, v));   // quad_perm [1,0,3,2]
-    v = min(v, dpp_else<0x4E, 0xf>(v, v));   // quad_perm [2,3,0,1]
-    v = min(v, dpp_else<0x141, 0xf>(v, v));  // row_half_mirror
-    v = min(v, dpp_else<0x140, 0xf>(v, v));  // row_mirror
-    const int a = __builtin_amdgcn_readlane(v, 0);
-    const int b = __builtin_amdgcn_readlane(v, 16);
-    const int c = __builtin_amdgcn_readlane(v, 32);
-    const int d = __builtin_amdgcn_readlane(v, 48);
-    return min(min(a, b), min(c, d));
+    return dpp_else<0x138, 0xf>(MAX ? 0 : LS_INF, v);  // wave_shr:1
 }
 
 // first place in [lo, hi) whose w exceeds lim (hi if none); W ascending
-__device__ __forceinline__ int upper_bound_w(const int *W, int lo, int hi, int lim)
+template <class IntPtr>
+__device__ __forceinline__ int upper_bound_w(IntPtr W, int lo, int hi, int lim)
 {
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
@@ -90,140 +107,403 @@ __device__ __forceinline__ int upper_bound_w(const int *W, int lo, int hi, int l
 __device__ int greedy_fill(const int *W, int *O, int m, int M, long long &mem, long long &S, SwapLds &L)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) { L.acc_mem = 0; L.acc_S = 0; }
-    __syncthreads();
-    long long carry = 0;
+    if (tid == 0) { L.fill_mem = 0; L.fill_S = 0; }
+    long long carry_w = 0, carry_o = 0;
     int K = 0;
-    for (int tile = 0; tile < m; tile += TPB) {
+    for (int tile = 0; tile < m; tile += LS_T) {
         const int i = tile + tid;
-        long long w = i < m ? (long long)W[i] : 0;
-        const long long own = w;
+        const int ov = i < m ? O[i] : 0;
+        long long w = i < m ? (long long)W[i] : 0, q = ov;
         for (int d = 1; d < 64; d <<= 1) {
-            const long long u = __shfl_up(w, d);
-            if (lane >= d) w += u;
+            const long long uw = __shfl_up(w, d), uq = __shfl_up(q, d);
+            if (lane >= d) { w += uw; q += uq; }
         }
-        if (lane == 63) L.scan_w[wave] = w;
+        if (lane == 63) { L.scan_w[wave] = w; L.scan_o[wave] = q; }
         __syncthreads();
-        long long off = carry, total = carry;
-        for (int v = 0; v < NWAVES; ++v) {
-            const long long x = L.scan_w[v];
-            if (v < wave) off += x;
-            total += x;
+        long long off_w = carry_w, off_o = carry_o, tot_w = carry_w, tot_o = carry_o;
+        for (int v = 0; v < LS_NW; ++v) {
+            const long long xw = L.scan_w[v], xo = L.scan_o[v];
+            if (v < wave) { off_w += xw; off_o += xo; }
+            tot_w += xw;
+            tot_o += xo;
         }
-        const bool fit = i < m && w + off <= (long long)M;
+        const long long pre = w + off_w;
+        const bool fit = i < m && pre <= (long long)M;
         if (fit) {
-            atomicAdd(&L.acc_mem, (unsigned long long)own);
-            atomicAdd(&L.acc_S, (unsigned long long)O[i]);
-            O[i] = (int)((unsigned)O[i] | LS_MEMBER);
+            O[i] = (int)((unsigned)ov | LS_MEMBER);
+            if (i + 1 >= m || pre + (long long)W[i + 1] > (long long)M) {  // the last one that fits
+                L.fill_mem = pre;
+                L.fill_S = q + off_o;
+            }
         }
         const int c = __syncthreads_count(fit);
         K += c;
-        carry = total;
-        if (c < TPB) break;  // uniform: c is the same in every thread
+        carry_w = tot_w;
+        carry_o = tot_o;
+        if (c < LS_T) break;  // uniform: c is the same in every thread
     }
     __syncthreads();
-    mem = (long long)L.acc_mem;
-    S = (long long)L.acc_S;
+    mem = L.fill_mem;
+    S = L.fill_S;
     return K;
 }
 
-// The exchanges of one batch.  W, O, PM: m sorted entries (LDS or global memory), members flagged
-// in O's sign bit, initially the first K.  Returns the number of exchanges; hi_out = a bound such
-// that every member lies before it.
-__device__ int swap_loop(const int *W, int *O, int *PM, int m, int K, int M, long long &mem, long long &S,
-                         int &hi_out, SwapLds &L)
+// rank[v] = number of the m sorted entries with w <= v, for v = 0..W[m-1] < LS_TABLE:
+// boundaries of the runs of equal w are scattered into a zeroed table, then a running maximum
+// fills the gaps (each thread owns a contiguous chunk, chunk totals scanned across the block).
+__device__ void build_rank(const int *W, int m, unsigned short *rank, SwapLds &L)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 2) { L.first_out[tid] = LS_NONE; L.first_in[tid] = LS_NONE; }
+    const int w_last = W[m - 1];
+    for (int v = tid; v <= w_last; v += LS_T) rank[v] = 0;
     __syncthreads();
-    int hi = K, swaps = 0;
+    for (int j = tid; j < m; j += LS_T) {
+        const int wj = W[j];
+        if (j + 1 == m || W[j + 1] != wj) rank[wj] = (unsigned short)(j + 1);
+    }
+    __syncthreads();
+    const int chunk = (w_last + LS_T) / LS_T;
+    const int lo = tid * chunk, hi = min(lo + chunk, w_last + 1);
+    int run = 0;
+    for (int v = lo; v < hi; ++v) run = max(run, (int)rank[v]);
+    const int incl = wave_scan<true>(run);
+    if (lane == 63) L.wave_min[wave] = incl;
+    int before = wave_prev<true>(incl);
+    __syncthreads();
+    for (int u = 0; u < LS_NW; ++u)
+        if (u < wave) before = max(before, L.wave_min[u]);
+    for (int v = lo; v < hi; ++v) {
+        before = max(before, (int)rank[v]);
+        rank[v] = (unsigned short)before;
+    }
+    __syncthreads();
+}
+
+// One tile of the prefix-minimum scan: ov[e] = entries of places base + tid*LS_E + e (members and
+// places past the end count as "none"); pm[e] receives the least o among non-members before each
+// place (carry = the same over all earlier tiles, updated) and is stored to PM[base + ...] for
+// places <= m.  Two barriers; PM is complete after the second.
+template <class IntPtr>
+__device__ __forceinline__ void scan_tile(const int (&ov)[LS_E], int (&pm)[LS_E], int &carry, SwapLds &L, IntPtr PM,
+                                          int base, int m)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int run = LS_INF;
+#pragma unroll
+    for (int e = 0; e < LS_E; ++e) {
+        pm[e] = run;
+        if (ov[e] >= 0) run = min(run, ov[e]);
+    }
+    const int incl = wave_scan<false>(run);
+    if (lane == 63) L.wave_min[wave] = incl;
+    int before = wave_prev<false>(incl);
+    __syncthreads();
+    int total = carry;
+    before = min(before, carry);
+#pragma unroll
+    for (int u = 0; u < LS_NW; ++u) {
+        const int x = L.wave_min[u];
+        if (u < wave) before = min(before, x);
+        total = min(total, x);
+    }
+#pragma unroll
+    for (int e = 0; e < LS_E; ++e) {
+        pm[e] = min(pm[e], before);
+        const int i = base + (int)threadIdx.x * LS_E + e;
+        if (i <= m) PM[i] = pm[e];
+    }
+    carry = total;
+    __syncthreads();
+}
+
+// Running state of one batch's exchanges, the same in every thread.
+struct SwapState {
+    long long mem, S;  // sum of s+o and of o over the members
+    int hi;            // every member lies before place hi
+    int w_hi;          // no member is larger than this
+    int swaps;
+};
+
+// The exchanges of one batch, any size.  W, O, PM: m sorted entries (LDS or global memory; PM
+// holds m + 1), members flagged in O's sign bit.  rank: table of build_rank or null.
+template <class IntPtr, class RankPtr>
+__device__ __forceinline__ void swap_loop(IntPtr W, IntPtr O, IntPtr PM, RankPtr rank, int m, int M, SwapState &st,
+                                          SwapLds &L)
+{
+    long long mem = st.mem, S = st.S;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w_last = W[m - 1];
+    // number of places whose w is at most lim; needs W[from - 1] <= lim and the answer <= to
+    auto ub = [&](int from, int to, int lim) {
+        if (rank) return (int)rank[min(lim, w_last)];  // rank[w_last] = m
+        return upper_bound_w(W, from, to, lim);
+    };
+    // this thread's places of the first tile, in registers (LS_INF = a non-member that never helps)
+    int own_o[LS_E], own_w[LS_E], own_pm[LS_E];
+#pragma unroll
+    for (int e = 0; e < LS_E; ++e) {
+        const int i = tid * LS_E + e;
+        own_o[e] = i < m ? O[i] : LS_INF;
+        own_w[e] = i < m ? W[i] : 0;
+    }
+    if (tid < 2) { L.first_out[tid] = LS_NO_KEY; L.first_in[tid][0] = LS_NONE; }
+    __syncthreads();
+    int hi = st.hi, swaps = st.swaps, w_hi = st.w_hi;
     for (int it = 0;; ++it) {
         const int slot = it & 1;
         const int slack = (int)((long long)M - mem);
-        // no member is larger than W[hi-1]; places from U on fit against no member
-        const int U = upper_bound_w(W, hi, m, W[hi - 1] + slack);
+        const int U = ub(hi, m, w_hi + slack);  // places from U on fit against no member
 
-        // ---- pm[j] = least o among non-members before place j, j = 0..U
+        // ---- pm[j] = least o among non-members before place j, for j = 0..U (entries past U may
+        //      be written too; nothing reads them)
         int carry = LS_INF;
-        for (int tile = 0; tile <= U; tile += TPB) {
-            const int i = tile + tid;
-            int v = LS_INF;
-            if (i < U) {
-                const int ov = O[i];
-                if (ov >= 0) v = ov;
+        scan_tile(own_o, own_pm, carry, L, PM, 0, m);
+        for (int tile = LS_TILE; tile <= U; tile += LS_TILE) {
+            int ov[LS_E], pm[LS_E];
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) {
+                const int i = tile + tid * LS_E + e;
+                ov[e] = i < m ? O[i] : LS_INF;
             }
-            const int incl = wave_scan_min(v);
-            if (lane == 63) L.wave_min[wave] = incl;
-            int excl = __shfl_up(incl, 1);
-            if (lane == 0) excl = LS_INF;
-            __syncthreads();
-            int off = carry, total = carry;
-            for (int u = 0; u < NWAVES; ++u) {
-                const int x = L.wave_min[u];
-                if (u < wave) off = min(off, x);
-                total = min(total, x);
-            }
-            if (i <= U) PM[i] = min(off, excl);
-            carry = total;
-            __syncthreads();
+            scan_tile(ov, pm, carry, L, PM, tile, m);
         }
 
-        // ---- first member with an improving partner that fits
-        int cand = LS_NONE;
-        for (int tile = 0; tile < hi; tile += TPB) {
-            const int a = tile + tid;
-            if (a < hi) {
-                const int ov = O[a];
-                if (ov < 0) {
-                    const int ub = upper_bound_w(W, a + 1, U, W[a] + slack);
-                    if (PM[ub] < (int)((unsigned)ov & ~LS_MEMBER)) cand = min(cand, a);
+        // ---- first member with an improving partner that fits: per wave the lowest lane of the
+        //      first tile that has one; waves combined by a minimum in LDS; the key carries its o
+        unsigned long long cand = LS_NO_KEY;
+        for (int tile = 0; tile < hi; tile += LS_TILE) {
+            unsigned long long mine = LS_NO_KEY;
+            int ov[LS_E], wv[LS_E];
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) {
+                const int a = tile + tid * LS_E + e;
+                if (tile == 0) { ov[e] = own_o[e]; wv[e] = own_w[e]; }
+                else { ov[e] = a < hi ? O[a] : LS_INF; wv[e] = a < hi ? W[a] : 0; }
+            }
+            if (rank) {  // loads issued for all places at once; non-members read rank[0] = 0, pm[0] = none
+                int j[LS_E], p[LS_E];
+#pragma unroll
+                for (int e = 0; e < LS_E; ++e) j[e] = rank[ov[e] < 0 ? min(wv[e] + slack, w_last) : 0];
+#pragma unroll
+                for (int e = 0; e < LS_E; ++e) p[e] = PM[j[e]];
+#pragma unroll
+                for (int e = LS_E - 1; e >= 0; --e) {
+                    const int oo = (int)((unsigned)ov[e] & ~LS_MEMBER);
+                    if (ov[e] < 0 && p[e] < oo)
+                        mine = ((unsigned long long)(tile + tid * LS_E + e) << 32) | (unsigned)oo;
+                }
+            } else {
+#pragma unroll
+                for (int e = LS_E - 1; e >= 0; --e) {
+                    const int a = tile + tid * LS_E + e;
+                    if (ov[e] < 0) {  // a member
+                        const int oo = (int)((unsigned)ov[e] & ~LS_MEMBER);
+                        if (PM[upper_bound_w(W, a + 1, U, wv[e] + slack)] < oo)
+                            mine = ((unsigned long long)a << 32) | (unsigned)oo;
+                    }
+                }
+            }
+            const unsigned long long bal = __builtin_amdgcn_ballot_w64(mine != LS_NO_KEY);
+            if (bal != 0 && cand == LS_NO_KEY) {
+                const int l = (int)__builtin_ctzll(bal);
+                const unsigned lo32 = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)mine, l);
+                const unsigned hi32 = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(mine >> 32), l);
+                cand = ((unsigned long long)hi32 << 32) | lo32;
+            }
+        }
+        if (lane == 0 && cand != LS_NO_KEY) atomicMin(&L.first_out[slot], cand);
+        __syncthreads();
+        const unsigned long long key = L.first_out[slot];
+        if (key == LS_NO_KEY) break;  // uniform
+        const int a_star = (int)(key >> 32), o_a = (int)(unsigned)key;
+        const int w_a = W[a_star];
+
+        // ---- its partner: the first non-member with smaller o, i.e. the one place where the
+        //      prefix minimum is still >= o_out and the entry itself is below it
+        {
+            int fb = LS_NONE, fo = 0, fw = 0;
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) {
+                const bool is = own_o[e] >= 0 && own_o[e] < o_a && own_pm[e] >= o_a;
+                fb = is ? tid * LS_E + e : fb;
+                fo = is ? own_o[e] : fo;
+                fw = is ? own_w[e] : fw;
+            }
+            if (fb != LS_NONE) {
+                L.first_in[slot][0] = fb;
+                L.first_in[slot][1] = fo;
+                L.first_in[slot][2] = fw;
+            }
+        }
+        for (int tile = LS_TILE; tile < U; tile += LS_TILE) {
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) {
+                const int b = tile + tid * LS_E + e;
+                if (b < U) {
+                    const int ov = O[b];
+                    if (ov >= 0 && ov < o_a && PM[b] >= o_a) {
+                        L.first_in[slot][0] = b;
+                        L.first_in[slot][1] = ov;
+                        L.first_in[slot][2] = W[b];
+                    }
                 }
             }
         }
-        cand = wave_min_i32(cand);
-        if (lane == 0 && cand != LS_NONE) atomicMin(&L.first_out[slot], cand);
         __syncthreads();
-        const int a_star = L.first_out[slot];
-        if (a_star == LS_NONE) break;  // uniform
-
-        // ---- its first partner: the first non-member with smaller o
-        const int o_a = (int)((unsigned)O[a_star] & ~LS_MEMBER);
-        int cb = LS_NONE;
-        for (int tile = 0; tile < U; tile += TPB) {
-            const int b = tile + tid;
-            if (b < U) {
-                const int ov = O[b];
-                if (ov >= 0 && ov < o_a) cb = min(cb, b);
-            }
-        }
-        cb = wave_min_i32(cb);
-        if (lane == 0 && cb != LS_NONE) atomicMin(&L.first_in[slot], cb);
-        __syncthreads();
-        const int b_star = L.first_in[slot];
+        const int b_star = L.first_in[slot][0], o_b = L.first_in[slot][1], w_b = L.first_in[slot][2];
         if (b_star == LS_NONE) break;  // cannot happen: pm said a partner exists; never spin
 
         // ---- exchange; every thread keeps the running sums, the owners rewrite the flags
-        const int o_b = (int)((unsigned)O[b_star] & ~LS_MEMBER);
-        mem += (long long)W[b_star] - (long long)W[a_star];
+        mem += (long long)w_b - (long long)w_a;
         S += (long long)o_b - (long long)o_a;
-        hi = max(hi, b_star + 1);
+        if (b_star >= hi) { hi = b_star + 1; w_hi = w_b; }
         ++swaps;
-        if ((a_star & (TPB - 1)) == tid) O[a_star] = o_a;
-        if ((b_star & (TPB - 1)) == tid) O[b_star] = (int)((unsigned)o_b | LS_MEMBER);
+        const int in_flag = (int)((unsigned)o_b | LS_MEMBER);
+        if (((a_star & (LS_TILE - 1)) / LS_E) == tid) O[a_star] = o_a;
+        if (((b_star & (LS_TILE - 1)) / LS_E) == tid) O[b_star] = in_flag;
+#pragma unroll
+        for (int e = 0; e < LS_E; ++e) {
+            if (tid * LS_E + e == a_star) own_o[e] = o_a;
+            if (tid * LS_E + e == b_star) own_o[e] = in_flag;
+        }
         if (tid == 0) {  // the other slot was last read two barriers ago; ready it for the next step
-            L.first_out[slot ^ 1] = LS_NONE;
-            L.first_in[slot ^ 1] = LS_NONE;
+            L.first_out[slot ^ 1] = LS_NO_KEY;
+            L.first_in[slot ^ 1][0] = LS_NONE;
         }
     }
-    hi_out = hi;
-    return swaps;
+    st.mem = mem;
+    st.S = S;
+    st.hi = hi;
+    st.w_hi = w_hi;
+    st.swaps = swaps;
 }
 
-__global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
-                                                         int32_t *order_out, int32_t *batch_end_out, double *F_out,
-                                                         int32_t *swaps_out, int32_t *num_batches_out, int *gw, int *go,
-                                                         int *gid, int *alt_o, int *buf0, int *buf1, int *by_o,
-                                                         int *batch_of, int32_t *words)
+// The same steps for the common small case, straight-line: working set in LDS, rank table present,
+// and every place that matters (U, see above) inside the first tile, so each thread works on the
+// LS_E places it keeps in registers and nothing is conditional but the two block-wide decisions.
+// Runs until no exchange is left (returns true) or the case no longer applies (returns false with
+// st and the flags in O consistent, for swap_loop to continue).
+__device__ __forceinline__ bool swap_steps_small(lds_int *W, lds_int *O, lds_int *PM, lds_rank *rank, int m, int M,
+                                                 SwapState &st, SwapLds &L)
+{
+    constexpr unsigned NO_KEY = 0xffffffffu;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int w_last = W[m - 1];
+    int own_o[LS_E], own_w[LS_E];
+#pragma unroll
+    for (int e = 0; e < LS_E; ++e) {
+        const int i = tid * LS_E + e;
+        own_o[e] = i < m ? O[i] : LS_INF;
+        own_w[e] = i < m ? W[i] : 0;
+    }
+    if (tid < 2) { L.first_key[tid] = NO_KEY; L.first_in[tid][0] = LS_NONE; }
+    __syncthreads();
+    int slack = (int)((long long)M - st.mem), hi = st.hi, w_hi = st.w_hi, swaps = st.swaps;
+    long long S = st.S;
+    bool done = false;
+    for (int it = 0;; ++it) {
+        const int slot = it & 1;
+        const int U = rank[min(w_hi + slack, w_last)];
+        if (U >= LS_TILE) break;  // uniform
+
+        // ---- prefix minimum of o over the non-members (a member reads as "none": its sign bit
+        //      makes it the largest unsigned value)
+        int pm[LS_E];
+        int run = LS_INF;
+#pragma unroll
+        for (int e = 0; e < LS_E; ++e) {
+            pm[e] = run;
+            run = (int)min((unsigned)run, (unsigned)own_o[e]);
+        }
+        const int incl = wave_scan<false>(run);
+        if (lane == 63) L.wave_min[wave] = incl;
+        int before = wave_prev<false>(incl);
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < LS_NW; ++u) before = u < wave ? min(before, L.wave_min[u]) : before;
+#pragma unroll
+        for (int e = 0; e < LS_E; ++e) {
+            pm[e] = min(pm[e], before);
+            PM[tid * LS_E + e] = pm[e];  // the table has room for the whole tile
+        }
+        __syncthreads();
+
+        // ---- first member with an improving partner that fits; key = place << 15 | o
+        unsigned key = NO_KEY;
+        {
+            int j[LS_E], p[LS_E];
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) j[e] = rank[own_o[e] < 0 ? min(own_w[e] + slack, w_last) : 0];
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) p[e] = PM[j[e]];
+#pragma unroll
+            for (int e = LS_E - 1; e >= 0; --e) {
+                const int oo = (int)((unsigned)own_o[e] & ~LS_MEMBER);
+                key = (own_o[e] < 0 && p[e] < oo) ? (unsigned)(((tid * LS_E + e) << 15) | oo) : key;
+            }
+        }
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(key != NO_KEY);
+        if (bal != 0) {
+            const unsigned k = (unsigned)__builtin_amdgcn_readlane((int)key, (int)__builtin_ctzll(bal));
+            if (lane == 0) atomicMin(&L.first_key[slot], k);
+        }
+        __syncthreads();
+        const unsigned best = L.first_key[slot];
+        if (best == NO_KEY) { done = true; break; }  // uniform
+        const int a_star = (int)(best >> 15), o_a = (int)(best & 0x7fffu);
+        const int w_a = W[a_star];
+
+        // ---- its partner: the one non-member below o_out whose prefix minimum is not
+        {
+            int fb = LS_NONE, fo = 0, fw = 0;
+#pragma unroll
+            for (int e = 0; e < LS_E; ++e) {
+                const bool is = (unsigned)own_o[e] < (unsigned)o_a && pm[e] >= o_a;
+                fb = is ? tid * LS_E + e : fb;
+                fo = is ? own_o[e] : fo;
+                fw = is ? own_w[e] : fw;
+            }
+            if (fb != LS_NONE) {
+                L.first_in[slot][0] = fb;
+                L.first_in[slot][1] = fo;
+                L.first_in[slot][2] = fw;
+            }
+        }
+        __syncthreads();
+        const int b_star = L.first_in[slot][0], o_b = L.first_in[slot][1], w_b = L.first_in[slot][2];
+        if (b_star == LS_NONE) { done = true; break; }  // cannot happen; never spin
+
+        // ---- exchange
+        slack -= w_b - w_a;
+        S += (long long)(o_b - o_a);
+        if (b_star >= hi) { hi = b_star + 1; w_hi = w_b; }
+        ++swaps;
+        const int in_flag = (int)((unsigned)o_b | LS_MEMBER);
+#pragma unroll
+        for (int e = 0; e < LS_E; ++e) {
+            own_o[e] = (tid * LS_E + e == a_star) ? o_a : own_o[e];
+            own_o[e] = (tid * LS_E + e == b_star) ? in_flag : own_o[e];
+        }
+        if ((a_star / LS_E) == tid) O[a_star] = o_a;
+        if ((b_star / LS_E) == tid) O[b_star] = in_flag;
+        if (tid == 0) {  // the other slot was last read two barriers ago; ready it for the next step
+            L.first_key[slot ^ 1] = NO_KEY;
+            L.first_in[slot ^ 1][0] = LS_NONE;
+        }
+    }
+    st.mem = (long long)M - slack;
+    st.S = S;
+    st.hi = hi;
+    st.w_hi = w_hi;
+    st.swaps = swaps;
+    return done;
+}
+
+__global__ __launch_bounds__(LS_T) void local_swap_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
+                                                          int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                                                          int32_t *swaps_out, int32_t *num_batches_out, int *gw, int *go,
+                                                          int *gid, int *alt_o, int *buf0, int *buf1, int *by_o,
+                                                          int *batch_of, int32_t *words)
 {
     __shared__ PhaseLds P;
     __shared__ SwapLds L;
@@ -232,7 +512,7 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
 
     // ---- well-formedness and key widths
     int omax = 0, wmax = 0, bad = 0;
-    for (int i = tid; i < n; i += TPB) {
+    for (int i = tid; i < n; i += LS_T) {
         const int sv = s[i], ov = o[i];
         if (sv < 1 || ov < 1 || (long long)sv + ov > (long long)M) bad = 1;
         omax = max(omax, ov);
@@ -255,7 +535,7 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
     }
 
     // ---- key sorts: ids by (o, id), kept for the emission order, then on by s+o
-    for (int i = tid; i < n; i += TPB) buf0[i] = i;
+    for (int i = tid; i < n; i += LS_T) buf0[i] = i;
     __syncthreads();
     int *cur = buf0, *alt = buf1;
     auto key_o = [o](int id) { return o[id]; };
@@ -264,13 +544,13 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
         radix_pass(cur, alt, n, shift, key_o, P.radix);
         int *t = cur; cur = alt; alt = t;
     }
-    for (int i = tid; i < n; i += TPB) by_o[i] = cur[i];
+    for (int i = tid; i < n; i += LS_T) by_o[i] = cur[i];
     __syncthreads();
     for (int shift = 0; shift < bits_of(wmax); shift += 8) {
         radix_pass(cur, alt, n, shift, key_w, P.radix);
         int *t = cur; cur = alt; alt = t;
     }
-    for (int i = tid; i < n; i += TPB) {
+    for (int i = tid; i < n; i += LS_T) {
         const int id = cur[i];
         gid[i] = id;
         go[i] = o[id];
@@ -285,30 +565,45 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
     while (a < n) {
         const int m = n - a;
         const bool in_lds = m <= LS_CAP;
-        int *W, *O, *PM;
+        const int *W = gw + a;
+        int *O = go + a;
         if (in_lds) {
-            for (int i = tid; i < m; i += TPB) {
+            for (int i = tid; i < m; i += LS_T) {
                 P.work.w[i] = gw[a + i];
                 P.work.o[i] = go[a + i];
             }
             __syncthreads();
+            W = P.work.w;
+            O = P.work.o;
         }
         long long mem = 0, S = 0;
-        int K, hi = 0, swaps = 0;
-        if (in_lds) {
-            K = greedy_fill(P.work.w, P.work.o, m, M, mem, S, L);
-            if (K >= 1) swaps = swap_loop(P.work.w, P.work.o, P.work.pm, m, K, M, mem, S, hi, L);
-            W = P.work.w; O = P.work.o; PM = P.work.pm;
-        } else {
-            K = greedy_fill(gw + a, go + a, m, M, mem, S, L);
-            if (K >= 1) swaps = swap_loop(gw + a, go + a, alt_o, m, K, M, mem, S, hi, L);
-            W = gw + a; O = go + a; PM = alt_o;
-        }
-        (void)PM;
+        int hi = 0, swaps = 0;
+        const int K = greedy_fill(W, O, m, M, mem, S, L);
         if (K < 1) {  // cannot happen for well-formed input; never spin
             if (tid == 0) atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
             break;
         }
+        SwapState st;
+        st.mem = mem;
+        st.S = S;
+        st.hi = K;
+        st.w_hi = W[K - 1];
+        st.swaps = 0;
+        if (in_lds) {  // the same loop, compiled for LDS addresses
+            lds_rank *rank = nullptr;
+            bool done = false;
+            if (W[m - 1] < LS_TABLE) {
+                build_rank(W, m, P.work.rank, L);
+                rank = (lds_rank *)P.work.rank;
+                done = swap_steps_small((lds_int *)P.work.w, (lds_int *)P.work.o, (lds_int *)P.work.pm, rank, m, M, st, L);
+            }
+            if (!done) swap_loop((lds_int *)P.work.w, (lds_int *)P.work.o, (lds_int *)P.work.pm, rank, m, M, st, L);
+        } else {
+            swap_loop(gw + a, go + a, alt_o, (const unsigned short *)nullptr, m, M, st, L);
+        }
+        S = st.S;
+        hi = st.hi;
+        swaps = st.swaps;
         __syncthreads();
         if (tid == 0) {
             batch_end_out[nb] = a + K;
@@ -318,7 +613,7 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
         // members get the batch number; non-members of [0, hi) close up behind the K removed
         // places (stable), through the spare arrays
         int carry = 0;
-        for (int tile = 0; tile < hi; tile += TPB) {
+        for (int tile = 0; tile < hi; tile += LS_T) {
             const int i = tile + tid;
             int keep = 0, ov = 0;
             if (i < hi) {
@@ -334,7 +629,7 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
             if (lane == 63) L.scan_c[wave] = c;
             __syncthreads();
             int off = carry, total = carry;
-            for (int u = 0; u < NWAVES; ++u) {
+            for (int u = 0; u < LS_NW; ++u) {
                 const int x = L.scan_c[u];
                 if (u < wave) off += x;
                 total += x;
@@ -350,7 +645,7 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
         }
         __threadfence_block();
         __syncthreads();
-        for (int i = K + tid; i < hi; i += TPB) {
+        for (int i = K + tid; i < hi; i += LS_T) {
             gw[a + i] = alt_w[i];
             go[a + i] = alt_o[i];
             gid[a + i] = alt_id[i];
@@ -373,7 +668,7 @@ __global__ __launch_bounds__(TPB) void local_swap_kernel(int32_t n, const int32_
         if (first) { src = dst; dst = other; first = false; }
         else { int *t = src; src = dst; dst = t; }
     }
-    for (int i = tid; i < n; i += TPB) order_out[i] = src[i];
+    for (int i = tid; i < n; i += LS_T) order_out[i] = src[i];
 }
 
 }  // namespace
@@ -397,7 +692,7 @@ int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t
     int *buf1 = buf0 + np;
     int *by_o = buf1 + np;
     int *batch_of = by_o + np;
-    hipLaunchKernelGGL(local_swap_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, order_out, batch_end_out, F_out,
+    hipLaunchKernelGGL(local_swap_kernel, dim3(1), dim3(LS_T), 0, st, n, s, o, M, order_out, batch_end_out, F_out,
                        swaps_out, num_batches_out, gw, go, gid, alt_o, buf0, buf1, by_o, batch_of, d_words);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

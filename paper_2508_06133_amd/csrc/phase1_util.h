@@ -1,18 +1,16 @@
-// Block-level building blocks of the Phase 1 kernels (one workgroup of 1024 threads builds the
-// whole order): a stable 8-bit LSD radix pass over request ids and small wavefront scans.
+// Block-level building blocks of the Phase 1 kernels (one workgroup of T threads builds the
+// whole order): a stable 8-bit LSD radix pass over request ids.
 #pragma once
 
 #include "kvsched_internal.h"
 
 namespace {
 
-constexpr int TPB = 1024;
-constexpr int NWAVES = TPB / 64;
-
+template <int T>
 struct RadixLds {
     int hist[256];
-    int wcount[NWAVES][256];  // per tile: lanes of wave w holding digit d
-    int woff[NWAVES][256];    // per tile: output offset of wave w's first lane with digit d
+    int wcount[T / 64][256];  // per tile: lanes of wave w holding digit d
+    int woff[T / 64][256];    // per tile: output offset of wave w's first lane with digit d
 };
 
 __device__ __forceinline__ unsigned long long lanemask_lt()
@@ -21,11 +19,12 @@ __device__ __forceinline__ unsigned long long lanemask_lt()
 }
 
 // One stable counting pass on an 8-bit digit of key(id).  in/out: [n] ids.
-template <class KeyFn>
-__device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key, RadixLds &L)
+template <int T, class KeyFn>
+__device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key, RadixLds<T> &L)
 {
+    constexpr int TPB = T, NWAVES = T / 64;
     const int tid = threadIdx.x, wave = tid >> 6;
-    if (tid < 256) L.hist[tid] = 0;
+    for (int i = tid; i < 256; i += TPB) L.hist[i] = 0;
     for (int i = tid; i < NWAVES * 256; i += TPB) (&L.wcount[0][0])[i] = 0;
     __syncthreads();
     for (int i = tid; i < n; i += TPB) atomicAdd(&L.hist[(key(in[i]) >> shift) & 255], 1);
@@ -54,15 +53,15 @@ __device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key,
         const int rank = __popcll(peers & lanemask_lt());
         if (valid && rank == 0) L.wcount[wave][d] = __popcll(peers);
         __syncthreads();
-        if (tid < 256) {  // per digit: offsets of the waves in order, advance the running base
-            int off = L.hist[tid];
+        for (int dd = tid; dd < 256; dd += TPB) {  // per digit: offsets of the waves in order, advance the running base
+            int off = L.hist[dd];
             for (int w = 0; w < NWAVES; ++w) {
-                const int c = L.wcount[w][tid];
-                L.wcount[w][tid] = 0;  // ready for the next tile
-                L.woff[w][tid] = off;
+                const int c = L.wcount[w][dd];
+                L.wcount[w][dd] = 0;  // ready for the next tile
+                L.woff[w][dd] = off;
                 off += c;
             }
-            L.hist[tid] = off;
+            L.hist[dd] = off;
         }
         __syncthreads();
         if (valid) out[L.woff[wave][d] + rank] = id;

@@ -15,8 +15,11 @@
 
 namespace {
 
+constexpr int TPB = 1024;
+constexpr int NWAVES = TPB / 64;
+
 struct Lds {
-    RadixLds radix;
+    RadixLds<TPB> radix;
     int hist[2];
     long long scan_a[NWAVES];
     long long scan_b[NWAVES];

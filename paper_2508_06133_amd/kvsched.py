@@ -81,11 +81,15 @@ class Context:
             raise KvschedError(rc, "kvsched_create")
 
     def close(self):
-        if getattr(self, "_h", None) and self._h.value:
+        if getattr(self, "_h", None) and self._h.value and _lib is not None:
             _lib.kvsched_destroy(self._h)
             self._h = ctypes.c_void_p()
 
-    __del__ = close
+    def __del__(self):  # at interpreter exit the module globals may already be gone
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def set_o_max(self, bound: int):
         rc = _lib.kvsched_set_o_max(self._h, int(bound))
