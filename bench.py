@@ -59,6 +59,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="candidate rows the CPU oracle is timed on")
+    ap.add_argument("--phase1", choices=("sorted_prefix", "local_swap"), default="sorted_prefix",
+                    help="Phase-1 solver run inside the step (the candidate set is always built around the sorted-prefix order)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the yardstick for FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
@@ -98,7 +100,10 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     def step():
-        ctx.sortedF(s, o, M)
+        if args.phase1 == "local_swap":
+            ctx.local_swap(s, o, M)
+        else:
+            ctx.sortedF(s, o, M)
         ctx.simulate(orders, s, o, M, tel_out=tel, completion_out=comp)
         ctx.argmin(tel, result_out=best)
 
@@ -159,7 +164,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "config 3: mixed chat+summarization, n=2000, M=131072, C=16384 "
                                "(Sorted-F order + 16127 1-swap neighbours + 256 random restarts)",
-                   "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item())},
+                   "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item()), "phase1": args.phase1},
         "request_rounds_per_s": C * sum_o * args.steps / wall,
         "gpu_ms_per_step": gpu_ms / args.steps,
         "timeline_kernel_ms": k_ms,
