@@ -5,8 +5,8 @@ smoke check and the benchmark's CPU-baseline leg may import this package; the GP
 library and its Python binding never do, and share no code with it.
 
   kvsched_oracle.c : Phase 2 of Algorithm 1 (literal and array-profile forms), sorted-prefix
-                     Phase 1 with the F-metric, Phase 1 with Local Swap Search, position moves,
-                     best neighbour.
+                     Phase 1 with the F-metric, Phase 1 with Local Swap Search, Phase 1 with exact
+                     batches (Algorithm 2), position moves, best neighbour.
   exact.py         : Algorithm 2 (exact DP), subset / permutation / start-time brute force,
                      lower bound -- tiny instances only.
   check.py         : direct-definition schedule checker (memory per round, greedy-earliest).
@@ -125,6 +125,21 @@ def local_swap(s, o, M, early_exit: bool = False):
                                      ctypes.c_int32(1 if early_exit else 0), _ptr(order, _i32p), _ptr(ends, _i32p),
                                      _ptr(F, _f64p), _ptr(swaps, _i32p), ctypes.byref(nb)))
     return order, ends[: nb.value].copy(), F[: nb.value].copy(), swaps[: nb.value].copy()
+
+
+def exact_phase1(s, o, M, feas_mode: int = 0, tie_rule: int = 0):
+    """Phase 1 with exact batches (Algorithm 2) -> (order[n], batch_end[nb], F[nb]).
+    feas_mode 0: sum of peaks <= M; 1: simultaneous-start memory profile <= M."""
+    s, o = _i32(s), _i32(o)
+    n = len(s)
+    order = np.zeros(n, dtype=np.int32)
+    ends = np.zeros(max(n, 1), dtype=np.int32)
+    F = np.zeros(max(n, 1), dtype=np.float64)
+    nb = ctypes.c_int32(0)
+    _check(_load().oracle_exact_phase1(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                       ctypes.c_int32(feas_mode), ctypes.c_int32(tie_rule), _ptr(order, _i32p),
+                                       _ptr(ends, _i32p), _ptr(F, _f64p), ctypes.byref(nb)))
+    return order, ends[: nb.value].copy(), F[: nb.value].copy()
 
 
 def apply_move(base, move):

@@ -50,13 +50,23 @@ def dp_best_batch(s, o, M):
     return best, ks, subs
 
 
-def brute_best_batch(s, o, M):
-    """min of F(X) = sum o / |X|^2 over non-empty subsets with sum (s+o) <= M."""
+def batch_profile_peak(s, o, ids) -> int:
+    """Largest memory of the set `ids` started together (Section 4's M(X, t) at the completion
+    times): max over j in X of sum over {i in X : o_i >= o_j} of (s_i + o_j)."""
+    return max(sum(int(s[i]) + int(o[j]) for i in ids if o[i] >= o[j]) for j in ids)
+
+
+def brute_best_batch(s, o, M, profile: bool = False):
+    """min of F(X) = sum o / |X|^2 over non-empty subsets with sum (s+o) <= M, or (profile) with
+    the simultaneous-start memory profile <= M.  Returns (F*, set of sizes attaining it)."""
     n = len(s)
     best, ks = None, set()
     for mask in range(1, 1 << n):
         ids = [i for i in range(n) if mask >> i & 1]
-        if sum(int(s[i]) + int(o[i]) for i in ids) > M:
+        if profile:
+            if batch_profile_peak(s, o, ids) > M:
+                continue
+        elif sum(int(s[i]) + int(o[i]) for i in ids) > M:
             continue
         F = Fraction(sum(int(o[i]) for i in ids), len(ids) ** 2)
         if best is None or F < best:

@@ -28,6 +28,11 @@
  *                             double scan, and one that leaves the inner scan at the first
  *                             request that no longer fits (the list is sorted by s+o, so none
  *                             after it fits either); the tests check that they agree.
+ *   oracle_exact_phase1       Algorithm 1, Phase 1, with every batch the exact minimiser of
+ *                             (F, -|X|): Algorithm 2's dynamic programme over (k, m) states with
+ *                             the chosen set carried along, feasibility either the sum of peaks
+ *                             (as Algorithm 2 prints it) or the simultaneous-start profile of
+ *                             Algorithm 1's Phase 1 (a derived programme over (k, sum s) states).
  *   oracle_apply_move / oracle_best_neighbor
  *                             position-level swap / insert neighbours of an order, scored by
  *                             total end-to-end latency (Section 2, "Objective").
@@ -347,6 +352,133 @@ int oracle_local_swap(int32_t n, const int32_t *s, const int32_t *o, int64_t M, 
     free(batch);
     free(inX);
     return ORACLE_OK;
+}
+
+/* -------------------------------------------------------------- Phase 1 (exact batches) */
+
+typedef struct { int32_t o; int32_t id; } oid_t;
+
+static int cmp_o_desc_id(const void *a, const void *b)
+{
+    const oid_t *x = (const oid_t *)a, *y = (const oid_t *)b;
+    if (x->o != y->o) return x->o > y->o ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+/*
+ * One exact batch over the requests ids[0..r) (ascending ids), Algorithm 2:
+ *   dp[k][m] = least sum of o over sets of k requests whose "load" is exactly m, path[k][m] = such
+ *   a set; requests are taken one by one, k runs downward, a state is replaced only by a strictly
+ *   smaller value; at the end every state is scored F = dp[k][m] / k^2 and the least is returned.
+ * feas_mode 0 (Algorithm 2 as printed): requests in input order, load = sum (s+o), a request may
+ *   join while the load stays <= M.
+ * feas_mode 1 (the constraint of Algorithm 1's Phase 1: with all of X started together, memory
+ *   at every completion time o_j, sum over {i in X: o_i >= o_j} of (s_i + o_j), is <= M):
+ *   requests in order of decreasing o (ties by id), load = sum s; when request j joins a set of k
+ *   it has the least o of the set, so the memory at time o_j is load + s_j + o_j (k + 1), which
+ *   must be <= M; the constraints at the larger completion times were met when those requests
+ *   joined and are not touched by j.  (Derived here; the paper gives no solver for this form.)
+ * Scoring order: k upward, m upward.  tie_rule 1 keeps the first least F met (Algorithm 2's strict
+ *   comparison); tie_rule 0 prefers the larger k among equal F (the text's (F, -|X|)), the first m
+ *   met within that k.
+ * inX[q] = 1 marks ids[q] as chosen.  Returns 0, or ORACLE_ENOMEM.
+ */
+static int exact_batch(int32_t r, const int32_t *ids, const int32_t *s, const int32_t *o, int64_t M,
+                       int32_t feas_mode, int32_t tie_rule, unsigned char *inX, int64_t *S_out,
+                       int64_t *K_out)
+{
+    const int64_t INF = INT64_MAX;
+    const size_t words = ((size_t)r + 63) / 64, cols = (size_t)M + 1, rows = (size_t)r + 1;
+    int64_t *dp = (int64_t *)malloc(sizeof(int64_t) * rows * cols);
+    uint64_t *path = (uint64_t *)calloc(rows * cols * words, sizeof(uint64_t));
+    oid_t *seq = (oid_t *)malloc(sizeof(oid_t) * (size_t)(r + 1));
+    if (!dp || !path || !seq) { free(dp); free(path); free(seq); return ORACLE_ENOMEM; }
+    for (size_t x = 0; x < rows * cols; ++x) dp[x] = INF;
+    dp[0] = 0;
+    for (int32_t q = 0; q < r; ++q) { seq[q].o = o[ids[q]]; seq[q].id = q; }  /* id = place in ids[] */
+    if (feas_mode == 1) qsort(seq, (size_t)r, sizeof(oid_t), cmp_o_desc_id);
+    for (int32_t t = 0; t < r; ++t) {
+        const int32_t q = seq[t].id, i = ids[q];
+        const int64_t load_i = feas_mode == 1 ? (int64_t)s[i] : (int64_t)s[i] + o[i];
+        for (int64_t k = r - 1; k >= 0; --k) {
+            for (int64_t m = 0; m <= M; ++m) {
+                const int64_t cur = dp[(size_t)k * cols + (size_t)m];
+                if (cur == INF) continue;
+                const int64_t new_m = m + load_i;
+                const int64_t need = feas_mode == 1 ? new_m + (int64_t)o[i] * (k + 1) : new_m;
+                if (need > M) continue;
+                const int64_t new_val = cur + o[i];
+                const size_t dst = (size_t)(k + 1) * cols + (size_t)new_m;
+                if (new_val < dp[dst]) {
+                    dp[dst] = new_val;
+                    memcpy(path + dst * words, path + ((size_t)k * cols + (size_t)m) * words, words * sizeof(uint64_t));
+                    path[dst * words + (size_t)q / 64] |= 1ull << (q % 64);
+                }
+            }
+        }
+    }
+    int64_t bestS = 0, bestk = 0;
+    size_t best = 0;
+    for (int64_t k = 1; k <= r; ++k) {
+        for (int64_t m = 0; m <= M; ++m) {
+            const int64_t v = dp[(size_t)k * cols + (size_t)m];
+            if (v == INF) continue;
+            int better;
+            if (bestk == 0) better = 1;
+            else {
+                const int c = cmp_F(v, k, bestS, bestk);
+                better = (c < 0) || (c == 0 && tie_rule == 0 && k > bestk);
+            }
+            if (better) { bestS = v; bestk = k; best = (size_t)k * cols + (size_t)m; }
+        }
+    }
+    for (int32_t q = 0; q < r; ++q) inX[q] = (unsigned char)((path[best * words + (size_t)q / 64] >> (q % 64)) & 1);
+    *S_out = bestS;
+    *K_out = bestk;
+    free(dp);
+    free(path);
+    free(seq);
+    return ORACLE_OK;
+}
+
+/*
+ * Phase 1 of Algorithm 1 with exact batches: choose the batch, append it in nondecreasing o
+ * (ties by id), remove it, repeat.  Outputs as oracle_sortedF.
+ */
+int oracle_exact_phase1(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t feas_mode,
+                        int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                        int32_t *nb_out)
+{
+    if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if ((tie_rule != 0 && tie_rule != 1) || (feas_mode != 0 && feas_mode != 1)) return ORACLE_EINVAL;
+    int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
+    skey_t *batch = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
+    unsigned char *inX = (unsigned char *)malloc((size_t)n + 1);
+    if (!ids || !batch || !inX) { free(ids); free(batch); free(inX); return ORACLE_ENOMEM; }
+    for (int32_t i = 0; i < n; ++i) ids[i] = i;
+    int32_t r = n, done = 0, nb = 0, rc = ORACLE_OK;
+    while (r > 0) {
+        int64_t S = 0, K = 0;
+        rc = exact_batch(r, ids, s, o, M, feas_mode, tie_rule, inX, &S, &K);
+        if (rc != ORACLE_OK) break;
+        int32_t nbatch = 0, keep = 0;
+        for (int32_t q = 0; q < r; ++q) {
+            if (inX[q]) { batch[nbatch].o = o[ids[q]]; batch[nbatch].id = ids[q]; batch[nbatch].w = 0; ++nbatch; }
+            else ids[keep++] = ids[q];
+        }
+        qsort(batch, (size_t)nbatch, sizeof(skey_t), cmp_o_id);
+        for (int32_t k = 0; k < nbatch; ++k) order_out[done + k] = batch[k].id;
+        done += nbatch;
+        r = keep;
+        if (batch_end_out) batch_end_out[nb] = done;
+        if (F_out) F_out[nb] = (double)S / ((double)K * (double)K);
+        ++nb;
+    }
+    if (nb_out) *nb_out = nb;
+    free(ids);
+    free(batch);
+    free(inX);
+    return rc;
 }
 
 /* ----------------------------------------------------------------- neighbourhood moves */
