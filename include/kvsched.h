@@ -55,7 +55,12 @@ typedef struct kvsched_ctx kvsched_ctx;
 #define KVSCHED_TIE_SMALLER 1 /* equal F: the smaller batch (first minimum scanning k upward) */
 
 /* largest supported decode length (slots of the per-timeline future-memory ring) */
+#define KVSCHED_FEAS_SUM_OF_PEAKS 0 /* a batch is feasible if sum (s_i + o_i) <= M (Algorithms 2-4)  */
+#define KVSCHED_FEAS_PROFILE 1      /* ... if, all started together, memory <= M at every completion
+                                       time (the constraint of Algorithm 1's Phase 1)              */
+
 #define KVSCHED_MAX_O 16384
+#define KVSCHED_EXACT_MAX_N 4096    /* most requests kvsched_exact_dp accepts                      */
 
 /* Create / destroy a context on HIP device `device_id`.  The context owns a few KB of device
  * and pinned host scratch plus buffers that grow with the largest n / K seen. */
@@ -136,6 +141,29 @@ int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t
 int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
                        int32_t *order_out, int32_t *batch_end_out, double *F_out,
                        int32_t *swaps_out, int32_t *num_batches_out, void *stream);
+
+/*
+ * Phase 1 of Algorithm 1 ("Batch Construction") with every batch the exact minimiser of
+ * (F(X), -|X|) over the feasible subsets of the remaining requests, by Algorithm 2 ("Exact
+ * Optimal Request Selection via Dynamic Programming"): dp[k][m] = least sum of o over sets of k
+ * requests of load exactly m; requests are offered one by one, a state is replaced only by a
+ * strictly smaller value and remembers the set that produced it; the state of least dp/k^2 is
+ * chosen (equal F: `tie_rule`, then the smaller load), its set is emitted in nondecreasing o_i
+ * (ties by id) and removed; repeat.
+ *   feas_mode KVSCHED_FEAS_SUM_OF_PEAKS: load = sum (s_i + o_i) <= M, requests offered in input order
+ *             (Algorithm 2 as printed);
+ *   feas_mode KVSCHED_FEAS_PROFILE: the memory of X started together, sum over {i: o_i >= o_j} of
+ *             (s_i + o_j), is <= M for every j in X (Algorithm 1, Phase 1); requests offered in
+ *             order of decreasing o_i (ties by id), load = sum s_i.
+ * Cost O(n^2 M) per batch; one host synchronisation per batch.
+ *
+ *   order_out, batch_end_out, F_out, num_batches_out   as for kvsched_sortedF
+ * ERANGE: n > KVSCHED_EXACT_MAX_N, or tables beyond 16 GiB ((k_max + 1) (M + 1) (8 + n / 8) bytes,
+ * k_max = the most requests that can share a batch).
+ */
+int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                     int32_t feas_mode, int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out,
+                     double *F_out, int32_t *num_batches_out, void *stream);
 
 /*
  * Local-search step on a priority order: every move is applied to `base_order` on the fly

@@ -7,6 +7,7 @@
 namespace {
 
 constexpr int64_t kMaxM = (int64_t)1 << 30;
+constexpr size_t kMaxExactTableBytes = (size_t)16 << 30;  // tables + records of the exact DP
 
 int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
 {
@@ -22,6 +23,30 @@ int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
     if (hipMalloc(&ctx->d_scratch, cap) != hipSuccess) return KVSCHED_ENOMEM;
     ctx->scratch_bytes = cap;
     return KVSCHED_OK;
+}
+
+int ensure_tables(kvsched_ctx *ctx, size_t bytes)
+{
+    if (bytes <= ctx->tables_bytes) return KVSCHED_OK;
+    if (ctx->d_tables) {
+        if (hipDeviceSynchronize() != hipSuccess) return KVSCHED_EHIP;
+        (void)hipFree(ctx->d_tables);
+        ctx->d_tables = nullptr;
+        ctx->tables_bytes = 0;
+    }
+    size_t cap = (bytes + ((size_t)1 << 20)) & ~(((size_t)1 << 20) - 1);
+    if (hipMalloc(&ctx->d_tables, cap) != hipSuccess) return KVSCHED_ENOMEM;
+    ctx->tables_bytes = cap;
+    return KVSCHED_OK;
+}
+
+// Read the context's device words back (one stream synchronisation).
+int read_words(kvsched_ctx *ctx, hipStream_t st)
+{
+    if (hipMemcpyAsync(ctx->h_words, ctx->d_words, sizeof(int32_t) * KVS_W_COUNT, hipMemcpyDeviceToHost, st) !=
+        hipSuccess)
+        return KVSCHED_EHIP;
+    return hipStreamSynchronize(st) == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
 // The timeline kernel, bracketed by the context's events when timing is on.
@@ -135,6 +160,8 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->h_words = nullptr;
     ctx->d_scratch = nullptr;
     ctx->scratch_bytes = 0;
+    ctx->d_tables = nullptr;
+    ctx->tables_bytes = 0;
     ctx->timing = 0;
     ctx->timed = 0;
     ctx->ev0 = nullptr;
@@ -157,6 +184,7 @@ void kvsched_destroy(kvsched_ctx *ctx)
     if (ctx->d_words) (void)hipFree(ctx->d_words);
     if (ctx->h_words) (void)hipHostFree(ctx->h_words);
     if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+    if (ctx->d_tables) (void)hipFree(ctx->d_tables);
     if (ctx->ev0) (void)hipEventDestroy(ctx->ev0);
     if (ctx->ev1) (void)hipEventDestroy(ctx->ev1);
     delete ctx;
@@ -306,6 +334,48 @@ int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int3
     if (rc != KVSCHED_OK) return rc;
     return kvs_launch_local_swap(n, s, o, (int32_t)M, order_out, batch_end_out, F_out, swaps_out, num_batches_out,
                                  ctx->d_scratch, ctx->d_words, st);
+}
+
+int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t feas_mode,
+                     int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                     int32_t *num_batches_out, void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!order_out || !batch_end_out || !F_out || !num_batches_out) return KVSCHED_EINVAL;
+    if (tie_rule != KVSCHED_TIE_LARGER && tie_rule != KVSCHED_TIE_SMALLER) return KVSCHED_EINVAL;
+    if (feas_mode != KVSCHED_FEAS_SUM_OF_PEAKS && feas_mode != KVSCHED_FEAS_PROFILE) return KVSCHED_EINVAL;
+    if (n > KVSCHED_EXACT_MAX_N) return KVSCHED_ERANGE;
+    hipStream_t st = (hipStream_t)stream;
+    rc = ensure_scratch(ctx, kvs_exact_dp_list_bytes(n));
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    rc = kvs_launch_exact_dp_prepare(n, s, o, (int32_t)M, feas_mode, ctx->d_scratch, ctx->d_words, num_batches_out, st);
+    if (rc != KVSCHED_OK) return rc;
+    rc = read_words(ctx, st);
+    if (rc != KVSCHED_OK) return rc;
+    int32_t r = ctx->h_words[KVS_W_REMAIN], kmax = ctx->h_words[KVS_W_KMAX];
+    if (r == 0) return KVSCHED_OK;  // malformed lengths: reported in the device status, no batches
+    if (r != n || kmax < 1 || kmax > n) return KVSCHED_EHIP;
+    const size_t bytes = kvs_exact_dp_table_bytes(r, kmax, (int32_t)M);
+    if (bytes > kMaxExactTableBytes) return KVSCHED_ERANGE;
+    rc = ensure_tables(ctx, bytes);
+    if (rc != KVSCHED_OK) return rc;
+    int32_t nb = 0;
+    while (r > 0) {  // r falls by at least one per batch
+        rc = kvs_launch_exact_dp_batch(n, r, kmax, s, o, (int32_t)M, feas_mode, tie_rule, nb, ctx->d_scratch,
+                                       ctx->d_tables, batch_end_out, F_out, ctx->d_words, st);
+        if (rc != KVSCHED_OK) return rc;
+        rc = read_words(ctx, st);
+        if (rc != KVSCHED_OK) return rc;
+        const int32_t r_next = ctx->h_words[KVS_W_REMAIN], k_next = ctx->h_words[KVS_W_KMAX];
+        ++nb;
+        if (r_next < 0 || r_next >= r || k_next > kmax || (r_next > 0 && k_next < 1)) return KVSCHED_EHIP;
+        r = r_next;
+        kmax = k_next;
+    }
+    return kvs_launch_exact_dp_emit(n, nb, ctx->d_scratch, order_out, num_batches_out, st);
 }
 
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,

@@ -1,0 +1,400 @@
+// Phase 1 of Algorithm 1 ("Batch Construction") with every batch the exact minimiser of
+// (F, -|X|), found by Algorithm 2 ("Exact Optimal Request Selection via Dynamic Programming"):
+//   dp[k][m] = least sum of o over sets of k requests whose load is exactly m,
+// requests taken one by one, k running downward, a state replaced only by a strictly smaller
+// value; at the end every state is scored F = dp[k][m] / k^2.
+//
+// On the GPU one request is one launch over all (k, m) states at once, reading the table of the
+// previous request and writing a second one (which is what "k downward" achieves in place): one
+// wavefront covers 64 consecutive loads m of one cardinality k, and its ballot of "this state was
+// improved by request t" is the only record kept of the chosen sets (bits[t][k][m / 64]).  The set
+// of the best state is recovered by walking those records backwards: at state (k, m) the last
+// request that improved it is a member, and the walk continues at (k - 1, m - load) among the
+// earlier requests.  That is the set Algorithm 2 carries in path[k][m].
+//
+// feas_mode 0: load = sum (s+o) <= M, requests in input order (Algorithm 2 as printed).
+// feas_mode 1: the constraint of Algorithm 1's Phase 1 (all of X started together stays within M
+//   at every completion time): requests in order of decreasing o, load = sum s, and request j may
+//   join k - 1 others only if load + o_j k <= M (j then has the least o, so this is the memory at
+//   its completion; the constraints at later completions are not touched by j).
+#include "phase1_util.h"
+
+namespace {
+
+constexpr int DP_T = 1024;  // threads of the single-workgroup helper kernels
+constexpr int DP_NW = DP_T / 64;
+constexpr int DP_INF = 0x7fffffff;
+constexpr int DP_STEP_T = 256;
+
+struct HelperLds {
+    RadixLds<DP_T> radix;
+    long long scan[DP_NW];
+    int scan_c[DP_NW];
+    int sh[4];
+    long long red_S[DP_NW];
+    int red_k[DP_NW];
+    int red_m[DP_NW];
+};
+
+__device__ __forceinline__ int cost_of(int sv, int ov, int feas_mode)
+{
+    return feas_mode ? sv + 1 : sv + ov;  // every feasible set of k requests has sum of cost <= M
+}
+
+// Length of the longest prefix of list[0..r) (ascending cost) whose costs sum to at most M: no
+// feasible set is larger.  All threads return the same value.
+__device__ int prefix_fit(const int *list, int r, const int *s, const int *o, int feas_mode, int M, HelperLds &L)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    long long carry = 0;
+    int K = 0;
+    for (int tile = 0; tile < r; tile += DP_T) {
+        const int i = tile + tid;
+        long long w = 0;
+        if (i < r) {
+            const int id = list[i];
+            w = cost_of(s[id], o[id], feas_mode);
+        }
+        for (int d = 1; d < 64; d <<= 1) {
+            const long long u = __shfl_up(w, d);
+            if (lane >= d) w += u;
+        }
+        if (lane == 63) L.scan[wave] = w;
+        __syncthreads();
+        long long off = carry, total = carry;
+        for (int v = 0; v < DP_NW; ++v) {
+            const long long x = L.scan[v];
+            if (v < wave) off += x;
+            total += x;
+        }
+        const int c = __syncthreads_count(i < r && w + off <= (long long)M);
+        K += c;
+        carry = total;
+        if (c < DP_T) break;  // uniform
+    }
+    __syncthreads();
+    return K;
+}
+
+// Validation, the three orders of the ids (emission order (o, id); processing order; ascending
+// cost), the first bound on the batch size.
+__global__ __launch_bounds__(DP_T) void dp_prepare_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
+                                                          int32_t feas_mode, int *proc, int *by_o, int *by_cost,
+                                                          int *buf0, int *buf1, int *batch_of, int32_t *words,
+                                                          int32_t *num_batches_out)
+{
+    __shared__ HelperLds L;
+    const int tid = threadIdx.x;
+    int omax = 0, cmax = 0, bad = 0;
+    for (int i = tid; i < n; i += DP_T) {
+        const int sv = s[i], ov = o[i];
+        if (sv < 1 || ov < 1 || (long long)sv + ov > (long long)M) bad = 1;
+        else {
+            omax = max(omax, ov);
+            cmax = max(cmax, cost_of(sv, ov, feas_mode));
+        }
+        batch_of[i] = -1;
+    }
+    if (tid < 4) L.sh[tid] = 0;
+    __syncthreads();
+    if (bad) atomicOr(&L.sh[2], 1);
+    atomicMax(&L.sh[0], omax);
+    atomicMax(&L.sh[1], cmax);
+    __syncthreads();
+    omax = L.sh[0];
+    cmax = L.sh[1];
+    if (L.sh[2] != 0) {  // a request that can never run: report, emit no batches
+        if (tid == 0) {
+            atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+            words[KVS_W_REMAIN] = 0;
+            words[KVS_W_KMAX] = 0;
+            *num_batches_out = 0;
+        }
+        return;
+    }
+    auto sort_by = [&](int *out, auto key, int kmax_key) {
+        for (int i = tid; i < n; i += DP_T) buf0[i] = i;
+        __syncthreads();
+        int *cur = buf0, *alt = buf1;
+        for (int shift = 0; shift < bits_of(kmax_key); shift += 8) {
+            radix_pass(cur, alt, n, shift, key, L.radix);
+            int *t = cur; cur = alt; alt = t;
+        }
+        for (int i = tid; i < n; i += DP_T) out[i] = cur[i];
+        __syncthreads();
+    };
+    sort_by(by_o, [o](int id) { return o[id]; }, omax);
+    if (feas_mode) sort_by(proc, [o, omax](int id) { return omax - o[id]; }, omax);
+    else {
+        for (int i = tid; i < n; i += DP_T) proc[i] = i;
+        __syncthreads();
+    }
+    sort_by(by_cost, [s, o, feas_mode](int id) { return cost_of(s[id], o[id], feas_mode); }, cmax);
+    __threadfence_block();
+    __syncthreads();
+    const int kmax = prefix_fit(by_cost, n, s, o, feas_mode, M, L);
+    if (tid == 0) {
+        words[KVS_W_REMAIN] = n;
+        words[KVS_W_KMAX] = kmax;
+    }
+}
+
+__global__ __launch_bounds__(DP_STEP_T) void dp_init_kernel(int *a, int *b, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * DP_STEP_T + threadIdx.x;
+    if (i < count) {
+        const int v = i == 0 ? 0 : DP_INF;  // dp[0][0] = 0
+        a[i] = v;
+        b[i] = v;
+    }
+}
+
+// Request proc[t] offered to every state: row k = blockIdx.y + 1, loads blockIdx.x * 256 ...
+__global__ __launch_bounds__(DP_STEP_T) void dp_step_kernel(const int *proc, int t, const int32_t *s, const int32_t *o,
+                                                            int32_t M, int32_t feas_mode, const int *src, int *dst,
+                                                            unsigned long long *bits_t, int Mp)
+{
+    const int k = blockIdx.y + 1;
+    const int m = blockIdx.x * DP_STEP_T + threadIdx.x;  // < Mp by the launch shape
+    const int id = proc[t];
+    const int oi = o[id];
+    const int load = feas_mode ? s[id] : s[id] + oi;
+    const size_t at = (size_t)k * Mp + m;
+    const int old = src[at];
+    int cand = DP_INF;
+    if (m <= M && m >= load) {
+        const int prev = src[at - Mp - load];
+        const bool fits = feas_mode == 0 || (long long)m + (long long)oi * k <= (long long)M;
+        if (prev != DP_INF && fits) cand = prev + oi;
+    }
+    const bool take = cand < old;
+    dst[at] = take ? cand : old;
+    const unsigned long long bal = __builtin_amdgcn_ballot_w64(take);
+    if ((threadIdx.x & 63) == 0) bits_t[(size_t)k * (Mp >> 6) + (m >> 6)] = bal;
+}
+
+// sign of Sa/ka^2 - Sb/kb^2 (S < 2^31, k <= 4096: the products stay below 2^55)
+__device__ __forceinline__ int dp_cmp_F(long long Sa, int ka, long long Sb, int kb)
+{
+    const long long l = Sa * (long long)kb * (long long)kb, r = Sb * (long long)ka * (long long)ka;
+    return l < r ? -1 : (l > r ? 1 : 0);
+}
+
+// Is state a a better final choice than state b?  Least F; among equal F the larger k
+// (KVSCHED_TIE_LARGER) or the smaller; then the smaller load (the first met scanning m upward).
+__device__ __forceinline__ bool dp_better(long long Sa, int ka, int ma, long long Sb, int kb, int mb, int tie_rule)
+{
+    if (ka == 0) return false;
+    if (kb == 0) return true;
+    const int c = dp_cmp_F(Sa, ka, Sb, kb);
+    if (c != 0) return c < 0;
+    if (ka != kb) return tie_rule == KVSCHED_TIE_LARGER ? ka > kb : ka < kb;
+    return ma < mb;
+}
+
+__global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const int *dp, int kmax, int32_t M, int Mp, int32_t tie_rule,
+                                                         int32_t done, int32_t nb, int32_t *batch_end_out, double *F_out,
+                                                         int32_t *words)
+{
+    __shared__ HelperLds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    long long bS = 0;
+    int bk = 0, bm = 0;
+    for (int k = 1; k <= kmax; ++k) {
+        const int *row = dp + (size_t)k * Mp;
+        for (int m = tid; m <= M; m += DP_T) {
+            const int v = row[m];
+            if (v != DP_INF && dp_better(v, k, m, bS, bk, bm, tie_rule)) { bS = v; bk = k; bm = m; }
+        }
+    }
+    for (int d = 32; d > 0; d >>= 1) {
+        const long long oS = __shfl_down(bS, d);
+        const int ok = __shfl_down(bk, d), om = __shfl_down(bm, d);
+        if (dp_better(oS, ok, om, bS, bk, bm, tie_rule)) { bS = oS; bk = ok; bm = om; }
+    }
+    if (lane == 0) { L.red_S[wave] = bS; L.red_k[wave] = bk; L.red_m[wave] = bm; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int v = 1; v < DP_NW; ++v)
+            if (dp_better(L.red_S[v], L.red_k[v], L.red_m[v], bS, bk, bm, tie_rule)) {
+                bS = L.red_S[v]; bk = L.red_k[v]; bm = L.red_m[v];
+            }
+        words[KVS_W_BESTK] = bk;
+        words[KVS_W_BESTM] = bm;
+        if (bk >= 1) {
+            batch_end_out[nb] = done + bk;
+            F_out[nb] = (double)bS / ((double)bk * (double)bk);
+        } else {  // cannot happen for well-formed input (a single request always fits)
+            atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+        }
+    }
+}
+
+// One wavefront follows the records back from the best state and stamps the members with the
+// batch number.  A set of k needs k requests, so only records of requests t >= k - 1 exist (rows
+// above t + 1 are not launched and hold nothing of this batch).  Every pass lowers `bound`, so the
+// loop ends.
+__global__ __launch_bounds__(64) void dp_walk_kernel(const unsigned long long *bits, const int *proc, int r, int kmax,
+                                                     int Mp, const int32_t *s, const int32_t *o, int32_t feas_mode,
+                                                     int32_t nb, int *batch_of, const int32_t *words)
+{
+    const int lane = threadIdx.x;
+    int k = words[KVS_W_BESTK], m = words[KVS_W_BESTM];
+    const size_t per_t = (size_t)(kmax + 1) * (Mp >> 6);
+    int bound = r - 1;
+    while (k > 0 && bound >= 0 && m >= 0) {
+        const int t = bound - lane;
+        bool hit = false;
+        if (t >= k - 1) hit = (bits[(size_t)t * per_t + (size_t)k * (Mp >> 6) + (m >> 6)] >> (m & 63)) & 1ull;
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(hit);
+        if (bal == 0) {
+            bound -= 64;
+            continue;
+        }
+        const int tstar = bound - (int)__builtin_ctzll(bal);  // the latest such request
+        const int id = proc[tstar];
+        if (lane == 0) batch_of[id] = nb;
+        m -= feas_mode ? s[id] : s[id] + o[id];
+        k -= 1;
+        bound = tstar - 1;
+    }
+}
+
+// Members leave proc[] and by_cost[] (both keep their order); the new count and the new bound on
+// the batch size go to the words the host reads.
+__global__ __launch_bounds__(DP_T) void dp_compact_kernel(int *proc, int *by_cost, int *tmp, int r, int32_t nb,
+                                                          const int *batch_of, const int32_t *s, const int32_t *o,
+                                                          int32_t feas_mode, int32_t M, int32_t *words)
+{
+    __shared__ HelperLds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int kept = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        int *list = pass == 0 ? proc : by_cost;
+        int carry = 0;
+        for (int tile = 0; tile < r; tile += DP_T) {
+            const int i = tile + tid;
+            int id = 0, keep = 0;
+            if (i < r) {
+                id = list[i];
+                keep = batch_of[id] != nb;
+            }
+            int c = keep;
+            for (int d = 1; d < 64; d <<= 1) {
+                const int u = __shfl_up(c, d);
+                if (lane >= d) c += u;
+            }
+            if (lane == 63) L.scan_c[wave] = c;
+            __syncthreads();
+            int off = carry, total = carry;
+            for (int u = 0; u < DP_NW; ++u) {
+                const int x = L.scan_c[u];
+                if (u < wave) off += x;
+                total += x;
+            }
+            if (keep) tmp[off + c - 1] = id;
+            carry = total;
+            __syncthreads();
+        }
+        kept = carry;
+        __threadfence_block();
+        __syncthreads();
+        for (int i = tid; i < kept; i += DP_T) list[i] = tmp[i];
+        __threadfence_block();
+        __syncthreads();
+    }
+    const int kmax = kept > 0 ? prefix_fit(by_cost, kept, s, o, feas_mode, M, L) : 0;
+    if (tid == 0) {
+        words[KVS_W_REMAIN] = kept;
+        words[KVS_W_KMAX] = kmax;
+    }
+}
+
+// The (o, id)-sorted ids ordered by batch number (stable): each batch in nondecreasing o.
+__global__ __launch_bounds__(DP_T) void dp_emit_kernel(int32_t n, const int *by_o, int *buf0, int *buf1,
+                                                       const int *batch_of, int32_t nb, int32_t *order_out,
+                                                       int32_t *num_batches_out)
+{
+    __shared__ HelperLds L;
+    const int tid = threadIdx.x;
+    const int *src = by_o;
+    int *dst = buf0, *other = buf1;
+    auto key_b = [batch_of](int id) { return batch_of[id]; };
+    bool first = true;
+    for (int shift = 0; shift < bits_of(nb - 1); shift += 8) {
+        radix_pass(src, dst, n, shift, key_b, L.radix);
+        if (first) { src = dst; dst = other; first = false; }
+        else { int *t = (int *)src; src = dst; dst = t; }
+    }
+    for (int i = tid; i < n; i += DP_T) order_out[i] = src[i];
+    if (tid == 0) *num_batches_out = nb;
+}
+
+bool launched() { return hipGetLastError() == hipSuccess; }
+
+}  // namespace
+
+size_t kvs_exact_dp_list_bytes(int32_t n)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    return np * 6 * sizeof(int) + 256;
+}
+
+size_t kvs_exact_dp_table_bytes(int32_t r, int32_t kmax, int32_t M)
+{
+    const size_t Mp = ((size_t)M + DP_STEP_T) & ~(size_t)(DP_STEP_T - 1);
+    return 2 * (size_t)(kmax + 1) * Mp * sizeof(int) + (size_t)r * (size_t)(kmax + 1) * (Mp / 8) + 256;
+}
+
+int kvs_launch_exact_dp_prepare(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
+                                void *lists, int32_t *d_words, int32_t *num_batches_out, hipStream_t st)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    int *proc = (int *)lists, *by_o = proc + np, *by_cost = by_o + np, *buf0 = by_cost + np, *buf1 = buf0 + np,
+        *batch_of = buf1 + np;
+    hipLaunchKernelGGL(dp_prepare_kernel, dim3(1), dim3(DP_T), 0, st, n, s, o, M, feas_mode, proc, by_o, by_cost, buf0,
+                       buf1, batch_of, d_words, num_batches_out);
+    return launched() ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+// One batch over the r remaining requests: tables, records, best state, members, compaction.
+int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t *s, const int32_t *o, int32_t M,
+                              int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
+                              int32_t *batch_end_out, double *F_out, int32_t *d_words, hipStream_t st)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    int *proc = (int *)lists, *by_cost = proc + 2 * np, *buf0 = by_cost + np, *batch_of = buf0 + 2 * np;
+    const int Mp = (int)(((size_t)M + DP_STEP_T) & ~(size_t)(DP_STEP_T - 1));
+    const size_t table = (size_t)(kmax + 1) * Mp;
+    int *dp[2] = {(int *)tables, (int *)tables + table};
+    unsigned long long *bits = (unsigned long long *)((int *)tables + 2 * table);
+    const size_t per_t = (size_t)(kmax + 1) * (Mp >> 6);
+    hipLaunchKernelGGL(dp_init_kernel, dim3((unsigned)((table + DP_STEP_T - 1) / DP_STEP_T)), dim3(DP_STEP_T), 0, st,
+                       dp[0], dp[1], table);
+    if (!launched()) return KVSCHED_EHIP;
+    for (int32_t t = 0; t < r; ++t) {
+        const int rows = t + 1 < kmax ? t + 1 : kmax;  // after t + 1 requests no set is larger
+        hipLaunchKernelGGL(dp_step_kernel, dim3((unsigned)(Mp / DP_STEP_T), (unsigned)rows), dim3(DP_STEP_T), 0, st,
+                           proc, t, s, o, M, feas_mode, dp[t & 1], dp[(t + 1) & 1], bits + (size_t)t * per_t, Mp);
+        if (!launched()) return KVSCHED_EHIP;
+    }
+    hipLaunchKernelGGL(dp_argmin_kernel, dim3(1), dim3(DP_T), 0, st, dp[r & 1], kmax, M, Mp, tie_rule, n - r, nb,
+                       batch_end_out, F_out, d_words);
+    if (!launched()) return KVSCHED_EHIP;
+    hipLaunchKernelGGL(dp_walk_kernel, dim3(1), dim3(64), 0, st, bits, proc, r, kmax, Mp, s, o, feas_mode, nb, batch_of,
+                       d_words);
+    if (!launched()) return KVSCHED_EHIP;
+    hipLaunchKernelGGL(dp_compact_kernel, dim3(1), dim3(DP_T), 0, st, proc, by_cost, buf0, r, nb, batch_of, s, o,
+                       feas_mode, M, d_words);
+    return launched() ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_exact_dp_emit(int32_t n, int32_t nb, void *lists, int32_t *order_out, int32_t *num_batches_out,
+                             hipStream_t st)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    int *proc = (int *)lists, *by_o = proc + np, *buf0 = proc + 3 * np, *buf1 = buf0 + np, *batch_of = buf1 + np;
+    hipLaunchKernelGGL(dp_emit_kernel, dim3(1), dim3(DP_T), 0, st, n, by_o, buf0, buf1, batch_of, nb, order_out,
+                       num_batches_out);
+    return launched() ? KVSCHED_OK : KVSCHED_EHIP;
+}

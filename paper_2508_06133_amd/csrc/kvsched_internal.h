@@ -11,6 +11,10 @@ enum {
     KVS_W_STATUS = 0,  // OR of KVSCHED_DEV_* bits for the call in flight
     KVS_W_OMAX = 1,    // largest decode length found by the length scan
     KVS_W_MINPOS = 2,  // smallest position any move touches (best_neighbor)
+    KVS_W_REMAIN = 3,  // exact DP: requests not yet in a batch
+    KVS_W_KMAX = 4,    // exact DP: bound on the size of the next batch
+    KVS_W_BESTK = 5,   // exact DP: best state of the batch in hand
+    KVS_W_BESTM = 6,
     KVS_W_COUNT = 8
 };
 
@@ -21,6 +25,8 @@ struct kvsched_ctx {
     int32_t *h_words;      // [KVS_W_COUNT] pinned host mirror
     void *d_scratch;       // grows on demand
     size_t scratch_bytes;
+    void *d_tables;        // exact DP: tables and records, grows on demand
+    size_t tables_bytes;
     int timing;            // record events around the timeline kernel
     int timed;             // a pair of events has been recorded
     hipEvent_t ev0, ev1;
@@ -68,6 +74,17 @@ int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t
 int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *tel_out, int32_t *d_words,
                            hipStream_t st);
 int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, int32_t with_base, hipStream_t st);
+
+// exactdp.hip
+size_t kvs_exact_dp_list_bytes(int32_t n);
+size_t kvs_exact_dp_table_bytes(int32_t r, int32_t kmax, int32_t M);
+int kvs_launch_exact_dp_prepare(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
+                                void *lists, int32_t *d_words, int32_t *num_batches_out, hipStream_t st);
+int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t *s, const int32_t *o, int32_t M,
+                              int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
+                              int32_t *batch_end_out, double *F_out, int32_t *d_words, hipStream_t st);
+int kvs_launch_exact_dp_emit(int32_t n, int32_t nb, void *lists, int32_t *order_out, int32_t *num_batches_out,
+                             hipStream_t st);
 
 // localswap.hip
 size_t kvs_local_swap_scratch_bytes(int32_t n);

@@ -18,6 +18,8 @@ OK = 0
 TIE_LARGER, TIE_SMALLER = 0, 1
 MOVE_SWAP, MOVE_INSERT = 0, 1
 DEV_BAD_LENGTH, DEV_BAD_ORDER, DEV_BAD_MOVE, DEV_O_MAX = 1, 2, 4, 8
+FEAS_SUM_OF_PEAKS, FEAS_PROFILE = 0, 1
+EXACT_MAX_N = 4096
 
 
 class KvschedError(RuntimeError):
@@ -48,6 +50,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
     lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     return lib
@@ -172,6 +175,21 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_local_swap")
         return order, ends, F, swaps, nb
+
+    def exact_dp(self, s, o, M, feas_mode: int = FEAS_SUM_OF_PEAKS, tie_rule: int = TIE_LARGER):
+        """Phase 1 with exact batches (Algorithm 2) -> (order [n], batch_end [n], F [n], num_batches [1])."""
+        n = s.shape[0]
+        dev = s.device
+        order = torch.empty(n, dtype=torch.int32, device=dev)
+        ends = torch.zeros(n, dtype=torch.int32, device=dev)
+        F = torch.zeros(n, dtype=torch.float64, device=dev)
+        nb = torch.zeros(1, dtype=torch.int32, device=dev)
+        rc = _lib.kvsched_exact_dp(self._h, n, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
+                                   int(feas_mode), int(tie_rule), order.data_ptr(), ends.data_ptr(), F.data_ptr(),
+                                   nb.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_exact_dp")
+        return order, ends, F, nb
 
     def best_neighbor(self, base_order, moves, s, o, M, want_tel: bool = True):
         """-> (tel [K] int64 or None, result [3] int64 = {best move, its TEL, TEL of base})."""
