@@ -351,6 +351,15 @@ int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
+    // Small problems run in one workgroup with both tables in LDS; a batch holds at most M / 2
+    // requests (each costs at least 2 of the budget), which may already show that they fit.
+    const int32_t k_host = (int32_t)((M / 2 < n) ? M / 2 : n);
+    if (const int lg = kvs_exact_dp_small_lg(n, k_host, (int32_t)M)) {
+        rc = ensure_tables(ctx, kvs_exact_dp_small_record_bytes(n, k_host, lg));
+        if (rc != KVSCHED_OK) return rc;
+        return kvs_launch_exact_dp_small(n, s, o, (int32_t)M, feas_mode, tie_rule, lg, ctx->d_scratch, ctx->d_tables,
+                                         order_out, batch_end_out, F_out, num_batches_out, ctx->d_words, st);
+    }
     rc = kvs_launch_exact_dp_prepare(n, s, o, (int32_t)M, feas_mode, ctx->d_scratch, ctx->d_words, num_batches_out, st);
     if (rc != KVSCHED_OK) return rc;
     rc = read_words(ctx, st);
@@ -358,6 +367,12 @@ int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_
     int32_t r = ctx->h_words[KVS_W_REMAIN], kmax = ctx->h_words[KVS_W_KMAX];
     if (r == 0) return KVSCHED_OK;  // malformed lengths: reported in the device status, no batches
     if (r != n || kmax < 1 || kmax > n) return KVSCHED_EHIP;
+    if (const int lg = kvs_exact_dp_small_lg(n, kmax, (int32_t)M)) {  // fits after all, with the true bound
+        rc = ensure_tables(ctx, kvs_exact_dp_small_record_bytes(n, kmax, lg));
+        if (rc != KVSCHED_OK) return rc;
+        return kvs_launch_exact_dp_small(n, s, o, (int32_t)M, feas_mode, tie_rule, lg, ctx->d_scratch, ctx->d_tables,
+                                         order_out, batch_end_out, F_out, num_batches_out, ctx->d_words, st);
+    }
     const size_t bytes = kvs_exact_dp_table_bytes(r, kmax, (int32_t)M);
     if (bytes > kMaxExactTableBytes) return KVSCHED_ERANGE;
     rc = ensure_tables(ctx, bytes);

@@ -25,6 +25,7 @@ constexpr int DP_T = 1024;  // threads of the single-workgroup helper kernels
 constexpr int DP_NW = DP_T / 64;
 constexpr int DP_INF = 0x7fffffff;
 constexpr int DP_STEP_T = 256;
+constexpr int DP_ARGMIN_BLOCKS = 256;
 
 struct HelperLds {
     RadixLds<DP_T> radix;
@@ -78,12 +79,11 @@ __device__ int prefix_fit(const int *list, int r, const int *s, const int *o, in
 
 // Validation, the three orders of the ids (emission order (o, id); processing order; ascending
 // cost), the first bound on the batch size.
-__global__ __launch_bounds__(DP_T) void dp_prepare_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
-                                                          int32_t feas_mode, int *proc, int *by_o, int *by_cost,
-                                                          int *buf0, int *buf1, int *batch_of, int32_t *words,
-                                                          int32_t *num_batches_out)
+// Returns that bound, or -1 for malformed lengths (reported; no batches).
+__device__ int prepare_body(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode, int *proc,
+                            int *by_o, int *by_cost, int *buf0, int *buf1, int *batch_of, int32_t *words,
+                            int32_t *num_batches_out, HelperLds &L)
 {
-    __shared__ HelperLds L;
     const int tid = threadIdx.x;
     int omax = 0, cmax = 0, bad = 0;
     for (int i = tid; i < n; i += DP_T) {
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(DP_T) void dp_prepare_kernel(int32_t n, const int32
             words[KVS_W_KMAX] = 0;
             *num_batches_out = 0;
         }
-        return;
+        return -1;
     }
     auto sort_by = [&](int *out, auto key, int kmax_key) {
         for (int i = tid; i < n; i += DP_T) buf0[i] = i;
@@ -132,8 +132,18 @@ __global__ __launch_bounds__(DP_T) void dp_prepare_kernel(int32_t n, const int32
     sort_by(by_cost, [s, o, feas_mode](int id) { return cost_of(s[id], o[id], feas_mode); }, cmax);
     __threadfence_block();
     __syncthreads();
-    const int kmax = prefix_fit(by_cost, n, s, o, feas_mode, M, L);
-    if (tid == 0) {
+    return prefix_fit(by_cost, n, s, o, feas_mode, M, L);
+}
+
+__global__ __launch_bounds__(DP_T) void dp_prepare_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
+                                                          int32_t feas_mode, int *proc, int *by_o, int *by_cost,
+                                                          int *buf0, int *buf1, int *batch_of, int32_t *words,
+                                                          int32_t *num_batches_out)
+{
+    __shared__ HelperLds L;
+    const int kmax = prepare_body(n, s, o, M, feas_mode, proc, by_o, by_cost, buf0, buf1, batch_of, words,
+                                  num_batches_out, L);
+    if (kmax >= 0 && threadIdx.x == 0) {
         words[KVS_W_REMAIN] = n;
         words[KVS_W_KMAX] = kmax;
     }
@@ -192,26 +202,16 @@ __device__ __forceinline__ bool dp_better(long long Sa, int ka, int ma, long lon
     return ma < mb;
 }
 
-__global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const int *dp, int kmax, int32_t M, int Mp, int32_t tie_rule,
-                                                         int32_t done, int32_t nb, int32_t *batch_end_out, double *F_out,
-                                                         int32_t *words)
+// Block-wide best of per-thread candidates; every thread receives it.
+__device__ void reduce_best(int32_t tie_rule, HelperLds &L, long long &bS, int &bk, int &bm)
 {
-    __shared__ HelperLds L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    long long bS = 0;
-    int bk = 0, bm = 0;
-    for (int k = 1; k <= kmax; ++k) {
-        const int *row = dp + (size_t)k * Mp;
-        for (int m = tid; m <= M; m += DP_T) {
-            const int v = row[m];
-            if (v != DP_INF && dp_better(v, k, m, bS, bk, bm, tie_rule)) { bS = v; bk = k; bm = m; }
-        }
-    }
     for (int d = 32; d > 0; d >>= 1) {
         const long long oS = __shfl_down(bS, d);
         const int ok = __shfl_down(bk, d), om = __shfl_down(bm, d);
         if (dp_better(oS, ok, om, bS, bk, bm, tie_rule)) { bS = oS; bk = ok; bm = om; }
     }
+    __syncthreads();  // the reduction slots may still be read from an earlier call
     if (lane == 0) { L.red_S[wave] = bS; L.red_k[wave] = bk; L.red_m[wave] = bm; }
     __syncthreads();
     if (tid == 0) {
@@ -219,14 +219,80 @@ __global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const int *dp, int kmax
             if (dp_better(L.red_S[v], L.red_k[v], L.red_m[v], bS, bk, bm, tie_rule)) {
                 bS = L.red_S[v]; bk = L.red_k[v]; bm = L.red_m[v];
             }
+        L.red_S[0] = bS;
+        L.red_k[0] = bk;
+        L.red_m[0] = bm;
+    }
+    __syncthreads();
+    bS = L.red_S[0];
+    bk = L.red_k[0];
+    bm = L.red_m[0];
+}
+
+// Best final state among rows k_first, k_first + k_step, ... <= kmax of a table (global or LDS);
+// every thread receives it (bk = 0: none).
+template <class TablePtr>
+__device__ void argmin_body(TablePtr dp, int k_first, int k_step, int kmax, int32_t M, int Mp, int32_t tie_rule,
+                            HelperLds &L, long long &bS, int &bk, int &bm)
+{
+    const int tid = threadIdx.x;
+    bS = 0;
+    bk = 0;
+    bm = 0;
+    for (int k = k_first; k <= kmax; k += k_step) {
+        for (int m = tid; m <= M; m += DP_T) {
+            const int v = dp[(size_t)k * Mp + m];
+            if (v != DP_INF && dp_better(v, k, m, bS, bk, bm, tie_rule)) { bS = v; bk = k; bm = m; }
+        }
+    }
+    reduce_best(tie_rule, L, bS, bk, bm);
+}
+
+// Thread 0: the outputs of batch nb (or the report that no state exists, which cannot happen for
+// well-formed input: a single request always fits).
+__device__ void publish_batch(long long bS, int bk, int32_t done, int32_t nb, int32_t *batch_end_out, double *F_out,
+                              int32_t *words)
+{
+    if (bk >= 1) {
+        batch_end_out[nb] = done + bk;
+        F_out[nb] = (double)bS / ((double)bk * (double)bk);
+    } else {
+        atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+    }
+}
+
+// Stage 1: workgroup b reduces rows 1 + b, 1 + b + G, ...; stage 2: one workgroup reduces the G partials.
+__global__ __launch_bounds__(DP_T) void dp_argmin_rows_kernel(const int *dp, int kmax, int32_t M, int Mp,
+                                                              int32_t tie_rule, long long *partial)
+{
+    __shared__ HelperLds L;
+    long long bS;
+    int bk, bm;
+    argmin_body(dp, 1 + (int)blockIdx.x, (int)gridDim.x, kmax, M, Mp, tie_rule, L, bS, bk, bm);
+    if (threadIdx.x == 0) {
+        partial[3 * blockIdx.x + 0] = bS;
+        partial[3 * blockIdx.x + 1] = bk;
+        partial[3 * blockIdx.x + 2] = bm;
+    }
+}
+
+__global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const long long *partial, int G, int32_t tie_rule, int32_t done,
+                                                         int32_t nb, int32_t *batch_end_out, double *F_out,
+                                                         int32_t *words)
+{
+    __shared__ HelperLds L;
+    long long bS = 0;
+    int bk = 0, bm = 0;
+    for (int g = threadIdx.x; g < G; g += DP_T) {
+        const long long S = partial[3 * g];
+        const int k = (int)partial[3 * g + 1], m = (int)partial[3 * g + 2];
+        if (dp_better(S, k, m, bS, bk, bm, tie_rule)) { bS = S; bk = k; bm = m; }
+    }
+    reduce_best(tie_rule, L, bS, bk, bm);
+    if (threadIdx.x == 0) {
         words[KVS_W_BESTK] = bk;
         words[KVS_W_BESTM] = bm;
-        if (bk >= 1) {
-            batch_end_out[nb] = done + bk;
-            F_out[nb] = (double)bS / ((double)bk * (double)bk);
-        } else {  // cannot happen for well-formed input (a single request always fits)
-            atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
-        }
+        publish_batch(bS, bk, done, nb, batch_end_out, F_out, words);
     }
 }
 
@@ -234,12 +300,10 @@ __global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const int *dp, int kmax
 // batch number.  A set of k needs k requests, so only records of requests t >= k - 1 exist (rows
 // above t + 1 are not launched and hold nothing of this batch).  Every pass lowers `bound`, so the
 // loop ends.
-__global__ __launch_bounds__(64) void dp_walk_kernel(const unsigned long long *bits, const int *proc, int r, int kmax,
-                                                     int Mp, const int32_t *s, const int32_t *o, int32_t feas_mode,
-                                                     int32_t nb, int *batch_of, const int32_t *words)
+__device__ void walk_body(const unsigned long long *bits, const int *proc, int r, int kmax, int Mp, const int32_t *s,
+                          const int32_t *o, int32_t feas_mode, int32_t nb, int *batch_of, int k, int m)
 {
-    const int lane = threadIdx.x;
-    int k = words[KVS_W_BESTK], m = words[KVS_W_BESTM];
+    const int lane = threadIdx.x & 63;
     const size_t per_t = (size_t)(kmax + 1) * (Mp >> 6);
     int bound = r - 1;
     while (k > 0 && bound >= 0 && m >= 0) {
@@ -260,15 +324,20 @@ __global__ __launch_bounds__(64) void dp_walk_kernel(const unsigned long long *b
     }
 }
 
-// Members leave proc[] and by_cost[] (both keep their order); the new count and the new bound on
-// the batch size go to the words the host reads.
-__global__ __launch_bounds__(DP_T) void dp_compact_kernel(int *proc, int *by_cost, int *tmp, int r, int32_t nb,
-                                                          const int *batch_of, const int32_t *s, const int32_t *o,
-                                                          int32_t feas_mode, int32_t M, int32_t *words)
+__global__ __launch_bounds__(64) void dp_walk_kernel(const unsigned long long *bits, const int *proc, int r, int kmax,
+                                                     int Mp, const int32_t *s, const int32_t *o, int32_t feas_mode,
+                                                     int32_t nb, int *batch_of, const int32_t *words)
 {
-    __shared__ HelperLds L;
+    walk_body(bits, proc, r, kmax, Mp, s, o, feas_mode, nb, batch_of, words[KVS_W_BESTK], words[KVS_W_BESTM]);
+}
+
+// Members leave proc[] and by_cost[] (both keep their order); kept = the new count, kmax = the new
+// bound on the batch size.
+__device__ void compact_body(int *proc, int *by_cost, int *tmp, int r, int32_t nb, const int *batch_of, const int32_t *s,
+                             const int32_t *o, int32_t feas_mode, int32_t M, HelperLds &L, int &kept, int &kmax)
+{
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int kept = 0;
+    kept = 0;
     for (int pass = 0; pass < 2; ++pass) {
         int *list = pass == 0 ? proc : by_cost;
         int carry = 0;
@@ -303,19 +372,26 @@ __global__ __launch_bounds__(DP_T) void dp_compact_kernel(int *proc, int *by_cos
         __threadfence_block();
         __syncthreads();
     }
-    const int kmax = kept > 0 ? prefix_fit(by_cost, kept, s, o, feas_mode, M, L) : 0;
-    if (tid == 0) {
+    kmax = kept > 0 ? prefix_fit(by_cost, kept, s, o, feas_mode, M, L) : 0;
+}
+
+__global__ __launch_bounds__(DP_T) void dp_compact_kernel(int *proc, int *by_cost, int *tmp, int r, int32_t nb,
+                                                          const int *batch_of, const int32_t *s, const int32_t *o,
+                                                          int32_t feas_mode, int32_t M, int32_t *words)
+{
+    __shared__ HelperLds L;
+    int kept, kmax;
+    compact_body(proc, by_cost, tmp, r, nb, batch_of, s, o, feas_mode, M, L, kept, kmax);
+    if (threadIdx.x == 0) {  // the words the host reads
         words[KVS_W_REMAIN] = kept;
         words[KVS_W_KMAX] = kmax;
     }
 }
 
 // The (o, id)-sorted ids ordered by batch number (stable): each batch in nondecreasing o.
-__global__ __launch_bounds__(DP_T) void dp_emit_kernel(int32_t n, const int *by_o, int *buf0, int *buf1,
-                                                       const int *batch_of, int32_t nb, int32_t *order_out,
-                                                       int32_t *num_batches_out)
+__device__ void emit_body(int32_t n, const int *by_o, int *buf0, int *buf1, const int *batch_of, int32_t nb,
+                          int32_t *order_out, int32_t *num_batches_out, HelperLds &L)
 {
-    __shared__ HelperLds L;
     const int tid = threadIdx.x;
     const int *src = by_o;
     int *dst = buf0, *other = buf1;
@@ -328,6 +404,100 @@ __global__ __launch_bounds__(DP_T) void dp_emit_kernel(int32_t n, const int *by_
     }
     for (int i = tid; i < n; i += DP_T) order_out[i] = src[i];
     if (tid == 0) *num_batches_out = nb;
+}
+
+__global__ __launch_bounds__(DP_T) void dp_emit_kernel(int32_t n, const int *by_o, int *buf0, int *buf1,
+                                                       const int *batch_of, int32_t nb, int32_t *order_out,
+                                                       int32_t *num_batches_out)
+{
+    __shared__ HelperLds L;
+    emit_body(n, by_o, buf0, buf1, batch_of, nb, order_out, num_batches_out, L);
+}
+
+// The whole Phase 1 in one workgroup when both tables fit in LDS (the settings Algorithm 2 is meant
+// for: about a hundred requests, M of a few hundred to a few thousand): no launch per request and
+// no host round trip per batch.  Row length Mp = 2^lg >= M + 1; the records still go to global
+// memory.  Same arithmetic and the same order of updates as the kernels above.
+constexpr int DP_SMALL_STATES = 12288;  // (kmax + 1) * Mp at most; two int tables = 96 KB of LDS
+constexpr int DP_SMALL_N = 1024;
+
+__global__ __launch_bounds__(DP_T) void dp_small_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
+                                                        int32_t feas_mode, int32_t tie_rule, int lg, int *proc, int *by_o,
+                                                        int *by_cost, int *buf0, int *buf1, int *batch_of,
+                                                        unsigned long long *bits, int32_t *order_out,
+                                                        int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
+                                                        int32_t *words)
+{
+    __shared__ HelperLds L;
+    __shared__ int tab[2][DP_SMALL_STATES];
+    __shared__ int req_o[DP_SMALL_N], req_load[DP_SMALL_N];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int Mp = 1 << lg;
+    int kmax = prepare_body(n, s, o, M, feas_mode, proc, by_o, by_cost, buf0, buf1, batch_of, words, num_batches_out, L);
+    if (kmax < 0) return;
+    int r = n, nb = 0;
+    while (r > 0) {
+        if (((kmax + 1) << lg) > DP_SMALL_STATES) {  // excluded by the host's choice of this kernel
+            if (tid == 0) atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+            break;
+        }
+        const int states = (kmax + 1) << lg;
+        for (int i = tid; i < states; i += DP_T) {
+            const int v = i == 0 ? 0 : DP_INF;
+            tab[0][i] = v;
+            tab[1][i] = v;
+        }
+        for (int t = tid; t < r; t += DP_T) {
+            const int id = proc[t];
+            req_o[t] = o[id];
+            req_load[t] = feas_mode ? s[id] : s[id] + o[id];
+        }
+        __syncthreads();
+        const size_t per_t = (size_t)(kmax + 1) << (lg - 6);
+        for (int t = 0; t < r; ++t) {
+            const int oi = req_o[t], load = req_load[t];
+            const int rows = t + 1 < kmax ? t + 1 : kmax;
+            const int cnt = rows << lg;
+            const int *src = tab[t & 1];
+            int *dst = tab[(t + 1) & 1];
+            for (int base = 0; base < cnt; base += DP_T) {
+                const int idx = base + tid;
+                if (idx < cnt) {  // whole wavefronts: cnt is a multiple of 64
+                    const int k = (idx >> lg) + 1, m = idx & (Mp - 1), at = idx + Mp;
+                    const int old = src[at];
+                    int cand = DP_INF;
+                    if (m <= M && m >= load) {
+                        const int prev = src[at - Mp - load];
+                        const bool fits = feas_mode == 0 || (long long)m + (long long)oi * k <= (long long)M;
+                        if (prev != DP_INF && fits) cand = prev + oi;
+                    }
+                    const bool take = cand < old;
+                    dst[at] = take ? cand : old;
+                    const unsigned long long bal = __builtin_amdgcn_ballot_w64(take);
+                    if (lane == 0) bits[(size_t)t * per_t + ((size_t)k << (lg - 6)) + (m >> 6)] = bal;
+                }
+            }
+            __syncthreads();
+        }
+        long long bS;
+        int bk, bm;
+        argmin_body(tab[r & 1], 1, 1, kmax, M, Mp, tie_rule, L, bS, bk, bm);
+        if (tid == 0) publish_batch(bS, bk, n - r, nb, batch_end_out, F_out, words);
+        if (bk < 1) break;  // uniform
+        __threadfence_block();
+        __syncthreads();
+        if (wave == 0) walk_body(bits, proc, r, kmax, Mp, s, o, feas_mode, nb, batch_of, bk, bm);
+        __threadfence_block();
+        __syncthreads();
+        int kept, knext;
+        compact_body(proc, by_cost, buf0, r, nb, batch_of, s, o, feas_mode, M, L, kept, knext);
+        if (kept >= r) break;  // cannot happen: a batch has at least one member; never spin
+        r = kept;
+        kmax = knext;
+        ++nb;
+    }
+    __syncthreads();
+    emit_body(n, by_o, buf0, buf1, batch_of, nb, order_out, num_batches_out, L);
 }
 
 bool launched() { return hipGetLastError() == hipSuccess; }
@@ -343,7 +513,8 @@ size_t kvs_exact_dp_list_bytes(int32_t n)
 size_t kvs_exact_dp_table_bytes(int32_t r, int32_t kmax, int32_t M)
 {
     const size_t Mp = ((size_t)M + DP_STEP_T) & ~(size_t)(DP_STEP_T - 1);
-    return 2 * (size_t)(kmax + 1) * Mp * sizeof(int) + (size_t)r * (size_t)(kmax + 1) * (Mp / 8) + 256;
+    return 2 * (size_t)(kmax + 1) * Mp * sizeof(int) + (size_t)r * (size_t)(kmax + 1) * (Mp / 8) +
+           3 * sizeof(long long) * DP_ARGMIN_BLOCKS + 256;
 }
 
 int kvs_launch_exact_dp_prepare(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
@@ -378,14 +549,49 @@ int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t 
                            proc, t, s, o, M, feas_mode, dp[t & 1], dp[(t + 1) & 1], bits + (size_t)t * per_t, Mp);
         if (!launched()) return KVSCHED_EHIP;
     }
-    hipLaunchKernelGGL(dp_argmin_kernel, dim3(1), dim3(DP_T), 0, st, dp[r & 1], kmax, M, Mp, tie_rule, n - r, nb,
-                       batch_end_out, F_out, d_words);
+    const int G = kmax < DP_ARGMIN_BLOCKS ? kmax : DP_ARGMIN_BLOCKS;
+    long long *partial = (long long *)(bits + (size_t)r * per_t);
+    hipLaunchKernelGGL(dp_argmin_rows_kernel, dim3((unsigned)G), dim3(DP_T), 0, st, dp[r & 1], kmax, M, Mp, tie_rule,
+                       partial);
+    if (!launched()) return KVSCHED_EHIP;
+    hipLaunchKernelGGL(dp_argmin_kernel, dim3(1), dim3(DP_T), 0, st, partial, G, tie_rule, n - r, nb, batch_end_out,
+                       F_out, d_words);
     if (!launched()) return KVSCHED_EHIP;
     hipLaunchKernelGGL(dp_walk_kernel, dim3(1), dim3(64), 0, st, bits, proc, r, kmax, Mp, s, o, feas_mode, nb, batch_of,
                        d_words);
     if (!launched()) return KVSCHED_EHIP;
     hipLaunchKernelGGL(dp_compact_kernel, dim3(1), dim3(DP_T), 0, st, proc, by_cost, buf0, r, nb, batch_of, s, o,
                        feas_mode, M, d_words);
+    return launched() ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+// Can the one-workgroup kernel take this problem?  kmax_bound: any bound on the batch size.
+// Returns log2 of its row length, or 0.
+int kvs_exact_dp_small_lg(int32_t n, int32_t kmax_bound, int32_t M)
+{
+    if (n > DP_SMALL_N) return 0;
+    int lg = 6;
+    while (((int64_t)1 << lg) < (int64_t)M + 1) ++lg;
+    if (lg > 13) return 0;
+    return (((int64_t)kmax_bound + 1) << lg) <= DP_SMALL_STATES ? lg : 0;
+}
+
+size_t kvs_exact_dp_small_record_bytes(int32_t n, int32_t kmax_bound, int lg)
+{
+    return (size_t)n * ((size_t)(kmax_bound + 1) << (lg - 6)) * sizeof(unsigned long long) + 256;
+}
+
+int kvs_launch_exact_dp_small(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
+                              int32_t tie_rule, int lg, void *lists, void *records, int32_t *order_out,
+                              int32_t *batch_end_out, double *F_out, int32_t *num_batches_out, int32_t *d_words,
+                              hipStream_t st)
+{
+    const size_t np = ((size_t)n + 64) & ~(size_t)63;
+    int *proc = (int *)lists, *by_o = proc + np, *by_cost = by_o + np, *buf0 = by_cost + np, *buf1 = buf0 + np,
+        *batch_of = buf1 + np;
+    hipLaunchKernelGGL(dp_small_kernel, dim3(1), dim3(DP_T), 0, st, n, s, o, M, feas_mode, tie_rule, lg, proc, by_o,
+                       by_cost, buf0, buf1, batch_of, (unsigned long long *)records, order_out, batch_end_out, F_out,
+                       num_batches_out, d_words);
     return launched() ? KVSCHED_OK : KVSCHED_EHIP;
 }
 

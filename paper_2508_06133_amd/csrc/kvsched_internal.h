@@ -83,6 +83,12 @@ int kvs_launch_exact_dp_prepare(int32_t n, const int32_t *s, const int32_t *o, i
 int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t *s, const int32_t *o, int32_t M,
                               int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
                               int32_t *batch_end_out, double *F_out, int32_t *d_words, hipStream_t st);
+int kvs_exact_dp_small_lg(int32_t n, int32_t kmax_bound, int32_t M);
+size_t kvs_exact_dp_small_record_bytes(int32_t n, int32_t kmax_bound, int lg);
+int kvs_launch_exact_dp_small(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
+                              int32_t tie_rule, int lg, void *lists, void *records, int32_t *order_out,
+                              int32_t *batch_end_out, double *F_out, int32_t *num_batches_out, int32_t *d_words,
+                              hipStream_t st);
 int kvs_launch_exact_dp_emit(int32_t n, int32_t nb, void *lists, int32_t *order_out, int32_t *num_batches_out,
                              hipStream_t st);
 

@@ -93,6 +93,11 @@ def test_config2_chat_lengths(ctx):
     _check(ctx, inst.s, inst.o, inst.M, "config 2, n=100", ties=(0,))
 
 
+def test_config2_full_size(ctx):
+    inst = workloads.instance(2)
+    _check(ctx, inst.s, inst.o, inst.M, "config 2", ties=(0,))
+
+
 def test_bad_lengths_and_limits(ctx):
     import torch
     from paper_2508_06133_amd import kvsched
