@@ -98,8 +98,8 @@ def simulate_many(s, o, M, orders, literal: bool = False, completions: bool = Tr
     return tel, comp
 
 
-def sortedF(s, o, M, tie_rule: int = 0):
-    """-> (order[n], batch_end[num_batches], F[num_batches])."""
+def sortedF(s, o, M, tie_rule: int = 0, feas_mode: int = 0):
+    """-> (order[n], batch_end[num_batches], F[num_batches]).  feas_mode as exact_phase1."""
     s, o = _i32(s), _i32(o)
     n = len(s)
     order = np.zeros(n, dtype=np.int32)
@@ -107,8 +107,8 @@ def sortedF(s, o, M, tie_rule: int = 0):
     F = np.zeros(max(n, 1), dtype=np.float64)
     nb = ctypes.c_int32(0)
     _check(_load().oracle_sortedF(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
-                                  ctypes.c_int32(tie_rule), _ptr(order, _i32p), _ptr(ends, _i32p), _ptr(F, _f64p),
-                                  ctypes.byref(nb)))
+                                  ctypes.c_int32(tie_rule), ctypes.c_int32(feas_mode), _ptr(order, _i32p),
+                                  _ptr(ends, _i32p), _ptr(F, _f64p), ctypes.byref(nb)))
     return order, ends[: nb.value].copy(), F[: nb.value].copy()
 
 

@@ -208,17 +208,22 @@ static int cmp_F(int64_t Sa, int64_t ka, int64_t Sb, int64_t kb)
  * tie_rule 0: among equal F take the larger batch (the text of Section 4: minimise
  *             (F, -|X|)); tie_rule 1: take the smaller batch (the first minimum met when
  *             scanning k upward, as Algorithm 2's final loop does).
- * Batch feasibility is the sum of peaks, sum (s_i + o_i) <= M, as in Algorithms 2-4.
+ * Batch feasibility: feas_mode 0, the sum of peaks, sum (s_i + o_i) <= M, as in Algorithms 2-4;
+ * feas_mode 1, the constraint of Algorithm 1's Phase 1: with the whole batch started together
+ * the memory at every member's completion time o_j, sum over {i: o_i >= o_j} of (s_i + o_j),
+ * is <= M.  Both are monotone in the prefix length.
  * Outputs: order_out[n]; batch_end_out[b] = number of requests in batches 0..b;
  *          F_out[b] = F of batch b (one IEEE division of exact integers); *nb_out.
  */
 int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
-                   int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *nb_out)
+                   int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                   int32_t *nb_out)
 {
     if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
-    if (tie_rule != 0 && tie_rule != 1) return ORACLE_EINVAL;
+    if ((tie_rule != 0 && tie_rule != 1) || (feas_mode != 0 && feas_mode != 1)) return ORACLE_EINVAL;
     skey_t *rem = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
-    if (!rem) return ORACLE_ENOMEM;
+    int64_t *at_end = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    if (!rem || !at_end) { free(rem); free(at_end); return ORACLE_ENOMEM; }
     for (int32_t i = 0; i < n; ++i) {
         rem[i].w = (int64_t)s[i] + o[i];
         rem[i].o = o[i];
@@ -229,9 +234,25 @@ int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int
     while (a < n) {
         int64_t W = 0, S = 0, bestS = 0, bestk = 0;
         for (int64_t k = 1; a + k <= n; ++k) {
-            W += rem[a + k - 1].w;
-            if (W > M) break;
-            S += rem[a + k - 1].o;
+            const skey_t *e = &rem[a + k - 1];
+            if (feas_mode == 0) {
+                W += e->w;
+                if (W > M) break;
+            } else {
+                /* at_end[j] = memory at the completion time of the j-th member when all start
+                 * together; the newcomer adds s_e + o_j to every time o_j <= o_e, and its own
+                 * completion time sees every member that lasts at least as long */
+                int64_t own = 0, peak = 0;
+                for (int64_t j = 0; j < k - 1; ++j) {
+                    const skey_t *f = &rem[a + j];
+                    if (e->o >= f->o) at_end[j] += (e->w - e->o) + f->o;
+                    if (f->o >= e->o) own += (f->w - f->o) + e->o;
+                }
+                at_end[k - 1] = own + e->w;
+                for (int64_t j = 0; j < k; ++j) if (at_end[j] > peak) peak = at_end[j];
+                if (peak > M) break;
+            }
+            S += e->o;
             int better;
             if (bestk == 0) better = 1;
             else {
@@ -250,6 +271,7 @@ int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int
     }
     if (nb_out) *nb_out = nb;
     free(rem);
+    free(at_end);
     return ORACLE_OK;
 }
 

@@ -383,3 +383,35 @@ def test_receding_horizon_oracle_invariants():
     a = ohorizon.horizon_step(inst.s, inst.o, inst.M, base, moves, 0, 8, literal=True)
     b = ohorizon.horizon_step(inst.s, inst.o, inst.M, base, moves, 0, 8, literal=False)
     assert a[3] == b[3] and (a[0] == b[0]).all() and (a[1] == b[1]).all()
+
+
+def test_sortedF_profile_feasibility_from_definition():
+    # feas_mode 1: every prefix is judged by the simultaneous-start memory profile of Section 4,
+    # recomputed here from its definition; the batch is the least-F prefix among the feasible ones.
+    rng = np.random.default_rng(61)
+    for trial in range(60):
+        n = int(rng.integers(1, 40))
+        s = rng.integers(1, 30, n).astype(np.int32)
+        o = rng.integers(1, 30, n).astype(np.int32)
+        M = int(rng.integers(60, 400))
+        for tie_rule in (0, 1):
+            order, ends, F = oracle.sortedF(s, o, M, tie_rule, 1)
+            remaining = sorted(range(n), key=lambda i: (int(s[i]) + int(o[i]), int(o[i]), i))
+            start = 0
+            for b, end in enumerate(ends):
+                feasible = [k for k in range(1, len(remaining) + 1)
+                            if exact.batch_profile_peak(s, o, remaining[:k]) <= M]
+                assert feasible == list(range(1, len(feasible) + 1))  # monotone in the prefix length
+                Fs = {k: Fraction(sum(int(o[i]) for i in remaining[:k]), k * k) for k in feasible}
+                best = min(Fs.values())
+                ks = [k for k in feasible if Fs[k] == best]
+                k_star = max(ks) if tie_rule == 0 else min(ks)
+                assert end - start == k_star and F[b] == float(best)
+                batch = sorted(remaining[:k_star], key=lambda i: (int(o[i]), i))
+                assert list(order[start:end]) == batch
+                remaining = remaining[k_star:]
+                start = end
+            assert not remaining
+    # the sum of peaks bounds the profile from above: mode 1 never has the smaller feasible extent
+    inst = workloads.instance(3)
+    assert oracle.sortedF(inst.s, inst.o, inst.M, 0, 1)[1][0] >= oracle.sortedF(inst.s, inst.o, inst.M, 0, 0)[1][0]
