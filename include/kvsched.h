@@ -111,11 +111,15 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
 
 /*
  * Phase 1 of Algorithm 1 ("Batch Construction") with the batch chosen among the feasible
- * prefixes of the remaining requests sorted by (s_i + o_i, o_i, i): for prefix length k with
- * sum_{first k}(s_i + o_i) <= M, F(k) = sum_{first k} o_i / k^2 (Section 4); the batch is the
- * prefix of least F (ties per `tie_rule`), emitted in nondecreasing o_i (ties by id); repeat
- * on what remains.  F is compared in exact integers; reported as one IEEE double division.
+ * prefixes of the remaining requests sorted by (s_i + o_i, o_i, i): for every feasible prefix
+ * length k, F(k) = sum_{first k} o_i / k^2 (Section 4); the batch is the prefix of least F (ties
+ * per `tie_rule`), emitted in nondecreasing o_i (ties by id); repeat on what remains.  F is
+ * compared in exact integers; reported as one IEEE double division.
  *
+ *   feas_mode        KVSCHED_FEAS_SUM_OF_PEAKS: prefix k is feasible if sum_{first k}(s_i + o_i) <= M;
+ *                    KVSCHED_FEAS_PROFILE: if, all k started together, the memory at every
+ *                    completion time o_j, sum over {i: o_i >= o_j} of (s_i + o_j), is <= M
+ *                    (the constraint of Algorithm 1's Phase 1).  Both are monotone in k.
  *   order_out        [n] int32: the Sorted-F priority order
  *   batch_end_out    [n] int32: batch_end_out[b] = number of requests in batches 0..b; only
  *                    the first *num_batches_out entries are written
@@ -123,8 +127,8 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
  *   num_batches_out  [1] int32
  */
 int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
-                    int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
-                    int32_t *num_batches_out, void *stream);
+                    int32_t tie_rule, int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out,
+                    double *F_out, int32_t *num_batches_out, void *stream);
 
 /*
  * Phase 1 of Algorithm 1 ("Batch Construction") with every batch chosen by Local Swap Search

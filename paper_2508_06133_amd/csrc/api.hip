@@ -304,19 +304,20 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
 }
 
 int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
-                    int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
-                    void *stream)
+                    int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                    int32_t *num_batches_out, void *stream)
 {
     int rc = check_common(ctx, n, s, o, M);
     if (rc != KVSCHED_OK) return rc;
     if (!order_out || !batch_end_out || !F_out || !num_batches_out) return KVSCHED_EINVAL;
     if (tie_rule != KVSCHED_TIE_LARGER && tie_rule != KVSCHED_TIE_SMALLER) return KVSCHED_EINVAL;
+    if (feas_mode != KVSCHED_FEAS_SUM_OF_PEAKS && feas_mode != KVSCHED_FEAS_PROFILE) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     rc = ensure_scratch(ctx, kvs_sortedF_scratch_bytes(n));
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
-    return kvs_launch_sortedF(n, s, o, (int32_t)M, tie_rule, order_out, batch_end_out, F_out, num_batches_out,
+    return kvs_launch_sortedF(n, s, o, (int32_t)M, tie_rule, feas_mode, order_out, batch_end_out, F_out, num_batches_out,
                               ctx->d_scratch, ctx->d_words, st);
 }
 

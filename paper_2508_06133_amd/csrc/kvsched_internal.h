@@ -100,7 +100,7 @@ int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t
 
 // sortedf.hip
 size_t kvs_sortedF_scratch_bytes(int32_t n);
-int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule,
+int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule, int32_t feas_mode,
                        int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
                        void *scratch, int32_t *d_words, hipStream_t st);
 

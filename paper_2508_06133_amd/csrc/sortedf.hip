@@ -8,8 +8,10 @@
 //   1. stable LSD radix sort of the ids by o            -> requests in (o, id) order
 //   2. continue the same sort on s+o                    -> requests in (s+o, o, id) order
 //   3. prefix sums W (of s+o) and S (of o) over that order
-//   4. per batch: feasible extent K by a two-level search on W, argmin over k <= K of S_k / k^2
-//      compared in exact 128-bit integers, tie rule applied; F reported as one fp64 division
+//   4. per batch: feasible extent K by a two-level search on W (sum of peaks <= M), extended by a
+//      bisection on the simultaneous-start memory profile when that is the feasibility asked for;
+//      argmin over k <= K of S_k / k^2 compared in exact 128-bit integers, tie rule applied;
+//      F reported as one fp64 division
 //   5. stable sort of the (o, id)-ordered ids by batch number -> each batch in nondecreasing o
 #include "phase1_util.h"
 
@@ -53,11 +55,73 @@ __device__ __forceinline__ bool better(long long Sa, int ka, long long Sb, int k
     return tie_rule == KVSCHED_TIE_LARGER ? ka > kb : ka < kb;
 }
 
+// Largest k in [0, rem] with g(k) <= M, for g increasing in k (k = 1..rem): a two-level count of
+// the probes that fit.  Every thread receives it.
+template <class G>
+__device__ int count_fitting(int rem, G g, int32_t M)
+{
+    const int tid = threadIdx.x;
+    const int stride = (rem + TPB - 1) / TPB;
+    const long long k1 = (long long)(tid + 1) * stride;  // coarse probes, a prefix of them fits
+    const bool ok1 = k1 <= rem && g(k1) <= (long long)M;
+    int K = __syncthreads_count(ok1) * stride;
+    const long long k2 = (long long)K + tid + 1;  // fine probes inside the next stride
+    const bool ok2 = tid < stride && k2 <= rem && g(k2) <= (long long)M;
+    K += __syncthreads_count(ok2);
+    return K;
+}
+
+// Do the k requests at places [a, a + k) of the (s+o, o, id) order, started together, stay within
+// M at every completion time?  Memory at time o_j = sum over {i: o_i >= o_j} of (s_i + o_j)
+// (Section 4).  The ids are visited in decreasing o through the (o, id) order; running sums of s
+// and of the count over the members seen so far give the memory at each member's completion (among
+// equal o the last one visited sees the whole group, the earlier ones a part of it, which cannot
+// exceed it).  Every thread receives the answer.
+__device__ bool profile_fits(int n, int a, int k, const int32_t *s, const int32_t *o, const int *by_o,
+                             const int *pos_w, int32_t M, Lds &L)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    long long carry_s = 0;
+    int carry_c = 0, viol = 0;
+    for (int tile = 0; tile < n; tile += TPB) {
+        const int idx = n - 1 - (tile + tid);
+        int id = 0, c = 0;
+        long long sv = 0;
+        if (idx >= 0) {
+            id = by_o[idx];
+            const int p = pos_w[id];
+            if (p >= a && p < a + k) { c = 1; sv = s[id]; }
+        }
+        const int member = c;
+        for (int d = 1; d < 64; d <<= 1) {
+            const long long us = __shfl_up(sv, d);
+            const int uc = __shfl_up(c, d);
+            if (lane >= d) { sv += us; c += uc; }
+        }
+        if (lane == 63) { L.scan_a[wave] = sv; L.scan_b[wave] = c; }
+        __syncthreads();
+        long long off_s = carry_s, tot_s = carry_s;
+        long long off_c = carry_c, tot_c = carry_c;
+        for (int v = 0; v < NWAVES; ++v) {
+            const long long xs = L.scan_a[v], xc = L.scan_b[v];
+            if (v < wave) { off_s += xs; off_c += xc; }
+            tot_s += xs;
+            tot_c += xc;
+        }
+        if (member && (sv + off_s) + (c + off_c) * (long long)o[id] > (long long)M) viol = 1;
+        carry_s = tot_s;
+        carry_c = (int)tot_c;
+        __syncthreads();
+        if (carry_c >= k) break;  // uniform: every member has been seen
+    }
+    return __syncthreads_or(viol) == 0;
+}
+
 __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
-                                                      int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out,
-                                                      double *F_out, int32_t *num_batches_out, int *buf0, int *buf1,
-                                                      int *by_o, long long *cumW, long long *cumS, int *batch_of,
-                                                      int32_t *words)
+                                                      int32_t tie_rule, int32_t feas_mode, int32_t *order_out,
+                                                      int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
+                                                      int *buf0, int *buf1, int *by_o, long long *cumW, long long *cumS,
+                                                      int *batch_of, int *pos_w, int32_t *words)
 {
     __shared__ Lds L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -107,6 +171,9 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         int *t = cur; cur = alt; alt = t;
     }
     const int *sorted = cur;  // (s+o, o, id) ascending
+    if (feas_mode == KVSCHED_FEAS_PROFILE) {
+        for (int i = tid; i < n; i += TPB) pos_w[sorted[i]] = i;
+    }
 
     // ---- 3: inclusive prefix sums over the sorted order; cumW[0] = cumS[0] = 0
     if (tid == 0) {
@@ -144,15 +211,20 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
     while (a < n) {
         const int rem = n - a;
         const long long W0 = cumW[a], S0 = cumS[a];
-        // feasible extent K = max{k : W_k <= M}; W is increasing, so count the feasible probes
-        const int stride = (rem + TPB - 1) / TPB;
-        const long long k1 = (long long)(tid + 1) * stride;  // coarse probes, a prefix of them fits
-        const bool ok1 = k1 <= rem && (cumW[a + k1] - W0 <= (long long)M);
-        int K = __syncthreads_count(ok1) * stride;
-        {
-            const long long k2 = (long long)K + tid + 1;  // fine probes inside the next stride
-            const bool ok2 = tid < stride && k2 <= rem && (cumW[a + k2] - W0 <= (long long)M);
-            K += __syncthreads_count(ok2);
+        // feasible extent K: the longest prefix within the budget (feasibility is monotone in k)
+        int K = count_fitting(rem, [&](long long k) { return cumW[a + k] - W0; }, M);  // sum of peaks <= M
+        if (feas_mode == KVSCHED_FEAS_PROFILE && K >= 1 && K < rem) {
+            // Started together, the prefix must stay within M at every completion time.  The sum of
+            // peaks bounds that memory from above (so K is feasible), and the memory at the earliest
+            // completion is at least sum (s_i + 1) (so nothing beyond hi is); bisect in between.
+            int lo = K;
+            int hi = count_fitting(rem, [&](long long k) { return (cumW[a + k] - W0) - (cumS[a + k] - S0) + k; }, M);
+            while (lo < hi) {
+                const int mid = lo + (hi - lo + 1) / 2;
+                if (profile_fits(n, a, mid, s, o, by_o, pos_w, M, L)) lo = mid;
+                else hi = mid - 1;
+            }
+            K = lo;
         }
         if (K < 1) {  // cannot happen for well-formed input; never spin
             if (tid == 0) atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
@@ -209,10 +281,10 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
 size_t kvs_sortedF_scratch_bytes(int32_t n)
 {
     const size_t np = ((size_t)n + 64) & ~(size_t)63;
-    return np * (4 * sizeof(int) + 2 * sizeof(long long)) + 256;
+    return np * (5 * sizeof(int) + 2 * sizeof(long long)) + 256;
 }
 
-int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule,
+int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule, int32_t feas_mode,
                        int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
                        void *scratch, int32_t *d_words, hipStream_t st)
 {
@@ -223,7 +295,8 @@ int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
     int *buf1 = buf0 + np;
     int *by_o = buf1 + np;
     int *batch_of = by_o + np;
-    hipLaunchKernelGGL(sortedF_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, tie_rule, order_out, batch_end_out,
-                       F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, batch_of, d_words);
+    int *pos_w = batch_of + np;
+    hipLaunchKernelGGL(sortedF_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, tie_rule, feas_mode, order_out,
+                       batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, batch_of, pos_w, d_words);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

@@ -48,7 +48,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_last_timeline_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.kvsched_argmin.argtypes = [vp, vp, i32, vp, vp]
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
-    lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, vp, vp, vp, vp, vp]
+    lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
@@ -144,7 +144,7 @@ class Context:
             raise KvschedError(rc, "kvsched_simulate")
         return tel, comp
 
-    def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER):
+    def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS):
         """-> (order [n] int32, batch_end [n] int32, F [n] float64, num_batches [1] int32); the first
         num_batches entries of batch_end / F are meaningful."""
         n = s.shape[0]
@@ -154,8 +154,8 @@ class Context:
         F = torch.zeros(n, dtype=torch.float64, device=dev)
         nb = torch.zeros(1, dtype=torch.int32, device=dev)
         rc = _lib.kvsched_sortedF(self._h, n, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
-                                  int(tie_rule), order.data_ptr(), ends.data_ptr(), F.data_ptr(), nb.data_ptr(),
-                                  _stream())
+                                  int(tie_rule), int(feas_mode), order.data_ptr(), ends.data_ptr(), F.data_ptr(),
+                                  nb.data_ptr(), _stream())
         if rc != OK:
             raise KvschedError(rc, "kvsched_sortedF")
         return order, ends, F, nb

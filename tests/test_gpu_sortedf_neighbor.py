@@ -25,20 +25,20 @@ def _to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda:0")
 
 
-def _gpu_sortedF(ctx, s, o, M, tie):
+def _gpu_sortedF(ctx, s, o, M, tie, feas_mode=0):
     import torch
 
-    order, ends, F, nb = ctx.sortedF(_to_dev(s), _to_dev(o), M, tie)
+    order, ends, F, nb = ctx.sortedF(_to_dev(s), _to_dev(o), M, tie, feas_mode)
     torch.cuda.synchronize()
     k = int(nb.item())
     return order.cpu().numpy(), ends.cpu().numpy()[:k], F.cpu().numpy()[:k]
 
 
-def _check_sortedF(ctx, s, o, M, what):
+def _check_sortedF(ctx, s, o, M, what, feas_mode=0):
     for tie in (0, 1):
-        print(f"sortedF {what}: n={len(s)} M={M} tie={tie}", flush=True)
-        order_o, ends_o, F_o = oracle.sortedF(s, o, M, tie)
-        order_g, ends_g, F_g = _gpu_sortedF(ctx, s, o, M, tie)
+        print(f"sortedF {what}: n={len(s)} M={M} tie={tie} feas={feas_mode}", flush=True)
+        order_o, ends_o, F_o = oracle.sortedF(s, o, M, tie, feas_mode)
+        order_g, ends_g, F_g = _gpu_sortedF(ctx, s, o, M, tie, feas_mode)
         assert len(ends_g) == len(ends_o) and (ends_g == ends_o).all(), what
         assert (order_g == order_o).all(), what
         assert np.allclose(F_g, F_o, rtol=1e-12, atol=0.0), what  # one IEEE division of exact integers
@@ -49,6 +49,27 @@ def _check_sortedF(ctx, s, o, M, what):
 def test_sortedF_configs(ctx, cfg):
     inst = workloads.instance(cfg)
     _check_sortedF(ctx, inst.s, inst.o, inst.M, f"config {cfg}")
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_sortedF_profile_feasibility_configs(ctx, cfg):
+    inst = workloads.instance(cfg)
+    _check_sortedF(ctx, inst.s, inst.o, inst.M, f"config {cfg}", feas_mode=1)
+
+
+def test_sortedF_profile_feasibility_config5_scaled(ctx):
+    inst = workloads.instance(5, n=6000, M=131072)
+    _check_sortedF(ctx, inst.s, inst.o, inst.M, "config 5 scaled", feas_mode=1)
+
+
+@pytest.mark.parametrize("n,smax,omax,M", [(1, 3, 3, 6), (2, 1, 3, 100), (64, 20, 6, 90), (65, 20, 60, 2000),
+                                           (1023, 50, 40, 3000), (1025, 3, 2, 40), (3000, 400, 400, 9000),
+                                           (2500, 1, 1, 1 << 20), (5000, 2, 200, 640)])
+def test_sortedF_profile_feasibility_random(ctx, n, smax, omax, M):
+    rng = np.random.default_rng(n * 5 + omax)
+    s = rng.integers(1, smax + 1, n).astype(np.int32)
+    o = rng.integers(1, omax + 1, n).astype(np.int32)
+    _check_sortedF(ctx, s, o, M, f"random n={n}", feas_mode=1)
 
 
 @pytest.mark.parametrize("n,smax,omax,M", [(1, 3, 3, 6), (2, 1, 3, 100), (64, 20, 6, 90), (65, 20, 6, 2000),
