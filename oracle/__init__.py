@@ -7,6 +7,8 @@ library and its Python binding never do, and share no code with it.
   kvsched_oracle.c : Phase 2 of Algorithm 1 (literal and array-profile forms), sorted-prefix
                      Phase 1 with the F-metric, Phase 1 with Local Swap Search, Phase 1 with exact
                      batches (Algorithm 2), position moves, best neighbour.
+  online_oracle.c  : scheduling under online arrivals (cached priority list, refresh triggers,
+                     look-ahead window; FCFS / shortest-decode-first / footprint / Sorted-F-Online).
   exact.py         : Algorithm 2 (exact DP), subset / permutation / start-time brute force,
                      lower bound -- tiny instances only.
   check.py         : direct-definition schedule checker (memory per round, greedy-earliest).
@@ -20,16 +22,16 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "kvsched_oracle.c")
+_SRCS = [os.path.join(_HERE, "kvsched_oracle.c"), os.path.join(_HERE, "online_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (a second or so)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", tmp])
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", *_SRCS, "-o", tmp])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -161,3 +163,25 @@ def best_neighbor(s, o, M, base, moves, literal: bool = False):
                                         _ptr(base, _i32p), _ptr(moves, _i32p), ctypes.c_int32(K),
                                         ctypes.c_int32(1 if literal else 0), _ptr(tel, _i64p), _ptr(res, _i64p)))
     return tel, (int(res[0]), int(res[1]), int(res[2]))
+
+
+PLANNER_ARRIVAL, PLANNER_SHORTEST_DECODE, PLANNER_FOOTPRINT, PLANNER_SORTED_F = 0, 1, 2, 3
+
+
+def online(a, s, o, M, planner: int, period: int = 10, window: int = 300, refresh=(1, 2), literal: bool = False):
+    """Scheduling under online arrivals (a[] nondecreasing) -> (p[n], c[n], stats) with
+    stats = (sum of c_i - a_i, refreshes of the cached order, last completion round, largest backlog).
+    refresh = (num, den): early refresh once the waiting newcomers reach num/den of the backlog
+    at the last refresh; den = 0 switches that trigger off."""
+    a, s, o = _i32(a), _i32(s), _i32(o)
+    n = len(s)
+    if len(o) != n or len(a) != n:
+        raise OracleError("length mismatch")
+    p = np.zeros(n, dtype=np.int32)
+    c = np.zeros(n, dtype=np.int32)
+    stats = np.zeros(4, dtype=np.int64)
+    _check(_load().oracle_online(ctypes.c_int32(n), _ptr(a, _i32p), _ptr(s, _i32p), _ptr(o, _i32p),
+                                 ctypes.c_int64(int(M)), ctypes.c_int32(planner), ctypes.c_int32(period),
+                                 ctypes.c_int32(window), ctypes.c_int32(int(refresh[0])), ctypes.c_int32(int(refresh[1])),
+                                 ctypes.c_int32(1 if literal else 0), _ptr(p, _i32p), _ptr(c, _i32p), _ptr(stats, _i64p)))
+    return p, c, tuple(int(x) for x in stats)

@@ -191,3 +191,40 @@ def candidates(cfg: int, base: np.ndarray, count: int | None = None) -> np.ndarr
                 rows[k, i], rows[k, j] = rows[k, j], rows[k, i]
         return rows
     raise ValueError("config 4 draws its candidates per re-planning window; see window_moves()")
+
+
+# ------------------------------------------------------------------- online arrivals
+
+# Normalised loads rho = lambda / lambda* of the paper's Poisson experiment (Section 7,
+# "Experiment under Online Poisson Arrivals": lambda = 0.05 .. 0.30 against lambda* = 0.104).
+ONLINE_RHO = (0.48, 0.67, 0.87, 1.06, 1.25, 1.44, 1.73, 2.02, 2.40, 2.88)
+ONLINE_M = 16492  # the KV budget the paper derives for its serving setup
+ONLINE_T = 4000  # iterations during which requests arrive
+
+
+def _online_lengths(rng: np.random.Generator, n: int, long_frac: float):
+    s, o = _chat_lengths(rng, n)
+    is_long = rng.random(n) < long_frac
+    s_long = rng.integers(2048, 8193, n).astype(np.int32)
+    o_long = rng.integers(100, 501, n).astype(np.int32)
+    return np.where(is_long, s_long, s).astype(np.int32), np.where(is_long, o_long, o).astype(np.int32)
+
+
+def online_lambda_star(M: int = ONLINE_M, long_frac: float = 0.2) -> float:
+    """Arrival rate at which the offered token-rounds equal the budget: M over the mean
+    memory-time area sum_{j=1..o}(s + j) of one request, estimated on a fixed seeded sample."""
+    s, o = _online_lengths(np.random.default_rng(SEED0 + 777), 200_000, long_frac)
+    area = s.astype(np.float64) * o + o.astype(np.float64) * (o + 1) / 2
+    return float(M / area.mean())
+
+
+def online_instance(seed: int, rho: float, T: int = ONLINE_T, M: int = ONLINE_M, long_frac: float = 0.2):
+    """Poisson arrivals of rate rho * lambda* per iteration over T iterations, lengths from the
+    short/long mixture (80/20 by default, as in the paper's online experiment; chat lengths and
+    long-document lengths as in configurations 2 and 3).  -> (a, s, o, M), a nondecreasing int32."""
+    rng = np.random.default_rng(SEED0 + 5000 + seed)
+    lam = rho * online_lambda_star(M, long_frac)
+    counts = rng.poisson(lam, T)
+    a = np.repeat(np.arange(T, dtype=np.int32), counts).astype(np.int32)
+    s, o = _online_lengths(rng, a.shape[0], long_frac)
+    return a, s, o, M
