@@ -8,7 +8,8 @@
  * integer program Optimal-IP in Section 6): rounds are 0,1,2,...; request i has prompt
  * length s_i and decode length o_i; started at round p it holds s_i + j tokens of KV memory
  * at round p + j (j = 1..o_i) and completes at round c_i = p + o_i; the memory held by all
- * running requests may not exceed M at any round.  All n requests are present at round 0.
+ * running requests may not exceed M at any round.  All n requests are present at round 0
+ * (kvsched_online alone takes arrival rounds).
  *
  * Conventions common to all entry points
  *   - Every array argument is a DEVICE pointer owned by the caller (for instance the
@@ -47,6 +48,9 @@ typedef struct kvsched_ctx kvsched_ctx;
 #define KVSCHED_DEV_BAD_ORDER 2  /* an order row is not a permutation of 0..n-1               */
 #define KVSCHED_DEV_BAD_MOVE 4   /* a move has type outside {0,1} or a position outside [0,n) */
 #define KVSCHED_DEV_O_MAX 8      /* a decode length exceeds the bound given to kvsched_set_o_max() */
+#define KVSCHED_DEV_BAD_ARRIVAL 16 /* kvsched_online: an arrival round is negative or out of order   */
+#define KVSCHED_DEV_BACKLOG 32     /* kvsched_online: more than KVSCHED_ONLINE_MAX_BACKLOG requests wait */
+#define KVSCHED_DEV_BAD_STREAM 64  /* kvsched_online: a stream descriptor is malformed or out of range */
 
 #define KVSCHED_MOVE_SWAP 0   /* exchange the entries at positions i and j                  */
 #define KVSCHED_MOVE_INSERT 1 /* take the entry at position i out, put it back at position j */
@@ -60,6 +64,15 @@ typedef struct kvsched_ctx kvsched_ctx;
                                        time (the constraint of Algorithm 1's Phase 1)              */
 
 #define KVSCHED_MAX_O 16384
+
+/* planners of kvsched_online: what a refresh of the cached priority order does with the backlog */
+#define KVSCHED_PLANNER_ARRIVAL 0         /* arrival order (id): FCFS                                   */
+#define KVSCHED_PLANNER_SHORTEST_DECODE 1 /* ascending (o_i, i): shortest decode first, MC-SF           */
+#define KVSCHED_PLANNER_FOOTPRINT 2       /* ascending (s_i + o_i, o_i, i): the paper's fallback order  */
+#define KVSCHED_PLANNER_SORTED_F 3        /* Sorted-F-Online: F-metric batches on a look-ahead window   */
+#define KVSCHED_ONLINE_MAX_BACKLOG 4096   /* most requests of one stream that may wait at once          */
+#define KVSCHED_ONLINE_MAX_WINDOW 1024    /* largest look-ahead window                                  */
+#define KVSCHED_ONLINE_MAX_O 8191         /* longest decode length kvsched_online accepts               */
 #define KVSCHED_EXACT_MAX_N 4096    /* most requests kvsched_exact_dp accepts                      */
 
 /* Create / destroy a context on HIP device `device_id`.  The context owns a few KB of device
@@ -211,6 +224,41 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
                          const int32_t *s, const int32_t *o, int64_t M, int64_t completed_in,
                          int32_t complete_every, int64_t *tel_out, int32_t *completion_out,
                          int64_t *result_out, void *stream);
+
+/*
+ * Scheduling under online arrivals (Section 6, "Heuristics under Online Arrival"; the policies of
+ * Section 7, "Experiment under Online Poisson Arrivals") for B independent request streams at once.
+ * Request i of a stream becomes known at round a_i.  Iteration t = 0, 1, 2, ... of a stream:
+ *   1. requests with a_i <= t join the backlog (arrived, not started) and the END of the cached
+ *      priority list, in arrival order;
+ *   2. if the backlog is not empty and a refresh is due, the planner re-orders the whole backlog
+ *      into a new cached list.  Due: the entries placed by the last refresh are used up (also:
+ *      never planned), or `period` iterations have passed since it, or refresh_den > 0 and
+ *      (entries that arrived since and still wait) * refresh_den >= refresh_num * (backlog size at
+ *      the last refresh) -- the paper uses period 10 and 1/2;
+ *   3. list entries are admitted from the front while the memory check of Eq. (1) holds beside the
+ *      running requests, stopping at the first that does not fit (as kvsched_simulate does).
+ * Planner KVSCHED_PLANNER_SORTED_F sorts the backlog by (s_i + o_i, o_i, i), re-orders the first
+ * min(window, backlog) entries by Phase 1 of Algorithm 1 with Local Swap Search batches over those
+ * entries alone (as kvsched_local_swap, budget M) and leaves the rest behind them in that
+ * fallback order (the paper: window 300).  The other planners sort the backlog by their key.
+ *
+ *   streams         [B][8] int32: {first request, number of requests, planner, period >= 1,
+ *                   window in [0, KVSCHED_ONLINE_MAX_WINDOW], refresh_num >= 0, refresh_den >= 0,
+ *                   first output slot}.  Streams may share requests (same arrivals under several
+ *                   policies); their output ranges must not overlap.
+ *   a, s, o         [N] int32: arrival round (>= 0, nondecreasing within a stream), prompt and
+ *                   decode length (o_i <= KVSCHED_ONLINE_MAX_O, s_i + o_i <= M)
+ *   completion_out  [out_len] int32: completion round c_i of request k of stream b at
+ *                   [first output slot of b + k]
+ *   stats_out       [B][4] int64: {sum of c_i - a_i, refreshes, last completion round, largest
+ *                   backlog}; all -1 for a stream that hit a device-visible fault
+ *                   (KVSCHED_DEV_BAD_LENGTH / _O_MAX / _BAD_ARRIVAL / _BACKLOG / _BAD_STREAM).
+ * ERANGE: a decode length above KVSCHED_ONLINE_MAX_O (from the length scan or kvsched_set_o_max).
+ */
+int kvsched_online(kvsched_ctx *ctx, int32_t B, const int32_t *streams, int32_t N, const int32_t *a,
+                   const int32_t *s, const int32_t *o, int64_t M, int32_t *completion_out, int32_t out_len,
+                   int64_t *stats_out, void *stream);
 
 /*
  * Candidate scoring step for explicit order rows (Section 2, "Objective": the score of a

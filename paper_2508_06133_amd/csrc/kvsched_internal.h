@@ -114,6 +114,11 @@ int kvs_launch_apply_best_move(const int32_t *order, int32_t n, const int32_t *m
 int kvs_launch_horizon_advance(const int32_t *order, const int32_t *completion, const int32_t *o, int32_t n,
                                int64_t completed_in, int32_t complete_every, int64_t *result_out, hipStream_t st);
 
+// online.hip
+int kvs_launch_online(int32_t B, const int32_t *streams, int32_t N, const int32_t *a, const int32_t *s,
+                      const int32_t *o, int32_t M, int32_t ring_slots, int32_t *completion_out, int32_t out_len,
+                      int64_t *stats_out, int32_t *d_words, hipStream_t st);
+
 // prefix.hip
 int kvs_launch_moves_min_position(const int32_t *moves, int32_t K, int32_t n, int32_t *d_words, hipStream_t st);
 int kvs_launch_check_prefix(const int32_t *orders, int32_t C, int32_t n, int32_t cp, int64_t *tel_out,
