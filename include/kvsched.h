@@ -49,7 +49,7 @@ typedef struct kvsched_ctx kvsched_ctx;
 #define KVSCHED_DEV_BAD_MOVE 4   /* a move has type outside {0,1} or a position outside [0,n) */
 #define KVSCHED_DEV_O_MAX 8      /* a decode length exceeds the bound given to kvsched_set_o_max() */
 #define KVSCHED_DEV_BAD_ARRIVAL 16 /* kvsched_online: an arrival round is negative or out of order   */
-#define KVSCHED_DEV_BACKLOG 32     /* kvsched_online: more than KVSCHED_ONLINE_MAX_BACKLOG requests wait */
+#define KVSCHED_DEV_BACKLOG 32     /* kvsched_online: more requests wait than the caller's backlog_cap   */
 #define KVSCHED_DEV_BAD_STREAM 64  /* kvsched_online: a stream descriptor is malformed or out of range */
 
 #define KVSCHED_MOVE_SWAP 0   /* exchange the entries at positions i and j                  */
@@ -70,9 +70,9 @@ typedef struct kvsched_ctx kvsched_ctx;
 #define KVSCHED_PLANNER_SHORTEST_DECODE 1 /* ascending (o_i, i): shortest decode first, MC-SF           */
 #define KVSCHED_PLANNER_FOOTPRINT 2       /* ascending (s_i + o_i, o_i, i): the paper's fallback order  */
 #define KVSCHED_PLANNER_SORTED_F 3        /* Sorted-F-Online: F-metric batches on a look-ahead window   */
-#define KVSCHED_ONLINE_MAX_BACKLOG 4096   /* most requests of one stream that may wait at once          */
+#define KVSCHED_ONLINE_MAX_BACKLOG 4096   /* largest backlog_cap                                        */
 #define KVSCHED_ONLINE_MAX_WINDOW 1024    /* largest look-ahead window                                  */
-#define KVSCHED_ONLINE_MAX_O 8191         /* longest decode length kvsched_online accepts               */
+#define KVSCHED_ONLINE_MAX_O 8192         /* longest decode length kvsched_online accepts               */
 #define KVSCHED_EXACT_MAX_N 4096    /* most requests kvsched_exact_dp accepts                      */
 
 /* Create / destroy a context on HIP device `device_id`.  The context owns a few KB of device
@@ -249,6 +249,11 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
  *                   policies); their output ranges must not overlap.
  *   a, s, o         [N] int32: arrival round (>= 0, nondecreasing within a stream), prompt and
  *                   decode length (o_i <= KVSCHED_ONLINE_MAX_O, s_i + o_i <= M)
+ *   backlog_cap     1..KVSCHED_ONLINE_MAX_BACKLOG: the most requests of one stream that may wait at
+ *                   the same time; a stream that exceeds it is faulted (KVSCHED_DEV_BACKLOG).  The
+ *                   per-stream state lives in LDS and is sized from this bound and the longest
+ *                   decode length (size classes 512 / 1024 / 4096 waiting requests): the smaller
+ *                   the bound, the more streams run side by side.
  *   completion_out  [out_len] int32: completion round c_i of request k of stream b at
  *                   [first output slot of b + k]
  *   stats_out       [B][4] int64: {sum of c_i - a_i, refreshes, last completion round, largest
@@ -257,8 +262,8 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
  * ERANGE: a decode length above KVSCHED_ONLINE_MAX_O (from the length scan or kvsched_set_o_max).
  */
 int kvsched_online(kvsched_ctx *ctx, int32_t B, const int32_t *streams, int32_t N, const int32_t *a,
-                   const int32_t *s, const int32_t *o, int64_t M, int32_t *completion_out, int32_t out_len,
-                   int64_t *stats_out, void *stream);
+                   const int32_t *s, const int32_t *o, int64_t M, int32_t backlog_cap, int32_t *completion_out,
+                   int32_t out_len, int64_t *stats_out, void *stream);
 
 /*
  * Candidate scoring step for explicit order rows (Section 2, "Objective": the score of a

@@ -497,20 +497,22 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
 }
 
 int kvsched_online(kvsched_ctx *ctx, int32_t B, const int32_t *streams, int32_t N, const int32_t *a,
-                   const int32_t *s, const int32_t *o, int64_t M, int32_t *completion_out, int32_t out_len,
-                   int64_t *stats_out, void *stream)
+                   const int32_t *s, const int32_t *o, int64_t M, int32_t backlog_cap, int32_t *completion_out,
+                   int32_t out_len, int64_t *stats_out, void *stream)
 {
     int rc = check_common(ctx, N, s, o, M);
     if (rc != KVSCHED_OK) return rc;
-    if (!streams || !a || !completion_out || !stats_out || B < 1 || out_len < 1) return KVSCHED_EINVAL;
+    if (!streams || !a || !completion_out || !stats_out || B < 1 || out_len < 1 || backlog_cap < 1)
+        return KVSCHED_EINVAL;
+    if (backlog_cap > KVSCHED_ONLINE_MAX_BACKLOG) return KVSCHED_ERANGE;
     hipStream_t st = (hipStream_t)stream;
     int32_t o_bound = 0;
     rc = scan_and_bound(ctx, s, o, N, M, st, &o_bound);
     if (rc != KVSCHED_OK) return rc;
     if (o_bound > KVSCHED_ONLINE_MAX_O) return KVSCHED_ERANGE;
-    int32_t H = 64;  // ring of the running requests' future memory: more slots than the longest decode
-    while (H <= o_bound) H <<= 1;
-    return kvs_launch_online(B, streams, N, a, s, o, (int32_t)M, H, completion_out, out_len, stats_out,
+    int32_t H = 64;  // ring of the running requests' future memory: a slot per round of the longest decode
+    while (H < o_bound) H <<= 1;
+    return kvs_launch_online(B, streams, N, a, s, o, (int32_t)M, backlog_cap, H, completion_out, out_len, stats_out,
                              ctx->d_words, st);
 }
 

@@ -1,6 +1,6 @@
 // Scheduling under online arrivals (Section 6, "Heuristics under Online Arrival"; Section 7,
-// "Experiment under Online Poisson Arrivals"): many independent request streams at once, one
-// workgroup of 256 threads per stream, the whole policy on the device.
+// "Experiment under Online Poisson Arrivals"): many independent request streams at once, ONE
+// 64-lane WAVEFRONT PER STREAM, the whole policy on the device.
 //
 // Per stream, iteration t = 0, 1, 2, ...:
 //   1. requests with a_i <= t join the backlog and the end of the cached priority list;
@@ -8,20 +8,27 @@
 //   3. list entries are admitted from the front while Eq. (1) holds beside the running requests,
 //      stopping at the first that does not fit.
 //
+// A stream is a chain of small dependent steps (a refresh of the paper's setting is some
+// twenty batches and a hundred exchanges on fifty requests), so nothing is gained by putting
+// more lanes on one stream; the chip is filled by running thousands of streams side by side.
+// One wavefront per stream needs no workgroup barrier anywhere: every decision is a ballot or a
+// wave reduction, and the LDS a stream needs (24 KB in the smallest size class) lets six
+// streams share a compute unit.
+//
 // State of a stream, all in LDS:
 //   * the backlog as an array of 64-bit keys sorted in the planner's order; a key packs
 //     (s+o, o, id) so that sorting, the fallback order and the lengths needed at admission all
 //     come from the one word.  Arrivals are merged in (rank among the newcomers + binary search
-//     in the backlog), admitted requests are struck out by a compaction; the two copies of the
-//     array alternate;
+//     in the backlog), admitted requests are struck out by a compaction; two copies alternate;
 //   * the cached list: a circular buffer of the same keys;
 //   * the running requests' future memory P(tau) for the next H rounds in a ring of H slots
-//     (H = power of two > longest decode length); an admission attempt checks its o rounds with
-//     all threads and one barrier;
-//   * the look-ahead window of the Sorted-F-Online planner lives in whichever backlog copy is
-//     idle: Phase 1 of Algorithm 1 with Local Swap Search batches on at most 1024 requests,
-//     4 sorted places per thread (greedy fill = longest prefix by a block scan; an exchange step
-//     = exclusive prefix minimum of o over non-members + one binary search per member).
+//     (H = power of two >= longest decode length; the slot of round t is cleared at iteration t
+//     before anything is admitted, so it can stand for round t + H); an attempt checks its o rounds 64 at
+//     a time and ends in one ballot;
+//   * the look-ahead window of the Sorted-F-Online planner: Phase 1 of Algorithm 1 with Local
+//     Swap Search batches, sorted place 64 r + lane in row r of the lane's registers (greedy fill
+//     = longest prefix by a saturating wave scan; an exchange step = exclusive prefix minimum of
+//     o over non-members, one binary search per member of the first rows, two ballots).
 #include "kvsched_internal.h"
 
 #include <limits.h>
@@ -30,26 +37,18 @@ namespace {
 
 typedef unsigned long long u64;
 
-constexpr int OT = 256;       // threads per stream
-constexpr int ONW = OT / 64;  // wavefronts per stream
-constexpr int OMAXQ = KVSCHED_ONLINE_MAX_BACKLOG;
 constexpr int OMAXW = KVSCHED_ONLINE_MAX_WINDOW;
-constexpr int OMAXH = KVSCHED_ONLINE_MAX_O + 1;
 constexpr int OMAXCOUNT = 1 << 20;  // ids are 20-bit fields of the keys
-static_assert((OMAXQ & (OMAXQ - 1)) == 0 && (OMAXH & (OMAXH - 1)) == 0, "ring sizes are powers of two");
-static_assert(7 * OMAXW + 8 <= 2 * OMAXQ, "the planner's scratch must fit in one backlog copy");
 
-struct OnlineLds {
-    u64 qa[OMAXQ];
-    u64 qb[OMAXQ];
-    u64 list[OMAXQ];
-    int ring[OMAXH];
-    u64 newk[OT];   // keys of the arrivals being merged, in arrival order
-    u64 newks[OT];  // the same keys sorted
-    unsigned dead[OMAXQ / 32];
-    long long part64[ONW];
-    int part[ONW];
-    int flag[3];
+template <int QCAP, int HCAP>
+struct StreamLds {
+    static constexpr int WCAP = QCAP < OMAXW ? QCAP : OMAXW;
+    u64 qa[QCAP];
+    u64 qb[QCAP];
+    u64 list[QCAP];
+    u64 wk[WCAP];  // the planner's window, compacted after every batch
+    int ring[HCAP];
+    unsigned dead[QCAP / 32];
 };
 
 // (s+o, o, id) <-> key.  Fields: s+o < 2^30, o < 2^14, id < 2^20.
@@ -79,98 +78,111 @@ struct Codec {
     }
 };
 
-// ---------------------------------------------------------------- block-wide primitives
-// Every thread of the workgroup calls them; each ends with a barrier so that the partial
-// arrays can be used again at once.
+// ------------------------------------------------------------------ wavefront primitives
+// All 64 lanes are active wherever these are called (control flow is uniform per stream).
 
-__device__ __forceinline__ int block_sum(int v, OnlineLds &L)
+__device__ __forceinline__ void wave_sync()
+{
+    // LDS traffic of one wavefront is served in order; this keeps the compiler from moving
+    // accesses across a point where lanes read what other lanes wrote
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+
+__device__ __forceinline__ u64 lanes_below()
+{
+    return (1ull << lane_id()) - 1ull;
+}
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ u64 uni64(u64 v)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+    return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 lane_u64(u64 v, int lane)  // lane is uniform
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), lane);
+    return ((u64)hi << 32) | lo;
+}
+
+// DPP moves: lanes whose source lies outside the pattern (or whose row is masked off) get `idle`.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp(int idle, int v)
+{
+    return __builtin_amdgcn_update_dpp(idle, v, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
+constexpr int DPP_BCAST15 = 0x142, DPP_BCAST31 = 0x143;  // last lane of a row -> the next row(s)
+
+// After these four steps every lane of a 16-lane row holds the row's total.
+#define KVS_ROW_BUTTERFLY(v, OP)                      \
+    v = OP(v, dpp<DPP_QUAD_1032>(v, v));              \
+    v = OP(v, dpp<DPP_QUAD_2301>(v, v));              \
+    v = OP(v, dpp<DPP_HALF_MIRROR>(v, v));            \
+    v = OP(v, dpp<DPP_MIRROR>(v, v));
+
+__device__ __forceinline__ int op_add(int a, int b) { return a + b; }
+__device__ __forceinline__ int op_min(int a, int b) { return min(a, b); }
+
+__device__ __forceinline__ int wave_sum(int v)
+{
+    KVS_ROW_BUTTERFLY(v, op_add)
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+
+__device__ __forceinline__ long long wave_sum64(long long v)
 {
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-    if ((threadIdx.x & 63) == 0) L.part[threadIdx.x >> 6] = v;
-    __syncthreads();
-    int tot = 0;
-    for (int u = 0; u < ONW; ++u) tot += L.part[u];
-    __syncthreads();
-    return tot;
+    return (long long)uni64((u64)v);
 }
 
-__device__ __forceinline__ int block_min(int v, OnlineLds &L)
+__device__ __forceinline__ int wave_min(int v)
 {
-    for (int d = 32; d >= 1; d >>= 1) v = min(v, __shfl_xor(v, d));
-    if ((threadIdx.x & 63) == 0) L.part[threadIdx.x >> 6] = v;
-    __syncthreads();
-    int r = INT_MAX;
-    for (int u = 0; u < ONW; ++u) r = min(r, L.part[u]);
-    __syncthreads();
-    return r;
+    KVS_ROW_BUTTERFLY(v, op_min)
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
-__device__ __forceinline__ int block_or(int v, OnlineLds &L)
+// Inclusive prefix scans over the 64 lanes: within rows by shifts of 1, 2, 4, 8, then the last
+// lane of row 0 / 2 into rows 1 / 3 and the last lane of row 1 into rows 2 and 3.
+
+// sums of non-negative values, saturating at cap (cap <= 2^30)
+__device__ __forceinline__ unsigned wave_incl_add_sat(unsigned v, unsigned cap)
 {
-    for (int d = 32; d >= 1; d >>= 1) v |= __shfl_xor(v, d);
-    if ((threadIdx.x & 63) == 0) L.part[threadIdx.x >> 6] = v;
-    __syncthreads();
-    int r = 0;
-    for (int u = 0; u < ONW; ++u) r |= L.part[u];
-    __syncthreads();
-    return r;
+    v = min(v + (unsigned)dpp<DPP_ROW_SHR1>(0, (int)v), cap);
+    v = min(v + (unsigned)dpp<DPP_ROW_SHR2>(0, (int)v), cap);
+    v = min(v + (unsigned)dpp<DPP_ROW_SHR4>(0, (int)v), cap);
+    v = min(v + (unsigned)dpp<DPP_ROW_SHR8>(0, (int)v), cap);
+    v = min(v + (unsigned)dpp<DPP_BCAST15, 0xa>(0, (int)v), cap);
+    v = min(v + (unsigned)dpp<DPP_BCAST31, 0xc>(0, (int)v), cap);
+    return v;
 }
 
-// exclusive prefix sum over the threads; *total = sum over all
-__device__ __forceinline__ int block_excl_add(int v, int *total, OnlineLds &L)
+// exclusive prefix minimum (INT_MAX for lane 0)
+__device__ __forceinline__ int wave_excl_min(int v)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-    for (int d = 1; d < 64; d <<= 1) {
-        const int u = __shfl_up(inc, d);
-        if (lane >= d) inc += u;
-    }
-    if (lane == 63) L.part[wave] = inc;
-    __syncthreads();
-    int off = 0, tot = 0;
-    for (int u = 0; u < ONW; ++u) {
-        const int x = L.part[u];
-        if (u < wave) off += x;
-        tot += x;
-    }
-    __syncthreads();
-    *total = tot;
-    return off + inc - v;
+    v = min(v, dpp<DPP_ROW_SHR1>(INT_MAX, v));
+    v = min(v, dpp<DPP_ROW_SHR2>(INT_MAX, v));
+    v = min(v, dpp<DPP_ROW_SHR4>(INT_MAX, v));
+    v = min(v, dpp<DPP_ROW_SHR8>(INT_MAX, v));
+    v = min(v, dpp<DPP_BCAST15, 0xa>(INT_MAX, v));
+    v = min(v, dpp<DPP_BCAST31, 0xc>(INT_MAX, v));
+    // one lane down: inside a row by a shift, across a row boundary from the row below's last lane
+    const int within = dpp<DPP_ROW_SHR1>(INT_MAX, v);
+    const int across = dpp<DPP_BCAST15, 0xe>(INT_MAX, v);
+    return (lane_id() & 15) ? within : across;
 }
 
-__device__ __forceinline__ long long block_excl_add64(long long v, OnlineLds &L)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    long long inc = v;
-    for (int d = 1; d < 64; d <<= 1) {
-        const long long u = __shfl_up(inc, d);
-        if (lane >= d) inc += u;
-    }
-    if (lane == 63) L.part64[wave] = inc;
-    __syncthreads();
-    long long off = 0;
-    for (int u = 0; u < wave; ++u) off += L.part64[u];
-    __syncthreads();
-    return off + inc - v;
-}
-
-// exclusive prefix minimum over the threads (INT_MAX for thread 0)
-__device__ __forceinline__ int block_excl_min(int v, OnlineLds &L)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-    for (int d = 1; d < 64; d <<= 1) {
-        const int u = __shfl_up(inc, d);
-        if (lane >= d) inc = min(inc, u);
-    }
-    if (lane == 63) L.part[wave] = inc;
-    int ex = __shfl_up(inc, 1);
-    if (lane == 0) ex = INT_MAX;
-    __syncthreads();
-    for (int u = 0; u < wave; ++u) ex = min(ex, L.part[u]);
-    __syncthreads();
-    return ex;
-}
+__device__ __forceinline__ int first_lane(u64 ballot) { return __ffsll((long long)ballot) - 1; }
 
 // number of entries of the ascending array a[0..n) that are < key
 __device__ __forceinline__ int lower_bound_u64(const u64 *a, int n, u64 key)
@@ -184,13 +196,13 @@ __device__ __forceinline__ int lower_bound_u64(const u64 *a, int n, u64 key)
     return lo;
 }
 
-// first index of the ascending array a[0..n) whose entry is > lim
-__device__ __forceinline__ int upper_bound_i32(const int *a, int n, int lim)
+// first index of wk[0..n) (keys ascending in s+o) whose s+o exceeds lim
+__device__ __forceinline__ int upper_bound_size(const u64 *wk, int n, int lim)
 {
     int lo = 0, hi = n;
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
-        if (a[mid] <= lim) lo = mid + 1;
+        if ((int)(wk[mid] >> 34) <= lim) lo = mid + 1;
         else hi = mid;
     }
     return lo;
@@ -203,141 +215,146 @@ __device__ __forceinline__ int upper_bound_i32(const int *a, int n, int lim)
 // order, then the first improving exchange (members and non-members scanned in the sorted
 // order; |X| is fixed, so F falls exactly when o_in < o_out) until none is left; the batch is
 // emitted by (o, id) and removed.  Writes the wn keys to list[0..wn) in priority order.
-// `wsc` is 7 * OMAXW + 8 ints of scratch.
-__device__ void plan_window(const u64 *src, int wn, int M, int *wsc, u64 *list, OnlineLds &L)
+// wk: WCAP keys of working storage; tmp: an idle array of >= max(wn + 1 ints, wn keys).
+template <int WCAP>
+__device__ void plan_window(const u64 *src, int wn, int M, u64 *wk, u64 *tmp, u64 *list)
 {
-    const int tid = threadIdx.x;
-    int *ww = wsc, *wo = wsc + OMAXW, *wid = wsc + 2 * OMAXW;
-    int *aw = wsc + 3 * OMAXW, *ao = wsc + 4 * OMAXW, *aid = wsc + 5 * OMAXW;
-    int *pm = wsc + 6 * OMAXW;  // OMAXW + 1 entries
-    u64 *bkey = (u64 *)aw;      // the batch's keys; aw and ao are idle while it is in use
+    constexpr int RMAX = WCAP / 64;
     constexpr u64 LOW34 = (1ull << 34) - 1;  // (o, id) of a key
+    const int lane = lane_id();
+    int *pm = (int *)tmp;  // pm[j] = least o among non-members at places < j, j = 0..m
+    u64 *bkey = tmp;       // the batch's keys (after the exchanges, pm is no longer needed)
 
-    for (int i = tid; i < wn; i += OT) {
-        const u64 k = src[i];
-        ww[i] = (int)(k >> 34);
-        wo[i] = (int)((k >> 20) & 0x3fffu);
-        wid[i] = (int)(k & 0xfffffu);
-    }
-    __syncthreads();
+    for (int i = lane; i < wn; i += 64) wk[i] = src[i];
+    wave_sync();
 
     int m = wn, outpos = 0;
-    const int base = 4 * tid;  // this thread's four sorted places
     while (m > 0) {
-        int w4[4], o4[4];
-        bool v4[4], mem4[4];
-        long long loc = 0;
+        const int R = (m + 63) >> 6;
+        // this lane's places 64 r + lane
+        int wreg[RMAX], oreg[RMAX];
+        unsigned valid = 0, mem = 0;  // bit r: place exists / is in the batch
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            v4[e] = base + e < m;
-            w4[e] = v4[e] ? ww[base + e] : 0;
-            o4[e] = v4[e] ? wo[base + e] : INT_MAX;
-            loc += w4[e];
+        for (int r = 0; r < RMAX; ++r) {
+            wreg[r] = 0;
+            oreg[r] = INT_MAX;
+            if (r < R && 64 * r + lane < m) {
+                const u64 k = wk[64 * r + lane];
+                wreg[r] = (int)(k >> 34);
+                oreg[r] = (int)((k >> 20) & 0x3fffu);
+                valid |= 1u << r;
+            }
         }
         // greedy fill: sizes ascend, so "add while it fits" is the longest prefix within M
-        long long run = block_excl_add64(loc, L);
-        int cnt = 0, wsum = 0;
+        const unsigned cap = (unsigned)M + 1u;
+        unsigned carry = 0;
+        int K = 0, memsum = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            run += w4[e];
-            mem4[e] = v4[e] && run <= (long long)M;
-            if (mem4[e]) { ++cnt; wsum += w4[e]; }
+        for (int r = 0; r < RMAX; ++r) {
+            if (r < R) {
+                const unsigned incl = min(wave_incl_add_sat((unsigned)wreg[r], cap) + carry, cap);
+                const bool in = ((valid >> r) & 1u) && incl <= (unsigned)M;
+                if (in) mem |= 1u << r;
+                const u64 bal = __builtin_amdgcn_ballot_w64(in);
+                K += __popcll(bal);
+                memsum += wave_sum(in ? wreg[r] : 0);
+                carry = (unsigned)__builtin_amdgcn_readlane((int)incl, 63);
+            }
         }
-        const int K = block_sum(cnt, L);
-        int memsum = block_sum(wsum, L);
 
         for (;;) {  // one exchange per turn; every exchange lowers the batch's sum of o
             const int slack = M - memsum;
-            int ex4[4], lm = INT_MAX;
+            int run = INT_MAX;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ex4[e] = lm;
-                if (v4[e] && !mem4[e]) lm = min(lm, o4[e]);
-            }
-            const int pre = block_excl_min(lm, L);
-            const int all = block_min(lm, L);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (v4[e]) pm[base + e] = min(pre, ex4[e]);  // least o among non-members before this place
-            if (tid == 0) pm[m] = all;
-            __syncthreads();
-            // a member has a partner iff some non-member that still fits has a smaller o; those
-            // that fit are the places before the first size above w + slack
-            int cand = INT_MAX;
-#pragma unroll
-            for (int e = 3; e >= 0; --e) {
-                if (mem4[e]) {
-                    const int ub = upper_bound_i32(ww, m, w4[e] + slack);
-                    if (pm[ub] < o4[e]) cand = base + e;
+            for (int r = 0; r < RMAX; ++r) {
+                if (r < R) {
+                    const bool out = ((valid >> r) & 1u) && !((mem >> r) & 1u);
+                    const int v = out ? oreg[r] : INT_MAX;
+                    pm[64 * r + lane] = min(wave_excl_min(v), run);
+                    run = min(run, wave_min(v));
                 }
             }
-            const int astar = block_min(cand, L);
-            if (astar == INT_MAX) break;
-            const int oa = wo[astar];
-            int cb = INT_MAX;
+            if (lane == 0) pm[m] = run;
+            wave_sync();
+            // a member has a partner iff some non-member that still fits has a smaller o; those
+            // that fit are the places before the first size above w + slack
+            int astar = -1;
 #pragma unroll
-            for (int e = 3; e >= 0; --e)
-                if (v4[e] && !mem4[e] && o4[e] < oa) cb = base + e;
-            const int bstar = block_min(cb, L);
-            if (bstar == INT_MAX) break;  // cannot happen: pm[] promised a partner before the bound
-            memsum += ww[bstar] - ww[astar];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (base + e == astar) mem4[e] = false;
-                if (base + e == bstar) mem4[e] = true;
+            for (int r = 0; r < RMAX; ++r) {
+                if (r < R && astar < 0) {
+                    const bool is_mem = (mem >> r) & 1u;
+                    if (__builtin_amdgcn_ballot_w64(is_mem) != 0) {
+                        bool has = false;
+                        if (is_mem) {
+                            const int ub = upper_bound_size(wk, m, wreg[r] + slack);
+                            has = pm[ub] < oreg[r];
+                        }
+                        const u64 bal = __builtin_amdgcn_ballot_w64(has);
+                        if (bal != 0) astar = 64 * r + first_lane(bal);
+                    }
+                }
             }
+            wave_sync();
+            if (astar < 0) break;
+            const u64 ka = uni64(wk[astar]);
+            const int oa = (int)((ka >> 20) & 0x3fffu);
+            int bstar = -1;
+#pragma unroll
+            for (int r = 0; r < RMAX; ++r) {
+                if (r < R && bstar < 0) {
+                    const bool ok = ((valid >> r) & 1u) && !((mem >> r) & 1u) && oreg[r] < oa;
+                    const u64 bal = __builtin_amdgcn_ballot_w64(ok);
+                    if (bal != 0) bstar = 64 * r + first_lane(bal);
+                }
+            }
+            if (bstar < 0) break;  // cannot happen: pm[] promised a partner before the bound
+            const u64 kb = uni64(wk[bstar]);
+            memsum += (int)(kb >> 34) - (int)(ka >> 34);
+            if (lane == (astar & 63)) mem &= ~(1u << (astar >> 6));
+            if (lane == (bstar & 63)) mem |= 1u << (bstar >> 6);
         }
 
         // the batch in nondecreasing o, ties by id: rank of each member among the members
-        int cntm = 0;
+        int nmem = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) cntm += mem4[e] ? 1 : 0;
-        int tot = 0;
-        int offm = block_excl_add(cntm, &tot, L);
-        u64 mine[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            mine[e] = 0;
-            if (mem4[e]) {
-                mine[e] = ((u64)w4[e] << 34) | ((u64)o4[e] << 20) | (u64)wid[base + e];
-                bkey[offm++] = mine[e];
+        for (int r = 0; r < RMAX; ++r) {
+            if (r < R) {
+                const bool is_mem = (mem >> r) & 1u;
+                const u64 bal = __builtin_amdgcn_ballot_w64(is_mem);
+                if (is_mem) bkey[nmem + __popcll(bal & lanes_below())] = wk[64 * r + lane];
+                nmem += __popcll(bal);
             }
         }
-        __syncthreads();
+        wave_sync();
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (mem4[e]) {
-                const u64 me = mine[e] & LOW34;
-                int r = 0;
-                for (int j = 0; j < K; ++j) r += ((bkey[j] & LOW34) < me) ? 1 : 0;
-                list[outpos + r] = mine[e];
+        for (int r = 0; r < RMAX; ++r) {
+            if (r < R) {
+                const bool is_mem = (mem >> r) & 1u;
+                if (__builtin_amdgcn_ballot_w64(is_mem) != 0) {
+                    const u64 mine = wk[64 * r + lane];
+                    const u64 me = mine & LOW34;
+                    int rank = 0;
+                    for (int j = 0; j < K; ++j) rank += ((bkey[j] & LOW34) < me) ? 1 : 0;
+                    if (is_mem) list[outpos + rank] = mine;
+                }
             }
         }
-        __syncthreads();
-        // what remains closes up, still sorted
-        int cntn = 0, idk[4];
+        wave_sync();
+        // what remains closes up in place, still sorted: row by row, each row read before it is
+        // written, and never written beyond itself
+        int kept = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            idk[e] = v4[e] ? wid[base + e] : 0;
-            cntn += (v4[e] && !mem4[e]) ? 1 : 0;
-        }
-        int offn = block_excl_add(cntn, &tot, L);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (v4[e] && !mem4[e]) {
-                aw[offn] = w4[e];
-                ao[offn] = o4[e];
-                aid[offn] = idk[e];
-                ++offn;
+        for (int r = 0; r < RMAX; ++r) {
+            if (r < R) {
+                const bool keep = ((valid >> r) & 1u) && !((mem >> r) & 1u);
+                const u64 k = ((valid >> r) & 1u) ? wk[64 * r + lane] : 0;
+                const u64 bal = __builtin_amdgcn_ballot_w64(keep);
+                wave_sync();
+                if (keep) wk[kept + __popcll(bal & lanes_below())] = k;
+                kept += __popcll(bal);
+                wave_sync();
             }
         }
-        __syncthreads();
-        for (int i = tid; i < m - K; i += OT) {
-            ww[i] = aw[i];
-            wo[i] = ao[i];
-            wid[i] = aid[i];
-        }
-        __syncthreads();
         outpos += K;
         m -= K;
     }
@@ -351,35 +368,39 @@ struct OnlineParams {
     int32_t N;
     const int32_t *a, *s, *o;
     int32_t M;
-    int32_t H;  // ring slots: power of two > longest decode length
+    int32_t H;    // ring slots: power of two >= longest decode length
+    int32_t cap;  // the caller's bound on the backlog of a stream
     int32_t out_len;
     int32_t *completion_out;
     int64_t *stats_out;  // [B][4]
     int32_t *d_words;
 };
 
-__global__ __launch_bounds__(OT) void online_kernel(OnlineParams p)
+template <int QCAP, int HCAP>
+__global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
 {
-    __shared__ OnlineLds L;
-    const int tid = threadIdx.x;
+    typedef StreamLds<QCAP, HCAP> Lds;
+    __shared__ Lds L;
+    constexpr int QM = QCAP - 1;
+    const int lane = lane_id();
     const int b = blockIdx.x;
     const int32_t *d = p.streams + 8 * (size_t)b;
-    const int begin = d[0], count = d[1], planner = d[2], period = d[3], window = d[4];
-    const int rnum = d[5], rden = d[6], outb = d[7];
+    const int begin = uni(d[0]), count = uni(d[1]), planner = uni(d[2]), period = uni(d[3]), window = uni(d[4]);
+    const int rnum = uni(d[5]), rden = uni(d[6]), outb = uni(d[7]);
     int64_t *stats = p.stats_out + 4 * (size_t)b;
     const bool bad_desc = begin < 0 || count < 0 || count > OMAXCOUNT || (long long)begin + count > p.N ||
                           planner < 0 || planner > KVSCHED_PLANNER_SORTED_F || period < 1 || window < 0 ||
                           window > OMAXW || rnum < 0 || rden < 0 || outb < 0 ||
                           (long long)outb + count > p.out_len;
     if (bad_desc) {
-        if (tid == 0) {
+        if (lane == 0) {
             atomicOr(&p.d_words[KVS_W_STATUS], KVSCHED_DEV_BAD_STREAM);
             stats[0] = stats[1] = stats[2] = stats[3] = -1;
         }
         return;
     }
     if (count == 0) {
-        if (tid == 0) stats[0] = stats[1] = stats[2] = stats[3] = 0;
+        if (lane == 0) stats[0] = stats[1] = stats[2] = stats[3] = 0;
         return;
     }
     const int H = p.H, HM = H - 1, M = p.M;
@@ -387,23 +408,21 @@ __global__ __launch_bounds__(OT) void online_kernel(OnlineParams p)
     int32_t *cout = p.completion_out + outb;
     Codec codec{planner};
 
-    for (int i = tid; i < H; i += OT) L.ring[i] = 0;
-    for (int i = tid; i < OMAXQ / 32; i += OT) L.dead[i] = 0;
-    if (tid < 3) L.flag[tid] = 0;
-    __syncthreads();
+    for (int i = lane; i < H; i += 64) L.ring[i] = 0;
+    for (int i = lane; i < QCAP / 32; i += 64) L.dead[i] = 0;
+    wave_sync();
 
     u64 *cur = L.qa, *oth = L.qb;
     int t = 0;
-    int q = 0;                 // backlog size = entries of the cached list
-    int head = 0;              // list entries are list[(head + i) & (OMAXQ - 1)], i < q
-    int planned_left = 0;      // leading list entries that were placed by the last refresh
+    int q = 0;             // backlog size = entries of the cached list
+    int head = 0;          // list entries are list[(head + i) & QM], i < q
+    int planned_left = 0;  // leading list entries that were placed by the last refresh
     int known = 0, started = 0;
     int t_plan = 0, backlog_at_plan = 0;
-    long long refreshes = 0, sum_c = 0, sum_a = 0;  // sum_a: this thread's share
+    long long refreshes = 0, sum_c = 0, sum_a = 0;  // sum_a: this lane's share
     int last_c = 0, max_backlog = 0;
-    int next_a = a[0];
+    int next_a = uni(a[0]);
     int fault = 0;
-    unsigned attempt = 0;
     // No admission for H iterations in a row with a backlog is impossible (every running request
     // has left by then and a single request always fits), idle stretches are skipped in one step:
     // the budget below is never reached by well-formed input and bounds the loop otherwise.
@@ -413,13 +432,13 @@ __global__ __launch_bounds__(OT) void online_kernel(OnlineParams p)
         if (--budget < 0) { fault = KVSCHED_DEV_BAD_STREAM; break; }
         if (q == 0 && next_a > t) {  // nothing waits: jump to the next arrival, retiring the rounds passed
             const int span = min(next_a - t, H);
-            for (int i = tid; i < span; i += OT) L.ring[(t + i) & HM] = 0;
+            for (int i = lane; i < span; i += 64) L.ring[(t + i) & HM] = 0;
             t = next_a;
-            __syncthreads();
+            wave_sync();
         }
-        // ---- 1. arrivals, up to 256 at a time
+        // ---- 1. arrivals, up to 64 at a time
         while (known < count && next_a <= t) {
-            const int idx = known + tid;
+            const int idx = known + lane;
             const int aj = idx < count ? a[idx] : INT_MAX;
             const bool in = aj <= t;
             int sj = 1, oj = 1, bad = 0;
@@ -427,36 +446,36 @@ __global__ __launch_bounds__(OT) void online_kernel(OnlineParams p)
                 sj = s[idx];
                 oj = o[idx];
                 if (sj < 1 || oj < 1 || (long long)sj + oj > (long long)M) bad |= KVSCHED_DEV_BAD_LENGTH;
-                if (oj >= H) bad |= KVSCHED_DEV_O_MAX;
+                if (oj > H) bad |= KVSCHED_DEV_O_MAX;
                 if (aj < 0 || (idx > 0 && a[idx - 1] > aj)) bad |= KVSCHED_DEV_BAD_ARRIVAL;
             }
-            const int kc = block_sum(in ? 1 : 0, L);
-            fault = block_or(bad, L);
-            if (q + kc > OMAXQ) fault |= KVSCHED_DEV_BACKLOG;
+            const int kc = __popcll(__builtin_amdgcn_ballot_w64(in));
+            for (int dlt = 32; dlt >= 1; dlt >>= 1) bad |= __shfl_xor(bad, dlt);
+            fault = uni(bad);
+            if (q + kc > p.cap) fault |= KVSCHED_DEV_BACKLOG;
             if (fault) break;
-            // merge: a newcomer lands at (entries of the backlog before it) + (newcomers before it)
+            // merge: a newcomer lands at (entries of the backlog before it) + (newcomers before it);
+            // an entry of the backlog moves up by the newcomers before it
             const u64 key = in ? codec.make(sj + oj, oj, idx) : ~0ull;
-            L.newk[tid] = key;
-            __syncthreads();
+            int rank = 0;
+            for (int i = 0; i < kc; ++i) rank += (lane_u64(key, i) < key) ? 1 : 0;
             if (in) {
-                int rank = 0;
-                for (int i = 0; i < kc; ++i) rank += (L.newk[i] < key) ? 1 : 0;
-                const int lb = lower_bound_u64(cur, q, key);
-                oth[lb + rank] = key;
-                L.newks[rank] = key;
-                L.list[(head + q + tid) & (OMAXQ - 1)] = key;  // arrival order
+                oth[lower_bound_u64(cur, q, key) + rank] = key;
+                L.list[(head + q + lane) & QM] = key;  // arrival order
                 sum_a += aj;
             }
-            __syncthreads();
-            for (int i = tid; i < q; i += OT) {
-                const u64 k = cur[i];
-                oth[i + lower_bound_u64(L.newks, kc, k)] = k;
+            for (int i0 = 0; i0 < q; i0 += 64) {
+                const int i = i0 + lane;
+                const u64 k = i < q ? cur[i] : 0;
+                int nb = 0;
+                for (int j = 0; j < kc; ++j) nb += (lane_u64(key, j) < k) ? 1 : 0;
+                if (i < q) oth[i + nb] = k;
             }
-            __syncthreads();
+            wave_sync();
             u64 *sw = cur; cur = oth; oth = sw;
             q += kc;
             known += kc;
-            next_a = known < count ? a[known] : INT_MAX;
+            next_a = known < count ? uni(a[known]) : INT_MAX;
         }
         if (fault) break;
         max_backlog = max(max_backlog, q);
@@ -470,81 +489,72 @@ __global__ __launch_bounds__(OT) void online_kernel(OnlineParams p)
                 int wn = 0;
                 if (planner == KVSCHED_PLANNER_SORTED_F && window > 0) {
                     wn = min(window, q);
-                    plan_window(cur, wn, M, (int *)oth, L.list, L);
+                    plan_window<Lds::WCAP>(cur, wn, M, L.wk, oth, L.list);
                 }
-                for (int i = wn + tid; i < q; i += OT) L.list[i] = cur[i];
+                for (int i = wn + lane; i < q; i += 64) L.list[i] = cur[i];
                 head = 0;
                 planned_left = q;
                 t_plan = t;
                 backlog_at_plan = q;
                 ++refreshes;
-                __syncthreads();
+                wave_sync();
             }
         }
 
         // ---- 3. admission of the longest feasible prefix of the list
-        if (tid == 0) L.ring[t & HM] = 0;  // round t is behind every check from now on
+        if (lane == 0) L.ring[t & HM] = 0;  // round t is behind every check from now on
+        wave_sync();
         int adm = 0;
         while (adm < q) {
-            const u64 key = L.list[(head + adm) & (OMAXQ - 1)];
+            const u64 key = uni64(L.list[(head + adm) & QM]);
             int w, oo, id;
             codec.split(key, w, oo, id);
             const int sr = w - oo;
-            const unsigned slot = attempt % 3u;
-            if (tid == 0) L.flag[(attempt + 1u) % 3u] = 0;
             bool viol = false;
-            for (int j = tid + 1; j <= oo; j += OT) viol |= L.ring[(t + j) & HM] + sr + j > M;
-            if (viol) L.flag[slot] = 1;
-            __syncthreads();
-            ++attempt;
-            if (L.flag[slot]) break;
-            for (int j = tid + 1; j <= oo; j += OT) L.ring[(t + j) & HM] += sr + j;
-            if (tid == 0) cout[id] = t + oo;
+            for (int j = lane + 1; j <= oo; j += 64) viol |= L.ring[(t + j) & HM] + sr + j > M;
+            if (__builtin_amdgcn_ballot_w64(viol) != 0) break;
+            for (int j = lane + 1; j <= oo; j += 64) L.ring[(t + j) & HM] += sr + j;
+            if (lane == 0) cout[id] = t + oo;
             sum_c += t + oo;
             last_c = max(last_c, t + oo);
             ++adm;
         }
         // ---- the admitted requests leave the backlog
         if (adm > 0) {
+            wave_sync();
             if (adm < q) {
-                for (int j = tid; j < adm; j += OT) {
-                    const int pos = lower_bound_u64(cur, q, L.list[(head + j) & (OMAXQ - 1)]);
+                for (int j = lane; j < adm; j += 64) {
+                    const int pos = lower_bound_u64(cur, q, L.list[(head + j) & QM]);
                     atomicOr(&L.dead[pos >> 5], 1u << (pos & 31));
                 }
-                __syncthreads();
-                const int per = (q + OT - 1) / OT;
-                const int lo = min(q, tid * per), hi = min(q, lo + per);
-                int alive = 0;
-                for (int i = lo; i < hi; ++i) alive += ((L.dead[i >> 5] >> (i & 31)) & 1u) ? 0 : 1;
-                int tot = 0;
-                int off = block_excl_add(alive, &tot, L);
-                for (int i = lo; i < hi; ++i)
-                    if (!((L.dead[i >> 5] >> (i & 31)) & 1u)) oth[off++] = cur[i];
-                __syncthreads();
-                for (int i = tid; i < (q + 31) / 32; i += OT) L.dead[i] = 0;
+                wave_sync();
+                int kept = 0;
+                for (int i0 = 0; i0 < q; i0 += 64) {
+                    const int i = i0 + lane;
+                    const bool alive = i < q && !((L.dead[i >> 5] >> (i & 31)) & 1u);
+                    const u64 bal = __builtin_amdgcn_ballot_w64(alive);
+                    if (alive) oth[kept + __popcll(bal & lanes_below())] = cur[i];
+                    kept += __popcll(bal);
+                }
+                wave_sync();
+                for (int i = lane; i < (q + 31) / 32; i += 64) L.dead[i] = 0;
                 u64 *sw = cur; cur = oth; oth = sw;
+                wave_sync();
             }
-            head = (head + adm) & (OMAXQ - 1);
+            head = (head + adm) & QM;
             q -= adm;
             started += adm;
             planned_left = max(planned_left - adm, 0);
-            __syncthreads();
         }
         ++t;
     }
 
-    // sum of a_i over the stream: every thread holds a share
-    for (int dlt = 32; dlt >= 1; dlt >>= 1) sum_a += __shfl_xor(sum_a, dlt);
-    __syncthreads();
-    if ((tid & 63) == 0) L.part64[tid >> 6] = sum_a;
-    __syncthreads();
-    if (tid == 0) {
+    const long long sa = wave_sum64(sum_a);
+    if (lane == 0) {
         if (fault) {
             atomicOr(&p.d_words[KVS_W_STATUS], fault);
             stats[0] = stats[1] = stats[2] = stats[3] = -1;
         } else {
-            long long sa = 0;
-            for (int u = 0; u < ONW; ++u) sa += L.part64[u];
             stats[0] = sum_c - sa;
             stats[1] = refreshes;
             stats[2] = last_c;
@@ -553,13 +563,22 @@ __global__ __launch_bounds__(OT) void online_kernel(OnlineParams p)
     }
 }
 
+template <int QCAP, int HCAP>
+int launch_online(const OnlineParams &p, hipStream_t st)
+{
+    hipLaunchKernelGGL((online_kernel<QCAP, HCAP>), dim3((unsigned)p.B), dim3(64), 0, st, p);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
 }  // namespace
 
+// Size classes (backlog capacity, ring slots) and the LDS a stream takes in each: 24 KB, 48 KB,
+// 136 KB; the smallest that holds the caller's backlog bound and the longest decode is used.
 int kvs_launch_online(int32_t B, const int32_t *streams, int32_t N, const int32_t *a, const int32_t *s,
-                      const int32_t *o, int32_t M, int32_t ring_slots, int32_t *completion_out, int32_t out_len,
-                      int64_t *stats_out, int32_t *d_words, hipStream_t st)
+                      const int32_t *o, int32_t M, int32_t backlog_cap, int32_t ring_slots, int32_t *completion_out,
+                      int32_t out_len, int64_t *stats_out, int32_t *d_words, hipStream_t st)
 {
-    if (ring_slots < 2 || ring_slots > OMAXH || (ring_slots & (ring_slots - 1))) return KVSCHED_ERANGE;
+    if (ring_slots < 2 || (ring_slots & (ring_slots - 1)) || backlog_cap < 1) return KVSCHED_ERANGE;
     OnlineParams p;
     p.B = B;
     p.streams = streams;
@@ -569,10 +588,14 @@ int kvs_launch_online(int32_t B, const int32_t *streams, int32_t N, const int32_
     p.o = o;
     p.M = M;
     p.H = ring_slots;
+    p.cap = backlog_cap;
     p.out_len = out_len;
     p.completion_out = completion_out;
     p.stats_out = stats_out;
     p.d_words = d_words;
-    hipLaunchKernelGGL(online_kernel, dim3((unsigned)B), dim3(OT), 0, st, p);
-    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+    if (backlog_cap <= 512 && ring_slots <= 2048) return launch_online<512, 2048>(p, st);
+    if (backlog_cap <= 1024 && ring_slots <= 4096) return launch_online<1024, 4096>(p, st);
+    if (backlog_cap <= KVSCHED_ONLINE_MAX_BACKLOG && ring_slots <= KVSCHED_ONLINE_MAX_O)
+        return launch_online<KVSCHED_ONLINE_MAX_BACKLOG, KVSCHED_ONLINE_MAX_O>(p, st);
+    return KVSCHED_ERANGE;
 }

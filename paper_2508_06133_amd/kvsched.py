@@ -20,7 +20,7 @@ MOVE_SWAP, MOVE_INSERT = 0, 1
 DEV_BAD_LENGTH, DEV_BAD_ORDER, DEV_BAD_MOVE, DEV_O_MAX = 1, 2, 4, 8
 DEV_BAD_ARRIVAL, DEV_BACKLOG, DEV_BAD_STREAM = 16, 32, 64
 PLANNER_ARRIVAL, PLANNER_SHORTEST_DECODE, PLANNER_FOOTPRINT, PLANNER_SORTED_F = 0, 1, 2, 3
-ONLINE_MAX_BACKLOG, ONLINE_MAX_WINDOW, ONLINE_MAX_O = 4096, 1024, 8191
+ONLINE_MAX_BACKLOG, ONLINE_MAX_WINDOW, ONLINE_MAX_O = 4096, 1024, 8192
 FEAS_SUM_OF_PEAKS, FEAS_PROFILE = 0, 1
 EXACT_MAX_N = 4096
 
@@ -56,7 +56,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
     lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
-    lib.kvsched_online.argtypes = [vp, i32, vp, i32, vp, vp, vp, i64, vp, i32, vp, vp]
+    lib.kvsched_online.argtypes = [vp, i32, vp, i32, vp, vp, vp, i64, i32, vp, i32, vp, vp]
     return lib
 
 
@@ -231,17 +231,19 @@ class Context:
             raise KvschedError(rc, "kvsched_horizon_step")
         return tel, res
 
-    def online(self, streams, a, s, o, M, completion_out, stats_out=None):
+    def online(self, streams, a, s, o, M, completion_out, stats_out=None, backlog_cap: int = ONLINE_MAX_BACKLOG):
         """streams [B, 8] int32 descriptors {first request, count, planner, period, window,
         refresh_num, refresh_den, first output slot}; a, s, o [N] int32; completion_out [out_len]
-        int32 is the tensor the descriptors' output slots refer to.
+        int32 is the tensor the descriptors' output slots refer to; backlog_cap bounds the requests
+        of one stream that may wait at once (smaller bounds let more streams run side by side).
         -> (completion_out, stats [B, 4] int64 = {sum of c_i - a_i, refreshes, last completion
         round, largest backlog})."""
         B = streams.shape[0]
         stats = torch.empty((B, 4), dtype=torch.int64, device=a.device) if stats_out is None else stats_out
         rc = _lib.kvsched_online(self._h, B, _dev(streams, torch.int32, "streams"), a.shape[0],
                                  _dev(a, torch.int32, "a"), _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"),
-                                 int(M), _dev(completion_out, torch.int32, "completion_out"), completion_out.shape[0],
+                                 int(M), int(backlog_cap), _dev(completion_out, torch.int32, "completion_out"),
+                                 completion_out.shape[0],
                                  _dev(stats, torch.int64, "stats_out"), _stream())
         if rc != OK:
             raise KvschedError(rc, "kvsched_online")

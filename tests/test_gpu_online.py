@@ -54,18 +54,19 @@ class Batch:
         self.cases.append((begin, count, planner, period, window, refresh, self.out))
         self.out += count
 
-    def run(self, ctx, M, what):
+    def run(self, ctx, M, what, cap=4096):
         import torch
 
         a, s, o = np.concatenate(self.a), np.concatenate(self.s), np.concatenate(self.o)
         print(f"online {what}: {len(self.desc)} streams, {self.N} requests, M={M}", flush=True)
         comp = torch.full((max(self.out, 1),), -7, dtype=torch.int32, device="cuda:0")
-        comp, stats = ctx.online(_to_dev(np.array(self.desc)), _to_dev(a), _to_dev(s), _to_dev(o), M, comp)
+        comp, stats = ctx.online(_to_dev(np.array(self.desc)), _to_dev(a), _to_dev(s), _to_dev(o), M, comp,
+                                 backlog_cap=cap)
         torch.cuda.synchronize()
         return a, s, o, comp.cpu().numpy(), stats.cpu().numpy()
 
-    def check(self, ctx, M, what):
-        a, s, o, comp, stats = self.run(ctx, M, what)
+    def check(self, ctx, M, what, cap=4096):
+        a, s, o, comp, stats = self.run(ctx, M, what, cap)
         for k, (begin, count, planner, period, window, refresh, out) in enumerate(self.cases):
             sl = slice(begin, begin + count)
             p_o, c_o, st_o = oracle.online(a[sl], s[sl], o[sl], M, planner, period, window, refresh)
@@ -97,7 +98,7 @@ def test_poisson_grid_three_policies(ctx):
             b.add_stream(r, FCFS, 1, 0, (0, 0))
             b.add_stream(r, MCSF, 1, 0, (0, 0))
             b.add_stream(r, SORTF, 10, 300, (1, 2))
-    b.check(ctx, workloads.ONLINE_M, "Poisson grid")
+    b.check(ctx, workloads.ONLINE_M, "Poisson grid", cap=512)
 
 
 def test_policy_parameter_sweep(ctx):
@@ -112,7 +113,7 @@ def test_policy_parameter_sweep(ctx):
     for planner in (FCFS, MCSF, FOOT):
         for period in (1, 7, 100):
             b.add_stream(r, planner, period, 0, (1, 2))
-    b.check(ctx, M, "parameter sweep")
+    b.check(ctx, M, "parameter sweep", cap=1024)
 
 
 def test_random_small_streams(ctx):
@@ -130,7 +131,7 @@ def test_random_small_streams(ctx):
             r = b.add_requests(a, s, o)
             b.add_stream(r, int(rng.integers(0, 4)), int(rng.integers(1, 9)), int(rng.integers(0, 20)),
                          (int(rng.integers(0, 4)), int(rng.integers(0, 4))))
-        b.check(ctx, M, f"random small streams, M={M}")
+        b.check(ctx, M, f"random small streams, M={M}", cap=(64, 600, 4096)[M_mode])
 
 
 def test_bursts_deep_backlog_and_full_window(ctx):
@@ -152,16 +153,23 @@ def test_bursts_deep_backlog_and_full_window(ctx):
 
 
 def test_longest_decode_and_idle_gaps(ctx):
-    # decode lengths up to the limit (ring of 8192 rounds), arrivals separated by gaps longer than
-    # the ring, and a request that exactly fills the budget
+    # decode lengths up to the limit (a ring slot per round of the longest decode, the slot of the
+    # current round standing for the round one ring ahead), arrivals separated by gaps longer than the
+    # ring, and a request that exactly fills the budget
     b = Batch()
     a = [0, 0, 3, 20000, 20000, 20001, 60000]
     s = [5, 1, 9, 1, 808, 2, 7]
-    o = [8191, 8000, 1, 8191, 8191, 4000, 3]
+    o = [8192, 8000, 1, 8192, 8191, 4000, 3]
     r = b.add_requests(a, s, o)
     for planner, period, window in ((FCFS, 1, 0), (MCSF, 1, 0), (FOOT, 4, 0), (SORTF, 10, 300), (SORTF, 1, 2)):
         b.add_stream(r, planner, period, window, (1, 2))
     b.check(ctx, 8999, "longest decode")
+    # the same at a power-of-two limit of the smallest size class
+    b = Batch()
+    r = b.add_requests([0, 0, 1, 5000], [3, 1, 2, 1], [2048, 2048, 2047, 2048])
+    for planner in (FCFS, MCSF, SORTF):
+        b.add_stream(r, planner, 3, 4, (1, 2))
+    b.check(ctx, 4100, "decode length = ring size", cap=16)
 
 
 def test_all_present_at_round_zero_equals_offline(ctx):
@@ -182,6 +190,29 @@ def test_all_present_at_round_zero_equals_offline(ctx):
     tel_g, comp_g = ctx.simulate(order_g[None, :].contiguous(), _to_dev(inst.s), _to_dev(inst.o), inst.M)
     torch.cuda.synchronize()
     assert int(tel_g.item()) == tel0 and (comp_g.cpu().numpy()[0] == comp).all()
+
+
+def test_size_classes_agree_and_the_bound_is_enforced(ctx):
+    # the same streams under every backlog bound that holds them: identical results; under a bound
+    # below the largest backlog the stream is faulted, whatever size class the bound falls in
+    a, s, o, M = workloads.online_instance(3, 2.4)
+    b = Batch()
+    r = b.add_requests(a, s, o)
+    b.add_stream(r, FCFS, 1, 0, (0, 0))
+    b.add_stream(r, SORTF, 10, 300, (1, 2))
+    ref = None
+    for cap in (4096, 1024, 512, 400):
+        _, _, _, comp, stats = b.run(ctx, M, f"size class for bound {cap}", cap)
+        if ref is None:
+            ref = (comp.copy(), stats.copy())
+            worst = int(stats[0, 3])
+            assert 100 < worst <= 400 and int(stats[1, 3]) < worst
+        assert (comp == ref[0]).all() and (stats == ref[1]).all(), cap
+        assert ctx.device_status() == 0
+    _, _, _, comp, stats = b.run(ctx, M, "bound below the backlog", worst - 1)
+    assert list(stats[0]) == [-1, -1, -1, -1] and (stats[1] == ref[1][1]).all()
+    _, _, _, comp, stats = b.run(ctx, M, "bound at the backlog", worst)
+    assert (stats == ref[1]).all()
 
 
 def test_faults_are_reported_per_stream(ctx):
@@ -224,4 +255,8 @@ def test_faults_are_reported_per_stream(ctx):
         comp = torch.zeros(2, dtype=torch.int32, device="cuda:0")
         ctx.online(_to_dev(np.array([[0, 2, 0, 1, 0, 0, 0, 0]])), _to_dev([0, 0]), _to_dev([1, 1]),
                    _to_dev([5, kvsched.ONLINE_MAX_O + 1]), 1 << 20, comp)
+    assert e.value.code == -2
+    with pytest.raises(kvsched.KvschedError) as e:
+        ctx.online(_to_dev(np.array([[0, 2, 0, 1, 0, 0, 0, 0]])), _to_dev([0, 0]), _to_dev([1, 1]), _to_dev([5, 5]),
+                   1 << 20, comp, backlog_cap=kvsched.ONLINE_MAX_BACKLOG + 1)
     assert e.value.code == -2
