@@ -52,6 +52,91 @@ def measured_traffic():
     return TRAFFIC_BYTES if h.hexdigest()[:16] == TRAFFIC_SOURCES_SHA256 else None
 
 
+def bench_online(args, ctx, dev) -> int:
+    """One step = every stream of the Poisson grid run to completion: 10 load levels x
+    `online_seeds` arrival sequences x 3 policies (arrival order, shortest decode first every
+    iteration, Sorted-F-Online with refresh 10 / window 300 / growth trigger 1/2)."""
+    import torch
+
+    from paper_2508_06133_amd import kvsched, workloads
+
+    A, S, O, desc = [], [], [], []
+    N = out = 0
+    policies = ((kvsched.PLANNER_ARRIVAL, 1, 0, 0, 0), (kvsched.PLANNER_SHORTEST_DECODE, 1, 0, 0, 0),
+                (kvsched.PLANNER_SORTED_F, 10, 300, 1, 2))
+    for rho in workloads.ONLINE_RHO:
+        for seed in range(args.online_seeds):
+            a, s, o, M = workloads.online_instance(seed, rho)
+            A.append(a), S.append(s), O.append(o)
+            for pl, per, win, num, den in policies:
+                desc.append([N, len(a), pl, per, win, num, den, out])
+                out += len(a)
+            N += len(a)
+    a, s, o = np.concatenate(A), np.concatenate(S), np.concatenate(O)
+    a_d, s_d, o_d = (torch.from_numpy(x).to(dev) for x in (a, s, o))
+    desc_d = torch.tensor(desc, dtype=torch.int32, device=dev)
+    comp = torch.zeros(out, dtype=torch.int32, device=dev)
+    stats = torch.zeros((len(desc), 4), dtype=torch.int64, device=dev)
+    ctx.set_o_max(2048)  # the generator clips decode lengths there; makes the call asynchronous
+    cap = 512
+
+    def step():
+        ctx.online(desc_d, a_d, s_d, o_d, M, comp, stats_out=stats, backlog_cap=cap)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if ctx.device_status() != 0:
+        print("bench.py: device status", ctx.device_status(), file=sys.stderr)
+        return 1
+    st = stats.cpu().numpy()
+    B = len(desc)
+    iterations = int(st[:, 2].sum())  # rounds up to the last completion, summed over streams
+    result = {
+        "metric": "online request streams evaluated/s (Poisson arrivals, 3 policies)",
+        "value": B * args.steps / wall,
+        "unit": "streams/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": f"online Poisson arrivals: {len(workloads.ONLINE_RHO)} loads x {args.online_seeds} "
+                               f"sequences x 3 policies, T={workloads.ONLINE_T}, M={M}",
+                   "streams": B, "requests": int(N), "backlog_cap": cap},
+        "requests_per_s": out * args.steps / wall,
+        "rounds_per_s": iterations * args.steps / wall,
+        "roofline": None,  # a stream is a chain of dependent steps: latency-bound, no throughput roofline applies
+    }
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure; only this baseline leg uses it
+
+        pick = list(range(0, B, max(1, B // 150)))
+        t0 = time.perf_counter()
+        for k in pick:
+            b0, cnt, pl, per, win, num, den, _ = desc[k]
+            _, _, so = oracle.online(a[b0:b0 + cnt], s[b0:b0 + cnt], o[b0:b0 + cnt], M, pl, per, win, (num, den))
+            if so != tuple(int(x) for x in st[k]):
+                print("bench.py: GPU and oracle disagree on stream", k, file=sys.stderr)
+                return 1
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": len(pick) / cpu_s, "unit": "streams/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"every {max(1, B // 150)}th of the {B} streams (oracle_online, "
+                                            f"array-profile form), single thread, {cpu_s:.1f} s"}
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +146,11 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=8192, help="candidate rows the CPU oracle is timed on")
     ap.add_argument("--phase1", choices=("sorted_prefix", "local_swap"), default="sorted_prefix",
                     help="Phase-1 solver run inside the step (the candidate set is always built around the sorted-prefix order)")
+    ap.add_argument("--workload", choices=("config3", "online"), default="config3",
+                    help="config3: the headline workload; online: the paper's Poisson-arrival experiment "
+                         "(Section 7) as a batch of independent streams through kvsched_online")
+    ap.add_argument("--online-seeds", type=int, default=200,
+                    help="arrival sequences per load level of the online workload (10 loads x 3 policies each)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the yardstick for FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
@@ -79,6 +169,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ctx = kvsched.Context(0)
+    if args.workload == "online":
+        return bench_online(args, ctx, dev)
 
     inst = workloads.instance(CFG)
     n, M = inst.n, inst.M

@@ -51,31 +51,23 @@ struct StreamLds {
     unsigned dead[QCAP / 32];
 };
 
-// (s+o, o, id) <-> key.  Fields: s+o < 2^30, o < 2^14, id < 2^20.
+// (s+o, o, id) <-> key.  Fields: s+o < 2^30 (30 bits), o <= 2^13 (14 bits), id < 2^20; the planner's
+// sort order decides which field is most significant.
 struct Codec {
-    int planner;
+    int w_shift, o_shift, id_shift;
+    __device__ explicit Codec(int planner)
+    {
+        if (planner == KVSCHED_PLANNER_ARRIVAL) { id_shift = 44; w_shift = 14; o_shift = 0; }        // (id)
+        else if (planner == KVSCHED_PLANNER_SHORTEST_DECODE) { o_shift = 50; id_shift = 30; w_shift = 0; }  // (o, id)
+        else { w_shift = 34; o_shift = 20; id_shift = 0; }                                           // (s+o, o, id)
+    }
     __device__ __forceinline__ u64 make(int w, int o, int id) const
     {
-        if (planner == KVSCHED_PLANNER_ARRIVAL) return ((u64)id << 44) | ((u64)w << 14) | (u64)o;
-        if (planner == KVSCHED_PLANNER_SHORTEST_DECODE) return ((u64)o << 50) | ((u64)id << 30) | (u64)w;
-        return ((u64)w << 34) | ((u64)o << 20) | (u64)id;
+        return ((u64)w << w_shift) | ((u64)o << o_shift) | ((u64)id << id_shift);
     }
-    __device__ __forceinline__ void split(u64 k, int &w, int &o, int &id) const
-    {
-        if (planner == KVSCHED_PLANNER_ARRIVAL) {
-            id = (int)(k >> 44);
-            w = (int)((k >> 14) & 0x3fffffffu);
-            o = (int)(k & 0x3fffu);
-        } else if (planner == KVSCHED_PLANNER_SHORTEST_DECODE) {
-            o = (int)(k >> 50);
-            id = (int)((k >> 30) & 0xfffffu);
-            w = (int)(k & 0x3fffffffu);
-        } else {
-            w = (int)(k >> 34);
-            o = (int)((k >> 20) & 0x3fffu);
-            id = (int)(k & 0xfffffu);
-        }
-    }
+    __device__ __forceinline__ int size(u64 k) const { return (int)((k >> w_shift) & 0x3fffffffu); }
+    __device__ __forceinline__ int decode(u64 k) const { return (int)((k >> o_shift) & 0x3fffu); }
+    __device__ __forceinline__ int id(u64 k) const { return (int)((k >> id_shift) & 0xfffffu); }
 };
 
 // ------------------------------------------------------------------ wavefront primitives
@@ -262,54 +254,89 @@ __device__ void plan_window(const u64 *src, int wn, int M, u64 *wk, u64 *tmp, u6
             }
         }
 
+        // Small batches in a window of at most two rows (the paper's online setting: a few requests
+        // per batch, some tens waiting) are searched as the pseudo-code scans: members in sorted
+        // order, each against all non-members at once from the registers.  Otherwise every member
+        // is tested at once through the prefix minimum of o over the non-members.
+        const bool by_member = R <= 2 && K <= 32;
         for (;;) {  // one exchange per turn; every exchange lowers the batch's sum of o
             const int slack = M - memsum;
-            int run = INT_MAX;
+            int astar = -1, bstar = -1, wa = 0, wb = 0;
+            if (by_member) {
 #pragma unroll
-            for (int r = 0; r < RMAX; ++r) {
-                if (r < R) {
-                    const bool out = ((valid >> r) & 1u) && !((mem >> r) & 1u);
-                    const int v = out ? oreg[r] : INT_MAX;
-                    pm[64 * r + lane] = min(wave_excl_min(v), run);
-                    run = min(run, wave_min(v));
-                }
-            }
-            if (lane == 0) pm[m] = run;
-            wave_sync();
-            // a member has a partner iff some non-member that still fits has a smaller o; those
-            // that fit are the places before the first size above w + slack
-            int astar = -1;
+                for (int ra = 0; ra < 2; ++ra) {
+                    if (ra < R && astar < 0) {
+                        u64 todo = __builtin_amdgcn_ballot_w64((mem >> ra) & 1u);
+                        while (todo != 0 && astar < 0) {
+                            const int la = first_lane(todo);
+                            todo &= todo - 1;
+                            const int w_out = __builtin_amdgcn_readlane(wreg[ra], la);
+                            const int o_out = __builtin_amdgcn_readlane(oreg[ra], la);
 #pragma unroll
-            for (int r = 0; r < RMAX; ++r) {
-                if (r < R && astar < 0) {
-                    const bool is_mem = (mem >> r) & 1u;
-                    if (__builtin_amdgcn_ballot_w64(is_mem) != 0) {
-                        bool has = false;
-                        if (is_mem) {
-                            const int ub = upper_bound_size(wk, m, wreg[r] + slack);
-                            has = pm[ub] < oreg[r];
+                            for (int rb = 0; rb < 2; ++rb) {
+                                if (rb < R && astar < 0) {
+                                    const bool ok = ((valid >> rb) & 1u) && !((mem >> rb) & 1u) &&
+                                                    wreg[rb] <= w_out + slack && oreg[rb] < o_out;
+                                    const u64 bal = __builtin_amdgcn_ballot_w64(ok);
+                                    if (bal != 0) {
+                                        astar = 64 * ra + la;
+                                        bstar = 64 * rb + first_lane(bal);
+                                        wa = w_out;
+                                        wb = __builtin_amdgcn_readlane(wreg[rb], first_lane(bal));
+                                    }
+                                }
+                            }
                         }
-                        const u64 bal = __builtin_amdgcn_ballot_w64(has);
-                        if (bal != 0) astar = 64 * r + first_lane(bal);
                     }
                 }
-            }
-            wave_sync();
-            if (astar < 0) break;
-            const u64 ka = uni64(wk[astar]);
-            const int oa = (int)((ka >> 20) & 0x3fffu);
-            int bstar = -1;
+                if (astar < 0) break;
+            } else {
+                int run = INT_MAX;
 #pragma unroll
-            for (int r = 0; r < RMAX; ++r) {
-                if (r < R && bstar < 0) {
-                    const bool ok = ((valid >> r) & 1u) && !((mem >> r) & 1u) && oreg[r] < oa;
-                    const u64 bal = __builtin_amdgcn_ballot_w64(ok);
-                    if (bal != 0) bstar = 64 * r + first_lane(bal);
+                for (int r = 0; r < RMAX; ++r) {
+                    if (r < R) {
+                        const bool out = ((valid >> r) & 1u) && !((mem >> r) & 1u);
+                        const int v = out ? oreg[r] : INT_MAX;
+                        pm[64 * r + lane] = min(wave_excl_min(v), run);
+                        run = min(run, wave_min(v));
+                    }
                 }
+                if (lane == 0) pm[m] = run;
+                wave_sync();
+                // a member has a partner iff some non-member that still fits has a smaller o; those
+                // that fit are the places before the first size above w + slack
+#pragma unroll
+                for (int r = 0; r < RMAX; ++r) {
+                    if (r < R && astar < 0) {
+                        const bool is_mem = (mem >> r) & 1u;
+                        if (__builtin_amdgcn_ballot_w64(is_mem) != 0) {
+                            bool has = false;
+                            if (is_mem) {
+                                const int ub = upper_bound_size(wk, m, wreg[r] + slack);
+                                has = pm[ub] < oreg[r];
+                            }
+                            const u64 bal = __builtin_amdgcn_ballot_w64(has);
+                            if (bal != 0) astar = 64 * r + first_lane(bal);
+                        }
+                    }
+                }
+                wave_sync();
+                if (astar < 0) break;
+                const u64 ka = uni64(wk[astar]);
+                const int oa = (int)((ka >> 20) & 0x3fffu);
+#pragma unroll
+                for (int r = 0; r < RMAX; ++r) {
+                    if (r < R && bstar < 0) {
+                        const bool ok = ((valid >> r) & 1u) && !((mem >> r) & 1u) && oreg[r] < oa;
+                        const u64 bal = __builtin_amdgcn_ballot_w64(ok);
+                        if (bal != 0) bstar = 64 * r + first_lane(bal);
+                    }
+                }
+                if (bstar < 0) break;  // cannot happen: pm[] promised a partner before the bound
+                wa = (int)(ka >> 34);
+                wb = (int)(uni64(wk[bstar]) >> 34);
             }
-            if (bstar < 0) break;  // cannot happen: pm[] promised a partner before the bound
-            const u64 kb = uni64(wk[bstar]);
-            memsum += (int)(kb >> 34) - (int)(ka >> 34);
+            memsum += wb - wa;
             if (lane == (astar & 63)) mem &= ~(1u << (astar >> 6));
             if (lane == (bstar & 63)) mem |= 1u << (bstar >> 6);
         }
@@ -406,7 +433,7 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
     const int H = p.H, HM = H - 1, M = p.M;
     const int32_t *a = p.a + begin, *s = p.s + begin, *o = p.o + begin;
     int32_t *cout = p.completion_out + outb;
-    Codec codec{planner};
+    const Codec codec(planner);
 
     for (int i = lane; i < H; i += 64) L.ring[i] = 0;
     for (int i = lane; i < QCAP / 32; i += 64) L.dead[i] = 0;
@@ -507,9 +534,8 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
         int adm = 0;
         while (adm < q) {
             const u64 key = uni64(L.list[(head + adm) & QM]);
-            int w, oo, id;
-            codec.split(key, w, oo, id);
-            const int sr = w - oo;
+            const int oo = codec.decode(key), id = codec.id(key);
+            const int sr = codec.size(key) - oo;
             bool viol = false;
             for (int j = lane + 1; j <= oo; j += 64) viol |= L.ring[(t + j) & HM] + sr + j > M;
             if (__builtin_amdgcn_ballot_w64(viol) != 0) break;

@@ -11,6 +11,7 @@ Both the CPU oracle's tests and the GPU path's tests/bench use it.
 """
 from __future__ import annotations
 
+import functools
 import itertools
 from dataclasses import dataclass
 
@@ -210,6 +211,7 @@ def _online_lengths(rng: np.random.Generator, n: int, long_frac: float):
     return np.where(is_long, s_long, s).astype(np.int32), np.where(is_long, o_long, o).astype(np.int32)
 
 
+@functools.lru_cache(maxsize=None)
 def online_lambda_star(M: int = ONLINE_M, long_frac: float = 0.2) -> float:
     """Arrival rate at which the offered token-rounds equal the budget: M over the mean
     memory-time area sum_{j=1..o}(s + j) of one request, estimated on a fixed seeded sample."""
