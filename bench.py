@@ -236,7 +236,17 @@ def main() -> int:
     sum_o = int(o64.sum().item())
     last_req = orders[:, -1].to(torch.int64)
     p_last = comp.gather(1, last_req[:, None]).squeeze(1).to(torch.int64) - o64[last_req]
-    visits = int((p_last + 2 * sum_o).sum().item())  # rounds waited through + window checked + window updated
+    # Rows that share leading positions with row 0 start from row 0's saved state; only what
+    # they place themselves is counted: rounds waited through since the resume point + window
+    # checked + window updated for the positions from there on.
+    resume = ctx.simulate_resume_positions(C).to(torch.int64)
+    order0 = orders[0].to(torch.int64)
+    o_row0 = o64[order0]
+    start0 = comp[0].to(torch.int64)[order0] - o_row0  # start rounds of row 0 by position
+    cum0 = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev), torch.cumsum(o_row0, 0)])
+    t_res = torch.where(resume > 0, start0[(resume - 1).clamp(min=0)], torch.zeros_like(resume))
+    visits = int(((p_last - t_res) + 2 * (sum_o - cum0[resume])).sum().item())
+    visits_from_scratch = int((p_last + 2 * sum_o).sum().item())
     lane_ops = OPS_PER_VISIT * visits
     k_ms = float(np.mean(kernel_ms))
     achieved = lane_ops / (k_ms * 1e-3)
@@ -263,7 +273,10 @@ def main() -> int:
         "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
         "roofline": {
             "bound": "alu",
-            "kernel": "timeline_reg_kernel<33,4,false>",
+            "kernel": "timeline_reg_kernel<33,4,false,true>",
+            "launches_per_step": 2,  # rows that share least with row 0 (and row 0, saving its state), then the rest
+            "resumed_rows": int((resume > 0).sum().item()),
+            "visits_without_resume": visits_from_scratch,
             "achieved": achieved / 1e12,
             "peak": PEAK_INT32_LANE_OPS / 1e12,
             "unit": "Tlane-op/s (int32)",

@@ -116,11 +116,28 @@ int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out);
  *   common_prefix   hint: the first common_prefix positions are identical in all rows
  *                   (0 = no hint).  Never changes results; a wrong hint is detected and
  *                   reported as KVSCHED_DEV_BAD_ORDER.
+ * Rows that repeat row 0 on their leading positions (local-search neighbours of a base order
+ * passed as row 0) need not be placed from the start: with 16384 rows or more (see
+ * kvsched_set_resume_min_rows) and no declared prefix, row 0's timeline state is saved every 64
+ * positions and the three quarters of the rows that share most with row 0 (all but 4096 of them
+ * when there are more than 16384) start from the last such state they share.  Results are the
+ * same; kvsched_simulate_resume_positions() tells which rows did so.
  * ERANGE: n * (ring size) >= 2^31 (round counters are int32), M >= 2^30, o_max bound too large.
  */
 int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n,
                      const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out,
                      int32_t *completion_out, int32_t common_prefix, void *stream);
+
+/* Number of rows from which kvsched_simulate resumes rows from saved states of row 0 (default
+ * 16384: below that the rows do not fill the GPU twice and the second launch costs more than the
+ * skipped positions save); 0 = never. */
+int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows);
+
+/* For accounting of work: resume_pos_out[c] (device, [C] int32) = the position from which row c of
+ * the LAST kvsched_simulate call on this context was placed (0 = from its first position; 64 b =
+ * resumed from row 0's state after 64 b positions).  C must be that call's C; valid until the next
+ * call on the context that is not kvsched_argmin / kvsched_device_status. */
+int kvsched_simulate_resume_positions(kvsched_ctx *ctx, int32_t C, int32_t *resume_pos_out, void *stream);
 
 /*
  * Phase 1 of Algorithm 1 ("Batch Construction") with the batch chosen among the feasible

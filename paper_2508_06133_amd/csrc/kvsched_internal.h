@@ -29,6 +29,9 @@ struct kvsched_ctx {
     size_t tables_bytes;
     int timing;            // record events around the timeline kernel
     int timed;             // a pair of events has been recorded
+    int32_t resume_rows;   // rows of the last kvsched_simulate call if it resumed rows from snapshots, else 0
+    int32_t resume_first;  // ... and how many of them (in sorted order) ran from the start
+    int32_t resume_min_rows;  // kvsched_simulate resumes rows from row 0's snapshots from this many rows on
     hipEvent_t ev0, ev1;
 };
 
@@ -52,14 +55,27 @@ struct SimParams {
     int32_t *d_words;
     int32_t o_bound;          // lengths above this are reported, not simulated
     // Register kernel only: simulate positions [k_begin, k_end) (k_end == 0: up to n), starting
-    // from / leaving behind a timeline state of KVS_STATE_WORDS(NR) int32 words:
-    // {B, t, tel low, tel high, 60 unused, then the NR x 64 profile registers}.
+    // from / leaving behind a saved timeline state of KVS_STATE_HEAD_WORDS + 64 NR int32 words:
+    // {b64, t, 62 unused, the 64 lanes' partial sums of completion rounds as int64, then the
+    // NR x 64 profile registers}.  t = -1 marks a state nothing may resume from.
     int32_t k_begin = 0;
     int32_t k_end = 0;
     const int32_t *state_in = nullptr;
     int32_t *state_out = nullptr;
+    // Register kernel, explicit rows only: resuming rows from snapshots of row 0.  When cand_list is
+    // set, wave w of the launch runs candidate cand_list[w].  Snapshot j (j >= 1) is the timeline
+    // state of row 0 after 64 j positions, at snapshots + (j - 1) * snap_stride.  The wave that runs
+    // candidate 0 writes snapshots 1..snap_blocks (word 1 of a snapshot, the round t, is set to -1 by
+    // the host beforehand: a snapshot that is never taken poisons whoever resumes from it); a
+    // candidate c with resume_block[c] = b > 0 starts from snapshot b at position 64 b.
+    const int32_t *cand_list = nullptr;
+    const int32_t *resume_block = nullptr;
+    int32_t *snapshots = nullptr;
+    int32_t snap_stride = 0;
+    int32_t snap_blocks = 0;
 };
-constexpr size_t KVS_STATE_MAX_WORDS = 64 + 65 * 64;
+constexpr int KVS_STATE_HEAD_WORDS = 192;
+constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 65 * 64;
 
 // simulate.hip
 int kvs_launch_scan_lengths(const int32_t *s, const int32_t *o, int32_t n, int32_t M, int32_t o_bound,
@@ -68,6 +84,7 @@ int kvs_launch_simulate(const SimParams &p, int32_t ring_slots, hipStream_t st);
 // timeline_reg.hip (decode lengths up to KVS_REG_MAX_O)
 constexpr int32_t KVS_REG_MAX_O = 4096;
 int kvs_launch_simulate_reg(const SimParams &p, hipStream_t st);
+int32_t kvs_reg_state_words(int32_t o_bound);  // words of one snapshot for this decode bound
 
 int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t *tel_out, int32_t *d_words,
                             hipStream_t st);
@@ -125,3 +142,11 @@ int kvs_launch_check_prefix(const int32_t *orders, int32_t C, int32_t n, int32_t
                             int32_t *d_words, hipStream_t st);
 int kvs_launch_broadcast_prefix(const int32_t *prefix, int32_t cp, int32_t C, int32_t n, int32_t *completion,
                                 hipStream_t st);
+// rows resumed from snapshots of row 0 (see SimParams)
+int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, hipStream_t st);
+int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t *tmp, int32_t *sorted, hipStream_t st);
+int kvs_launch_copy_row0_prefix(const int32_t *orders, int32_t C, int32_t n, const int32_t *sorted, int32_t first,
+                                const int32_t *blocks, int32_t by_position, int32_t *completion, hipStream_t st);
+int kvs_launch_mark_snapshots_unusable(int32_t *snapshots, int32_t count, int32_t stride, hipStream_t st);
+int kvs_launch_resume_plan(const int32_t *sorted, int32_t C, int32_t first, const int32_t *blocks,
+                           int32_t *resume_pos_out, hipStream_t st);

@@ -3,6 +3,7 @@
 // the same timeline state (admission is in order, Algorithm 1's Phase 2), so the prefix is run
 // once and its state handed to all of them.
 #include "kvsched_internal.h"
+#include "phase1_util.h"
 
 #include <limits.h>
 
@@ -47,7 +48,135 @@ __global__ __launch_bounds__(256) void broadcast_prefix_kernel(const int32_t *pr
     for (int k = threadIdx.x; k < cp; k += blockDim.x) dst[k] = prefix[k];
 }
 
+// Rows that agree with row 0 on their leading positions can start from a snapshot of row 0's
+// timeline.  blocks[c] = number of leading 64-position blocks on which row c equals row 0, at
+// most (n - 1) / 64 so that something is left to place; 0 for row 0 itself, which is the row
+// that takes the snapshots.  One wavefront per row, reading stops at the first difference.
+__global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks)
+{
+    const int lane = threadIdx.x & 63;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= C) return;
+    const int32_t *a = orders;
+    const int32_t *b = orders + (size_t)c * (size_t)n;
+    const int cap = (n - 1) >> 6;
+    int nb = 0;
+    if (c > 0) {
+        for (; nb < cap; ++nb) {
+            const int k = 64 * nb + lane;  // < n: block nb < cap is complete
+            if (__builtin_amdgcn_ballot_w64(a[k] != b[k]) != 0) break;
+        }
+    }
+    if (lane == 0) blocks[c] = nb;
+}
+
+// Row indices in ascending order of blocks[], equal values by ascending row (stable): row 0
+// comes first.  One workgroup.
+__global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blocks, int32_t C, int32_t *tmp,
+                                                              int32_t *sorted)
+{
+    __shared__ RadixLds<1024> L;
+    __shared__ int sh_max[16];
+    int mx = 0;
+    for (int i = threadIdx.x; i < C; i += 1024) {
+        tmp[i] = i;
+        mx = max(mx, blocks[i]);
+    }
+    for (int d = 32; d > 0; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
+    if ((threadIdx.x & 63) == 0) sh_max[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    for (int w = 0; w < 16; ++w) mx = max(mx, sh_max[w]);
+    auto key = [blocks](int id) { return blocks[id]; };
+    // an even number of passes so that the result lands in `sorted`
+    int *src = tmp, *dst = sorted;
+    int passes = (bits_of(mx) + 7) / 8;
+    if (passes & 1) ++passes;
+    __threadfence_block();
+    __syncthreads();
+    for (int pass = 0; pass < passes; ++pass) {
+        radix_pass<1024>(src, dst, C, 8 * pass, key, L);
+        __threadfence_block();
+        __syncthreads();
+        int *sw = src; src = dst; dst = sw;
+    }
+}
+
+// Completion rounds of the positions a resumed row did not place itself: those of row 0.
+// Wave w handles row sorted[first + w].
+__global__ __launch_bounds__(256) void copy_row0_prefix_kernel(const int32_t *orders, int32_t C, int32_t n,
+                                                               const int32_t *sorted, int32_t first,
+                                                               const int32_t *blocks, int32_t by_position,
+                                                               int32_t *completion)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = first + blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= C) return;
+    const int c = sorted[w];
+    const int cp = 64 * blocks[c];
+    const int32_t *row = orders + (size_t)c * (size_t)n;
+    int32_t *dst = completion + (size_t)c * (size_t)n;
+    for (int k = lane; k < cp; k += 64) {
+        const int idx = by_position ? k : min(max(row[k], 0), n - 1);
+        dst[idx] = completion[idx];
+    }
+}
+
+// Word 1 of a snapshot is its round t; -1 there makes every timeline that resumes from it report
+// tel = -1.  All snapshots start like that; row 0's wave overwrites those it takes.
+__global__ __launch_bounds__(256) void mark_snapshots_unusable_kernel(int32_t *snapshots, int32_t count, int32_t stride)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < count) snapshots[(size_t)j * (size_t)stride + 1] = -1;
+}
+
+// resume_pos_out[c] = position from which row c was simulated (0: from the start).
+__global__ __launch_bounds__(256) void resume_plan_kernel(const int32_t *sorted, int32_t C, int32_t first,
+                                                          const int32_t *blocks, int32_t *resume_pos_out)
+{
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= C) return;
+    const int c = sorted[w];
+    resume_pos_out[c] = w >= first ? 64 * blocks[c] : 0;
+}
+
 }  // namespace
+
+int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL(shared_blocks_kernel, dim3((unsigned)((C + 3) / 4)), dim3(256), 0, st, orders, C, n, blocks);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t *tmp, int32_t *sorted, hipStream_t st)
+{
+    hipLaunchKernelGGL(sort_by_blocks_kernel, dim3(1), dim3(1024), 0, st, blocks, C, tmp, sorted);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_copy_row0_prefix(const int32_t *orders, int32_t C, int32_t n, const int32_t *sorted, int32_t first,
+                                const int32_t *blocks, int32_t by_position, int32_t *completion, hipStream_t st)
+{
+    if (first >= C) return KVSCHED_OK;
+    hipLaunchKernelGGL(copy_row0_prefix_kernel, dim3((unsigned)((C - first + 3) / 4)), dim3(256), 0, st, orders, C, n,
+                       sorted, first, blocks, by_position, completion);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_mark_snapshots_unusable(int32_t *snapshots, int32_t count, int32_t stride, hipStream_t st)
+{
+    if (count < 1) return KVSCHED_OK;
+    hipLaunchKernelGGL(mark_snapshots_unusable_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+                       snapshots, count, stride);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_resume_plan(const int32_t *sorted, int32_t C, int32_t first, const int32_t *blocks,
+                           int32_t *resume_pos_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(resume_plan_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, sorted, C, first, blocks,
+                       resume_pos_out);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
 
 int kvs_launch_moves_min_position(const int32_t *moves, int32_t K, int32_t n, int32_t *d_words, hipStream_t st)
 {

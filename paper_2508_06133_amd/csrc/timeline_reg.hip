@@ -334,12 +334,46 @@ __device__ __forceinline__ int wave_max_dpp(int v)
     return out;
 }
 
-template <int NR, int WPB, bool MOVES>
+// One int32 read through the scalar unit (the address is the same for the whole wavefront).
+__device__ __forceinline__ int scalar_read(const int32_t *base, int index)
+{
+    int v;
+    asm volatile("s_load_dword %[v], %[base], %[off]\n"
+                 "s_waitcnt lgkmcnt(0)\n"
+                 : [v] "=s"(v)
+                 : [base] "s"(base), [off] "s"(index * 4)
+                 : "memory");
+    return v;
+}
+
+// Head of a saved timeline state: words 0, 1 = b64, t (every lane stores the same two values), then
+// the lanes' partial sums of completion rounds as 64 int64 at byte 256.  The profile rows follow
+// at byte 768 (prof_store).  Written in assembly so that no temporary can land in the profile block.
+__device__ __forceinline__ void state_head_store(int32_t *snap, int b64, int t, long long tel_lane, int lane)
+{
+    int a, b, off;
+    asm volatile("v_mov_b32 %[a], %[b64]\n"
+                 "v_mov_b32 %[b], %[t]\n"
+                 "v_mov_b32 %[off], 0\n"
+                 "global_store_dword %[off], %[a], %[base]\n"
+                 "global_store_dword %[off], %[b], %[base] offset:4\n"
+                 "v_lshlrev_b32 %[off], 3, %[lane]\n"
+                 "global_store_dwordx2 %[off], %[tel], %[base] offset:256\n"
+                 "s_waitcnt vmcnt(0)\n"
+                 : [a] "=&v"(a), [b] "=&v"(b), [off] "=&v"(off)
+                 : [base] "s"(snap), [b64] "s"(b64), [t] "s"(t), [tel] "v"(tel_lane), [lane] "v"(lane)
+                 : "memory");
+}
+
+// RES: the launch runs the candidates named by p.cand_list; the wave of candidate 0 saves its
+// state every 64 positions, candidates with a resume block start from such a snapshot.
+template <int NR, int WPB, bool MOVES, bool RES>
 __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
 {
     const int lane = threadIdx.x & (WAVE - 1);
-    const int cand = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + (threadIdx.x >> 6));
-    if (cand >= p.C) return;
+    const int wave_no = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + (threadIdx.x >> 6));
+    if (wave_no >= p.C) return;
+    const int cand = RES ? scalar_read(p.cand_list, wave_no) : wave_no;
 
     const int n_all = p.n;
     const int M = p.M;
@@ -361,21 +395,29 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
 
     // positions [k_first, n) of the order are placed; the state after the first k_first ones
     // (a prefix shared by all candidates) comes from memory when there is one
-    const int k_first = p.k_begin;
+    int k_first = p.k_begin;
+    const int32_t *state_in = p.state_in;
+    if (RES && p.resume_block) {
+        const int rb = scalar_read(p.resume_block, cand);
+        if (rb > 0) {
+            k_first = 64 * rb;
+            state_in = p.snapshots + (size_t)(rb - 1) * (size_t)p.snap_stride;
+        }
+    }
+    const bool takes_snapshots = RES && p.snap_blocks > 0 && cand == 0;
     const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
     int b64 = 0;             // round of lane 0 of register 0: 64 * floor((t + 1) / 64)
     int t = 0;               // start round of the previous request in the order
     long long tel_lane = 0;  // completion rounds summed per lane; added up over the lanes at the end
-    if (p.state_in) {
-        if (p.state_in[1] < 0) {  // the shared prefix could not be scheduled
+    if (state_in) {
+        b64 = scalar_read(state_in, 0);
+        t = scalar_read(state_in, 1);
+        if (t < 0) {  // the shared prefix could not be scheduled
             if (lane == 0 && p.tel_out) p.tel_out[cand] = -1;
             return;
         }
-        b64 = p.state_in[0];
-        t = p.state_in[1];
-        if (lane == 0)
-            tel_lane = (long long)(((unsigned long long)(unsigned)p.state_in[3] << 32) | (unsigned)p.state_in[2]);
-        prof_load<NR>(p.state_in + 64, lane);
+        tel_lane = ((const long long *)(state_in + 64))[lane];
+        prof_load<NR>(state_in + KVS_STATE_HEAD_WORDS, lane);
     } else {
         prof_init<NR>();
     }
@@ -391,6 +433,11 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         ov_n = p.o[rq_n];
     }
     for (int k0 = k_first; k0 < n; k0 += WAVE) {
+        if (takes_snapshots && k0 > 0 && (k0 >> 6) <= p.snap_blocks) {  // the state after k0 positions
+            int32_t *snap = p.snapshots + (size_t)((k0 >> 6) - 1) * (size_t)p.snap_stride;
+            state_head_store(snap, b64, t, tel_lane, lane);
+            prof_store<NR>(snap + KVS_STATE_HEAD_WORDS, lane);
+        }
         const int k = k0 + lane;
         const int rq = rq_n, sv = sv_n, ov = ov_n;
         rq_n = 0, sv_n = 1, ov_n = 1;
@@ -405,7 +452,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
                 if (p.tel_out) p.tel_out[cand] = -1;
                 if (p.state_out) p.state_out[1] = -1;  // poisons every timeline that resumes from it
             }
-            return;
+            return;  // (snapshots not taken stay marked unusable, as the host left them)
         }
         const int cnt = min(WAVE, n - k0);
         int cv = 0;  // completion round of position k0 + lane
@@ -439,17 +486,12 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         tel_lane += cv;
         if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
+    if (p.state_out) {
+        state_head_store(p.state_out, b64, t, tel_lane, lane);
+        prof_store<NR>(p.state_out + KVS_STATE_HEAD_WORDS, lane);
+    }
     for (int d = 32; d > 0; d >>= 1) tel_lane += __shfl_down(tel_lane, d);
     const long long tel = tel_lane;  // lane 0 holds the total
-    if (p.state_out) {
-        if (lane == 0) {
-            p.state_out[0] = b64;
-            p.state_out[1] = t;
-            p.state_out[2] = (int)(unsigned)((unsigned long long)tel & 0xffffffffull);
-            p.state_out[3] = (int)(unsigned)((unsigned long long)tel >> 32);
-        }
-        prof_store<NR>(p.state_out + 64, lane);
-    }
     if (lane == 0 && p.tel_out) p.tel_out[cand] = tel;
 }
 
@@ -457,14 +499,24 @@ template <int NR, int WPB>
 int launch_reg(const SimParams &p, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((p.C + WPB - 1) / WPB);
-    if (p.src.orders)
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    if (p.src.orders && p.cand_list)
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    else if (p.src.orders)
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     else
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
 }  // namespace
+
+static int reg_rows_for(int32_t o_bound)
+{
+    const int rows = (o_bound + 63) / 64 + 1;
+    return rows <= 9 ? 9 : rows <= 33 ? 33 : 65;
+}
+
+int32_t kvs_reg_state_words(int32_t o_bound) { return KVS_STATE_HEAD_WORDS + 64 * reg_rows_for(o_bound); }
 
 // o_bound <= KVS_REG_MAX_O.  Rows needed: ceil(o_bound / 64) + 1.
 int kvs_launch_simulate_reg(const SimParams &p, hipStream_t st)

@@ -51,6 +51,8 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_last_timeline_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.kvsched_argmin.argtypes = [vp, vp, i32, vp, vp]
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
+    lib.kvsched_simulate_resume_positions.argtypes = [vp, i32, vp, vp]
+    lib.kvsched_set_resume_min_rows.argtypes = [vp, i32]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
@@ -147,6 +149,19 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_simulate")
         return tel, comp
+
+    def set_resume_min_rows(self, rows: int):
+        rc = _lib.kvsched_set_resume_min_rows(self._h, int(rows))
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_set_resume_min_rows")
+
+    def simulate_resume_positions(self, C: int, device="cuda:0"):
+        """-> [C] int32: position from which each row of the last simulate() call was placed."""
+        out = torch.empty(int(C), dtype=torch.int32, device=device)
+        rc = _lib.kvsched_simulate_resume_positions(self._h, int(C), out.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_simulate_resume_positions")
+        return out
 
     def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS):
         """-> (order [n] int32, batch_end [n] int32, F [n] float64, num_batches [1] int32); the first

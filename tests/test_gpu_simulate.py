@@ -250,3 +250,92 @@ def test_wrong_common_prefix_hint_is_reported(ctx):
     assert status == kvsched.DEV_BAD_ORDER and tel_g[3] == -1
     keep = [0, 1, 2, 4, 5]
     assert (tel_g[keep] == tel_o[keep]).all()
+
+
+def _resume_positions(ctx, C):
+    import torch
+
+    pos = ctx.simulate_resume_positions(C)
+    torch.cuda.synchronize()
+    return pos.cpu().numpy()
+
+
+@pytest.fixture
+def resume_from_2048_rows(ctx):
+    ctx.set_resume_min_rows(2048)
+    yield
+    ctx.set_resume_min_rows(16384)
+
+
+@pytest.mark.parametrize("cfg,n,C,completions", [(3, 700, 2500, True), (2, 321, 2048, True), (3, 1000, 5000, False),
+                                                 (3, 16500, 2100, True), (5, 1100, 3000, True)])
+def test_rows_resumed_from_row0_snapshots(ctx, resume_from_2048_rows, cfg, n, C, completions):
+    # row 0 = base: the rows that share most with row 0 start from its saved state (threshold
+    # lowered so that small cases take that path; the full-size config 3 test takes it by default).
+    # Neighbours by one swap, rows equal to row 0, rows that differ at position 0, random rows;
+    # n = 16500 has completion rounds scattered by request id instead of permuted rows.
+    inst = workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rng = np.random.default_rng(31 + cfg)
+    rows = np.broadcast_to(base, (C, n)).copy()
+    for c in range(1, C):
+        kind = c % 8
+        if kind == 0:
+            continue  # identical to row 0
+        if kind == 1:
+            rows[c] = rng.permutation(n).astype(np.int32)
+        else:
+            lo = 0 if kind == 2 else int(rng.integers(0, n - 1))
+            j = int(rng.integers(lo + 1, n))
+            rows[c, lo], rows[c, j] = rows[c, j], rows[c, lo]
+    print(f"resume: config {cfg} n={n} C={C}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows, completions=completions)
+    pos = _resume_positions(ctx, C)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o if completions else None, f"resume config {cfg}")
+    # the plan: a row never resumes beyond what it shares with row 0, always on a 64-position
+    # boundary, and a good part of the rows does resume
+    differs = rows != base[None, :]
+    shared = np.where(differs.any(axis=1), differs.argmax(axis=1), n)
+    assert (pos % 64 == 0).all() and (pos <= shared).all() and (pos < n).all() and pos[0] == 0
+    assert (pos > 0).sum() > C // 4
+    # same rows without resuming: same results
+    ctx.set_resume_min_rows(0)
+    tel_p, comp_p, _ = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows, completions=completions)
+    assert (_resume_positions(ctx, C) == 0).all()
+    _assert_equal(tel_p, comp_p, tel_g, comp_g, "with and without resuming")
+
+
+def test_resume_with_a_request_that_cannot_be_scheduled(ctx, resume_from_2048_rows):
+    # a request with s + o > M at position 300 of row 0: row 0 stops there, the snapshots behind
+    # it are never taken, and every row that holds the request gets tel = -1 whether it would
+    # have resumed before or after it
+    from paper_2508_06133_amd import kvsched
+
+    inst = workloads.instance(2, n=640)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    s = inst.s.copy()
+    s[base[300]] = inst.M  # cannot fit
+    C = 2304
+    rng = np.random.default_rng(5)
+    rows = np.broadcast_to(base, (C, inst.n)).copy()
+    for c in range(1, C):
+        i, j = sorted(int(x) for x in rng.choice(inst.n, 2, replace=False))
+        rows[c, i], rows[c, j] = rows[c, j], rows[c, i]
+    tel_g, comp_g, status = _gpu_simulate(ctx, s, inst.o, inst.M, rows)
+    assert status & kvsched.DEV_BAD_LENGTH
+    assert (tel_g == -1).all()
+    # and the same rows with well-formed lengths right afterwards (scratch is reused)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert status == 0
+    _assert_equal(tel_g, comp_g, tel_o, comp_o, "after a faulty call")
+
+
+def test_resume_plan_is_empty_below_the_row_threshold(ctx):
+    inst = workloads.instance(2)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(2, base, count=4096)
+    _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    assert (_resume_positions(ctx, 4096) == 0).all()
