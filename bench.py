@@ -33,13 +33,13 @@ PEAK_HBM_BYTES = 8.0e12
 OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for one request
 CFG = 3
 
-# HBM traffic of one launch of the dominant kernel on this workload, from rocprofv3 counters
-# (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 64855 KiB x 1.9997 (what a plain
-# 256 MiB copy reads per KiB moved) + WRITE_SIZE 128445 KiB x 1.0.  Valid only for the kernel
-# sources it was measured on; reported as null once they change.
-TRAFFIC_BYTES = int((64855 * 1.9997 + 128445 * 1.0) * 1024)
+# HBM traffic of the dominant kernel per step (its two launches) on this workload, from rocprofv3
+# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE (16357 + 31226) KiB x 1.9997
+# (what a plain 256 MiB copy reads per KiB moved) + WRITE_SIZE (32385 + 58428) KiB x 1.0.  Valid
+# only for the kernel sources it was measured on; reported as null once they change.
+TRAFFIC_BYTES = int(((16357 + 31226) * 1.9997 + (32385 + 58428) * 1.0) * 1024)
 TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
-TRAFFIC_SOURCES_SHA256 = "6484ac64260b01ea"
+TRAFFIC_SOURCES_SHA256 = "00487e87562805c9"
 
 
 def measured_traffic():
@@ -250,7 +250,7 @@ def main() -> int:
     lane_ops = OPS_PER_VISIT * visits
     k_ms = float(np.mean(kernel_ms))
     achieved = lane_ops / (k_ms * 1e-3)
-    hbm_bytes = C * (4 * n + 4 * n + 8) + 8 * n
+    hbm_bytes = int((8 * (n - resume) + 8).sum().item()) + 8 * n  # order entries read, completion rounds written, from the resume point on
     result = {
         "metric": "candidate schedules evaluated/s (n=2000 mixed)",
         "value": C * args.steps / wall,
@@ -282,7 +282,7 @@ def main() -> int:
             "unit": "Tlane-op/s (int32)",
             "frac": achieved / PEAK_INT32_LANE_OPS,
             "traffic": measured_traffic(),
-            "visits_per_launch": visits,
+            "visits_per_step": visits,  # over the kernel's two launches
             "ops_per_visit": OPS_PER_VISIT,
             "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / (k_ms * 1e-3) / 1e9,
                     "frac_of_8TBps": hbm_bytes / (k_ms * 1e-3) / PEAK_HBM_BYTES},
