@@ -100,22 +100,24 @@ def simulate_many(s, o, M, orders, literal: bool = False, completions: bool = Tr
     return tel, comp
 
 
-def sortedF(s, o, M, tie_rule: int = 0, feas_mode: int = 0):
-    """-> (order[n], batch_end[num_batches], F[num_batches]).  feas_mode as exact_phase1."""
+def sortedF(s, o, M, tie_rule: int = 0, feas_mode: int = 0, alpha=(0, 1)):
+    """-> (order[n], batch_end[num_batches], F[num_batches]).  feas_mode as exact_phase1.
+    alpha = (a, b): the metric is G = sum (a s_i + b o_i) / (b |X|^2); (0, 1) is the F-metric."""
     s, o = _i32(s), _i32(o)
     n = len(s)
     order = np.zeros(n, dtype=np.int32)
     ends = np.zeros(max(n, 1), dtype=np.int32)
     F = np.zeros(max(n, 1), dtype=np.float64)
     nb = ctypes.c_int32(0)
-    _check(_load().oracle_sortedF(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+    _check(_load().oracle_sortedG(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                  ctypes.c_int32(int(alpha[0])), ctypes.c_int32(int(alpha[1])),
                                   ctypes.c_int32(tie_rule), ctypes.c_int32(feas_mode), _ptr(order, _i32p),
                                   _ptr(ends, _i32p), _ptr(F, _f64p), ctypes.byref(nb)))
     return order, ends[: nb.value].copy(), F[: nb.value].copy()
 
 
-def local_swap(s, o, M, early_exit: bool = False):
-    """Phase 1 with Local Swap Search -> (order[n], batch_end[nb], F[nb], swaps[nb])."""
+def local_swap(s, o, M, early_exit: bool = False, alpha=(0, 1)):
+    """Phase 1 with Local Swap Search -> (order[n], batch_end[nb], F[nb], swaps[nb]).  alpha as sortedF."""
     s, o = _i32(s), _i32(o)
     n = len(s)
     order = np.zeros(n, dtype=np.int32)
@@ -123,22 +125,24 @@ def local_swap(s, o, M, early_exit: bool = False):
     F = np.zeros(max(n, 1), dtype=np.float64)
     swaps = np.zeros(max(n, 1), dtype=np.int32)
     nb = ctypes.c_int32(0)
-    _check(_load().oracle_local_swap(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+    _check(_load().oracle_local_swap_G(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                     ctypes.c_int32(int(alpha[0])), ctypes.c_int32(int(alpha[1])),
                                      ctypes.c_int32(1 if early_exit else 0), _ptr(order, _i32p), _ptr(ends, _i32p),
                                      _ptr(F, _f64p), _ptr(swaps, _i32p), ctypes.byref(nb)))
     return order, ends[: nb.value].copy(), F[: nb.value].copy(), swaps[: nb.value].copy()
 
 
-def exact_phase1(s, o, M, feas_mode: int = 0, tie_rule: int = 0):
+def exact_phase1(s, o, M, feas_mode: int = 0, tie_rule: int = 0, alpha=(0, 1)):
     """Phase 1 with exact batches (Algorithm 2) -> (order[n], batch_end[nb], F[nb]).
-    feas_mode 0: sum of peaks <= M; 1: simultaneous-start memory profile <= M."""
+    feas_mode 0: sum of peaks <= M; 1: simultaneous-start memory profile <= M.  alpha as sortedF."""
     s, o = _i32(s), _i32(o)
     n = len(s)
     order = np.zeros(n, dtype=np.int32)
     ends = np.zeros(max(n, 1), dtype=np.int32)
     F = np.zeros(max(n, 1), dtype=np.float64)
     nb = ctypes.c_int32(0)
-    _check(_load().oracle_exact_phase1(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+    _check(_load().oracle_exact_phase1_G(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), ctypes.c_int64(int(M)),
+                                       ctypes.c_int32(int(alpha[0])), ctypes.c_int32(int(alpha[1])),
                                        ctypes.c_int32(feas_mode), ctypes.c_int32(tie_rule), _ptr(order, _i32p),
                                        _ptr(ends, _i32p), _ptr(F, _f64p), ctypes.byref(nb)))
     return order, ends[: nb.value].copy(), F[: nb.value].copy()

@@ -33,6 +33,14 @@
  *                             the chosen set carried along, feasibility either the sum of peaks
  *                             (as Algorithm 2 prints it) or the simultaneous-start profile of
  *                             Algorithm 1's Phase 1 (a derived programme over (k, sum s) states).
+ *   oracle_sortedG / oracle_local_swap_G / oracle_exact_phase1_G
+ *                             the same three Phase-1 procedures with the generalised metric of
+ *                             Section 7 ("Robustness to prefill weighting"),
+ *                             G(X) = sum (alpha s_i + o_i) / |X|^2 with alpha = a / b given as two
+ *                             integers: the effective length g_i = a s_i + b o_i (b times the paper's)
+ *                             takes the place of o_i in the selection metric only; feasibility, the
+ *                             sort keys and the emission order inside a batch keep the true lengths.
+ *                             alpha = 0 is the F-metric.
  *   oracle_apply_move / oracle_best_neighbor
  *                             position-level swap / insert neighbours of an order, scored by
  *                             total end-to-end latency (Section 2, "Objective").
@@ -179,7 +187,7 @@ int oracle_simulate_profile(int32_t n, const int32_t *s, const int32_t *o, int64
 
 /* -------------------------------------------------------------- Phase 1 (sorted prefix) */
 
-typedef struct { int64_t w; int32_t o; int32_t id; } skey_t;
+typedef struct { int64_t w; int64_t g; int32_t o; int32_t id; } skey_t;  /* g: effective length a s + b o */
 
 static int cmp_size_o_id(const void *a, const void *b)
 {
@@ -215,17 +223,19 @@ static int cmp_F(int64_t Sa, int64_t ka, int64_t Sb, int64_t kb)
  * Outputs: order_out[n]; batch_end_out[b] = number of requests in batches 0..b;
  *          F_out[b] = F of batch b (one IEEE division of exact integers); *nb_out.
  */
-int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
-                   int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out,
-                   int32_t *nb_out)
+int oracle_sortedG(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t ga, int32_t gb,
+                   int32_t tie_rule, int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out,
+                   double *F_out, int32_t *nb_out)
 {
     if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
     if ((tie_rule != 0 && tie_rule != 1) || (feas_mode != 0 && feas_mode != 1)) return ORACLE_EINVAL;
+    if (ga < 0 || gb < 1) return ORACLE_EINVAL;
     skey_t *rem = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
     int64_t *at_end = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
     if (!rem || !at_end) { free(rem); free(at_end); return ORACLE_ENOMEM; }
     for (int32_t i = 0; i < n; ++i) {
         rem[i].w = (int64_t)s[i] + o[i];
+        rem[i].g = (int64_t)ga * s[i] + (int64_t)gb * o[i];
         rem[i].o = o[i];
         rem[i].id = i;
     }
@@ -252,7 +262,7 @@ int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int
                 for (int64_t j = 0; j < k; ++j) if (at_end[j] > peak) peak = at_end[j];
                 if (peak > M) break;
             }
-            S += e->o;
+            S += e->g;
             int better;
             if (bestk == 0) better = 1;
             else {
@@ -266,13 +276,20 @@ int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int
         for (int64_t k = 0; k < bestk; ++k) order_out[a + k] = rem[a + k].id;
         a += (int32_t)bestk;
         if (batch_end_out) batch_end_out[nb] = a;
-        if (F_out) F_out[nb] = (double)bestS / ((double)bestk * (double)bestk);
+        if (F_out) F_out[nb] = (double)bestS / ((double)gb * (double)bestk * (double)bestk);
         ++nb;
     }
     if (nb_out) *nb_out = nb;
     free(rem);
     free(at_end);
     return ORACLE_OK;
+}
+
+int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
+                   int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                   int32_t *nb_out)
+{
+    return oracle_sortedG(n, s, o, M, 0, 1, tie_rule, feas_mode, order_out, batch_end_out, F_out, nb_out);
 }
 
 /* ---------------------------------------------------------- Phase 1 (Local Swap Search) */
@@ -297,7 +314,7 @@ static int64_t local_swap_batch(const skey_t *rem, int32_t m, int64_t M, int ear
         if (mem + rem[r].w <= M) {
             inX[r] = 1;
             mem += rem[r].w;
-            S += rem[r].o;
+            S += rem[r].g;
             ++K;
         }
     }
@@ -313,7 +330,7 @@ static int64_t local_swap_batch(const skey_t *rem, int32_t m, int64_t M, int ear
                     if (early_exit) break;
                     continue;
                 }
-                const int64_t d_o = (int64_t)rem[b].o - rem[a].o;
+                const int64_t d_o = rem[b].g - rem[a].g;  /* change of the metric's numerator */
                 if (S + d_o < S) {  /* newF < currentF, same |X| on both sides */
                     inX[a] = 0;
                     inX[b] = 1;
@@ -336,17 +353,19 @@ static int64_t local_swap_batch(const skey_t *rem, int32_t m, int64_t M, int ear
  * remaining requests, append it in nondecreasing o (ties by id), remove it, repeat.
  * Outputs as oracle_sortedF, plus swaps_out[b] = exchanges made while forming batch b.
  */
-int oracle_local_swap(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t early_exit,
-                      int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
-                      int32_t *nb_out)
+int oracle_local_swap_G(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t ga, int32_t gb,
+                        int32_t early_exit, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                        int32_t *swaps_out, int32_t *nb_out)
 {
     if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if (ga < 0 || gb < 1) return ORACLE_EINVAL;
     skey_t *rem = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
     skey_t *batch = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
     unsigned char *inX = (unsigned char *)malloc((size_t)n + 1);
     if (!rem || !batch || !inX) { free(rem); free(batch); free(inX); return ORACLE_ENOMEM; }
     for (int32_t i = 0; i < n; ++i) {
         rem[i].w = (int64_t)s[i] + o[i];
+        rem[i].g = (int64_t)ga * s[i] + (int64_t)gb * o[i];
         rem[i].o = o[i];
         rem[i].id = i;
     }
@@ -365,7 +384,7 @@ int oracle_local_swap(int32_t n, const int32_t *s, const int32_t *o, int64_t M, 
         done += nbatch;
         m = keep;
         if (batch_end_out) batch_end_out[nb] = done;
-        if (F_out) F_out[nb] = (double)S / ((double)K * (double)K);
+        if (F_out) F_out[nb] = (double)S / ((double)gb * (double)K * (double)K);
         if (swaps_out) swaps_out[nb] = (int32_t)swaps;
         ++nb;
     }
@@ -374,6 +393,13 @@ int oracle_local_swap(int32_t n, const int32_t *s, const int32_t *o, int64_t M, 
     free(batch);
     free(inX);
     return ORACLE_OK;
+}
+
+int oracle_local_swap(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t early_exit,
+                      int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
+                      int32_t *nb_out)
+{
+    return oracle_local_swap_G(n, s, o, M, 0, 1, early_exit, order_out, batch_end_out, F_out, swaps_out, nb_out);
 }
 
 /* -------------------------------------------------------------- Phase 1 (exact batches) */
@@ -406,8 +432,8 @@ static int cmp_o_desc_id(const void *a, const void *b)
  * inX[q] = 1 marks ids[q] as chosen.  Returns 0, or ORACLE_ENOMEM.
  */
 static int exact_batch(int32_t r, const int32_t *ids, const int32_t *s, const int32_t *o, int64_t M,
-                       int32_t feas_mode, int32_t tie_rule, unsigned char *inX, int64_t *S_out,
-                       int64_t *K_out)
+                       int32_t ga, int32_t gb, int32_t feas_mode, int32_t tie_rule, unsigned char *inX,
+                       int64_t *S_out, int64_t *K_out)
 {
     const int64_t INF = INT64_MAX;
     const size_t words = ((size_t)r + 63) / 64, cols = (size_t)M + 1, rows = (size_t)r + 1;
@@ -429,7 +455,7 @@ static int exact_batch(int32_t r, const int32_t *ids, const int32_t *s, const in
                 const int64_t new_m = m + load_i;
                 const int64_t need = feas_mode == 1 ? new_m + (int64_t)o[i] * (k + 1) : new_m;
                 if (need > M) continue;
-                const int64_t new_val = cur + o[i];
+                const int64_t new_val = cur + (int64_t)ga * s[i] + (int64_t)gb * o[i];  /* dp holds sums of the effective length */
                 const size_t dst = (size_t)(k + 1) * cols + (size_t)new_m;
                 if (new_val < dp[dst]) {
                     dp[dst] = new_val;
@@ -467,11 +493,12 @@ static int exact_batch(int32_t r, const int32_t *ids, const int32_t *s, const in
  * Phase 1 of Algorithm 1 with exact batches: choose the batch, append it in nondecreasing o
  * (ties by id), remove it, repeat.  Outputs as oracle_sortedF.
  */
-int oracle_exact_phase1(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t feas_mode,
-                        int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
-                        int32_t *nb_out)
+int oracle_exact_phase1_G(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t ga, int32_t gb,
+                          int32_t feas_mode, int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out,
+                          double *F_out, int32_t *nb_out)
 {
     if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if (ga < 0 || gb < 1) return ORACLE_EINVAL;
     if ((tie_rule != 0 && tie_rule != 1) || (feas_mode != 0 && feas_mode != 1)) return ORACLE_EINVAL;
     int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
     skey_t *batch = (skey_t *)malloc(sizeof(skey_t) * (size_t)(n + 1));
@@ -481,11 +508,11 @@ int oracle_exact_phase1(int32_t n, const int32_t *s, const int32_t *o, int64_t M
     int32_t r = n, done = 0, nb = 0, rc = ORACLE_OK;
     while (r > 0) {
         int64_t S = 0, K = 0;
-        rc = exact_batch(r, ids, s, o, M, feas_mode, tie_rule, inX, &S, &K);
+        rc = exact_batch(r, ids, s, o, M, ga, gb, feas_mode, tie_rule, inX, &S, &K);
         if (rc != ORACLE_OK) break;
         int32_t nbatch = 0, keep = 0;
         for (int32_t q = 0; q < r; ++q) {
-            if (inX[q]) { batch[nbatch].o = o[ids[q]]; batch[nbatch].id = ids[q]; batch[nbatch].w = 0; ++nbatch; }
+            if (inX[q]) { batch[nbatch].o = o[ids[q]]; batch[nbatch].id = ids[q]; batch[nbatch].w = 0; batch[nbatch].g = 0; ++nbatch; }
             else ids[keep++] = ids[q];
         }
         qsort(batch, (size_t)nbatch, sizeof(skey_t), cmp_o_id);
@@ -493,7 +520,7 @@ int oracle_exact_phase1(int32_t n, const int32_t *s, const int32_t *o, int64_t M
         done += nbatch;
         r = keep;
         if (batch_end_out) batch_end_out[nb] = done;
-        if (F_out) F_out[nb] = (double)S / ((double)K * (double)K);
+        if (F_out) F_out[nb] = (double)S / ((double)gb * (double)K * (double)K);
         ++nb;
     }
     if (nb_out) *nb_out = nb;
@@ -501,6 +528,13 @@ int oracle_exact_phase1(int32_t n, const int32_t *s, const int32_t *o, int64_t M
     free(batch);
     free(inX);
     return rc;
+}
+
+int oracle_exact_phase1(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t feas_mode,
+                        int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                        int32_t *nb_out)
+{
+    return oracle_exact_phase1_G(n, s, o, M, 0, 1, feas_mode, tie_rule, order_out, batch_end_out, F_out, nb_out);
 }
 
 /* ----------------------------------------------------------------- neighbourhood moves */
