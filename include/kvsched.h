@@ -65,6 +65,11 @@ typedef struct kvsched_ctx kvsched_ctx;
 
 #define KVSCHED_MAX_O 16384
 
+/* Phase-1 batch solvers selectable in kvsched_phase1_G */
+#define KVSCHED_SOLVER_SORTED_PREFIX 0 /* as kvsched_sortedF    */
+#define KVSCHED_SOLVER_LOCAL_SWAP 1    /* as kvsched_local_swap */
+#define KVSCHED_SOLVER_EXACT_DP 2      /* as kvsched_exact_dp   */
+
 /* planners of kvsched_online: what a refresh of the cached priority order does with the backlog */
 #define KVSCHED_PLANNER_ARRIVAL 0         /* arrival order (id): FCFS                                   */
 #define KVSCHED_PLANNER_SHORTEST_DECODE 1 /* ascending (o_i, i): shortest decode first, MC-SF           */
@@ -198,6 +203,26 @@ int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int3
 int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
                      int32_t feas_mode, int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out,
                      double *F_out, int32_t *num_batches_out, void *stream);
+
+/*
+ * Phase 1 of Algorithm 1 under the generalised metric of Section 7 ("Robustness to prefill
+ * weighting"), G(X) = sum (alpha s_i + o_i) / |X|^2 with alpha = alpha_num / alpha_den (alpha_num >= 0,
+ * alpha_den >= 1; alpha = 0 is the F-metric and gives exactly what the three calls above give).  The
+ * effective length alpha s_i + o_i takes the place of o_i in the metric only: batch feasibility, the
+ * sort keys (s_i + o_i, o_i, i) and the emission of a batch in nondecreasing o_i keep the true
+ * lengths.  Decisions are taken on the integers alpha_num s_i + alpha_den o_i, exactly.
+ *
+ *   solver      KVSCHED_SOLVER_SORTED_PREFIX / _LOCAL_SWAP (feas_mode must be SUM_OF_PEAKS; tie_rule
+ *               unused; an exchange is taken when it lowers the sum of effective lengths) / _EXACT_DP
+ *   G_out       [n] double: G of batch b = sum (alpha_num s_i + alpha_den o_i) / (alpha_den |X|^2)
+ *   swaps_out   [n] int32 or NULL: exchanges per batch (local swap only)
+ *   other arguments as for the solver's own call
+ * ERANGE: max(alpha_num, alpha_den) > 65535; for Local Swap Search max(alpha_num, alpha_den) * M >= 2^31,
+ * for the exact DP max(alpha_num, alpha_den) * 2 M >= 2^31 (effective lengths are held in int32).
+ */
+int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                     int32_t alpha_num, int32_t alpha_den, int32_t tie_rule, int32_t feas_mode, int32_t *order_out,
+                     int32_t *batch_end_out, double *G_out, int32_t *swaps_out, int32_t *num_batches_out, void *stream);
 
 /*
  * Local-search step on a priority order: every move is applied to `base_order` on the fly

@@ -380,9 +380,10 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     return kvs_launch_check_prefix(orders, C, n, cp, tel_out, ctx->d_words, st);
 }
 
-int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
-                    int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out,
-                    int32_t *num_batches_out, void *stream)
+// The three Phase-1 solvers; (ga, gb) = (0, 1) is the F-metric.
+static int run_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t ga,
+                       int32_t gb, int32_t tie_rule, int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out,
+                       double *F_out, int32_t *num_batches_out, void *stream)
 {
     int rc = check_common(ctx, n, s, o, M);
     if (rc != KVSCHED_OK) return rc;
@@ -394,13 +395,21 @@ int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
-    return kvs_launch_sortedF(n, s, o, (int32_t)M, tie_rule, feas_mode, order_out, batch_end_out, F_out, num_batches_out,
-                              ctx->d_scratch, ctx->d_words, st);
+    return kvs_launch_sortedF(n, s, o, (int32_t)M, ga, gb, tie_rule, feas_mode, order_out, batch_end_out, F_out,
+                              num_batches_out, ctx->d_scratch, ctx->d_words, st);
 }
 
-int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
-                       int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
-                       int32_t *num_batches_out, void *stream)
+int kvsched_sortedF(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t tie_rule,
+                    int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                    int32_t *num_batches_out, void *stream)
+{
+    return run_sortedF(ctx, n, s, o, M, 0, 1, tie_rule, feas_mode, order_out, batch_end_out, F_out, num_batches_out,
+                       stream);
+}
+
+static int run_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t ga,
+                          int32_t gb, int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
+                          int32_t *num_batches_out, void *stream)
 {
     int rc = check_common(ctx, n, s, o, M);
     if (rc != KVSCHED_OK) return rc;
@@ -410,13 +419,20 @@ int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int3
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, 0, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
-    return kvs_launch_local_swap(n, s, o, (int32_t)M, order_out, batch_end_out, F_out, swaps_out, num_batches_out,
-                                 ctx->d_scratch, ctx->d_words, st);
+    return kvs_launch_local_swap(n, s, o, (int32_t)M, ga, gb, order_out, batch_end_out, F_out, swaps_out,
+                                 num_batches_out, ctx->d_scratch, ctx->d_words, st);
 }
 
-int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t feas_mode,
-                     int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
-                     int32_t *num_batches_out, void *stream)
+int kvsched_local_swap(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                       int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *swaps_out,
+                       int32_t *num_batches_out, void *stream)
+{
+    return run_local_swap(ctx, n, s, o, M, 0, 1, order_out, batch_end_out, F_out, swaps_out, num_batches_out, stream);
+}
+
+static int run_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t ga,
+                        int32_t gb, int32_t feas_mode, int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out,
+                        double *F_out, int32_t *num_batches_out, void *stream)
 {
     int rc = check_common(ctx, n, s, o, M);
     if (rc != KVSCHED_OK) return rc;
@@ -435,7 +451,7 @@ int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_
     if (const int lg = kvs_exact_dp_small_lg(n, k_host, (int32_t)M)) {
         rc = ensure_tables(ctx, kvs_exact_dp_small_record_bytes(n, k_host, lg));
         if (rc != KVSCHED_OK) return rc;
-        return kvs_launch_exact_dp_small(n, s, o, (int32_t)M, feas_mode, tie_rule, lg, ctx->d_scratch, ctx->d_tables,
+        return kvs_launch_exact_dp_small(n, s, o, (int32_t)M, ga, gb, feas_mode, tie_rule, lg, ctx->d_scratch, ctx->d_tables,
                                          order_out, batch_end_out, F_out, num_batches_out, ctx->d_words, st);
     }
     rc = kvs_launch_exact_dp_prepare(n, s, o, (int32_t)M, feas_mode, ctx->d_scratch, ctx->d_words, num_batches_out, st);
@@ -448,7 +464,7 @@ int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_
     if (const int lg = kvs_exact_dp_small_lg(n, kmax, (int32_t)M)) {  // fits after all, with the true bound
         rc = ensure_tables(ctx, kvs_exact_dp_small_record_bytes(n, kmax, lg));
         if (rc != KVSCHED_OK) return rc;
-        return kvs_launch_exact_dp_small(n, s, o, (int32_t)M, feas_mode, tie_rule, lg, ctx->d_scratch, ctx->d_tables,
+        return kvs_launch_exact_dp_small(n, s, o, (int32_t)M, ga, gb, feas_mode, tie_rule, lg, ctx->d_scratch, ctx->d_tables,
                                          order_out, batch_end_out, F_out, num_batches_out, ctx->d_words, st);
     }
     const size_t bytes = kvs_exact_dp_table_bytes(r, kmax, (int32_t)M);
@@ -457,7 +473,7 @@ int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_
     if (rc != KVSCHED_OK) return rc;
     int32_t nb = 0;
     while (r > 0) {  // r falls by at least one per batch
-        rc = kvs_launch_exact_dp_batch(n, r, kmax, s, o, (int32_t)M, feas_mode, tie_rule, nb, ctx->d_scratch,
+        rc = kvs_launch_exact_dp_batch(n, r, kmax, s, o, (int32_t)M, ga, gb, feas_mode, tie_rule, nb, ctx->d_scratch,
                                        ctx->d_tables, batch_end_out, F_out, ctx->d_words, st);
         if (rc != KVSCHED_OK) return rc;
         rc = read_words(ctx, st);
@@ -469,6 +485,43 @@ int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_
         kmax = k_next;
     }
     return kvs_launch_exact_dp_emit(n, nb, ctx->d_scratch, order_out, num_batches_out, st);
+}
+
+int kvsched_exact_dp(kvsched_ctx *ctx, int32_t n, const int32_t *s, const int32_t *o, int64_t M, int32_t feas_mode,
+                     int32_t tie_rule, int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                     int32_t *num_batches_out, void *stream)
+{
+    return run_exact_dp(ctx, n, s, o, M, 0, 1, feas_mode, tie_rule, order_out, batch_end_out, F_out, num_batches_out,
+                        stream);
+}
+
+int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
+                     int32_t alpha_num, int32_t alpha_den, int32_t tie_rule, int32_t feas_mode, int32_t *order_out,
+                     int32_t *batch_end_out, double *G_out, int32_t *swaps_out, int32_t *num_batches_out, void *stream)
+{
+    if (alpha_num < 0 || alpha_den < 1 || M < 1) return KVSCHED_EINVAL;
+    // Effective lengths alpha_num s_i + alpha_den o_i <= big (s_i + o_i) <= big M.  The sorted-prefix
+    // kernel sums them in int64 (and needs alpha_den k^2 exact in a double); Local Swap Search keeps one
+    // per request in an int32; the exact DP keeps sums over a batch in int32 (at most M under the sum of
+    // peaks, 2 M under the profile constraint).
+    const int64_t big = alpha_num > alpha_den ? alpha_num : alpha_den;
+    const int64_t lim = (int64_t)1 << 31;
+    if (big > 65535) return KVSCHED_ERANGE;
+    if (solver == KVSCHED_SOLVER_LOCAL_SWAP && big * M >= lim) return KVSCHED_ERANGE;
+    if (solver == KVSCHED_SOLVER_EXACT_DP && big * 2 * M >= lim) return KVSCHED_ERANGE;
+    switch (solver) {
+        case KVSCHED_SOLVER_SORTED_PREFIX:
+            return run_sortedF(ctx, n, s, o, M, alpha_num, alpha_den, tie_rule, feas_mode, order_out, batch_end_out,
+                               G_out, num_batches_out, stream);
+        case KVSCHED_SOLVER_LOCAL_SWAP:
+            if (feas_mode != KVSCHED_FEAS_SUM_OF_PEAKS) return KVSCHED_EINVAL;
+            return run_local_swap(ctx, n, s, o, M, alpha_num, alpha_den, order_out, batch_end_out, G_out, swaps_out,
+                                  num_batches_out, stream);
+        case KVSCHED_SOLVER_EXACT_DP:
+            return run_exact_dp(ctx, n, s, o, M, alpha_num, alpha_den, feas_mode, tie_rule, order_out, batch_end_out,
+                                G_out, num_batches_out, stream);
+        default: return KVSCHED_EINVAL;
+    }
 }
 
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,

@@ -161,21 +161,22 @@ __global__ __launch_bounds__(DP_STEP_T) void dp_init_kernel(int *a, int *b, size
 
 // Request proc[t] offered to every state: row k = blockIdx.y + 1, loads blockIdx.x * 256 ...
 __global__ __launch_bounds__(DP_STEP_T) void dp_step_kernel(const int *proc, int t, const int32_t *s, const int32_t *o,
-                                                            int32_t M, int32_t feas_mode, const int *src, int *dst,
-                                                            unsigned long long *bits_t, int Mp)
+                                                            int32_t M, int32_t ga, int32_t gb, int32_t feas_mode,
+                                                            const int *src, int *dst, unsigned long long *bits_t, int Mp)
 {
     const int k = blockIdx.y + 1;
     const int m = blockIdx.x * DP_STEP_T + threadIdx.x;  // < Mp by the launch shape
     const int id = proc[t];
     const int oi = o[id];
     const int load = feas_mode ? s[id] : s[id] + oi;
+    const int gi = ga * s[id] + gb * oi;  // what dp sums: o, or the effective length of the G metric
     const size_t at = (size_t)k * Mp + m;
     const int old = src[at];
     int cand = DP_INF;
     if (m <= M && m >= load) {
         const int prev = src[at - Mp - load];
         const bool fits = feas_mode == 0 || (long long)m + (long long)oi * k <= (long long)M;
-        if (prev != DP_INF && fits) cand = prev + oi;
+        if (prev != DP_INF && fits) cand = prev + gi;
     }
     const bool take = cand < old;
     dst[at] = take ? cand : old;
@@ -250,12 +251,12 @@ __device__ void argmin_body(TablePtr dp, int k_first, int k_step, int kmax, int3
 
 // Thread 0: the outputs of batch nb (or the report that no state exists, which cannot happen for
 // well-formed input: a single request always fits).
-__device__ void publish_batch(long long bS, int bk, int32_t done, int32_t nb, int32_t *batch_end_out, double *F_out,
-                              int32_t *words)
+__device__ void publish_batch(long long bS, int bk, int32_t gb, int32_t done, int32_t nb, int32_t *batch_end_out,
+                              double *F_out, int32_t *words)
 {
     if (bk >= 1) {
         batch_end_out[nb] = done + bk;
-        F_out[nb] = (double)bS / ((double)bk * (double)bk);
+        F_out[nb] = (double)bS / ((double)gb * (double)bk * (double)bk);
     } else {
         atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
     }
@@ -276,9 +277,9 @@ __global__ __launch_bounds__(DP_T) void dp_argmin_rows_kernel(const int *dp, int
     }
 }
 
-__global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const long long *partial, int G, int32_t tie_rule, int32_t done,
-                                                         int32_t nb, int32_t *batch_end_out, double *F_out,
-                                                         int32_t *words)
+__global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const long long *partial, int G, int32_t tie_rule, int32_t gb,
+                                                         int32_t done, int32_t nb, int32_t *batch_end_out,
+                                                         double *F_out, int32_t *words)
 {
     __shared__ HelperLds L;
     long long bS = 0;
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(DP_T) void dp_argmin_kernel(const long long *partia
     if (threadIdx.x == 0) {
         words[KVS_W_BESTK] = bk;
         words[KVS_W_BESTM] = bm;
-        publish_batch(bS, bk, done, nb, batch_end_out, F_out, words);
+        publish_batch(bS, bk, gb, done, nb, batch_end_out, F_out, words);
     }
 }
 
@@ -422,7 +423,7 @@ constexpr int DP_SMALL_STATES = 12288;  // (kmax + 1) * Mp at most; two int tabl
 constexpr int DP_SMALL_N = 1024;
 
 __global__ __launch_bounds__(DP_T) void dp_small_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
-                                                        int32_t feas_mode, int32_t tie_rule, int lg, int *proc, int *by_o,
+                                                        int32_t ga, int32_t gb, int32_t feas_mode, int32_t tie_rule, int lg, int *proc, int *by_o,
                                                         int *by_cost, int *buf0, int *buf1, int *batch_of,
                                                         unsigned long long *bits, int32_t *order_out,
                                                         int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
@@ -430,7 +431,7 @@ __global__ __launch_bounds__(DP_T) void dp_small_kernel(int32_t n, const int32_t
 {
     __shared__ HelperLds L;
     __shared__ int tab[2][DP_SMALL_STATES];
-    __shared__ int req_o[DP_SMALL_N], req_load[DP_SMALL_N];
+    __shared__ int req_o[DP_SMALL_N], req_load[DP_SMALL_N], req_g[DP_SMALL_N];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Mp = 1 << lg;
     int kmax = prepare_body(n, s, o, M, feas_mode, proc, by_o, by_cost, buf0, buf1, batch_of, words, num_batches_out, L);
@@ -451,11 +452,12 @@ __global__ __launch_bounds__(DP_T) void dp_small_kernel(int32_t n, const int32_t
             const int id = proc[t];
             req_o[t] = o[id];
             req_load[t] = feas_mode ? s[id] : s[id] + o[id];
+            req_g[t] = ga * s[id] + gb * o[id];
         }
         __syncthreads();
         const size_t per_t = (size_t)(kmax + 1) << (lg - 6);
         for (int t = 0; t < r; ++t) {
-            const int oi = req_o[t], load = req_load[t];
+            const int oi = req_o[t], load = req_load[t], gi = req_g[t];
             const int rows = t + 1 < kmax ? t + 1 : kmax;
             const int cnt = rows << lg;
             const int *src = tab[t & 1];
@@ -469,7 +471,7 @@ __global__ __launch_bounds__(DP_T) void dp_small_kernel(int32_t n, const int32_t
                     if (m <= M && m >= load) {
                         const int prev = src[at - Mp - load];
                         const bool fits = feas_mode == 0 || (long long)m + (long long)oi * k <= (long long)M;
-                        if (prev != DP_INF && fits) cand = prev + oi;
+                        if (prev != DP_INF && fits) cand = prev + gi;
                     }
                     const bool take = cand < old;
                     dst[at] = take ? cand : old;
@@ -482,7 +484,7 @@ __global__ __launch_bounds__(DP_T) void dp_small_kernel(int32_t n, const int32_t
         long long bS;
         int bk, bm;
         argmin_body(tab[r & 1], 1, 1, kmax, M, Mp, tie_rule, L, bS, bk, bm);
-        if (tid == 0) publish_batch(bS, bk, n - r, nb, batch_end_out, F_out, words);
+        if (tid == 0) publish_batch(bS, bk, gb, n - r, nb, batch_end_out, F_out, words);
         if (bk < 1) break;  // uniform
         __threadfence_block();
         __syncthreads();
@@ -530,7 +532,7 @@ int kvs_launch_exact_dp_prepare(int32_t n, const int32_t *s, const int32_t *o, i
 
 // One batch over the r remaining requests: tables, records, best state, members, compaction.
 int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t *s, const int32_t *o, int32_t M,
-                              int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
+                              int32_t ga, int32_t gb, int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
                               int32_t *batch_end_out, double *F_out, int32_t *d_words, hipStream_t st)
 {
     const size_t np = ((size_t)n + 64) & ~(size_t)63;
@@ -546,7 +548,7 @@ int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t 
     for (int32_t t = 0; t < r; ++t) {
         const int rows = t + 1 < kmax ? t + 1 : kmax;  // after t + 1 requests no set is larger
         hipLaunchKernelGGL(dp_step_kernel, dim3((unsigned)(Mp / DP_STEP_T), (unsigned)rows), dim3(DP_STEP_T), 0, st,
-                           proc, t, s, o, M, feas_mode, dp[t & 1], dp[(t + 1) & 1], bits + (size_t)t * per_t, Mp);
+                           proc, t, s, o, M, ga, gb, feas_mode, dp[t & 1], dp[(t + 1) & 1], bits + (size_t)t * per_t, Mp);
         if (!launched()) return KVSCHED_EHIP;
     }
     const int G = kmax < DP_ARGMIN_BLOCKS ? kmax : DP_ARGMIN_BLOCKS;
@@ -554,7 +556,7 @@ int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t 
     hipLaunchKernelGGL(dp_argmin_rows_kernel, dim3((unsigned)G), dim3(DP_T), 0, st, dp[r & 1], kmax, M, Mp, tie_rule,
                        partial);
     if (!launched()) return KVSCHED_EHIP;
-    hipLaunchKernelGGL(dp_argmin_kernel, dim3(1), dim3(DP_T), 0, st, partial, G, tie_rule, n - r, nb, batch_end_out,
+    hipLaunchKernelGGL(dp_argmin_kernel, dim3(1), dim3(DP_T), 0, st, partial, G, tie_rule, gb, n - r, nb, batch_end_out,
                        F_out, d_words);
     if (!launched()) return KVSCHED_EHIP;
     hipLaunchKernelGGL(dp_walk_kernel, dim3(1), dim3(64), 0, st, bits, proc, r, kmax, Mp, s, o, feas_mode, nb, batch_of,
@@ -581,15 +583,15 @@ size_t kvs_exact_dp_small_record_bytes(int32_t n, int32_t kmax_bound, int lg)
     return (size_t)n * ((size_t)(kmax_bound + 1) << (lg - 6)) * sizeof(unsigned long long) + 256;
 }
 
-int kvs_launch_exact_dp_small(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
-                              int32_t tie_rule, int lg, void *lists, void *records, int32_t *order_out,
+int kvs_launch_exact_dp_small(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
+                              int32_t feas_mode, int32_t tie_rule, int lg, void *lists, void *records, int32_t *order_out,
                               int32_t *batch_end_out, double *F_out, int32_t *num_batches_out, int32_t *d_words,
                               hipStream_t st)
 {
     const size_t np = ((size_t)n + 64) & ~(size_t)63;
     int *proc = (int *)lists, *by_o = proc + np, *by_cost = by_o + np, *buf0 = by_cost + np, *buf1 = buf0 + np,
         *batch_of = buf1 + np;
-    hipLaunchKernelGGL(dp_small_kernel, dim3(1), dim3(DP_T), 0, st, n, s, o, M, feas_mode, tie_rule, lg, proc, by_o,
+    hipLaunchKernelGGL(dp_small_kernel, dim3(1), dim3(DP_T), 0, st, n, s, o, M, ga, gb, feas_mode, tie_rule, lg, proc, by_o,
                        by_cost, buf0, buf1, batch_of, (unsigned long long *)records, order_out, batch_end_out, F_out,
                        num_batches_out, d_words);
     return launched() ? KVSCHED_OK : KVSCHED_EHIP;

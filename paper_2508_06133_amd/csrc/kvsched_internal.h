@@ -97,12 +97,14 @@ size_t kvs_exact_dp_list_bytes(int32_t n);
 size_t kvs_exact_dp_table_bytes(int32_t r, int32_t kmax, int32_t M);
 int kvs_launch_exact_dp_prepare(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
                                 void *lists, int32_t *d_words, int32_t *num_batches_out, hipStream_t st);
+// ga, gb: the metric's numerator sums ga s_i + gb o_i (0, 1: the F-metric; else G with alpha = ga / gb)
 int kvs_launch_exact_dp_batch(int32_t n, int32_t r, int32_t kmax, const int32_t *s, const int32_t *o, int32_t M,
-                              int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
+                              int32_t ga, int32_t gb, int32_t feas_mode, int32_t tie_rule, int32_t nb, void *lists, void *tables,
                               int32_t *batch_end_out, double *F_out, int32_t *d_words, hipStream_t st);
 int kvs_exact_dp_small_lg(int32_t n, int32_t kmax_bound, int32_t M);
 size_t kvs_exact_dp_small_record_bytes(int32_t n, int32_t kmax_bound, int lg);
-int kvs_launch_exact_dp_small(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t feas_mode,
+int kvs_launch_exact_dp_small(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
+                              int32_t feas_mode,
                               int32_t tie_rule, int lg, void *lists, void *records, int32_t *order_out,
                               int32_t *batch_end_out, double *F_out, int32_t *num_batches_out, int32_t *d_words,
                               hipStream_t st);
@@ -111,13 +113,15 @@ int kvs_launch_exact_dp_emit(int32_t n, int32_t nb, void *lists, int32_t *order_
 
 // localswap.hip
 size_t kvs_local_swap_scratch_bytes(int32_t n);
-int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t *order_out,
+int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
+                          int32_t *order_out,
                           int32_t *batch_end_out, double *F_out, int32_t *swaps_out, int32_t *num_batches_out,
                           void *scratch, int32_t *d_words, hipStream_t st);
 
 // sortedf.hip
 size_t kvs_sortedF_scratch_bytes(int32_t n);
-int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule, int32_t feas_mode,
+int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
+                       int32_t tie_rule, int32_t feas_mode,
                        int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
                        void *scratch, int32_t *d_words, hipStream_t st);
 

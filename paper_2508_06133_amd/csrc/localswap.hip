@@ -30,6 +30,7 @@ constexpr int LS_TILE = LS_T * LS_E;
 constexpr int LS_NW = LS_T / 64;
 constexpr int LS_CAP = 10240;            // remaining requests held in LDS (3 x 40 KB + the 32 KB table)
 constexpr int LS_TABLE = 16384;          // sizes covered by the rank table
+constexpr int LS_SMALL_VALUE = 1 << 15;  // values (o, or a s + b o) the straight-line steps can carry
 constexpr int LS_INF = 0x7fffffff;
 constexpr unsigned LS_MEMBER = 0x80000000u;  // membership flag kept in the sign bit of the o entry
 constexpr int LS_NONE = 0x7fffffff;
@@ -500,7 +501,7 @@ __device__ __forceinline__ bool swap_steps_small(lds_int *W, lds_int *O, lds_int
 }
 
 __global__ __launch_bounds__(LS_T) void local_swap_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
-                                                          int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                                                          int32_t ga, int32_t gb, int32_t *order_out, int32_t *batch_end_out, double *F_out,
                                                           int32_t *swaps_out, int32_t *num_batches_out, int *gw, int *go,
                                                           int *gid, int *alt_o, int *buf0, int *buf1, int *by_o,
                                                           int *batch_of, int32_t *words)
@@ -511,21 +512,25 @@ __global__ __launch_bounds__(LS_T) void local_swap_kernel(int32_t n, const int32
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // ---- well-formedness and key widths
-    int omax = 0, wmax = 0, bad = 0;
+    int omax = 0, wmax = 0, vmax = 0, bad = 0;
     for (int i = tid; i < n; i += LS_T) {
         const int sv = s[i], ov = o[i];
-        if (sv < 1 || ov < 1 || (long long)sv + ov > (long long)M) bad = 1;
+        const bool ok = sv >= 1 && ov >= 1 && (long long)sv + ov <= (long long)M;
+        if (!ok) bad = 1;
         omax = max(omax, ov);
         wmax = max(wmax, (sv < 1 || ov < 1) ? 0 : (int)min((long long)sv + ov, (long long)M));
+        vmax = max(vmax, ok ? ga * sv + gb * ov : 0);
     }
     if (tid < 4) sh[tid] = 0;
     __syncthreads();
     if (bad) atomicOr(&sh[2], 1);
     atomicMax(&sh[0], omax);
     atomicMax(&sh[1], wmax);
+    atomicMax(&sh[3], vmax);
     __syncthreads();
     omax = sh[0];
     wmax = sh[1];
+    vmax = sh[3];  // largest value an exchange compares: o, or the effective length of the G metric
     if (sh[2] != 0) {  // a request that can never run: report, emit no batches
         if (tid == 0) {
             atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
@@ -553,7 +558,7 @@ __global__ __launch_bounds__(LS_T) void local_swap_kernel(int32_t n, const int32
     for (int i = tid; i < n; i += LS_T) {
         const int id = cur[i];
         gid[i] = id;
-        go[i] = o[id];
+        go[i] = ga * s[id] + gb * o[id];  // what an exchange must lower: o, or the effective length of the G metric
         gw[i] = s[id] + o[id];
     }
     __threadfence_block();
@@ -595,7 +600,8 @@ __global__ __launch_bounds__(LS_T) void local_swap_kernel(int32_t n, const int32
             if (W[m - 1] < LS_TABLE) {
                 build_rank(W, m, P.work.rank, L);
                 rank = (lds_rank *)P.work.rank;
-                done = swap_steps_small((lds_int *)P.work.w, (lds_int *)P.work.o, (lds_int *)P.work.pm, rank, m, M, st, L);
+                if (vmax < LS_SMALL_VALUE)  // the straight-line steps pack (place, value) into 32 bits
+                    done = swap_steps_small((lds_int *)P.work.w, (lds_int *)P.work.o, (lds_int *)P.work.pm, rank, m, M, st, L);
             }
             if (!done) swap_loop((lds_int *)P.work.w, (lds_int *)P.work.o, (lds_int *)P.work.pm, rank, m, M, st, L);
         } else {
@@ -607,7 +613,7 @@ __global__ __launch_bounds__(LS_T) void local_swap_kernel(int32_t n, const int32
         __syncthreads();
         if (tid == 0) {
             batch_end_out[nb] = a + K;
-            F_out[nb] = (double)S / ((double)K * (double)K);
+            F_out[nb] = (double)S / ((double)gb * (double)K * (double)K);
             if (swaps_out) swaps_out[nb] = swaps;
         }
         // members get the batch number; non-members of [0, hi) close up behind the K removed
@@ -679,7 +685,8 @@ size_t kvs_local_swap_scratch_bytes(int32_t n)
     return np * 8 * sizeof(int) + 256;
 }
 
-int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t *order_out,
+int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
+                          int32_t *order_out,
                           int32_t *batch_end_out, double *F_out, int32_t *swaps_out, int32_t *num_batches_out,
                           void *scratch, int32_t *d_words, hipStream_t st)
 {
@@ -692,7 +699,7 @@ int kvs_launch_local_swap(int32_t n, const int32_t *s, const int32_t *o, int32_t
     int *buf1 = buf0 + np;
     int *by_o = buf1 + np;
     int *batch_of = by_o + np;
-    hipLaunchKernelGGL(local_swap_kernel, dim3(1), dim3(LS_T), 0, st, n, s, o, M, order_out, batch_end_out, F_out,
+    hipLaunchKernelGGL(local_swap_kernel, dim3(1), dim3(LS_T), 0, st, n, s, o, M, ga, gb, order_out, batch_end_out, F_out,
                        swaps_out, num_batches_out, gw, go, gid, alt_o, buf0, buf1, by_o, batch_of, d_words);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

@@ -1,6 +1,8 @@
 // Sorted-F order construction: Phase 1 of Algorithm 1 ("Batch Construction") with the batch
 // taken among the feasible prefixes of the remaining requests sorted by (s+o, o, id), scored
-// by the F-metric of Section 4, F(X) = sum o_i / |X|^2.
+// by the F-metric of Section 4, F(X) = sum o_i / |X|^2, or by the generalised metric of Section 7
+// ("Robustness to prefill weighting"), G(X) = sum (alpha s_i + o_i) / |X|^2 with alpha = ga / gb: the
+// effective length ga s_i + gb o_i replaces o_i in the metric's numerator, nowhere else.
 //
 // Since every batch is a prefix of what remains, the remaining requests stay sorted: one key
 // sort serves all batches, and batch b is the segment [a_b, a_b + k*) of the sorted array.
@@ -118,9 +120,10 @@ __device__ bool profile_fits(int n, int a, int k, const int32_t *s, const int32_
 }
 
 __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
-                                                      int32_t tie_rule, int32_t feas_mode, int32_t *order_out,
-                                                      int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
-                                                      int *buf0, int *buf1, int *by_o, long long *cumW, long long *cumS,
+                                                      int32_t ga, int32_t gb, int32_t tie_rule, int32_t feas_mode,
+                                                      int32_t *order_out, int32_t *batch_end_out, double *F_out,
+                                                      int32_t *num_batches_out, int *buf0, int *buf1, int *by_o,
+                                                      long long *cumW, long long *cumS, long long *cumG,
                                                       int *batch_of, int *pos_w, int32_t *words)
 {
     __shared__ Lds L;
@@ -181,6 +184,7 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         L.carry_b = 0;
         cumW[0] = 0;
         cumS[0] = 0;
+        cumG[0] = 0;  // (cumG is cumS itself under the F-metric)
     }
     __syncthreads();
     for (int tile = 0; tile < n; tile += TPB) {
@@ -204,13 +208,18 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         if (tid == TPB - 1) { L.carry_a = w + offw; L.carry_b = q + offq; }
         __syncthreads();
     }
+    if (cumG != cumS) {  // sum of the effective lengths = ga (W - S) + gb S
+        __threadfence_block();
+        __syncthreads();
+        for (int i = tid; i <= n; i += TPB) cumG[i] = (long long)ga * (cumW[i] - cumS[i]) + (long long)gb * cumS[i];
+    }
     __threadfence_block();
 
     // ---- 4: batches
     int a = 0, nb = 0;
     while (a < n) {
         const int rem = n - a;
-        const long long W0 = cumW[a], S0 = cumS[a];
+        const long long W0 = cumW[a], S0 = cumS[a], G0 = cumG[a];
         // feasible extent K: the longest prefix within the budget (feasibility is monotone in k)
         int K = count_fitting(rem, [&](long long k) { return cumW[a + k] - W0; }, M);  // sum of peaks <= M
         if (feas_mode == KVSCHED_FEAS_PROFILE && K >= 1 && K < rem) {
@@ -233,7 +242,7 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         long long bS = 0;
         int bk = 0;
         for (int k = tid + 1; k <= K; k += TPB) {
-            const long long Sk = cumS[a + k] - S0;
+            const long long Sk = cumG[a + k] - G0;
             if (better(Sk, k, bS, bk, tie_rule)) { bS = Sk; bk = k; }
         }
         for (int d = 32; d > 0; d >>= 1) {
@@ -249,7 +258,7 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
             L.best_S = bS;
             L.best_k = bk;
             batch_end_out[nb] = a + bk;
-            F_out[nb] = (double)bS / ((double)bk * (double)bk);
+            F_out[nb] = (double)bS / ((double)gb * (double)bk * (double)bk);
         }
         __syncthreads();
         const int kstar = L.best_k;
@@ -281,22 +290,24 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
 size_t kvs_sortedF_scratch_bytes(int32_t n)
 {
     const size_t np = ((size_t)n + 64) & ~(size_t)63;
-    return np * (5 * sizeof(int) + 2 * sizeof(long long)) + 256;
+    return np * (5 * sizeof(int) + 3 * sizeof(long long)) + 256;
 }
 
-int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t tie_rule, int32_t feas_mode,
-                       int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
+int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
+                       int32_t tie_rule, int32_t feas_mode, int32_t *order_out, int32_t *batch_end_out, double *F_out, int32_t *num_batches_out,
                        void *scratch, int32_t *d_words, hipStream_t st)
 {
     const size_t np = ((size_t)n + 64) & ~(size_t)63;
     long long *cumW = (long long *)scratch;
     long long *cumS = cumW + np;
-    int *buf0 = (int *)(cumS + np);
+    long long *cumG = (ga == 0 && gb == 1) ? cumS : cumS + np;
+    int *buf0 = (int *)(cumS + 2 * np);
     int *buf1 = buf0 + np;
     int *by_o = buf1 + np;
     int *batch_of = by_o + np;
     int *pos_w = batch_of + np;
-    hipLaunchKernelGGL(sortedF_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, tie_rule, feas_mode, order_out,
-                       batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, batch_of, pos_w, d_words);
+    hipLaunchKernelGGL(sortedF_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, ga, gb, tie_rule, feas_mode,
+                       order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, cumG, batch_of,
+                       pos_w, d_words);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

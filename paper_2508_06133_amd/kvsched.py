@@ -23,6 +23,7 @@ PLANNER_ARRIVAL, PLANNER_SHORTEST_DECODE, PLANNER_FOOTPRINT, PLANNER_SORTED_F = 
 ONLINE_MAX_BACKLOG, ONLINE_MAX_WINDOW, ONLINE_MAX_O = 4096, 1024, 8192
 FEAS_SUM_OF_PEAKS, FEAS_PROFILE = 0, 1
 EXACT_MAX_N = 4096
+SOLVER_SORTED_PREFIX, SOLVER_LOCAL_SWAP, SOLVER_EXACT_DP = 0, 1, 2
 
 
 class KvschedError(RuntimeError):
@@ -56,6 +57,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
+    lib.kvsched_phase1_G.argtypes = [vp, i32, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
     lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.kvsched_online.argtypes = [vp, i32, vp, i32, vp, vp, vp, i64, i32, vp, i32, vp, vp]
@@ -209,6 +211,23 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_exact_dp")
         return order, ends, F, nb
+
+    def phase1_G(self, solver: int, s, o, M, alpha, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS):
+        """Phase 1 under G = sum (alpha s + o) / |X|^2, alpha = (num, den)
+        -> (order [n], batch_end [n], G [n], swaps [n], num_batches [1])."""
+        n = s.shape[0]
+        dev = s.device
+        order = torch.empty(n, dtype=torch.int32, device=dev)
+        ends = torch.zeros(n, dtype=torch.int32, device=dev)
+        G = torch.zeros(n, dtype=torch.float64, device=dev)
+        swaps = torch.zeros(n, dtype=torch.int32, device=dev)
+        nb = torch.zeros(1, dtype=torch.int32, device=dev)
+        rc = _lib.kvsched_phase1_G(self._h, int(solver), n, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
+                                   int(alpha[0]), int(alpha[1]), int(tie_rule), int(feas_mode), order.data_ptr(),
+                                   ends.data_ptr(), G.data_ptr(), swaps.data_ptr(), nb.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_phase1_G")
+        return order, ends, G, swaps, nb
 
     def best_neighbor(self, base_order, moves, s, o, M, want_tel: bool = True):
         """-> (tel [K] int64 or None, result [3] int64 = {best move, its TEL, TEL of base})."""
