@@ -6,7 +6,8 @@ library and its Python binding never do, and share no code with it.
 
   kvsched_oracle.c : Phase 2 of Algorithm 1 (literal and array-profile forms), sorted-prefix
                      Phase 1 with the F-metric, Phase 1 with Local Swap Search, Phase 1 with exact
-                     batches (Algorithm 2), position moves, best neighbour.
+                     batches (Algorithm 2), the same under the G metric, position moves, best neighbour,
+                     Phase 2 under predicted decode lengths (running estimates, ordered eviction).
   online_oracle.c  : scheduling under online arrivals (cached priority list, refresh triggers,
                      look-ahead window; FCFS / shortest-decode-first / footprint / Sorted-F-Online).
   exact.py         : Algorithm 2 (exact DP), subset / permutation / start-time brute force,
@@ -167,6 +168,29 @@ def best_neighbor(s, o, M, base, moves, literal: bool = False):
                                         _ptr(base, _i32p), _ptr(moves, _i32p), ctypes.c_int32(K),
                                         ctypes.c_int32(1 if literal else 0), _ptr(tel, _i64p), _ptr(res, _i64p)))
     return tel, (int(res[0]), int(res[1]), int(res[2]))
+
+
+def simulate_predicted(s, o, est0, M, order, literal: bool = False, max_runs: int = 0):
+    """Phase 2 under predicted decode lengths (running estimates, ordered eviction).
+    -> (p[n], c[n], TEL, evictions[n], runs[k, 4] = {request, start, end, 0 completed | 1 stopped})."""
+    s, o, est0, order = _i32(s), _i32(o), _i32(est0), _i32(order)
+    n = len(s)
+    if len(o) != n or len(est0) != n or len(order) != n:
+        raise OracleError("length mismatch")
+    p = np.zeros(n, dtype=np.int32)
+    c = np.zeros(n, dtype=np.int32)
+    ev = np.zeros(n, dtype=np.int32)
+    runs = np.zeros((max(max_runs, 1), 4), dtype=np.int32)
+    tel = ctypes.c_int64(0)
+    nr = ctypes.c_int32(0)
+    _check(_load().oracle_simulate_predicted(ctypes.c_int32(n), _ptr(s, _i32p), _ptr(o, _i32p), _ptr(est0, _i32p),
+                                             ctypes.c_int64(int(M)), _ptr(order, _i32p),
+                                             ctypes.c_int32(1 if literal else 0), _ptr(p, _i32p), _ptr(c, _i32p),
+                                             ctypes.byref(tel), _ptr(ev, _i32p), _ptr(runs, _i32p) if max_runs else None,
+                                             ctypes.c_int32(max_runs), ctypes.byref(nr)))
+    if max_runs and nr.value > max_runs:
+        raise OracleError("run log too small")
+    return p, c, int(tel.value), ev, runs[: nr.value].copy() if max_runs else None
 
 
 PLANNER_ARRIVAL, PLANNER_SHORTEST_DECODE, PLANNER_FOOTPRINT, PLANNER_SORTED_F = 0, 1, 2, 3

@@ -609,3 +609,144 @@ int oracle_simulate_many(int32_t n, const int32_t *s, const int32_t *o, int64_t 
     }
     return ORACLE_OK;
 }
+
+/* ------------------------------------- Phase 2 under predicted decode lengths (A_min / A_max) */
+
+/*
+ * Section 5, "Handling Prediction Uncertainty via Adaptive Output Length Refinement", and the
+ * appendix algorithm "Sorted-F + A_min".  The scheduler does not know o_i; it holds a running
+ * estimate e_i (started from est0_i: the lower bound l_i for A_min, the upper bound u_i for the
+ * conservative A_max, o_i itself for exact predictions) and runs Phase 2 with e_i in place of o_i:
+ *
+ * round t = 0, 1, 2, ...
+ *   1. a running request started at p has produced a = t - p tokens.  If a = o_i it has finished:
+ *      it leaves and c_i = t.  Otherwise it needs at least one more token: e_i <- max(e_i, a + 1).
+ *   2. admission: the requests that wait are taken in the order's sequence; one is started at t if,
+ *      with every running request j assumed to hold s_j + (tq - p_j) at the rounds
+ *      tq = p_j + 1 .. p_j + e_j and nothing afterwards, memory stays <= M at every future round;
+ *      the first that does not fit ends the round's admissions.
+ *   3. eviction: while that projected memory exceeds M at some future round, the running request of
+ *      least (e_i, i) is stopped: it loses what it has produced, keeps its e_i, and waits again at
+ *      its own place of the order.
+ * The paper's pseudo-code counts rounds from 1 and writes the update as max(e_i, t - p_i); with
+ * rounds from 0 and a request occupying the rounds p + 1 .. p + o (the convention used throughout
+ * this file) "has produced e_i tokens without completing" reads a + 1.
+ *
+ * literal != 0: the projected memory is re-summed from the running set for every future round;
+ * else it is kept in an array and adjusted when an estimate grows, a request finishes before its
+ * estimate, or one is stopped.
+ * Outputs: p_out / c_out [n] start and completion round of the run that completed; tel = sum c_i;
+ * evictions_out[i] = times request i was stopped; runs_out (may be NULL) receives up to max_runs
+ * rows {request, start round, end round, 0 completed | 1 stopped}, *n_runs_out their number.
+ */
+int oracle_simulate_predicted(int32_t n, const int32_t *s, const int32_t *o, const int32_t *est0, int64_t M,
+                              const int32_t *order, int32_t literal, int32_t *p_out, int32_t *c_out,
+                              int64_t *tel_out, int32_t *evictions_out, int32_t *runs_out, int32_t max_runs,
+                              int32_t *n_runs_out)
+{
+    if (oracle_check_instance(n, s, o, M) != ORACLE_OK) return ORACLE_EINVAL;
+    if (!is_permutation(n, order)) return ORACLE_EINVAL;
+    int64_t horizon = 4;
+    for (int32_t i = 0; i < n; ++i) {
+        if (est0[i] < 1 || (int64_t)s[i] + est0[i] > M) return ORACLE_EINVAL;
+        if (est0[i] > horizon) horizon = est0[i];
+        if (o[i] > horizon) horizon = o[i];
+    }
+    horizon += 2;  /* reservations never reach further ahead than the largest estimate */
+    int32_t *est = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
+    int32_t *state = (int32_t *)calloc((size_t)n + 1, sizeof(int32_t)); /* 0 waits, 1 runs, 2 done */
+    int64_t *p = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    int64_t *P = (int64_t *)calloc((size_t)horizon, sizeof(int64_t));  /* P[tq mod horizon], tq > t */
+    if (!est || !state || !p || !P) { free(est); free(state); free(p); free(P); return ORACLE_ENOMEM; }
+    memcpy(est, est0, sizeof(int32_t) * (size_t)n);
+    if (evictions_out) memset(evictions_out, 0, sizeof(int32_t) * (size_t)n);
+    int32_t done = 0, n_runs = 0;
+    int64_t tel = 0;
+#define PROJ(i, tq) (((tq) - p[i] >= 1 && (tq) - p[i] <= (int64_t)est[i]) ? (int64_t)s[i] + ((tq) - p[i]) : 0)
+#define LOG_RUN(i, end, kind)                                                              \
+    do {                                                                                   \
+        if (runs_out && n_runs < max_runs) {                                               \
+            runs_out[4 * n_runs] = (i); runs_out[4 * n_runs + 1] = (int32_t)p[i];          \
+            runs_out[4 * n_runs + 2] = (int32_t)(end); runs_out[4 * n_runs + 3] = (kind);  \
+        }                                                                                  \
+        ++n_runs;                                                                          \
+    } while (0)
+    for (int64_t t = 0; done < n; ++t) {
+        P[t % horizon] = 0;  /* round t is past */
+        /* 1. progress of the running requests */
+        for (int32_t i = 0; i < n; ++i) {
+            if (state[i] != 1) continue;
+            const int64_t a = t - p[i];
+            if (a == o[i]) {  /* finished; what it had reserved beyond this round is released */
+                if (!literal)
+                    for (int64_t tq = t + 1; tq <= p[i] + est[i]; ++tq) P[tq % horizon] -= s[i] + (tq - p[i]);
+                state[i] = 2;
+                ++done;
+                tel += t;
+                if (p_out) p_out[i] = (int32_t)p[i];
+                if (c_out) c_out[i] = (int32_t)t;
+                LOG_RUN(i, t, 0);
+            } else if (a + 1 > est[i]) {  /* still going: one more round is reserved */
+                est[i] = (int32_t)(a + 1);
+                if (!literal) P[(t + 1) % horizon] += s[i] + (a + 1);
+            }
+        }
+        /* 2. admission in the order's sequence */
+        for (int32_t k = 0; k < n; ++k) {
+            const int32_t r = order[k];
+            if (state[r] != 0) continue;
+            int feasible = 1;
+            if (literal) {
+                p[r] = t;
+                state[r] = 1;  /* tentatively */
+                for (int64_t tq = t + 1; tq < t + horizon && feasible; ++tq) {
+                    int64_t sum = 0;
+                    for (int32_t j = 0; j < n; ++j)
+                        if (state[j] == 1) sum += PROJ(j, tq);
+                    if (sum > M) feasible = 0;
+                }
+                if (!feasible) state[r] = 0;
+            } else {
+                for (int64_t j = 1; j <= est[r] && feasible; ++j)
+                    if (P[(t + j) % horizon] + s[r] + j > M) feasible = 0;
+                if (feasible) {
+                    for (int64_t j = 1; j <= est[r]; ++j) P[(t + j) % horizon] += s[r] + j;
+                    p[r] = t;
+                    state[r] = 1;
+                }
+            }
+            if (!feasible) break;
+        }
+        /* 3. eviction while the projection overflows */
+        for (;;) {
+            int over = 0;
+            for (int64_t tq = t + 1; tq < t + horizon && !over; ++tq) {
+                int64_t sum = 0;
+                if (literal) {
+                    for (int32_t j = 0; j < n; ++j)
+                        if (state[j] == 1) sum += PROJ(j, tq);
+                } else {
+                    sum = P[tq % horizon];
+                }
+                if (sum > M) over = 1;
+            }
+            if (!over) break;
+            int32_t victim = -1;
+            for (int32_t j = 0; j < n; ++j)
+                if (state[j] == 1 && (victim < 0 || est[j] < est[victim])) victim = j;
+            if (victim < 0) break;  /* cannot happen: an empty system holds nothing */
+            if (!literal)
+                for (int64_t tq = t + 1; tq <= p[victim] + est[victim]; ++tq)
+                    P[tq % horizon] -= s[victim] + (tq - p[victim]);
+            state[victim] = 0;
+            if (evictions_out) ++evictions_out[victim];
+            LOG_RUN(victim, t, 1);
+        }
+    }
+#undef PROJ
+#undef LOG_RUN
+    if (tel_out) *tel_out = tel;
+    if (n_runs_out) *n_runs_out = n_runs;
+    free(est); free(state); free(p); free(P);
+    return ORACLE_OK;
+}
