@@ -51,6 +51,7 @@ typedef struct kvsched_ctx kvsched_ctx;
 #define KVSCHED_DEV_BAD_ARRIVAL 16 /* kvsched_online: an arrival round is negative or out of order   */
 #define KVSCHED_DEV_BACKLOG 32     /* kvsched_online: more requests wait than the caller's backlog_cap   */
 #define KVSCHED_DEV_BAD_STREAM 64  /* kvsched_online: a stream descriptor is malformed or out of range */
+#define KVSCHED_DEV_ROUND_LIMIT 128 /* kvsched_simulate_predicted: a timeline passed 2^26 rounds          */
 
 #define KVSCHED_MOVE_SWAP 0   /* exchange the entries at positions i and j                  */
 #define KVSCHED_MOVE_INSERT 1 /* take the entry at position i out, put it back at position j */
@@ -137,6 +138,36 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
  * 16384: below that the rows do not fill the GPU twice and the second launch costs more than the
  * skipped positions save); 0 = never. */
 int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows);
+
+/*
+ * Phase 2 under predicted decode lengths (Section 5, "Handling Prediction Uncertainty via Adaptive
+ * Output Length Refinement"; appendix algorithm "Sorted-F + A_min") for C candidate orders at once.
+ * The scheduler does not see o_i: it holds a running estimate e_i, started from est0_i (the lower
+ * bound of the predicted interval for A_min, the upper bound for the conservative A_max, o_i itself
+ * for exact predictions), and at every round t
+ *   1. a running request that has produced a = t - p tokens leaves if a = o_i (c_i = t); otherwise
+ *      it needs at least one more token: e_i <- max(e_i, a + 1);
+ *   2. waiting requests are started in the row's sequence while memory, with every running request
+ *      j assumed to hold s_j + (tq - p_j) at rounds tq = p_j + 1 .. p_j + e_j and nothing afterwards,
+ *      stays <= M at every future round; the first that does not fit ends the round's admissions;
+ *   3. while that projection exceeds M, the running request of least (e_i, i) is stopped: it loses
+ *      what it has produced, keeps e_i, and waits again at its own place of the row.
+ * With est0 = o this is kvsched_simulate.  (The paper's pseudo-code counts rounds from 1 and writes
+ * the update as max(e_i, t - p_i); with rounds from 0 that is a + 1.)
+ *
+ *   orders          [C][n] int32 permutations, n <= 65535 and 20 n + 4 H <= 160 KB with H the power
+ *                   of two >= every o_i and est0_i
+ *   est0            [E][n] int32 by request id, 1 <= est0_i, s_i + est0_i <= M; E = 1 (one
+ *                   prediction for all rows) or E = C (row c is run under prediction c)
+ *   tel_out         [C] int64: sum of completion rounds, -1 for a faulty row
+ *   completion_out  [C][n] int32 by request id, or NULL
+ *   evictions_out   [C] int32 or NULL: times a request was stopped in row c
+ * The largest estimate is read back from the device (one host synchronisation) unless
+ * kvsched_set_o_max() gave a bound, which then covers estimates as well.
+ */
+int kvsched_simulate_predicted(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n, const int32_t *s,
+                               const int32_t *o, const int32_t *est0, int32_t E, int64_t M, int64_t *tel_out,
+                               int32_t *completion_out, int32_t *evictions_out, void *stream);
 
 /* For accounting of work: resume_pos_out[c] (device, [C] int32) = the position from which row c of
  * the LAST kvsched_simulate call on this context was placed (0 = from its first position; 64 b =

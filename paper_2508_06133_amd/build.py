@@ -18,7 +18,7 @@ import tempfile
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvsched.so")
-SOURCES = ["api.hip", "simulate.hip", "timeline_reg.hip", "sortedf.hip", "localswap.hip", "exactdp.hip", "horizon.hip", "permute.hip", "prefix.hip", "online.hip"]
+SOURCES = ["api.hip", "simulate.hip", "timeline_reg.hip", "sortedf.hip", "localswap.hip", "exactdp.hip", "horizon.hip", "permute.hip", "prefix.hip", "online.hip", "predicted.hip"]
 DEVICE_FLAGS = [
     "--offload-arch=gfx950",
     "-O3",

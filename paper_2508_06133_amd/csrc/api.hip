@@ -662,6 +662,35 @@ int kvsched_simulate_resume_positions(kvsched_ctx *ctx, int32_t C, int32_t *resu
     return kvs_launch_resume_plan(sorted, C, ctx->resume_first, blocks, resume_pos_out, st);
 }
 
+int kvsched_simulate_predicted(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n, const int32_t *s,
+                               const int32_t *o, const int32_t *est0, int32_t E, int64_t M, int64_t *tel_out,
+                               int32_t *completion_out, int32_t *evictions_out, void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!orders || !est0 || !tel_out || C < 1 || (E != 1 && E != C)) return KVSCHED_EINVAL;
+    if (n > 65535) return KVSCHED_ERANGE;
+    hipStream_t st = (hipStream_t)stream;
+    rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, ctx->o_max_bound, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    int32_t bound = ctx->o_max_bound;
+    if (bound <= 0) {
+        rc = kvs_launch_scan_estimates(est0, (size_t)E * (size_t)n, ctx->d_words, st);
+        if (rc != KVSCHED_OK) return rc;
+        rc = read_words(ctx, st);
+        if (rc != KVSCHED_OK) return rc;
+        bound = ctx->h_words[KVS_W_OMAX] > ctx->h_words[KVS_W_ESTMAX] ? ctx->h_words[KVS_W_OMAX]
+                                                                      : ctx->h_words[KVS_W_ESTMAX];
+    }
+    if (bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
+    const int32_t H = ring_slots_for(bound < 1 ? 1 : bound);
+    if (kvs_predicted_lds_bytes(n, H) > KVS_PREDICTED_MAX_LDS) return KVSCHED_ERANGE;
+    rc = kvs_launch_predicted(orders, C, n, s, o, est0, E, (int32_t)M, H, 1 << 26, tel_out, completion_out,
+                              evictions_out, ctx->d_words, st);
+    if (rc != KVSCHED_OK) return rc;
+    return kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
+}
+
 int kvsched_argmin(kvsched_ctx *ctx, const int64_t *tel, int32_t C, int64_t *result_out, void *stream)
 {
     if (!ctx || !tel || !result_out || C < 1) return KVSCHED_EINVAL;

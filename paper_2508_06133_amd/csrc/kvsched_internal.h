@@ -15,6 +15,7 @@ enum {
     KVS_W_KMAX = 4,    // exact DP: bound on the size of the next batch
     KVS_W_BESTK = 5,   // exact DP: best state of the batch in hand
     KVS_W_BESTM = 6,
+    KVS_W_ESTMAX = 7,  // largest initial estimate (kvsched_simulate_predicted)
     KVS_W_COUNT = 8
 };
 
@@ -139,6 +140,14 @@ int kvs_launch_horizon_advance(const int32_t *order, const int32_t *completion, 
 int kvs_launch_online(int32_t B, const int32_t *streams, int32_t N, const int32_t *a, const int32_t *s,
                       const int32_t *o, int32_t M, int32_t backlog_cap, int32_t ring_slots, int32_t *completion_out,
                       int32_t out_len, int64_t *stats_out, int32_t *d_words, hipStream_t st);
+
+// predicted.hip
+constexpr size_t KVS_PREDICTED_MAX_LDS = 160 * 1024;  // LDS of one workgroup on gfx950
+int kvs_launch_scan_estimates(const int32_t *est, size_t count, int32_t *d_words, hipStream_t st);
+size_t kvs_predicted_lds_bytes(int32_t n, int32_t H);
+int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int32_t *s, const int32_t *o,
+                         const int32_t *est0, int32_t E, int32_t M, int32_t H, int32_t round_limit, int64_t *tel_out,
+                         int32_t *completion_out, int32_t *evictions_out, int32_t *d_words, hipStream_t st);
 
 // prefix.hip
 int kvs_launch_moves_min_position(const int32_t *moves, int32_t K, int32_t n, int32_t *d_words, hipStream_t st);

@@ -1,0 +1,342 @@
+// Phase 2 under predicted decode lengths (Section 5, "Handling Prediction Uncertainty via Adaptive
+// Output Length Refinement"; appendix algorithm "Sorted-F + A_min"), many candidate orders at once,
+// one 64-lane wavefront per candidate.
+//
+// The scheduler does not know o_i.  It holds a running estimate e_i (started from the caller's
+// est0: lower bounds for A_min, upper bounds for the conservative A_max) and runs the admission
+// of Algorithm 1's Phase 2 on the memory the running requests are PROJECTED to hold; round t:
+//   1. a running request that has produced a = t - p tokens leaves if a = o_i, else needs one
+//      more: e_i <- max(e_i, a + 1);
+//   2. waiting requests are started in the order's sequence while the projection stays <= M;
+//   3. while the projection exceeds M, the running request of least (e_i, i) is stopped; it keeps
+//      e_i, loses its progress and waits again at its own place of the order.
+//
+// State of a candidate, all in LDS (one wavefront per workgroup, 20 n + 4 H bytes):
+//   * per position of the order: s, o, current estimate, start round (or waiting / done), id;
+//   * the projected memory of the requests that are still inside their estimate, as a ring of
+//     H >= max(estimate, o) slots (slot t is cleared at round t and then stands for round t + H);
+//   * the requests that have outrun their estimate are not in the ring: each of them reserves
+//     exactly the next round, s_j + (t + 1 - p_j), so two scalars (their count and the sum of
+//     s_j - p_j) give their share of round t + 1, and a round costs nothing per such request;
+//   * the running positions as a compact list; a request matters again only when it reaches its
+//     estimate or its true length, so the list is scanned only at the earliest such round.
+#include "kvsched_internal.h"
+
+#include <limits.h>
+
+namespace {
+
+constexpr int PW = 64;
+constexpr int P_WAITING = -1, P_DONE = -2;
+constexpr int EST_OVERRUN = 0;  // estimate field of a request that has outrun it: e = t - p + 1
+
+struct PredParams {
+    const int32_t *orders;  // [C][n]
+    int32_t C, n;
+    const int32_t *s, *o;
+    const int32_t *est0;  // [E][n]
+    int32_t E;
+    int32_t M;
+    int32_t H;            // ring slots: power of two >= every estimate and every o
+    int32_t round_limit;  // a run that lasts longer is reported, not continued
+    int64_t *tel_out;         // [C]
+    int32_t *completion_out;  // [C][n] by request id, or NULL
+    int32_t *evictions_out;   // [C] or NULL
+    int32_t *d_words;
+};
+
+__device__ __forceinline__ int p_uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ void p_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ int p_wave_min(int v)
+{
+    for (int d = 32; d >= 1; d >>= 1) v = min(v, __shfl_xor(v, d));
+    return p_uni(v);
+}
+
+__global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
+{
+    extern __shared__ int lds[];
+    const int lane = threadIdx.x;
+    const int cand = blockIdx.x;
+    const int n = p.n, M = p.M, H = p.H, HM = H - 1;
+    int *ring = lds;
+    int *S = ring + H;
+    int *O = S + n;
+    int *EST = O + n;
+    int *PS = EST + n;  // start round of a running position, P_WAITING, P_DONE
+    unsigned short *ID = (unsigned short *)(PS + n);
+    unsigned short *ACT = ID + ((n + 1) & ~1);  // running positions, unordered
+
+    const int32_t *row = p.orders + (size_t)cand * (size_t)n;
+    const int32_t *est0 = p.est0 + (p.E > 1 ? (size_t)cand * (size_t)n : 0);
+    int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n : nullptr;
+
+    for (int i = lane; i < H; i += PW) ring[i] = 0;
+    int bad = 0;
+    for (int k = lane; k < n; k += PW) {
+        const int id = min(max(row[k], 0), n - 1);
+        const int sv = p.s[id], ov = p.o[id], ev = est0[id];
+        if (sv < 1 || ov < 1 || ev < 1 || ov > H || ev > H || (long long)sv + ov > (long long)M ||
+            (long long)sv + ev > (long long)M)
+            bad = 1;
+        S[k] = sv;
+        O[k] = ov;
+        EST[k] = ev;
+        PS[k] = P_WAITING;
+        ID[k] = (unsigned short)id;
+    }
+    if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever
+        if (lane == 0) {
+            p.tel_out[cand] = -1;
+            if (p.evictions_out) p.evictions_out[cand] = 0;
+            atomicOr(&p.d_words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+        }
+        return;
+    }
+    p_sync();
+
+    int t = 0;
+    int head = 0;      // no waiting position lies before it
+    int nact = 0;      // entries of ACT
+    int done = 0;
+    int ov_cnt = 0;    // requests past their estimate ...
+    long long ov_sp = 0;  // ... and the sum of s_j - p_j over them
+    int next_due = INT_MAX;  // earliest round at which a running request reaches its estimate or its end
+    int evictions = 0;
+    long long tel = 0;
+    bool over_limit = false;
+
+    while (done < n) {
+        if (t >= p.round_limit) { over_limit = true; break; }
+        // nothing waits, nobody outruns an estimate: nothing can happen before the next due round
+        if (head >= n && ov_cnt == 0 && next_due > t) {
+            const int span = min(next_due - t, H);
+            for (int i = lane; i < span; i += PW) ring[(t + i) & HM] = 0;
+            t = next_due;
+            p_sync();
+        }
+        if (lane == 0) ring[t & HM] = 0;  // round t is past
+        p_sync();
+
+        // ---- 1. running requests that reach their estimate or their end at this round
+        if (t >= next_due) {
+            int due_min = INT_MAX;
+            int keep_base = 0;  // ACT is compacted in place: entries kept so far
+            for (int a0 = 0; a0 < nact; a0 += PW) {
+                const int a = a0 + lane;
+                const bool in = a < nact;
+                const int pos = in ? ACT[a] : 0;
+                const int ps = in ? PS[pos] : 0, ov = in ? O[pos] : 0, ev = in ? EST[pos] : 0, sv = in ? S[pos] : 0;
+                const int prod = t - ps;
+                const bool fin = in && prod == ov;
+                const bool expire = in && !fin && ev != EST_OVERRUN && prod == ev;  // goes on past its estimate
+                // finished: completion round, and what it had reserved beyond this round is released
+                unsigned long long fin_mask = __builtin_amdgcn_ballot_w64(fin);
+                if (fin) {
+                    PS[pos] = P_DONE;
+                    if (crow) crow[ID[pos]] = t;
+                }
+                const int nfin = __popcll(fin_mask);
+                done += nfin;
+                tel += (long long)nfin * t;
+                const unsigned long long fin_ov = __builtin_amdgcn_ballot_w64(fin && ev == EST_OVERRUN);
+                ov_cnt -= __popcll(fin_ov);
+                {
+                    long long d = (fin && ev == EST_OVERRUN) ? (long long)sv - ps : 0;
+                    for (int dd = 32; dd >= 1; dd >>= 1) d += __shfl_xor(d, dd);
+                    ov_sp -= (long long)(((unsigned long long)(unsigned)p_uni((int)(unsigned)(d >> 32)) << 32) |
+                                         (unsigned)p_uni((int)(unsigned)d));
+                }
+                unsigned long long early = __builtin_amdgcn_ballot_w64(fin && ev != EST_OVERRUN && ev > ov);
+                while (early != 0) {  // over-estimated: rounds t+1 .. p + e were reserved for it
+                    const int l = __builtin_ctzll(early);
+                    early &= early - 1;
+                    const int ps_l = __builtin_amdgcn_readlane(ps, l), ev_l = __builtin_amdgcn_readlane(ev, l);
+                    const int sv_l = __builtin_amdgcn_readlane(sv, l);
+                    for (int tq = t + 1 + lane; tq <= ps_l + ev_l; tq += PW) ring[tq & HM] -= sv_l + (tq - ps_l);
+                }
+                // past its estimate: from now on it reserves the next round only
+                const unsigned long long exp_mask = __builtin_amdgcn_ballot_w64(expire);
+                if (expire) EST[pos] = EST_OVERRUN;
+                ov_cnt += __popcll(exp_mask);
+                {
+                    long long d = expire ? (long long)sv - ps : 0;
+                    for (int dd = 32; dd >= 1; dd >>= 1) d += __shfl_xor(d, dd);
+                    ov_sp += (long long)(((unsigned long long)(unsigned)p_uni((int)(unsigned)(d >> 32)) << 32) |
+                                         (unsigned)p_uni((int)(unsigned)d));
+                }
+                // the rest stays; when is it due next?
+                const bool keep = in && !fin;
+                const bool overrun = keep && (ev == EST_OVERRUN || expire);
+                if (keep) due_min = min(due_min, ps + (overrun ? ov : min(ev, ov)));
+                const unsigned long long keep_mask = __builtin_amdgcn_ballot_w64(keep);
+                p_sync();  // every lane has read its ACT entry of this tile
+                if (keep) ACT[keep_base + __popcll(keep_mask & ((1ull << lane) - 1ull))] = (unsigned short)pos;
+                keep_base += __popcll(keep_mask);
+                p_sync();
+            }
+            nact = keep_base;
+            next_due = p_wave_min(due_min);
+        }
+
+        // ---- 2. admission in the order's sequence
+        const int ov_next = (int)(ov_sp + (long long)ov_cnt * (t + 1));  // the overrunners' share of round t + 1
+        while (head < n) {
+            // first waiting position at or after head
+            int pos = -1;
+            for (int k0 = head; k0 < n && pos < 0; k0 += PW) {
+                const int k = k0 + lane;
+                const unsigned long long w = __builtin_amdgcn_ballot_w64(k < n && PS[k] == P_WAITING);
+                if (w != 0) pos = k0 + __builtin_ctzll(w);
+            }
+            if (pos < 0) { head = n; break; }
+            head = pos;
+            const int sv = p_uni(S[pos]), ev = p_uni(EST[pos]), ov = p_uni(O[pos]);
+            bool viol = false;
+            for (int j = lane + 1; j <= ev; j += PW) viol |= ring[(t + j) & HM] + (j == 1 ? ov_next : 0) + sv + j > M;
+            if (__builtin_amdgcn_ballot_w64(viol) != 0) break;
+            for (int j = lane + 1; j <= ev; j += PW) ring[(t + j) & HM] += sv + j;
+            if (lane == 0) {
+                PS[pos] = t;
+                ACT[nact] = (unsigned short)pos;
+            }
+            ++nact;
+            next_due = min(next_due, t + min(ev, ov));
+            head = pos + 1;
+            p_sync();
+        }
+
+        // ---- 3. eviction while round t + 1 is projected above M (only that round can be: the ring
+        //         held a feasible projection and only the overrunners' reservations are new)
+        if (ov_cnt > 0) {
+            p_sync();
+            while (p_uni(ring[(t + 1) & HM]) + (int)(ov_sp + (long long)ov_cnt * (t + 1)) > M) {
+                int best = INT_MAX;  // (current estimate, id) of the running requests, least first
+                for (int a0 = 0; a0 < nact; a0 += PW) {
+                    const int a = a0 + lane;
+                    if (a < nact) {
+                        const int pos = ACT[a];
+                        const int ev = EST[pos];
+                        const int cur = ev == EST_OVERRUN ? t - PS[pos] + 1 : ev;
+                        best = min(best, (cur << 16) | (int)ID[pos]);
+                    }
+                }
+                best = p_wave_min(best);
+                if (best == INT_MAX) break;  // cannot happen: an empty system holds nothing
+                // find it in the list again (ids of a permutation are distinct)
+                int slot = -1, vpos = -1;
+                for (int a0 = 0; a0 < nact && slot < 0; a0 += PW) {
+                    const int a = a0 + lane;
+                    bool hit = false;
+                    int pos = 0;
+                    if (a < nact) {
+                        pos = ACT[a];
+                        const int ev = EST[pos];
+                        const int cur = ev == EST_OVERRUN ? t - PS[pos] + 1 : ev;
+                        hit = ((cur << 16) | (int)ID[pos]) == best;
+                    }
+                    const unsigned long long m = __builtin_amdgcn_ballot_w64(hit);
+                    if (m != 0) {
+                        const int l = __builtin_ctzll(m);
+                        slot = a0 + l;
+                        vpos = __builtin_amdgcn_readlane(pos, l);
+                    }
+                }
+                if (slot < 0) break;
+                const int ps = p_uni(PS[vpos]), ev = p_uni(EST[vpos]), sv = p_uni(S[vpos]);
+                if (ev == EST_OVERRUN) {
+                    --ov_cnt;
+                    ov_sp -= (long long)sv - ps;
+                } else {
+                    for (int tq = t + 1 + lane; tq <= ps + ev; tq += PW) ring[tq & HM] -= sv + (tq - ps);
+                }
+                p_sync();
+                if (lane == 0) {
+                    if (ev == EST_OVERRUN) EST[vpos] = t - ps + 1;  // what it is known to need
+                    PS[vpos] = P_WAITING;
+                    ACT[slot] = ACT[nact - 1];
+                }
+                --nact;
+                head = min(head, vpos);
+                ++evictions;
+                p_sync();
+            }
+        }
+        ++t;
+    }
+
+    if (lane == 0) {
+        if (over_limit) {
+            p.tel_out[cand] = -1;
+            atomicOr(&p.d_words[KVS_W_STATUS], KVSCHED_DEV_ROUND_LIMIT);
+        } else {
+            p.tel_out[cand] = tel;
+        }
+        if (p.evictions_out) p.evictions_out[cand] = evictions;
+    }
+}
+
+__global__ __launch_bounds__(1024) void scan_estimates_kernel(const int32_t *est, size_t count, int32_t *words)
+{
+    __shared__ int sh[16];
+    int mx = 0;
+    for (size_t i = threadIdx.x; i < count; i += 1024) mx = max(mx, est[i]);
+    for (int d = 32; d >= 1; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) mx = max(mx, sh[w]);
+        words[KVS_W_ESTMAX] = mx;
+    }
+}
+
+}  // namespace
+
+int kvs_launch_scan_estimates(const int32_t *est, size_t count, int32_t *d_words, hipStream_t st)
+{
+    hipLaunchKernelGGL(scan_estimates_kernel, dim3(1), dim3(1024), 0, st, est, count, d_words);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+size_t kvs_predicted_lds_bytes(int32_t n, int32_t H)
+{
+    return sizeof(int) * ((size_t)H + 4 * (size_t)n) + sizeof(unsigned short) * (2 * (((size_t)n + 1) & ~(size_t)1));
+}
+
+int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int32_t *s, const int32_t *o,
+                         const int32_t *est0, int32_t E, int32_t M, int32_t H, int32_t round_limit, int64_t *tel_out,
+                         int32_t *completion_out, int32_t *evictions_out, int32_t *d_words, hipStream_t st)
+{
+    const size_t bytes = kvs_predicted_lds_bytes(n, H);
+    if (bytes > KVS_PREDICTED_MAX_LDS || n > 65535) return KVSCHED_ERANGE;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)predicted_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)KVS_PREDICTED_MAX_LDS) != hipSuccess)
+            return KVSCHED_EHIP;
+        attr_set = true;
+    }
+    PredParams p;
+    p.orders = orders;
+    p.C = C;
+    p.n = n;
+    p.s = s;
+    p.o = o;
+    p.est0 = est0;
+    p.E = E;
+    p.M = M;
+    p.H = H;
+    p.round_limit = round_limit;
+    p.tel_out = tel_out;
+    p.completion_out = completion_out;
+    p.evictions_out = evictions_out;
+    p.d_words = d_words;
+    hipLaunchKernelGGL(predicted_kernel, dim3((unsigned)C), dim3(PW), bytes, st, p);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}

@@ -18,7 +18,7 @@ OK = 0
 TIE_LARGER, TIE_SMALLER = 0, 1
 MOVE_SWAP, MOVE_INSERT = 0, 1
 DEV_BAD_LENGTH, DEV_BAD_ORDER, DEV_BAD_MOVE, DEV_O_MAX = 1, 2, 4, 8
-DEV_BAD_ARRIVAL, DEV_BACKLOG, DEV_BAD_STREAM = 16, 32, 64
+DEV_BAD_ARRIVAL, DEV_BACKLOG, DEV_BAD_STREAM, DEV_ROUND_LIMIT = 16, 32, 64, 128
 PLANNER_ARRIVAL, PLANNER_SHORTEST_DECODE, PLANNER_FOOTPRINT, PLANNER_SORTED_F = 0, 1, 2, 3
 ONLINE_MAX_BACKLOG, ONLINE_MAX_WINDOW, ONLINE_MAX_O = 4096, 1024, 8192
 FEAS_SUM_OF_PEAKS, FEAS_PROFILE = 0, 1
@@ -57,6 +57,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
+    lib.kvsched_simulate_predicted.argtypes = [vp, vp, i32, i32, vp, vp, vp, i32, i64, vp, vp, vp, vp]
     lib.kvsched_phase1_G.argtypes = [vp, i32, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
     lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
@@ -211,6 +212,23 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_exact_dp")
         return order, ends, F, nb
+
+    def simulate_predicted(self, orders, s, o, est0, M, completions: bool = True):
+        """Phase 2 under predicted decode lengths.  orders [C, n]; est0 [n] or [C, n] initial estimates
+        -> (tel [C] int64, completion [C, n] int32 or None, evictions [C] int32)."""
+        C, n = orders.shape
+        dev = orders.device
+        E = 1 if est0.dim() == 1 else est0.shape[0]
+        tel = torch.empty(C, dtype=torch.int64, device=dev)
+        comp = torch.empty((C, n), dtype=torch.int32, device=dev) if completions else None
+        ev = torch.empty(C, dtype=torch.int32, device=dev)
+        rc = _lib.kvsched_simulate_predicted(self._h, _dev(orders, torch.int32, "orders"), C, n,
+                                             _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"),
+                                             _dev(est0, torch.int32, "est0"), E, int(M), tel.data_ptr(),
+                                             comp.data_ptr() if comp is not None else None, ev.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_simulate_predicted")
+        return tel, comp, ev
 
     def phase1_G(self, solver: int, s, o, M, alpha, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS):
         """Phase 1 under G = sum (alpha s + o) / |X|^2, alpha = (num, den)

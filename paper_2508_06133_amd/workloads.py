@@ -230,3 +230,19 @@ def online_instance(seed: int, rho: float, T: int = ONLINE_T, M: int = ONLINE_M,
     a = np.repeat(np.arange(T, dtype=np.int32), counts).astype(np.int32)
     s, o = _online_lengths(rng, a.shape[0], long_frac)
     return a, s, o, M
+
+
+# ------------------------------------------------------------- predicted decode lengths
+
+def prediction_intervals(seed: int, s: np.ndarray, o: np.ndarray, M: int, gamma: float):
+    """Interval predictions [lower_i, upper_i] around the true decode lengths (Section 5,
+    "Prediction Model": o_i in [l_i, u_i], gamma = inf l_i / u_i): l_i = ceil(a_i o_i) and
+    u_i = floor(o_i / b_i) with a_i, b_i uniform in [sqrt(gamma), 1], u_i capped so that
+    s_i + u_i <= M.  -> (lower, upper) int32."""
+    rng = np.random.default_rng(SEED0 + 9000 + seed)
+    g = float(np.sqrt(gamma))
+    a = rng.uniform(g, 1.0, o.shape[0])
+    b = rng.uniform(g, 1.0, o.shape[0])
+    lower = np.maximum(1, np.ceil(a * o)).astype(np.int64)
+    upper = np.minimum(np.floor(o / b), np.asarray(M, dtype=np.int64) - s).astype(np.int64)
+    return np.minimum(lower, o).astype(np.int32), np.maximum(upper, o).astype(np.int32)
