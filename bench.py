@@ -137,6 +137,84 @@ def bench_online(args, ctx, dev) -> int:
     return 0
 
 
+def bench_predicted(args, ctx, dev) -> int:
+    """One step = Phase 1 on the lower bounds + the 16384 config-3 candidate orders run under
+    predicted decode lengths (running estimates from the lower bounds, ordered eviction) + argmin."""
+    import torch
+
+    from paper_2508_06133_amd import workloads
+
+    inst = workloads.instance(CFG)
+    n, M = inst.n, inst.M
+    lower, upper = workloads.prediction_intervals(CFG, inst.s, inst.o, M, args.gamma)
+    s = torch.from_numpy(inst.s).to(dev)
+    o = torch.from_numpy(inst.o).to(dev)
+    lo = torch.from_numpy(lower).to(dev)
+    order_d, _, _, nb_d = ctx.sortedF(s, lo, M)  # the scheduler sees only the predictions
+    torch.cuda.synchronize()
+    rows_h = workloads.candidates(CFG, order_d.cpu().numpy())
+    C = rows_h.shape[0]
+    orders = torch.from_numpy(rows_h).to(dev)
+    ctx.set_o_max(int(max(inst.o.max(), lower.max())))
+    best = torch.empty(2, dtype=torch.int64, device=dev)
+    out = {}
+
+    def step():
+        ctx.sortedF(s, lo, M)
+        out["r"] = ctx.simulate_predicted(orders, s, o, lo, M)
+        ctx.argmin(out["r"][0], result_out=best)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if ctx.device_status() != 0:
+        print("bench.py: device status", ctx.device_status(), file=sys.stderr)
+        return 1
+    tel, comp, ev = out["r"]
+    tel_h = tel.cpu().numpy()
+    result = {
+        "metric": "candidate schedules evaluated/s under predicted decode lengths (n=2000 mixed)",
+        "value": C * args.steps / wall,
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": f"config 3 candidates (n={n}, M={M}, C={C}) under interval predictions, gamma={args.gamma}, "
+                               "estimates started from the lower bounds", "n": n, "M": M, "C": C},
+        "mean_evictions_per_candidate": float(ev.float().mean().item()),
+        "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
+        "roofline": None,  # a round-by-round event loop per candidate: latency- and LDS-capacity-bound
+    }
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure; only this baseline leg uses it
+
+        rows_cpu = min(args.cpu_rows, 128)
+        t0 = time.perf_counter()
+        for c in range(rows_cpu):
+            _, c_o, tel_o, ev_o, _ = oracle.simulate_predicted(inst.s, inst.o, lower, M, rows_h[c])
+            if tel_o != tel_h[c]:
+                print("bench.py: GPU and oracle disagree on row", c, file=sys.stderr)
+                return 1
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": rows_cpu / cpu_s, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"first {rows_cpu} of the {C} candidate rows (oracle_simulate_predicted, "
+                                            f"array form), single thread, {cpu_s:.1f} s"}
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,9 +224,12 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=8192, help="candidate rows the CPU oracle is timed on")
     ap.add_argument("--phase1", choices=("sorted_prefix", "local_swap"), default="sorted_prefix",
                     help="Phase-1 solver run inside the step (the candidate set is always built around the sorted-prefix order)")
-    ap.add_argument("--workload", choices=("config3", "online"), default="config3",
+    ap.add_argument("--workload", choices=("config3", "online", "predicted"), default="config3",
                     help="config3: the headline workload; online: the paper's Poisson-arrival experiment "
-                         "(Section 7) as a batch of independent streams through kvsched_online")
+                         "(Section 7) as a batch of independent streams through kvsched_online; predicted: the "
+                         "config-3 candidates run under interval predictions of the decode lengths "
+                         "(kvsched_simulate_predicted, estimates started from the lower bounds)")
+    ap.add_argument("--gamma", type=float, default=0.6, help="prediction confidence inf l_i / u_i of --workload predicted")
     ap.add_argument("--online-seeds", type=int, default=200,
                     help="arrival sequences per load level of the online workload (10 loads x 3 policies each)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -171,6 +252,8 @@ def main() -> int:
     ctx = kvsched.Context(0)
     if args.workload == "online":
         return bench_online(args, ctx, dev)
+    if args.workload == "predicted":
+        return bench_predicted(args, ctx, dev)
 
     inst = workloads.instance(CFG)
     n, M = inst.n, inst.M

@@ -103,6 +103,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
 
     int t = 0;
     int head = 0;      // no waiting position lies before it
+    int hpos = -1, hs = 0, he = 0, ho = 0;  // the waiting position the admission is stuck at, if any, with its s, e, o
     int nact = 0;      // entries of ACT
     int done = 0;
     int ov_cnt = 0;    // requests past their estimate ...
@@ -187,28 +188,56 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
 
         // ---- 2. admission in the order's sequence
         const int ov_next = (int)(ov_sp + (long long)ov_cnt * (t + 1));  // the overrunners' share of round t + 1
+        int t_skip = t + 1;  // the next round at which anything can happen
         while (head < n) {
-            // first waiting position at or after head
-            int pos = -1;
-            for (int k0 = head; k0 < n && pos < 0; k0 += PW) {
-                const int k = k0 + lane;
-                const unsigned long long w = __builtin_amdgcn_ballot_w64(k < n && PS[k] == P_WAITING);
-                if (w != 0) pos = k0 + __builtin_ctzll(w);
+            if (hpos < 0) {  // first waiting position at or after head; kept while it stays blocked
+                for (int k0 = head; k0 < n && hpos < 0; k0 += PW) {
+                    const int k = k0 + lane;
+                    const unsigned long long w = __builtin_amdgcn_ballot_w64(k < n && PS[k] == P_WAITING);
+                    if (w != 0) hpos = k0 + __builtin_ctzll(w);
+                }
+                if (hpos < 0) { head = n; break; }
+                head = hpos;
+                hs = p_uni(S[hpos]);
+                he = p_uni(EST[hpos]);
+                ho = p_uni(O[hpos]);
             }
-            if (pos < 0) { head = n; break; }
-            head = pos;
-            const int sv = p_uni(S[pos]), ev = p_uni(EST[pos]), ov = p_uni(O[pos]);
-            bool viol = false;
-            for (int j = lane + 1; j <= ev; j += PW) viol |= ring[(t + j) & HM] + (j == 1 ? ov_next : 0) + sv + j > M;
-            if (__builtin_amdgcn_ballot_w64(viol) != 0) break;
-            for (int j = lane + 1; j <= ev; j += PW) ring[(t + j) & HM] += sv + j;
+            if (ov_cnt == 0) {
+                // Nobody outruns an estimate, so until the next due round the projection does not
+                // change: look for the earliest start from t on.  Round tq rules out the starts
+                // t' < tq with t' < ring(tq) + s + tq - M; rounds more than H ahead hold nothing.
+                // Each turn moves the start to the largest bound seen and looks only at the rounds
+                // that entered the window (t', t' + e] since.
+                int start = t, lo = t + 1;
+                const int bias = hs - M;
+                for (;;) {
+                    const int hi = min(start + he, t + H);
+                    int acc = INT_MIN;
+                    for (int tq = lo + lane; tq <= hi; tq += PW) acc = max(acc, min(tq, ring[tq & HM] + bias + tq));
+                    const int bound = -p_wave_min(-max(acc, INT_MIN + 1));
+                    if (bound <= start) break;  // fits at `start`
+                    start = bound;
+                    lo = hi + 1;
+                    if (start >= next_due) break;  // the running set changes first
+                }
+                if (start > t) {  // blocked now; nothing happens before min(start, next_due)
+                    t_skip = min(start, next_due);
+                    break;
+                }
+            } else {
+                bool viol = false;
+                for (int j = lane + 1; j <= he; j += PW) viol |= ring[(t + j) & HM] + (j == 1 ? ov_next : 0) + hs + j > M;
+                if (__builtin_amdgcn_ballot_w64(viol) != 0) break;
+            }
+            for (int j = lane + 1; j <= he; j += PW) ring[(t + j) & HM] += hs + j;
             if (lane == 0) {
-                PS[pos] = t;
-                ACT[nact] = (unsigned short)pos;
+                PS[hpos] = t;
+                ACT[nact] = (unsigned short)hpos;
             }
             ++nact;
-            next_due = min(next_due, t + min(ev, ov));
-            head = pos + 1;
+            next_due = min(next_due, t + min(he, ho));
+            head = hpos + 1;
+            hpos = -1;
             p_sync();
         }
 
@@ -263,12 +292,20 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                     ACT[slot] = ACT[nact - 1];
                 }
                 --nact;
-                head = min(head, vpos);
+                if (vpos < head) { head = vpos; hpos = -1; }
                 ++evictions;
                 p_sync();
             }
         }
-        ++t;
+        // rounds t + 1 .. t_skip - 1 change nothing (set only while nobody outruns an estimate)
+        if (t_skip > t + 1 && ov_cnt == 0) {
+            const int span = min(t_skip - t - 1, H);
+            for (int i = lane; i < span; i += PW) ring[(t + 1 + i) & HM] = 0;
+            t = t_skip;
+            p_sync();
+        } else {
+            ++t;
+        }
     }
 
     if (lane == 0) {
