@@ -155,7 +155,7 @@ int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows);
  * With est0 = o this is kvsched_simulate.  (The paper's pseudo-code counts rounds from 1 and writes
  * the update as max(e_i, t - p_i); with rounds from 0 that is a + 1.)
  *
- *   orders          [C][n] int32 permutations, n <= 65535 and 20 n + 4 H <= 160 KB with H the power
+ *   orders          [C][n] int32 permutations, n <= 65535 and 16 n + 4 H <= 160 KB with H the power
  *                   of two >= every o_i and est0_i
  *   est0            [E][n] int32 by request id, 1 <= est0_i, s_i + est0_i <= M; E = 1 (one
  *                   prediction for all rows) or E = C (row c is run under prediction c)

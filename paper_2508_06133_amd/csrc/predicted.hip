@@ -11,7 +11,7 @@
 //   3. while the projection exceeds M, the running request of least (e_i, i) is stopped; it keeps
 //      e_i, loses its progress and waits again at its own place of the order.
 //
-// State of a candidate, all in LDS (one wavefront per workgroup, 20 n + 4 H bytes):
+// State of a candidate, all in LDS (one wavefront per workgroup, 16 n + 4 H bytes):
 //   * per position of the order: s, o, current estimate, start round (or waiting / done), id;
 //   * the projected memory of the requests that are still inside their estimate, as a ring of
 //     H >= max(estimate, o) slots (slot t is cleared at round t and then stands for round t + H);
@@ -66,12 +66,13 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     const int cand = blockIdx.x;
     const int n = p.n, M = p.M, H = p.H, HM = H - 1;
     int *ring = lds;
+    const int n2 = (n + 1) & ~1;
     int *S = ring + H;
-    int *O = S + n;
-    int *EST = O + n;
-    int *PS = EST + n;  // start round of a running position, P_WAITING, P_DONE
-    unsigned short *ID = (unsigned short *)(PS + n);
-    unsigned short *ACT = ID + ((n + 1) & ~1);  // running positions, unordered
+    int *PS = S + n;  // start round of a running position, P_WAITING, P_DONE
+    unsigned short *O = (unsigned short *)(PS + n);  // lengths and estimates are at most 16384
+    unsigned short *EST = O + n2;
+    unsigned short *ID = EST + n2;
+    unsigned short *ACT = ID + n2;  // running positions, unordered
 
     const int32_t *row = p.orders + (size_t)cand * (size_t)n;
     const int32_t *est0 = p.est0 + (p.E > 1 ? (size_t)cand * (size_t)n : 0);
@@ -86,8 +87,8 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
             (long long)sv + ev > (long long)M)
             bad = 1;
         S[k] = sv;
-        O[k] = ov;
-        EST[k] = ev;
+        O[k] = (unsigned short)ov;
+        EST[k] = (unsigned short)ev;
         PS[k] = P_WAITING;
         ID[k] = (unsigned short)id;
     }
@@ -125,65 +126,68 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         if (lane == 0) ring[t & HM] = 0;  // round t is past
         p_sync();
 
-        // ---- 1. running requests that reach their estimate or their end at this round
+        // ---- 1. running requests that reach their estimate or their end at this round.  A light
+        //         pass finds them (usually one or two) and the next due round of the others; each
+        //         is then handled by the whole wavefront; finished ones leave the list in a second pass.
         if (t >= next_due) {
-            int due_min = INT_MAX;
-            int keep_base = 0;  // ACT is compacted in place: entries kept so far
+            int due_min = INT_MAX;  // per lane: over the entries that stay as they are
+            int due_new = INT_MAX;  // uniform: over the entries that started to overrun
+            int removed = 0;
             for (int a0 = 0; a0 < nact; a0 += PW) {
                 const int a = a0 + lane;
                 const bool in = a < nact;
                 const int pos = in ? ACT[a] : 0;
-                const int ps = in ? PS[pos] : 0, ov = in ? O[pos] : 0, ev = in ? EST[pos] : 0, sv = in ? S[pos] : 0;
-                const int prod = t - ps;
-                const bool fin = in && prod == ov;
-                const bool expire = in && !fin && ev != EST_OVERRUN && prod == ev;  // goes on past its estimate
-                // finished: completion round, and what it had reserved beyond this round is released
-                unsigned long long fin_mask = __builtin_amdgcn_ballot_w64(fin);
-                if (fin) {
-                    PS[pos] = P_DONE;
-                    if (crow) crow[ID[pos]] = t;
+                const int ps = in ? PS[pos] : 0, ov = in ? O[pos] : 0, ev = in ? EST[pos] : 0;
+                const int due = ps + (ev == EST_OVERRUN ? ov : min(ev, ov));
+                const bool now = in && due <= t;
+                if (in && !now) due_min = min(due_min, due);
+                unsigned long long m = __builtin_amdgcn_ballot_w64(now);
+                while (m != 0) {
+                    const int l = __builtin_ctzll(m);
+                    m &= m - 1;
+                    const int pos_l = __builtin_amdgcn_readlane(pos, l), ps_l = __builtin_amdgcn_readlane(ps, l);
+                    const int ov_l = __builtin_amdgcn_readlane(ov, l), ev_l = __builtin_amdgcn_readlane(ev, l);
+                    const int sv_l = p_uni(S[pos_l]);
+                    if (t - ps_l == ov_l) {  // finished
+                        if (lane == 0) {
+                            PS[pos_l] = P_DONE;
+                            if (crow) crow[ID[pos_l]] = t;
+                            ACT[a0 + l] = 0xffff;  // leaves the list
+                        }
+                        ++done;
+                        ++removed;
+                        tel += t;
+                        if (ev_l == EST_OVERRUN) {
+                            --ov_cnt;
+                            ov_sp -= (long long)sv_l - ps_l;
+                        } else {  // over-estimated: rounds t+1 .. p + e were reserved for it
+                            for (int tq = t + 1 + lane; tq <= ps_l + ev_l; tq += PW) ring[tq & HM] -= sv_l + (tq - ps_l);
+                        }
+                    } else {  // goes on past its estimate: from now on it reserves the next round only
+                        if (lane == 0) EST[pos_l] = EST_OVERRUN;
+                        ++ov_cnt;
+                        ov_sp += (long long)sv_l - ps_l;
+                        due_new = min(due_new, ps_l + ov_l);
+                    }
                 }
-                const int nfin = __popcll(fin_mask);
-                done += nfin;
-                tel += (long long)nfin * t;
-                const unsigned long long fin_ov = __builtin_amdgcn_ballot_w64(fin && ev == EST_OVERRUN);
-                ov_cnt -= __popcll(fin_ov);
-                {
-                    long long d = (fin && ev == EST_OVERRUN) ? (long long)sv - ps : 0;
-                    for (int dd = 32; dd >= 1; dd >>= 1) d += __shfl_xor(d, dd);
-                    ov_sp -= (long long)(((unsigned long long)(unsigned)p_uni((int)(unsigned)(d >> 32)) << 32) |
-                                         (unsigned)p_uni((int)(unsigned)d));
-                }
-                unsigned long long early = __builtin_amdgcn_ballot_w64(fin && ev != EST_OVERRUN && ev > ov);
-                while (early != 0) {  // over-estimated: rounds t+1 .. p + e were reserved for it
-                    const int l = __builtin_ctzll(early);
-                    early &= early - 1;
-                    const int ps_l = __builtin_amdgcn_readlane(ps, l), ev_l = __builtin_amdgcn_readlane(ev, l);
-                    const int sv_l = __builtin_amdgcn_readlane(sv, l);
-                    for (int tq = t + 1 + lane; tq <= ps_l + ev_l; tq += PW) ring[tq & HM] -= sv_l + (tq - ps_l);
-                }
-                // past its estimate: from now on it reserves the next round only
-                const unsigned long long exp_mask = __builtin_amdgcn_ballot_w64(expire);
-                if (expire) EST[pos] = EST_OVERRUN;
-                ov_cnt += __popcll(exp_mask);
-                {
-                    long long d = expire ? (long long)sv - ps : 0;
-                    for (int dd = 32; dd >= 1; dd >>= 1) d += __shfl_xor(d, dd);
-                    ov_sp += (long long)(((unsigned long long)(unsigned)p_uni((int)(unsigned)(d >> 32)) << 32) |
-                                         (unsigned)p_uni((int)(unsigned)d));
-                }
-                // the rest stays; when is it due next?
-                const bool keep = in && !fin;
-                const bool overrun = keep && (ev == EST_OVERRUN || expire);
-                if (keep) due_min = min(due_min, ps + (overrun ? ov : min(ev, ov)));
-                const unsigned long long keep_mask = __builtin_amdgcn_ballot_w64(keep);
-                p_sync();  // every lane has read its ACT entry of this tile
-                if (keep) ACT[keep_base + __popcll(keep_mask & ((1ull << lane) - 1ull))] = (unsigned short)pos;
-                keep_base += __popcll(keep_mask);
-                p_sync();
             }
-            nact = keep_base;
-            next_due = p_wave_min(due_min);
+            next_due = min(p_wave_min(due_min), due_new);
+            if (removed > 0) {  // close the list up, in place: a tile is read before it is written
+                p_sync();
+                int kept = 0;
+                for (int a0 = 0; a0 < nact; a0 += PW) {
+                    const int a = a0 + lane;
+                    const int pos = a < nact ? ACT[a] : 0xffff;
+                    const bool keep = pos != 0xffff;
+                    const unsigned long long km = __builtin_amdgcn_ballot_w64(keep);
+                    p_sync();
+                    if (keep) ACT[kept + __popcll(km & ((1ull << lane) - 1ull))] = (unsigned short)pos;
+                    kept += __popcll(km);
+                    p_sync();
+                }
+                nact = kept;
+            }
+            p_sync();
         }
 
         // ---- 2. admission in the order's sequence
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 }
                 p_sync();
                 if (lane == 0) {
-                    if (ev == EST_OVERRUN) EST[vpos] = t - ps + 1;  // what it is known to need
+                    if (ev == EST_OVERRUN) EST[vpos] = (unsigned short)(t - ps + 1);  // what it is known to need
                     PS[vpos] = P_WAITING;
                     ACT[slot] = ACT[nact - 1];
                 }
@@ -297,8 +301,27 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 p_sync();
             }
         }
-        // rounds t + 1 .. t_skip - 1 change nothing (set only while nobody outruns an estimate)
-        if (t_skip > t + 1 && ov_cnt == 0) {
+        // While requests outrun their estimates the projection of round t' + 1 grows by their count
+        // every round; until the next due round nothing else changes.  Round t' needs work only if
+        // that projection passes M (eviction) or leaves room for the first token of the blocked
+        // request (a necessary condition for its admission): find the first such round.
+        if (ov_cnt > 0 && (hpos >= 0 || head >= n) && next_due > t + 1) {
+            const int room = hpos >= 0 ? hs + 1 : INT_MAX / 2;  // nothing waits: only the overflow matters
+            int found = next_due;
+            for (int base = t + 1; base < next_due && found == next_due; base += PW) {
+                const int tr = base + lane;
+                bool hit = false;
+                if (tr < next_due) {
+                    const long long x = (long long)ring[(tr + 1) & HM] + ov_sp + (long long)ov_cnt * (tr + 1);
+                    hit = x > (long long)M || x + room <= (long long)M;
+                }
+                const unsigned long long m = __builtin_amdgcn_ballot_w64(hit);
+                if (m != 0) found = base + __builtin_ctzll(m);
+            }
+            t_skip = found;
+        }
+        // rounds t + 1 .. t_skip - 1 change nothing
+        if (t_skip > t + 1) {
             const int span = min(t_skip - t - 1, H);
             for (int i = lane; i < span; i += PW) ring[(t + 1 + i) & HM] = 0;
             t = t_skip;
@@ -343,7 +366,7 @@ int kvs_launch_scan_estimates(const int32_t *est, size_t count, int32_t *d_words
 
 size_t kvs_predicted_lds_bytes(int32_t n, int32_t H)
 {
-    return sizeof(int) * ((size_t)H + 4 * (size_t)n) + sizeof(unsigned short) * (2 * (((size_t)n + 1) & ~(size_t)1));
+    return sizeof(int) * ((size_t)H + 2 * (size_t)n) + sizeof(unsigned short) * (4 * (((size_t)n + 1) & ~(size_t)1));
 }
 
 int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int32_t *s, const int32_t *o,
