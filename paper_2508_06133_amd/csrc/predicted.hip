@@ -375,12 +375,13 @@ int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int3
 {
     const size_t bytes = kvs_predicted_lds_bytes(n, H);
     if (bytes > KVS_PREDICTED_MAX_LDS || n > 65535) return KVSCHED_ERANGE;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // beyond 64 KB of dynamic LDS the kernel's limit has to be raised first; only as far as needed
+    static size_t lds_limit = 64 * 1024;
+    if (bytes > lds_limit) {
         if (hipFuncSetAttribute((const void *)predicted_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)KVS_PREDICTED_MAX_LDS) != hipSuccess)
+                                (int)bytes) != hipSuccess)
             return KVSCHED_EHIP;
-        attr_set = true;
+        lds_limit = bytes;
     }
     PredParams p;
     p.orders = orders;
