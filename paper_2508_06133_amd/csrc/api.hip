@@ -371,11 +371,11 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         rc = kvs_launch_broadcast_prefix(prefix_comp, cp, C, n, completion_out, st);
         if (rc != KVSCHED_OK) return rc;
     }
-    if (p.completion_by_position) {
-        rc = kvs_launch_permute_rows(orders, C, n, completion_out, st);
-        if (rc != KVSCHED_OK) return rc;
+    if (p.completion_by_position) {  // this pass over the rows checks them as well
+        rc = kvs_launch_permute_rows(orders, C, n, completion_out, tel_out, ctx->d_words, st);
+    } else {
+        rc = kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
     }
-    rc = kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
     if (rc != KVSCHED_OK || cp == 0) return rc;
     return kvs_launch_check_prefix(orders, C, n, cp, tel_out, ctx->d_words, st);
 }

@@ -5,30 +5,44 @@
 // timeline kernel means 4-byte stores scattered over an 8 KB row while thousands of rows are
 // in flight: measured HBM write traffic was 9x the payload.  Instead the timeline kernel stores
 // by position (256 contiguous bytes per 64 positions) and this kernel permutes each row in
-// place: one workgroup per row, the row staged in LDS, read and written coalesced.
+// place: one workgroup per row, the row staged in LDS, read and written coalesced.  The same pass
+// over the order row checks that it is a permutation of 0..n-1 (a bitmap of n bits beside the row).
 #include "kvsched_internal.h"
 
 namespace {
 
-__global__ __launch_bounds__(256) void permute_rows_kernel(const int32_t *orders, int32_t n, int32_t *completion)
+__global__ __launch_bounds__(256) void permute_rows_kernel(const int32_t *orders, int32_t n, int32_t *completion,
+                                                           int64_t *tel_out, int32_t *words)
 {
     extern __shared__ int row_by_id[];
+    unsigned int *seen = (unsigned int *)(row_by_id + n);  // one bit per request id
     const int32_t *order = orders + (size_t)blockIdx.x * (size_t)n;
     int32_t *comp = completion + (size_t)blockIdx.x * (size_t)n;
+    for (int i = threadIdx.x; i < ((n + 31) >> 5); i += blockDim.x) seen[i] = 0;
+    __syncthreads();
+    int bad = 0;
     for (int k = threadIdx.x; k < n; k += blockDim.x) {
-        const int r = min(max(order[k], 0), n - 1);  // rows that are no permutation are reported elsewhere
+        const int raw = order[k];
+        const int r = min(max(raw, 0), n - 1);
+        const unsigned int bit = 1u << (r & 31);
+        if (raw != r || (atomicOr(&seen[r >> 5], bit) & bit)) bad = 1;  // out of range, or met before
         row_by_id[r] = comp[k];
     }
-    __syncthreads();
+    if (__syncthreads_or(bad) && threadIdx.x == 0) {  // the row is no permutation: its results are void
+        tel_out[blockIdx.x] = -1;
+        atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_ORDER);
+    }
     for (int i = threadIdx.x; i < n; i += blockDim.x) comp[i] = row_by_id[i];
 }
 
 }  // namespace
 
-int kvs_launch_permute_rows(const int32_t *orders, int32_t C, int32_t n, int32_t *completion, hipStream_t st)
+int kvs_launch_permute_rows(const int32_t *orders, int32_t C, int32_t n, int32_t *completion, int64_t *tel_out,
+                            int32_t *d_words, hipStream_t st)
 {
     if (n > KVS_PERMUTE_MAX_N) return KVSCHED_ERANGE;
-    hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)C), dim3(256), sizeof(int32_t) * (size_t)n, st, orders, n,
-                       completion);
+    const size_t lds = sizeof(int32_t) * ((size_t)n + (((size_t)n + 31) >> 5));
+    hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)C), dim3(256), lds, st, orders, n, completion, tel_out,
+                       d_words);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

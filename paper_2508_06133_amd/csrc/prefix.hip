@@ -78,19 +78,17 @@ __global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blo
     __shared__ RadixLds<1024> L;
     __shared__ int sh_max[16];
     int mx = 0;
-    for (int i = threadIdx.x; i < C; i += 1024) {
-        tmp[i] = i;
-        mx = max(mx, blocks[i]);
-    }
+    for (int i = threadIdx.x; i < C; i += 1024) mx = max(mx, blocks[i]);
     for (int d = 32; d > 0; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
     if ((threadIdx.x & 63) == 0) sh_max[threadIdx.x >> 6] = mx;
     __syncthreads();
     for (int w = 0; w < 16; ++w) mx = max(mx, sh_max[w]);
     auto key = [blocks](int id) { return blocks[id]; };
-    // an even number of passes so that the result lands in `sorted`
-    int *src = tmp, *dst = sorted;
-    int passes = (bits_of(mx) + 7) / 8;
-    if (passes & 1) ++passes;
+    // one 8-bit pass per byte of the largest count; the ids start in whichever buffer makes the
+    // last pass land in `sorted`
+    const int passes = (bits_of(mx) + 7) / 8;
+    int *src = (passes & 1) ? tmp : sorted, *dst = (passes & 1) ? sorted : tmp;
+    for (int i = threadIdx.x; i < C; i += 1024) src[i] = i;
     __threadfence_block();
     __syncthreads();
     for (int pass = 0; pass < passes; ++pass) {
