@@ -29,13 +29,20 @@ __device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key,
     __syncthreads();
     for (int i = tid; i < n; i += TPB) atomicAdd(&L.hist[(key(in[i]) >> shift) & 255], 1);
     __syncthreads();
-    if (tid == 0) {  // exclusive scan of the 256 digit counts -> running output base per digit
-        int run = 0;
-        for (int d = 0; d < 256; ++d) {
-            const int c = L.hist[d];
-            L.hist[d] = run;
-            run += c;
+    if (wave == 0) {  // exclusive scan of the 256 digit counts -> running output base per digit
+        const int lane = tid;
+        const int c0 = L.hist[4 * lane], c1 = L.hist[4 * lane + 1], c2 = L.hist[4 * lane + 2],
+                  c3 = L.hist[4 * lane + 3];
+        int incl = c0 + c1 + c2 + c3;  // each lane owns four digits
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
         }
+        const int base = incl - (c0 + c1 + c2 + c3);
+        L.hist[4 * lane] = base;
+        L.hist[4 * lane + 1] = base + c0;
+        L.hist[4 * lane + 2] = base + c0 + c1;
+        L.hist[4 * lane + 3] = base + c0 + c1 + c2;
     }
     __syncthreads();
     for (int tile = 0; tile < n; tile += TPB) {

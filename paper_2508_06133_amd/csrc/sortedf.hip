@@ -15,6 +15,10 @@
 //      argmin over k <= K of S_k / k^2 compared in exact 128-bit integers, tie rule applied;
 //      F reported as one fp64 division
 //   5. stable sort of the (o, id)-ordered ids by batch number -> each batch in nondecreasing o
+// The working arrays and a copy of the lengths (56 bytes per request) live in LDS when they fit
+// beside the sort's tables (n up to about 2200), else in the caller's scratch buffer in HBM: the construction is a chain of short
+// dependent steps by one workgroup, so its time is the latency of those arrays; in particular a
+// barrier waits until every store before it has been acknowledged, which for HBM takes microseconds.
 #include "phase1_util.h"
 
 namespace {
@@ -33,6 +37,7 @@ struct Lds {
     long long best_S;
     int best_k;
     int flag;
+    int fit[2];
 };
 
 // sign of Sa/ka^2 - Sb/kb^2 in exact integers (Sa, Sb < 2^63; ka, kb < 2^31)
@@ -57,13 +62,63 @@ __device__ __forceinline__ bool better(long long Sa, int ka, long long Sb, int k
     return tie_rule == KVSCHED_TIE_LARGER ? ka > kb : ka < kb;
 }
 
-// Largest k in [0, rem] with g(k) <= M, for g increasing in k (k = 1..rem): a two-level count of
-// the probes that fit.  Every thread receives it.
+// The same question when every S < 2^32 and every k < 2^16: both cross products fit in 64 bits.
+__device__ __forceinline__ bool better_small(unsigned Sa, int ka, unsigned Sb, int kb, int tie_rule)
+{
+    const unsigned long long l = (unsigned long long)Sa * (unsigned)(kb * kb);
+    const unsigned long long r = (unsigned long long)Sb * (unsigned)(ka * ka);
+    const bool wins = l != r ? l < r : (tie_rule == KVSCHED_TIE_LARGER ? ka > kb : ka < kb);
+    return ka != 0 && (kb == 0 || wins);
+}
+
+template <int CTRL>
+__device__ __forceinline__ void take_better_small(unsigned &bS, int &bk, int tie_rule)
+{
+    const unsigned oS = (unsigned)__builtin_amdgcn_update_dpp((int)bS, (int)bS, CTRL, 0xf, 0xf, false);
+    const int ok = __builtin_amdgcn_update_dpp(bk, bk, CTRL, 0xf, 0xf, false);
+    if (better_small(oS, ok, bS, bk, tie_rule)) { bS = oS; bk = ok; }
+}
+
+// Best (S, k) of a 16-lane row into all its lanes: lane exchanges 1, 2 apart, then the two
+// mirrorings (quads, halves).  "Better" is a strict total order on distinct k, so any tree works.
+__device__ __forceinline__ void row_best_small(unsigned &bS, int &bk, int tie_rule)
+{
+    take_better_small<0xB1>(bS, bk, tie_rule);   // quad_perm [1,0,3,2]
+    take_better_small<0x4E>(bS, bk, tie_rule);   // quad_perm [2,3,0,1]
+    take_better_small<0x141>(bS, bk, tie_rule);  // row_half_mirror
+    take_better_small<0x140>(bS, bk, tie_rule);  // row_mirror
+}
+
+// Largest k in [0, rem] with g(k) <= M, for g increasing in k (k = 1..rem).  Every thread
+// receives it.  While a thread's share of the probes is short (rem <= 4 TPB) each thread counts
+// the fitting probes of its own run of consecutive k and the one thread whose run holds the
+// boundary publishes the answer: one barrier.  `slot` alternates between back-to-back calls.
 template <class G>
-__device__ int count_fitting(int rem, G g, int32_t M)
+__device__ int count_fitting(int rem, G g, int32_t M, Lds &L, int slot)
 {
     const int tid = threadIdx.x;
     const int stride = (rem + TPB - 1) / TPB;
+    if (stride <= 4) {
+        const int k0 = tid * stride;  // this thread probes k0+1 .. k0+stride, and k0+stride+1 to see the boundary
+        bool fit[5];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int k = k0 + 1 + j;
+            fit[j] = j <= stride && k <= rem && g((long long)k) <= (long long)M;
+        }
+        int c = 0;
+        bool beyond = false;  // does the first probe after this thread's run fit?
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            if (j < stride) c += fit[j] ? 1 : 0;
+            if (j == stride) beyond = fit[j];
+        }
+        // a prefix of all probes fits: the boundary lies in the run that fits at least partly and
+        // is not followed by a fitting probe; if nothing fits at all, thread 0 reports 0
+        if ((c > 0 && !beyond) || (tid == 0 && c == 0)) L.fit[slot] = k0 + c;
+        __syncthreads();
+        return L.fit[slot];
+    }
     const long long k1 = (long long)(tid + 1) * stride;  // coarse probes, a prefix of them fits
     const bool ok1 = k1 <= rem && g(k1) <= (long long)M;
     int K = __syncthreads_count(ok1) * stride;
@@ -119,7 +174,8 @@ __device__ bool profile_fits(int n, int a, int k, const int32_t *s, const int32_
     return __syncthreads_or(viol) == 0;
 }
 
-__global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
+template <bool IN_LDS>
+__global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *s_in, const int32_t *o_in, int32_t M,
                                                       int32_t ga, int32_t gb, int32_t tie_rule, int32_t feas_mode,
                                                       int32_t *order_out, int32_t *batch_end_out, double *F_out,
                                                       int32_t *num_batches_out, int *buf0, int *buf1, int *by_o,
@@ -127,12 +183,37 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
                                                       int *batch_of, int *pos_w, int32_t *words)
 {
     __shared__ Lds L;
+    extern __shared__ long long lds_arrays[];
+    // In this instantiation every working array below is carved from LDS and nothing else, so that
+    // the accesses compile to LDS instructions (a pointer that may be either costs HBM-like latency).
+    const int32_t *s = s_in, *o = o_in;
+    int *ends = batch_end_out;  // batch ends: collected in LDS and copied out at the end, or written in place
+    int *s_lds = nullptr, *o_lds = nullptr;  // the lengths too: every later read of them is a gather by request id
+    if constexpr (IN_LDS) {
+        const size_t np = ((size_t)n + 64) & ~(size_t)63;
+        const bool alias = cumG == cumS;
+        cumW = lds_arrays;
+        cumS = cumW + np;
+        cumG = alias ? cumS : cumS + np;
+        buf0 = (int *)(lds_arrays + 3 * np);
+        buf1 = buf0 + np;
+        by_o = buf1 + np;
+        batch_of = by_o + np;
+        pos_w = batch_of + np;
+        ends = pos_w + np;
+        s_lds = ends + np;
+        o_lds = s_lds + np;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // ---- well-formedness and key widths
     int omax = 0, wmax = 0, bad = 0;
     for (int i = tid; i < n; i += TPB) {
-        const int sv = s[i], ov = o[i];
+        const int sv = s_in[i], ov = o_in[i];
+        if constexpr (IN_LDS) {
+            s_lds[i] = sv;
+            o_lds[i] = ov;
+        }
         if (sv < 1 || ov < 1 || (long long)sv + ov > (long long)M) bad = 1;
         omax = max(omax, ov);
         wmax = max(wmax, (sv < 1 || ov < 1) ? 0 : (int)min((long long)sv + ov, (long long)M));
@@ -155,6 +236,11 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
             *num_batches_out = 0;
         }
         return;
+    }
+
+    if constexpr (IN_LDS) {
+        s = s_lds;
+        o = o_lds;
     }
 
     // ---- 1/2: key sorts (ids start in id order, every pass is stable)
@@ -214,20 +300,22 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         for (int i = tid; i <= n; i += TPB) cumG[i] = (long long)ga * (cumW[i] - cumS[i]) + (long long)gb * cumS[i];
     }
     __threadfence_block();
+    __syncthreads();
 
     // ---- 4: batches
+    const bool small = n < 65536 && cumG[n] < (1ll << 32);
     int a = 0, nb = 0;
     while (a < n) {
         const int rem = n - a;
         const long long W0 = cumW[a], S0 = cumS[a], G0 = cumG[a];
         // feasible extent K: the longest prefix within the budget (feasibility is monotone in k)
-        int K = count_fitting(rem, [&](long long k) { return cumW[a + k] - W0; }, M);  // sum of peaks <= M
+        int K = count_fitting(rem, [&](long long k) { return cumW[a + k] - W0; }, M, L, 0);  // sum of peaks <= M
         if (feas_mode == KVSCHED_FEAS_PROFILE && K >= 1 && K < rem) {
             // Started together, the prefix must stay within M at every completion time.  The sum of
             // peaks bounds that memory from above (so K is feasible), and the memory at the earliest
             // completion is at least sum (s_i + 1) (so nothing beyond hi is); bisect in between.
             int lo = K;
-            int hi = count_fitting(rem, [&](long long k) { return (cumW[a + k] - W0) - (cumS[a + k] - S0) + k; }, M);
+            int hi = count_fitting(rem, [&](long long k) { return (cumW[a + k] - W0) - (cumS[a + k] - S0) + k; }, M, L, 1);
             while (lo < hi) {
                 const int mid = lo + (hi - lo + 1) / 2;
                 if (profile_fits(n, a, mid, s, o, by_o, pos_w, M, L)) lo = mid;
@@ -241,31 +329,75 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         }
         long long bS = 0;
         int bk = 0;
-        for (int k = tid + 1; k <= K; k += TPB) {
-            const long long Sk = cumG[a + k] - G0;
-            if (better(Sk, k, bS, bk, tie_rule)) { bS = Sk; bk = k; }
+        if (small) {  // every numerator below 2^32, every size below 2^16: 64-bit cross products, lane exchanges
+            unsigned bs = 0;
+            for (int k = tid + 1; k <= K; k += TPB) {
+                const unsigned Sk = (unsigned)(cumG[a + k] - G0);
+                if (better_small(Sk, k, bs, bk, tie_rule)) { bs = Sk; bk = k; }
+            }
+            if (wave * 64 < K) {  // (a wave without candidates leaves the arithmetic units to the others)
+                row_best_small(bs, bk, tie_rule);
+                for (int d = 16; d <= 32; d <<= 1) {
+                    const unsigned oS = (unsigned)__shfl_xor((int)bs, d);
+                    const int ok = __shfl_xor(bk, d);
+                    if (better_small(oS, ok, bs, bk, tie_rule)) { bs = oS; bk = ok; }
+                }
+            }
+            if (lane == 0) { L.red_S[wave] = bs; L.red_k[wave] = bk; }
+            __syncthreads();
+            if (wave == 0) {  // the waves' winners in the first row of lanes
+                static_assert(NWAVES == 16, "one 16-lane row holds the waves' winners");
+                bs = (unsigned)L.red_S[lane & 15];
+                bk = L.red_k[lane & 15];
+                row_best_small(bs, bk, tie_rule);
+                if (lane == 0) {
+                    L.best_k = bk;
+                    ends[nb] = a + bk;
+                }
+            }
+        } else {
+            for (int k = tid + 1; k <= K; k += TPB) {
+                const long long Sk = cumG[a + k] - G0;
+                if (better(Sk, k, bS, bk, tie_rule)) { bS = Sk; bk = k; }
+            }
+            if (wave * 64 < K) {
+                for (int d = 32; d > 0; d >>= 1) {
+                    const long long oS = __shfl_down(bS, d);
+                    const int ok = __shfl_down(bk, d);
+                    if (better(oS, ok, bS, bk, tie_rule)) { bS = oS; bk = ok; }
+                }
+            }
+            if (lane == 0) { L.red_S[wave] = bS; L.red_k[wave] = bk; }
+            __syncthreads();
+            if (wave == 0) {  // the waves' winners, one per lane
+                bS = lane < NWAVES ? L.red_S[lane] : 0;
+                bk = lane < NWAVES ? L.red_k[lane] : 0;
+                for (int d = NWAVES / 2; d > 0; d >>= 1) {
+                    const long long oS = __shfl_down(bS, d);
+                    const int ok = __shfl_down(bk, d);
+                    if (better(oS, ok, bS, bk, tie_rule)) { bS = oS; bk = ok; }
+                }
+                if (lane == 0) {
+                    L.best_k = bk;
+                    ends[nb] = a + bk;
+                }
+            }
         }
-        for (int d = 32; d > 0; d >>= 1) {
-            const long long oS = __shfl_down(bS, d);
-            const int ok = __shfl_down(bk, d);
-            if (better(oS, ok, bS, bk, tie_rule)) { bS = oS; bk = ok; }
-        }
-        if (lane == 0) { L.red_S[wave] = bS; L.red_k[wave] = bk; }
         __syncthreads();
-        if (tid == 0) {
-            for (int v = 1; v < NWAVES; ++v)
-                if (better(L.red_S[v], L.red_k[v], bS, bk, tie_rule)) { bS = L.red_S[v]; bk = L.red_k[v]; }
-            L.best_S = bS;
-            L.best_k = bk;
-            batch_end_out[nb] = a + bk;
-            F_out[nb] = (double)bS / ((double)gb * (double)bk * (double)bk);
-        }
-        __syncthreads();
+        // (no barrier closes the iteration: the next one passes a barrier before it writes what is read here)
         const int kstar = L.best_k;
         for (int i = tid; i < kstar; i += TPB) batch_of[sorted[a + i]] = nb;
-        __syncthreads();
         a += kstar;
         ++nb;
+    }
+    __threadfence_block();
+    __syncthreads();
+    // metric values of the batches: one fp64 division each
+    for (int b = tid; b < nb; b += TPB) {
+        const int lo = b == 0 ? 0 : ends[b - 1], hi = ends[b];
+        if constexpr (IN_LDS) batch_end_out[b] = hi;
+        const double k = (double)(hi - lo);
+        F_out[b] = (double)(cumG[hi] - cumG[lo]) / ((double)gb * k * k);
     }
     if (tid == 0) *num_batches_out = nb;
     __threadfence_block();
@@ -290,7 +422,7 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
 size_t kvs_sortedF_scratch_bytes(int32_t n)
 {
     const size_t np = ((size_t)n + 64) & ~(size_t)63;
-    return np * (5 * sizeof(int) + 3 * sizeof(long long)) + 256;
+    return np * (8 * sizeof(int) + 3 * sizeof(long long)) + 256;
 }
 
 int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M, int32_t ga, int32_t gb,
@@ -306,8 +438,24 @@ int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
     int *by_o = buf1 + np;
     int *batch_of = by_o + np;
     int *pos_w = batch_of + np;
-    hipLaunchKernelGGL(sortedF_kernel, dim3(1), dim3(TPB), 0, st, n, s, o, M, ga, gb, tie_rule, feas_mode,
-                       order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, cumG, batch_of,
-                       pos_w, d_words);
+    const size_t arrays = kvs_sortedF_scratch_bytes(n);
+    constexpr size_t kLdsPerWorkgroup = 160 * 1024;
+    if (arrays + sizeof(Lds) <= kLdsPerWorkgroup) {
+        // more than 64 KB of LDS in all: the kernel's limit on the dynamic part is raised first, as far as needed
+        static size_t granted = 64 * 1024 - sizeof(Lds);
+        if (arrays > granted) {
+            if (hipFuncSetAttribute((const void *)sortedF_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)arrays) != hipSuccess)
+                return KVSCHED_EHIP;
+            granted = arrays;
+        }
+        hipLaunchKernelGGL(sortedF_kernel<true>, dim3(1), dim3(TPB), arrays, st, n, s, o, M, ga, gb, tie_rule,
+                           feas_mode, order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS,
+                           cumG, batch_of, pos_w, d_words);
+    } else {
+        hipLaunchKernelGGL(sortedF_kernel<false>, dim3(1), dim3(TPB), 0, st, n, s, o, M, ga, gb, tie_rule, feas_mode,
+                           order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, cumG,
+                           batch_of, pos_w, d_words);
+    }
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
