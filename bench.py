@@ -237,7 +237,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build evaluates schedules on ONE GPU; --gpus must be 1 "
-              "(candidates would shard across GPUs, see DESIGN.md)", file=sys.stderr)
+              "(candidates are independent and would shard across GPUs; that is not built)", file=sys.stderr)
         return 2
 
     import torch
