@@ -139,6 +139,13 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
  * skipped positions save); 0 = never. */
 int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows);
 
+/* How the resumed rows get row 0's saved states.  on != 0 (default): all rows run in one launch,
+ * row 0's wavefront flags each state once the whole device can read it, a row waits (a bounded
+ * time) for the state it needs and otherwise takes the latest one that is there.  on == 0: two
+ * launches, the quarter of the rows that shares least with row 0 (at most 4096) beside row 0 in
+ * the first, the others in the second.  Results are the same. */
+int kvsched_set_resume_one_launch(kvsched_ctx *ctx, int32_t on);
+
 /*
  * Phase 2 under predicted decode lengths (Section 5, "Handling Prediction Uncertainty via Adaptive
  * Output Length Refinement"; appendix algorithm "Sorted-F + A_min") for C candidate orders at once.

@@ -43,7 +43,12 @@ def is_stale() -> bool:
 
 
 def reserved_vgpr_violations(asm_text: str, base: int = RESERVED_VGPR_BASE) -> list[str]:
-    """Compiler-generated lines inside timeline_reg_kernel bodies that name a VGPR >= base."""
+    """Compiler-generated lines inside timeline_reg_kernel bodies that name a VGPR >= base.
+
+    A body runs from the kernel's label to its .Lfunc_end label (s_endpgm may come early, for the
+    exits in the prologue); inline assembly sits between the ASMSTART / ASMEND (or APP / NO_APP)
+    comment lines the compiler emits around it.
+    """
     bad = []
     in_kernel = in_asm = False
     for line in asm_text.splitlines():
@@ -53,13 +58,13 @@ def reserved_vgpr_violations(asm_text: str, base: int = RESERVED_VGPR_BASE) -> l
             continue
         if not in_kernel:
             continue
-        if s.startswith("s_endpgm"):
+        if s.startswith(".Lfunc_end"):
             in_kernel = False
             continue
-        if s.startswith(";APP"):
+        if s.startswith((";;#ASMSTART", ";APP", "#APP")):
             in_asm = True
             continue
-        if s.startswith(";NO_APP"):
+        if s.startswith((";;#ASMEND", ";NO_APP", "#NO_APP")):
             in_asm = False
             continue
         if in_asm or not s or s.startswith((";", ".")):

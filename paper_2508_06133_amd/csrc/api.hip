@@ -182,6 +182,7 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->resume_rows = 0;
     ctx->resume_first = 0;
     ctx->resume_min_rows = kResumeMinRowsDefault;
+    ctx->resume_one_launch = 1;
     ctx->ev0 = nullptr;
     ctx->ev1 = nullptr;
     if (hipMalloc((void **)&ctx->d_words, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess ||
@@ -225,6 +226,13 @@ int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound)
     if (!ctx || o_max_bound < 0) return KVSCHED_EINVAL;
     if (o_max_bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
     ctx->o_max_bound = o_max_bound;
+    return KVSCHED_OK;
+}
+
+int kvsched_set_resume_one_launch(kvsched_ctx *ctx, int32_t on)
+{
+    if (!ctx) return KVSCHED_EINVAL;
+    ctx->resume_one_launch = on ? 1 : 0;
     return KVSCHED_OK;
 }
 
@@ -321,37 +329,57 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         const int32_t nblk = (n - 1) / WAVE_POSITIONS;
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
-        rc = ensure_scratch(ctx, 3 * list_bytes + align256(sizeof(int32_t) * (size_t)nblk * (size_t)stride));
+        const size_t snap_bytes = align256(sizeof(int32_t) * (size_t)nblk * (size_t)stride);
+        rc = ensure_scratch(ctx, 3 * list_bytes + snap_bytes + align256(sizeof(int32_t) * (size_t)nblk));
         if (rc != KVSCHED_OK) return rc;
         int32_t *blocks = (int32_t *)ctx->d_scratch;
         int32_t *sorted = (int32_t *)((char *)ctx->d_scratch + list_bytes);
         int32_t *tmp = (int32_t *)((char *)ctx->d_scratch + 2 * list_bytes);
         int32_t *snaps = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes);
+        int32_t *flags = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes);
         rc = kvs_launch_shared_blocks(orders, C, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
         rc = kvs_launch_sort_by_blocks(blocks, C, tmp, sorted, st);
         if (rc != KVSCHED_OK) return rc;
-        rc = kvs_launch_mark_snapshots_unusable(snaps, nblk, stride, st);
-        if (rc != KVSCHED_OK) return rc;
-        const int32_t first = (C + 3) / 4 < kResumeFirstLaunchMax ? (C + 3) / 4 : kResumeFirstLaunchMax;
-        if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
-        SimParams a = p;  // rows sorted[0 .. first): from the start; row 0 (sorted[0]) takes the snapshots
-        a.C = first;
-        a.cand_list = sorted;
-        a.snapshots = snaps;
-        a.snap_stride = stride;
-        a.snap_blocks = nblk;
-        rc = kvs_launch_simulate_reg(a, st);
-        if (rc != KVSCHED_OK) return rc;
-        SimParams b = p;  // rows sorted[first .. C): from their snapshot
-        b.C = C - first;
-        b.cand_list = sorted + first;
-        b.resume_block = blocks;
-        b.snapshots = snaps;
-        b.snap_stride = stride;
-        b.snap_blocks = 0;
-        rc = kvs_launch_simulate_reg(b, st);
-        if (rc != KVSCHED_OK) return rc;
+        int32_t first = 0;
+        if (ctx->resume_one_launch) {
+            // All rows in one launch, those that share least with row 0 first: row 0's wave flags each
+            // snapshot as it is written, the others wait for theirs (most find it there already).
+            hipLaunchKernelGGL(kvs_fill_zero_i32, dim3((unsigned)((nblk + 255) / 256)), dim3(256), 0, st, flags, nblk);
+            if (hipGetLastError() != hipSuccess) return KVSCHED_EHIP;
+            if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
+            SimParams a = p;
+            a.cand_list = sorted;
+            a.resume_block = blocks;
+            a.snapshots = snaps;
+            a.snap_stride = stride;
+            a.snap_blocks = nblk;
+            a.snap_flags = flags;
+            rc = kvs_launch_simulate_reg(a, st);
+            if (rc != KVSCHED_OK) return rc;
+        } else {
+            rc = kvs_launch_mark_snapshots_unusable(snaps, nblk, stride, st);
+            if (rc != KVSCHED_OK) return rc;
+            first = (C + 3) / 4 < kResumeFirstLaunchMax ? (C + 3) / 4 : kResumeFirstLaunchMax;
+            if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
+            SimParams a = p;  // rows sorted[0 .. first): from the start; row 0 (sorted[0]) takes the snapshots
+            a.C = first;
+            a.cand_list = sorted;
+            a.snapshots = snaps;
+            a.snap_stride = stride;
+            a.snap_blocks = nblk;
+            rc = kvs_launch_simulate_reg(a, st);
+            if (rc != KVSCHED_OK) return rc;
+            SimParams b = p;  // rows sorted[first .. C): from their snapshot
+            b.C = C - first;
+            b.cand_list = sorted + first;
+            b.resume_block = blocks;
+            b.snapshots = snaps;
+            b.snap_stride = stride;
+            b.snap_blocks = 0;
+            rc = kvs_launch_simulate_reg(b, st);
+            if (rc != KVSCHED_OK) return rc;
+        }
         if (ctx->timing) {
             if (hipEventRecord(ctx->ev1, st) != hipSuccess) return KVSCHED_EHIP;
             ctx->timed = 1;

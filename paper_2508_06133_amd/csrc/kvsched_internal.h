@@ -33,6 +33,7 @@ struct kvsched_ctx {
     int32_t resume_rows;   // rows of the last kvsched_simulate call if it resumed rows from snapshots, else 0
     int32_t resume_first;  // ... and how many of them (in sorted order) ran from the start
     int32_t resume_min_rows;  // kvsched_simulate resumes rows from row 0's snapshots from this many rows on
+    int32_t resume_one_launch;  // ... in one launch (rows wait for their snapshot) rather than two
     hipEvent_t ev0, ev1;
 };
 
@@ -69,11 +70,17 @@ struct SimParams {
     // candidate 0 writes snapshots 1..snap_blocks (word 1 of a snapshot, the round t, is set to -1 by
     // the host beforehand: a snapshot that is never taken poisons whoever resumes from it); a
     // candidate c with resume_block[c] = b > 0 starts from snapshot b at position 64 b.
+    // With snap_flags (snap_blocks words, zero at launch) both happen in ONE launch: the wave of
+    // candidate 0 sets snap_flags[j - 1] once snapshot j can be read by the whole device (or marks
+    // it as not coming), a candidate with b > 0 waits for snap_flags[b - 1], a bounded time, then
+    // takes the latest snapshot that is there and writes the block it really started from back to
+    // resume_block[c].
     const int32_t *cand_list = nullptr;
-    const int32_t *resume_block = nullptr;
+    int32_t *resume_block = nullptr;
     int32_t *snapshots = nullptr;
     int32_t snap_stride = 0;
     int32_t snap_blocks = 0;
+    int32_t *snap_flags = nullptr;
 };
 constexpr int KVS_STATE_HEAD_WORDS = 192;
 constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 65 * 64;

@@ -349,25 +349,128 @@ __device__ __forceinline__ int scalar_read(const int32_t *base, int index)
 // Head of a saved timeline state: words 0, 1 = b64, t (every lane stores the same two values), then
 // the lanes' partial sums of completion rounds as 64 int64 at byte 256.  The profile rows follow
 // at byte 768 (prof_store).  Written in assembly so that no temporary can land in the profile block.
+template <int NR>
 __device__ __forceinline__ void state_head_store(int32_t *snap, int b64, int t, long long tel_lane, int lane)
 {
     int a, b, off;
-    asm volatile("v_mov_b32 %[a], %[b64]\n"
-                 "v_mov_b32 %[b], %[t]\n"
-                 "v_mov_b32 %[off], 0\n"
-                 "global_store_dword %[off], %[a], %[base]\n"
-                 "global_store_dword %[off], %[b], %[base] offset:4\n"
-                 "v_lshlrev_b32 %[off], 3, %[lane]\n"
-                 "global_store_dwordx2 %[off], %[tel], %[base] offset:256\n"
+#define KVS_STMT(CLOB, ASC, DESC)                                                                        \
+    asm volatile("v_mov_b32 %[a], %[b64]\n"                                                              \
+                 "v_mov_b32 %[b], %[t]\n"                                                                \
+                 "v_mov_b32 %[off], 0\n"                                                                 \
+                 "global_store_dword %[off], %[a], %[base]\n"                                            \
+                 "global_store_dword %[off], %[b], %[base] offset:4\n"                                   \
+                 "v_lshlrev_b32 %[off], 3, %[lane]\n"                                                    \
+                 "global_store_dwordx2 %[off], %[tel], %[base] offset:256\n"                             \
+                 "s_waitcnt vmcnt(0)\n"                                                                  \
+                 : [a] "=&v"(a), [b] "=&v"(b), [off] "=&v"(off)                                          \
+                 : [base] "s"(snap), [b64] "s"(b64), [t] "s"(t), [tel] "v"(tel_lane), [lane] "v"(lane)   \
+                 : "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
+// Snapshots handed over inside one launch.  The wave that writes a snapshot and the waves that read
+// it run on different compute units, in general under different L2 caches, so the hand-over follows
+// the device-scope release / acquire sequences of the hardware's memory model, written out here
+// because the snapshot itself is stored and loaded by assembly the compiler does not see into:
+//   writer: all stores done -> write back the L2 -> done -> store the flag at device scope;
+//   reader: load the flag at device scope -> invalidate stale cache lines -> load the snapshot.
+constexpr int KVS_SNAP_READY = 1;  // (0: not there yet)
+constexpr int KVS_SNAP_NEVER = 2;  // the writer gave up before it got there
+// A reader polls about every 3 us and gives up after 4096 polls (some 14 ms: far longer than the
+// writer needs per snapshot unless the timelines themselves take much longer than that); it then
+// starts from the latest snapshot that is there, or from the beginning.  Every wait ends.
+constexpr int KVS_SNAP_WAIT_POLLS = 4096;
+
+template <int NR>
+__device__ __forceinline__ void snapshot_flag_set(int32_t *flags, int index, int value)  // device-scope store
+{
+    int off, v;
+#define KVS_STMT(CLOB, ASC, DESC)                                                       \
+    asm volatile("v_mov_b32 %[off], %[idx]\n"                                           \
+                 "v_mov_b32 %[v], %[val]\n"                                             \
+                 "global_store_dword %[off], %[v], %[base] sc1\n"                       \
+                 : [off] "=&v"(off), [v] "=&v"(v)                                       \
+                 : [base] "s"(flags), [idx] "s"(index * 4), [val] "s"(value)            \
+                 : "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+}
+
+template <int NR>
+__device__ __forceinline__ void snapshot_publish(int32_t *flags, int index)
+{
+    asm volatile("s_waitcnt vmcnt(0)\n"
+                 "buffer_wbl2 sc1\n"
+                 "s_waitcnt vmcnt(0)\n" ::: "memory");
+    snapshot_flag_set<NR>(flags, index, KVS_SNAP_READY);
+}
+
+// The reader's side as one scalar loop: poll flag rb - 1 until it is set (or the polls are used up),
+// then, unless it says READY, step down to the latest snapshot that is READY (0: none); finally the
+// cache invalidation that lets the loads that follow see the snapshot.  rb = 0 (nothing to wait for)
+// passes through.  Written as a single block so that the compiler sees one scalar result, as from
+// a scalar load.
+__device__ __forceinline__ int snapshot_wait(const int32_t *flags, int rb)
+{
+    int f, cnt, off, voff, v;
+    asm volatile("s_mov_b32 %[cnt], %c[polls]\n"
+                 "s_cmp_eq_u32 %[rb], 0\n"
+                 "s_cbranch_scc1 4f\n"
+                 "1:\n"
+                 "s_lshl_b32 %[off], %[rb], 2\n"
+                 "s_sub_u32 %[off], %[off], 4\n"
+                 "v_mov_b32 %[voff], %[off]\n"
+                 "global_load_dword %[v], %[voff], %[base] sc1\n"
                  "s_waitcnt vmcnt(0)\n"
-                 : [a] "=&v"(a), [b] "=&v"(b), [off] "=&v"(off)
-                 : [base] "s"(snap), [b64] "s"(b64), [t] "s"(t), [tel] "v"(tel_lane), [lane] "v"(lane)
+                 "v_readfirstlane_b32 %[f], %[v]\n"
+                 "s_cmp_lg_u32 %[f], 0\n"
+                 "s_cbranch_scc1 2f\n"
+                 "s_sleep 127\n"
+                 "s_sub_u32 %[cnt], %[cnt], 1\n"
+                 "s_cmp_lg_u32 %[cnt], 0\n"
+                 "s_cbranch_scc1 1b\n"
+                 "2:\n"
+                 "s_cmp_eq_u32 %[f], %c[ready]\n"
+                 "s_cbranch_scc1 4f\n"
+                 "3:\n"
+                 "s_sub_u32 %[rb], %[rb], 1\n"
+                 "s_cmp_eq_u32 %[rb], 0\n"
+                 "s_cbranch_scc1 4f\n"
+                 "s_lshl_b32 %[off], %[rb], 2\n"
+                 "s_sub_u32 %[off], %[off], 4\n"
+                 "v_mov_b32 %[voff], %[off]\n"
+                 "global_load_dword %[v], %[voff], %[base] sc1\n"
+                 "s_waitcnt vmcnt(0)\n"
+                 "v_readfirstlane_b32 %[f], %[v]\n"
+                 "s_cmp_eq_u32 %[f], %c[ready]\n"
+                 "s_cbranch_scc0 3b\n"
+                 "4:\n"
+                 "buffer_inv sc1\n"
+                 : [rb] "+s"(rb), [f] "=&s"(f), [cnt] "=&s"(cnt), [off] "=&s"(off), [voff] "=&v"(voff), [v] "=&v"(v)
+                 : [base] "s"(flags), [polls] "n"(KVS_SNAP_WAIT_POLLS), [ready] "n"(KVS_SNAP_READY)
+                 : "scc", "memory");
+    return rb;
+}
+
+// One int32 of a snapshot's head through the vector unit (the scalar cache takes no part in the
+// hand-over above).
+__device__ __forceinline__ int snapshot_word(const int32_t *snap, int index)
+{
+    int off, v;
+    asm volatile("v_mov_b32 %[off], %[idx]\n"
+                 "global_load_dword %[v], %[off], %[base]\n"
+                 "s_waitcnt vmcnt(0)\n"
+                 : [off] "=&v"(off), [v] "=&v"(v)
+                 : [base] "s"(snap), [idx] "s"(index * 4)
                  : "memory");
+    return __builtin_amdgcn_readfirstlane(v);
 }
 
 // RES: the launch runs the candidates named by p.cand_list; the wave of candidate 0 saves its
 // state every 64 positions, candidates with a resume block start from such a snapshot.
-template <int NR, int WPB, bool MOVES, bool RES>
+// ONE (with RES): both in the same launch, handed over through p.snap_flags.
+template <int NR, int WPB, bool MOVES, bool RES, bool ONE>
 __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
 {
     const int lane = threadIdx.x & (WAVE - 1);
@@ -398,20 +501,24 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     int k_first = p.k_begin;
     const int32_t *state_in = p.state_in;
     if (RES && p.resume_block) {
-        const int rb = scalar_read(p.resume_block, cand);
+        const int planned = scalar_read(p.resume_block, cand);
+        // ONE: taken in this very launch: wait for it, within bounds
+        const int rb = ONE ? snapshot_wait(p.snap_flags, planned) : planned;
+        if (ONE && rb != planned) p.resume_block[cand] = rb;  // (every lane, same value) the accounts show what was really skipped
         if (rb > 0) {
             k_first = 64 * rb;
             state_in = p.snapshots + (size_t)(rb - 1) * (size_t)p.snap_stride;
         }
     }
     const bool takes_snapshots = RES && p.snap_blocks > 0 && cand == 0;
+    if (ONE && takes_snapshots) __builtin_amdgcn_s_setprio(3);  // the others wait for this wave
     const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
     int b64 = 0;             // round of lane 0 of register 0: 64 * floor((t + 1) / 64)
     int t = 0;               // start round of the previous request in the order
     long long tel_lane = 0;  // completion rounds summed per lane; added up over the lanes at the end
     if (state_in) {
-        b64 = scalar_read(state_in, 0);
-        t = scalar_read(state_in, 1);
+        b64 = snapshot_word(state_in, 0);
+        t = snapshot_word(state_in, 1);
         if (t < 0) {  // the shared prefix could not be scheduled
             if (lane == 0 && p.tel_out) p.tel_out[cand] = -1;
             return;
@@ -435,8 +542,9 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     for (int k0 = k_first; k0 < n; k0 += WAVE) {
         if (takes_snapshots && k0 > 0 && (k0 >> 6) <= p.snap_blocks) {  // the state after k0 positions
             int32_t *snap = p.snapshots + (size_t)((k0 >> 6) - 1) * (size_t)p.snap_stride;
-            state_head_store(snap, b64, t, tel_lane, lane);
+            state_head_store<NR>(snap, b64, t, tel_lane, lane);
             prof_store<NR>(snap + KVS_STATE_HEAD_WORDS, lane);
+            if (ONE) snapshot_publish<NR>(p.snap_flags, (k0 >> 6) - 1);
         }
         const int k = k0 + lane;
         const int rq = rq_n, sv = sv_n, ov = ov_n;
@@ -452,6 +560,8 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
                 if (p.tel_out) p.tel_out[cand] = -1;
                 if (p.state_out) p.state_out[1] = -1;  // poisons every timeline that resumes from it
             }
+            if (ONE && takes_snapshots)  // nobody shall wait for the snapshots that will not come
+                for (int j = k0 >> 6; j < p.snap_blocks; ++j) snapshot_flag_set<NR>(p.snap_flags, j, KVS_SNAP_NEVER);
             return;  // (snapshots not taken stay marked unusable, as the host left them)
         }
         const int cnt = min(WAVE, n - k0);
@@ -487,7 +597,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
     if (p.state_out) {
-        state_head_store(p.state_out, b64, t, tel_lane, lane);
+        state_head_store<NR>(p.state_out, b64, t, tel_lane, lane);
         prof_store<NR>(p.state_out + KVS_STATE_HEAD_WORDS, lane);
     }
     for (int d = 32; d > 0; d >>= 1) tel_lane += __shfl_down(tel_lane, d);
@@ -499,12 +609,14 @@ template <int NR, int WPB>
 int launch_reg(const SimParams &p, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((p.C + WPB - 1) / WPB);
-    if (p.src.orders && p.cand_list)
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    if (p.src.orders && p.cand_list && p.snap_flags)
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    else if (p.src.orders && p.cand_list)
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     else if (p.src.orders)
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, false, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     else
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true, false, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 

@@ -54,6 +54,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
     lib.kvsched_simulate_resume_positions.argtypes = [vp, i32, vp, vp]
     lib.kvsched_set_resume_min_rows.argtypes = [vp, i32]
+    lib.kvsched_set_resume_one_launch.argtypes = [vp, i32]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.kvsched_local_swap.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.kvsched_exact_dp.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
@@ -152,6 +153,11 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_simulate")
         return tel, comp
+
+    def set_resume_one_launch(self, on: bool):
+        rc = _lib.kvsched_set_resume_one_launch(self._h, 1 if on else 0)
+        if rc != 0:
+            raise KvschedError(rc, "kvsched_set_resume_one_launch")
 
     def set_resume_min_rows(self, rows: int):
         rc = _lib.kvsched_set_resume_min_rows(self._h, int(rows))

@@ -54,13 +54,19 @@ def test_reserved_vgpr_scan_of_the_build():
     text = "\n".join([
         "_ZN12_GLOBAL__N_119timeline_reg_kernelILi33ELi4ELb0EEEv9SimParams: ; @x",
         "\tv_add_u32_e32 v31, v1, v2",
-        "\t;APP",
+        "\t;;#ASMSTART",
         "  v_mov_b32 v[32+kvs_r], 64*kvs_r",
         "v_mov_b32 v40, 0",
-        "\t;NO_APP",
+        "\t;;#ASMEND",
+        "\ts_endpgm",  # an early exit of the prologue: the body goes on to .Lfunc_end
         "\tv_add_u32_e32 v33, v1, v2",
+        "\t;APP",
+        "v_mov_b32 v41, 0",
+        "\t;NO_APP",
         "\tv_mov_b64_e32 v[30:33], 0",
         "\ts_endpgm",
+        ".Lfunc_end0:",
+        "\tv_mov_b32_e32 v51, 0",
         "_Z5otherv:",
         "\tv_mov_b32_e32 v50, 0",
     ])
