@@ -112,6 +112,7 @@ constexpr int32_t kMinSharedPrefix = 64;  // shorter shared prefixes are not wor
 // the start next to row 0.
 constexpr int32_t kResumeMinRowsDefault = 16384;
 constexpr int32_t kResumeFirstLaunchMax = 4096;
+constexpr int32_t kResumeWaitPollsDefault = 4096;  // about 14 ms
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -182,7 +183,7 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->resume_rows = 0;
     ctx->resume_first = 0;
     ctx->resume_min_rows = kResumeMinRowsDefault;
-    ctx->resume_one_launch = 1;
+    ctx->resume_wait_polls = kResumeWaitPollsDefault;
     ctx->ev0 = nullptr;
     ctx->ev1 = nullptr;
     if (hipMalloc((void **)&ctx->d_words, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess ||
@@ -229,10 +230,10 @@ int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound)
     return KVSCHED_OK;
 }
 
-int kvsched_set_resume_one_launch(kvsched_ctx *ctx, int32_t on)
+int kvsched_set_resume_one_launch(kvsched_ctx *ctx, int32_t wait_polls)
 {
-    if (!ctx) return KVSCHED_EINVAL;
-    ctx->resume_one_launch = on ? 1 : 0;
+    if (!ctx || wait_polls < 0) return KVSCHED_EINVAL;
+    ctx->resume_wait_polls = wait_polls;
     return KVSCHED_OK;
 }
 
@@ -342,7 +343,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         rc = kvs_launch_sort_by_blocks(blocks, C, tmp, sorted, st);
         if (rc != KVSCHED_OK) return rc;
         int32_t first = 0;
-        if (ctx->resume_one_launch) {
+        if (ctx->resume_wait_polls > 0) {
             // All rows in one launch, those that share least with row 0 first: row 0's wave flags each
             // snapshot as it is written, the others wait for theirs (most find it there already).
             hipLaunchKernelGGL(kvs_fill_zero_i32, dim3((unsigned)((nblk + 255) / 256)), dim3(256), 0, st, flags, nblk);
@@ -355,6 +356,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
             a.snap_stride = stride;
             a.snap_blocks = nblk;
             a.snap_flags = flags;
+            a.snap_wait_polls = ctx->resume_wait_polls;
             rc = kvs_launch_simulate_reg(a, st);
             if (rc != KVSCHED_OK) return rc;
         } else {

@@ -33,7 +33,7 @@ struct kvsched_ctx {
     int32_t resume_rows;   // rows of the last kvsched_simulate call if it resumed rows from snapshots, else 0
     int32_t resume_first;  // ... and how many of them (in sorted order) ran from the start
     int32_t resume_min_rows;  // kvsched_simulate resumes rows from row 0's snapshots from this many rows on
-    int32_t resume_one_launch;  // ... in one launch (rows wait for their snapshot) rather than two
+    int32_t resume_wait_polls;  // ... in one launch, a row waiting at most so many polls for its snapshot; 0: in two launches
     hipEvent_t ev0, ev1;
 };
 
@@ -81,6 +81,7 @@ struct SimParams {
     int32_t snap_stride = 0;
     int32_t snap_blocks = 0;
     int32_t *snap_flags = nullptr;
+    int32_t snap_wait_polls = 0;  // polls (about 3 us each) a candidate waits for its snapshot at most
 };
 constexpr int KVS_STATE_HEAD_WORDS = 192;
 constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 65 * 64;

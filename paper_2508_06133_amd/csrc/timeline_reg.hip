@@ -377,10 +377,10 @@ __device__ __forceinline__ void state_head_store(int32_t *snap, int b64, int t, 
 //   reader: load the flag at device scope -> invalidate stale cache lines -> load the snapshot.
 constexpr int KVS_SNAP_READY = 1;  // (0: not there yet)
 constexpr int KVS_SNAP_NEVER = 2;  // the writer gave up before it got there
-// A reader polls about every 3 us and gives up after 4096 polls (some 14 ms: far longer than the
-// writer needs per snapshot unless the timelines themselves take much longer than that); it then
-// starts from the latest snapshot that is there, or from the beginning.  Every wait ends.
-constexpr int KVS_SNAP_WAIT_POLLS = 4096;
+// A reader polls about every 3 us and gives up after SimParams::snap_wait_polls polls (by default
+// some 14 ms: far longer than the writer needs per snapshot unless the timelines themselves take much
+// longer than that); it then starts from the latest snapshot that is there, or from the beginning.
+// Every wait ends.
 
 template <int NR>
 __device__ __forceinline__ void snapshot_flag_set(int32_t *flags, int index, int value)  // device-scope store
@@ -411,10 +411,10 @@ __device__ __forceinline__ void snapshot_publish(int32_t *flags, int index)
 // cache invalidation that lets the loads that follow see the snapshot.  rb = 0 (nothing to wait for)
 // passes through.  Written as a single block so that the compiler sees one scalar result, as from
 // a scalar load.
-__device__ __forceinline__ int snapshot_wait(const int32_t *flags, int rb)
+__device__ __forceinline__ int snapshot_wait(const int32_t *flags, int rb, int polls)
 {
     int f, cnt, off, voff, v;
-    asm volatile("s_mov_b32 %[cnt], %c[polls]\n"
+    asm volatile("s_max_i32 %[cnt], %[polls], 1\n"
                  "s_cmp_eq_u32 %[rb], 0\n"
                  "s_cbranch_scc1 4f\n"
                  "1:\n"
@@ -448,7 +448,7 @@ __device__ __forceinline__ int snapshot_wait(const int32_t *flags, int rb)
                  "4:\n"
                  "buffer_inv sc1\n"
                  : [rb] "+s"(rb), [f] "=&s"(f), [cnt] "=&s"(cnt), [off] "=&s"(off), [voff] "=&v"(voff), [v] "=&v"(v)
-                 : [base] "s"(flags), [polls] "n"(KVS_SNAP_WAIT_POLLS), [ready] "n"(KVS_SNAP_READY)
+                 : [base] "s"(flags), [polls] "s"(polls), [ready] "n"(KVS_SNAP_READY)
                  : "scc", "memory");
     return rb;
 }
@@ -503,7 +503,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     if (RES && p.resume_block) {
         const int planned = scalar_read(p.resume_block, cand);
         // ONE: taken in this very launch: wait for it, within bounds
-        const int rb = ONE ? snapshot_wait(p.snap_flags, planned) : planned;
+        const int rb = ONE ? snapshot_wait(p.snap_flags, planned, p.snap_wait_polls) : planned;
         if (ONE && rb != planned) p.resume_block[cand] = rb;  // (every lane, same value) the accounts show what was really skipped
         if (rb > 0) {
             k_first = 64 * rb;
@@ -511,7 +511,6 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         }
     }
     const bool takes_snapshots = RES && p.snap_blocks > 0 && cand == 0;
-    if (ONE && takes_snapshots) __builtin_amdgcn_s_setprio(3);  // the others wait for this wave
     const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
     int b64 = 0;             // round of lane 0 of register 0: 64 * floor((t + 1) / 64)
     int t = 0;               // start round of the previous request in the order

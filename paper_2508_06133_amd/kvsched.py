@@ -154,8 +154,8 @@ class Context:
             raise KvschedError(rc, "kvsched_simulate")
         return tel, comp
 
-    def set_resume_one_launch(self, on: bool):
-        rc = _lib.kvsched_set_resume_one_launch(self._h, 1 if on else 0)
+    def set_resume_one_launch(self, wait_polls: int):
+        rc = _lib.kvsched_set_resume_one_launch(self._h, int(wait_polls))
         if rc != 0:
             raise KvschedError(rc, "kvsched_set_resume_one_launch")
 

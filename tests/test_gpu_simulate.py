@@ -89,6 +89,12 @@ def test_config3_full_size(ctx):
         tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
         assert status == 0
         _assert_equal(tel_g, comp_g, tel_o, comp_o, f"config 3, launch {launch}")
+    # (those took the default path: rows resumed from row 0's states within one launch; the same in two launches)
+    ctx.set_resume_one_launch(0)
+    tel_2, comp_2, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+    ctx.set_resume_one_launch(4096)
+    assert status == 0
+    _assert_equal(tel_2, comp_2, tel_o, comp_o, "config 3, two launches")
     # properties that hold for every row at any size
     assert (comp_g >= inst.o[None, :]).all()
     assert (tel_g == comp_g.astype(np.int64).sum(axis=1)).all()
@@ -265,6 +271,7 @@ def resume_from_2048_rows(ctx):
     ctx.set_resume_min_rows(2048)
     yield
     ctx.set_resume_min_rows(16384)
+    ctx.set_resume_one_launch(4096)
 
 
 @pytest.mark.parametrize("cfg,n,C,completions", [(3, 700, 2500, True), (2, 321, 2048, True), (3, 1000, 5000, False),
@@ -300,6 +307,20 @@ def test_rows_resumed_from_row0_snapshots(ctx, resume_from_2048_rows, cfg, n, C,
     shared = np.where(differs.any(axis=1), differs.argmax(axis=1), n)
     assert (pos % 64 == 0).all() and (pos <= shared).all() and (pos < n).all() and pos[0] == 0
     assert (pos > 0).sum() > C // 4
+    # the other ways to hand row 0's states over: rows that give up waiting after one poll and
+    # start from the latest state that is there (or from their first position), and two launches.
+    # Same results; the positions reported stay within what each row shares with row 0, and a
+    # row that gave up did not start later than planned
+    for polls in (1, 0):
+        ctx.set_resume_one_launch(polls)
+        tel_q, comp_q, status_q = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows, completions=completions)
+        pos_q = _resume_positions(ctx, C)
+        assert status_q == 0
+        _assert_equal(tel_q, comp_q, tel_g, comp_g, f"resume with wait_polls={polls}")
+        assert (pos_q % 64 == 0).all() and (pos_q <= shared).all() and pos_q[0] == 0
+        if polls == 1:
+            assert (pos_q <= pos).all()
+    ctx.set_resume_one_launch(4096)
     # same rows without resuming: same results
     ctx.set_resume_min_rows(0)
     tel_p, comp_p, _ = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows, completions=completions)
@@ -323,14 +344,16 @@ def test_resume_with_a_request_that_cannot_be_scheduled(ctx, resume_from_2048_ro
     for c in range(1, C):
         i, j = sorted(int(x) for x in rng.choice(inst.n, 2, replace=False))
         rows[c, i], rows[c, j] = rows[c, j], rows[c, i]
-    tel_g, comp_g, status = _gpu_simulate(ctx, s, inst.o, inst.M, rows)
-    assert status & kvsched.DEV_BAD_LENGTH
-    assert (tel_g == -1).all()
-    # and the same rows with well-formed lengths right afterwards (scratch is reused)
     tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
-    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
-    assert status == 0
-    _assert_equal(tel_g, comp_g, tel_o, comp_o, "after a faulty call")
+    for polls in (4096, 0):  # one launch (row 0's wave tells the waiting rows that nothing more comes), two launches
+        ctx.set_resume_one_launch(polls)
+        tel_g, comp_g, status = _gpu_simulate(ctx, s, inst.o, inst.M, rows)
+        assert status & kvsched.DEV_BAD_LENGTH
+        assert (tel_g == -1).all()
+        # and the same rows with well-formed lengths right afterwards (scratch is reused)
+        tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o, f"after a faulty call, wait_polls={polls}")
 
 
 def test_resume_plan_is_empty_below_the_row_threshold(ctx):
