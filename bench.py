@@ -33,13 +33,13 @@ PEAK_HBM_BYTES = 8.0e12
 OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for one request
 CFG = 3
 
-# HBM traffic of the dominant kernel per step (its two launches) on this workload, from rocprofv3
-# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE (16357 + 31226) KiB x 1.9997
-# (what a plain 256 MiB copy reads per KiB moved) + WRITE_SIZE (32385 + 58428) KiB x 1.0.  Valid
-# only for the kernel sources it was measured on; reported as null once they change.
-TRAFFIC_BYTES = int(((16357 + 31226) * 1.9997 + (32385 + 58428) * 1.0) * 1024)
+# HBM traffic of the dominant kernel per launch (one per step) on this workload, from rocprofv3
+# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 46957 KiB x 1.9997 (what a
+# plain 256 MiB copy reads per KiB moved) + WRITE_SIZE 89420 KiB x 1.0.  Valid only for the kernel
+# sources it was measured on; reported as null once they change.
+TRAFFIC_BYTES = int((46957 * 1.9997 + 89420 * 1.0) * 1024)
 TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
-TRAFFIC_SOURCES_SHA256 = "00487e87562805c9"
+TRAFFIC_SOURCES_SHA256 = "2c21d0c7c77d27be"
 
 
 def measured_traffic():

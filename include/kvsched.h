@@ -125,9 +125,9 @@ int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out);
  * Rows that repeat row 0 on their leading positions (local-search neighbours of a base order
  * passed as row 0) need not be placed from the start: with 16384 rows or more (see
  * kvsched_set_resume_min_rows) and no declared prefix, row 0's timeline state is saved every 64
- * positions and the three quarters of the rows that share most with row 0 (all but 4096 of them
- * when there are more than 16384) start from the last such state they share.  Results are the
- * same; kvsched_simulate_resume_positions() tells which rows did so.
+ * positions and every row that shares at least 64 leading positions with row 0 starts from the
+ * last such state it shares (see kvsched_set_resume_one_launch for how the states are handed
+ * over).  Results are the same; kvsched_simulate_resume_positions() tells which rows did so.
  * ERANGE: n * (ring size) >= 2^31 (round counters are int32), M >= 2^30, o_max bound too large.
  */
 int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n,
