@@ -221,7 +221,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="candidate rows the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="candidate rows the CPU oracle is timed on")
     ap.add_argument("--phase1", choices=("sorted_prefix", "local_swap"), default="sorted_prefix",
                     help="Phase-1 solver run inside the step (the candidate set is always built around the sorted-prefix order)")
     ap.add_argument("--workload", choices=("config3", "online", "predicted"), default="config3",

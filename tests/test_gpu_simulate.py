@@ -328,6 +328,28 @@ def test_rows_resumed_from_row0_snapshots(ctx, resume_from_2048_rows, cfg, n, C,
     _assert_equal(tel_p, comp_p, tel_g, comp_g, "with and without resuming")
 
 
+def test_resume_with_short_decode_lengths(ctx, resume_from_2048_rows):
+    # decode lengths up to 200: the smallest register file of the timeline kernel (the other
+    # resume cases run the two larger ones), under the three hand-over settings
+    rng = np.random.default_rng(77)
+    n, C, M = 900, 2200, 4000
+    s = rng.integers(1, 301, n).astype(np.int32)
+    o = rng.integers(1, 201, n).astype(np.int32)
+    base, _, _ = oracle.sortedF(s, o, M)
+    rows = np.broadcast_to(base, (C, n)).copy()
+    for c in range(1, C):
+        i, j = (int(x) for x in rng.choice(n, 2, replace=False))
+        rows[c, i], rows[c, j] = rows[c, j], rows[c, i]
+    tel_o, comp_o = oracle.simulate_many(s, o, M, rows, literal=False)
+    for polls in (4096, 1, 0):
+        ctx.set_resume_one_launch(polls)
+        tel_g, comp_g, status = _gpu_simulate(ctx, s, o, M, rows)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o, f"short decode lengths, wait_polls={polls}")
+        if polls != 1:  # (rows that poll once, all of them in flight from the start, find nothing yet)
+            assert (_resume_positions(ctx, C) > 0).sum() > C // 4
+
+
 def test_resume_with_a_request_that_cannot_be_scheduled(ctx, resume_from_2048_rows):
     # a request with s + o > M at position 300 of row 0: row 0 stops there, the snapshots behind
     # it are never taken, and every row that holds the request gets tel = -1 whether it would
