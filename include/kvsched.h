@@ -123,7 +123,7 @@ int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out);
  *                   (0 = no hint).  Never changes results; a wrong hint is detected and
  *                   reported as KVSCHED_DEV_BAD_ORDER.
  * Rows that repeat row 0 on their leading positions (local-search neighbours of a base order
- * passed as row 0) need not be placed from the start: with 16384 rows or more (see
+ * passed as row 0) need not be placed from the start: with enough rows and positions (see
  * kvsched_set_resume_min_rows) and no declared prefix, row 0's timeline state is saved every 64
  * positions and every row that shares at least 64 leading positions with row 0 starts from the
  * last such state it shares (see kvsched_set_resume_one_launch for how the states are handed
@@ -134,9 +134,12 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
                      const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out,
                      int32_t *completion_out, int32_t common_prefix, void *stream);
 
-/* Number of rows from which kvsched_simulate resumes rows from saved states of row 0 (default
- * 16384: below that the rows do not fill the GPU twice and the second launch costs more than the
- * skipped positions save); 0 = never. */
+/* Number of rows from which kvsched_simulate resumes rows from saved states of row 0.  Default
+ * KVSCHED_RESUME_AUTO: when the plan and the wait for row 0 are likely to cost less than the
+ * skipped positions save (at least 4096 rows, 385 positions and 8 million positions in all; 16384 rows
+ * when the states are handed over between two launches); 0 = never; rows > 0 = whenever there are
+ * that many rows (and more than 128 positions). */
+#define KVSCHED_RESUME_AUTO (-1)
 int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows);
 
 /* How the resumed rows get row 0's saved states.  wait_polls > 0 (default 4096): all rows run in

@@ -105,12 +105,19 @@ int scan_and_bound(kvsched_ctx *ctx, const int32_t *s, const int32_t *o, int32_t
 }
 
 constexpr int32_t kMinSharedPrefix = 64;  // shorter shared prefixes are not worth a launch
-// Resuming rows from snapshots of row 0 costs a second launch behind the one in which row 0
-// runs; it pays once the rows fill the chip about twice over (256 compute units x 4 SIMDs x 8 waves
-// = 8192 timelines in flight; measured on 16384 rows: 2.75 ms in one launch, 2.36 ms resumed).
-// The quarter of the rows that shares least with row 0 (at most half a chip's worth) runs from
-// the start next to row 0.
-constexpr int32_t kResumeMinRowsDefault = 16384;
+// Resuming rows from snapshots of row 0 costs the plan (which rows share what with row 0, sorted:
+// some 60 us for 16384 rows) and the wait for row 0's wave; it pays when there is enough work to
+// skip.  Measured on random one-swap neighbours of a base order, whole call, no resume / resumed in
+// one launch: n = 2000: 4096 rows 1.02 / 0.96 ms, 8192 rows 1.63 / 1.33, 16384 rows 2.96 / 2.25;
+// n = 500: 8192 rows 0.42 / 0.41, 16384 rows 0.74 / 0.69; n = 200: never (0.33 / 0.40 at 16384 rows).
+// Hence, unless the caller sets a row threshold of his own: at least 4096 rows, 6 blocks of 64
+// positions and 8 million positions in all.  In two launches (the quarter of the rows that shares least,
+// at most half a chip's worth, from the start next to row 0, then the others) the first launch lasts
+// a whole timeline whatever it holds: that pays from 16384 rows on (n = 2000: 2.96 / 2.53 ms).
+constexpr int32_t kResumeAutoMinRows = 4096;
+constexpr int32_t kResumeAutoMinRowsTwoLaunches = 16384;
+constexpr int32_t kResumeAutoMinBlocks = 6;
+constexpr int64_t kResumeAutoMinPositions = 8000000;
 constexpr int32_t kResumeFirstLaunchMax = 4096;
 constexpr int32_t kResumeWaitPollsDefault = 4096;  // about 14 ms
 
@@ -182,7 +189,7 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->timed = 0;
     ctx->resume_rows = 0;
     ctx->resume_first = 0;
-    ctx->resume_min_rows = kResumeMinRowsDefault;
+    ctx->resume_min_rows = KVSCHED_RESUME_AUTO;
     ctx->resume_wait_polls = kResumeWaitPollsDefault;
     ctx->ev0 = nullptr;
     ctx->ev1 = nullptr;
@@ -239,7 +246,7 @@ int kvsched_set_resume_one_launch(kvsched_ctx *ctx, int32_t wait_polls)
 
 int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows)
 {
-    if (!ctx || rows < 0) return KVSCHED_EINVAL;
+    if (!ctx || (rows < 0 && rows != KVSCHED_RESUME_AUTO)) return KVSCHED_EINVAL;
     ctx->resume_min_rows = rows;
     return KVSCHED_OK;
 }
@@ -325,8 +332,14 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     // No declared prefix: rows that agree with row 0 on their leading 64-position blocks resume
     // from snapshots of row 0's timeline (taken by row 0's own wave in the first launch).
     ctx->resume_rows = 0;
-    if (cp == 0 && ctx->resume_min_rows > 0 && C >= ctx->resume_min_rows && n > 2 * WAVE_POSITIONS &&
-        o_bound <= KVS_REG_MAX_O) {
+    bool resume = cp == 0 && n > 2 * WAVE_POSITIONS && o_bound <= KVS_REG_MAX_O;
+    if (ctx->resume_min_rows == KVSCHED_RESUME_AUTO)
+        resume = resume && (n - 1) / WAVE_POSITIONS >= kResumeAutoMinBlocks &&
+                 (int64_t)C * (int64_t)n >= kResumeAutoMinPositions &&
+                 C >= (ctx->resume_wait_polls > 0 ? kResumeAutoMinRows : kResumeAutoMinRowsTwoLaunches);
+    else
+        resume = resume && ctx->resume_min_rows > 0 && C >= ctx->resume_min_rows;
+    if (resume) {
         const int32_t nblk = (n - 1) / WAVE_POSITIONS;
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);

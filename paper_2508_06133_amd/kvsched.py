@@ -24,6 +24,7 @@ ONLINE_MAX_BACKLOG, ONLINE_MAX_WINDOW, ONLINE_MAX_O = 4096, 1024, 8192
 FEAS_SUM_OF_PEAKS, FEAS_PROFILE = 0, 1
 EXACT_MAX_N = 4096
 SOLVER_SORTED_PREFIX, SOLVER_LOCAL_SWAP, SOLVER_EXACT_DP = 0, 1, 2
+RESUME_AUTO = -1
 
 
 class KvschedError(RuntimeError):

@@ -270,7 +270,7 @@ def _resume_positions(ctx, C):
 def resume_from_2048_rows(ctx):
     ctx.set_resume_min_rows(2048)
     yield
-    ctx.set_resume_min_rows(16384)
+    ctx.set_resume_min_rows(-1)  # back to the automatic choice
     ctx.set_resume_one_launch(4096)
 
 
@@ -378,9 +378,21 @@ def test_resume_with_a_request_that_cannot_be_scheduled(ctx, resume_from_2048_ro
         _assert_equal(tel_g, comp_g, tel_o, comp_o, f"after a faulty call, wait_polls={polls}")
 
 
-def test_resume_plan_is_empty_below_the_row_threshold(ctx):
+def test_resume_is_chosen_by_size_unless_told_otherwise(ctx):
+    # the automatic choice: not for 4096 rows of 200 positions (three blocks: nothing to gain) ...
     inst = workloads.instance(2)
     base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
     rows = workloads.candidates(2, base, count=4096)
     _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
     assert (_resume_positions(ctx, 4096) == 0).all()
+    # ... but for 4096 neighbours of a 2000-position order, and not below 4096 rows
+    inst = workloads.instance(3)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rows = workloads.candidates(3, base)[:4096]
+    tel_g, _, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows, completions=False)
+    pos = _resume_positions(ctx, 4096)
+    assert status == 0 and (pos > 0).sum() > 2048
+    tel_h, _, _ = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows[:4000], completions=False)
+    assert (_resume_positions(ctx, 4000) == 0).all() and (tel_h == tel_g[:4000]).all()
+    with pytest.raises(Exception):
+        ctx.set_resume_min_rows(-2)
