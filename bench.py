@@ -137,6 +137,84 @@ def bench_online(args, ctx, dev) -> int:
     return 0
 
 
+def bench_phase1(args, ctx, dev) -> int:
+    """One step = the Phase-1 constructions of the library on resident inputs: the sorted-prefix
+    order under both feasibility tests and Local Swap Search on configs 3, 4 and 5 (n = 2000, 10000,
+    100000), the exact batches of Algorithm 2 on the first 100 requests of config 2."""
+    import torch
+
+    from paper_2508_06133_amd import kvsched, workloads
+
+    cases = []
+    for cfg in (3, 4, 5):
+        inst = workloads.instance(cfg)
+        cases.append((cfg, inst, torch.from_numpy(inst.s).to(dev), torch.from_numpy(inst.o).to(dev)))
+    small = workloads.instance(2, n=100)
+    s_small, o_small = torch.from_numpy(small.s).to(dev), torch.from_numpy(small.o).to(dev)
+    out = {}
+
+    def step():
+        for cfg, inst, s, o in cases:
+            out[cfg, "prefix"] = ctx.sortedF(s, o, inst.M, kvsched.TIE_LARGER, kvsched.FEAS_SUM_OF_PEAKS)
+            out[cfg, "prefix_profile"] = ctx.sortedF(s, o, inst.M, kvsched.TIE_LARGER, kvsched.FEAS_PROFILE)
+            out[cfg, "swap"] = ctx.local_swap(s, o, inst.M)
+        out[2, "exact"] = ctx.exact_dp(s_small, o_small, small.M)
+
+    calls = 3 * len(cases) + 1
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if ctx.device_status() != 0:
+        print("bench.py: device status", ctx.device_status(), file=sys.stderr)
+        return 1
+    requests = sum(3 * inst.n for _, inst, _, _ in cases) + small.n
+    result = {
+        "metric": "Phase-1 orders constructed/s (sorted prefix, Local Swap Search, exact batches)",
+        "value": calls * args.steps / wall,
+        "unit": "orders/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int64",
+        "data": "synthetic",
+        "config": {"workload": "Phase 1: sorted prefix (sum of peaks, profile) and Local Swap Search on configs 3, 4, 5 "
+                               "(n = 2000, 10000, 100000); Algorithm 2 on 100 requests of config 2",
+                   "calls_per_step": calls, "requests_per_step": requests},
+        "batches": {f"config{cfg}_{k}": int(v[-1].item()) for (cfg, k), v in out.items()},
+        "roofline": None,  # one workgroup per construction, a chain of short dependent steps: latency-bound
+    }
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure; only this baseline leg uses it
+
+        t0 = time.perf_counter()
+        n_cpu = 0
+        for cfg, inst, _, _ in cases[:2]:  # config 5 takes the oracle's quadratic Local Swap Search minutes
+            ref = {"prefix": oracle.sortedF(inst.s, inst.o, inst.M, feas_mode=0),  # sum of peaks
+                   "prefix_profile": oracle.sortedF(inst.s, inst.o, inst.M, feas_mode=1),  # profile
+                   "swap": oracle.local_swap(inst.s, inst.o, inst.M)}
+            n_cpu += 3
+            for k, r in ref.items():
+                if not (np.asarray(r[0]) == out[cfg, k][0].cpu().numpy()).all():
+                    print(f"bench.py: GPU and oracle disagree on config {cfg} {k}", file=sys.stderr)
+                    return 1
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n_cpu / cpu_s, "unit": "orders/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the {n_cpu} constructions on configs 3 and 4 (oracle_sortedF, "
+                                            f"oracle_local_swap), single thread, {cpu_s:.1f} s"}
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
 def bench_predicted(args, ctx, dev) -> int:
     """One step = Phase 1 on the lower bounds + the 16384 config-3 candidate orders run under
     predicted decode lengths (running estimates from the lower bounds, ordered eviction) + argmin."""
@@ -224,11 +302,12 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=16384, help="candidate rows the CPU oracle is timed on")
     ap.add_argument("--phase1", choices=("sorted_prefix", "local_swap"), default="sorted_prefix",
                     help="Phase-1 solver run inside the step (the candidate set is always built around the sorted-prefix order)")
-    ap.add_argument("--workload", choices=("config3", "online", "predicted"), default="config3",
+    ap.add_argument("--workload", choices=("config3", "online", "predicted", "phase1"), default="config3",
                     help="config3: the headline workload; online: the paper's Poisson-arrival experiment "
                          "(Section 7) as a batch of independent streams through kvsched_online; predicted: the "
                          "config-3 candidates run under interval predictions of the decode lengths "
-                         "(kvsched_simulate_predicted, estimates started from the lower bounds)")
+                         "(kvsched_simulate_predicted, estimates started from the lower bounds); phase1: the "
+                         "Phase-1 constructions (sorted prefix, Local Swap Search, exact batches) on configs 3, 4, 5")
     ap.add_argument("--gamma", type=float, default=0.6, help="prediction confidence inf l_i / u_i of --workload predicted")
     ap.add_argument("--online-seeds", type=int, default=200,
                     help="arrival sequences per load level of the online workload (10 loads x 3 policies each)")
@@ -252,6 +331,8 @@ def main() -> int:
     ctx = kvsched.Context(0)
     if args.workload == "online":
         return bench_online(args, ctx, dev)
+    if args.workload == "phase1":
+        return bench_phase1(args, ctx, dev)
     if args.workload == "predicted":
         return bench_predicted(args, ctx, dev)
 

@@ -130,10 +130,11 @@ __device__ int count_fitting(int rem, G g, int32_t M, Lds &L, int slot)
 
 // Do the k requests at places [a, a + k) of the (s+o, o, id) order, started together, stay within
 // M at every completion time?  Memory at time o_j = sum over {i: o_i >= o_j} of (s_i + o_j)
-// (Section 4).  The ids are visited in decreasing o through the (o, id) order; running sums of s
-// and of the count over the members seen so far give the memory at each member's completion (among
-// equal o the last one visited sees the whole group, the earlier ones a part of it, which cannot
-// exceed it).  Every thread receives the answer.
+// (Section 4).  The ids are visited in decreasing o through a list in ascending o that holds every
+// member (all requests in (o, id) order, or the candidates of the batch sorted by o); running sums
+// of s and of the count over the members seen so far give the memory at each member's completion
+// (among equal o the last one visited sees the whole group, the earlier ones a part of it, which
+// cannot exceed it).  Every thread receives the answer.
 __device__ bool profile_fits(int n, int a, int k, const int32_t *s, const int32_t *o, const int *by_o,
                              const int *pos_w, int32_t M, Lds &L)
 {
@@ -174,7 +175,8 @@ __device__ bool profile_fits(int n, int a, int k, const int32_t *s, const int32_
     return __syncthreads_or(viol) == 0;
 }
 
-template <bool IN_LDS>
+// PROFILE: feas_mode is KVSCHED_FEAS_PROFILE (its code stays out of the other instantiation)
+template <bool IN_LDS, bool PROFILE>
 __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *s_in, const int32_t *o_in, int32_t M,
                                                       int32_t ga, int32_t gb, int32_t tie_rule, int32_t feas_mode,
                                                       int32_t *order_out, int32_t *batch_end_out, double *F_out,
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         int *t = cur; cur = alt; alt = t;
     }
     const int *sorted = cur;  // (s+o, o, id) ascending
-    if (feas_mode == KVSCHED_FEAS_PROFILE) {
+    if (PROFILE) {
         for (int i = tid; i < n; i += TPB) pos_w[sorted[i]] = i;
     }
 
@@ -310,15 +312,46 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
         const long long W0 = cumW[a], S0 = cumS[a], G0 = cumG[a];
         // feasible extent K: the longest prefix within the budget (feasibility is monotone in k)
         int K = count_fitting(rem, [&](long long k) { return cumW[a + k] - W0; }, M, L, 0);  // sum of peaks <= M
-        if (feas_mode == KVSCHED_FEAS_PROFILE && K >= 1 && K < rem) {
+        if (PROFILE && K >= 1 && K < rem) {
             // Started together, the prefix must stay within M at every completion time.  The sum of
             // peaks bounds that memory from above (so K is feasible), and the memory at the earliest
             // completion is at least sum (s_i + 1) (so nothing beyond hi is); bisect in between.
             int lo = K;
             int hi = count_fitting(rem, [&](long long k) { return (cumW[a + k] - W0) - (cumS[a + k] - S0) + k; }, M, L, 1);
+            const int *list = by_o;  // ascending o, holds every member of any prefix probed
+            int len = n;
+            if (!IN_LDS && lo < hi) {
+                // Many requests: a probe through all of them costs more than the batch is worth, and hi
+                // (nothing beyond it fits even at the earliest completion) can lie far above the answer
+                // when decode lengths are long.  So the candidates of this batch are sorted by o once
+                // (stable passes, two spare arrays) and serve every probe; and only the first `cap` of
+                // them, doubled while all of them fit.
+                int cap = min(hi, lo + max(lo, TPB));
+                for (;;) {
+                    const int *src = sorted + a;
+                    int *dst = alt, *oth = pos_w + (((size_t)n + 64) & ~(size_t)63);
+                    for (int shift = 0; shift < bits_of(omax); shift += 8) {
+                        radix_pass(src, dst, cap, shift, key_o, L.radix);
+                        src = dst;
+                        dst = oth;
+                        oth = (int *)src;
+                    }
+                    list = src;
+                    len = cap;
+                    if (cap < hi) {
+                        if (profile_fits(len, a, cap, s, o, list, pos_w, M, L)) {
+                            lo = cap;
+                            cap = min(hi, 2 * cap);
+                            continue;
+                        }
+                        hi = cap - 1;
+                    }
+                    break;
+                }
+            }
             while (lo < hi) {
                 const int mid = lo + (hi - lo + 1) / 2;
-                if (profile_fits(n, a, mid, s, o, by_o, pos_w, M, L)) lo = mid;
+                if (profile_fits(len, a, mid, s, o, list, pos_w, M, L)) lo = mid;
                 else hi = mid - 1;
             }
             K = lo;
@@ -439,23 +472,33 @@ int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
     int *batch_of = by_o + np;
     int *pos_w = batch_of + np;
     const size_t arrays = kvs_sortedF_scratch_bytes(n);
+    const int profile = feas_mode == KVSCHED_FEAS_PROFILE ? 1 : 0;
     constexpr size_t kLdsPerWorkgroup = 160 * 1024;
     if (arrays + sizeof(Lds) <= kLdsPerWorkgroup) {
         // more than 64 KB of LDS in all: the kernel's limit on the dynamic part is raised first, as far as needed
-        static size_t granted = 64 * 1024 - sizeof(Lds);
-        if (arrays > granted) {
-            if (hipFuncSetAttribute((const void *)sortedF_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)arrays) != hipSuccess)
+        static size_t granted[2] = {64 * 1024 - sizeof(Lds), 64 * 1024 - sizeof(Lds)};
+        if (arrays > granted[profile]) {
+            const void *fn = profile ? (const void *)sortedF_kernel<true, true> : (const void *)sortedF_kernel<true, false>;
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)arrays) != hipSuccess)
                 return KVSCHED_EHIP;
-            granted = arrays;
+            granted[profile] = arrays;
         }
-        hipLaunchKernelGGL(sortedF_kernel<true>, dim3(1), dim3(TPB), arrays, st, n, s, o, M, ga, gb, tie_rule,
+        if (profile)
+            hipLaunchKernelGGL((sortedF_kernel<true, true>), dim3(1), dim3(TPB), arrays, st, n, s, o, M, ga, gb, tie_rule,
+                               feas_mode, order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW,
+                               cumS, cumG, batch_of, pos_w, d_words);
+        else
+            hipLaunchKernelGGL((sortedF_kernel<true, false>), dim3(1), dim3(TPB), arrays, st, n, s, o, M, ga, gb, tie_rule,
+                               feas_mode, order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW,
+                               cumS, cumG, batch_of, pos_w, d_words);
+    } else if (profile) {
+        hipLaunchKernelGGL((sortedF_kernel<false, true>), dim3(1), dim3(TPB), 0, st, n, s, o, M, ga, gb, tie_rule,
                            feas_mode, order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS,
                            cumG, batch_of, pos_w, d_words);
     } else {
-        hipLaunchKernelGGL(sortedF_kernel<false>, dim3(1), dim3(TPB), 0, st, n, s, o, M, ga, gb, tie_rule, feas_mode,
-                           order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS, cumG,
-                           batch_of, pos_w, d_words);
+        hipLaunchKernelGGL((sortedF_kernel<false, false>), dim3(1), dim3(TPB), 0, st, n, s, o, M, ga, gb, tie_rule,
+                           feas_mode, order_out, batch_end_out, F_out, num_batches_out, buf0, buf1, by_o, cumW, cumS,
+                           cumG, batch_of, pos_w, d_words);
     }
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

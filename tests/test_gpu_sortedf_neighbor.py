@@ -51,7 +51,7 @@ def test_sortedF_configs(ctx, cfg):
     _check_sortedF(ctx, inst.s, inst.o, inst.M, f"config {cfg}")
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_sortedF_profile_feasibility_configs(ctx, cfg):
     inst = workloads.instance(cfg)
     _check_sortedF(ctx, inst.s, inst.o, inst.M, f"config {cfg}", feas_mode=1)
