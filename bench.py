@@ -352,6 +352,9 @@ def main() -> int:
     comp = torch.empty((C, n), dtype=torch.int32, device=dev)
     best = torch.empty(2, dtype=torch.int64, device=dev)
 
+    p1_out = (order_d, ends_d, F_d, nb_d)  # Phase 1 writes into the same tensors every step
+    ctx.set_o_max(int(inst.o.max()))  # the caller's bound on decode lengths: no read-back inside the step
+
     ctx.enable_timing(True)
     stream = torch.cuda.current_stream()
 
@@ -359,7 +362,7 @@ def main() -> int:
         if args.phase1 == "local_swap":
             ctx.local_swap(s, o, M)
         else:
-            ctx.sortedF(s, o, M)
+            ctx.sortedF(s, o, M, out=p1_out)
         ctx.simulate(orders, s, o, M, tel_out=tel, completion_out=comp)
         ctx.argmin(tel, result_out=best)
 

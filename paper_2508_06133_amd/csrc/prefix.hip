@@ -70,19 +70,52 @@ __global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *order
     if (lane == 0) blocks[c] = nb;
 }
 
-// Row indices in ascending order of blocks[], equal values by ascending row (stable): row 0
-// comes first.  One workgroup.
+// Row indices in ascending order of blocks[], row 0 first.  One workgroup.  Up to 2047 blocks (any
+// order of up to 131072 positions) it is a counting sort in LDS: count, scan, scatter through one
+// cursor per value; rows of equal value come in no particular order (the order only decides which
+// rows are dispatched first).  Beyond that, stable 8-bit radix passes.
+constexpr int KVS_COUNT_SORT_KEYS = 2048;
+
 __global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blocks, int32_t C, int32_t *tmp,
                                                               int32_t *sorted)
 {
     __shared__ RadixLds<1024> L;
     __shared__ int sh_max[16];
+    __shared__ int cnt[KVS_COUNT_SORT_KEYS];
+    __shared__ int wave_total[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int mx = 0;
-    for (int i = threadIdx.x; i < C; i += 1024) mx = max(mx, blocks[i]);
+    for (int i = tid; i < C; i += 1024) mx = max(mx, blocks[i]);
     for (int d = 32; d > 0; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
-    if ((threadIdx.x & 63) == 0) sh_max[threadIdx.x >> 6] = mx;
+    if (lane == 0) sh_max[wave] = mx;
+    cnt[tid] = 0;
+    cnt[tid + 1024] = 0;
     __syncthreads();
     for (int w = 0; w < 16; ++w) mx = max(mx, sh_max[w]);
+    if (mx < KVS_COUNT_SORT_KEYS) {
+        for (int i = tid; i < C; i += 1024) atomicAdd(&cnt[blocks[i]], 1);
+        __syncthreads();
+        // exclusive scan of the 2048 counts, two consecutive ones per thread
+        const int c0 = cnt[2 * tid], c1 = cnt[2 * tid + 1];
+        int incl = c0 + c1;
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        if (lane == 63) wave_total[wave] = incl;
+        __syncthreads();
+        int off = 0;
+        for (int w = 0; w < wave; ++w) off += wave_total[w];
+        const int start = off + incl - (c0 + c1);
+        cnt[2 * tid] = start + (tid == 0 ? 1 : 0);  // (slot 0 is row 0's: its value is 0, the lowest)
+        cnt[2 * tid + 1] = start + c0;
+        __syncthreads();
+        for (int i = tid; i < C; i += 1024) {
+            if (i == 0) sorted[0] = 0;
+            else sorted[atomicAdd(&cnt[blocks[i]], 1)] = i;
+        }
+        return;
+    }
     auto key = [blocks](int id) { return blocks[id]; };
     // one 8-bit pass per byte of the largest count; the ids start in whichever buffer makes the
     // last pass land in `sorted`

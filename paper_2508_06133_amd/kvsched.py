@@ -173,15 +173,23 @@ class Context:
             raise KvschedError(rc, "kvsched_simulate_resume_positions")
         return out
 
-    def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS):
+    def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS, out=None):
         """-> (order [n] int32, batch_end [n] int32, F [n] float64, num_batches [1] int32); the first
-        num_batches entries of batch_end / F are meaningful."""
+        num_batches entries of batch_end / F are meaningful.  out: the four tensors to write into
+        (a caller in a loop keeps them; otherwise they are allocated, batch_end and F zero-filled)."""
         n = s.shape[0]
         dev = s.device
-        order = torch.empty(n, dtype=torch.int32, device=dev)
-        ends = torch.zeros(n, dtype=torch.int32, device=dev)
-        F = torch.zeros(n, dtype=torch.float64, device=dev)
-        nb = torch.zeros(1, dtype=torch.int32, device=dev)
+        if out is None:
+            order = torch.empty(n, dtype=torch.int32, device=dev)
+            ends = torch.zeros(n, dtype=torch.int32, device=dev)
+            F = torch.zeros(n, dtype=torch.float64, device=dev)
+            nb = torch.zeros(1, dtype=torch.int32, device=dev)
+        else:
+            order, ends, F, nb = out
+            _dev(order, torch.int32, "order"), _dev(ends, torch.int32, "batch_end")
+            _dev(F, torch.float64, "F"), _dev(nb, torch.int32, "num_batches")
+            if order.shape[0] < n or ends.shape[0] < n or F.shape[0] < n or nb.shape[0] < 1:
+                raise ValueError("sortedF: output tensors too short")
         rc = _lib.kvsched_sortedF(self._h, n, _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
                                   int(tie_rule), int(feas_mode), order.data_ptr(), ends.data_ptr(), F.data_ptr(),
                                   nb.data_ptr(), _stream())
