@@ -123,6 +123,12 @@ constexpr int32_t kResumeWaitPollsDefault = 4096;  // about 14 ms
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
+__global__ void kvs_copy_i32(int32_t *dst, const int32_t *src, int32_t n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
 __global__ void kvs_fill_zero_i32(int32_t *dst, int32_t n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -332,6 +338,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     // No declared prefix: rows that agree with row 0 on their leading 64-position blocks resume
     // from snapshots of row 0's timeline (taken by row 0's own wave in the first launch).
     ctx->resume_rows = 0;
+    const int32_t *resumed_blocks = nullptr, *resumed_row0 = nullptr;
     bool resume = cp == 0 && n > 2 * WAVE_POSITIONS && o_bound <= KVS_REG_MAX_O;
     if (ctx->resume_min_rows == KVSCHED_RESUME_AUTO)
         resume = resume && (n - 1) / WAVE_POSITIONS >= kResumeAutoMinBlocks &&
@@ -344,13 +351,15 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
         const size_t snap_bytes = align256(sizeof(int32_t) * (size_t)nblk * (size_t)stride);
-        rc = ensure_scratch(ctx, 3 * list_bytes + snap_bytes + align256(sizeof(int32_t) * (size_t)nblk));
+        const size_t flag_bytes = align256(sizeof(int32_t) * (size_t)nblk);
+        rc = ensure_scratch(ctx, 3 * list_bytes + snap_bytes + flag_bytes + align256(sizeof(int32_t) * (size_t)n));
         if (rc != KVSCHED_OK) return rc;
         int32_t *blocks = (int32_t *)ctx->d_scratch;
         int32_t *sorted = (int32_t *)((char *)ctx->d_scratch + list_bytes);
         int32_t *tmp = (int32_t *)((char *)ctx->d_scratch + 2 * list_bytes);
         int32_t *snaps = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes);
         int32_t *flags = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes);
+        int32_t *row0 = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes + flag_bytes);
         rc = kvs_launch_shared_blocks(orders, C, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
         rc = kvs_launch_sort_by_blocks(blocks, C, tmp, sorted, st);
@@ -399,7 +408,13 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
             if (hipEventRecord(ctx->ev1, st) != hipSuccess) return KVSCHED_EHIP;
             ctx->timed = 1;
         }
-        if (completion_out) {
+        if (completion_out && p.completion_by_position) {
+            // the permute pass takes the positions a row did not place from this copy of row 0's row
+            hipLaunchKernelGGL(kvs_copy_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, row0, completion_out, n);
+            if (hipGetLastError() != hipSuccess) return KVSCHED_EHIP;
+            resumed_blocks = blocks;
+            resumed_row0 = row0;
+        } else if (completion_out) {
             rc = kvs_launch_copy_row0_prefix(orders, C, n, sorted, first, blocks, p.completion_by_position,
                                              completion_out, st);
             if (rc != KVSCHED_OK) return rc;
@@ -415,7 +430,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         if (rc != KVSCHED_OK) return rc;
     }
     if (p.completion_by_position) {  // this pass over the rows checks them as well
-        rc = kvs_launch_permute_rows(orders, C, n, completion_out, tel_out, ctx->d_words, st);
+        rc = kvs_launch_permute_rows(orders, C, n, completion_out, tel_out, ctx->d_words, resumed_blocks, resumed_row0, st);
     } else {
         rc = kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
     }

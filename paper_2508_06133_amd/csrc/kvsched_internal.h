@@ -137,8 +137,10 @@ int kvs_launch_sortedF(int32_t n, const int32_t *s, const int32_t *o, int32_t M,
 // permute.hip: rows of completion rounds from position order to request-id order, in place; rows
 // that are no permutation get tel = -1 and KVSCHED_DEV_BAD_ORDER (what kvs_launch_check_orders does)
 constexpr int32_t KVS_PERMUTE_MAX_N = 15872;  // one row and its bitmap must fit in 64 KB of LDS
+// resume_block / row0 (or NULL): row c placed only the positions from 64 resume_block[c] on; the
+// completion rounds before them are row0[k], row 0's in position order
 int kvs_launch_permute_rows(const int32_t *orders, int32_t C, int32_t n, int32_t *completion, int64_t *tel_out,
-                            int32_t *d_words, hipStream_t st);
+                            int32_t *d_words, const int32_t *resume_block, const int32_t *row0, hipStream_t st);
 
 // horizon.hip
 int kvs_launch_apply_best_move(const int32_t *order, int32_t n, const int32_t *moves, const int64_t *result,

@@ -7,18 +7,22 @@
 // by position (256 contiguous bytes per 64 positions) and this kernel permutes each row in
 // place: one workgroup per row, the row staged in LDS, read and written coalesced.  The same pass
 // over the order row checks that it is a permutation of 0..n-1 (a bitmap of n bits beside the row).
+// A row that was resumed from row 0's timeline after 64 b positions did not place those itself: their
+// completion rounds are row 0's, taken from a copy of row 0's row in position order.
 #include "kvsched_internal.h"
 
 namespace {
 
 __global__ __launch_bounds__(256) void permute_rows_kernel(const int32_t *orders, int32_t n, int32_t *completion,
-                                                           int64_t *tel_out, int32_t *words)
+                                                           int64_t *tel_out, int32_t *words,
+                                                           const int32_t *resume_block, const int32_t *row0)
 {
     extern __shared__ int row_by_id[];
     unsigned int *seen = (unsigned int *)(row_by_id + n);  // one bit per request id
     const int32_t *order = orders + (size_t)blockIdx.x * (size_t)n;
     int32_t *comp = completion + (size_t)blockIdx.x * (size_t)n;
     for (int i = threadIdx.x; i < ((n + 31) >> 5); i += blockDim.x) seen[i] = 0;
+    const int shared = resume_block ? min(64 * resume_block[blockIdx.x], n) : 0;  // positions placed by row 0 only
     __syncthreads();
     int bad = 0;
     for (int k = threadIdx.x; k < n; k += blockDim.x) {
@@ -26,7 +30,7 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(const int32_t *orders
         const int r = min(max(raw, 0), n - 1);
         const unsigned int bit = 1u << (r & 31);
         if (raw != r || (atomicOr(&seen[r >> 5], bit) & bit)) bad = 1;  // out of range, or met before
-        row_by_id[r] = comp[k];
+        row_by_id[r] = k < shared ? row0[k] : comp[k];
     }
     if (__syncthreads_or(bad) && threadIdx.x == 0) {  // the row is no permutation: its results are void
         tel_out[blockIdx.x] = -1;
@@ -38,11 +42,11 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(const int32_t *orders
 }  // namespace
 
 int kvs_launch_permute_rows(const int32_t *orders, int32_t C, int32_t n, int32_t *completion, int64_t *tel_out,
-                            int32_t *d_words, hipStream_t st)
+                            int32_t *d_words, const int32_t *resume_block, const int32_t *row0, hipStream_t st)
 {
     if (n > KVS_PERMUTE_MAX_N) return KVSCHED_ERANGE;
     const size_t lds = sizeof(int32_t) * ((size_t)n + (((size_t)n + 31) >> 5));
     hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)C), dim3(256), lds, st, orders, n, completion, tel_out,
-                       d_words);
+                       d_words, resume_block, row0);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
