@@ -278,6 +278,12 @@ int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t 
  *   tel_out     [K]    int64 or NULL: latency of every neighbour (-1 for a malformed move)
  *   result_out  [3]    int64: {index of the best move or -1 if none is valid, its total
  *               latency, total latency of base_order itself}
+ * Work that the neighbours share with the base order is done once: when no move touches a
+ * position before p >= 64, those p positions are placed once and every timeline starts from
+ * there; otherwise, with enough moves and positions (kvsched_set_resume_min_rows, with the moves
+ * counted as rows), the base order's timeline saves its state every 64 positions and a move on
+ * positions i, j starts from the last state before min(i, j) (handed over within the launch, see
+ * kvsched_set_resume_one_launch).  Results are the same.
  */
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n,
                           const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o,

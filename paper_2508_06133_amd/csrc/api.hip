@@ -123,6 +123,15 @@ constexpr int32_t kResumeWaitPollsDefault = 4096;  // about 14 ms
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
+// Are C timelines of n positions to be resumed from the states of the first of them?
+static bool resume_pays(const kvsched_ctx *ctx, int32_t C, int32_t n, int32_t o_bound)
+{
+    if (n <= 2 * WAVE_POSITIONS || o_bound > KVS_REG_MAX_O) return false;
+    if (ctx->resume_min_rows != KVSCHED_RESUME_AUTO) return ctx->resume_min_rows > 0 && C >= ctx->resume_min_rows;
+    return (n - 1) / WAVE_POSITIONS >= kResumeAutoMinBlocks && (int64_t)C * (int64_t)n >= kResumeAutoMinPositions &&
+           C >= (ctx->resume_wait_polls > 0 ? kResumeAutoMinRows : kResumeAutoMinRowsTwoLaunches);
+}
+
 __global__ void kvs_copy_i32(int32_t *dst, const int32_t *src, int32_t n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -339,14 +348,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     // from snapshots of row 0's timeline (taken by row 0's own wave in the first launch).
     ctx->resume_rows = 0;
     const int32_t *resumed_blocks = nullptr, *resumed_row0 = nullptr;
-    bool resume = cp == 0 && n > 2 * WAVE_POSITIONS && o_bound <= KVS_REG_MAX_O;
-    if (ctx->resume_min_rows == KVSCHED_RESUME_AUTO)
-        resume = resume && (n - 1) / WAVE_POSITIONS >= kResumeAutoMinBlocks &&
-                 (int64_t)C * (int64_t)n >= kResumeAutoMinPositions &&
-                 C >= (ctx->resume_wait_polls > 0 ? kResumeAutoMinRows : kResumeAutoMinRowsTwoLaunches);
-    else
-        resume = resume && ctx->resume_min_rows > 0 && C >= ctx->resume_min_rows;
-    if (resume) {
+    if (cp == 0 && resume_pays(ctx, C, n, o_bound)) {
         const int32_t nblk = (n - 1) / WAVE_POSITIONS;
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
@@ -362,7 +364,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         int32_t *row0 = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes + flag_bytes);
         rc = kvs_launch_shared_blocks(orders, C, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
-        rc = kvs_launch_sort_by_blocks(blocks, C, tmp, sorted, st);
+        rc = kvs_launch_sort_by_blocks(blocks, C, 0, tmp, sorted, st);
         if (rc != KVSCHED_OK) return rc;
         int32_t first = 0;
         if (ctx->resume_wait_polls > 0) {
@@ -582,6 +584,17 @@ int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t 
     }
 }
 
+// Scratch of kvsched_best_neighbor: K + 1 latencies, the state of a shared prefix, and the plan for
+// resuming each move's timeline from the base order's (three lists of K + 1 entries, a flag and a saved
+// state of the largest kind per 64 positions).
+static size_t neighbor_scratch_bytes(int32_t K, int32_t n)
+{
+    const size_t nblk = (size_t)((n - 1) / WAVE_POSITIONS);
+    return align256(sizeof(int64_t) * ((size_t)K + 1)) + state_bytes() +
+           3 * align256(sizeof(int32_t) * ((size_t)K + 1)) + align256(sizeof(int32_t) * nblk) +
+           align256(sizeof(int32_t) * nblk * KVS_STATE_MAX_WORDS);
+}
+
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,
                           const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out, int64_t *result_out,
                           void *stream)
@@ -590,9 +603,9 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     if (rc != KVSCHED_OK) return rc;
     if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    // scratch: [K+1] latencies (neighbours, then the base order) | state of the shared prefix
+    // scratch: [K+1] latencies (neighbours, then the base order) | state of the shared prefix | resume plan
     const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1));
-    rc = ensure_scratch(ctx, tel_bytes + state_bytes());
+    rc = ensure_scratch(ctx, neighbor_scratch_bytes(K, n));
     if (rc != KVSCHED_OK) return rc;
     int64_t *tel = (int64_t *)ctx->d_scratch;
     int32_t *state = (int32_t *)((char *)ctx->d_scratch + tel_bytes);
@@ -623,7 +636,38 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
         p.k_begin = min_pos;
         p.state_in = state;
     }
-    rc = run_timelines(ctx, p, H, st);
+    if (!p.state_in && ctx->resume_wait_polls > 0 && resume_pays(ctx, K + 1, n, o_bound)) {
+        // Moves anywhere in the order (no prefix common to all): a move at positions i, j leaves the
+        // positions before min(i, j) as they are, so its timeline starts from the state the base
+        // order's timeline (run in the same launch) has saved at the last 64-position boundary before.
+        const int32_t C = K + 1;
+        const int32_t nblk = (n - 1) / WAVE_POSITIONS;
+        const int32_t stride = kvs_reg_state_words(o_bound);
+        const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
+        char *plan = (char *)ctx->d_scratch + tel_bytes + state_bytes();
+        int32_t *blocks = (int32_t *)plan;
+        int32_t *sorted = (int32_t *)(plan + list_bytes);
+        int32_t *tmp = (int32_t *)(plan + 2 * list_bytes);
+        int32_t *flags = (int32_t *)(plan + 3 * list_bytes);
+        int32_t *snaps = (int32_t *)(plan + 3 * list_bytes + align256(sizeof(int32_t) * (size_t)nblk));
+        rc = kvs_launch_move_blocks(moves, K, n, blocks, st);
+        if (rc != KVSCHED_OK) return rc;
+        rc = kvs_launch_sort_by_blocks(blocks, C, K, tmp, sorted, st);
+        if (rc != KVSCHED_OK) return rc;
+        hipLaunchKernelGGL(kvs_fill_zero_i32, dim3((unsigned)((nblk + 255) / 256)), dim3(256), 0, st, flags, nblk);
+        if (hipGetLastError() != hipSuccess) return KVSCHED_EHIP;
+        p.cand_list = sorted;
+        p.resume_block = blocks;
+        p.snapshots = snaps;
+        p.snap_stride = stride;
+        p.snap_blocks = nblk;
+        p.snap_flags = flags;
+        p.snap_wait_polls = ctx->resume_wait_polls;
+        p.snap_cand = K;
+        rc = kvs_launch_simulate_reg(p, st);
+    } else {
+        rc = run_timelines(ctx, p, H, st);
+    }
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_check_moves(moves, K, n, tel, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
@@ -645,7 +689,7 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     if (K < 1 || K == INT32_MAX || n < 1) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     // scratch: [K+1] latencies of best_neighbor | new order [n] | completion rounds [n] | one latency
-    const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1)) + state_bytes();  // best_neighbor's part
+    const size_t tel_bytes = neighbor_scratch_bytes(K, n);  // best_neighbor's part
     const size_t row_bytes = align256(sizeof(int32_t) * (size_t)n);
     int rc = ctx ? ensure_scratch(ctx, tel_bytes + 2 * row_bytes + 256) : KVSCHED_EINVAL;
     if (rc != KVSCHED_OK) return rc;

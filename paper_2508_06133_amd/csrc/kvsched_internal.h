@@ -67,7 +67,7 @@ struct SimParams {
     // Register kernel, explicit rows only: resuming rows from snapshots of row 0.  When cand_list is
     // set, wave w of the launch runs candidate cand_list[w].  Snapshot j (j >= 1) is the timeline
     // state of row 0 after 64 j positions, at snapshots + (j - 1) * snap_stride.  The wave that runs
-    // candidate 0 writes snapshots 1..snap_blocks (word 1 of a snapshot, the round t, is set to -1 by
+    // candidate snap_cand (row 0) writes snapshots 1..snap_blocks (word 1 of a snapshot, the round t, is set to -1 by
     // the host beforehand: a snapshot that is never taken poisons whoever resumes from it); a
     // candidate c with resume_block[c] = b > 0 starts from snapshot b at position 64 b.
     // With snap_flags (snap_blocks words, zero at launch) both happen in ONE launch: the wave of
@@ -82,6 +82,7 @@ struct SimParams {
     int32_t snap_blocks = 0;
     int32_t *snap_flags = nullptr;
     int32_t snap_wait_polls = 0;  // polls (about 3 us each) a candidate waits for its snapshot at most
+    int32_t snap_cand = 0;        // the candidate whose wave writes the snapshots (row 0; the base order among moves)
 };
 constexpr int KVS_STATE_HEAD_WORDS = 192;
 constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 65 * 64;
@@ -169,7 +170,9 @@ int kvs_launch_broadcast_prefix(const int32_t *prefix, int32_t cp, int32_t C, in
                                 hipStream_t st);
 // rows resumed from snapshots of row 0 (see SimParams)
 int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, hipStream_t st);
-int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t *tmp, int32_t *sorted, hipStream_t st);
+int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t first_row, int32_t *tmp, int32_t *sorted,
+                              hipStream_t st);
+int kvs_launch_move_blocks(const int32_t *moves, int32_t K, int32_t n, int32_t *blocks, hipStream_t st);
 int kvs_launch_copy_row0_prefix(const int32_t *orders, int32_t C, int32_t n, const int32_t *sorted, int32_t first,
                                 const int32_t *blocks, int32_t by_position, int32_t *completion, hipStream_t st);
 int kvs_launch_mark_snapshots_unusable(int32_t *snapshots, int32_t count, int32_t stride, hipStream_t st);

@@ -70,14 +70,32 @@ __global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *order
     if (lane == 0) blocks[c] = nb;
 }
 
-// Row indices in ascending order of blocks[], row 0 first.  One workgroup.  Up to 2047 blocks (any
+// The same count for the neighbours of a base order given as moves: a swap or an insertion of
+// positions i, j leaves the positions before min(i, j) as they are; a move that changes nothing
+// shares all of them (up to the cap), a malformed one is taken to share nothing.  blocks[K] = 0 stands
+// for the base order itself, the timeline that takes the snapshots.
+__global__ __launch_bounds__(256) void move_blocks_kernel(const int32_t *moves, int32_t K, int32_t n, int32_t *blocks)
+{
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m > K) return;
+    int nb = 0;
+    if (m < K) {
+        const int ty = moves[3 * (size_t)m], i = moves[3 * (size_t)m + 1], j = moves[3 * (size_t)m + 2];
+        const bool ok = (ty == KVSCHED_MOVE_SWAP || ty == KVSCHED_MOVE_INSERT) && i >= 0 && j >= 0 && i < n && j < n;
+        const int cap = (n - 1) >> 6;
+        if (ok) nb = i == j ? cap : min(min(i, j) >> 6, cap);
+    }
+    blocks[m] = nb;
+}
+
+// Row indices in ascending order of blocks[], row first_row (whose count is 0) first.  One workgroup.  Up to 2047 blocks (any
 // order of up to 131072 positions) it is a counting sort in LDS: count, scan, scatter through one
 // cursor per value; rows of equal value come in no particular order (the order only decides which
 // rows are dispatched first).  Beyond that, stable 8-bit radix passes.
 constexpr int KVS_COUNT_SORT_KEYS = 2048;
 
-__global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blocks, int32_t C, int32_t *tmp,
-                                                              int32_t *sorted)
+__global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blocks, int32_t C, int32_t first_row,
+                                                              int32_t *tmp, int32_t *sorted)
 {
     __shared__ RadixLds<1024> L;
     __shared__ int sh_max[16];
@@ -107,11 +125,11 @@ __global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blo
         int off = 0;
         for (int w = 0; w < wave; ++w) off += wave_total[w];
         const int start = off + incl - (c0 + c1);
-        cnt[2 * tid] = start + (tid == 0 ? 1 : 0);  // (slot 0 is row 0's: its value is 0, the lowest)
+        cnt[2 * tid] = start + (tid == 0 ? 1 : 0);  // (slot 0 is first_row's: its value is 0, the lowest)
         cnt[2 * tid + 1] = start + c0;
         __syncthreads();
         for (int i = tid; i < C; i += 1024) {
-            if (i == 0) sorted[0] = 0;
+            if (i == first_row) sorted[0] = i;
             else sorted[atomicAdd(&cnt[blocks[i]], 1)] = i;
         }
         return;
@@ -121,7 +139,8 @@ __global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blo
     // last pass land in `sorted`
     const int passes = (bits_of(mx) + 7) / 8;
     int *src = (passes & 1) ? tmp : sorted, *dst = (passes & 1) ? sorted : tmp;
-    for (int i = threadIdx.x; i < C; i += 1024) src[i] = i;
+    // (stable passes keep the starting order among equal counts: first_row goes in first)
+    for (int i = threadIdx.x; i < C; i += 1024) src[i] = i == 0 ? first_row : (i <= first_row ? i - 1 : i);
     __threadfence_block();
     __syncthreads();
     for (int pass = 0; pass < passes; ++pass) {
@@ -178,9 +197,16 @@ int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
-int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t *tmp, int32_t *sorted, hipStream_t st)
+int kvs_launch_move_blocks(const int32_t *moves, int32_t K, int32_t n, int32_t *blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL(sort_by_blocks_kernel, dim3(1), dim3(1024), 0, st, blocks, C, tmp, sorted);
+    hipLaunchKernelGGL(move_blocks_kernel, dim3((unsigned)(K / 256 + 1)), dim3(256), 0, st, moves, K, n, blocks);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t first_row, int32_t *tmp, int32_t *sorted,
+                              hipStream_t st)
+{
+    hipLaunchKernelGGL(sort_by_blocks_kernel, dim3(1), dim3(1024), 0, st, blocks, C, first_row, tmp, sorted);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 

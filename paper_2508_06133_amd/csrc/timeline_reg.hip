@@ -510,7 +510,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             state_in = p.snapshots + (size_t)(rb - 1) * (size_t)p.snap_stride;
         }
     }
-    const bool takes_snapshots = RES && p.snap_blocks > 0 && cand == 0;
+    const bool takes_snapshots = RES && p.snap_blocks > 0 && cand == p.snap_cand;
     const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
     int b64 = 0;             // round of lane 0 of register 0: 64 * floor((t + 1) / 64)
     int t = 0;               // start round of the previous request in the order
@@ -608,7 +608,9 @@ template <int NR, int WPB>
 int launch_reg(const SimParams &p, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((p.C + WPB - 1) / WPB);
-    if (p.src.orders && p.cand_list && p.snap_flags)
+    if (p.src.moves && p.cand_list && p.snap_flags)  // moves against a base order, resumed from the base order's states
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true, true, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+    else if (p.src.orders && p.cand_list && p.snap_flags)
         hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     else if (p.src.orders && p.cand_list)
         hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);

@@ -174,6 +174,51 @@ def test_best_neighbor_shared_prefix(ctx, cfg, n, lo, width, K):
     assert ctx.device_status() == 0
 
 
+@pytest.mark.parametrize("cfg,n,K,min_rows", [(3, 2000, 4200, -1), (3, 700, 600, 256), (2, 330, 2300, 2048),
+                                              (5, 1100, 500, 128)])
+def test_best_neighbor_moves_anywhere_resume_from_the_base_order(ctx, cfg, n, K, min_rows):
+    # swaps and insertions all over the order (no prefix common to all): each move's timeline starts
+    # from the state the base order's timeline saved before the first position the move touches.
+    # min_rows = -1: the library's own choice takes that path at this size; else forced for small cases.
+    # Identity moves, moves at position 0 and at the last position, and malformed moves among them;
+    # the same under the three hand-over settings and with resuming off
+    from paper_2508_06133_amd import kvsched
+
+    inst = workloads.instance(cfg) if n == 2000 else workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    moves = workloads.window_moves(np.random.default_rng(cfg + 40), K, 0, n)
+    moves[5] = (0, 0, n - 1)
+    moves[6] = (1, n - 1, 0)
+    moves[7] = (1, 0, n - 1)
+    moves[8] = (0, n - 1, n - 2)
+    moves[9] = (1, 77, 77)
+    print(f"best_neighbor over the whole order: config {cfg} n={n} K={K}", flush=True)
+    tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=False)
+    try:
+        ctx.set_resume_min_rows(min_rows)
+        for polls in (4096, 1, 0):
+            ctx.set_resume_one_launch(polls)
+            tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+            assert (tel_g == tel_o).all() and res_g == res_o, polls
+            assert ctx.device_status() == 0
+        ctx.set_resume_one_launch(4096)
+        bad = moves.copy()
+        bad[11] = (2, 1, 2)
+        bad[12] = (0, -1, 3)
+        bad[13] = (1, 5, n)
+        tel_b, res_b = _gpu_best(ctx, inst.s, inst.o, inst.M, base, bad)
+        assert ctx.device_status() == kvsched.DEV_BAD_MOVE
+        keep = np.ones(K, dtype=bool)
+        keep[11:14] = False
+        assert list(tel_b[11:14]) == [-1, -1, -1] and (tel_b[keep] == tel_o[keep]).all()
+        ctx.set_resume_min_rows(0)
+        tel_p, res_p = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+        assert (tel_p == tel_o).all() and res_p == res_o
+    finally:
+        ctx.set_resume_min_rows(-1)
+        ctx.set_resume_one_launch(4096)
+
+
 def test_best_neighbor_only_identity_moves(ctx):
     inst = workloads.instance(2, n=130)
     base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
