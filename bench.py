@@ -34,12 +34,12 @@ OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for on
 CFG = 3
 
 # HBM traffic of the dominant kernel per launch (one per step) on this workload, from rocprofv3
-# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 46957 KiB x 1.9997 (what a
-# plain 256 MiB copy reads per KiB moved) + WRITE_SIZE 89420 KiB x 1.0.  Valid only for the kernel
+# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 46945 KiB x 1.9997 (what a
+# plain 256 MiB copy reads per KiB moved) + WRITE_SIZE 89424 KiB x 1.0.  Valid only for the kernel
 # sources it was measured on; reported as null once they change.
-TRAFFIC_BYTES = int((46957 * 1.9997 + 89420 * 1.0) * 1024)
+TRAFFIC_BYTES = int((46945 * 1.9997 + 89424 * 1.0) * 1024)
 TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
-TRAFFIC_SOURCES_SHA256 = "2c21d0c7c77d27be"
+TRAFFIC_SOURCES_SHA256 = "9b56300fbfa94759"
 
 
 def measured_traffic():
