@@ -62,11 +62,24 @@ __global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *order
     const int cap = (n - 1) >> 6;
     int nb = 0;
     if (c > 0) {
+        // four blocks a turn: the loads of a turn are in flight together, the turns are a dependent chain
+        for (; nb + 4 <= cap; nb += 4) {
+            const int k = 64 * nb + lane;  // < n: blocks below cap are complete
+            const bool d0 = a[k] != b[k], d1 = a[k + 64] != b[k + 64], d2 = a[k + 128] != b[k + 128],
+                       d3 = a[k + 192] != b[k + 192];
+            const bool e0 = __builtin_amdgcn_ballot_w64(d0) != 0, e1 = __builtin_amdgcn_ballot_w64(d1) != 0,
+                       e2 = __builtin_amdgcn_ballot_w64(d2) != 0, e3 = __builtin_amdgcn_ballot_w64(d3) != 0;
+            if (e0 | e1 | e2 | e3) {
+                nb += e0 ? 0 : e1 ? 1 : e2 ? 2 : 3;
+                goto done;
+            }
+        }
         for (; nb < cap; ++nb) {
-            const int k = 64 * nb + lane;  // < n: block nb < cap is complete
+            const int k = 64 * nb + lane;
             if (__builtin_amdgcn_ballot_w64(a[k] != b[k]) != 0) break;
         }
     }
+done:
     if (lane == 0) blocks[c] = nb;
 }
 

@@ -189,8 +189,8 @@ __global__ __launch_bounds__(256) void check_moves_kernel(const int32_t *moves, 
 __global__ __launch_bounds__(1024) void argmin_kernel(const int64_t *tel, int32_t K, int64_t *result_out,
                                                       int32_t with_base)
 {
-    __shared__ long long sh_tel[1024];
-    __shared__ int sh_idx[1024];
+    __shared__ long long sh_tel[16];
+    __shared__ int sh_idx[16];
     long long bt = -1;
     int bi = -1;
     for (int m = threadIdx.x; m < K; m += blockDim.x) {
@@ -200,22 +200,37 @@ __global__ __launch_bounds__(1024) void argmin_kernel(const int64_t *tel, int32_
             bi = m;
         }
     }
-    sh_tel[threadIdx.x] = bt;
-    sh_idx[threadIdx.x] = bi;
-    __syncthreads();
-    for (int stride = 512; stride > 0; stride >>= 1) {
-        if ((int)threadIdx.x < stride) {
-            const long long ot = sh_tel[threadIdx.x + stride];
-            const int oi = sh_idx[threadIdx.x + stride];
-            const long long mt = sh_tel[threadIdx.x];
-            const int mi = sh_idx[threadIdx.x];
-            if (oi >= 0 && (mi < 0 || ot < mt || (ot == mt && oi < mi))) {
-                sh_tel[threadIdx.x] = ot;
-                sh_idx[threadIdx.x] = oi;
-            }
+    // (least latency, then lowest index) is a total order: any reduction tree gives the same winner
+    auto take = [&](long long ot, int oi) {
+        if (oi >= 0 && (bi < 0 || ot < bt || (ot == bt && oi < bi))) {
+            bt = ot;
+            bi = oi;
         }
-        __syncthreads();
+    };
+    for (int d = 32; d > 0; d >>= 1) {
+        const long long ot = __shfl_xor(bt, d);
+        const int oi = __shfl_xor(bi, d);
+        take(ot, oi);
     }
+    if ((threadIdx.x & 63) == 0) {
+        sh_tel[threadIdx.x >> 6] = bt;
+        sh_idx[threadIdx.x >> 6] = bi;
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        bt = threadIdx.x < 16 ? sh_tel[threadIdx.x] : -1;
+        bi = threadIdx.x < 16 ? sh_idx[threadIdx.x] : -1;
+        for (int d = 8; d > 0; d >>= 1) {
+            const long long ot = __shfl_xor(bt, d);
+            const int oi = __shfl_xor(bi, d);
+            take(ot, oi);
+        }
+        if (threadIdx.x == 0) {
+            sh_tel[0] = bt;
+            sh_idx[0] = bi;
+        }
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
         const bool base_ok = !with_base || tel[K] >= 0;  // a faulty base order makes every neighbour faulty
         result_out[0] = base_ok ? sh_idx[0] : -1;
