@@ -345,7 +345,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         p.state_in = state;
     }
     // No declared prefix: rows that agree with row 0 on their leading 64-position blocks resume
-    // from snapshots of row 0's timeline (taken by row 0's own wave in the first launch).
+    // from snapshots of row 0's timeline, taken by row 0's own wave.
     ctx->resume_rows = 0;
     const int32_t *resumed_blocks = nullptr, *resumed_row0 = nullptr;
     if (cp == 0 && resume_pays(ctx, C, n, o_bound)) {
