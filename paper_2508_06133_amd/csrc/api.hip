@@ -120,6 +120,9 @@ constexpr int32_t kResumeAutoMinBlocks = 6;
 constexpr int64_t kResumeAutoMinPositions = 8000000;
 constexpr int32_t kResumeFirstLaunchMax = 4096;
 constexpr int32_t kResumeWaitPollsDefault = 4096;  // about 14 ms
+// Streams of kvsched_online run one per wavefront, at most some 1500 to 3000 at once on 256 compute
+// units (LDS-limited): below that every stream starts at once and their order is of no consequence.
+constexpr int32_t kOnlineOrderMinStreams = 1024;
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -744,8 +747,15 @@ int kvsched_online(kvsched_ctx *ctx, int32_t B, const int32_t *streams, int32_t 
     if (o_bound > KVSCHED_ONLINE_MAX_O) return KVSCHED_ERANGE;
     int32_t H = 64;  // ring of the running requests' future memory: a slot per round of the longest decode
     while (H < o_bound) H <<= 1;
+    // More streams than run at once: those with most work go first (the order needs 2 B ints of scratch).
+    int32_t *order_scratch = nullptr;
+    if (B > kOnlineOrderMinStreams) {
+        rc = ensure_scratch(ctx, 2 * sizeof(int32_t) * (size_t)B);
+        if (rc != KVSCHED_OK) return rc;
+        order_scratch = (int32_t *)ctx->d_scratch;
+    }
     return kvs_launch_online(B, streams, N, a, s, o, (int32_t)M, backlog_cap, H, completion_out, out_len, stats_out,
-                             ctx->d_words, st);
+                             order_scratch, ctx->d_words, st);
 }
 
 int kvsched_simulate_resume_positions(kvsched_ctx *ctx, int32_t C, int32_t *resume_pos_out, void *stream)

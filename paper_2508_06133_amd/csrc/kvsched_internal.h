@@ -152,7 +152,7 @@ int kvs_launch_horizon_advance(const int32_t *order, const int32_t *completion, 
 // online.hip
 int kvs_launch_online(int32_t B, const int32_t *streams, int32_t N, const int32_t *a, const int32_t *s,
                       const int32_t *o, int32_t M, int32_t backlog_cap, int32_t ring_slots, int32_t *completion_out,
-                      int32_t out_len, int64_t *stats_out, int32_t *d_words, hipStream_t st);
+                      int32_t out_len, int64_t *stats_out, int32_t *order_scratch, int32_t *d_words, hipStream_t st);
 
 // predicted.hip
 constexpr size_t KVS_PREDICTED_MAX_LDS = 160 * 1024;  // LDS of one workgroup on gfx950

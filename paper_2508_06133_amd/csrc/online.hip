@@ -30,6 +30,7 @@
 //     = longest prefix by a saturating wave scan; an exchange step = exclusive prefix minimum of
 //     o over non-members, one binary search per member of the first rows, two ballots).
 #include "kvsched_internal.h"
+#include "phase1_util.h"
 
 #include <limits.h>
 
@@ -401,7 +402,40 @@ struct OnlineParams {
     int32_t *completion_out;
     int64_t *stats_out;  // [B][4]
     int32_t *d_words;
+    const int32_t *by_cost;  // [B] stream numbers in ascending order of estimated work, or NULL
 };
+
+// A batch takes as long as its longest stream, which should therefore not start last: the streams are
+// taken in descending order of a rough measure of their work, requests x 8 for Sorted-F-Online (every
+// refresh plans a window by Local Swap Search), requests x 1 for the planners that only sort.
+// One workgroup: stable 8-bit radix passes on that measure.
+__global__ __launch_bounds__(1024) void online_order_kernel(const int32_t *streams, int32_t B, int32_t *tmp, int32_t *sorted)
+{
+    __shared__ RadixLds<1024> L;
+    __shared__ int sh_max[16];
+    auto cost = [streams](int b) {
+        const int count = streams[8 * (size_t)b + 1], planner = streams[8 * (size_t)b + 2];
+        const int c = min(max(count, 0), 1 << 27);
+        return planner == KVSCHED_PLANNER_SORTED_F ? 8 * c : c;
+    };
+    int mx = 0;
+    for (int i = threadIdx.x; i < B; i += 1024) mx = max(mx, cost(i));
+    for (int d = 32; d > 0; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
+    if ((threadIdx.x & 63) == 0) sh_max[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    for (int w = 0; w < 16; ++w) mx = max(mx, sh_max[w]);
+    const int passes = (bits_of(mx) + 7) / 8;
+    int *src = (passes & 1) ? tmp : sorted, *dst = (passes & 1) ? sorted : tmp;  // the last pass lands in `sorted`
+    for (int i = threadIdx.x; i < B; i += 1024) src[i] = i;
+    __threadfence_block();
+    __syncthreads();
+    for (int pass = 0; pass < passes; ++pass) {
+        radix_pass<1024>(src, dst, B, 8 * pass, cost, L);
+        __threadfence_block();
+        __syncthreads();
+        int *sw = src; src = dst; dst = sw;
+    }
+}
 
 template <int QCAP, int HCAP>
 __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
@@ -410,7 +444,7 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
     __shared__ Lds L;
     constexpr int QM = QCAP - 1;
     const int lane = lane_id();
-    const int b = blockIdx.x;
+    const int b = p.by_cost ? uni(p.by_cost[p.B - 1 - (int)blockIdx.x]) : (int)blockIdx.x;  // most work first
     const int32_t *d = p.streams + 8 * (size_t)b;
     const int begin = uni(d[0]), count = uni(d[1]), planner = uni(d[2]), period = uni(d[3]), window = uni(d[4]);
     const int rnum = uni(d[5]), rden = uni(d[6]), outb = uni(d[7]);
@@ -602,10 +636,16 @@ int launch_online(const OnlineParams &p, hipStream_t st)
 // 136 KB; the smallest that holds the caller's backlog bound and the longest decode is used.
 int kvs_launch_online(int32_t B, const int32_t *streams, int32_t N, const int32_t *a, const int32_t *s,
                       const int32_t *o, int32_t M, int32_t backlog_cap, int32_t ring_slots, int32_t *completion_out,
-                      int32_t out_len, int64_t *stats_out, int32_t *d_words, hipStream_t st)
+                      int32_t out_len, int64_t *stats_out, int32_t *order_scratch, int32_t *d_words, hipStream_t st)
 {
     if (ring_slots < 2 || (ring_slots & (ring_slots - 1)) || backlog_cap < 1) return KVSCHED_ERANGE;
     OnlineParams p;
+    p.by_cost = nullptr;
+    if (order_scratch) {  // [2 B]: the order, and the other buffer of the sort
+        hipLaunchKernelGGL(online_order_kernel, dim3(1), dim3(1024), 0, st, streams, B, order_scratch + B, order_scratch);
+        if (hipGetLastError() != hipSuccess) return KVSCHED_EHIP;
+        p.by_cost = order_scratch;
+    }
     p.B = B;
     p.streams = streams;
     p.N = N;

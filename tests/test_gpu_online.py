@@ -134,6 +134,37 @@ def test_random_small_streams(ctx):
         b.check(ctx, M, f"random small streams, M={M}", cap=(64, 600, 4096)[M_mode])
 
 
+def test_more_streams_than_run_at_once_are_taken_by_work(ctx):
+    # beyond 1024 streams the library starts those with most work first (an order of its own over the
+    # batch): results and their places in the outputs must not depend on it.  Streams of very
+    # different sizes, and two with a malformed descriptor among them
+    from paper_2508_06133_amd import kvsched
+
+    rng = np.random.default_rng(23)
+    b = Batch()
+    M = 300
+    for k in range(1300):
+        n = int(rng.integers(1, 4)) if k % 3 else int(rng.integers(40, 160))
+        s = rng.integers(1, 120, n)
+        o = rng.integers(1, 120, n)
+        a = np.sort(rng.integers(0, 50, n))
+        r = b.add_requests(a, s, o)
+        b.add_stream(r, int(rng.integers(0, 4)), int(rng.integers(1, 12)), int(rng.integers(0, 40)), (1, 2))
+    b.check(ctx, M, "1300 streams", cap=512)
+    bad = (17, 900)
+    for k in bad:
+        b.desc[k][3] = 0  # refresh period 0
+    a, s, o, comp, stats = b.run(ctx, M, "1300 streams, two malformed", cap=512)
+    assert ctx.device_status() == kvsched.DEV_BAD_STREAM
+    for k, (begin, count, planner, period, window, refresh, out) in enumerate(b.cases):
+        if k in bad:
+            assert (stats[k] == -1).all()
+        elif k % 50 == 0 or k in (16, 18, 899, 901):
+            sl = slice(begin, begin + count)
+            _, c_o, st_o = oracle.online(a[sl], s[sl], o[sl], M, planner, period, window, refresh)
+            assert tuple(int(x) for x in stats[k]) == st_o and (comp[out : out + count] == c_o).all(), k
+
+
 def test_bursts_deep_backlog_and_full_window(ctx):
     # everything arrives in a few large bursts: more than 256 arrivals per iteration (merged in
     # chunks), a backlog in the thousands, the largest window, batches of hundreds of requests
