@@ -315,7 +315,7 @@ def main() -> int:
                     help="also run one plain 256 MiB device copy, the yardstick for FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build evaluates schedules on ONE GPU; --gpus must be 1 "
+        print("bench.py: libkvsched evaluates schedules on ONE GPU; --gpus must be 1 "
               "(candidates are independent and would shard across GPUs; that is not built)", file=sys.stderr)
         return 2
 
