@@ -76,6 +76,47 @@ __device__ void radix_pass(const int *in, int *out, int n, int shift, KeyFn key,
     }
 }
 
+// The same pass done by ONE wavefront (no barriers: LDS operations of a wavefront take effect in
+// program order): 64 ids a turn, in order, each lane ranked among the lanes of its turn that hold the
+// same digit; hist[] holds 256 running output positions.
+template <class KeyFn>
+__device__ void radix_pass_wave(const int *in, int *out, int n, int shift, KeyFn key, int *hist)
+{
+    const int lane = threadIdx.x & 63;
+    for (int i = lane; i < 256; i += 64) hist[i] = 0;
+    for (int i = lane; i < n; i += 64) atomicAdd(&hist[(key(in[i]) >> shift) & 255], 1);
+    {
+        const int c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+        int incl = c0 + c1 + c2 + c3;  // each lane owns four digits
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        const int base = incl - (c0 + c1 + c2 + c3);
+        hist[4 * lane] = base;
+        hist[4 * lane + 1] = base + c0;
+        hist[4 * lane + 2] = base + c0 + c1;
+        hist[4 * lane + 3] = base + c0 + c1 + c2;
+    }
+    for (int i0 = 0; i0 < n; i0 += 64) {
+        const int i = i0 + lane;
+        const bool valid = i < n;
+        const int id = valid ? in[i] : 0;
+        const int d = valid ? ((key(id) >> shift) & 255) : 256;
+        unsigned long long peers = ~0ull;
+#pragma unroll
+        for (int b = 0; b < 9; ++b) {
+            const unsigned long long bal = __builtin_amdgcn_ballot_w64((d >> b) & 1);
+            peers &= ((d >> b) & 1) ? bal : ~bal;
+        }
+        const int rank = __popcll(peers & lanemask_lt());
+        const int cnt = __popcll(peers);
+        const int base = valid ? hist[d] : 0;
+        if (valid) out[base + rank] = id;
+        if (valid && rank == cnt - 1) hist[d] = base + cnt;  // one lane per digit moves its position on
+    }
+}
+
 __device__ __forceinline__ int bits_of(long long v)
 {
     return v <= 0 ? 1 : 64 - __clzll(v);

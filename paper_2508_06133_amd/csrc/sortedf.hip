@@ -304,6 +304,83 @@ __global__ __launch_bounds__(TPB) void sortedF_kernel(int32_t n, const int32_t *
     __threadfence_block();
     __syncthreads();
 
+    // ---- 4 and 5 by one wavefront when everything sits in LDS and feasibility is the sum of peaks:
+    // the steps that follow are short and dependent; sixteen wavefronts meeting at barriers after
+    // each of them take 2.5 us a batch, one wavefront on its own 2 us (and the final sort 8 us instead of 4).
+    if constexpr (IN_LDS && !PROFILE) {
+        if (wave != 0) return;
+        const bool small1 = n < 65536 && cumG[n] < (1ll << 32);
+        int a1 = 0, nb1 = 0;
+        while (a1 < n) {
+            const long long W0 = cumW[a1], G0 = cumG[a1];
+            // feasible extent K: 64 probes a turn narrow [lo, lo + span] (fit(lo) holds; fit is monotone)
+            int lo = 0, span = n - a1;
+            while (span > 0) {
+                const int step = (span + 63) >> 6;
+                const int k = lo + (lane + 1) * step;
+                const bool ok = k <= lo + span && cumW[a1 + k] - W0 <= (long long)M;
+                const int c = __popcll(__builtin_amdgcn_ballot_w64(ok));  // a prefix of the probes fits
+                const int hi = lo + span;
+                lo += c * step;
+                span = min(hi, lo + step - 1) - lo;
+            }
+            const int K = lo;
+            if (K < 1) {  // cannot happen for well-formed input; never spin
+                if (lane == 0) atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_LENGTH);
+                break;
+            }
+            int bk = 0;
+            if (small1) {
+                unsigned bs = 0;
+                for (int k = lane + 1; k <= K; k += 64) {
+                    const unsigned Sk = (unsigned)(cumG[a1 + k] - G0);
+                    if (better_small(Sk, k, bs, bk, tie_rule)) { bs = Sk; bk = k; }
+                }
+                row_best_small(bs, bk, tie_rule);
+                for (int d = 16; d <= 32; d <<= 1) {
+                    const unsigned oS = (unsigned)__shfl_xor((int)bs, d);
+                    const int ok = __shfl_xor(bk, d);
+                    if (better_small(oS, ok, bs, bk, tie_rule)) { bs = oS; bk = ok; }
+                }
+            } else {
+                long long bS = 0;
+                for (int k = lane + 1; k <= K; k += 64) {
+                    const long long Sk = cumG[a1 + k] - G0;
+                    if (better(Sk, k, bS, bk, tie_rule)) { bS = Sk; bk = k; }
+                }
+                for (int d = 1; d < 64; d <<= 1) {  // (exchanges both ways: every lane ends with the winner)
+                    const long long oS = __shfl_xor(bS, d);
+                    const int ok = __shfl_xor(bk, d);
+                    if (better(oS, ok, bS, bk, tie_rule)) { bS = oS; bk = ok; }
+                }
+            }
+            const int kstar = __builtin_amdgcn_readfirstlane(bk);
+            if (lane == 0) ends[nb1] = a1 + kstar;
+            for (int i = lane; i < kstar; i += 64) batch_of[sorted[a1 + i]] = nb1;
+            a1 += kstar;
+            ++nb1;
+        }
+        if (lane == 0) *num_batches_out = nb1;
+        for (int b = lane; b < nb1; b += 64) {
+            const int lo = b == 0 ? 0 : ends[b - 1], hi = ends[b];
+            batch_end_out[b] = hi;
+            const double k = (double)(hi - lo);
+            F_out[b] = (double)(cumG[hi] - cumG[lo]) / ((double)gb * k * k);
+        }
+        // the (o, id)-sorted ids by batch number (stable): `sorted` and the other sort buffer are free now
+        const int *src1 = by_o;
+        int *dst1 = alt, *oth1 = cur;
+        auto key_b1 = [batch_of](int id) { return batch_of[id]; };
+        for (int shift = 0; shift < bits_of(nb1 - 1); shift += 8) {
+            radix_pass_wave(src1, dst1, n, shift, key_b1, L.radix.hist);
+            src1 = dst1;
+            dst1 = oth1;
+            oth1 = (int *)src1;
+        }
+        for (int i = lane; i < n; i += 64) order_out[i] = src1[i];
+        return;
+    }
+
     // ---- 4: batches
     const bool small = n < 65536 && cumG[n] < (1ll << 32);
     int a = 0, nb = 0;
