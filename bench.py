@@ -42,14 +42,30 @@ TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
 TRAFFIC_SOURCES_SHA256 = "9b56300fbfa94759"
 
 
-def measured_traffic():
+# Issue slots the same kernel really used on this workload (profiles/timeline_kernel_config3_counters.md):
+# SQ_INSTS_VALU 1.185e9 x 4 cycles / (1024 SIMDs x 4.95e6 cycles) and (SQ_INSTS_SALU 8.763e8 +
+# SQ_INSTS_BRANCH 2.248e8) / (256 scalar units x 4.95e6 cycles), cycles from GRBM_GUI_ACTIVE / 8 XCDs.
+# The accounting above credits 6 lane-ops per visit where the kernel issues 4.9, so the physical
+# utilisation is this, not roofline.frac.
+ISSUE_SLOTS = {"valu": 0.934, "scalar_and_branch": 0.868}
+
+
+def _kernel_sources_unchanged() -> bool:
     import hashlib
 
     h = hashlib.sha256()
     for f in TRAFFIC_SOURCES:
         with open(os.path.join(ROOT, "paper_2508_06133_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
-    return TRAFFIC_BYTES if h.hexdigest()[:16] == TRAFFIC_SOURCES_SHA256 else None
+    return h.hexdigest()[:16] == TRAFFIC_SOURCES_SHA256
+
+
+def measured_traffic():
+    return TRAFFIC_BYTES if _kernel_sources_unchanged() else None
+
+
+def measured_issue_slots():
+    return ISSUE_SLOTS if _kernel_sources_unchanged() else None
 
 
 def bench_online(args, ctx, dev) -> int:
@@ -449,6 +465,7 @@ def main() -> int:
             "unit": "Tlane-op/s (int32)",
             "frac": achieved / PEAK_INT32_LANE_OPS,
             "traffic": measured_traffic(),
+            "issue_slots_measured": measured_issue_slots(),
             "visits_per_step": visits,  # from each row's resume point on
             "ops_per_visit": OPS_PER_VISIT,
             "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / (k_ms * 1e-3) / 1e9,
