@@ -24,7 +24,9 @@
  *     a malformed move) set bits in a device status word, readable with
  *     kvsched_device_status(); the affected candidates get tel = -1.
  *   - int32 for lengths, ids, orders, rounds; int64 for M and total latencies.
- *   - A context is bound to one device and may be used by one host thread at a time.
+ *   - A context is bound to one device and may be used by one host thread at a time; its calls
+ *     share the context's scratch memory, so work of two calls on one context must not overlap on
+ *     the GPU (same stream, or ordered by events).  Independent work takes a context each.
  */
 #ifndef KVSCHED_H
 #define KVSCHED_H
