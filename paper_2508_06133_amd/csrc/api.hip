@@ -367,14 +367,12 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         int32_t *row0 = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes + flag_bytes);
         rc = kvs_launch_shared_blocks(orders, C, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
-        rc = kvs_launch_sort_by_blocks(blocks, C, 0, tmp, sorted, st);
+        rc = kvs_launch_sort_by_blocks(blocks, C, 0, tmp, sorted, flags, nblk, st);  // (clears the flags too)
         if (rc != KVSCHED_OK) return rc;
         int32_t first = 0;
         if (ctx->resume_wait_polls > 0) {
             // All rows in one launch, those that share least with row 0 first: row 0's wave flags each
             // snapshot as it is written, the others wait for theirs (most find it there already).
-            hipLaunchKernelGGL(kvs_fill_zero_i32, dim3((unsigned)((nblk + 255) / 256)), dim3(256), 0, st, flags, nblk);
-            if (hipGetLastError() != hipSuccess) return KVSCHED_EHIP;
             if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
             SimParams a = p;
             a.cand_list = sorted;
@@ -655,10 +653,8 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
         int32_t *snaps = (int32_t *)(plan + 3 * list_bytes + align256(sizeof(int32_t) * (size_t)nblk));
         rc = kvs_launch_move_blocks(moves, K, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
-        rc = kvs_launch_sort_by_blocks(blocks, C, K, tmp, sorted, st);
+        rc = kvs_launch_sort_by_blocks(blocks, C, K, tmp, sorted, flags, nblk, st);  // (clears the flags too)
         if (rc != KVSCHED_OK) return rc;
-        hipLaunchKernelGGL(kvs_fill_zero_i32, dim3((unsigned)((nblk + 255) / 256)), dim3(256), 0, st, flags, nblk);
-        if (hipGetLastError() != hipSuccess) return KVSCHED_EHIP;
         p.cand_list = sorted;
         p.resume_block = blocks;
         p.snapshots = snaps;

@@ -170,8 +170,9 @@ int kvs_launch_broadcast_prefix(const int32_t *prefix, int32_t cp, int32_t C, in
                                 hipStream_t st);
 // rows resumed from snapshots of row 0 (see SimParams)
 int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, hipStream_t st);
+// flags / nflags: words to clear on the way (the snapshot flags of the launch that follows), or NULL
 int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t first_row, int32_t *tmp, int32_t *sorted,
-                              hipStream_t st);
+                              int32_t *flags, int32_t nflags, hipStream_t st);
 int kvs_launch_move_blocks(const int32_t *moves, int32_t K, int32_t n, int32_t *blocks, hipStream_t st);
 int kvs_launch_copy_row0_prefix(const int32_t *orders, int32_t C, int32_t n, const int32_t *sorted, int32_t first,
                                 const int32_t *blocks, int32_t by_position, int32_t *completion, hipStream_t st);

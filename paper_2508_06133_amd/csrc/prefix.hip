@@ -107,9 +107,12 @@ __global__ __launch_bounds__(256) void move_blocks_kernel(const int32_t *moves, 
 // rows are dispatched first).  Beyond that, stable 8-bit radix passes.
 constexpr int KVS_COUNT_SORT_KEYS = 2048;
 
+// Also clears the `nflags` snapshot flags of the launch that follows (saves a launch of its own).
 __global__ __launch_bounds__(1024) void sort_by_blocks_kernel(const int32_t *blocks, int32_t C, int32_t first_row,
-                                                              int32_t *tmp, int32_t *sorted)
+                                                              int32_t *tmp, int32_t *sorted, int32_t *flags,
+                                                              int32_t nflags)
 {
+    for (int i = threadIdx.x; i < nflags; i += 1024) flags[i] = 0;
     __shared__ RadixLds<1024> L;
     __shared__ int sh_max[16];
     __shared__ int cnt[KVS_COUNT_SORT_KEYS];
@@ -217,9 +220,10 @@ int kvs_launch_move_blocks(const int32_t *moves, int32_t K, int32_t n, int32_t *
 }
 
 int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t first_row, int32_t *tmp, int32_t *sorted,
-                              hipStream_t st)
+                              int32_t *flags, int32_t nflags, hipStream_t st)
 {
-    hipLaunchKernelGGL(sort_by_blocks_kernel, dim3(1), dim3(1024), 0, st, blocks, C, first_row, tmp, sorted);
+    hipLaunchKernelGGL(sort_by_blocks_kernel, dim3(1), dim3(1024), 0, st, blocks, C, first_row, tmp, sorted, flags,
+                       flags ? nflags : 0);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
