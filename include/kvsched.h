@@ -145,11 +145,12 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
 int kvsched_set_resume_min_rows(kvsched_ctx *ctx, int32_t rows);
 
 /* How the resumed rows get row 0's saved states.  wait_polls > 0 (default 4096): all rows run in
- * one launch, row 0's wavefront flags each state once the whole device can read it, a row polls
- * for the state it needs about every 3 microseconds, at most wait_polls times, and otherwise starts
- * from the latest state that is there (or from its first position).  wait_polls == 0: two launches,
- * the quarter of the rows that shares least with row 0 (at most 4096) beside row 0 in the first, the
- * others in the second.  Results are the same in every case.  EINVAL: wait_polls < 0. */
+ * one launch, row 0's wavefront reports each state once the whole device can read it, a row polls
+ * for the state it needs about every 3 microseconds for as long as row 0 keeps reporting progress
+ * (it gives up after wait_polls polls without any) and otherwise starts from the latest state that
+ * is there (or from its first position).  wait_polls == 0: two launches, the quarter of the rows that
+ * shares least with row 0 (at most 4096) beside row 0 in the first, the others in the second.  Results
+ * are the same in every case.  EINVAL: wait_polls < 0. */
 int kvsched_set_resume_one_launch(kvsched_ctx *ctx, int32_t wait_polls);
 
 /*

@@ -356,7 +356,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
         const size_t snap_bytes = align256(sizeof(int32_t) * (size_t)nblk * (size_t)stride);
-        const size_t flag_bytes = align256(sizeof(int32_t) * (size_t)nblk);
+        const size_t flag_bytes = align256(sizeof(int32_t) * KVS_PROGRESS_WORDS);  // the progress word of row 0's wave
         rc = ensure_scratch(ctx, 3 * list_bytes + snap_bytes + flag_bytes + align256(sizeof(int32_t) * (size_t)n));
         if (rc != KVSCHED_OK) return rc;
         int32_t *blocks = (int32_t *)ctx->d_scratch;
@@ -367,11 +367,11 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         int32_t *row0 = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes + flag_bytes);
         rc = kvs_launch_shared_blocks(orders, C, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
-        rc = kvs_launch_sort_by_blocks(blocks, C, 0, tmp, sorted, flags, nblk, st);  // (clears the flags too)
+        rc = kvs_launch_sort_by_blocks(blocks, C, 0, tmp, sorted, flags, KVS_PROGRESS_WORDS, st);  // (clears the progress word too)
         if (rc != KVSCHED_OK) return rc;
         int32_t first = 0;
         if (ctx->resume_wait_polls > 0) {
-            // All rows in one launch, those that share least with row 0 first: row 0's wave flags each
+            // All rows in one launch, those that share least with row 0 first: row 0's wave reports each
             // snapshot as it is written, the others wait for theirs (most find it there already).
             if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
             SimParams a = p;
@@ -592,7 +592,7 @@ static size_t neighbor_scratch_bytes(int32_t K, int32_t n)
 {
     const size_t nblk = (size_t)((n - 1) / WAVE_POSITIONS);
     return align256(sizeof(int64_t) * ((size_t)K + 1)) + state_bytes() +
-           3 * align256(sizeof(int32_t) * ((size_t)K + 1)) + align256(sizeof(int32_t) * nblk) +
+           3 * align256(sizeof(int32_t) * ((size_t)K + 1)) + align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) +
            align256(sizeof(int32_t) * nblk * KVS_STATE_MAX_WORDS);
 }
 
@@ -650,10 +650,10 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
         int32_t *sorted = (int32_t *)(plan + list_bytes);
         int32_t *tmp = (int32_t *)(plan + 2 * list_bytes);
         int32_t *flags = (int32_t *)(plan + 3 * list_bytes);
-        int32_t *snaps = (int32_t *)(plan + 3 * list_bytes + align256(sizeof(int32_t) * (size_t)nblk));
+        int32_t *snaps = (int32_t *)(plan + 3 * list_bytes + align256(sizeof(int32_t) * KVS_PROGRESS_WORDS));
         rc = kvs_launch_move_blocks(moves, K, n, blocks, st);
         if (rc != KVSCHED_OK) return rc;
-        rc = kvs_launch_sort_by_blocks(blocks, C, K, tmp, sorted, flags, nblk, st);  // (clears the flags too)
+        rc = kvs_launch_sort_by_blocks(blocks, C, K, tmp, sorted, flags, KVS_PROGRESS_WORDS, st);  // (clears the progress word too)
         if (rc != KVSCHED_OK) return rc;
         p.cand_list = sorted;
         p.resume_block = blocks;

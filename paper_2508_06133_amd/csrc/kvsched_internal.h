@@ -70,11 +70,11 @@ struct SimParams {
     // candidate snap_cand (row 0) writes snapshots 1..snap_blocks (word 1 of a snapshot, the round t, is set to -1 by
     // the host beforehand: a snapshot that is never taken poisons whoever resumes from it); a
     // candidate c with resume_block[c] = b > 0 starts from snapshot b at position 64 b.
-    // With snap_flags (snap_blocks words, zero at launch) both happen in ONE launch: the wave of
-    // candidate 0 sets snap_flags[j - 1] once snapshot j can be read by the whole device (or marks
-    // it as not coming), a candidate with b > 0 waits for snap_flags[b - 1], a bounded time, then
-    // takes the latest snapshot that is there and writes the block it really started from back to
-    // resume_block[c].
+    // With snap_flags (the progress word in KVS_PROGRESS_WORDS words, zero at launch) both happen in ONE launch: the wave of
+    // candidate snap_cand stores there the number of snapshots it has published so far (or ~that number
+    // when it stops early), a candidate with b > 0 waits until the word reaches b, as long as the word
+    // keeps moving, then takes the latest snapshot that is there and writes the block it really started
+    // from back to resume_block[c].
     const int32_t *cand_list = nullptr;
     int32_t *resume_block = nullptr;
     int32_t *snapshots = nullptr;
@@ -85,6 +85,10 @@ struct SimParams {
     int32_t snap_cand = 0;        // the candidate whose wave writes the snapshots (row 0; the base order among moves)
 };
 constexpr int KVS_STATE_HEAD_WORDS = 192;
+// the progress word of the snapshot hand-over: this many copies, this far apart (SimParams::snap_flags)
+constexpr int KVS_PROGRESS_COPIES = 64;
+constexpr int KVS_PROGRESS_STRIDE_WORDS = 16;
+constexpr int KVS_PROGRESS_WORDS = KVS_PROGRESS_COPIES * KVS_PROGRESS_STRIDE_WORDS;
 constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 65 * 64;
 
 // simulate.hip

@@ -373,82 +373,85 @@ __device__ __forceinline__ void state_head_store(int32_t *snap, int b64, int t, 
 // it run on different compute units, in general under different L2 caches, so the hand-over follows
 // the device-scope release / acquire sequences of the hardware's memory model, written out here
 // because the snapshot itself is stored and loaded by assembly the compiler does not see into:
-//   writer: all stores done -> write back the L2 -> done -> store the flag at device scope;
-//   reader: load the flag at device scope -> invalidate stale cache lines -> load the snapshot.
-constexpr int KVS_SNAP_READY = 1;  // (0: not there yet)
-constexpr int KVS_SNAP_NEVER = 2;  // the writer gave up before it got there
-// A reader polls about every 3 us and gives up after SimParams::snap_wait_polls polls (by default
-// some 14 ms: far longer than the writer needs per snapshot unless the timelines themselves take much
-// longer than that); it then starts from the latest snapshot that is there, or from the beginning.
-// Every wait ends.
+//   writer: all stores done -> write back the L2 -> done -> store the progress word at device scope;
+//   reader: load the progress word at device scope -> invalidate stale cache lines -> load the snapshot.
+// The progress word (zero at launch) holds the number j of snapshots published so far (they are taken
+// in order), or ~j once the writer has stopped after j of them (a request that cannot be scheduled).
+// It is kept in KVS_PROGRESS_COPIES copies, 64 bytes apart, written by one store of the writer's 64
+// lanes; a reader polls the copy of its wave number: thousands of readers polling one address slow
+// the writer down measurably.
+// A reader that needs snapshot b polls the word about every 3 us until it is >= b; it gives up when
+// the word says the writer has stopped, or has not moved for SimParams::snap_wait_polls polls (by
+// default some 14 ms), and then starts from the latest snapshot there is, or from the beginning.
+// The writer waits for nobody, so the word stops moving at the latest when the writer's wave ends,
+// and every wait ends.
 
 template <int NR>
-__device__ __forceinline__ void snapshot_flag_set(int32_t *flags, int index, int value)  // device-scope store
+__device__ __forceinline__ void snapshot_progress_set(int32_t *progress, int value, int lane)  // device-scope store
 {
+    static_assert(KVS_PROGRESS_COPIES == 64 && KVS_PROGRESS_STRIDE_WORDS == 16, "one copy per lane, 64 bytes apart");
     int off, v;
 #define KVS_STMT(CLOB, ASC, DESC)                                                       \
-    asm volatile("v_mov_b32 %[off], %[idx]\n"                                           \
+    asm volatile("v_lshlrev_b32 %[off], 6, %[lane]\n"                                   \
                  "v_mov_b32 %[v], %[val]\n"                                             \
                  "global_store_dword %[off], %[v], %[base] sc1\n"                       \
                  : [off] "=&v"(off), [v] "=&v"(v)                                       \
-                 : [base] "s"(flags), [idx] "s"(index * 4), [val] "s"(value)            \
+                 : [base] "s"(progress), [val] "s"(value), [lane] "v"(lane)             \
                  : "memory", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
 }
 
 template <int NR>
-__device__ __forceinline__ void snapshot_publish(int32_t *flags, int index)
+__device__ __forceinline__ void snapshot_publish(int32_t *progress, int count, int lane)
 {
     asm volatile("s_waitcnt vmcnt(0)\n"
                  "buffer_wbl2 sc1\n"
                  "s_waitcnt vmcnt(0)\n" ::: "memory");
-    snapshot_flag_set<NR>(flags, index, KVS_SNAP_READY);
+    snapshot_progress_set<NR>(progress, count, lane);
 }
 
-// The reader's side as one scalar loop: poll flag rb - 1 until it is set (or the polls are used up),
-// then, unless it says READY, step down to the latest snapshot that is READY (0: none); finally the
-// cache invalidation that lets the loads that follow see the snapshot.  rb = 0 (nothing to wait for)
-// passes through.  Written as a single block so that the compiler sees one scalar result, as from
-// a scalar load.
-__device__ __forceinline__ int snapshot_wait(const int32_t *flags, int rb, int polls)
+// The reader's side as one scalar loop; returns the snapshot to start from (0: none).  rb = 0
+// (nothing to wait for) passes through.  Written as a single block so that the compiler sees one
+// scalar result, as from a scalar load.
+__device__ __forceinline__ int snapshot_wait(const int32_t *progress, int rb, int polls, int copy)
 {
-    int f, cnt, off, voff, v;
-    asm volatile("s_max_i32 %[cnt], %[polls], 1\n"
-                 "s_cmp_eq_u32 %[rb], 0\n"
+    int f, cnt, last, voff, v;
+    asm volatile("s_cmp_eq_u32 %[rb], 0\n"
                  "s_cbranch_scc1 4f\n"
+                 "s_max_i32 %[cnt], %[polls], 1\n"
+                 "s_mov_b32 %[last], -1\n"
+                 "s_lshl_b32 %[f], %[copy], 6\n"
+                 "v_mov_b32 %[voff], %[f]\n"
                  "1:\n"
-                 "s_lshl_b32 %[off], %[rb], 2\n"
-                 "s_sub_u32 %[off], %[off], 4\n"
-                 "v_mov_b32 %[voff], %[off]\n"
                  "global_load_dword %[v], %[voff], %[base] sc1\n"
                  "s_waitcnt vmcnt(0)\n"
                  "v_readfirstlane_b32 %[f], %[v]\n"
-                 "s_cmp_lg_u32 %[f], 0\n"
+                 "s_cmp_lt_i32 %[f], 0\n"
+                 "s_cbranch_scc1 3f\n"  // the writer has stopped
+                 "s_cmp_ge_i32 %[f], %[rb]\n"
+                 "s_cbranch_scc1 4f\n"  // it is there
+                 "s_cmp_eq_u32 %[f], %[last]\n"
                  "s_cbranch_scc1 2f\n"
-                 "s_sleep 127\n"
-                 "s_sub_u32 %[cnt], %[cnt], 1\n"
-                 "s_cmp_lg_u32 %[cnt], 0\n"
-                 "s_cbranch_scc1 1b\n"
+                 "s_mov_b32 %[last], %[f]\n"  // the writer has moved: count anew
+                 "s_max_i32 %[cnt], %[polls], 1\n"
+                 "s_branch 5f\n"
                  "2:\n"
-                 "s_cmp_eq_u32 %[f], %c[ready]\n"
-                 "s_cbranch_scc1 4f\n"
+                 "s_sub_u32 %[cnt], %[cnt], 1\n"
+                 "s_cmp_eq_u32 %[cnt], 0\n"
+                 "s_cbranch_scc0 5f\n"
+                 "s_mov_b32 %[rb], %[f]\n"  // waited long enough: what there is (f < rb)
+                 "s_branch 4f\n"
+                 "5:\n"
+                 "s_sleep 127\n"
+                 "s_branch 1b\n"
                  "3:\n"
-                 "s_sub_u32 %[rb], %[rb], 1\n"
-                 "s_cmp_eq_u32 %[rb], 0\n"
-                 "s_cbranch_scc1 4f\n"
-                 "s_lshl_b32 %[off], %[rb], 2\n"
-                 "s_sub_u32 %[off], %[off], 4\n"
-                 "v_mov_b32 %[voff], %[off]\n"
-                 "global_load_dword %[v], %[voff], %[base] sc1\n"
-                 "s_waitcnt vmcnt(0)\n"
-                 "v_readfirstlane_b32 %[f], %[v]\n"
-                 "s_cmp_eq_u32 %[f], %c[ready]\n"
-                 "s_cbranch_scc0 3b\n"
+                 "s_not_b32 %[f], %[f]\n"  // snapshots published before it stopped
+                 "s_min_i32 %[rb], %[rb], %[f]\n"
                  "4:\n"
                  "buffer_inv sc1\n"
-                 : [rb] "+s"(rb), [f] "=&s"(f), [cnt] "=&s"(cnt), [off] "=&s"(off), [voff] "=&v"(voff), [v] "=&v"(v)
-                 : [base] "s"(flags), [polls] "s"(polls), [ready] "n"(KVS_SNAP_READY)
+                 : [rb] "+s"(rb), [f] "=&s"(f), [cnt] "=&s"(cnt), [last] "=&s"(last), [voff] "=&v"(voff), [v] "=&v"(v)
+                 : [base] "s"(progress), [polls] "s"(polls), [copy] "s"(copy)
                  : "scc", "memory");
     return rb;
 }
@@ -503,7 +506,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     if (RES && p.resume_block) {
         const int planned = scalar_read(p.resume_block, cand);
         // ONE: taken in this very launch: wait for it, within bounds
-        const int rb = ONE ? snapshot_wait(p.snap_flags, planned, p.snap_wait_polls) : planned;
+        const int rb = ONE ? snapshot_wait(p.snap_flags, planned, p.snap_wait_polls, wave_no & (KVS_PROGRESS_COPIES - 1)) : planned;
         if (ONE && rb != planned) p.resume_block[cand] = rb;  // (every lane, same value) the accounts show what was really skipped
         if (rb > 0) {
             k_first = 64 * rb;
@@ -543,7 +546,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             int32_t *snap = p.snapshots + (size_t)((k0 >> 6) - 1) * (size_t)p.snap_stride;
             state_head_store<NR>(snap, b64, t, tel_lane, lane);
             prof_store<NR>(snap + KVS_STATE_HEAD_WORDS, lane);
-            if (ONE) snapshot_publish<NR>(p.snap_flags, (k0 >> 6) - 1);
+            if (ONE) snapshot_publish<NR>(p.snap_flags, k0 >> 6, lane);
         }
         const int k = k0 + lane;
         const int rq = rq_n, sv = sv_n, ov = ov_n;
@@ -560,7 +563,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
                 if (p.state_out) p.state_out[1] = -1;  // poisons every timeline that resumes from it
             }
             if (ONE && takes_snapshots)  // nobody shall wait for the snapshots that will not come
-                for (int j = k0 >> 6; j < p.snap_blocks; ++j) snapshot_flag_set<NR>(p.snap_flags, j, KVS_SNAP_NEVER);
+                snapshot_progress_set<NR>(p.snap_flags, ~(k0 >> 6), lane);
             return;  // (snapshots not taken stay marked unusable, as the host left them)
         }
         const int cnt = min(WAVE, n - k0);

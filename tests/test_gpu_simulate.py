@@ -350,6 +350,35 @@ def test_resume_with_short_decode_lengths(ctx, resume_from_2048_rows):
             assert (_resume_positions(ctx, C) > 0).sum() > C // 4
 
 
+def test_resume_with_more_than_2047_blocks(ctx):
+    # 140000 positions = 2187 blocks of 64: the resume plan is sorted by radix passes instead of by
+    # counting, and there are that many saved states and flags.  Rows that differ from row 0 only near
+    # the end (most of the work skipped), anywhere, and at position 0
+    rng = np.random.default_rng(78)
+    n, C, M = 140000, 70, 600
+    s = rng.integers(1, 41, n).astype(np.int32)
+    o = rng.integers(1, 9, n).astype(np.int32)
+    base, _, _ = oracle.sortedF(s, o, M)
+    rows = np.broadcast_to(base, (C, n)).copy()
+    for c in range(1, C):
+        i = int(rng.integers(n - 5000, n - 1)) if c % 3 == 0 else 0 if c == 1 else int(rng.integers(0, n - 1))
+        j = int(rng.integers(i + 1, n))
+        rows[c, i], rows[c, j] = rows[c, j], rows[c, i]
+    tel_o, comp_o = oracle.simulate_many(s, o, M, rows, literal=False)
+    try:
+        ctx.set_resume_min_rows(64)
+        for polls in (4096, 0):
+            ctx.set_resume_one_launch(polls)
+            tel_g, comp_g, status = _gpu_simulate(ctx, s, o, M, rows, completions=(polls != 0))
+            assert status == 0
+            _assert_equal(tel_g, comp_g, tel_o, comp_o, f"2187 blocks, wait_polls={polls}")
+            pos = _resume_positions(ctx, C)
+            assert pos[0] == 0 and pos[1] == 0 and (pos % 64 == 0).all() and pos.max() > 64 * 2047
+    finally:
+        ctx.set_resume_min_rows(-1)
+        ctx.set_resume_one_launch(4096)
+
+
 def test_resume_with_a_request_that_cannot_be_scheduled(ctx, resume_from_2048_rows):
     # a request with s + o > M at position 300 of row 0: row 0 stops there, the snapshots behind
     # it are never taken, and every row that holds the request gets tel = -1 whether it would
