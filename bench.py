@@ -34,20 +34,20 @@ OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for on
 CFG = 3
 
 # HBM traffic of the dominant kernel per launch (one per step) on this workload, from rocprofv3
-# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 46945 KiB x 1.9997 (what a
-# plain 256 MiB copy reads per KiB moved) + WRITE_SIZE 89424 KiB x 1.0.  Valid only for the kernel
+# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 46963 KiB x 1.9997 (what a
+# plain 256 MiB copy reads per KiB moved) + WRITE_SIZE 89485 KiB x 1.0.  Valid only for the kernel
 # sources it was measured on; reported as null once they change.
-TRAFFIC_BYTES = int((46945 * 1.9997 + 89424 * 1.0) * 1024)
+TRAFFIC_BYTES = int((46963 * 1.9997 + 89485 * 1.0) * 1024)
 TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
-TRAFFIC_SOURCES_SHA256 = "9b56300fbfa94759"
+TRAFFIC_SOURCES_SHA256 = "35d75c7b25cb13ed"
 
 
 # Issue slots the same kernel really used on this workload (profiles/timeline_kernel_config3_counters.md):
-# SQ_INSTS_VALU 1.185e9 x 4 cycles / (1024 SIMDs x 4.95e6 cycles) and (SQ_INSTS_SALU 8.763e8 +
-# SQ_INSTS_BRANCH 2.248e8) / (256 scalar units x 4.95e6 cycles), cycles from GRBM_GUI_ACTIVE / 8 XCDs.
+# SQ_INSTS_VALU 1.185e9 x 4 cycles / (1024 SIMDs x 4.94e6 cycles) and (SQ_INSTS_SALU 8.763e8 +
+# SQ_INSTS_BRANCH 2.252e8) / (256 scalar units x 4.94e6 cycles), cycles from GRBM_GUI_ACTIVE / 8 XCDs.
 # The accounting above credits 6 lane-ops per visit where the kernel issues 4.9, so the physical
 # utilisation is this, not roofline.frac.
-ISSUE_SLOTS = {"valu": 0.934, "scalar_and_branch": 0.868}
+ISSUE_SLOTS = {"valu": 0.937, "scalar_and_branch": 0.871}
 
 
 def _kernel_sources_unchanged() -> bool:
