@@ -61,11 +61,12 @@ typedef struct kvsched_ctx kvsched_ctx;
 #define KVSCHED_TIE_LARGER 0  /* equal F: the larger batch (Section 4: minimise (F, -|X|))   */
 #define KVSCHED_TIE_SMALLER 1 /* equal F: the smaller batch (first minimum scanning k upward) */
 
-/* largest supported decode length (slots of the per-timeline future-memory ring) */
+/* Phase-1 batch feasibility */
 #define KVSCHED_FEAS_SUM_OF_PEAKS 0 /* a batch is feasible if sum (s_i + o_i) <= M (Algorithms 2-4)  */
 #define KVSCHED_FEAS_PROFILE 1      /* ... if, all started together, memory <= M at every completion
                                        time (the constraint of Algorithm 1's Phase 1)              */
 
+/* largest supported decode length (slots of the per-timeline future-memory ring) */
 #define KVSCHED_MAX_O 16384
 
 /* Phase-1 batch solvers selectable in kvsched_phase1_G */
@@ -291,6 +292,30 @@ int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t 
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n,
                           const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o,
                           int64_t M, int64_t *tel_out, int64_t *result_out, void *stream);
+
+/*
+ * kvsched_best_neighbor for callers that cannot allocate device memory while they run: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and
+ * results; what differs:
+ *   - its working memory (latencies of the K + 1 timelines, the plan and the saved states for
+ *     resuming) is a fixed array of KVSCHED_STATIC_SCRATCH_MIB MiB in the library's device image (one
+ *     copy on every GPU the library is used on, held until the process ends; its address on the
+ *     context's device is looked up once, in kvsched_create).  The call allocates and frees nothing
+ *     and never waits for the device;
+ *   - o_max_bound (1..KVSCHED_MAX_O) is the caller's bound on the decode lengths, as for
+ *     kvsched_set_o_max (a longer one is reported as KVSCHED_DEV_O_MAX, tel = -1), in place of the
+ *     length scan's read-back;
+ *   - ERANGE when the working memory needed, about 20 (K + 1) + 17408 floor((n - 1) / 64) + 24576
+ *     bytes, exceeds the array (K = 65536 moves fit up to n = 16384 positions), or the context's
+ *     device number is 64 or more.
+ * Every call on a GPU uses that GPU's one array, whatever the context: two such calls whose work
+ * overlaps on one GPU race (order them on one stream or by events).  Nothing in the array needs to
+ * be zero at entry; it keeps the last call's contents.
+ */
+#define KVSCHED_STATIC_SCRATCH_MIB 8
+int kvsched_best_neighbor_static(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves,
+                                 int32_t K, const int32_t *s, const int32_t *o, int64_t M, int32_t o_max_bound,
+                                 int64_t *tel_out, int64_t *result_out, void *stream);
 
 /*
  * One re-planning step of receding-horizon scheduling (Section 6, "Heuristics under Online

@@ -2,9 +2,36 @@
 // All arithmetic of the method runs in the kernels of simulate.hip and sortedf.hip.
 #include "kvsched_internal.h"
 
+#include <mutex>
 #include <new>
 
+// Working memory of kvsched_best_neighbor_static: a fixed array in the library's device image, so
+// that the call needs no allocation.  Every GPU the library is used on holds its own copy at its
+// own address; host code never uses the array's name as an address but asks the runtime for it,
+// once per device (static_scratch_of_current_device), and passes that pointer on.
+constexpr size_t KVS_STATIC_SCRATCH_BYTES = (size_t)KVSCHED_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[KVS_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_scratch[kMaxDevices];  // device address of `scratch` on each GPU, once resolved
+
+// Address of this library's `scratch` array on the device that is current (call after hipSetDevice).
+int static_scratch_of_current_device(int device, void **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return KVSCHED_ERANGE;
+    std::lock_guard<std::mutex> guard(g_static_mu);
+    if (!g_static_scratch[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KVSCHED_EHIP;
+        g_static_scratch[device] = p;
+    }
+    *out = g_static_scratch[device];
+    return KVSCHED_OK;
+}
 
 constexpr int64_t kMaxM = (int64_t)1 << 30;
 constexpr int32_t WAVE_POSITIONS = 64;  // positions of an order a wavefront fetches at a time
@@ -201,6 +228,7 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->h_words = nullptr;
     ctx->d_scratch = nullptr;
     ctx->scratch_bytes = 0;
+    ctx->static_scratch = nullptr;
     ctx->d_tables = nullptr;
     ctx->tables_bytes = 0;
     ctx->timing = 0;
@@ -216,6 +244,14 @@ int kvsched_create(kvsched_ctx **out, int device_id)
         hipMemset(ctx->d_words, 0, sizeof(int32_t) * KVS_W_COUNT) != hipSuccess) {
         kvsched_destroy(ctx);
         return KVSCHED_ENOMEM;
+    }
+    // devices beyond the table simply cannot use kvsched_best_neighbor_static
+    if (device_id < kMaxDevices) {
+        const int rc = static_scratch_of_current_device(device_id, &ctx->static_scratch);
+        if (rc != KVSCHED_OK) {
+            kvsched_destroy(ctx);
+            return rc;
+        }
     }
     *out = ctx;
     return KVSCHED_OK;
@@ -596,22 +632,26 @@ static size_t neighbor_scratch_bytes(int32_t K, int32_t n)
            align256(sizeof(int32_t) * nblk * KVS_STATE_MAX_WORDS);
 }
 
-int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,
-                          const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out, int64_t *result_out,
-                          void *stream)
+// kvsched_best_neighbor on working memory `work` of at least neighbor_scratch_bytes(K, n) bytes.
+// o_bound_known > 0: the caller's bound on the decode lengths; nothing is read back from the device
+// (so the lowest position the moves touch is not known either and no common prefix is placed ahead:
+// moves far into the order start from the base order's saved states instead).
+static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known, const int32_t *base_order, int32_t n,
+                            const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o, int64_t M,
+                            int64_t *tel_out, int64_t *result_out, hipStream_t st)
 {
-    int rc = check_common(ctx, n, s, o, M);
-    if (rc != KVSCHED_OK) return rc;
-    if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
-    hipStream_t st = (hipStream_t)stream;
-    // scratch: [K+1] latencies (neighbours, then the base order) | state of the shared prefix | resume plan
+    // work: [K+1] latencies (neighbours, then the base order) | state of the shared prefix | resume plan
     const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1));
-    rc = ensure_scratch(ctx, neighbor_scratch_bytes(K, n));
-    if (rc != KVSCHED_OK) return rc;
-    int64_t *tel = (int64_t *)ctx->d_scratch;
-    int32_t *state = (int32_t *)((char *)ctx->d_scratch + tel_bytes);
+    int64_t *tel = (int64_t *)work;
+    int32_t *state = (int32_t *)((char *)work + tel_bytes);
     int32_t o_bound = 0, min_pos = 0;
-    rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound, moves, K, &min_pos);
+    int rc;
+    if (o_bound_known > 0) {
+        rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, o_bound_known, ctx->d_words, st);
+        o_bound = o_bound_known;
+    } else {
+        rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound, moves, K, &min_pos);
+    }
     if (rc != KVSCHED_OK) return rc;
     const int32_t H = ring_slots_for(o_bound);
     if ((int64_t)n * (int64_t)H >= kMaxM) return KVSCHED_ERANGE;
@@ -645,7 +685,7 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
         const int32_t nblk = (n - 1) / WAVE_POSITIONS;
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
-        char *plan = (char *)ctx->d_scratch + tel_bytes + state_bytes();
+        char *plan = (char *)work + tel_bytes + state_bytes();
         int32_t *blocks = (int32_t *)plan;
         int32_t *sorted = (int32_t *)(plan + list_bytes);
         int32_t *tmp = (int32_t *)(plan + 2 * list_bytes);
@@ -678,6 +718,36 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
         hipMemcpyAsync(tel_out, tel, sizeof(int64_t) * (size_t)K, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return KVSCHED_EHIP;
     return KVSCHED_OK;
+}
+
+int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves, int32_t K,
+                          const int32_t *s, const int32_t *o, int64_t M, int64_t *tel_out, int64_t *result_out,
+                          void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
+    rc = ensure_scratch(ctx, neighbor_scratch_bytes(K, n));
+    if (rc != KVSCHED_OK) return rc;
+    return best_neighbor_on(ctx, ctx->d_scratch, ctx->o_max_bound, base_order, n, moves, K, s, o, M, tel_out,
+                            result_out, (hipStream_t)stream);
+}
+
+int kvsched_best_neighbor_static(kvsched_ctx *ctx, const int32_t *base_order, int32_t n, const int32_t *moves,
+                                 int32_t K, const int32_t *s, const int32_t *o, int64_t M, int32_t o_max_bound,
+                                 int64_t *tel_out, int64_t *result_out, void *stream)
+{
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX || o_max_bound < 1) return KVSCHED_EINVAL;
+    if (o_max_bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
+    if (!ctx->static_scratch) return KVSCHED_ERANGE;  // device number beyond the table of resolved addresses
+    if (neighbor_scratch_bytes(K, n) > KVS_STATIC_SCRATCH_BYTES) return KVSCHED_ERANGE;
+    // Nothing in the array has to start at zero: the latencies, the prefix state and the plan's lists are
+    // written before they are read, and the progress word of the hand-over is cleared by the kernel that
+    // sorts the plan.
+    return best_neighbor_on(ctx, ctx->static_scratch, o_max_bound, base_order, n, moves, K, s, o, M, tel_out,
+                            result_out, (hipStream_t)stream);
 }
 
 int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int32_t *moves, int32_t K,

@@ -26,6 +26,7 @@ struct kvsched_ctx {
     int32_t *h_words;      // [KVS_W_COUNT] pinned host mirror
     void *d_scratch;       // grows on demand
     size_t scratch_bytes;
+    void *static_scratch;  // this device's address of the library's fixed working array (never freed)
     void *d_tables;        // exact DP: tables and records, grows on demand
     size_t tables_bytes;
     int timing;            // record events around the timeline kernel

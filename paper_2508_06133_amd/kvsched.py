@@ -62,6 +62,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_simulate_predicted.argtypes = [vp, vp, i32, i32, vp, vp, vp, i32, i64, vp, vp, vp, vp]
     lib.kvsched_phase1_G.argtypes = [vp, i32, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.kvsched_best_neighbor.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp, vp, vp]
+    lib.kvsched_best_neighbor_static.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i32, vp, vp, vp]
     lib.kvsched_horizon_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.kvsched_online.argtypes = [vp, i32, vp, i32, vp, vp, vp, i64, i32, vp, i32, vp, vp]
     return lib
@@ -276,6 +277,19 @@ class Context:
         if rc != OK:
             raise KvschedError(rc, "kvsched_best_neighbor")
         return tel, res
+
+    def best_neighbor_static(self, base_order, moves, s, o, M, o_max_bound: int, tel_out, result_out):
+        """kvsched_best_neighbor on the library's fixed working array: the caller passes every output
+        tensor (tel_out [K] int64 or None, result_out [3] int64); nothing is allocated."""
+        rc = _lib.kvsched_best_neighbor_static(self._h, _dev(base_order, torch.int32, "base_order"),
+                                               base_order.shape[0], _dev(moves, torch.int32, "moves"), moves.shape[0],
+                                               _dev(s, torch.int32, "s"), _dev(o, torch.int32, "o"), int(M),
+                                               int(o_max_bound),
+                                               _dev(tel_out, torch.int64, "tel_out") if tel_out is not None else None,
+                                               _dev(result_out, torch.int64, "result_out"), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_best_neighbor_static")
+        return tel_out, result_out
 
     def horizon_step(self, order, moves, s, o, M, completed_in: int, complete_every: int, want_tel: bool = False,
                      completion_out=None):
