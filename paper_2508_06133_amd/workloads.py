@@ -137,6 +137,32 @@ def window_moves(rng: np.random.Generator, count: int, lo: int, hi: int) -> np.n
     return moves
 
 
+def moves_anywhere(rng: np.random.Generator, count: int, n: int) -> np.ndarray:
+    """Move 0 is the identity; the rest are swaps and inserts (a coin each) on two positions drawn
+    uniformly over the whole order (they may coincide: the identity again)."""
+    moves = np.zeros((count, 3), dtype=np.int32)
+    if count > 1:
+        moves[1:, 0] = rng.integers(0, 2, count - 1)
+        moves[1:, 1] = rng.integers(0, n, count - 1)
+        moves[1:, 2] = rng.integers(0, n, count - 1)
+    return moves
+
+
+def tight_instance(seed: int, n: int, o_max: int, long_frac: float = 0.25, width: float = 3.0) -> Instance:
+    """A small instance under a tight budget, for parity cases in which most requests have to wait:
+    decode lengths uniform in [1, o_max // 16] or, with probability long_frac, in (o_max // 2, o_max]
+    (one request has exactly o_max), prompts uniform in [1, o_max // 4], and a budget of `width` times
+    the largest s + o."""
+    rng = np.random.default_rng(SEED0 + 7000 + seed)
+    short = rng.integers(1, max(1, o_max // 16) + 1, n)
+    long_ = rng.integers(o_max // 2 + 1, o_max + 1, n)
+    o = np.where(rng.random(n) < long_frac, long_, short).astype(np.int32)
+    o[int(rng.integers(0, n))] = o_max
+    s = rng.integers(1, max(1, o_max // 4) + 1, n).astype(np.int32)
+    M = int(width * int((s.astype(np.int64) + o).max()))
+    return Instance(f"tight{seed}", s, o, M)
+
+
 def orders_from_moves(base: np.ndarray, moves: np.ndarray) -> np.ndarray:
     rows = np.empty((moves.shape[0], base.shape[0]), dtype=np.int32)
     for k in range(moves.shape[0]):

@@ -68,33 +68,29 @@ def test_horizon_step_literal_tiny(ctx):
     assert (comp.cpu().numpy() == comp_o).all()
 
 
-def test_config4_full_size_two_windows_sampled(ctx):
-    # n = 10000, M = 2^20, 65536 moves per 512-window: the first two re-plans at full size.  The
-    # oracle re-computes the chosen move, the base order and a sample of the neighbours.
-    from paper_2508_06133_amd import horizon
+def test_hand_worked_example_on_gpu(ctx, golden_dir):
+    # tests/golden/horizon_worked.txt: eight requests, three re-plans worked by hand (candidates'
+    # latencies, chosen move, timeline, T / completed / committed of every step)
+    import os
+    import torch
 
-    inst = workloads.instance(4)
-    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
-    print(f"config 4: n={inst.n} M={inst.M}", flush=True)
-    rng = np.random.default_rng(4)
-    order_g, comp_g, log = horizon.receding_horizon(ctx, _dev(inst.s), _dev(inst.o), inst.M, _dev(base), 512, 256, 65536,
-                                                    rng=rng, keep_tel=True, max_steps=2)
-    rng_o = np.random.default_rng(4)
-    order = base
+    from conftest import read_golden
+    from test_oracle_horizon import ints, worked_moves
+
+    g = read_golden(os.path.join(golden_dir, "horizon_worked.txt"))
+    s, o, M = _dev(ints(g["s"])), _dev(ints(g["o"])), int(g["M"])
+    order = _dev(ints(g["base_order"]))
+    comp = torch.empty(order.shape[0], dtype=torch.int32, device="cuda:0")
     completed = 0
-    for rec in log:
-        moves = workloads.window_moves(rng_o, 65536, rec["lo"], rec["hi"])
-        tel = rec["tel"]
-        assert rec["best"] == int(np.argmin(tel)) and rec["best_tel"] == int(tel.min())  # first minimum
-        sample = np.unique(np.concatenate([np.arange(0, 65536, 4096), [rec["best"], 1, 65535]]))
-        rows = workloads.orders_from_moves(order, moves[sample])
-        tel_o, _ = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False, completions=False)
-        assert (tel[sample] == tel_o).all()
-        assert rec["base_tel"] == tel_o[0] == tel[0]  # move 0 is the identity
-        order = workloads.apply_move(order, moves[rec["best"]])
-        p, c, _ = oracle.simulate(inst.s, inst.o, inst.M, order, literal=False)
-        k = min(inst.n, completed + 256)
-        T = int(np.sort(c)[k - 1])
-        assert (rec["T"], rec["completed"], rec["committed"]) == (T, int((c <= T).sum()), int((p[order] <= T).sum()))
-        completed = rec["completed"]
-    assert (order_g.cpu().numpy() == order).all() and (comp_g.cpu().numpy() == c).all()
+    for k in (1, 2, 3):
+        lo, hi = ints(g[f"step{k}_lo_hi"])
+        tel, res = ctx.horizon_step(order, _dev(worked_moves(lo, hi)), s, o, M, completed, int(g["complete_every"]),
+                                    want_tel=True, completion_out=comp)
+        torch.cuda.synchronize()
+        T, done, committed = ints(g[f"step{k}_T_completed_committed"])
+        want = ints(g[f"step{k}_tel"])
+        assert tel.cpu().tolist() == want
+        assert res.cpu().tolist() == [int(g[f"step{k}_best"]), min(want), want[0], committed, done, T]
+        assert order.cpu().tolist() == ints(g[f"step{k}_order"]) and comp.cpu().tolist() == ints(g[f"step{k}_completion"])
+        completed = done
+    assert ctx.device_status() == 0

@@ -112,18 +112,7 @@ def test_config5_scaled_and_full_rows(ctx):
     _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 5 scaled")
 
 
-def test_config5_full_size_rows(ctx):
-    # n = 100000, decode lengths 1 or 4096: the 65-row register file, 200 M request-rounds per
-    # timeline.  Base order and two perturbed rows against the array-profile oracle.
-    inst = workloads.instance(5)
-    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
-    rows = workloads.candidates(5, base, count=3)
-    print(f"config 5: n={inst.n} C={rows.shape[0]}", flush=True)
-    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
-    tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows)
-    assert status == 0
-    _assert_equal(tel_g, comp_g, tel_o, comp_o, "config 5")
-    assert tel_g.max() > 2 ** 31  # needs the 64-bit accumulator
+# (configuration 5 at its full size, every one of its 1025 rows: tests/test_gpu_full_size_parity.py)
 
 
 @pytest.mark.parametrize("n,omax,smax,M,C", [
