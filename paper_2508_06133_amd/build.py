@@ -2,10 +2,11 @@
 
 hipcc cross-compiles without a GPU, so this runs anywhere the ROCm toolchain is installed.
 
-timeline_reg.hip keeps per-timeline state in a block of physical VGPRs (v24 upward) that only
-its inline-assembly blocks touch.  That is sound only while the compiler-generated part of those
-kernels stays below v24, so the build emits the device assembly of that file and fails if any
-compiler-generated instruction of a timeline_reg_kernel names a VGPR of the block.
+timeline_reg.hip keeps per-timeline state in a block of physical VGPRs (v28 upward) that only
+its inline-assembly blocks touch.  That is sound only while everything the compiler allocates in those
+kernels (its own code and the operand registers it hands to the assembly statements) stays below v28,
+so the build emits the device assembly of that file and fails if a timeline_reg_kernel names a VGPR of
+the block anywhere but in the hand-written row code, or if it did not see every instantiation.
 """
 from __future__ import annotations
 
@@ -27,7 +28,7 @@ DEVICE_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 FLAGS = DEVICE_FLAGS + ["-fPIC", "-shared", "-Wall", "-Wno-unused-function"]
-RESERVED_VGPR_BASE = 24  # KVS_PB in timeline_reg.hip
+RESERVED_VGPR_BASE = 28  # KVS_PB in timeline_reg.hip
 
 
 def lib_path() -> str:
@@ -42,19 +43,38 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def reserved_vgpr_violations(asm_text: str, base: int = RESERVED_VGPR_BASE) -> list[str]:
-    """Compiler-generated lines inside timeline_reg_kernel bodies that name a VGPR >= base.
+def timeline_reg_instantiations() -> int:
+    """Kernel instantiations kvs_launch_simulate_reg can reach: one per launch statement of launch_reg
+    and profile-file size."""
+    src = open(os.path.join(CSRC, "timeline_reg.hip")).read()
+    launches = len(re.findall(r"hipLaunchKernelGGL\(\(timeline_reg_kernel<NR, WPB,", src))
+    sizes = len(re.findall(r"return launch_reg<\d+, \d+>\(p, st\);", src))
+    return launches * sizes
 
-    A body runs from the kernel's label to its .Lfunc_end label (s_endpgm may come early, for the
-    exits in the prologue); inline assembly sits between the ASMSTART / ASMEND (or APP / NO_APP)
-    comment lines the compiler emits around it.
+
+def reserved_vgpr_scan(asm_text: str, base: int = RESERVED_VGPR_BASE) -> tuple[list[str], int]:
+    """(offending lines, kernel bodies scanned) for the timeline_reg_kernel bodies of a device assembly.
+
+    The profile block of an instantiation with NR rows (read off the kernel's mangled name) is
+    v[base, base + NR).  It belongs to the hand-written assembly alone, which names it only as
+    v[<base>+...].  Offending are therefore: a compiler-generated line that names a VGPR of the block in
+    any form, and a line INSIDE an assembly statement that names one as plain vN or v[a:b] -- an operand
+    register the compiler substituted (temporaries and inputs of the statements must lie outside the
+    block as well).  A body runs from the kernel's label to its .Lfunc_end label (s_endpgm may come
+    early, for the exits in the prologue); inline assembly sits between the ASMSTART / ASMEND (or APP /
+    NO_APP) comment lines the compiler emits around it.
     """
     bad = []
+    bodies = 0
     in_kernel = in_asm = False
+    top = base
     for line in asm_text.splitlines():
         s = line.strip()
-        if re.match(r"^_Z\w*timeline_reg_kernel\w*:", s):
+        m = re.match(r"^_Z\w*timeline_reg_kernelILi(\d+)E\w*:", s)
+        if m:
             in_kernel, in_asm = True, False
+            top = base + int(m.group(1))
+            bodies += 1
             continue
         if not in_kernel:
             continue
@@ -67,31 +87,38 @@ def reserved_vgpr_violations(asm_text: str, base: int = RESERVED_VGPR_BASE) -> l
         if s.startswith((";;#ASMEND", ";NO_APP", "#NO_APP")):
             in_asm = False
             continue
-        if in_asm or not s or s.startswith((";", ".")):
+        if not s or s.startswith(";") or (not in_asm and s.startswith(".")):
             continue
         code = s.split(";", 1)[0]
-        regs = [int(m) for m in re.findall(r"\bv(\d+)\b", code)]
-        for lo, hi in re.findall(r"\bv\[(\d+):(\d+)\]", code):
-            regs += [int(lo), int(hi)]
-        if any(r >= base for r in regs):
+        regs = [(int(m), int(m)) for m in re.findall(r"\bv(\d+)\b", code)]
+        regs += [(int(lo), int(hi)) for lo, hi in re.findall(r"\bv\[(\d+):(\d+)\]", code)]
+        if any(lo < top and hi >= base for lo, hi in regs):
             bad.append(s)
-    return bad
+    return bad, bodies
 
 
-def check_reserved_vgprs(hipcc: str, verbose: bool = False) -> None:
+def reserved_vgpr_violations(asm_text: str, base: int = RESERVED_VGPR_BASE) -> list[str]:
+    return reserved_vgpr_scan(asm_text, base)[0]
+
+
+def emit_timeline_reg_assembly(hipcc: str) -> str:
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "timeline_reg.s")
         cmd = [hipcc, *DEVICE_FLAGS, "-S", "--cuda-device-only", os.path.join(CSRC, "timeline_reg.hip"), "-o", out]
         subprocess.check_call(cmd, stderr=subprocess.DEVNULL)
-        text = open(out).read()
-    if "timeline_reg_kernel" not in text:
-        raise RuntimeError("device assembly of timeline_reg.hip holds no timeline_reg_kernel")
-    bad = reserved_vgpr_violations(text)
+        return open(out).read()
+
+
+def check_reserved_vgprs(hipcc: str, verbose: bool = False) -> None:
+    bad, bodies = reserved_vgpr_scan(emit_timeline_reg_assembly(hipcc))
+    want = timeline_reg_instantiations()
+    if bodies != want or want == 0:
+        raise RuntimeError(f"scanned {bodies} timeline_reg_kernel bodies, the launcher can reach {want}")
     if bad:
-        raise RuntimeError("compiler-generated code uses the reserved VGPR block (v%d..):\n  " % RESERVED_VGPR_BASE
-                           + "\n  ".join(bad[:10]))
+        raise RuntimeError("the reserved VGPR block (v%d..) is named outside the hand-written row code:\n  "
+                           % RESERVED_VGPR_BASE + "\n  ".join(bad[:10]))
     if verbose:
-        print("reserved VGPR block untouched by compiler-generated code", flush=True)
+        print(f"reserved VGPR block untouched in all {bodies} timeline_reg_kernel bodies", flush=True)
 
 
 def build(verbose: bool = False) -> str:

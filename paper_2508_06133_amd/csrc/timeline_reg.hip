@@ -19,19 +19,20 @@
 //   update  per row:  Q_r += s + (tau - t)
 //   Only the last row of a window is lane-masked (rounds beyond t + o), by value.
 //
-// The row loops are hand-written gfx950 assembly over a fixed block of physical VGPRs (v24
-// upward) that only these assembly blocks touch.  The kernel is bound by the scalar unit (one per
-// compute unit, shared by its four SIMDs: adding eight scalar instructions per request cost
-// 11 % of the run time, eight vector instructions 1.6 %), so the loops are laid out to need
-// almost no scalar work: a pass over rows 0..re is entered by one computed jump
-// (s_getpc / s_setpc, 64-byte slots) to a stub that handles the masked last row `re` with
-// constant register numbers and then branches into a descending chain of full rows re-1..0,
-// which runs to its end without a single compare or branch.  Rows are paired (five vector
-// instructions per two rows in the check, three in the update).  Only the rounds that enter
-// the window after t has moved are reached through VGPR index mode.
-// The compiler-generated part of the kernel needs fewer than 24 VGPRs, so it never allocates
-// the block (the build verifies that); the clobber lists keep the block, s72, s73 and vcc out
-// of its hands across the assembly statements.
+// The row loops are hand-written gfx950 assembly over a fixed block of physical VGPRs (v28
+// upward) that only these assembly blocks touch, and the whole placement of up to 64 consecutive
+// requests is ONE assembly statement (place_block): the vector unit's issue slots are what bounds
+// the kernel, and the code a compiler wraps around separate check / update statements (copies for
+// loop-carried values, a compare and a select to keep a completion round, recomputed masks) cost
+// a third of them.  A pass over rows 0..re is entered by one computed jump (s_getpc / s_setpc,
+// 64-byte slots) to a stub that handles the masked last row `re` with constant register numbers
+// and then branches into a descending chain of full rows re-1..0, which runs to its end without
+// a single compare or branch.  Rows are paired (five vector instructions per two rows in the
+// check, three in the update).
+// The compiler-generated part of the kernel and the operands of the assembly statements need
+// fewer than 28 VGPRs, so the block is never allocated (the build verifies that on the emitted
+// assembly of every instantiation); the clobber lists keep the block, s72, s73 and vcc out of the
+// compiler's hands across the assembly statements.
 #include "kvsched_internal.h"
 #include "device_util.h"
 
@@ -39,17 +40,17 @@
 
 namespace {
 
-// First register of the profile block; the KVS_CLOB_* lists start there.
-#define KVS_PB "24"
+// First register of the profile block; the KVS_CLOB_* lists start there.  The compiler's own
+// registers (and the operands it hands to the assembly statements) must stay below it: the build
+// checks that on the emitted assembly of every instantiation.
+#define KVS_PB "28"
 
-#define KVS_CLOB_9 "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32"
-#define KVS_CLOB_33                                                                                               \
-    KVS_CLOB_9, "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", \
-        "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56"
-#define KVS_CLOB_65                                                                                                \
-    KVS_CLOB_33, "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", \
-        "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85",   \
-        "v86", "v87", "v88"
+#define KVS_CLOB_9 "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35", "v36"
+#define KVS_CLOB_33 KVS_CLOB_9, "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", \
+    "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60"
+#define KVS_CLOB_65 KVS_CLOB_33, "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", \
+    "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", \
+    "v89", "v90", "v91", "v92"
 
 // Row numbers as the assembler's .irp wants them: all rows ascending (one stub each), and the
 // rows that can be the last row of a window with at least one full row below, descending.
@@ -59,12 +60,6 @@ namespace {
 #define KVS_DESC_33 "32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
 #define KVS_ASC_65 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63,64"
 #define KVS_DESC_65 "64,63,62,61,60,59,58,57,56,55,54,53,52,51,50,49,48,47,46,45,44,43,42,41,40,39,38,37,36,35,34,33,32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
-
-// gfx950 needs a wait state between s_set_gpr_idx_on and the first VALU instruction that uses
-// the index: issued back to back, about 0.3 % of the timelines of a fully occupied GPU came
-// out wrong (never on a lightly loaded one); a single s_nop removed every mismatch.  Two wait
-// states are inserted.
-#define KVS_IDX_WAIT "s_nop 1\n"
 
 // Expands STMT(clobber-list, rows ascending, rows descending) for the instantiated file size
 // (NR - 1 must be even: the row chains process rows in pairs).
@@ -137,201 +132,241 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 #undef KVS_STMT
 }
 
-// Rows move down by one: row r takes over the rounds of row r + 1 (whose offset was 64 more);
-// the top row becomes empty.
-template <int NR>
-__device__ __forceinline__ void prof_rotate1()
-{
-#define KVS_STMT(CLOB, ASC, DESC)                                                            \
-    asm volatile(".set kvs_r, 0\n"                                                 \
-                 ".rept %c[nrm1]\n"                                                \
-                 "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n" \
-                 "  .set kvs_r, kvs_r+1\n"                                         \
-                 ".endr\n"                                                         \
-                 "v_mov_b32 v[" KVS_PB "+%c[nrm1]], 64*%c[nrm1]\n"                 \
-                 :                                                                 \
-                 : [nrm1] "n"(NR - 1)                                              \
-                 : CLOB)
-    KVS_FOR_NR(KVS_STMT);
-#undef KVS_STMT
-}
-
-// Computed jump to the 64-byte slot of row re = x64/64 - 1: the slots start 64 bytes after the
-// instruction that follows s_getpc_b64 (four 4-byte instructions, then padding).
-#define KVS_DISPATCH                      \
-    "s_getpc_b64 s[72:73]\n"              \
-    "s_andn2_b32 %[t0], %[x64], 63\n"     \
-    "s_add_u32 s72, s72, %[t0]\n"         \
-    "s_addc_u32 s73, s73, 0\n"            \
-    "s_setpc_b64 s[72:73]\n"              \
-    ".fill 12, 4, 0xbf800000\n"
-
 // Pads the slot that began at the last label 7 to 64 bytes (never executed: slots end in a branch).
 #define KVS_SLOT_END "  .fill (64-(.-7b))/4, 4, 0xbf800000\n"
 
-// Rows 0..re (row 0 holds round t + 1): per lane, the largest over its rounds of the least
-// admissible start, relative to the lane's round in row 0.  x64 = (t + o - b64) + 64, so that
-// re = x64/64 - 1 and the last round of the window sits in lane x64 & 63 of row re; sb = s - M;
-// vmin = INT_MIN in every lane.
+// ---------------------------------------------------------------------------------------------
+// Placing up to 64 consecutive requests of the order: ONE assembly statement.
+//
+// Lane j of vsb / vo holds s - M and o of the j-th request.  For each request in turn:
+//   check    rows 0..re of the profile (re = row of the window's last round t + o): per lane
+//            acc = max over rows of min(Q_r + (s - M), 64 r), the least admissible start that the
+//            lane's rounds impose, relative to the lane's round in row 0 (the last row is masked by
+//            value beyond round t + o: vcc);
+//   blocked  iff acc > (t - b64) - lane in some lane.  Then t becomes the largest such bound
+//            (six DPP steps), the register file moves down so that row 0 holds round t + 1 again,
+//            and only the rounds that have entered the window since are looked at (rows rs..re,
+//            one computed jump per row: the row number is not known at compile time and VGPR
+//            index mode is avoided); repeat;
+//   admit    rows 0..re get the ramp s + (tau - t); the completion round t + o goes to lane j of cv.
+// A pass over rows 0..re is entered by one computed jump (s_getpc / s_setpc, 64-byte slots) to a
+// stub that handles the masked last row with constant register numbers and branches into a
+// descending chain of full rows re-1..0, which runs to its end without a compare or a branch:
+// five vector instructions per two rows in the check, three in the update.
+//
+// Wait states (gfx950 does not interlock these; the distances below are by construction):
+//   a VALU instruction that reads an SGPR or VCC written by a VALU instruction (v_readlane,
+//   v_cmp) needs two instructions in between: sb and vcc are read by vector instructions only
+//   behind the computed jump (at least five scalar instructions later); oj, nd and the DPP result
+//   are read by scalar instructions, which need none;
+//   DPP reads of a VGPR written by the previous VALU instruction, and v_readlane of one: s_nop 1.
+// EXEC is narrowed to the window's lanes for the one masked addition of the update and restored.
+// M0 carries the lane number for v_writelane (two different SGPR operands are not encodable); the
+// kernel has no other use of M0 (no LDS, no relative addressing).
+#define KVS_JUMP                  \
+    "s_getpc_b64 s[72:73]\n"      \
+    "s_add_u32 s72, s72, %[off]\n" \
+    "s_addc_u32 s73, s73, 0\n"    \
+    "s_setpc_b64 s[72:73]\n"
+
+// Maximum over the 64 lanes of %[y] into lane 63 (four DPP steps inside the 16-lane rows, two row
+// broadcasts), read into %[tc].
+#define KVS_WAVE_MAX                                                                            \
+    "s_nop 1\n"                                                                                 \
+    "v_max_i32_dpp %[y], %[y], %[y] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"           \
+    "s_nop 1\n"                                                                                 \
+    "v_max_i32_dpp %[y], %[y], %[y] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n"           \
+    "s_nop 1\n"                                                                                 \
+    "v_max_i32_dpp %[y], %[y], %[y] row_half_mirror row_mask:0xf bank_mask:0xf\n"               \
+    "s_nop 1\n"                                                                                 \
+    "v_max_i32_dpp %[y], %[y], %[y] row_mirror row_mask:0xf bank_mask:0xf\n"                    \
+    "s_nop 1\n"                                                                                 \
+    "v_max_i32_dpp %[y], %[y], %[y] row_bcast:15 row_mask:0xa bank_mask:0xf\n"                  \
+    "s_nop 1\n"                                                                                 \
+    "v_max_i32_dpp %[y], %[y], %[y] row_bcast:31 row_mask:0xc bank_mask:0xf\n"                  \
+    "s_nop 1\n"                                                                                 \
+    "v_readlane_b32 %[tc], %[y], 63\n"
+
 template <int NR>
-__device__ __forceinline__ int prof_check_from0(int x64, int sb, int lane, int vmin)
+__device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, int vmin, int Mp64, int &t, int &b64)
 {
-    int acc, y, z, t0;
-#define KVS_STMT(CLOB, ASC, DESC)                                                              \
-    asm volatile("s_and_b32 %[t0], %[x64], 63\n"                                               \
-                 "v_cmp_ge_u32 vcc, %[t0], %[lane]\n" KVS_DISPATCH                             \
-                 ".irp r," ASC "\n"                                                            \
-                 "7:\n"                                                                        \
-                 "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                \
-                 "  v_min_i32 %[y], 64*\\r, %[y]\n"                                            \
-                 "  v_cndmask_b32 %[acc], %[vmin], %[y], vcc\n"                                \
-                 "  .if \\r == 0\n"                                                            \
-                 "    s_branch 9f\n"                                                           \
-                 "  .else\n"                                                                   \
-                 "    .if (\\r & 1) == 1\n"                                                    \
-                 "      v_mov_b32 %[z], %[acc]\n"                                              \
-                 "    .endif\n"                                                                \
-                 "    s_branch 20\\r\\()f\n"                                                   \
-                 "  .endif\n" KVS_SLOT_END                                                     \
-                 ".endr\n"                                                                     \
-                 ".irp r," DESC "\n"                                                           \
-                 "20\\r:\n"                                                                    \
-                 "  .if ((\\r-1) & 1) == 1\n"                                                  \
-                 "    v_add_u32 %[z], %[sb], v[" KVS_PB "+\\r-1]\n"                            \
-                 "    v_min_i32 %[z], 64*(\\r-1), %[z]\n"                                      \
-                 "  .else\n"                                                                   \
-                 "    v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r-1]\n"                            \
-                 "    v_min_i32 %[y], 64*(\\r-1), %[y]\n"                                      \
-                 "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                 \
-                 "  .endif\n"                                                                  \
-                 ".endr\n"                                                                     \
-                 "9:\n"                                                                        \
-                 : [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [t0] "=&s"(t0)                \
-                 : [x64] "s"(x64), [sb] "s"(sb), [lane] "v"(lane), [vmin] "v"(vmin)            \
-                 : "scc", "vcc", "s72", "s73", CLOB)
+    int cv, acc, y, z, tl;
+    int j, sb, oj, x64, off, u64, w, rs, ta, tb, tc;
+    long long nd, m2, sx;
+#define KVS_STMT(CLOB, ASC, DESC)                                                                       \
+    asm volatile(                                                                                       \
+        "s_mov_b64 %[sx], exec\n"                                                                       \
+        "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
+        "v_sub_u32 %[tl], %[u64], %[lane]\n" /* (t - b64) - lane */                                     \
+        "s_add_u32 %[u64], %[u64], 64\n"     /* x64 of a request is its decode length plus this */      \
+        "s_sub_u32 %[w], %[Mp64], %[u64]\n"  /* ramp of a request in lane l of row 0: (s - M) + w + l */ \
+        "v_mov_b32 %[cv], 0\n"                                                                          \
+        "s_mov_b32 %[j], 0\n"                                                                           \
+        /* ---- next request */                                                                         \
+        "40:\n"                                                                                         \
+        "v_readlane_b32 %[sb], %[vsb], %[j]\n"                                                          \
+        "v_readlane_b32 %[oj], %[vo], %[j]\n"                                                           \
+        "s_add_u32 %[x64], %[oj], %[u64]\n" /* (t + o - b64) + 64: row and lane of the window's last round */ \
+        "s_and_b32 %[ta], %[x64], 63\n"                                                                 \
+        "v_cmp_ge_u32 vcc, %[ta], %[lane]\n"                                                            \
+        "s_andn2_b32 %[off], %[x64], 63\n" /* 64 (re + 1): the slots start 64 bytes behind s_getpc's successor */ \
+        KVS_JUMP ".fill 13, 4, 0xbf800000\n"                                                            \
+        ".irp r," ASC "\n"                                                                              \
+        "7:\n"                                                                                          \
+        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
+        "  v_cndmask_b32 %[acc], %[vmin], %[y], vcc\n"                                                  \
+        "  .if \\r == 0\n"                                                                              \
+        "    s_branch 41f\n"                                                                            \
+        "  .else\n"                                                                                     \
+        "    .if (\\r & 1) == 1\n"                                                                      \
+        "      v_mov_b32 %[z], %[acc]\n"                                                                \
+        "    .endif\n"                                                                                  \
+        "    s_branch 20\\r\\()f\n"                                                                     \
+        "  .endif\n" KVS_SLOT_END                                                                       \
+        ".endr\n"                                                                                       \
+        ".irp r," DESC "\n"                                                                             \
+        "20\\r:\n"                                                                                      \
+        "  .if ((\\r-1) & 1) == 1\n"                                                                    \
+        "    v_add_u32 %[z], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
+        "    v_min_i32 %[z], 64*(\\r-1), %[z]\n"                                                        \
+        "  .else\n"                                                                                     \
+        "    v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
+        "    v_min_i32 %[y], 64*(\\r-1), %[y]\n"                                                        \
+        "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                                   \
+        "  .endif\n"                                                                                    \
+        ".endr\n"                                                                                       \
+        /* ---- does some round ask for a later start? */                                               \
+        "41:\n"                                                                                         \
+        "v_cmp_gt_i32_e64 %[nd], %[acc], %[tl]\n"                                                       \
+        "s_cmp_lg_u64 %[nd], 0\n"                                                                       \
+        "s_cbranch_scc1 44f\n"                                                                          \
+        /* ---- admit at round t */                                                                     \
+        "s_add_u32 %[rs], %[sb], %[w]\n"                                                                \
+        KVS_JUMP ".fill 13, 4, 0xbf800000\n"                                                            \
+        ".irp r," ASC "\n"                                                                              \
+        "7:\n"                                                                                          \
+        "  .if \\r == 0\n"                                                                              \
+        "    v_add_u32 %[y], %[rs], %[lane]\n"                                                          \
+        "    s_mov_b64 exec, vcc\n"                                                                     \
+        "    v_add_u32 v[" KVS_PB "], %[y], v[" KVS_PB "]\n"                                            \
+        "    s_mov_b64 exec, %[sx]\n"                                                                   \
+        "    s_branch 43f\n"                                                                            \
+        "  .else\n"                                                                                     \
+        "    s_add_u32 %[ta], %[rs], 64*\\r\n"                                                          \
+        "    v_add_u32 %[y], %[ta], %[lane]\n"                                                          \
+        "    s_mov_b64 exec, vcc\n"                                                                     \
+        "    v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                    \
+        "    s_mov_b64 exec, %[sx]\n"                                                                   \
+        /*   z: ramp of the even row of the pair that holds row r - 1 */                                \
+        "    .if (\\r & 1) == 1\n"                                                                      \
+        "      v_subrev_u32 %[z], 64, %[y]\n"                                                           \
+        "    .else\n"                                                                                   \
+        "      v_add_u32 %[z], 0xffffff80, %[y]\n"                                                      \
+        "    .endif\n"                                                                                  \
+        "    s_branch 30\\r\\()f\n"                                                                     \
+        "  .endif\n" KVS_SLOT_END                                                                       \
+        ".endr\n"                                                                                       \
+        ".irp r," DESC "\n"                                                                             \
+        "30\\r:\n"                                                                                      \
+        "  .if ((\\r-1) & 1) == 1\n"                                                                    \
+        "    v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[z], 64\n"                           \
+        "  .else\n"                                                                                     \
+        "    v_add_u32 v[" KVS_PB "+\\r-1], %[z], v[" KVS_PB "+\\r-1]\n"                                \
+        "    .if (\\r-1) >= 2\n"                                                                        \
+        "      v_add_u32 %[z], 0xffffff80, %[z]\n"                                                      \
+        "    .endif\n"                                                                                  \
+        "  .endif\n"                                                                                    \
+        ".endr\n"                                                                                       \
+        "43:\n"                                                                                         \
+        "s_add_u32 %[ta], %[t], %[oj]\n"                                                                \
+        "s_mov_b32 m0, %[j]\n"                                                                          \
+        "s_nop 0\n"                                                                                     \
+        "v_writelane_b32 %[cv], %[ta], m0\n"                                                            \
+        "s_add_u32 %[j], %[j], 1\n"                                                                     \
+        "s_cmp_lt_u32 %[j], %[cnt]\n"                                                                   \
+        "s_cbranch_scc1 40b\n"                                                                          \
+        "s_branch 50f\n"                                                                                \
+        /* ---- blocked: move t to the largest bound, the register file with it, look at what is new */ \
+        "44:\n"                                                                                         \
+        "v_add_u32 %[y], %[acc], %[lane]\n"                                                             \
+        KVS_WAVE_MAX                                                                                    \
+        "s_add_u32 %[tb], %[x64], %[b64]\n"                                                             \
+        "s_sub_u32 %[tb], %[tb], 63\n"       /* first round not looked at yet */                        \
+        "s_add_u32 %[t], %[tc], %[b64]\n"                                                               \
+        "s_add_u32 %[tc], %[t], 1\n"                                                                    \
+        "s_andn2_b32 %[tc], %[tc], 63\n"     /* row 0 starts at 64 floor((t + 1) / 64) */               \
+        "s_sub_u32 %[rs], %[tc], %[b64]\n"                                                              \
+        "s_lshr_b32 %[rs], %[rs], 6\n"       /* rows to move down */                                    \
+        "s_mov_b32 %[b64], %[tc]\n"                                                                     \
+        "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
+        "v_sub_u32 %[tl], %[u64], %[lane]\n"                                                            \
+        "s_add_u32 %[u64], %[u64], 64\n"                                                                \
+        "s_sub_u32 %[w], %[Mp64], %[u64]\n"                                                             \
+        "s_add_u32 %[x64], %[oj], %[u64]\n"                                                             \
+        "s_andn2_b32 %[off], %[x64], 63\n"                                                              \
+        "s_and_b32 %[ta], %[x64], 63\n"                                                                 \
+        "v_cmp_ge_u32 vcc, %[ta], %[lane]\n"                                                            \
+        "s_sub_u32 %[tb], %[tb], %[b64]\n"                                                              \
+        "s_lshr_b32 %[tb], %[tb], 6\n"       /* its row */                                              \
+        "s_lshr_b32 %[tc], %[x64], 6\n"                                                                 \
+        "s_sub_u32 %[tc], %[tc], 1\n"        /* last row of the window */                               \
+        "s_cmp_ge_u32 %[rs], %c[nr]\n"                                                                  \
+        "s_cbranch_scc1 47f\n"                                                                          \
+        "45:\n"                                                                                         \
+        "s_cmp_eq_u32 %[rs], 0\n"                                                                       \
+        "s_cbranch_scc1 46f\n"                                                                          \
+        ".set kvs_r, 0\n"                                                                               \
+        ".rept %c[nr]-1\n"                                                                              \
+        "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n"                               \
+        "  .set kvs_r, kvs_r+1\n"                                                                       \
+        ".endr\n"                                                                                       \
+        "v_mov_b32 v[" KVS_PB "+%c[nr]-1], 64*(%c[nr]-1)\n"                                             \
+        "s_sub_u32 %[rs], %[rs], 1\n"                                                                   \
+        "s_branch 45b\n"                                                                                \
+        "47:\n"                                                                                         \
+        ".set kvs_r, 0\n"                                                                               \
+        ".rept %c[nr]\n"                                                                                \
+        "  v_mov_b32 v[" KVS_PB "+kvs_r], 64*kvs_r\n"                                                   \
+        "  .set kvs_r, kvs_r+1\n"                                                                       \
+        ".endr\n"                                                                                       \
+        "46:\n"                                                                                         \
+        "v_mov_b32 %[acc], %[vmin]\n"                                                                   \
+        "48:\n"                                                                                         \
+        "s_cmp_eq_u32 %[tb], %[tc]\n"                                                                   \
+        "s_cselect_b64 %[m2], vcc, -1\n"     /* only the window's last row is masked */                 \
+        "s_add_u32 %[ta], %[tb], 1\n"                                                                   \
+        "s_lshl_b32 %[ta], %[ta], 4\n"       /* 16-byte slots, the first 16 bytes behind s_getpc's successor */ \
+        "s_getpc_b64 s[72:73]\n"                                                                        \
+        "s_add_u32 s72, s72, %[ta]\n"                                                                   \
+        "s_addc_u32 s73, s73, 0\n"                                                                      \
+        "s_setpc_b64 s[72:73]\n"                                                                        \
+        ".fill 1, 4, 0xbf800000\n"                                                                      \
+        ".irp r," ASC "\n"                                                                              \
+        "7:\n"                                                                                          \
+        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
+        "  s_branch 49f\n"                                                                              \
+        "  .fill (16-(.-7b))/4, 4, 0xbf800000\n"                                                        \
+        ".endr\n"                                                                                       \
+        "49:\n"                                                                                         \
+        "v_cndmask_b32_e64 %[y], %[vmin], %[y], %[m2]\n"                                                \
+        "v_max_i32 %[acc], %[acc], %[y]\n"                                                              \
+        "s_add_u32 %[tb], %[tb], 1\n"                                                                   \
+        "s_cmp_le_u32 %[tb], %[tc]\n"                                                                   \
+        "s_cbranch_scc1 48b\n"                                                                          \
+        "s_branch 41b\n"                                                                                \
+        "50:\n"                                                                                         \
+        : [cv] "=&v"(cv), [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [tl] "=&v"(tl), [j] "=&s"(j),  \
+          [sb] "=&s"(sb), [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64),         \
+          [w] "=&s"(w), [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [nd] "=&s"(nd), \
+          [m2] "=&s"(m2), [sx] "=&s"(sx), [t] "+s"(t), [b64] "+s"(b64)                                  \
+        : [cnt] "s"(cnt), [vsb] "v"(vsb), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
+          [Mp64] "s"(Mp64), [nr] "n"(NR)                                                                \
+        : "scc", "vcc", "s72", "s73", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
-    return acc;
-}
-
-// The same over rows rs..re with rs > 0 unknown at compile time (the rounds that entered the
-// window after t moved): short scalar loop through VGPR index mode.
-template <int NR>
-__device__ __forceinline__ int prof_check_from(int rs, int x64, int sb, int lane, int vmin)
-{
-    int acc, y, t0, t1, re;
-#define KVS_STMT(CLOB, ASC, DESC)                                                                 \
-    asm volatile("v_mov_b32 %[acc], %[vmin]\n"                                                    \
-                 "s_lshr_b32 %[re], %[x64], 6\n"                                                  \
-                 "s_sub_u32 %[re], %[re], 1\n"                                                    \
-                 "s_mov_b32 %[t1], %[rs]\n"                                                       \
-                 "s_cmp_ge_u32 %[t1], %[re]\n"                                                    \
-                 "s_cbranch_scc1 2f\n"                                                            \
-                 "1:\n"                                                                           \
-                 "s_set_gpr_idx_on %[t1], gpr_idx(SRC0)\n" KVS_IDX_WAIT                           \
-                 "v_mov_b32 %[y], v[" KVS_PB "]\n"                                                \
-                 "s_set_gpr_idx_off\n"                                                            \
-                 "s_lshl_b32 %[t0], %[t1], 6\n"                                                   \
-                 "v_add_u32 %[y], %[sb], %[y]\n"                                                  \
-                 "v_min_i32 %[y], %[t0], %[y]\n"                                                  \
-                 "v_max_i32 %[acc], %[acc], %[y]\n"                                               \
-                 "s_add_u32 %[t1], %[t1], 1\n"                                                    \
-                 "s_cmp_lt_u32 %[t1], %[re]\n"                                                    \
-                 "s_cbranch_scc1 1b\n"                                                            \
-                 "2:\n"                                                                           \
-                 "s_set_gpr_idx_on %[re], gpr_idx(SRC0)\n" KVS_IDX_WAIT                           \
-                 "v_mov_b32 %[y], v[" KVS_PB "]\n"                                                \
-                 "s_set_gpr_idx_off\n"                                                            \
-                 "s_lshl_b32 %[t0], %[re], 6\n"                                                   \
-                 "v_add_u32 %[y], %[sb], %[y]\n"                                                  \
-                 "v_min_i32 %[y], %[t0], %[y]\n"                                                  \
-                 "s_and_b32 %[t0], %[x64], 63\n"                                                  \
-                 "v_cmp_ge_u32 vcc, %[t0], %[lane]\n"                                             \
-                 "v_cndmask_b32 %[y], %[vmin], %[y], vcc\n"                                       \
-                 "v_max_i32 %[acc], %[acc], %[y]\n"                                               \
-                 : [acc] "=&v"(acc), [y] "=&v"(y), [t0] "=&s"(t0), [t1] "=&s"(t1), [re] "=&s"(re) \
-                 : [rs] "s"(rs), [x64] "s"(x64), [sb] "s"(sb), [lane] "v"(lane), [vmin] "v"(vmin) \
-                 : "scc", "vcc", CLOB)
-    KVS_FOR_NR(KVS_STMT);
-#undef KVS_STMT
-    return acc;
-}
-
-// Admit: rows 0..re get the request's ramp.  ramp = s + (tau - t) for the lane's round in row 0.
-// The chain of full rows runs downwards with a running ramp `e` (the ramp of the even row of
-// the current pair) that steps by -128 per pair; the lowest pair uses `ramp` itself.
-template <int NR>
-__device__ __forceinline__ void prof_update(int x64, int ramp, int lane)
-{
-    int y, e, t0;
-#define KVS_STMT(CLOB, ASC, DESC)                                                              \
-    asm volatile("s_and_b32 %[t0], %[x64], 63\n"                                               \
-                 "v_cmp_ge_u32 vcc, %[t0], %[lane]\n" KVS_DISPATCH                             \
-                 ".irp r," ASC "\n"                                                            \
-                 "7:\n"                                                                        \
-                 "  .if \\r == 0\n"                                                            \
-                 "    v_cndmask_b32 %[y], 0, %[ramp], vcc\n"                                   \
-                 "  .else\n"                                                                   \
-                 "    v_add_u32 %[y], 64*\\r, %[ramp]\n"                                       \
-                 "    v_cndmask_b32 %[y], 0, %[y], vcc\n"                                      \
-                 "  .endif\n"                                                                  \
-                 "  v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                    \
-                 "  .if \\r >= 3\n"                                                            \
-                 "    v_add_u32 %[e], 128*((\\r-1)/2), %[ramp]\n"                              \
-                 "  .endif\n"                                                                  \
-                 "  .if \\r == 0\n"                                                            \
-                 "    s_branch 8f\n"                                                           \
-                 "  .else\n"                                                                   \
-                 "    s_branch 30\\r\\()f\n"                                                   \
-                 "  .endif\n" KVS_SLOT_END                                                     \
-                 ".endr\n"                                                                     \
-                 ".irp r," DESC "\n"                                                           \
-                 "30\\r:\n"                                                                    \
-                 "  .if (\\r-1) >= 2\n"                                                        \
-                 "    .if ((\\r-1) & 1) == 1\n"                                                \
-                 "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[e], 64\n"       \
-                 "    .else\n"                                                                 \
-                 "      v_add_u32 v[" KVS_PB "+\\r-1], %[e], v[" KVS_PB "+\\r-1]\n"            \
-                 "      v_add_u32 %[e], 0xffffff80, %[e]\n"                                    \
-                 "    .endif\n"                                                                \
-                 "  .else\n"                                                                   \
-                 "    .if ((\\r-1) & 1) == 1\n"                                                \
-                 "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[ramp], 64\n"    \
-                 "    .else\n"                                                                 \
-                 "      v_add_u32 v[" KVS_PB "+\\r-1], %[ramp], v[" KVS_PB "+\\r-1]\n"         \
-                 "    .endif\n"                                                                \
-                 "  .endif\n"                                                                  \
-                 ".endr\n"                                                                     \
-                 "8:\n"                                                                        \
-                 : [y] "=&v"(y), [e] "=&v"(e), [t0] "=&s"(t0)                                  \
-                 : [x64] "s"(x64), [ramp] "v"(ramp), [lane] "v"(lane)                          \
-                 : "scc", "vcc", "s72", "s73", CLOB)
-    KVS_FOR_NR(KVS_STMT);
-#undef KVS_STMT
-}
-
-// Maximum over the 64 lanes (all active).  Four DPP steps give every lane of a 16-lane row the
-// row's maximum; two row broadcasts carry it to lane 63.  A DPP read of a register written by
-// the previous instruction needs two wait states.
-__device__ __forceinline__ int wave_max_dpp(int v)
-{
-    int out;
-    asm volatile("s_nop 1\n"
-                 "v_max_i32_dpp %[v], %[v], %[v] quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n"
-                 "s_nop 1\n"
-                 "v_max_i32_dpp %[v], %[v], %[v] quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n"
-                 "s_nop 1\n"
-                 "v_max_i32_dpp %[v], %[v], %[v] row_half_mirror row_mask:0xf bank_mask:0xf\n"
-                 "s_nop 1\n"
-                 "v_max_i32_dpp %[v], %[v], %[v] row_mirror row_mask:0xf bank_mask:0xf\n"
-                 "s_nop 1\n"
-                 "v_max_i32_dpp %[v], %[v], %[v] row_bcast:15 row_mask:0xa bank_mask:0xf\n"
-                 "s_nop 1\n"
-                 "v_max_i32_dpp %[v], %[v], %[v] row_bcast:31 row_mask:0xc bank_mask:0xf\n"
-                 "s_nop 1\n"
-                 "v_readlane_b32 %[out], %[v], 63\n"
-                 : [v] "+v"(v), [out] "=s"(out));
-    return out;
+    return cv;
 }
 
 // One int32 read through the scalar unit (the address is the same for the whole wavefront).
@@ -530,7 +565,6 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     } else {
         prof_init<NR>();
     }
-    int u64 = t - b64 + 64;  // x64 of a request is its decode length plus this
     const int vmin = INT_MIN;
 
     // 64 positions of the order at a time: ids read coalesced, lengths gathered; the next
@@ -567,34 +601,8 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             return;  // (snapshots not taken stay marked unusable, as the host left them)
         }
         const int cnt = min(WAVE, n - k0);
-        int cv = 0;  // completion round of position k0 + lane
-        for (int j = 0; j < cnt; ++j) {
-            const int sj = __builtin_amdgcn_readlane(sv, j);
-            const int oj = __builtin_amdgcn_readlane(ov, j);
-            const int sb = sj - M;
-            int x64 = oj + u64;  // (t + oj - b64) + 64: row and lane of the window's last round
-            int need = prof_check_from0<NR>(x64, sb, lane, vmin) + (lane + b64);  // least start the lane's rounds allow
-            while (__builtin_amdgcn_ballot_w64(need > t) != 0) {
-                t = wave_max_dpp(need);
-                const int lo = x64 + b64 - 63;  // first round not looked at yet
-                // keep register 0 on the row of round t + 1
-                const int b64n = (t + 1) & ~63;
-                int shift = (b64n - b64) >> 6;
-                b64 = b64n;
-                u64 = t - b64 + 64;
-                x64 = oj + u64;
-                if (shift >= NR) {
-                    prof_init<NR>();
-                } else {
-                    for (; shift > 0; --shift) prof_rotate1<NR>();
-                }
-                need = prof_check_from<NR>((lo - b64) >> 6, x64, sb, lane, vmin) + (lane + b64);
-            }
-            // admitted at round t: holds sj + a tokens at round t + a, i.e. sj - t + b64 + l in lane l of row 0
-            prof_update<NR>(x64, lane + (sj + 64 - u64), lane);
-            const int hi = t + oj;
-            cv = (lane == j) ? hi : cv;  // vector compare + select: the scalar unit is the scarce one
-        }
+        // the up to 64 requests of this block, one after the other; cv: completion round of position k0 + lane
+        const int cv = place_block<NR>(cnt, sv - M, ov, lane, vmin, M + 64, t, b64);
         tel_lane += cv;
         if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
