@@ -132,42 +132,39 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 #undef KVS_STMT
 }
 
-// Pads the slot that began at the last label 7 to 64 bytes (never executed: slots end in a branch).
-#define KVS_SLOT_END "  .fill (64-(.-7b))/4, 4, 0xbf800000\n"
-
 // ---------------------------------------------------------------------------------------------
 // Placing up to 64 consecutive requests of the order: ONE assembly statement.
 //
-// Lane j of vsb / vo holds s - M and o of the j-th request.  For each request in turn:
+// Lane j of vsb / vo holds s - M and o of the j-th request (j is kept in M0, the lane number of
+// v_readlane / v_writelane).  For each request in turn:
 //   check    rows 0..re of the profile (re = row of the window's last round t + o): per lane
 //            acc = max over rows of min(Q_r + (s - M), 64 r), the least admissible start that the
 //            lane's rounds impose, relative to the lane's round in row 0 (the last row is masked by
-//            value beyond round t + o: vcc);
+//            value beyond round t + o: the lanes of mk);
 //   blocked  iff acc > (t - b64) - lane in some lane.  Then t becomes the largest such bound
 //            (six DPP steps), the register file moves down so that row 0 holds round t + 1 again,
-//            and only the rounds that have entered the window since are looked at (rows rs..re,
-//            one computed jump per row: the row number is not known at compile time and VGPR
-//            index mode is avoided); repeat;
+//            and only the rounds that have entered the window since are looked at: nearly always
+//            the window's last row alone (one computed jump to a stub of that row), otherwise rows
+//            rs..re one by one (a computed jump per row: the row number is not known at compile
+//            time and VGPR index mode is avoided); repeat;
 //   admit    rows 0..re get the ramp s + (tau - t); the completion round t + o goes to lane j of cv.
-// A pass over rows 0..re is entered by one computed jump (s_getpc / s_setpc, 64-byte slots) to a
-// stub that handles the masked last row with constant register numbers and branches into a
+// A pass over rows 0..re is entered by one computed jump (table base + 64 (re + 1), s_setpc) to a
+// 64-byte stub that handles the masked last row with constant register numbers and branches into a
 // descending chain of full rows re-1..0, which runs to its end without a compare or a branch:
 // five vector instructions per two rows in the check, three in the update.
 //
+// Both the vector unit (one instruction per cycle and compute unit) and the scalar unit (the same,
+// shared by the four SIMDs) are close to saturated by this loop, so it is written to need few of
+// either: the window mask is one scalar shift, the table addresses are computed once per block.
+//
 // Wait states (gfx950 does not interlock these; the distances below are by construction):
-//   a VALU instruction that reads an SGPR or VCC written by a VALU instruction (v_readlane,
-//   v_cmp) needs two instructions in between: sb and vcc are read by vector instructions only
-//   behind the computed jump (at least five scalar instructions later); oj, nd and the DPP result
-//   are read by scalar instructions, which need none;
+//   a VALU instruction that reads an SGPR or VCC written by a VALU instruction (v_readlane, v_cmp)
+//   needs two instructions in between: sb is read by vector instructions only behind a computed
+//   jump (at least five scalar instructions later); oj, vcc and the DPP result are read by scalar
+//   instructions, which need none;
 //   DPP reads of a VGPR written by the previous VALU instruction, and v_readlane of one: s_nop 1.
 // EXEC is narrowed to the window's lanes for the one masked addition of the update and restored.
-// M0 carries the lane number for v_writelane (two different SGPR operands are not encodable); the
-// kernel has no other use of M0 (no LDS, no relative addressing).
-#define KVS_JUMP                  \
-    "s_getpc_b64 s[72:73]\n"      \
-    "s_add_u32 s72, s72, %[off]\n" \
-    "s_addc_u32 s73, s73, 0\n"    \
-    "s_setpc_b64 s[72:73]\n"
+// The kernel has no other use of M0 (no LDS, no relative addressing).
 
 // Maximum over the 64 lanes of %[y] into lane 63 (four DPP steps inside the 16-lane rows, two row
 // broadcasts), read into %[tc].
@@ -187,35 +184,51 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
     "s_nop 1\n"                                                                                 \
     "v_readlane_b32 %[tc], %[y], 63\n"
 
+// Pads the slot that began at the last label 7 to the given number of bytes (never executed: slots
+// end in a branch).
+#define KVS_SLOT_PAD(bytes) "  .fill (" #bytes "-(.-7b))/4, 4, 0xbf800000\n"
+
 template <int NR>
 __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, int vmin, int Mp64, int &t, int &b64)
 {
     int cv, acc, y, z, tl;
-    int j, sb, oj, x64, off, u64, w, rs, ta, tb, tc;
-    long long nd, m2, sx;
+    int sb, oj, x64, off, u64, w, rs, ta, tb, tc, cl, ch, ul, uh, rl, rh;
+    long long mk, m2, sx;
 #define KVS_STMT(CLOB, ASC, DESC)                                                                       \
     asm volatile(                                                                                       \
         "s_mov_b64 %[sx], exec\n"                                                                       \
+        /* table addresses: slot of row r at base + 64 (r + 1) for the check and update stubs, */      \
+        /* at base + 32 r for the stubs of a single row */                                              \
+        "s_getpc_b64 s[72:73]\n"                                                                        \
+        "60:\n"                                                                                         \
+        "s_add_u32 %[cl], s72, 61f-60b-64\n"                                                            \
+        "s_addc_u32 %[ch], s73, 0\n"                                                                    \
+        "s_add_u32 %[ul], s72, 62f-60b-64\n"                                                            \
+        "s_addc_u32 %[uh], s73, 0\n"                                                                    \
+        "s_add_u32 %[rl], s72, 63f-60b\n"                                                               \
+        "s_addc_u32 %[rh], s73, 0\n"                                                                    \
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n" /* (t - b64) - lane */                                     \
         "s_add_u32 %[u64], %[u64], 64\n"     /* x64 of a request is its decode length plus this */      \
         "s_sub_u32 %[w], %[Mp64], %[u64]\n"  /* ramp of a request in lane l of row 0: (s - M) + w + l */ \
         "v_mov_b32 %[cv], 0\n"                                                                          \
-        "s_mov_b32 %[j], 0\n"                                                                           \
+        "s_mov_b32 m0, 0\n"                                                                             \
         /* ---- next request */                                                                         \
         "40:\n"                                                                                         \
-        "v_readlane_b32 %[sb], %[vsb], %[j]\n"                                                          \
-        "v_readlane_b32 %[oj], %[vo], %[j]\n"                                                           \
+        "v_readlane_b32 %[sb], %[vsb], m0\n"                                                            \
+        "v_readlane_b32 %[oj], %[vo], m0\n"                                                             \
         "s_add_u32 %[x64], %[oj], %[u64]\n" /* (t + o - b64) + 64: row and lane of the window's last round */ \
-        "s_and_b32 %[ta], %[x64], 63\n"                                                                 \
-        "v_cmp_ge_u32 vcc, %[ta], %[lane]\n"                                                            \
-        "s_andn2_b32 %[off], %[x64], 63\n" /* 64 (re + 1): the slots start 64 bytes behind s_getpc's successor */ \
-        KVS_JUMP ".fill 13, 4, 0xbf800000\n"                                                            \
+        "s_lshl_b64 %[mk], -2, %[x64]\n"    /* the lanes behind it (the shift uses x64 mod 64) */       \
+        "s_andn2_b32 %[off], %[x64], 63\n"  /* 64 (re + 1) */                                           \
+        "s_add_u32 s72, %[cl], %[off]\n"                                                                \
+        "s_addc_u32 s73, %[ch], 0\n"                                                                    \
+        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "61:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
         "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
-        "  v_cndmask_b32 %[acc], %[vmin], %[y], vcc\n"                                                  \
+        "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
         "  .if \\r == 0\n"                                                                              \
         "    s_branch 41f\n"                                                                            \
         "  .else\n"                                                                                     \
@@ -223,7 +236,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "      v_mov_b32 %[z], %[acc]\n"                                                                \
         "    .endif\n"                                                                                  \
         "    s_branch 20\\r\\()f\n"                                                                     \
-        "  .endif\n" KVS_SLOT_END                                                                       \
+        "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
         ".endr\n"                                                                                       \
         ".irp r," DESC "\n"                                                                             \
         "20\\r:\n"                                                                                      \
@@ -238,24 +251,26 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         ".endr\n"                                                                                       \
         /* ---- does some round ask for a later start? */                                               \
         "41:\n"                                                                                         \
-        "v_cmp_gt_i32_e64 %[nd], %[acc], %[tl]\n"                                                       \
-        "s_cmp_lg_u64 %[nd], 0\n"                                                                       \
-        "s_cbranch_scc1 44f\n"                                                                          \
+        "v_cmp_gt_i32 vcc, %[acc], %[tl]\n"                                                             \
+        "s_cbranch_vccnz 44f\n"                                                                         \
         /* ---- admit at round t */                                                                     \
         "s_add_u32 %[rs], %[sb], %[w]\n"                                                                \
-        KVS_JUMP ".fill 13, 4, 0xbf800000\n"                                                            \
+        "s_add_u32 s72, %[ul], %[off]\n"                                                                \
+        "s_addc_u32 s73, %[uh], 0\n"                                                                    \
+        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "62:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
         "  .if \\r == 0\n"                                                                              \
         "    v_add_u32 %[y], %[rs], %[lane]\n"                                                          \
-        "    s_mov_b64 exec, vcc\n"                                                                     \
+        "    s_andn2_b64 exec, %[sx], %[mk]\n"                                                          \
         "    v_add_u32 v[" KVS_PB "], %[y], v[" KVS_PB "]\n"                                            \
         "    s_mov_b64 exec, %[sx]\n"                                                                   \
         "    s_branch 43f\n"                                                                            \
         "  .else\n"                                                                                     \
         "    s_add_u32 %[ta], %[rs], 64*\\r\n"                                                          \
         "    v_add_u32 %[y], %[ta], %[lane]\n"                                                          \
-        "    s_mov_b64 exec, vcc\n"                                                                     \
+        "    s_andn2_b64 exec, %[sx], %[mk]\n"                                                          \
         "    v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                    \
         "    s_mov_b64 exec, %[sx]\n"                                                                   \
         /*   z: ramp of the even row of the pair that holds row r - 1 */                                \
@@ -265,7 +280,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "      v_add_u32 %[z], 0xffffff80, %[y]\n"                                                      \
         "    .endif\n"                                                                                  \
         "    s_branch 30\\r\\()f\n"                                                                     \
-        "  .endif\n" KVS_SLOT_END                                                                       \
+        "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
         ".endr\n"                                                                                       \
         ".irp r," DESC "\n"                                                                             \
         "30\\r:\n"                                                                                      \
@@ -280,42 +295,38 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         ".endr\n"                                                                                       \
         "43:\n"                                                                                         \
         "s_add_u32 %[ta], %[t], %[oj]\n"                                                                \
-        "s_mov_b32 m0, %[j]\n"                                                                          \
-        "s_nop 0\n"                                                                                     \
         "v_writelane_b32 %[cv], %[ta], m0\n"                                                            \
-        "s_add_u32 %[j], %[j], 1\n"                                                                     \
-        "s_cmp_lt_u32 %[j], %[cnt]\n"                                                                   \
+        "s_add_u32 m0, m0, 1\n"                                                                         \
+        "s_cmp_lt_u32 m0, %[cnt]\n"                                                                     \
         "s_cbranch_scc1 40b\n"                                                                          \
         "s_branch 50f\n"                                                                                \
         /* ---- blocked: move t to the largest bound, the register file with it, look at what is new */ \
         "44:\n"                                                                                         \
         "v_add_u32 %[y], %[acc], %[lane]\n"                                                             \
         KVS_WAVE_MAX                                                                                    \
-        "s_add_u32 %[tb], %[x64], %[b64]\n"                                                             \
-        "s_sub_u32 %[tb], %[tb], 63\n"       /* first round not looked at yet */                        \
+        "s_sub_u32 %[tb], %[x64], 63\n"                                                                 \
+        "s_lshr_b32 %[tb], %[tb], 6\n"       /* row of the first round not looked at yet */             \
         "s_add_u32 %[t], %[tc], %[b64]\n"                                                               \
         "s_add_u32 %[tc], %[t], 1\n"                                                                    \
         "s_andn2_b32 %[tc], %[tc], 63\n"     /* row 0 starts at 64 floor((t + 1) / 64) */               \
         "s_sub_u32 %[rs], %[tc], %[b64]\n"                                                              \
         "s_lshr_b32 %[rs], %[rs], 6\n"       /* rows to move down */                                    \
         "s_mov_b32 %[b64], %[tc]\n"                                                                     \
+        "s_sub_u32 %[tb], %[tb], %[rs]\n"    /* ... in the moved file */                                \
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n"                                                            \
         "s_add_u32 %[u64], %[u64], 64\n"                                                                \
         "s_sub_u32 %[w], %[Mp64], %[u64]\n"                                                             \
         "s_add_u32 %[x64], %[oj], %[u64]\n"                                                             \
+        "s_lshl_b64 %[mk], -2, %[x64]\n"                                                                \
         "s_andn2_b32 %[off], %[x64], 63\n"                                                              \
-        "s_and_b32 %[ta], %[x64], 63\n"                                                                 \
-        "v_cmp_ge_u32 vcc, %[ta], %[lane]\n"                                                            \
-        "s_sub_u32 %[tb], %[tb], %[b64]\n"                                                              \
-        "s_lshr_b32 %[tb], %[tb], 6\n"       /* its row */                                              \
         "s_lshr_b32 %[tc], %[x64], 6\n"                                                                 \
         "s_sub_u32 %[tc], %[tc], 1\n"        /* last row of the window */                               \
+        "s_cmp_eq_u32 %[rs], 0\n"                                                                       \
+        "s_cbranch_scc1 46f\n"                                                                          \
         "s_cmp_ge_u32 %[rs], %c[nr]\n"                                                                  \
         "s_cbranch_scc1 47f\n"                                                                          \
         "45:\n"                                                                                         \
-        "s_cmp_eq_u32 %[rs], 0\n"                                                                       \
-        "s_cbranch_scc1 46f\n"                                                                          \
         ".set kvs_r, 0\n"                                                                               \
         ".rept %c[nr]-1\n"                                                                              \
         "  v_subrev_u32 v[" KVS_PB "+kvs_r], 64, v[" KVS_PB "+kvs_r+1]\n"                               \
@@ -323,7 +334,9 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         ".endr\n"                                                                                       \
         "v_mov_b32 v[" KVS_PB "+%c[nr]-1], 64*(%c[nr]-1)\n"                                             \
         "s_sub_u32 %[rs], %[rs], 1\n"                                                                   \
-        "s_branch 45b\n"                                                                                \
+        "s_cmp_lg_u32 %[rs], 0\n"                                                                       \
+        "s_cbranch_scc1 45b\n"                                                                          \
+        "s_branch 46f\n"                                                                                \
         "47:\n"                                                                                         \
         ".set kvs_r, 0\n"                                                                               \
         ".rept %c[nr]\n"                                                                                \
@@ -331,10 +344,27 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "  .set kvs_r, kvs_r+1\n"                                                                       \
         ".endr\n"                                                                                       \
         "46:\n"                                                                                         \
-        "v_mov_b32 %[acc], %[vmin]\n"                                                                   \
+        "s_cmp_lt_u32 %[tb], %[tc]\n"                                                                   \
+        "s_cbranch_scc1 48f\n"                                                                          \
+        /* only the window's last row is new */                                                         \
+        "s_lshl_b32 %[ta], %[tc], 5\n"                                                                  \
+        "s_add_u32 s72, %[rl], %[ta]\n"                                                                 \
+        "s_addc_u32 s73, %[rh], 0\n"                                                                    \
+        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "63:\n"                                                                                         \
+        ".irp r," ASC "\n"                                                                              \
+        "7:\n"                                                                                          \
+        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
+        "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
+        "  s_branch 41b\n" KVS_SLOT_PAD(32)                                                             \
+        ".endr\n"                                                                                       \
+        /* rows tb..tc, the last of them masked */                                                      \
         "48:\n"                                                                                         \
+        "v_mov_b32 %[acc], %[vmin]\n"                                                                   \
+        "51:\n"                                                                                         \
         "s_cmp_eq_u32 %[tb], %[tc]\n"                                                                   \
-        "s_cselect_b64 %[m2], vcc, -1\n"     /* only the window's last row is masked */                 \
+        "s_cselect_b64 %[m2], %[mk], 0\n"                                                               \
         "s_add_u32 %[ta], %[tb], 1\n"                                                                   \
         "s_lshl_b32 %[ta], %[ta], 4\n"       /* 16-byte slots, the first 16 bytes behind s_getpc's successor */ \
         "s_getpc_b64 s[72:73]\n"                                                                        \
@@ -346,21 +376,21 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "7:\n"                                                                                          \
         "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
-        "  s_branch 49f\n"                                                                              \
-        "  .fill (16-(.-7b))/4, 4, 0xbf800000\n"                                                        \
+        "  s_branch 49f\n" KVS_SLOT_PAD(16)                                                             \
         ".endr\n"                                                                                       \
         "49:\n"                                                                                         \
-        "v_cndmask_b32_e64 %[y], %[vmin], %[y], %[m2]\n"                                                \
+        "v_cndmask_b32_e64 %[y], %[y], %[vmin], %[m2]\n"                                                \
         "v_max_i32 %[acc], %[acc], %[y]\n"                                                              \
         "s_add_u32 %[tb], %[tb], 1\n"                                                                   \
         "s_cmp_le_u32 %[tb], %[tc]\n"                                                                   \
-        "s_cbranch_scc1 48b\n"                                                                          \
+        "s_cbranch_scc1 51b\n"                                                                          \
         "s_branch 41b\n"                                                                                \
         "50:\n"                                                                                         \
-        : [cv] "=&v"(cv), [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [tl] "=&v"(tl), [j] "=&s"(j),  \
-          [sb] "=&s"(sb), [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64),         \
-          [w] "=&s"(w), [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [nd] "=&s"(nd), \
-          [m2] "=&s"(m2), [sx] "=&s"(sx), [t] "+s"(t), [b64] "+s"(b64)                                  \
+        : [cv] "=&v"(cv), [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [tl] "=&v"(tl), [sb] "=&s"(sb), \
+          [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64), [w] "=&s"(w),           \
+          [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [cl] "=&s"(cl), [ch] "=&s"(ch), \
+          [ul] "=&s"(ul), [uh] "=&s"(uh), [rl] "=&s"(rl), [rh] "=&s"(rh), [mk] "=&s"(mk), [m2] "=&s"(m2), \
+          [sx] "=&s"(sx), [t] "+s"(t), [b64] "+s"(b64)                                                  \
         : [cnt] "s"(cnt), [vsb] "v"(vsb), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
           [Mp64] "s"(Mp64), [nr] "n"(NR)                                                                \
         : "scc", "vcc", "s72", "s73", CLOB)
