@@ -2,15 +2,19 @@
 """Benchmark of the schedule-evaluation hot path on one MI355X.
 
 One step = one pass of the whole path over one batch of synthetic input, everything already
-resident in HBM: Sorted-F order construction (Phase 1), evaluation of the C candidate orders
-(Phase 2: timelines, total latency and completion rounds per candidate), argmin over the
-candidates.  Workload: configuration 3 ("mixed chat + summarisation": n = 2000 requests,
-M = 131072 tokens, C = 16384 candidates = Sorted-F order, 16127 distinct 1-swap neighbours,
-256 random restarts).
+resident in HBM: Sorted-F order construction (Phase 1), evaluation of the candidate orders (Phase 2:
+timelines, total latency and completion rounds per candidate), argmin over the candidates.
 
-Prints ONE JSON line:  candidate schedules evaluated per second, the roofline object of the
-dominant kernel (integer-VALU bound; algorithmic lane-ops from the outputs of the run) and the
-CPU oracle timed on the same rows on this host.
+Default workload: configuration 3 ("mixed chat + summarisation": n = 2000 requests, M = 131072
+tokens, C = 16384 candidates = Sorted-F order, 16127 distinct 1-swap neighbours, 256 random
+restarts).  --workload config1 | config2 | config5 run the same step on those configurations,
+--workload config4 the receding-horizon run (one step = all re-plans of 65536 moves each until every
+position is committed).
+
+Prints ONE JSON line: candidate schedules evaluated per second, request-rounds per second, the
+roofline object of the dominant kernel (integer-VALU bound; algorithmic lane-ops counted from the
+outputs of the run, kernel time from HIP events on the kernel's stream) and the CPU oracle timed on
+a sample of the same candidates on this host, on one thread and on all cores.
 """
 from __future__ import annotations
 
@@ -19,6 +23,7 @@ import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -30,42 +35,134 @@ if ROOT not in sys.path:
 # lane per clock (the fp32 vector peak of 157.3 TFLOP/s counts an FMA as two and packs two).
 PEAK_INT32_LANE_OPS = 256 * 4 * 16 * 2.4e9
 PEAK_HBM_BYTES = 8.0e12
-OPS_PER_VISIT = 6  # int32 lane-ops to inspect or update one future round for one request
+# Lane-ops the exact algorithm needs per slot visit (one future round inspected or updated for one
+# request) on a dense profile: the check of two rows (128 visits) is add, min, add, min and one
+# three-way max = 5 wave instructions, the update of two rows is two adds and one step of the shared
+# ramp = 3; (5 + 3) x 64 lanes / 256 visits = 2.  Everything else the kernel issues (masked last
+# rows, dead lanes of partial rows, per-request bookkeeping, moving the register file) is overhead
+# and is not credited, so the fraction below cannot exceed the share of issue slots the kernel uses.
+OPS_PER_VISIT = 2
 CFG = 3
 
-# HBM traffic of the dominant kernel per launch (one per step) on this workload, from rocprofv3
-# counters (profiles/timeline_kernel_config3_traffic.md): FETCH_SIZE 46963 KiB x 1.9997 (what a
-# plain 256 MiB copy reads per KiB moved) + WRITE_SIZE 89485 KiB x 1.0.  Valid only for the kernel
-# sources it was measured on; reported as null once they change.
-TRAFFIC_BYTES = int((46963 * 1.9997 + 89485 * 1.0) * 1024)
-TRAFFIC_SOURCES = ("timeline_reg.hip", "device_util.h")
-TRAFFIC_SOURCES_SHA256 = "35d75c7b25cb13ed"
+# What rocprofv3 counters measured for the dominant kernel of a workload (summaries and commands in
+# profiles/): HBM bytes per launch (FETCH_SIZE, WRITE_SIZE scaled by what a plain 256 MiB copy reads
+# on the same counters), share of the vector / scalar issue slots in use, vector lane-slots issued
+# per credited visit.  Valid only for the kernel sources they were taken on (hash below); reported as
+# null once those change.
+PROFILED = {
+}
+PROFILED_SOURCES = ("timeline_reg.hip", "device_util.h")
+PROFILED_SOURCES_SHA256 = ""
 
 
-# Issue slots the same kernel really used on this workload (profiles/timeline_kernel_config3_counters.md):
-# SQ_INSTS_VALU 1.185e9 x 4 cycles / (1024 SIMDs x 4.94e6 cycles) and (SQ_INSTS_SALU 8.763e8 +
-# SQ_INSTS_BRANCH 2.252e8) / (256 scalar units x 4.94e6 cycles), cycles from GRBM_GUI_ACTIVE / 8 XCDs.
-# The accounting above credits 6 lane-ops per visit where the kernel issues 4.9, so the physical
-# utilisation is this, not roofline.frac.
-ISSUE_SLOTS = {"valu": 0.937, "scalar_and_branch": 0.871}
-
-
-def _kernel_sources_unchanged() -> bool:
+def _kernel_sources_hash() -> str:
     import hashlib
 
     h = hashlib.sha256()
-    for f in TRAFFIC_SOURCES:
+    for f in PROFILED_SOURCES:
         with open(os.path.join(ROOT, "paper_2508_06133_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
-    return h.hexdigest()[:16] == TRAFFIC_SOURCES_SHA256
+    return h.hexdigest()[:16]
 
 
-def measured_traffic():
-    return TRAFFIC_BYTES if _kernel_sources_unchanged() else None
+def profiled(workload: str):
+    """(traffic bytes per launch, issue figures) from the committed counter summaries, or (None, None)."""
+    rec = PROFILED.get(workload)
+    if rec is None or _kernel_sources_hash() != PROFILED_SOURCES_SHA256:
+        return None, None
+    return rec.get("traffic_bytes"), rec.get("issue")
 
 
-def measured_issue_slots():
-    return ISSUE_SLOTS if _kernel_sources_unchanged() else None
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def host_threads() -> int:
+    return max(1, min(16, os.cpu_count() or 1))  # a one-GPU box's share of the host is 16 cores
+
+
+def cpu_baseline_rows(inst, make_rows, C: int, tel_gpu, what: str):
+    """The oracle (oracle_simulate_profile, as it stands) on a bounded sample of the candidates:
+    one thread, then every host thread at once (one ordinary single-threaded call per chunk of rows;
+    ctypes releases the interpreter lock).  make_rows(lo, hi) -> order rows [hi - lo, n] of candidates
+    lo..hi-1.  Returns the cpu_baseline object, or None when GPU and oracle disagree."""
+    import oracle  # test infrastructure; only this baseline leg uses it
+
+    def run(rows):
+        return oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False, completions=True)[0]
+
+    t0 = time.perf_counter()
+    probe = run(make_rows(0, min(2, C)))
+    per_row = max((time.perf_counter() - t0) / min(2, C), 1e-6)
+    if not (probe == tel_gpu[: len(probe)]).all():
+        return None
+    threads = host_threads()
+    n1 = int(min(C, max(2, 6.0 / per_row)))
+    rows1 = make_rows(0, n1)
+    t0 = time.perf_counter()
+    tel1 = run(rows1)
+    s1 = time.perf_counter() - t0
+    if not (tel1 == tel_gpu[:n1]).all():
+        return None
+    nA = int(min(C, max(threads, 6.0 * threads / per_row)))
+    rowsA = rows1 if nA == n1 else make_rows(0, nA)
+    chunk = max(1, min(64, -(-nA // (4 * threads))))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        parts = list(pool.map(lambda lo: run(rowsA[lo:lo + chunk]), range(0, nA, chunk)))
+    sA = time.perf_counter() - t0
+    if not (np.concatenate(parts) == tel_gpu[:nA]).all():
+        return None
+    return {
+        "value": nA / sA,
+        "unit": "candidates/s",
+        "cores": threads,
+        "kind": "oracle",
+        "cpu_model": cpu_model(),
+        "host_cores": os.cpu_count(),
+        "single_thread": {"value": n1 / s1, "unit": "candidates/s", "cores": 1, "sample_rows": n1, "seconds": round(s1, 2)},
+        "sample": f"first {nA} of the {C} {what} on {threads} threads ({sA:.1f} s), first {n1} on one thread "
+                  f"({s1:.1f} s); array-profile oracle (oracle_simulate_profile), plain C, one row after the other per thread",
+    }
+
+
+def roofline_object(kernel: str, visits: int, kernel_ms_total: float, launches: int, workload: str, hbm_bytes: int,
+                    extra: dict | None = None):
+    """Integer-VALU roofline of the timeline kernel: credited lane-ops = OPS_PER_VISIT x visits."""
+    secs = kernel_ms_total * 1e-3
+    achieved = OPS_PER_VISIT * visits / secs
+    traffic, issue = profiled(workload)
+    obj = {
+        "bound": "alu",
+        "kernel": kernel,
+        "launches": launches,
+        "avg_launch_ms": kernel_ms_total / launches,
+        "achieved": achieved / 1e12,
+        "peak": PEAK_INT32_LANE_OPS / 1e12,
+        "unit": "Tlane-op/s (int32)",
+        "frac": achieved / PEAK_INT32_LANE_OPS,
+        "traffic": traffic,
+        "visits": visits,
+        "ops_per_visit": OPS_PER_VISIT,
+        "issue_measured": issue,
+        "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / secs / 1e9,
+                "frac_of_8TBps": hbm_bytes / secs / PEAK_HBM_BYTES},
+    }
+    if extra:
+        obj.update(extra)
+    return obj
+
+
+def reg_rows(o_max: int) -> int:
+    rows = (o_max + 63) // 64 + 1
+    return 9 if rows <= 9 else 33 if rows <= 33 else 65
 
 
 def bench_online(args, ctx, dev) -> int:
@@ -309,17 +406,274 @@ def bench_predicted(args, ctx, dev) -> int:
     return 0
 
 
+def bench_rows(args, ctx, dev, cfg: int) -> int:
+    """Configurations 1, 2, 3, 5: one step = Sorted-F order (sorted-prefix scoring, or Local Swap
+    Search with --phase1 local_swap) + timelines of all candidate rows + argmin."""
+    import torch
+
+    from paper_2508_06133_amd import workloads
+
+    inst = workloads.instance(cfg)
+    n, M = inst.n, inst.M
+    s = torch.from_numpy(inst.s).to(dev)
+    o = torch.from_numpy(inst.o).to(dev)
+
+    # The candidate set is built around the Sorted-F order; that order comes from the library.
+    order_d, ends_d, F_d, nb_d = ctx.sortedF(s, o, M)
+    torch.cuda.synchronize()
+    base = order_d.cpu().numpy()
+    rows_h = workloads.candidates(cfg, base)
+    C = rows_h.shape[0]
+    orders = torch.from_numpy(rows_h).to(dev)
+    tel = torch.empty(C, dtype=torch.int64, device=dev)
+    comp = torch.empty((C, n), dtype=torch.int32, device=dev)
+    best = torch.empty(2, dtype=torch.int64, device=dev)
+
+    p1_out = (order_d, ends_d, F_d, nb_d)  # Phase 1 writes into the same tensors every step
+    o_max = int(inst.o.max())
+    ctx.set_o_max(o_max)  # the caller's bound on decode lengths: no read-back inside the step
+    ctx.enable_timing(True)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        if args.phase1 == "local_swap":
+            ctx.local_swap(s, o, M)
+        else:
+            ctx.sortedF(s, o, M, out=p1_out)
+        ctx.simulate(orders, s, o, M, tel_out=tel, completion_out=comp)
+        ctx.argmin(tel, result_out=best)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    kernel_ms = []
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+        kernel_ms.append(ctx.last_timeline_ms())  # events on the stream the kernel ran on
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    status = ctx.device_status()
+    if status != 0:
+        print(f"bench.py: device status {status}", file=sys.stderr)
+        return 1
+
+    if args.calibrate_copy:  # 2^26 int32 = 256 MiB read + 256 MiB written by one elementwise kernel
+        src = torch.arange(1 << 26, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # ---- accounting from the outputs of the run (outside the timed region)
+    tel_h = tel.cpu().numpy()
+    o64 = o.to(torch.int64)
+    sum_o = int(o64.sum().item())
+    last_req = orders[:, -1].to(torch.int64)
+    p_last = comp.gather(1, last_req[:, None]).squeeze(1).to(torch.int64) - o64[last_req]
+    # Rows that share leading positions with row 0 start from row 0's saved state; only what
+    # they place themselves is counted: rounds waited through since the resume point + window
+    # checked + window updated for the positions from there on.
+    resume = ctx.simulate_resume_positions(C).to(torch.int64)
+    order0 = orders[0].to(torch.int64)
+    o_row0 = o64[order0]
+    start0 = comp[0].to(torch.int64)[order0] - o_row0  # start rounds of row 0 by position
+    cum0 = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev), torch.cumsum(o_row0, 0)])
+    t_res = torch.where(resume > 0, start0[(resume - 1).clamp(min=0)], torch.zeros_like(resume))
+    visits = int(((p_last - t_res) + 2 * (sum_o - cum0[resume])).sum().item())
+    visits_from_scratch = int((p_last + 2 * sum_o).sum().item())
+    resumed_rows = int((resume > 0).sum().item())
+    hbm_bytes = int((8 * (n - resume) + 8).sum().item()) + 8 * n  # order entries read, completion rounds written, from the resume point on
+    kernel = f"timeline_reg_kernel<{reg_rows(o_max)},4,false,{'true,true' if resumed_rows else 'false,false'}>"
+    names = {1: "config 1: tiny exact, n=8, M=48, all 8! orders + the Sorted-F order",
+             2: "config 2: short conversation, n=200, M=16384, Sorted-F order + 4095 random pairwise swaps",
+             3: "config 3: mixed chat+summarization, n=2000, M=131072, C=16384 "
+                "(Sorted-F order + 16127 1-swap neighbours + 256 random restarts)",
+             5: "config 5: adversarial bimodal, n=100000, M=2097152, Sorted-F order (prefix scoring of every batch) "
+                "+ 1024 rows of 64 random swaps"}
+    result = {
+        "metric": "candidate schedules evaluated/s (n=2000 mixed)" if cfg == 3
+                  else f"candidate schedules evaluated/s (config {cfg}, n={n})",
+        "value": C * args.steps / wall,
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": names[cfg], "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item()),
+                   "phase1": args.phase1},
+        "request_rounds_per_s": C * sum_o * args.steps / wall,
+        "gpu_ms_per_step": gpu_ms / args.steps,
+        "timeline_kernel_ms": float(np.mean(kernel_ms)),
+        "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
+        "roofline": roofline_object(kernel, visits * args.steps, float(np.sum(kernel_ms)), args.steps, f"config{cfg}",
+                                    hbm_bytes * args.steps,
+                                    {"resumed_rows": resumed_rows, "visits_without_resume": visits_from_scratch}),
+    }
+    if not args.no_cpu_baseline:
+        base_line = cpu_baseline_rows(inst, lambda lo, hi: rows_h[lo:hi], C, tel_h, "candidate rows")
+        if base_line is None:
+            print("bench.py: GPU and oracle disagree on the sampled rows", file=sys.stderr)
+            return 1
+        result["cpu_baseline"] = base_line
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
+def bench_horizon(args, ctx, dev) -> int:
+    """Configuration 4: one step = the whole receding-horizon run (n = 10000, windows of 512 positions,
+    65536 swap / insert moves per window, a new plan after every 256 completions, every timeline run
+    to completion), through kvsched_horizon_step; the host loop draws each window's moves and reads
+    48 bytes back per re-plan."""
+    import torch
+
+    from paper_2508_06133_amd import horizon, workloads
+
+    inst = workloads.instance(4)
+    n, M = inst.n, inst.M
+    window, every, K = 512, 256, 65536
+    s = torch.from_numpy(inst.s).to(dev)
+    o = torch.from_numpy(inst.o).to(dev)
+    order_d, _, _, nb_d = ctx.sortedF(s, o, M)
+    torch.cuda.synchronize()
+    o_max = int(inst.o.max())
+    ctx.enable_timing(True)
+
+    class Timed:  # the context, recording the candidates' launch time of every re-plan
+        def __init__(self):
+            self.ms = []
+
+        def horizon_step(self, *a, **kw):
+            out = ctx.horizon_step(*a, **kw)
+            self.ms.append(ctx.last_timeline_ms())
+            return out
+
+    p1_out = ctx.sortedF(s, o, M)
+
+    def run(keep_tel=False, max_steps=None, timed=None, keep_completion=False):
+        ctx.sortedF(s, o, M, out=p1_out)  # Phase 1 is part of the step (the order itself is order_d, computed above)
+        return horizon.receding_horizon(timed or ctx, s, o, M, order_d, window, every, K, rng=np.random.default_rng(4),
+                                        keep_tel=keep_tel, max_steps=max_steps, keep_completion=keep_completion)
+
+    for _ in range(min(args.warmup, 1)):
+        run()
+    torch.cuda.synchronize()
+    timed = Timed()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        order_g, comp_g, log = run(timed=timed)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    _, _, log = run(keep_completion=True)  # the same run once more, untimed, keeping every chosen timeline for the accounts
+    status = ctx.device_status()
+    if status != 0:
+        print(f"bench.py: device status {status}", file=sys.stderr)
+        return 1
+    replans = len(log)
+    timelines = replans * (K + 2)  # the moves, the order as it stands, the chosen order again for its completion rounds
+
+    # ---- accounting (outside the timed region).  Every candidate of a window repeats the order up to
+    # the first position a move touches: the library places that prefix once (windows behind position 64)
+    # or starts each move from the state saved at its 64-position block (first window).  Credited per
+    # candidate: rounds waited through from its start point on + windows checked and updated for the
+    # positions from there on, with the start rounds of the chosen timeline of that re-plan standing in
+    # for the candidates' own (they differ inside the window only; 2 sum(o) dominates).
+    o_h = inst.o.astype(np.int64)
+    rng = np.random.default_rng(4)
+    order = order_d.cpu().numpy()
+    visits = 0
+    hbm_bytes = 0
+    for rec in log:
+        moves = workloads.window_moves(rng, K, rec["lo"], rec["hi"])
+        touched = np.minimum(moves[:, 1], moves[:, 2])
+        ident = moves[:, 1] == moves[:, 2]
+        order = workloads.apply_move(order, moves[rec["best"]])
+        start = (rec["completion"].astype(np.int64) - o_h)[order]  # start rounds of the chosen order, by position
+        cum = np.concatenate([[0], np.cumsum(o_h[order])])
+        lowest = int(touched[~ident].min()) if (~ident).any() else n
+        if lowest >= 64:  # common prefix placed once, every candidate starts behind it
+            first = np.full(K + 1, lowest, dtype=np.int64)
+            visits += int(start[lowest - 1] + 2 * cum[lowest])  # the prefix itself
+        else:  # from the saved state of the move's block (identity moves: of the last block)
+            first = np.where(ident, (n - 1) // 64 * 64, touched // 64 * 64).astype(np.int64)
+            first = np.concatenate([first, [0]])  # the order as it stands runs from the start and saves the states
+        t_first = np.where(first > 0, start[np.maximum(first - 1, 0)], 0)
+        visits += int(((start[-1] - t_first) + 2 * (cum[n] - cum[first])).sum())
+        visits += int(start[-1] + 2 * cum[n])  # the chosen order once more
+        hbm_bytes += 12 * K + 8 * (K + 1) + 12 * n
+    kernel_ms_total = float(np.sum(timed.ms))
+    launches = len(timed.ms)
+    sum_o = int(o_h.sum())
+    result = {
+        "metric": "candidate schedules evaluated/s (config 4, receding horizon, n=10000)",
+        "value": timelines * args.steps / wall,
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": min(args.warmup, 1),
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "config 4: receding horizon, n=10000 (config-3 mixture), M=1048576, windows of 512 positions "
+                               "re-planned every 256 completions, 65536 swap/insert moves per window, every timeline to completion",
+                   "n": n, "M": M, "moves_per_window": K, "replans_per_step": replans, "sortedF_batches": int(nb_d.item())},
+        "request_rounds_per_s": timelines * sum_o * args.steps / wall,
+        "ms_per_replan": wall * 1e3 / args.steps / replans,
+        "candidate_launch_ms_per_replan": kernel_ms_total / launches,
+        "final_tel": int(log[-1]["best_tel"]), "start_tel": int(log[0]["base_tel"]),
+        "roofline": roofline_object(f"timeline_reg_kernel<{reg_rows(o_max)},4,true,...> (the candidates' launch of each re-plan)",
+                                    visits * args.steps, kernel_ms_total, launches, "config4", hbm_bytes * args.steps,
+                                    {"note": "visits credited from each candidate's start point (common prefix or saved "
+                                             "state of its block) on; the chosen timeline's start rounds stand in for the "
+                                             "candidates' own"}),
+    }
+    if not args.no_cpu_baseline:
+        # the first window's candidates through the oracle
+        _, _, log1 = run(keep_tel=True, max_steps=1)
+        torch.cuda.synchronize()
+        base = order_d.cpu().numpy()
+        moves = workloads.window_moves(np.random.default_rng(4), K, 0, min(n, window))
+        base_line = cpu_baseline_rows(inst, lambda lo, hi: workloads.orders_from_moves(base, moves[lo:hi]), K, log1[0]["tel"],
+                                      "moves of the first window")
+        if base_line is None:
+            print("bench.py: GPU and oracle disagree on the sampled moves", file=sys.stderr)
+            return 1
+        result["cpu_baseline"] = base_line
+    print(json.dumps(result))
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--cpu-rows", type=int, default=16384, help="candidate rows the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=128, help="candidate rows the CPU oracle is timed on (--workload predicted)")
     ap.add_argument("--phase1", choices=("sorted_prefix", "local_swap"), default="sorted_prefix",
                     help="Phase-1 solver run inside the step (the candidate set is always built around the sorted-prefix order)")
-    ap.add_argument("--workload", choices=("config3", "online", "predicted", "phase1"), default="config3",
-                    help="config3: the headline workload; online: the paper's Poisson-arrival experiment "
+    ap.add_argument("--workload", choices=("config1", "config2", "config3", "config4", "config5", "online", "predicted",
+                                           "phase1"), default="config3",
+                    help="config3: the headline workload; config1 / config2 / config5: the same step on those "
+                         "configurations; config4: the receding-horizon run (65536 moves per 512-window); online: the paper's Poisson-arrival experiment "
                          "(Section 7) as a batch of independent streams through kvsched_online; predicted: the "
                          "config-3 candidates run under interval predictions of the decode lengths "
                          "(kvsched_simulate_predicted, estimates started from the lower bounds); phase1: the "
@@ -352,148 +706,9 @@ def main() -> int:
     if args.workload == "predicted":
         return bench_predicted(args, ctx, dev)
 
-    inst = workloads.instance(CFG)
-    n, M = inst.n, inst.M
-    s = torch.from_numpy(inst.s).to(dev)
-    o = torch.from_numpy(inst.o).to(dev)
-
-    # The candidate set is built around the Sorted-F order; that order comes from the library.
-    order_d, ends_d, F_d, nb_d = ctx.sortedF(s, o, M)
-    torch.cuda.synchronize()
-    base = order_d.cpu().numpy()
-    rows_h = workloads.candidates(CFG, base)
-    C = rows_h.shape[0]
-    orders = torch.from_numpy(rows_h).to(dev)
-    tel = torch.empty(C, dtype=torch.int64, device=dev)
-    comp = torch.empty((C, n), dtype=torch.int32, device=dev)
-    best = torch.empty(2, dtype=torch.int64, device=dev)
-
-    p1_out = (order_d, ends_d, F_d, nb_d)  # Phase 1 writes into the same tensors every step
-    ctx.set_o_max(int(inst.o.max()))  # the caller's bound on decode lengths: no read-back inside the step
-
-    ctx.enable_timing(True)
-    stream = torch.cuda.current_stream()
-
-    def step():
-        if args.phase1 == "local_swap":
-            ctx.local_swap(s, o, M)
-        else:
-            ctx.sortedF(s, o, M, out=p1_out)
-        ctx.simulate(orders, s, o, M, tel_out=tel, completion_out=comp)
-        ctx.argmin(tel, result_out=best)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    kernel_ms = []
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(args.steps):
-        step()
-        kernel_ms.append(ctx.last_timeline_ms())  # events on the stream the kernel ran on
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    gpu_ms = ev0.elapsed_time(ev1)
-    ms_per_step = wall * 1e3 / args.steps
-    status = ctx.device_status()
-    if status != 0:
-        print(f"bench.py: device status {status}", file=sys.stderr)
-        return 1
-
-    if args.calibrate_copy:  # 2^26 int32 = 256 MiB read + 256 MiB written by one elementwise kernel
-        src = torch.arange(1 << 26, dtype=torch.int32, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    # ---- accounting from the outputs of the run (outside the timed region)
-    tel_h = tel.cpu().numpy()
-    o64 = o.to(torch.int64)
-    sum_o = int(o64.sum().item())
-    last_req = orders[:, -1].to(torch.int64)
-    p_last = comp.gather(1, last_req[:, None]).squeeze(1).to(torch.int64) - o64[last_req]
-    # Rows that share leading positions with row 0 start from row 0's saved state; only what
-    # they place themselves is counted: rounds waited through since the resume point + window
-    # checked + window updated for the positions from there on.
-    resume = ctx.simulate_resume_positions(C).to(torch.int64)
-    order0 = orders[0].to(torch.int64)
-    o_row0 = o64[order0]
-    start0 = comp[0].to(torch.int64)[order0] - o_row0  # start rounds of row 0 by position
-    cum0 = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev), torch.cumsum(o_row0, 0)])
-    t_res = torch.where(resume > 0, start0[(resume - 1).clamp(min=0)], torch.zeros_like(resume))
-    visits = int(((p_last - t_res) + 2 * (sum_o - cum0[resume])).sum().item())
-    visits_from_scratch = int((p_last + 2 * sum_o).sum().item())
-    lane_ops = OPS_PER_VISIT * visits
-    k_ms = float(np.mean(kernel_ms))
-    achieved = lane_ops / (k_ms * 1e-3)
-    hbm_bytes = int((8 * (n - resume) + 8).sum().item()) + 8 * n  # order entries read, completion rounds written, from the resume point on
-    result = {
-        "metric": "candidate schedules evaluated/s (n=2000 mixed)",
-        "value": C * args.steps / wall,
-        "unit": "candidates/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "int32",
-        "data": "synthetic",
-        "config": {"workload": "config 3: mixed chat+summarization, n=2000, M=131072, C=16384 "
-                               "(Sorted-F order + 16127 1-swap neighbours + 256 random restarts)",
-                   "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item()), "phase1": args.phase1},
-        "request_rounds_per_s": C * sum_o * args.steps / wall,
-        "gpu_ms_per_step": gpu_ms / args.steps,
-        "timeline_kernel_ms": k_ms,
-        "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
-        "roofline": {
-            "bound": "alu",
-            "kernel": "timeline_reg_kernel<33,4,false,true,true>",
-            "launches_per_step": 1,  # row 0 saves its state every 64 positions; the rows that share them wait for theirs
-            "resumed_rows": int((resume > 0).sum().item()),
-            "visits_without_resume": visits_from_scratch,
-            "achieved": achieved / 1e12,
-            "peak": PEAK_INT32_LANE_OPS / 1e12,
-            "unit": "Tlane-op/s (int32)",
-            "frac": achieved / PEAK_INT32_LANE_OPS,
-            "traffic": measured_traffic(),
-            "issue_slots_measured": measured_issue_slots(),
-            "visits_per_step": visits,  # from each row's resume point on
-            "ops_per_visit": OPS_PER_VISIT,
-            "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / (k_ms * 1e-3) / 1e9,
-                    "frac_of_8TBps": hbm_bytes / (k_ms * 1e-3) / PEAK_HBM_BYTES},
-        },
-    }
-
-    if not args.no_cpu_baseline:
-        import oracle  # test infrastructure; only this baseline leg uses it
-
-        rows_cpu = rows_h[: max(1, min(args.cpu_rows, C))]
-        t0 = time.perf_counter()
-        tel_o, _ = oracle.simulate_many(inst.s, inst.o, M, rows_cpu, literal=False, completions=True)
-        cpu_s = time.perf_counter() - t0
-        if not (tel_o == tel_h[: rows_cpu.shape[0]]).all():
-            print("bench.py: GPU and oracle disagree on the sampled rows", file=sys.stderr)
-            return 1
-        result["cpu_baseline"] = {
-            "value": rows_cpu.shape[0] / cpu_s,
-            "unit": "candidates/s",
-            "cores": 1,
-            "kind": "oracle",
-            "sample": f"first {rows_cpu.shape[0]} of the {C} candidate rows, array-profile oracle "
-                      f"(oracle_simulate_profile), single thread, {cpu_s:.1f} s",
-        }
-    print(json.dumps(result))
-    ctx.close()
-    return 0
+    if args.workload == "config4":
+        return bench_horizon(args, ctx, dev)
+    return bench_rows(args, ctx, dev, int(args.workload[-1]))
 
 
 if __name__ == "__main__":

@@ -99,10 +99,13 @@ const char *kvsched_strerror(int status);
  * the bound is reported as KVSCHED_DEV_O_MAX and the affected candidates get tel = -1. */
 int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound);
 
-/* Optional kernel timing.  With `on` != 0 every later kvsched_simulate / kvsched_best_neighbor
- * call records a pair of HIP events around its timeline kernel on the caller's stream;
- * kvsched_last_timeline_ms() waits for the second event and returns the kernel's duration in
- * milliseconds (EINVAL if timing is off or no call was made). */
+/* Optional kernel timing.  With `on` != 0 every later kvsched_simulate / kvsched_best_neighbor /
+ * kvsched_horizon_step call records a pair of HIP events on the caller's stream around the launch
+ * (two launches when rows are resumed in two) that runs its candidates' timelines;
+ * kvsched_last_timeline_ms() waits for the second event and returns that duration in milliseconds
+ * (EINVAL if timing is off or no call was made).  Outside the bracket: the one-wavefront launch
+ * that places a prefix common to all candidates, and kvsched_horizon_step's timeline of the
+ * chosen order. */
 int kvsched_enable_timing(kvsched_ctx *ctx, int on);
 int kvsched_last_timeline_ms(kvsched_ctx *ctx, float *ms_out);
 

@@ -703,7 +703,12 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
         p.snap_flags = flags;
         p.snap_wait_polls = ctx->resume_wait_polls;
         p.snap_cand = K;
+        if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
         rc = kvs_launch_simulate_reg(p, st);
+        if (rc == KVSCHED_OK && ctx->timing) {
+            if (hipEventRecord(ctx->ev1, st) != hipSuccess) return KVSCHED_EHIP;
+            ctx->timed = 1;
+        }
     } else {
         rc = run_timelines(ctx, p, H, st);
     }

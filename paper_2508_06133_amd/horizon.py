@@ -12,10 +12,11 @@ from . import workloads
 
 
 def receding_horizon(ctx, s, o, M, base_order, window: int = 512, complete_every: int = 256, moves_per_window: int = 65536,
-                     rng: np.random.Generator | None = None, keep_tel: bool = False, max_steps: int | None = None):
+                     rng: np.random.Generator | None = None, keep_tel: bool = False, max_steps: int | None = None,
+                     keep_completion: bool = False):
     """-> (final order tensor, completion rounds tensor, list of per-step records).
 
-    Each record: dict(lo, hi, best, best_tel, base_tel, committed, completed, T[, tel])."""
+    Each record: dict(lo, hi, best, best_tel, base_tel, committed, completed, T[, tel][, completion])."""
     rng = np.random.default_rng(0) if rng is None else rng
     n = int(base_order.shape[0])
     dev = base_order.device
@@ -31,6 +32,8 @@ def receding_horizon(ctx, s, o, M, base_order, window: int = 512, complete_every
         rec = dict(lo=lo, hi=hi, best=r[0], best_tel=r[1], base_tel=r[2], committed=r[3], completed=r[4], T=r[5])
         if keep_tel:
             rec["tel"] = tel.cpu().numpy()
+        if keep_completion:  # completion rounds of the chosen order, by request id
+            rec["completion"] = completion.cpu().numpy()
         log.append(rec)
         if r[0] < 0:
             raise RuntimeError("receding_horizon: the order or the instance is malformed (see device_status)")
