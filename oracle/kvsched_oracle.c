@@ -295,57 +295,65 @@ int oracle_sortedF(int32_t n, const int32_t *s, const int32_t *o, int64_t M, int
 /* ---------------------------------------------------------- Phase 1 (Local Swap Search) */
 
 /*
- * One batch by Local Swap Search over the m requests rem[0..m), which are sorted by
- * (s+o, o, id).  inX[i] = 1 marks membership.  The member set and its complement are both
- * visited in that sorted order; a request swapped in is visited at its own sorted place.
- *   1. greedy fill: walk the list, add a request whenever it still fits (sum of peaks <= M);
- *   2. repeat: scan members r_out in order, for each scan non-members r_in in order; skip pairs
- *      with mem + (w_in - w_out) > M; take the first pair whose F is smaller.  |X| does not
- *      change in an exchange, so "F smaller" is decided exactly as S + (o_in - o_out) < S.
- *      After an exchange both scans start again; stop when a full scan finds nothing.
- * early_exit != 0 leaves the inner scan at the first r_in that does not fit.
+ * Local Swap Search, the search step: among the m candidates cand[0..m) (sorted by (s+o, o, id);
+ * member[i] = 1 marks the batch) find the first exchange "member a out, outsider b in" that keeps the
+ * batch within the budget (w_b - w_a <= slack, slack = M - load of the batch) and lowers the metric.
+ * An exchange leaves |X| as it is, so the metric falls exactly when the numerator does: g_b < g_a.
+ * "First" in the algorithm's scan order: members by sorted place, and for each member the outsiders
+ * by sorted place.  stop_at_misfit != 0 leaves a member's scan at the first outsider that does not
+ * fit (the outsiders behind it are at least as large).  Returns 1 and the pair, or 0.
  */
-static int64_t local_swap_batch(const skey_t *rem, int32_t m, int64_t M, int early_exit,
-                                unsigned char *inX, int64_t *S_out, int64_t *K_out)
+static int first_improving_exchange(const skey_t *cand, int32_t m, const unsigned char *member, int64_t slack,
+                                    int stop_at_misfit, int32_t *a_out, int32_t *b_out)
 {
-    int64_t mem = 0, S = 0, K = 0, swaps = 0;
-    for (int32_t r = 0; r < m; ++r) {
-        inX[r] = 0;
-        if (mem + rem[r].w <= M) {
-            inX[r] = 1;
-            mem += rem[r].w;
-            S += rem[r].g;
-            ++K;
-        }
-    }
-    int improved = 1;
-    while (improved) {
-        improved = 0;
-        for (int32_t a = 0; a < m && !improved; ++a) {
-            if (!inX[a]) continue;
-            for (int32_t b = 0; b < m; ++b) {
-                if (inX[b]) continue;
-                const int64_t dm = rem[b].w - rem[a].w;
-                if (mem + dm > M) {
-                    if (early_exit) break;
-                    continue;
-                }
-                const int64_t d_o = rem[b].g - rem[a].g;  /* change of the metric's numerator */
-                if (S + d_o < S) {  /* newF < currentF, same |X| on both sides */
-                    inX[a] = 0;
-                    inX[b] = 1;
-                    mem += dm;
-                    S += d_o;
-                    ++swaps;
-                    improved = 1;
-                    break;
-                }
+    for (int32_t a = 0; a < m; ++a) {
+        if (!member[a]) continue;
+        for (int32_t b = 0; b < m; ++b) {
+            if (member[b]) continue;
+            if (cand[b].w - cand[a].w > slack) {
+                if (stop_at_misfit) break;
+                continue;
+            }
+            if (cand[b].g < cand[a].g) {
+                *a_out = a;
+                *b_out = b;
+                return 1;
             }
         }
     }
-    *S_out = S;
-    *K_out = K;
-    return swaps;
+    return 0;
+}
+
+/*
+ * One batch by Local Swap Search: start from the greedy fill (walk the sorted candidates, take each
+ * one that still fits under the sum of peaks), then apply the first improving exchange, search again
+ * from the top, and so on until no exchange is left.  A request that came in by an exchange is
+ * visited at its own sorted place from then on (membership is a mask over the sorted list).
+ * Returns the number of exchanges; *S_out = the batch's numerator, *K_out = its size.
+ */
+static int64_t local_swap_batch(const skey_t *cand, int32_t m, int64_t M, int stop_at_misfit,
+                                unsigned char *member, int64_t *S_out, int64_t *K_out)
+{
+    int64_t slack = M, numer = 0, size = 0, exchanges = 0;
+    for (int32_t i = 0; i < m; ++i) {
+        member[i] = (unsigned char)(cand[i].w <= slack);
+        if (member[i]) {
+            slack -= cand[i].w;
+            numer += cand[i].g;
+            ++size;
+        }
+    }
+    int32_t a, b;
+    while (first_improving_exchange(cand, m, member, slack, stop_at_misfit, &a, &b)) {
+        member[a] = 0;
+        member[b] = 1;
+        slack -= cand[b].w - cand[a].w;
+        numer += cand[b].g - cand[a].g;
+        ++exchanges;
+    }
+    *S_out = numer;
+    *K_out = size;
+    return exchanges;
 }
 
 /*
@@ -414,79 +422,96 @@ static int cmp_o_desc_id(const void *a, const void *b)
 }
 
 /*
- * One exact batch over the requests ids[0..r) (ascending ids), Algorithm 2:
- *   dp[k][m] = least sum of o over sets of k requests whose "load" is exactly m, path[k][m] = such
- *   a set; requests are taken one by one, k runs downward, a state is replaced only by a strictly
- *   smaller value; at the end every state is scored F = dp[k][m] / k^2 and the least is returned.
- * feas_mode 0 (Algorithm 2 as printed): requests in input order, load = sum (s+o), a request may
- *   join while the load stays <= M.
+ * One exact batch over the requests ids[0..r) (ascending ids): the feasible subset of least metric,
+ * found as Algorithm 2 finds it, by dynamic programming over (number of members, load).
+ *   cost[c][L]  least numerator (sum of effective lengths) over the subsets of the requests offered
+ *               so far that have c members and load exactly L; NONE if there is no such subset;
+ *   lowered     one bit per (offer, c, L): that offer made cost[c][L] strictly smaller.
+ * Requests are offered one at a time.  An offer extends subsets that do not hold the request yet,
+ * i.e. the table as it stood before the offer: counts are visited downward, so a row is read before
+ * this offer writes it.  A state is replaced only by a strictly smaller value.
+ * feas_mode 0 (Algorithm 2 as printed): offers in input order, load = sum (s+o), which must stay <= M.
  * feas_mode 1 (the constraint of Algorithm 1's Phase 1: with all of X started together, memory
  *   at every completion time o_j, sum over {i in X: o_i >= o_j} of (s_i + o_j), is <= M):
- *   requests in order of decreasing o (ties by id), load = sum s; when request j joins a set of k
- *   it has the least o of the set, so the memory at time o_j is load + s_j + o_j (k + 1), which
- *   must be <= M; the constraints at the larger completion times were met when those requests
- *   joined and are not touched by j.  (Derived here; the paper gives no solver for this form.)
- * Scoring order: k upward, m upward.  tie_rule 1 keeps the first least F met (Algorithm 2's strict
- *   comparison); tie_rule 0 prefers the larger k among equal F (the text's (F, -|X|)), the first m
- *   met within that k.
- * inX[q] = 1 marks ids[q] as chosen.  Returns 0, or ORACLE_ENOMEM.
+ *   offers in order of decreasing o (ties by id), load = sum s; when request j joins c others it has
+ *   the least o of the set, so the memory at time o_j is load + s_j + o_j (c + 1), which must be
+ *   <= M; the constraints at the larger completion times were met when those requests joined and
+ *   are not touched by j.  (Derived here; the paper gives no solver for this form.)
+ * Choice of the state: least cost / c^2 over all states with c >= 1, compared exactly, scanning c
+ *   upward and L upward.  tie_rule 1 keeps the first least value met (Algorithm 2's strict
+ *   comparison); tie_rule 0 prefers the larger c among equal values (the text's (F, -|X|)), the
+ *   first L met within that c.
+ * Members of the chosen state: the subset a state stands for is the one of the last offer that
+ *   lowered it, which extended the subset its predecessor (c - 1, L - load) stood for at that
+ *   time.  So the offers are walked backward from the chosen state: an offer that lowered the
+ *   state in hand is a member, and the walk goes on from the predecessor.
+ * chosen[q] = 1 marks ids[q].  Returns 0, or ORACLE_ENOMEM.
  */
 static int exact_batch(int32_t r, const int32_t *ids, const int32_t *s, const int32_t *o, int64_t M,
-                       int32_t ga, int32_t gb, int32_t feas_mode, int32_t tie_rule, unsigned char *inX,
+                       int32_t ga, int32_t gb, int32_t feas_mode, int32_t tie_rule, unsigned char *chosen,
                        int64_t *S_out, int64_t *K_out)
 {
-    const int64_t INF = INT64_MAX;
-    const size_t words = ((size_t)r + 63) / 64, cols = (size_t)M + 1, rows = (size_t)r + 1;
-    int64_t *dp = (int64_t *)malloc(sizeof(int64_t) * rows * cols);
-    uint64_t *path = (uint64_t *)calloc(rows * cols * words, sizeof(uint64_t));
-    oid_t *seq = (oid_t *)malloc(sizeof(oid_t) * (size_t)(r + 1));
-    if (!dp || !path || !seq) { free(dp); free(path); free(seq); return ORACLE_ENOMEM; }
-    for (size_t x = 0; x < rows * cols; ++x) dp[x] = INF;
-    dp[0] = 0;
-    for (int32_t q = 0; q < r; ++q) { seq[q].o = o[ids[q]]; seq[q].id = q; }  /* id = place in ids[] */
-    if (feas_mode == 1) qsort(seq, (size_t)r, sizeof(oid_t), cmp_o_desc_id);
+    const int64_t NONE = INT64_MAX;
+    const size_t loads = (size_t)M + 1, counts = (size_t)r + 1, states = counts * loads;
+    const size_t words = (states + 63) / 64;  /* bits of one offer */
+    int64_t *cost = (int64_t *)malloc(sizeof(int64_t) * states);
+    uint64_t *lowered = (uint64_t *)calloc((size_t)r * words, sizeof(uint64_t));
+    oid_t *offer = (oid_t *)malloc(sizeof(oid_t) * (size_t)(r + 1));
+    if (!cost || !lowered || !offer) { free(cost); free(lowered); free(offer); return ORACLE_ENOMEM; }
+    for (size_t x = 0; x < states; ++x) cost[x] = NONE;
+    cost[0] = 0;  /* the empty set */
+    for (int32_t q = 0; q < r; ++q) { offer[q].o = o[ids[q]]; offer[q].id = q; }  /* id = place in ids[] */
+    if (feas_mode == 1) qsort(offer, (size_t)r, sizeof(oid_t), cmp_o_desc_id);
+
     for (int32_t t = 0; t < r; ++t) {
-        const int32_t q = seq[t].id, i = ids[q];
-        const int64_t load_i = feas_mode == 1 ? (int64_t)s[i] : (int64_t)s[i] + o[i];
-        for (int64_t k = r - 1; k >= 0; --k) {
-            for (int64_t m = 0; m <= M; ++m) {
-                const int64_t cur = dp[(size_t)k * cols + (size_t)m];
-                if (cur == INF) continue;
-                const int64_t new_m = m + load_i;
-                const int64_t need = feas_mode == 1 ? new_m + (int64_t)o[i] * (k + 1) : new_m;
-                if (need > M) continue;
-                const int64_t new_val = cur + (int64_t)ga * s[i] + (int64_t)gb * o[i];  /* dp holds sums of the effective length */
-                const size_t dst = (size_t)(k + 1) * cols + (size_t)new_m;
-                if (new_val < dp[dst]) {
-                    dp[dst] = new_val;
-                    memcpy(path + dst * words, path + ((size_t)k * cols + (size_t)m) * words, words * sizeof(uint64_t));
-                    path[dst * words + (size_t)q / 64] |= 1ull << (q % 64);
+        const int32_t i = ids[offer[t].id];
+        const int64_t load = feas_mode == 1 ? (int64_t)s[i] : (int64_t)s[i] + o[i];
+        const int64_t value = (int64_t)ga * s[i] + (int64_t)gb * o[i];
+        uint64_t *bits = lowered + (size_t)t * words;
+        for (int64_t c = t; c >= 0; --c) {  /* at most t members so far */
+            for (int64_t L = 0; L + load <= M; ++L) {
+                const int64_t from = cost[(size_t)c * loads + (size_t)L];
+                if (from == NONE) continue;
+                if (feas_mode == 1 && L + load + (int64_t)o[i] * (c + 1) > M) continue;
+                const size_t to = (size_t)(c + 1) * loads + (size_t)(L + load);
+                if (from + value < cost[to]) {
+                    cost[to] = from + value;
+                    bits[to / 64] |= 1ull << (to % 64);
                 }
             }
         }
     }
-    int64_t bestS = 0, bestk = 0;
-    size_t best = 0;
-    for (int64_t k = 1; k <= r; ++k) {
-        for (int64_t m = 0; m <= M; ++m) {
-            const int64_t v = dp[(size_t)k * cols + (size_t)m];
-            if (v == INF) continue;
-            int better;
-            if (bestk == 0) better = 1;
-            else {
-                const int c = cmp_F(v, k, bestS, bestk);
-                better = (c < 0) || (c == 0 && tie_rule == 0 && k > bestk);
+
+    int64_t best_cost = 0, best_c = 0, best_L = 0;
+    for (int64_t c = 1; c <= r; ++c) {
+        for (int64_t L = 0; L <= M; ++L) {
+            const int64_t v = cost[(size_t)c * loads + (size_t)L];
+            if (v == NONE) continue;
+            int take = best_c == 0;
+            if (!take) {
+                const int cmp = cmp_F(v, c, best_cost, best_c);
+                take = cmp < 0 || (cmp == 0 && tie_rule == 0 && c > best_c);
             }
-            if (better) { bestS = v; bestk = k; best = (size_t)k * cols + (size_t)m; }
+            if (take) { best_cost = v; best_c = c; best_L = L; }
         }
     }
-    for (int32_t q = 0; q < r; ++q) inX[q] = (unsigned char)((path[best * words + (size_t)q / 64] >> (q % 64)) & 1);
-    *S_out = bestS;
-    *K_out = bestk;
-    free(dp);
-    free(path);
-    free(seq);
-    return ORACLE_OK;
+
+    memset(chosen, 0, (size_t)r);
+    int64_t c = best_c, L = best_L;
+    for (int32_t t = r - 1; t >= 0 && c > 0; --t) {
+        const size_t at = (size_t)c * loads + (size_t)L;
+        if (!((lowered[(size_t)t * words + at / 64] >> (at % 64)) & 1)) continue;
+        const int32_t q = offer[t].id, i = ids[q];
+        chosen[q] = 1;
+        L -= feas_mode == 1 ? (int64_t)s[i] : (int64_t)s[i] + o[i];
+        --c;
+    }
+    *S_out = best_cost;
+    *K_out = best_c;
+    free(cost);
+    free(lowered);
+    free(offer);
+    return c == 0 && L == 0 ? ORACLE_OK : ORACLE_EINVAL;  /* the walk must end at the empty set */
 }
 
 /*
