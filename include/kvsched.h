@@ -89,6 +89,16 @@ typedef struct kvsched_ctx kvsched_ctx;
 int kvsched_create(kvsched_ctx **out, int device_id);
 void kvsched_destroy(kvsched_ctx *ctx);
 
+/* The context's scratch buffer grows when a call needs more than any call before it, and growing
+ * means waiting for the device, freeing and allocating.  A caller that wants none of that inside
+ * its loop reserves once, for the largest call it will make: kvsched_simulate with up to `rows`
+ * rows, kvsched_best_neighbor / kvsched_horizon_step with up to `moves` moves, and the Phase-1
+ * calls (kvsched_sortedF, kvsched_local_swap, kvsched_phase1_G with those solvers), all on up to
+ * `n` positions (0 rows / moves: that call is not planned).  Calls within these sizes then never
+ * allocate.  (kvsched_exact_dp sizes its tables from the data and kvsched_online from the number
+ * of streams: not covered.)  ENOMEM if the device cannot provide the buffer. */
+int kvsched_reserve(kvsched_ctx *ctx, int32_t rows, int32_t n, int32_t moves);
+
 /* Static description of a return code. */
 const char *kvsched_strerror(int status);
 
@@ -308,9 +318,10 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
  *   - o_max_bound (1..KVSCHED_MAX_O) is the caller's bound on the decode lengths, as for
  *     kvsched_set_o_max (a longer one is reported as KVSCHED_DEV_O_MAX, tel = -1), in place of the
  *     length scan's read-back;
- *   - ERANGE when the working memory needed, about 20 (K + 1) + 17408 floor((n - 1) / 64) + 24576
- *     bytes, exceeds the array (K = 65536 moves fit up to n = 16384 positions), or the context's
- *     device number is 64 or more.
+ *   - ERANGE when the working memory needed, about 20 (K + 1) + (768 + 256 R) floor((n - 1) / 64) +
+ *     64 KiB bytes with R = 9 / 33 / 65 / 129 / 225 for o_max_bound up to 512 / 2048 / 4096 / 8192 /
+ *     14336, exceeds the array (K = 65536 moves with o_max_bound <= 4096 fit up to n = 16384
+ *     positions), or the context's device number is 64 or more.
  * Every call on a GPU uses that GPU's one array, whatever the context: two such calls whose work
  * overlaps on one GPU race (order them on one stream or by events).  Nothing in the array needs to
  * be zero at entry; it keeps the last call's contents.

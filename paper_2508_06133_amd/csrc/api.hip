@@ -152,6 +152,7 @@ constexpr int32_t kResumeWaitPollsDefault = 4096;  // about 14 ms
 constexpr int32_t kOnlineOrderMinStreams = 1024;
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+size_t neighbor_scratch_bytes(int32_t K, int32_t n, int32_t o_bound);
 
 // Are C timelines of n positions to be resumed from the states of the first of them?
 static bool resume_pays(const kvsched_ctx *ctx, int32_t C, int32_t n, int32_t o_bound)
@@ -281,6 +282,35 @@ const char *kvsched_strerror(int status)
         case KVSCHED_ENOMEM: return "out of device or host memory";
         default: return "unknown status";
     }
+}
+
+int kvsched_reserve(kvsched_ctx *ctx, int32_t rows, int32_t n, int32_t moves)
+{
+    if (!ctx || rows < 0 || n < 1 || moves < 0) return KVSCHED_EINVAL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    // the largest of what the calls named in the header ask of the scratch buffer at these sizes
+    const size_t nblk = (size_t)((n - 1) / WAVE_POSITIONS);
+    const size_t row_bytes = align256(sizeof(int32_t) * (size_t)n);
+    size_t need = kvs_sortedF_scratch_bytes(n);
+    const size_t swap = kvs_local_swap_scratch_bytes(n);
+    if (swap > need) need = swap;
+    if (rows > 0) {
+        const size_t sim = 3 * align256(sizeof(int32_t) * (size_t)rows) +
+                           align256(sizeof(int32_t) * nblk * KVS_STATE_MAX_WORDS) +
+                           align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) + row_bytes;
+        const size_t pre = state_bytes() + row_bytes;  // a declared common prefix
+        if (sim > need) need = sim;
+        if (pre > need) need = pre;
+    }
+    if (moves > 0) {
+        const size_t hor = neighbor_scratch_bytes(moves, n, ctx->o_max_bound) + 2 * row_bytes + 256;
+        if (hor > need) need = hor;
+    }
+    const int32_t keep = ctx->resume_rows;  // reserving is no call: the last resume plan stays readable unless the buffer moves
+    const bool grows = need > ctx->scratch_bytes;
+    const int rc = ensure_scratch(ctx, need);
+    if (!grows) ctx->resume_rows = keep;
+    return rc;
 }
 
 int kvsched_set_o_max(kvsched_ctx *ctx, int32_t o_max_bound)
@@ -624,13 +654,19 @@ int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t 
 // Scratch of kvsched_best_neighbor: K + 1 latencies, the state of a shared prefix, and the plan for
 // resuming each move's timeline from the base order's (three lists of K + 1 entries, a flag and a saved
 // state of the largest kind per 64 positions).
-static size_t neighbor_scratch_bytes(int32_t K, int32_t n)
+namespace {
+// o_bound: the caller's bound on the decode lengths if there is one (it fixes the size of a saved state), else 0.
+size_t neighbor_scratch_bytes(int32_t K, int32_t n, int32_t o_bound)
 {
     const size_t nblk = (size_t)((n - 1) / WAVE_POSITIONS);
+    const size_t words = o_bound > KVS_REG_MAX_O ? 0  // beyond the register kernel nothing is resumed
+                         : o_bound > 0           ? (size_t)kvs_reg_state_words(o_bound)
+                                                 : KVS_STATE_MAX_WORDS;
     return align256(sizeof(int64_t) * ((size_t)K + 1)) + state_bytes() +
            3 * align256(sizeof(int32_t) * ((size_t)K + 1)) + align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) +
-           align256(sizeof(int32_t) * nblk * KVS_STATE_MAX_WORDS);
+           align256(sizeof(int32_t) * nblk * words);
 }
+}  // namespace
 
 // kvsched_best_neighbor on working memory `work` of at least neighbor_scratch_bytes(K, n) bytes.
 // o_bound_known > 0: the caller's bound on the decode lengths; nothing is read back from the device
@@ -732,7 +768,7 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
     int rc = check_common(ctx, n, s, o, M);
     if (rc != KVSCHED_OK) return rc;
     if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
-    rc = ensure_scratch(ctx, neighbor_scratch_bytes(K, n));
+    rc = ensure_scratch(ctx, neighbor_scratch_bytes(K, n, ctx->o_max_bound));
     if (rc != KVSCHED_OK) return rc;
     return best_neighbor_on(ctx, ctx->d_scratch, ctx->o_max_bound, base_order, n, moves, K, s, o, M, tel_out,
                             result_out, (hipStream_t)stream);
@@ -747,7 +783,7 @@ int kvsched_best_neighbor_static(kvsched_ctx *ctx, const int32_t *base_order, in
     if (!base_order || !moves || !result_out || K < 1 || K == INT32_MAX || o_max_bound < 1) return KVSCHED_EINVAL;
     if (o_max_bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
     if (!ctx->static_scratch) return KVSCHED_ERANGE;  // device number beyond the table of resolved addresses
-    if (neighbor_scratch_bytes(K, n) > KVS_STATIC_SCRATCH_BYTES) return KVSCHED_ERANGE;
+    if (neighbor_scratch_bytes(K, n, o_max_bound) > KVS_STATIC_SCRATCH_BYTES) return KVSCHED_ERANGE;
     // Nothing in the array has to start at zero: the latencies, the prefix state and the plan's lists are
     // written before they are read, and the progress word of the hand-over is cleared by the kernel that
     // sorts the plan.
@@ -763,7 +799,7 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     if (K < 1 || K == INT32_MAX || n < 1) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     // scratch: [K+1] latencies of best_neighbor | new order [n] | completion rounds [n] | one latency
-    const size_t tel_bytes = neighbor_scratch_bytes(K, n);  // best_neighbor's part
+    const size_t tel_bytes = neighbor_scratch_bytes(K, n, ctx ? ctx->o_max_bound : 0);  // best_neighbor's part
     const size_t row_bytes = align256(sizeof(int32_t) * (size_t)n);
     int rc = ctx ? ensure_scratch(ctx, tel_bytes + 2 * row_bytes + 256) : KVSCHED_EINVAL;
     if (rc != KVSCHED_OK) return rc;

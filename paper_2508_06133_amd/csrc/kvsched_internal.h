@@ -90,14 +90,14 @@ constexpr int KVS_STATE_HEAD_WORDS = 192;
 constexpr int KVS_PROGRESS_COPIES = 64;
 constexpr int KVS_PROGRESS_STRIDE_WORDS = 16;
 constexpr int KVS_PROGRESS_WORDS = KVS_PROGRESS_COPIES * KVS_PROGRESS_STRIDE_WORDS;
-constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 65 * 64;
+constexpr size_t KVS_STATE_MAX_WORDS = KVS_STATE_HEAD_WORDS + 225 * 64;
 
 // simulate.hip
 int kvs_launch_scan_lengths(const int32_t *s, const int32_t *o, int32_t n, int32_t M, int32_t o_bound,
                             int32_t *d_words, hipStream_t st);
 int kvs_launch_simulate(const SimParams &p, int32_t ring_slots, hipStream_t st);
 // timeline_reg.hip (decode lengths up to KVS_REG_MAX_O)
-constexpr int32_t KVS_REG_MAX_O = 4096;
+constexpr int32_t KVS_REG_MAX_O = 14336;  // 224 rows of 64 rounds, and one more row for the window's offset
 int kvs_launch_simulate_reg(const SimParams &p, hipStream_t st);
 int32_t kvs_reg_state_words(int32_t o_bound);  // words of one snapshot for this decode bound
 

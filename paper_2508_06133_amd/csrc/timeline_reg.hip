@@ -42,15 +42,29 @@ namespace {
 
 // First register of the profile block; the KVS_CLOB_* lists start there.  The compiler's own
 // registers (and the operands it hands to the assembly statements) must stay below it: the build
-// checks that on the emitted assembly of every instantiation.
+// checks that on the emitted assembly of every instantiation.  (The lists below are generated text:
+// registers v28.., row numbers 0..NR-1 ascending and NR-1..1 descending for each file size.)
 #define KVS_PB "28"
 
 #define KVS_CLOB_9 "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35", "v36"
-#define KVS_CLOB_33 KVS_CLOB_9, "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", \
-    "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60"
-#define KVS_CLOB_65 KVS_CLOB_33, "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", \
-    "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", \
-    "v89", "v90", "v91", "v92"
+#define KVS_CLOB_33 KVS_CLOB_9, "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", \
+    "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60"
+#define KVS_CLOB_65 KVS_CLOB_33, "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", \
+    "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", \
+    "v88", "v89", "v90", "v91", "v92"
+#define KVS_CLOB_129 KVS_CLOB_65, "v93", "v94", "v95", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", \
+    "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", \
+    "v118", "v119", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v128", "v129", "v130", \
+    "v131", "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", "v140", "v141", "v142", "v143", \
+    "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", "v156"
+#define KVS_CLOB_225 KVS_CLOB_129, "v157", "v158", "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", \
+    "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", "v176", "v177", "v178", "v179", "v180", \
+    "v181", "v182", "v183", "v184", "v185", "v186", "v187", "v188", "v189", "v190", "v191", "v192", "v193", \
+    "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", "v204", "v205", "v206", \
+    "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", "v216", "v217", "v218", "v219", \
+    "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "v231", "v232", \
+    "v233", "v234", "v235", "v236", "v237", "v238", "v239", "v240", "v241", "v242", "v243", "v244", "v245", \
+    "v246", "v247", "v248", "v249", "v250", "v251", "v252"
 
 // Row numbers as the assembler's .irp wants them: all rows ascending (one stub each), and the
 // rows that can be the last row of a window with at least one full row below, descending.
@@ -60,19 +74,28 @@ namespace {
 #define KVS_DESC_33 "32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
 #define KVS_ASC_65 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63,64"
 #define KVS_DESC_65 "64,63,62,61,60,59,58,57,56,55,54,53,52,51,50,49,48,47,46,45,44,43,42,41,40,39,38,37,36,35,34,33,32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
+#define KVS_ASC_129 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63,64,65,66,67,68,69,70,71,72,73,74,75,76,77,78,79,80,81,82,83,84,85,86,87,88,89,90,91,92,93,94,95,96,97,98,99,100,101,102,103,104,105,106,107,108,109,110,111,112,113,114,115,116,117,118,119,120,121,122,123,124,125,126,127,128"
+#define KVS_DESC_129 "128,127,126,125,124,123,122,121,120,119,118,117,116,115,114,113,112,111,110,109,108,107,106,105,104,103,102,101,100,99,98,97,96,95,94,93,92,91,90,89,88,87,86,85,84,83,82,81,80,79,78,77,76,75,74,73,72,71,70,69,68,67,66,65,64,63,62,61,60,59,58,57,56,55,54,53,52,51,50,49,48,47,46,45,44,43,42,41,40,39,38,37,36,35,34,33,32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
+#define KVS_ASC_225 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63,64,65,66,67,68,69,70,71,72,73,74,75,76,77,78,79,80,81,82,83,84,85,86,87,88,89,90,91,92,93,94,95,96,97,98,99,100,101,102,103,104,105,106,107,108,109,110,111,112,113,114,115,116,117,118,119,120,121,122,123,124,125,126,127,128,129,130,131,132,133,134,135,136,137,138,139,140,141,142,143,144,145,146,147,148,149,150,151,152,153,154,155,156,157,158,159,160,161,162,163,164,165,166,167,168,169,170,171,172,173,174,175,176,177,178,179,180,181,182,183,184,185,186,187,188,189,190,191,192,193,194,195,196,197,198,199,200,201,202,203,204,205,206,207,208,209,210,211,212,213,214,215,216,217,218,219,220,221,222,223,224"
+#define KVS_DESC_225 "224,223,222,221,220,219,218,217,216,215,214,213,212,211,210,209,208,207,206,205,204,203,202,201,200,199,198,197,196,195,194,193,192,191,190,189,188,187,186,185,184,183,182,181,180,179,178,177,176,175,174,173,172,171,170,169,168,167,166,165,164,163,162,161,160,159,158,157,156,155,154,153,152,151,150,149,148,147,146,145,144,143,142,141,140,139,138,137,136,135,134,133,132,131,130,129,128,127,126,125,124,123,122,121,120,119,118,117,116,115,114,113,112,111,110,109,108,107,106,105,104,103,102,101,100,99,98,97,96,95,94,93,92,91,90,89,88,87,86,85,84,83,82,81,80,79,78,77,76,75,74,73,72,71,70,69,68,67,66,65,64,63,62,61,60,59,58,57,56,55,54,53,52,51,50,49,48,47,46,45,44,43,42,41,40,39,38,37,36,35,34,33,32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
 
 // Expands STMT(clobber-list, rows ascending, rows descending) for the instantiated file size
 // (NR - 1 must be even: the row chains process rows in pairs).
-#define KVS_FOR_NR(STMT)                                                                            \
-    do {                                                                                            \
-        if constexpr (NR == 9) {                                                                    \
-            STMT(KVS_CLOB_9, KVS_ASC_9, KVS_DESC_9);                                                \
-        } else if constexpr (NR == 33) {                                                            \
-            STMT(KVS_CLOB_33, KVS_ASC_33, KVS_DESC_33);                                             \
-        } else {                                                                                    \
-            static_assert(NR == 9 || NR == 33 || NR == 65, "profile file sizes: 9, 33 or 65 rows"); \
-            STMT(KVS_CLOB_65, KVS_ASC_65, KVS_DESC_65);                                             \
-        }                                                                                           \
+#define KVS_FOR_NR(STMT)                                                                         \
+    do {                                                                                         \
+        static_assert(NR == 9 || NR == 33 || NR == 65 || NR == 129 || NR == 225,                 \
+                      "profile file sizes: 9, 33, 65, 129 or 225 rows");                         \
+        if constexpr (NR == 9) {                                                                 \
+            STMT(KVS_CLOB_9, KVS_ASC_9, KVS_DESC_9);                                             \
+        } else if constexpr (NR == 33) {                                                         \
+            STMT(KVS_CLOB_33, KVS_ASC_33, KVS_DESC_33);                                          \
+        } else if constexpr (NR == 65) {                                                         \
+            STMT(KVS_CLOB_65, KVS_ASC_65, KVS_DESC_65);                                          \
+        } else if constexpr (NR == 129) {                                                        \
+            STMT(KVS_CLOB_129, KVS_ASC_129, KVS_DESC_129);                                       \
+        } else {                                                                                 \
+            STMT(KVS_CLOB_225, KVS_ASC_225, KVS_DESC_225);                                       \
+        }                                                                                        \
     } while (0)
 
 // Q_r = 64 r for all rows: nothing committed.
@@ -667,17 +690,21 @@ int launch_reg(const SimParams &p, hipStream_t st)
 static int reg_rows_for(int32_t o_bound)
 {
     const int rows = (o_bound + 63) / 64 + 1;
-    return rows <= 9 ? 9 : rows <= 33 ? 33 : 65;
+    return rows <= 9 ? 9 : rows <= 33 ? 33 : rows <= 65 ? 65 : rows <= 129 ? 129 : 225;
 }
 
 int32_t kvs_reg_state_words(int32_t o_bound) { return KVS_STATE_HEAD_WORDS + 64 * reg_rows_for(o_bound); }
 
-// o_bound <= KVS_REG_MAX_O.  Rows needed: ceil(o_bound / 64) + 1.
+// o_bound <= KVS_REG_MAX_O.  Rows needed: ceil(o_bound / 64) + 1.  Wavefronts per SIMD by file size
+// (512 VGPRs per SIMD lane): 8 up to 33 rows, 5 at 65, 3 at 129, 2 at 225; a file cannot be larger
+// than that, vector instructions address 256 registers.
 int kvs_launch_simulate_reg(const SimParams &p, hipStream_t st)
 {
     const int rows = (p.o_bound + 63) / 64 + 1;
     if (rows <= 9) return launch_reg<9, 4>(p, st);
     if (rows <= 33) return launch_reg<33, 4>(p, st);
     if (rows <= 65) return launch_reg<65, 4>(p, st);
+    if (rows <= 129) return launch_reg<129, 4>(p, st);
+    if (rows <= 225) return launch_reg<225, 4>(p, st);
     return KVSCHED_ERANGE;
 }

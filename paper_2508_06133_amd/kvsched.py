@@ -48,6 +48,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_strerror.argtypes = [ctypes.c_int]
     lib.kvsched_strerror.restype = ctypes.c_char_p
     lib.kvsched_set_o_max.argtypes = [vp, i32]
+    lib.kvsched_reserve.argtypes = [vp, i32, i32, i32]
     lib.kvsched_device_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
     lib.kvsched_enable_timing.argtypes = [vp, ctypes.c_int]
     lib.kvsched_last_timeline_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
@@ -105,6 +106,12 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def reserve(self, rows: int, n: int, moves: int = 0):
+        """Size the context's scratch once for calls of up to `rows` rows / `moves` moves of `n` positions."""
+        rc = _lib.kvsched_reserve(self._h, int(rows), int(n), int(moves))
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_reserve")
 
     def set_o_max(self, bound: int):
         rc = _lib.kvsched_set_o_max(self._h, int(bound))

@@ -4,7 +4,7 @@
 * configuration 4 at its stated size (n = 10000, 65536 moves per 512-window): every candidate of the
   first window, and the whole receding-horizon run -- every 64th candidate of every window, every
   chosen move, every commit triple, the final order and timeline;
-* every instantiation of the register kernel (9 / 33 / 65 profile rows; explicit rows or moves;
+* every instantiation of the register kernel (9 / 33 / 65 / 129 / 225 profile rows; explicit rows or moves;
   from the start, resumed in one launch, resumed in two) with at least 8192 timelines in flight
   on an instance whose tight budget makes most requests wait, twice each, all rows compared.
 
@@ -148,14 +148,16 @@ def test_config4_full_size_whole_run(ctx):
 
 # --------------------------- every instantiation of the register kernel on a fully occupied GPU
 
-OCCUPANCY_CASES = [(9, 320, 512), (33, 256, 2048), (65, 200, 4096)]  # (profile rows, n, longest decode)
+# (profile rows, n, longest decode, share of long decodes)
+OCCUPANCY_CASES = [(9, 320, 512, 0.25), (33, 256, 2048, 0.25), (65, 200, 4096, 0.25), (129, 136, 8192, 0.08),
+                   (225, 132, 14336, 0.05)]
 OCCUPANCY_ROWS = 8192 + 448  # eight wavefronts on each of the 1024 SIMDs, and a ragged rest
 
 
 @pytest.fixture(scope="module", params=OCCUPANCY_CASES, ids=lambda c: f"NR{c[0]}")
 def occupancy_case(request):
-    nr, n, o_max = request.param
-    inst = workloads.tight_instance(o_max + n, n, o_max)
+    nr, n, o_max, long_frac = request.param
+    inst = workloads.tight_instance(o_max + n, n, o_max, long_frac=long_frac)
     assert (int(inst.o.max()) + 63) // 64 + 1 == nr
     base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
     moves = workloads.moves_anywhere(np.random.default_rng(nr), OCCUPANCY_ROWS, n)

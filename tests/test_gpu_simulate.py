@@ -118,7 +118,8 @@ def test_config5_scaled_and_full_rows(ctx):
 @pytest.mark.parametrize("n,omax,smax,M,C", [
     (1, 5, 5, 10, 3), (2, 64, 10, 80, 5), (63, 64, 40, 600, 33), (64, 65, 40, 700, 17), (65, 130, 300, 3000, 40),
     (200, 9, 9, 60, 257), (130, 1000, 2000, 20000, 20), (97, 2048, 512, 30000, 12), (50, 4096, 100, 50000, 9),
-    (40, 5000, 100, 60000, 5),
+    (40, 5000, 100, 60000, 5), (70, 8192, 300, 40000, 7), (50, 9000, 100, 50000, 5), (45, 14336, 50, 60000, 5),
+    (40, 15000, 50, 60000, 4), (30, 16384, 20, 70000, 3),
 ])
 def test_random_instances_across_ring_sizes(ctx, n, omax, smax, M, C):
     rng = np.random.default_rng(1000 + n + omax)
@@ -180,6 +181,38 @@ def test_o_max_bound_makes_calls_asynchronous_and_is_checked(ctx):
         assert status & kvsched.DEV_O_MAX and (tel_g == -1).all()
     finally:
         ctx.set_o_max(0)
+
+
+def test_reserved_scratch_serves_later_calls():
+    # kvsched_reserve sizes the scratch once; rows resumed from row 0's states, a move step and a
+    # Phase-1 call of those sizes then run on it with the usual results
+    import torch
+    from paper_2508_06133_amd import kvsched
+
+    c = kvsched.Context(0)
+    try:
+        inst = workloads.instance(3, n=300)
+        c.reserve(600, inst.n, 500)
+        with pytest.raises(kvsched.KvschedError):
+            c.reserve(-1, inst.n, 0)
+        base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+        moves = workloads.moves_anywhere(np.random.default_rng(5), 500, inst.n)
+        rows = workloads.orders_from_moves(base, moves)
+        tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+        c.set_resume_min_rows(1)
+        tel_g, comp_g, status = _gpu_simulate(c, inst.s, inst.o, inst.M, rows)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o, "reserved, rows")
+        dev = torch.device("cuda:0")
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+        tel_m, res = c.best_neighbor(to(base), to(moves), to(inst.s), to(inst.o), inst.M)
+        torch.cuda.synchronize()
+        assert (tel_m.cpu().numpy() == tel_o).all() and int(res[0]) == int(np.argmin(tel_o))
+        order, _, _, _ = c.sortedF(to(inst.s), to(inst.o), inst.M)
+        torch.cuda.synchronize()
+        assert (order.cpu().numpy() == base).all()
+    finally:
+        c.close()
 
 
 def test_host_side_errors(ctx):
