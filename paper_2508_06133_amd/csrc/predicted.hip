@@ -11,15 +11,32 @@
 //   3. while the projection exceeds M, the running request of least (e_i, i) is stopped; it keeps
 //      e_i, loses its progress and waits again at its own place of the order.
 //
-// State of a candidate, all in LDS (one wavefront per workgroup, 16 n + 4 H bytes):
-//   * per position of the order: s, o, current estimate, start round (or waiting / done), id;
+// State of a candidate in LDS (one wavefront per workgroup):
 //   * the projected memory of the requests that are still inside their estimate, as a ring of
 //     H >= max(estimate, o) slots (slot t is cleared at round t and then stands for round t + H);
 //   * the requests that have outrun their estimate are not in the ring: each of them reserves
 //     exactly the next round, s_j + (t + 1 - p_j), so two scalars (their count and the sum of
 //     s_j - p_j) give their share of round t + 1, and a round costs nothing per such request;
-//   * the running positions as a compact list; a request matters again only when it reaches its
-//     estimate or its true length, so the list is scanned only at the earliest such round.
+//   * per position of the order only what changes and must outlive a stop: the current estimate
+//     (16 bits) and waiting / running / done (2 bits);
+//   * the RUNNING requests as a compact unordered list of complete entries: position, id, s, o,
+//     estimate, the low 16 bits of the start round (a running request started at most o <= 16384
+//     rounds ago, so the round itself follows from the current one) and of the round at which the
+//     entry next matters (it reaches its estimate or its true length).  The pass that finds the
+//     due entries and the next due round reads that last array alone; an entry that finishes
+//     leaves a hole that the list's last entry fills.
+// Lengths and ids of the waiting positions are not kept at all: admission walks the order from the
+// front, so the 64 positions around the first waiting one sit in registers (one position per lane,
+// fetched from the order row and the length tables when the walk leaves the window).
+// The list is what decides how many candidates fit a compute unit, and a wavefront here spends
+// most of its time waiting on its own dependent instructions, so twice the wavefronts per SIMD
+// is nearly twice the rate: a first launch runs every candidate with a list of at most `cap`
+// entries, sized so that eight candidates share a compute unit (two wavefronts per SIMD); a
+// candidate whose list overflows gives up and is run again by a second launch whose list holds
+// all n positions (three to four candidates per compute unit).
+// A blocked request is not re-examined round by round: the search over the ring gives the earliest
+// start its reservations allow, and that bound holds until memory is released (an eviction, or a
+// request that finishes before its estimate), whoever outruns an estimate meanwhile.
 #include "kvsched_internal.h"
 
 #include <limits.h>
@@ -27,8 +44,9 @@
 namespace {
 
 constexpr int PW = 64;
-constexpr int P_WAITING = -1, P_DONE = -2;
 constexpr int EST_OVERRUN = 0;  // estimate field of a request that has outrun it: e = t - p + 1
+constexpr unsigned ST_WAITING = 0, ST_RUNNING = 1, ST_DONE = 2;  // two bits per position
+constexpr int MAX_HOLES = 64;  // finished entries of one pass whose places are filled from the list's end
 
 struct PredParams {
     const int32_t *orders;  // [C][n]
@@ -38,6 +56,9 @@ struct PredParams {
     int32_t E;
     int32_t M;
     int32_t H;            // ring slots: power of two >= every estimate and every o
+    int32_t cap;          // entries of the running list (even)
+    int32_t second;       // 0: every candidate, overflow sets retry[c]; 1: only candidates with retry[c] != 0
+    int32_t *retry;       // [C]
     int32_t round_limit;  // a run that lasts longer is reported, not continued
     int64_t *tel_out;         // [C]
     int32_t *completion_out;  // [C][n] by request id, or NULL
@@ -53,10 +74,17 @@ __device__ __forceinline__ void p_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// Minimum over the 64 lanes by lane exchanges inside the vector unit (four steps within the rows of
+// 16 lanes, two row broadcasts; lane 63 ends up with the result).
 __device__ __forceinline__ int p_wave_min(int v)
 {
-    for (int d = 32; d >= 1; d >>= 1) v = min(v, __shfl_xor(v, d));
-    return p_uni(v);
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false));  // row_half_mirror
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false));  // row_mirror
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xa, 0xf, false));  // row_bcast:15 into rows 1 and 3
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xc, 0xf, false));  // row_bcast:31 into rows 2 and 3
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
@@ -64,21 +92,26 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     extern __shared__ int lds[];
     const int lane = threadIdx.x;
     const int cand = blockIdx.x;
-    const int n = p.n, M = p.M, H = p.H, HM = H - 1;
+    if (p.second && p.retry[cand] == 0) return;
+    const int n = p.n, M = p.M, H = p.H, HM = H - 1, cap = p.cap;
+    const int n2 = (n + 1) & ~1, stw = (n + 15) >> 4;
     int *ring = lds;
-    const int n2 = (n + 1) & ~1;
-    int *S = ring + H;
-    int *PS = S + n;  // start round of a running position, P_WAITING, P_DONE
-    unsigned short *O = (unsigned short *)(PS + n);  // lengths and estimates are at most 16384
-    unsigned short *EST = O + n2;
-    unsigned short *ID = EST + n2;
-    unsigned short *ACT = ID + n2;  // running positions, unordered
+    unsigned *ST = (unsigned *)(ring + H);             // states, 16 positions a word
+    int *LS = (int *)(ST + stw);                       // the running list: s ...
+    unsigned short *EST = (unsigned short *)(LS + cap);  // current estimate of every position
+    unsigned short *LPOS = EST + n2;                   // ... position in the order,
+    unsigned short *LID = LPOS + cap;                  // request id,
+    unsigned short *LO = LID + cap;                    // decode length,
+    unsigned short *LE = LO + cap;                     // estimate (EST_OVERRUN once outrun),
+    unsigned short *LPS = LE + cap;                    // start round, low 16 bits,
+    unsigned short *LDUE = LPS + cap;                  // round it next matters at, low 16 bits
 
     const int32_t *row = p.orders + (size_t)cand * (size_t)n;
     const int32_t *est0 = p.est0 + (p.E > 1 ? (size_t)cand * (size_t)n : 0);
     int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n : nullptr;
 
     for (int i = lane; i < H; i += PW) ring[i] = 0;
+    for (int i = lane; i < stw; i += PW) ST[i] = 0;  // all waiting
     int bad = 0;
     for (int k = lane; k < n; k += PW) {
         const int id = min(max(row[k], 0), n - 1);
@@ -86,11 +119,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         if (sv < 1 || ov < 1 || ev < 1 || ov > H || ev > H || (long long)sv + ov > (long long)M ||
             (long long)sv + ev > (long long)M)
             bad = 1;
-        S[k] = sv;
-        O[k] = (unsigned short)ov;
         EST[k] = (unsigned short)ev;
-        PS[k] = P_WAITING;
-        ID[k] = (unsigned short)id;
     }
     if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever
         if (lane == 0) {
@@ -102,17 +131,21 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     }
     p_sync();
 
+    // the 64 positions [w_base, w_base + 64) of the order: lane l holds id, s, o of position w_base + l
+    int w_base = -PW, w_id = 0, w_s = 1, w_o = 1;
+
     int t = 0;
     int head = 0;      // no waiting position lies before it
-    int hpos = -1, hs = 0, he = 0, ho = 0;  // the waiting position the admission is stuck at, if any, with its s, e, o
-    int nact = 0;      // entries of ACT
+    int hpos = -1, hs = 0, he = 0, ho = 0, hid = 0;  // the waiting position the admission is stuck at, if any
+    int ring_start = 0;  // ... and a round before which the ring's reservations rule out its start
+    int nact = 0;      // entries of the list
     int done = 0;
     int ov_cnt = 0;    // requests past their estimate ...
     long long ov_sp = 0;  // ... and the sum of s_j - p_j over them
     int next_due = INT_MAX;  // earliest round at which a running request reaches its estimate or its end
     int evictions = 0;
     long long tel = 0;
-    bool over_limit = false;
+    bool over_limit = false, overflow = false;
 
     while (done < n) {
         if (t >= p.round_limit) { over_limit = true; break; }
@@ -126,66 +159,90 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         if (lane == 0) ring[t & HM] = 0;  // round t is past
         p_sync();
 
-        // ---- 1. running requests that reach their estimate or their end at this round.  A light
-        //         pass finds them (usually one or two) and the next due round of the others; each
-        //         is then handled by the whole wavefront; finished ones leave the list in a second pass.
+        // ---- 1. running requests that reach their estimate or their end at this round.  One pass over
+        //         the due rounds finds them (usually one or two) and the next due round of the others;
+        //         each is then handled by the whole wavefront; a finished one leaves a hole in the list.
         if (t >= next_due) {
-            int due_min = INT_MAX;  // per lane: over the entries that stay as they are
-            int due_new = INT_MAX;  // uniform: over the entries that started to overrun
-            int removed = 0;
+            int wait_min = INT_MAX;  // per lane: rounds until the entries that stay as they are matter again
+            int due_new = INT_MAX;   // uniform: next due round of the entries handled here
+            int holes = 0, hole_at = 0;  // lane i of hole_at: list place of the i-th finished entry
             for (int a0 = 0; a0 < nact; a0 += PW) {
                 const int a = a0 + lane;
                 const bool in = a < nact;
-                const int pos = in ? ACT[a] : 0;
-                const int ps = in ? PS[pos] : 0, ov = in ? O[pos] : 0, ev = in ? EST[pos] : 0;
-                const int due = ps + (ev == EST_OVERRUN ? ov : min(ev, ov));
-                const bool now = in && due <= t;
-                if (in && !now) due_min = min(due_min, due);
+                const int wait = in ? (int)(short)(unsigned short)(LDUE[a] - t) : 1;  // due - t (at most 16384 ahead)
+                const bool now = in && wait <= 0;
+                if (in && !now) wait_min = min(wait_min, wait);
                 unsigned long long m = __builtin_amdgcn_ballot_w64(now);
                 while (m != 0) {
-                    const int l = __builtin_ctzll(m);
+                    const int e = a0 + __builtin_ctzll(m);  // the entry
                     m &= m - 1;
-                    const int pos_l = __builtin_amdgcn_readlane(pos, l), ps_l = __builtin_amdgcn_readlane(ps, l);
-                    const int ov_l = __builtin_amdgcn_readlane(ov, l), ev_l = __builtin_amdgcn_readlane(ev, l);
-                    const int sv_l = p_uni(S[pos_l]);
+                    const int ps16 = LPS[e], ov_r = LO[e], ev_r = LE[e], s_r = LS[e];  // four reads in flight
+                    const int ps_l = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(ps16));
+                    const int ov_l = p_uni(ov_r), ev_l = p_uni(ev_r), sv_l = p_uni(s_r);
                     if (t - ps_l == ov_l) {  // finished
                         if (lane == 0) {
-                            PS[pos_l] = P_DONE;
-                            if (crow) crow[ID[pos_l]] = t;
-                            ACT[a0 + l] = 0xffff;  // leaves the list
+                            const int pos = LPOS[e];
+                            ST[pos >> 4] = (ST[pos >> 4] & ~(3u << ((pos & 15) * 2))) | (ST_DONE << ((pos & 15) * 2));
+                            if (crow) crow[LID[e]] = t;
                         }
                         ++done;
-                        ++removed;
                         tel += t;
+                        if (holes < MAX_HOLES) hole_at = lane == holes ? e : hole_at;
+                        ++holes;
                         if (ev_l == EST_OVERRUN) {
                             --ov_cnt;
                             ov_sp -= (long long)sv_l - ps_l;
                         } else {  // over-estimated: rounds t+1 .. p + e were reserved for it
                             for (int tq = t + 1 + lane; tq <= ps_l + ev_l; tq += PW) ring[tq & HM] -= sv_l + (tq - ps_l);
+                            ring_start = 0;  // memory released: the blocked request may fit earlier
                         }
                     } else {  // goes on past its estimate: from now on it reserves the next round only
-                        if (lane == 0) EST[pos_l] = EST_OVERRUN;
+                        if (lane == 0) {
+                            LE[e] = EST_OVERRUN;
+                            LDUE[e] = (unsigned short)(ps_l + ov_l);
+                        }
                         ++ov_cnt;
                         ov_sp += (long long)sv_l - ps_l;
                         due_new = min(due_new, ps_l + ov_l);
                     }
                 }
             }
-            next_due = min(p_wave_min(due_min), due_new);
-            if (removed > 0) {  // close the list up, in place: a tile is read before it is written
+            const int w = p_wave_min(wait_min);
+            next_due = min(w == INT_MAX ? INT_MAX : t + w, due_new);
+            if (holes > 0) {
                 p_sync();
-                int kept = 0;
-                for (int a0 = 0; a0 < nact; a0 += PW) {
-                    const int a = a0 + lane;
-                    const int pos = a < nact ? ACT[a] : 0xffff;
-                    const bool keep = pos != 0xffff;
-                    const unsigned long long km = __builtin_amdgcn_ballot_w64(keep);
-                    p_sync();
-                    if (keep) ACT[kept + __popcll(km & ((1ull << lane) - 1ull))] = (unsigned short)pos;
-                    kept += __popcll(km);
-                    p_sync();
+                if (holes <= MAX_HOLES) {
+                    // fill each hole with the list's last entry, the hole furthest back first: the last
+                    // entry is then never a hole that is still to be filled
+                    for (int h = holes - 1; h >= 0; --h) {
+                        const int at = __builtin_amdgcn_readlane(hole_at, h);
+                        --nact;
+                        if (at != nact && lane == 0) {
+                            LPOS[at] = LPOS[nact], LID[at] = LID[nact], LO[at] = LO[nact], LE[at] = LE[nact];
+                            LPS[at] = LPS[nact], LDUE[at] = LDUE[nact], LS[at] = LS[nact];
+                        }
+                        p_sync();
+                    }
+                } else {  // (more than a tile of requests finishing in one round) close the list up: the done ones go
+                    int kept = 0;
+                    for (int a0 = 0; a0 < nact; a0 += PW) {
+                        const int a = a0 + lane;
+                        const bool in = a < nact;
+                        const int pos = in ? LPOS[a] : 0, id = in ? LID[a] : 0, ov = in ? LO[a] : 0, ev = in ? LE[a] : 0;
+                        const int ps = in ? LPS[a] : 0, due = in ? LDUE[a] : 0, sv = in ? LS[a] : 0;
+                        const bool keep = in && ((ST[pos >> 4] >> ((pos & 15) * 2)) & 3u) == ST_RUNNING;
+                        const unsigned long long km = __builtin_amdgcn_ballot_w64(keep);
+                        p_sync();
+                        if (keep) {
+                            const int to = kept + __popcll(km & ((1ull << lane) - 1ull));
+                            LPOS[to] = (unsigned short)pos, LID[to] = (unsigned short)id, LO[to] = (unsigned short)ov;
+                            LE[to] = (unsigned short)ev, LPS[to] = (unsigned short)ps, LDUE[to] = (unsigned short)due, LS[to] = sv;
+                        }
+                        kept += __popcll(km);
+                        p_sync();
+                    }
+                    nact = kept;
                 }
-                nact = kept;
             }
             p_sync();
         }
@@ -195,23 +252,51 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         int t_skip = t + 1;  // the next round at which anything can happen
         while (head < n) {
             if (hpos < 0) {  // first waiting position at or after head; kept while it stays blocked
-                for (int k0 = head; k0 < n && hpos < 0; k0 += PW) {
-                    const int k = k0 + lane;
-                    const unsigned long long w = __builtin_amdgcn_ballot_w64(k < n && PS[k] == P_WAITING);
-                    if (w != 0) hpos = k0 + __builtin_ctzll(w);
+                for (int w0 = head >> 4; w0 < stw && hpos < 0; w0 += PW) {  // 16 positions a lane, 1024 a turn
+                    const int wi = w0 + lane;
+                    const unsigned x = wi < stw ? ST[wi] : 0xffffffffu;
+                    unsigned wait = ~(x | (x >> 1)) & 0x55555555u;  // bit 2 j: position 16 wi + j waits
+                    if (wi == (head >> 4)) wait &= ~0u << ((head & 15) * 2);  // not before head
+                    const unsigned long long any = __builtin_amdgcn_ballot_w64(wait != 0);
+                    if (any != 0) {
+                        const int l = __builtin_ctzll(any);
+                        const unsigned wl = (unsigned)__builtin_amdgcn_readlane((int)wait, l);
+                        const int k = (w0 + l) * 16 + (__builtin_ctz(wl) >> 1);
+                        if (k < n) hpos = k;  // (the last word's spare fields read as waiting)
+                        else break;
+                    }
                 }
                 if (hpos < 0) { head = n; break; }
                 head = hpos;
-                hs = p_uni(S[hpos]);
+                if (hpos < w_base || hpos >= w_base + PW) {  // fetch the 64 positions around it
+                    w_base = hpos & ~(PW - 1);
+                    const int k = w_base + lane;
+                    w_id = 0, w_s = 1, w_o = 1;
+                    if (k < n) {
+                        w_id = min(max(row[k], 0), n - 1);
+                        w_s = p.s[w_id];
+                        w_o = p.o[w_id];
+                    }
+                }
+                hs = __builtin_amdgcn_readlane(w_s, hpos - w_base);
+                ho = __builtin_amdgcn_readlane(w_o, hpos - w_base);
+                hid = __builtin_amdgcn_readlane(w_id, hpos - w_base);
                 he = p_uni(EST[hpos]);
-                ho = p_uni(O[hpos]);
+                ring_start = 0;
             }
-            if (ov_cnt == 0) {
-                // Nobody outruns an estimate, so until the next due round the projection does not
-                // change: look for the earliest start from t on.  Round tq rules out the starts
-                // t' < tq with t' < ring(tq) + s + tq - M; rounds more than H ahead hold nothing.
-                // Each turn moves the start to the largest bound seen and looks only at the rounds
-                // that entered the window (t', t' + e] since.
+            if (t < ring_start) {  // the ring rules this round out (nothing was released since that was found)
+                if (ov_cnt == 0) t_skip = min(ring_start, next_due);
+                break;
+            }
+            // a start at t against the reservations in the ring
+            bool viol = false;
+            for (int j = lane + 1; j <= he; j += PW) viol |= ring[(t + j) & HM] + hs + j > M;
+            if (__builtin_amdgcn_ballot_w64(viol) != 0) {
+                // Blocked by them.  They change only by admissions (none while this request is blocked)
+                // and releases, so they are searched once for the earliest start they allow: round tq
+                // rules out the starts t' < tq with t' < ring(tq) + s + tq - M; rounds more than H ahead
+                // hold nothing.  Each turn moves the start to the largest bound seen and looks only at the
+                // rounds that entered the window (t', t' + e] since.
                 int start = t, lo = t + 1;
                 const int bias = hs - M;
                 for (;;) {
@@ -224,19 +309,20 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                     lo = hi + 1;
                     if (start >= next_due) break;  // the running set changes first
                 }
-                if (start > t) {  // blocked now; nothing happens before min(start, next_due)
-                    t_skip = min(start, next_due);
-                    break;
-                }
-            } else {
-                bool viol = false;
-                for (int j = lane + 1; j <= he; j += PW) viol |= ring[(t + j) & HM] + (j == 1 ? ov_next : 0) + hs + j > M;
-                if (__builtin_amdgcn_ballot_w64(viol) != 0) break;
+                ring_start = start;  // (> t)
+                if (ov_cnt == 0) t_skip = min(start, next_due);  // nothing happens before
+                break;
             }
+            ring_start = t;
+            // the ring allows a start now; the requests past their estimate also hold round t + 1
+            if (ov_cnt > 0 && p_uni(ring[(t + 1) & HM]) + ov_next + hs + 1 > M) break;
+            if (nact == cap) { overflow = true; break; }  // (first launch only: the second one's list holds every position)
             for (int j = lane + 1; j <= he; j += PW) ring[(t + j) & HM] += hs + j;
             if (lane == 0) {
-                PS[hpos] = t;
-                ACT[nact] = (unsigned short)hpos;
+                ST[hpos >> 4] = (ST[hpos >> 4] & ~(3u << ((hpos & 15) * 2))) | (ST_RUNNING << ((hpos & 15) * 2));
+                LPOS[nact] = (unsigned short)hpos, LID[nact] = (unsigned short)hid, LO[nact] = (unsigned short)ho;
+                LE[nact] = (unsigned short)he, LPS[nact] = (unsigned short)t, LS[nact] = hs;
+                LDUE[nact] = (unsigned short)(t + min(he, ho));
             }
             ++nact;
             next_due = min(next_due, t + min(he, ho));
@@ -244,6 +330,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
             hpos = -1;
             p_sync();
         }
+        if (overflow) break;
 
         // ---- 3. eviction while round t + 1 is projected above M (only that round can be: the ring
         //         held a feasible projection and only the overrunners' reservations are new)
@@ -254,46 +341,38 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 for (int a0 = 0; a0 < nact; a0 += PW) {
                     const int a = a0 + lane;
                     if (a < nact) {
-                        const int pos = ACT[a];
-                        const int ev = EST[pos];
-                        const int cur = ev == EST_OVERRUN ? t - PS[pos] + 1 : ev;
-                        best = min(best, (cur << 16) | (int)ID[pos]);
+                        const int ev = LE[a];
+                        const int cur = ev == EST_OVERRUN ? (int)(unsigned short)((unsigned short)t - LPS[a]) + 1 : ev;
+                        best = min(best, (cur << 16) | (int)LID[a]);
                     }
                 }
                 best = p_wave_min(best);
                 if (best == INT_MAX) break;  // cannot happen: an empty system holds nothing
                 // find it in the list again (ids of a permutation are distinct)
-                int slot = -1, vpos = -1;
+                int slot = -1;
                 for (int a0 = 0; a0 < nact && slot < 0; a0 += PW) {
                     const int a = a0 + lane;
-                    bool hit = false;
-                    int pos = 0;
-                    if (a < nact) {
-                        pos = ACT[a];
-                        const int ev = EST[pos];
-                        const int cur = ev == EST_OVERRUN ? t - PS[pos] + 1 : ev;
-                        hit = ((cur << 16) | (int)ID[pos]) == best;
-                    }
-                    const unsigned long long m = __builtin_amdgcn_ballot_w64(hit);
-                    if (m != 0) {
-                        const int l = __builtin_ctzll(m);
-                        slot = a0 + l;
-                        vpos = __builtin_amdgcn_readlane(pos, l);
-                    }
+                    const unsigned long long m = __builtin_amdgcn_ballot_w64(a < nact && (int)LID[a] == (best & 0xffff));
+                    if (m != 0) slot = a0 + __builtin_ctzll(m);
                 }
                 if (slot < 0) break;
-                const int ps = p_uni(PS[vpos]), ev = p_uni(EST[vpos]), sv = p_uni(S[vpos]);
+                const int vpos = p_uni(LPOS[slot]);
+                const int ps = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(LPS[slot]));
+                const int ev = p_uni(LE[slot]), sv = p_uni(LS[slot]);
                 if (ev == EST_OVERRUN) {
                     --ov_cnt;
                     ov_sp -= (long long)sv - ps;
                 } else {
                     for (int tq = t + 1 + lane; tq <= ps + ev; tq += PW) ring[tq & HM] -= sv + (tq - ps);
+                    ring_start = 0;  // memory released
                 }
                 p_sync();
                 if (lane == 0) {
-                    if (ev == EST_OVERRUN) EST[vpos] = (unsigned short)(t - ps + 1);  // what it is known to need
-                    PS[vpos] = P_WAITING;
-                    ACT[slot] = ACT[nact - 1];
+                    EST[vpos] = (unsigned short)(ev == EST_OVERRUN ? t - ps + 1 : ev);  // what it is known to need
+                    ST[vpos >> 4] &= ~(3u << ((vpos & 15) * 2));  // waits again
+                    const int last = nact - 1;
+                    LPOS[slot] = LPOS[last], LID[slot] = LID[last], LO[slot] = LO[last], LE[slot] = LE[last];
+                    LPS[slot] = LPS[last], LDUE[slot] = LDUE[last], LS[slot] = LS[last];
                 }
                 --nact;
                 if (vpos < head) { head = vpos; hpos = -1; }
@@ -303,17 +382,19 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         }
         // While requests outrun their estimates the projection of round t' + 1 grows by their count
         // every round; until the next due round nothing else changes.  Round t' needs work only if
-        // that projection passes M (eviction) or leaves room for the first token of the blocked
-        // request (a necessary condition for its admission): find the first such round.
+        // that projection passes M (eviction) or, from the round on that the ring allows the blocked
+        // request to start at, leaves room for its first token (both necessary for its admission):
+        // find the first such round.
         if (ov_cnt > 0 && (hpos >= 0 || head >= n) && next_due > t + 1) {
             const int room = hpos >= 0 ? hs + 1 : INT_MAX / 2;  // nothing waits: only the overflow matters
+            const int from = hpos >= 0 ? ring_start : INT_MAX;
             int found = next_due;
             for (int base = t + 1; base < next_due && found == next_due; base += PW) {
                 const int tr = base + lane;
                 bool hit = false;
                 if (tr < next_due) {
                     const long long x = (long long)ring[(tr + 1) & HM] + ov_sp + (long long)ov_cnt * (tr + 1);
-                    hit = x > (long long)M || x + room <= (long long)M;
+                    hit = x > (long long)M || (tr >= from && x + room <= (long long)M);
                 }
                 const unsigned long long m = __builtin_amdgcn_ballot_w64(hit);
                 if (m != 0) found = base + __builtin_ctzll(m);
@@ -332,14 +413,24 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     }
 
     if (lane == 0) {
-        if (over_limit) {
-            p.tel_out[cand] = -1;
-            atomicOr(&p.d_words[KVS_W_STATUS], KVSCHED_DEV_ROUND_LIMIT);
+        if (overflow) {
+            p.retry[cand] = 1;  // the second launch runs this candidate with a list of n entries
         } else {
-            p.tel_out[cand] = tel;
+            if (over_limit) {
+                p.tel_out[cand] = -1;
+                atomicOr(&p.d_words[KVS_W_STATUS], KVSCHED_DEV_ROUND_LIMIT);
+            } else {
+                p.tel_out[cand] = tel;
+            }
+            if (p.evictions_out) p.evictions_out[cand] = evictions;
         }
-        if (p.evictions_out) p.evictions_out[cand] = evictions;
     }
+}
+
+__global__ void clear_retry_kernel(int32_t *retry, int32_t C)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < C) retry[i] = 0;
 }
 
 __global__ __launch_bounds__(1024) void scan_estimates_kernel(const int32_t *est, size_t count, int32_t *words)
@@ -364,25 +455,37 @@ int kvs_launch_scan_estimates(const int32_t *est, size_t count, int32_t *d_words
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
-size_t kvs_predicted_lds_bytes(int32_t n, int32_t H)
+// LDS of one candidate whose running list has `cap` entries.
+static size_t predicted_lds_bytes(int32_t n, int32_t H, int32_t cap)
 {
-    return sizeof(int) * ((size_t)H + 2 * (size_t)n) + sizeof(unsigned short) * (4 * (((size_t)n + 1) & ~(size_t)1));
+    const size_t n2 = ((size_t)n + 1) & ~(size_t)1, stw = ((size_t)n + 15) >> 4;
+    return sizeof(int) * ((size_t)H + stw + (size_t)cap) + sizeof(unsigned short) * (n2 + 6 * (size_t)cap);
 }
+
+// ... with a list that holds every position: what a candidate may need at worst.
+size_t kvs_predicted_lds_bytes(int32_t n, int32_t H) { return predicted_lds_bytes(n, H, (n + 1) & ~1); }
 
 int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int32_t *s, const int32_t *o,
                          const int32_t *est0, int32_t E, int32_t M, int32_t H, int32_t round_limit, int64_t *tel_out,
-                         int32_t *completion_out, int32_t *evictions_out, int32_t *d_words, hipStream_t st)
+                         int32_t *completion_out, int32_t *evictions_out, int32_t *retry, int32_t *d_words,
+                         hipStream_t st)
 {
-    const size_t bytes = kvs_predicted_lds_bytes(n, H);
-    if (bytes > KVS_PREDICTED_MAX_LDS || n > 65535) return KVSCHED_ERANGE;
+    const int32_t cap_all = (n + 1) & ~1;
+    const size_t bytes_all = predicted_lds_bytes(n, H, cap_all);
+    if (bytes_all > KVS_PREDICTED_MAX_LDS || n > 65535) return KVSCHED_ERANGE;
     // beyond 64 KB of dynamic LDS the kernel's limit has to be raised first; only as far as needed
     static size_t lds_limit = 64 * 1024;
-    if (bytes > lds_limit) {
+    if (bytes_all > lds_limit) {
         if (hipFuncSetAttribute((const void *)predicted_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)bytes) != hipSuccess)
+                                (int)bytes_all) != hipSuccess)
             return KVSCHED_EHIP;
-        lds_limit = bytes;
+        lds_limit = bytes_all;
     }
+    // First launch: the longest list with which eight candidates share a compute unit's 160 KB; worth it
+    // when that is at least 128 entries and fewer than all.
+    const size_t budget = 26 * 1024;  // six to a compute unit: LDS is handed out in whole KB (measured: 26.5 KB each gives five)
+    const size_t fixed = predicted_lds_bytes(n, H, 0);
+    int32_t cap_first = fixed < budget ? (int32_t)((budget - fixed) / 16) & ~1 : 0;
     PredParams p;
     p.orders = orders;
     p.C = C;
@@ -393,11 +496,24 @@ int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int3
     p.E = E;
     p.M = M;
     p.H = H;
+    p.retry = retry;
     p.round_limit = round_limit;
     p.tel_out = tel_out;
     p.completion_out = completion_out;
     p.evictions_out = evictions_out;
     p.d_words = d_words;
-    hipLaunchKernelGGL(predicted_kernel, dim3((unsigned)C), dim3(PW), bytes, st, p);
+    if (cap_first >= 128 && cap_first < cap_all && retry) {
+        hipLaunchKernelGGL(clear_retry_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, retry, C);
+        p.cap = cap_first;
+        p.second = 0;
+        hipLaunchKernelGGL(predicted_kernel, dim3((unsigned)C), dim3(PW), predicted_lds_bytes(n, H, cap_first), st, p);
+        p.cap = cap_all;
+        p.second = 1;
+        hipLaunchKernelGGL(predicted_kernel, dim3((unsigned)C), dim3(PW), bytes_all, st, p);
+    } else {
+        p.cap = cap_all;
+        p.second = 0;
+        hipLaunchKernelGGL(predicted_kernel, dim3((unsigned)C), dim3(PW), bytes_all, st, p);
+    }
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
