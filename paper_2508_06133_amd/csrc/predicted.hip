@@ -18,13 +18,15 @@
 //     exactly the next round, s_j + (t + 1 - p_j), so two scalars (their count and the sum of
 //     s_j - p_j) give their share of round t + 1, and a round costs nothing per such request;
 //   * per position of the order only what changes and must outlive a stop: the current estimate
-//     (16 bits) and waiting / running / done (2 bits);
-//   * the RUNNING requests as a compact unordered list of complete entries: position, id, s, o,
-//     estimate, the low 16 bits of the start round (a running request started at most o <= 16384
-//     rounds ago, so the round itself follows from the current one) and of the round at which the
-//     entry next matters (it reaches its estimate or its true length).  The pass that finds the
-//     due entries and the next due round reads that last array alone; an entry that finishes
-//     leaves a hole that the list's last entry fills.
+//     (16 bits) and one bit "waits"; every position from `frontier` on waits (none of them was
+//     ever started), so the bits are looked at only after a request was stopped;
+//   * the RUNNING requests as a compact unordered list of complete entries: three words
+//     {s, position | id, o | estimate} side by side (a stride of three words is free of bank
+//     conflicts) and, in arrays of their own, the low 16 bits of the start round (a running request
+//     started at most o <= 16384 rounds ago, so the round itself follows from the current one) and of
+//     the round at which the entry next matters (it reaches its estimate or its true length).  The
+//     pass that finds the due entries and the next due round reads that last array alone; an entry
+//     that finishes leaves a hole that the list's last entry fills.
 // Lengths and ids of the waiting positions are not kept at all: admission walks the order from the
 // front, so the 64 positions around the first waiting one sit in registers (one position per lane,
 // fetched from the order row and the length tables when the walk leaves the window).
@@ -45,7 +47,6 @@ namespace {
 
 constexpr int PW = 64;
 constexpr int EST_OVERRUN = 0;  // estimate field of a request that has outrun it: e = t - p + 1
-constexpr unsigned ST_WAITING = 0, ST_RUNNING = 1, ST_DONE = 2;  // two bits per position
 constexpr int MAX_HOLES = 64;  // finished entries of one pass whose places are filled from the list's end
 
 struct PredParams {
@@ -94,16 +95,12 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     const int cand = blockIdx.x;
     if (p.second && p.retry[cand] == 0) return;
     const int n = p.n, M = p.M, H = p.H, HM = H - 1, cap = p.cap;
-    const int n2 = (n + 1) & ~1, stw = (n + 15) >> 4;
+    const int n2 = (n + 1) & ~1, stw = (n + 31) >> 5;
     int *ring = lds;
-    unsigned *ST = (unsigned *)(ring + H);             // states, 16 positions a word
-    int *LS = (int *)(ST + stw);                       // the running list: s ...
-    unsigned short *EST = (unsigned short *)(LS + cap);  // current estimate of every position
-    unsigned short *LPOS = EST + n2;                   // ... position in the order,
-    unsigned short *LID = LPOS + cap;                  // request id,
-    unsigned short *LO = LID + cap;                    // decode length,
-    unsigned short *LE = LO + cap;                     // estimate (EST_OVERRUN once outrun),
-    unsigned short *LPS = LE + cap;                    // start round, low 16 bits,
+    unsigned *WAIT = (unsigned *)(ring + H);           // bit k & 31 of word k >> 5: position k waits (below the frontier)
+    int *LE = (int *)(WAIT + stw);                     // the running list, three words an entry: s, position | id << 16, o | estimate << 16
+    unsigned short *EST = (unsigned short *)(LE + 3 * cap);  // current estimate of every position
+    unsigned short *LPS = EST + n2;                    // start round of an entry, low 16 bits
     unsigned short *LDUE = LPS + cap;                  // round it next matters at, low 16 bits
 
     const int32_t *row = p.orders + (size_t)cand * (size_t)n;
@@ -111,7 +108,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n : nullptr;
 
     for (int i = lane; i < H; i += PW) ring[i] = 0;
-    for (int i = lane; i < stw; i += PW) ST[i] = 0;  // all waiting
+    for (int i = lane; i < stw; i += PW) WAIT[i] = 0;  // nobody was stopped yet
     int bad = 0;
     for (int k = lane; k < n; k += PW) {
         const int id = min(max(row[k], 0), n - 1);
@@ -133,6 +130,8 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
 
     // the 64 positions [w_base, w_base + 64) of the order: lane l holds id, s, o of position w_base + l
     int w_base = -PW, w_id = 0, w_s = 1, w_o = 1;
+    int x_base = -PW, x_id = 0, x_s = 1, x_o = 1;  // ... and the 64 behind them, fetched ahead of need
+    int frontier = 0;  // every position from here on waits and was never started
 
     int t = 0;
     int head = 0;      // no waiting position lies before it
@@ -176,15 +175,12 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 while (m != 0) {
                     const int e = a0 + __builtin_ctzll(m);  // the entry
                     m &= m - 1;
-                    const int ps16 = LPS[e], ov_r = LO[e], ev_r = LE[e], s_r = LS[e];  // four reads in flight
+                    const int ps16 = LPS[e], s_r = LE[3 * e], oe_r = LE[3 * e + 2];  // three reads in flight
                     const int ps_l = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(ps16));
-                    const int ov_l = p_uni(ov_r), ev_l = p_uni(ev_r), sv_l = p_uni(s_r);
+                    const int oe_l = p_uni(oe_r), sv_l = p_uni(s_r);
+                    const int ov_l = oe_l & 0xffff, ev_l = (int)((unsigned)oe_l >> 16);
                     if (t - ps_l == ov_l) {  // finished
-                        if (lane == 0) {
-                            const int pos = LPOS[e];
-                            ST[pos >> 4] = (ST[pos >> 4] & ~(3u << ((pos & 15) * 2))) | (ST_DONE << ((pos & 15) * 2));
-                            if (crow) crow[LID[e]] = t;
-                        }
+                        if (crow && lane == 0) crow[(unsigned)LE[3 * e + 1] >> 16] = t;
                         ++done;
                         tel += t;
                         if (holes < MAX_HOLES) hole_at = lane == holes ? e : hole_at;
@@ -198,7 +194,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                         }
                     } else {  // goes on past its estimate: from now on it reserves the next round only
                         if (lane == 0) {
-                            LE[e] = EST_OVERRUN;
+                            LE[3 * e + 2] = ov_l;  // (estimate field EST_OVERRUN)
                             LDUE[e] = (unsigned short)(ps_l + ov_l);
                         }
                         ++ov_cnt;
@@ -218,25 +214,28 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                         const int at = __builtin_amdgcn_readlane(hole_at, h);
                         --nact;
                         if (at != nact && lane == 0) {
-                            LPOS[at] = LPOS[nact], LID[at] = LID[nact], LO[at] = LO[nact], LE[at] = LE[nact];
-                            LPS[at] = LPS[nact], LDUE[at] = LDUE[nact], LS[at] = LS[nact];
+                            LE[3 * at] = LE[3 * nact], LE[3 * at + 1] = LE[3 * nact + 1], LE[3 * at + 2] = LE[3 * nact + 2];
+                            LPS[at] = LPS[nact], LDUE[at] = LDUE[nact];
                         }
                         p_sync();
                     }
-                } else {  // (more than a tile of requests finishing in one round) close the list up: the done ones go
+                } else {  // (more than a tile of requests finishing in one round) close the list up: the due ones that have finished go
                     int kept = 0;
                     for (int a0 = 0; a0 < nact; a0 += PW) {
                         const int a = a0 + lane;
                         const bool in = a < nact;
-                        const int pos = in ? LPOS[a] : 0, id = in ? LID[a] : 0, ov = in ? LO[a] : 0, ev = in ? LE[a] : 0;
-                        const int ps = in ? LPS[a] : 0, due = in ? LDUE[a] : 0, sv = in ? LS[a] : 0;
-                        const bool keep = in && ((ST[pos >> 4] >> ((pos & 15) * 2)) & 3u) == ST_RUNNING;
+                        const int e0 = in ? LE[3 * a] : 0, e1 = in ? LE[3 * a + 1] : 0, e2 = in ? LE[3 * a + 2] : 0;
+                        const int ps = in ? LPS[a] : 0, due = in ? LDUE[a] : 0;
+                        // finished: due now, and the start lies the true length back
+                        const bool fin = in && (unsigned short)due == (unsigned short)t &&
+                                         (unsigned short)((unsigned short)t - (unsigned short)ps) == (unsigned short)(e2 & 0xffff);
+                        const bool keep = in && !fin;
                         const unsigned long long km = __builtin_amdgcn_ballot_w64(keep);
                         p_sync();
                         if (keep) {
                             const int to = kept + __popcll(km & ((1ull << lane) - 1ull));
-                            LPOS[to] = (unsigned short)pos, LID[to] = (unsigned short)id, LO[to] = (unsigned short)ov;
-                            LE[to] = (unsigned short)ev, LPS[to] = (unsigned short)ps, LDUE[to] = (unsigned short)due, LS[to] = sv;
+                            LE[3 * to] = e0, LE[3 * to + 1] = e1, LE[3 * to + 2] = e2;
+                            LPS[to] = (unsigned short)ps, LDUE[to] = (unsigned short)due;
                         }
                         kept += __popcll(km);
                         p_sync();
@@ -252,30 +251,44 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         int t_skip = t + 1;  // the next round at which anything can happen
         while (head < n) {
             if (hpos < 0) {  // first waiting position at or after head; kept while it stays blocked
-                for (int w0 = head >> 4; w0 < stw && hpos < 0; w0 += PW) {  // 16 positions a lane, 1024 a turn
-                    const int wi = w0 + lane;
-                    const unsigned x = wi < stw ? ST[wi] : 0xffffffffu;
-                    unsigned wait = ~(x | (x >> 1)) & 0x55555555u;  // bit 2 j: position 16 wi + j waits
-                    if (wi == (head >> 4)) wait &= ~0u << ((head & 15) * 2);  // not before head
-                    const unsigned long long any = __builtin_amdgcn_ballot_w64(wait != 0);
-                    if (any != 0) {
-                        const int l = __builtin_ctzll(any);
-                        const unsigned wl = (unsigned)__builtin_amdgcn_readlane((int)wait, l);
-                        const int k = (w0 + l) * 16 + (__builtin_ctz(wl) >> 1);
-                        if (k < n) hpos = k;  // (the last word's spare fields read as waiting)
-                        else break;
+                if (head < frontier) {  // among the stopped ones: 32 positions a lane, 2048 a turn
+                    for (int w0 = head >> 5; w0 < stw && hpos < 0; w0 += PW) {
+                        const int wi = w0 + lane;
+                        unsigned wait = wi < stw ? WAIT[wi] : 0u;
+                        if (wi == (head >> 5)) wait &= ~0u << (head & 31);  // not before head
+                        const unsigned long long any = __builtin_amdgcn_ballot_w64(wait != 0);
+                        if (any != 0) {
+                            const int l = __builtin_ctzll(any);
+                            hpos = (w0 + l) * 32 + __builtin_ctz((unsigned)__builtin_amdgcn_readlane((int)wait, l));
+                        }
                     }
+                    if (hpos < 0) hpos = frontier;  // none: the first position never started
+                } else {
+                    hpos = head;
                 }
-                if (hpos < 0) { head = n; break; }
+                if (hpos >= n) { hpos = -1; head = n; break; }
                 head = hpos;
-                if (hpos < w_base || hpos >= w_base + PW) {  // fetch the 64 positions around it
-                    w_base = hpos & ~(PW - 1);
-                    const int k = w_base + lane;
-                    w_id = 0, w_s = 1, w_o = 1;
+                if (hpos < w_base || hpos >= w_base + PW) {  // the 64 positions around it
+                    const int base = hpos & ~(PW - 1);
+                    if (base == x_base) {  // fetched ahead
+                        w_id = x_id, w_s = x_s, w_o = x_o;
+                    } else {
+                        const int k = base + lane;
+                        w_id = 0, w_s = 1, w_o = 1;
+                        if (k < n) {
+                            w_id = min(max(row[k], 0), n - 1);
+                            w_s = p.s[w_id];
+                            w_o = p.o[w_id];
+                        }
+                    }
+                    w_base = base;
+                    x_base = base + PW;  // the loads for the next 64 are issued now and waited for when used
+                    const int k = x_base + lane;
+                    x_id = 0, x_s = 1, x_o = 1;
                     if (k < n) {
-                        w_id = min(max(row[k], 0), n - 1);
-                        w_s = p.s[w_id];
-                        w_o = p.o[w_id];
+                        x_id = min(max(row[k], 0), n - 1);
+                        x_s = p.s[x_id];
+                        x_o = p.o[x_id];
                     }
                 }
                 hs = __builtin_amdgcn_readlane(w_s, hpos - w_base);
@@ -289,8 +302,13 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 break;
             }
             // a start at t against the reservations in the ring
+            // (two tiles of 64 rounds a turn, their reads in flight together; a slot behind the window is read and ignored)
             bool viol = false;
-            for (int j = lane + 1; j <= he; j += PW) viol |= ring[(t + j) & HM] + hs + j > M;
+            for (int j = lane + 1; j <= he; j += 2 * PW) {
+                const int r0 = ring[(t + j) & HM], r1 = ring[(t + j + PW) & HM];
+                viol |= r0 + hs + j > M;
+                viol |= j + PW <= he && r1 + hs + j + PW > M;
+            }
             if (__builtin_amdgcn_ballot_w64(viol) != 0) {
                 // Blocked by them.  They change only by admissions (none while this request is blocked)
                 // and releases, so they are searched once for the earliest start they allow: round tq
@@ -319,11 +337,12 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
             if (nact == cap) { overflow = true; break; }  // (first launch only: the second one's list holds every position)
             for (int j = lane + 1; j <= he; j += PW) ring[(t + j) & HM] += hs + j;
             if (lane == 0) {
-                ST[hpos >> 4] = (ST[hpos >> 4] & ~(3u << ((hpos & 15) * 2))) | (ST_RUNNING << ((hpos & 15) * 2));
-                LPOS[nact] = (unsigned short)hpos, LID[nact] = (unsigned short)hid, LO[nact] = (unsigned short)ho;
-                LE[nact] = (unsigned short)he, LPS[nact] = (unsigned short)t, LS[nact] = hs;
+                if (hpos < frontier) WAIT[hpos >> 5] &= ~(1u << (hpos & 31));  // a stopped one starts again
+                LE[3 * nact] = hs, LE[3 * nact + 1] = hpos | (hid << 16), LE[3 * nact + 2] = ho | (he << 16);
+                LPS[nact] = (unsigned short)t;
                 LDUE[nact] = (unsigned short)(t + min(he, ho));
             }
+            if (hpos >= frontier) frontier = hpos + 1;
             ++nact;
             next_due = min(next_due, t + min(he, ho));
             head = hpos + 1;
@@ -341,9 +360,9 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 for (int a0 = 0; a0 < nact; a0 += PW) {
                     const int a = a0 + lane;
                     if (a < nact) {
-                        const int ev = LE[a];
+                        const int ev = (int)((unsigned)LE[3 * a + 2] >> 16);
                         const int cur = ev == EST_OVERRUN ? (int)(unsigned short)((unsigned short)t - LPS[a]) + 1 : ev;
-                        best = min(best, (cur << 16) | (int)LID[a]);
+                        best = min(best, (cur << 16) | (int)((unsigned)LE[3 * a + 1] >> 16));
                     }
                 }
                 best = p_wave_min(best);
@@ -352,13 +371,15 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 int slot = -1;
                 for (int a0 = 0; a0 < nact && slot < 0; a0 += PW) {
                     const int a = a0 + lane;
-                    const unsigned long long m = __builtin_amdgcn_ballot_w64(a < nact && (int)LID[a] == (best & 0xffff));
+                    const unsigned long long m =
+                        __builtin_amdgcn_ballot_w64(a < nact && (int)((unsigned)LE[3 * a + 1] >> 16) == (best & 0xffff));
                     if (m != 0) slot = a0 + __builtin_ctzll(m);
                 }
                 if (slot < 0) break;
-                const int vpos = p_uni(LPOS[slot]);
-                const int ps = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(LPS[slot]));
-                const int ev = p_uni(LE[slot]), sv = p_uni(LS[slot]);
+                const int s_r = LE[3 * slot], pi_r = LE[3 * slot + 1], oe_r = LE[3 * slot + 2], ps16 = LPS[slot];
+                const int vpos = p_uni(pi_r) & 0xffff;
+                const int ps = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(ps16));
+                const int ev = (int)((unsigned)p_uni(oe_r) >> 16), sv = p_uni(s_r);
                 if (ev == EST_OVERRUN) {
                     --ov_cnt;
                     ov_sp -= (long long)sv - ps;
@@ -369,10 +390,10 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 p_sync();
                 if (lane == 0) {
                     EST[vpos] = (unsigned short)(ev == EST_OVERRUN ? t - ps + 1 : ev);  // what it is known to need
-                    ST[vpos >> 4] &= ~(3u << ((vpos & 15) * 2));  // waits again
+                    WAIT[vpos >> 5] |= 1u << (vpos & 31);  // waits again
                     const int last = nact - 1;
-                    LPOS[slot] = LPOS[last], LID[slot] = LID[last], LO[slot] = LO[last], LE[slot] = LE[last];
-                    LPS[slot] = LPS[last], LDUE[slot] = LDUE[last], LS[slot] = LS[last];
+                    LE[3 * slot] = LE[3 * last], LE[3 * slot + 1] = LE[3 * last + 1], LE[3 * slot + 2] = LE[3 * last + 2];
+                    LPS[slot] = LPS[last], LDUE[slot] = LDUE[last];
                 }
                 --nact;
                 if (vpos < head) { head = vpos; hpos = -1; }
@@ -458,8 +479,8 @@ int kvs_launch_scan_estimates(const int32_t *est, size_t count, int32_t *d_words
 // LDS of one candidate whose running list has `cap` entries.
 static size_t predicted_lds_bytes(int32_t n, int32_t H, int32_t cap)
 {
-    const size_t n2 = ((size_t)n + 1) & ~(size_t)1, stw = ((size_t)n + 15) >> 4;
-    return sizeof(int) * ((size_t)H + stw + (size_t)cap) + sizeof(unsigned short) * (n2 + 6 * (size_t)cap);
+    const size_t n2 = ((size_t)n + 1) & ~(size_t)1, stw = ((size_t)n + 31) >> 5;
+    return sizeof(int) * ((size_t)H + stw + 3 * (size_t)cap) + sizeof(unsigned short) * (n2 + 2 * (size_t)cap);
 }
 
 // ... with a list that holds every position: what a candidate may need at worst.
