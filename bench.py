@@ -50,9 +50,21 @@ CFG = 3
 # per credited visit.  Valid only for the kernel sources they were taken on (hash below); reported as
 # null once those change.
 PROFILED = {
+    # profiles/timeline_kernel_config3_traffic.md, timeline_kernel_config3_counters.md
+    "config3": {"traffic_bytes": int((47114.8 * 1.99974 + 89414.8 * 1.0) * 1024),
+                "issue": {"valu": 0.937, "scalar_and_branch": 0.828, "lane_slots_per_visit": 3.88,
+                          "source": "profiles/timeline_kernel_config3_counters.md"}},
+    # profiles/timeline_kernel_config5_rows65.md (one wavefront per SIMD)
+    "config5": {"traffic_bytes": None,
+                "issue": {"valu": 0.415, "scalar_and_branch": 0.062, "lane_slots_per_visit": 2.25,
+                          "source": "profiles/timeline_kernel_config5_rows65.md"}},
+    # profiles/timeline_kernel_config4_moves.md (candidates' launches; saturated, the clock a little above nominal)
+    "config4": {"traffic_bytes": None,
+                "issue": {"valu": 1.0, "scalar_and_branch": 0.92, "lane_slots_per_visit": 3.65,
+                          "source": "profiles/timeline_kernel_config4_moves.md"}},
 }
 PROFILED_SOURCES = ("timeline_reg.hip", "device_util.h")
-PROFILED_SOURCES_SHA256 = ""
+PROFILED_SOURCES_SHA256 = "49e69cea5fa61caf"
 
 
 def _kernel_sources_hash() -> str:
