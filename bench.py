@@ -64,7 +64,7 @@ PROFILED = {
                           "source": "profiles/timeline_kernel_config4_moves.md"}},
 }
 PROFILED_SOURCES = ("timeline_reg.hip", "device_util.h")
-PROFILED_SOURCES_SHA256 = "49e69cea5fa61caf"
+PROFILED_SOURCES_SHA256 = "c8a5df4a44bc73d6"
 
 
 def _kernel_sources_hash() -> str:

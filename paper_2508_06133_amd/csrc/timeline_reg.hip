@@ -502,59 +502,68 @@ __device__ __forceinline__ void snapshot_publish(int32_t *progress, int count, i
 // The reader's side as one scalar loop; returns the snapshot to start from (0: none).  rb = 0
 // (nothing to wait for) passes through.  Written as a single block so that the compiler sees one
 // scalar result, as from a scalar load.
+template <int NR>
 __device__ __forceinline__ int snapshot_wait(const int32_t *progress, int rb, int polls, int copy)
 {
     int f, cnt, last, voff, v;
-    asm volatile("s_cmp_eq_u32 %[rb], 0\n"
-                 "s_cbranch_scc1 4f\n"
-                 "s_max_i32 %[cnt], %[polls], 1\n"
-                 "s_mov_b32 %[last], -1\n"
-                 "s_lshl_b32 %[f], %[copy], 6\n"
-                 "v_mov_b32 %[voff], %[f]\n"
-                 "1:\n"
-                 "global_load_dword %[v], %[voff], %[base] sc1\n"
-                 "s_waitcnt vmcnt(0)\n"
-                 "v_readfirstlane_b32 %[f], %[v]\n"
-                 "s_cmp_lt_i32 %[f], 0\n"
-                 "s_cbranch_scc1 3f\n"  // the writer has stopped
-                 "s_cmp_ge_i32 %[f], %[rb]\n"
-                 "s_cbranch_scc1 4f\n"  // it is there
-                 "s_cmp_eq_u32 %[f], %[last]\n"
-                 "s_cbranch_scc1 2f\n"
-                 "s_mov_b32 %[last], %[f]\n"  // the writer has moved: count anew
-                 "s_max_i32 %[cnt], %[polls], 1\n"
-                 "s_branch 5f\n"
-                 "2:\n"
-                 "s_sub_u32 %[cnt], %[cnt], 1\n"
-                 "s_cmp_eq_u32 %[cnt], 0\n"
-                 "s_cbranch_scc0 5f\n"
-                 "s_mov_b32 %[rb], %[f]\n"  // waited long enough: what there is (f < rb)
-                 "s_branch 4f\n"
-                 "5:\n"
-                 "s_sleep 127\n"
-                 "s_branch 1b\n"
-                 "3:\n"
-                 "s_not_b32 %[f], %[f]\n"  // snapshots published before it stopped
-                 "s_min_i32 %[rb], %[rb], %[f]\n"
-                 "4:\n"
-                 "buffer_inv sc1\n"
-                 : [rb] "+s"(rb), [f] "=&s"(f), [cnt] "=&s"(cnt), [last] "=&s"(last), [voff] "=&v"(voff), [v] "=&v"(v)
-                 : [base] "s"(progress), [polls] "s"(polls), [copy] "s"(copy)
-                 : "scc", "memory");
+#define KVS_STMT(CLOB, ASC, DESC)                                                                                 \
+    asm volatile("s_cmp_eq_u32 %[rb], 0\n"                                                                        \
+                 "s_cbranch_scc1 4f\n"                                                                            \
+                 "s_max_i32 %[cnt], %[polls], 1\n"                                                                \
+                 "s_mov_b32 %[last], -1\n"                                                                        \
+                 "s_lshl_b32 %[f], %[copy], 6\n"                                                                  \
+                 "v_mov_b32 %[voff], %[f]\n"                                                                      \
+                 "1:\n"                                                                                           \
+                 "global_load_dword %[v], %[voff], %[base] sc1\n"                                                 \
+                 "s_waitcnt vmcnt(0)\n"                                                                           \
+                 "v_readfirstlane_b32 %[f], %[v]\n"                                                               \
+                 "s_cmp_lt_i32 %[f], 0\n"                                                                         \
+                 "s_cbranch_scc1 3f\n" /* the writer has stopped */                                               \
+                 "s_cmp_ge_i32 %[f], %[rb]\n"                                                                     \
+                 "s_cbranch_scc1 4f\n" /* it is there */                                                          \
+                 "s_cmp_eq_u32 %[f], %[last]\n"                                                                   \
+                 "s_cbranch_scc1 2f\n"                                                                            \
+                 "s_mov_b32 %[last], %[f]\n" /* the writer has moved: count anew */                               \
+                 "s_max_i32 %[cnt], %[polls], 1\n"                                                                \
+                 "s_branch 5f\n"                                                                                  \
+                 "2:\n"                                                                                           \
+                 "s_sub_u32 %[cnt], %[cnt], 1\n"                                                                  \
+                 "s_cmp_eq_u32 %[cnt], 0\n"                                                                       \
+                 "s_cbranch_scc0 5f\n"                                                                            \
+                 "s_mov_b32 %[rb], %[f]\n" /* waited long enough: what there is (f < rb) */                       \
+                 "s_branch 4f\n"                                                                                  \
+                 "5:\n"                                                                                           \
+                 "s_sleep 127\n"                                                                                  \
+                 "s_branch 1b\n"                                                                                  \
+                 "3:\n"                                                                                           \
+                 "s_not_b32 %[f], %[f]\n" /* snapshots published before it stopped */                             \
+                 "s_min_i32 %[rb], %[rb], %[f]\n"                                                                 \
+                 "4:\n"                                                                                           \
+                 "buffer_inv sc1\n"                                                                               \
+                 : [rb] "+s"(rb), [f] "=&s"(f), [cnt] "=&s"(cnt), [last] "=&s"(last), [voff] "=&v"(voff),         \
+                   [v] "=&v"(v)                                                                                   \
+                 : [base] "s"(progress), [polls] "s"(polls), [copy] "s"(copy)                                     \
+                 : "scc", "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
     return rb;
 }
 
 // One int32 of a snapshot's head through the vector unit (the scalar cache takes no part in the
 // hand-over above).
+template <int NR>
 __device__ __forceinline__ int snapshot_word(const int32_t *snap, int index)
 {
     int off, v;
-    asm volatile("v_mov_b32 %[off], %[idx]\n"
-                 "global_load_dword %[v], %[off], %[base]\n"
-                 "s_waitcnt vmcnt(0)\n"
-                 : [off] "=&v"(off), [v] "=&v"(v)
-                 : [base] "s"(snap), [idx] "s"(index * 4)
-                 : "memory");
+#define KVS_STMT(CLOB, ASC, DESC)                              \
+    asm volatile("v_mov_b32 %[off], %[idx]\n"                  \
+                 "global_load_dword %[v], %[off], %[base]\n"   \
+                 "s_waitcnt vmcnt(0)\n"                        \
+                 : [off] "=&v"(off), [v] "=&v"(v)              \
+                 : [base] "s"(snap), [idx] "s"(index * 4)      \
+                 : "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
     return __builtin_amdgcn_readfirstlane(v);
 }
 
@@ -594,7 +603,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     if (RES && p.resume_block) {
         const int planned = scalar_read(p.resume_block, cand);
         // ONE: taken in this very launch: wait for it, within bounds
-        const int rb = ONE ? snapshot_wait(p.snap_flags, planned, p.snap_wait_polls, wave_no & (KVS_PROGRESS_COPIES - 1)) : planned;
+        const int rb = ONE ? snapshot_wait<NR>(p.snap_flags, planned, p.snap_wait_polls, wave_no & (KVS_PROGRESS_COPIES - 1)) : planned;
         if (ONE && rb != planned) p.resume_block[cand] = rb;  // (every lane, same value) the accounts show what was really skipped
         if (rb > 0) {
             k_first = 64 * rb;
@@ -607,8 +616,8 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     int t = 0;               // start round of the previous request in the order
     long long tel_lane = 0;  // completion rounds summed per lane; added up over the lanes at the end
     if (state_in) {
-        b64 = snapshot_word(state_in, 0);
-        t = snapshot_word(state_in, 1);
+        b64 = snapshot_word<NR>(state_in, 0);
+        t = snapshot_word<NR>(state_in, 1);
         if (t < 0) {  // the shared prefix could not be scheduled
             if (lane == 0 && p.tel_out) p.tel_out[cand] = -1;
             return;
