@@ -159,26 +159,33 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 // Placing up to 64 consecutive requests of the order: ONE assembly statement.
 //
 // Lane j of vsb / vo holds s - M and o of the j-th request (j is kept in M0, the lane number of
-// v_readlane / v_writelane).  For each request in turn:
-//   check    rows 0..re of the profile (re = row of the window's last round t + o): per lane
-//            acc = max over rows of min(Q_r + (s - M), 64 r), the least admissible start that the
-//            lane's rounds impose, relative to the lane's round in row 0 (the last row is masked by
-//            value beyond round t + o: the lanes of mk);
-//   blocked  iff acc > (t - b64) - lane in some lane.  Then t becomes the largest such bound
-//            (six DPP steps), the register file moves down so that row 0 holds round t + 1 again,
-//            and only the rounds that have entered the window since are looked at: nearly always
-//            the window's last row alone (one computed jump to a stub of that row), otherwise rows
-//            rs..re one by one (a computed jump per row: the row number is not known at compile
-//            time and VGPR index mode is avoided); repeat;
-//   admit    rows 0..re get the ramp s + (tau - t); the completion round t + o goes to lane j of cv.
+// v_readlane / v_writelane).  Round tau imposes the start bound min(P(tau) + s - M + tau, tau) on the
+// request (from round tau on it no longer overlaps tau); with Q_r = P + 64 r that is, relative to the
+// lane's round in row 0, min(Q_r + (s - M), 64 r).  For each request in turn:
+//   blocked? rows 0..re of the profile (re = row of the window's last round t + o; the last row is
+//            masked by value beyond that round: the lanes of mk).  A limit 64 r, r >= 1, exceeds
+//            every admissible (t - b64) - lane, so whether the request is blocked does not depend
+//            on those limits: acc = max(max over rows >= 1 of Q_r + (s - M), min(Q_0 + (s - M), 0)),
+//            one v_max3 per two rows, and the request is blocked iff acc > (t - b64) - lane in some
+//            lane.  Most requests are not, and are admitted after this pass alone;
+//   bounds   if acc <= 64 in every lane no limit of a row >= 1 was reached and acc already holds
+//            the exact bounds; otherwise a second pass takes the rows with their limits
+//            (acc = max over rows of min(Q_r + (s - M), 64 r), five instructions per two rows);
+//   move on  t becomes the largest bound (six DPP steps), the register file moves down so that row 0
+//            holds round t + 1 again, and only the rounds that have entered the window since are
+//            looked at: nearly always the window's last row alone (one computed jump to a stub of
+//            that row), otherwise rows rs..re one by one (a computed jump per row: the row number is
+//            not known at compile time and VGPR index mode is avoided); blocked again: repeat;
+//   admit    rows 0..re get the ramp s + (tau - t) (by value zero beyond the window); the completion
+//            round t + o goes to lane j of cv.
 // A pass over rows 0..re is entered by one computed jump (table base + 64 (re + 1), s_setpc) to a
 // 64-byte stub that handles the masked last row with constant register numbers and branches into a
-// descending chain of full rows re-1..0, which runs to its end without a compare or a branch:
-// five vector instructions per two rows in the check, three in the update.
+// descending chain of full rows re-1..0, which runs to its end without a compare or a branch.
 //
 // Both the vector unit (one instruction per cycle and compute unit) and the scalar unit (the same,
 // shared by the four SIMDs) are close to saturated by this loop, so it is written to need few of
-// either: the window mask is one scalar shift, the table addresses are computed once per block.
+// either: the window mask is one scalar shift, the table addresses are computed once per block,
+// EXEC is never touched.
 //
 // Wait states (gfx950 does not interlock these; the distances below are by construction):
 //   a VALU instruction that reads an SGPR or VCC written by a VALU instruction (v_readlane, v_cmp)
@@ -186,7 +193,6 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 //   jump (at least five scalar instructions later); oj, vcc and the DPP result are read by scalar
 //   instructions, which need none;
 //   DPP reads of a VGPR written by the previous VALU instruction, and v_readlane of one: s_nop 1.
-// EXEC is narrowed to the window's lanes for the one masked addition of the update and restored.
 // The kernel has no other use of M0 (no LDS, no relative addressing).
 
 // Maximum over the 64 lanes of %[y] into lane 63 (four DPP steps inside the 16-lane rows, two row
@@ -212,18 +218,19 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 #define KVS_SLOT_PAD(bytes) "  .fill (" #bytes "-(.-7b))/4, 4, 0xbf800000\n"
 
 template <int NR>
-__device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, int vmin, int Mp64, int &t, int &b64)
+__device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, int vmin, int M, int &t, int &b64)
 {
-    int cv, acc, y, z, tl;
-    int sb, oj, x64, off, u64, w, rs, ta, tb, tc, cl, ch, ul, uh, rl, rh;
-    long long mk, m2, sx;
+    int cv, acc, y, z, tl, vw;
+    int sb, oj, x64, off, u64, w, rs, ta, tb, tc, ql, qh, cl, ch, ul, uh, rl, rh;
+    long long mk, m2;
 #define KVS_STMT(CLOB, ASC, DESC)                                                                       \
     asm volatile(                                                                                       \
-        "s_mov_b64 %[sx], exec\n"                                                                       \
-        /* table addresses: slot of row r at base + 64 (r + 1) for the check and update stubs, */      \
+        /* table addresses: slot of row r at base + 64 (r + 1) for the stubs of a whole pass, */       \
         /* at base + 32 r for the stubs of a single row */                                              \
         "s_getpc_b64 s[72:73]\n"                                                                        \
         "60:\n"                                                                                         \
+        "s_add_u32 %[ql], s72, 64f-60b-64\n"                                                            \
+        "s_addc_u32 %[qh], s73, 0\n"                                                                    \
         "s_add_u32 %[cl], s72, 61f-60b-64\n"                                                            \
         "s_addc_u32 %[ch], s73, 0\n"                                                                    \
         "s_add_u32 %[ul], s72, 62f-60b-64\n"                                                            \
@@ -233,75 +240,80 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n" /* (t - b64) - lane */                                     \
         "s_add_u32 %[u64], %[u64], 64\n"     /* x64 of a request is its decode length plus this */      \
-        "s_sub_u32 %[w], %[Mp64], %[u64]\n"  /* ramp of a request in lane l of row 0: (s - M) + w + l */ \
+        "s_sub_u32 %[w], %[M], %[u64]\n"                                                                \
+        "v_add_u32 %[vw], %[w], %[lane]\n"   /* ramp in lane l of the window's last row: vw + (s - M) + 64 (re + 1) */ \
         "v_mov_b32 %[cv], 0\n"                                                                          \
         "s_mov_b32 m0, 0\n"                                                                             \
-        /* ---- next request */                                                                         \
+        /* ---- next request: is it blocked at all? */                                                  \
         "40:\n"                                                                                         \
         "v_readlane_b32 %[sb], %[vsb], m0\n"                                                            \
         "v_readlane_b32 %[oj], %[vo], m0\n"                                                             \
         "s_add_u32 %[x64], %[oj], %[u64]\n" /* (t + o - b64) + 64: row and lane of the window's last round */ \
         "s_lshl_b64 %[mk], -2, %[x64]\n"    /* the lanes behind it (the shift uses x64 mod 64) */       \
         "s_andn2_b32 %[off], %[x64], 63\n"  /* 64 (re + 1) */                                           \
-        "s_add_u32 s72, %[cl], %[off]\n"                                                                \
-        "s_addc_u32 s73, %[ch], 0\n"                                                                    \
+        "s_add_u32 s72, %[ql], %[off]\n"                                                                \
+        "s_addc_u32 s73, %[qh], 0\n"                                                                    \
         "s_setpc_b64 s[72:73]\n"                                                                        \
-        "61:\n"                                                                                         \
+        "64:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
-        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
-        "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
-        "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
         "  .if \\r == 0\n"                                                                              \
+        "    v_add_u32 %[y], %[sb], v[" KVS_PB "]\n"                                                    \
+        "    v_min_i32 %[y], 0, %[y]\n"                                                                 \
+        "    v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                          \
         "    s_branch 41f\n"                                                                            \
         "  .else\n"                                                                                     \
-        "    .if (\\r & 1) == 1\n"                                                                      \
-        "      v_mov_b32 %[z], %[acc]\n"                                                                \
+        "    v_cndmask_b32_e64 %[acc], v[" KVS_PB "+\\r], %[vmin], %[mk]\n"                             \
+        "    .if \\r == 1\n"                                                                            \
+        "      s_branch 26f\n"                                                                          \
+        "    .else\n"                                                                                   \
+        "      .if (\\r & 1) == 0\n"                                                                    \
+        "        v_max_i32 %[acc], %[acc], v[" KVS_PB "+\\r-1]\n"                                       \
+        "      .endif\n"                                                                                \
+        "      s_branch 25\\r\\()f\n"                                                                   \
         "    .endif\n"                                                                                  \
-        "    s_branch 20\\r\\()f\n"                                                                     \
         "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
         ".endr\n"                                                                                       \
+        /* entry 25r: the rows below stub r's, two per instruction, down to row 1 */                    \
         ".irp r," DESC "\n"                                                                             \
-        "20\\r:\n"                                                                                      \
-        "  .if ((\\r-1) & 1) == 1\n"                                                                    \
-        "    v_add_u32 %[z], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
-        "    v_min_i32 %[z], 64*(\\r-1), %[z]\n"                                                        \
-        "  .else\n"                                                                                     \
-        "    v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
-        "    v_min_i32 %[y], 64*(\\r-1), %[y]\n"                                                        \
-        "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                                   \
+        "25\\r:\n"                                                                                      \
+        "  .if (\\r & 1) == 1\n"                                                                        \
+        "    .if \\r >= 3\n"                                                                             \
+        "      v_max3_i32 %[acc], %[acc], v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-2]\n"                   \
+        "    .endif\n"                                                                                  \
         "  .endif\n"                                                                                    \
         ".endr\n"                                                                                       \
-        /* ---- does some round ask for a later start? */                                               \
+        "26:\n"                                                                                         \
+        "v_add_u32 %[acc], %[sb], %[acc]\n"                                                             \
+        "v_add_u32 %[y], %[sb], v[" KVS_PB "]\n"                                                        \
+        "v_min_i32 %[y], 0, %[y]\n"                                                                     \
+        "v_max_i32 %[acc], %[acc], %[y]\n"                                                              \
         "41:\n"                                                                                         \
         "v_cmp_gt_i32 vcc, %[acc], %[tl]\n"                                                             \
-        "s_cbranch_vccnz 44f\n"                                                                         \
+        "s_cbranch_vccnz 52f\n"                                                                         \
         /* ---- admit at round t */                                                                     \
-        "s_add_u32 %[rs], %[sb], %[w]\n"                                                                \
+        "42:\n"                                                                                         \
+        "s_add_u32 %[rs], %[sb], %[off]\n"                                                              \
         "s_add_u32 s72, %[ul], %[off]\n"                                                                \
         "s_addc_u32 s73, %[uh], 0\n"                                                                    \
         "s_setpc_b64 s[72:73]\n"                                                                        \
         "62:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
+        "  v_add_u32 %[y], %[rs], %[vw]\n"                                                              \
         "  .if \\r == 0\n"                                                                              \
-        "    v_add_u32 %[y], %[rs], %[lane]\n"                                                          \
-        "    s_andn2_b64 exec, %[sx], %[mk]\n"                                                          \
+        "    v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                  \
         "    v_add_u32 v[" KVS_PB "], %[y], v[" KVS_PB "]\n"                                            \
-        "    s_mov_b64 exec, %[sx]\n"                                                                   \
         "    s_branch 43f\n"                                                                            \
         "  .else\n"                                                                                     \
-        "    s_add_u32 %[ta], %[rs], 64*\\r\n"                                                          \
-        "    v_add_u32 %[y], %[ta], %[lane]\n"                                                          \
-        "    s_andn2_b64 exec, %[sx], %[mk]\n"                                                          \
-        "    v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                    \
-        "    s_mov_b64 exec, %[sx]\n"                                                                   \
         /*   z: ramp of the even row of the pair that holds row r - 1 */                                \
         "    .if (\\r & 1) == 1\n"                                                                      \
         "      v_subrev_u32 %[z], 64, %[y]\n"                                                           \
         "    .else\n"                                                                                   \
         "      v_add_u32 %[z], 0xffffff80, %[y]\n"                                                      \
         "    .endif\n"                                                                                  \
+        "    v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                  \
+        "    v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                    \
         "    s_branch 30\\r\\()f\n"                                                                     \
         "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
         ".endr\n"                                                                                       \
@@ -323,7 +335,41 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_cmp_lt_u32 m0, %[cnt]\n"                                                                     \
         "s_cbranch_scc1 40b\n"                                                                          \
         "s_branch 50f\n"                                                                                \
-        /* ---- blocked: move t to the largest bound, the register file with it, look at what is new */ \
+        /* ---- blocked.  The bounds found are exact unless one exceeds 64 in some lane (only then */   \
+        /* can a row's limit 64 r, r >= 1, have mattered): then the pass with the limits */             \
+        "52:\n"                                                                                         \
+        "v_cmp_lt_i32 vcc, 64, %[acc]\n"                                                                \
+        "s_cbranch_vccz 44f\n"                                                                          \
+        "s_add_u32 s72, %[cl], %[off]\n"                                                                \
+        "s_addc_u32 s73, %[ch], 0\n"                                                                    \
+        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "61:\n"                                                                                         \
+        ".irp r," ASC "\n"                                                                              \
+        "7:\n"                                                                                          \
+        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
+        "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
+        "  .if \\r == 0\n"                                                                              \
+        "    s_branch 44f\n"                                                                            \
+        "  .else\n"                                                                                     \
+        "    .if (\\r & 1) == 1\n"                                                                      \
+        "      v_mov_b32 %[z], %[acc]\n"                                                                \
+        "    .endif\n"                                                                                  \
+        "    s_branch 20\\r\\()f\n"                                                                     \
+        "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
+        ".endr\n"                                                                                       \
+        ".irp r," DESC "\n"                                                                             \
+        "20\\r:\n"                                                                                      \
+        "  .if ((\\r-1) & 1) == 1\n"                                                                    \
+        "    v_add_u32 %[z], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
+        "    v_min_i32 %[z], 64*(\\r-1), %[z]\n"                                                        \
+        "  .else\n"                                                                                     \
+        "    v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
+        "    v_min_i32 %[y], 64*(\\r-1), %[y]\n"                                                        \
+        "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                                   \
+        "  .endif\n"                                                                                    \
+        ".endr\n"                                                                                       \
+        /* ---- move t to the largest bound, the register file with it, look at what is new */          \
         "44:\n"                                                                                         \
         "v_add_u32 %[y], %[acc], %[lane]\n"                                                             \
         KVS_WAVE_MAX                                                                                    \
@@ -339,7 +385,8 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n"                                                            \
         "s_add_u32 %[u64], %[u64], 64\n"                                                                \
-        "s_sub_u32 %[w], %[Mp64], %[u64]\n"                                                             \
+        "s_sub_u32 %[w], %[M], %[u64]\n"                                                                \
+        "v_add_u32 %[vw], %[w], %[lane]\n"                                                              \
         "s_add_u32 %[x64], %[oj], %[u64]\n"                                                             \
         "s_lshl_b64 %[mk], -2, %[x64]\n"                                                                \
         "s_andn2_b32 %[off], %[x64], 63\n"                                                              \
@@ -380,7 +427,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
         "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
-        "  s_branch 41b\n" KVS_SLOT_PAD(32)                                                             \
+        "  s_branch 53f\n" KVS_SLOT_PAD(32)                                                             \
         ".endr\n"                                                                                       \
         /* rows tb..tc, the last of them masked */                                                      \
         "48:\n"                                                                                         \
@@ -407,15 +454,19 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_add_u32 %[tb], %[tb], 1\n"                                                                   \
         "s_cmp_le_u32 %[tb], %[tc]\n"                                                                   \
         "s_cbranch_scc1 51b\n"                                                                          \
-        "s_branch 41b\n"                                                                                \
+        /* ---- the new rounds' bounds (exact): admitted now, or blocked once more */                   \
+        "53:\n"                                                                                         \
+        "v_cmp_gt_i32 vcc, %[acc], %[tl]\n"                                                             \
+        "s_cbranch_vccz 42b\n"                                                                          \
+        "s_branch 44b\n"                                                                                \
         "50:\n"                                                                                         \
-        : [cv] "=&v"(cv), [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [tl] "=&v"(tl), [sb] "=&s"(sb), \
-          [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64), [w] "=&s"(w),           \
-          [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [cl] "=&s"(cl), [ch] "=&s"(ch), \
-          [ul] "=&s"(ul), [uh] "=&s"(uh), [rl] "=&s"(rl), [rh] "=&s"(rh), [mk] "=&s"(mk), [m2] "=&s"(m2), \
-          [sx] "=&s"(sx), [t] "+s"(t), [b64] "+s"(b64)                                                  \
+        : [cv] "=&v"(cv), [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [tl] "=&v"(tl), [vw] "=&v"(vw), \
+          [sb] "=&s"(sb), [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64),         \
+          [w] "=&s"(w), [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [ql] "=&s"(ql), \
+          [qh] "=&s"(qh), [cl] "=&s"(cl), [ch] "=&s"(ch), [ul] "=&s"(ul), [uh] "=&s"(uh), [rl] "=&s"(rl), \
+          [rh] "=&s"(rh), [mk] "=&s"(mk), [m2] "=&s"(m2), [t] "+s"(t), [b64] "+s"(b64)                  \
         : [cnt] "s"(cnt), [vsb] "v"(vsb), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
-          [Mp64] "s"(Mp64), [nr] "n"(NR)                                                                \
+          [M] "s"(M), [nr] "n"(NR)                                                                      \
         : "scc", "vcc", "s72", "s73", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
@@ -627,7 +678,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     } else {
         prof_init<NR>();
     }
-    const int vmin = INT_MIN;
+    const int vmin = -(1 << 30);  // below every bound (s - M > -2^30), and s - M may still be added to it
 
     // 64 positions of the order at a time: ids read coalesced, lengths gathered; the next
     // block is fetched while the current one is being placed
@@ -664,7 +715,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         }
         const int cnt = min(WAVE, n - k0);
         // the up to 64 requests of this block, one after the other; cv: completion round of position k0 + lane
-        const int cv = place_block<NR>(cnt, sv - M, ov, lane, vmin, M + 64, t, b64);
+        const int cv = place_block<NR>(cnt, sv - M, ov, lane, vmin, M, t, b64);
         tel_lane += cv;
         if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
     }
