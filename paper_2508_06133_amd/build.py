@@ -2,9 +2,9 @@
 
 hipcc cross-compiles without a GPU, so this runs anywhere the ROCm toolchain is installed.
 
-timeline_reg.hip keeps per-timeline state in a block of physical VGPRs (v28 upward) that only
+timeline_reg.hip keeps per-timeline state in a block of physical VGPRs (v30 upward) that only
 its inline-assembly blocks touch.  That is sound only while everything the compiler allocates in those
-kernels (its own code and the operand registers it hands to the assembly statements) stays below v28,
+kernels (its own code and the operand registers it hands to the assembly statements) stays below v30,
 so the build emits the device assembly of that file and fails if a timeline_reg_kernel names a VGPR of
 the block anywhere but in the hand-written row code, or if it did not see every instantiation.
 """
@@ -28,7 +28,7 @@ DEVICE_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 FLAGS = DEVICE_FLAGS + ["-fPIC", "-shared", "-Wall", "-Wno-unused-function"]
-RESERVED_VGPR_BASE = 28  # KVS_PB in timeline_reg.hip
+RESERVED_VGPR_BASE = 30  # KVS_PB in timeline_reg.hip
 
 
 def lib_path() -> str:

@@ -43,28 +43,29 @@ namespace {
 // First register of the profile block; the KVS_CLOB_* lists start there.  The compiler's own
 // registers (and the operands it hands to the assembly statements) must stay below it: the build
 // checks that on the emitted assembly of every instantiation.  (The lists below are generated text:
-// registers v28.., row numbers 0..NR-1 ascending and NR-1..1 descending for each file size.)
-#define KVS_PB "28"
+// registers v30.., row numbers 0..NR-1 ascending and NR-1..1 descending for each file size.)
+#define KVS_PB "30"
 
-#define KVS_CLOB_9 "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35", "v36"
-#define KVS_CLOB_33 KVS_CLOB_9, "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", \
-    "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60"
-#define KVS_CLOB_65 KVS_CLOB_33, "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", \
-    "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", \
-    "v88", "v89", "v90", "v91", "v92"
-#define KVS_CLOB_129 KVS_CLOB_65, "v93", "v94", "v95", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", \
+#define KVS_CLOB_9 "v30", "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38"
+#define KVS_CLOB_33 KVS_CLOB_9, "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", \
+    "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62"
+#define KVS_CLOB_65 KVS_CLOB_33, "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", \
+    "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", \
+    "v89", "v90", "v91", "v92", "v93", "v94"
+#define KVS_CLOB_129 KVS_CLOB_65, "v95", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", \
     "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", \
     "v118", "v119", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v128", "v129", "v130", \
     "v131", "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", "v140", "v141", "v142", "v143", \
-    "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", "v156"
-#define KVS_CLOB_225 KVS_CLOB_129, "v157", "v158", "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", \
+    "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", "v156", \
+    "v157", "v158"
+#define KVS_CLOB_225 KVS_CLOB_129, "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", \
     "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", "v176", "v177", "v178", "v179", "v180", \
     "v181", "v182", "v183", "v184", "v185", "v186", "v187", "v188", "v189", "v190", "v191", "v192", "v193", \
     "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", "v204", "v205", "v206", \
     "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", "v216", "v217", "v218", "v219", \
     "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "v231", "v232", \
     "v233", "v234", "v235", "v236", "v237", "v238", "v239", "v240", "v241", "v242", "v243", "v244", "v245", \
-    "v246", "v247", "v248", "v249", "v250", "v251", "v252"
+    "v246", "v247", "v248", "v249", "v250", "v251", "v252", "v253", "v254"
 
 // Row numbers as the assembler's .irp wants them: all rows ascending (one stub each), and the
 // rows that can be the last row of a window with at least one full row below, descending.
@@ -158,14 +159,15 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 // ---------------------------------------------------------------------------------------------
 // Placing up to 64 consecutive requests of the order: ONE assembly statement.
 //
-// Lane j of vsb / vo holds s - M and o of the j-th request (j is kept in M0, the lane number of
-// v_readlane / v_writelane).  Round tau imposes the start bound min(P(tau) + s - M + tau, tau) on the
+// Lane j of vns / vo holds M - s and o of a request; the requests are taken from lane cnt - 1 down to
+// lane 0 (the lane number is kept in M0 for v_readlane / v_writelane, and the loop ends when it
+// borrows).  Round tau imposes the start bound min(P(tau) + s - M + tau, tau) on the
 // request (from round tau on it no longer overlaps tau); with Q_r = P + 64 r that is, relative to the
 // lane's round in row 0, min(Q_r + (s - M), 64 r).  For each request in turn:
 //   blocked? rows 0..re of the profile (re = row of the window's last round t + o; the last row is
 //            masked by value beyond that round: the lanes of mk).  A limit 64 r, r >= 1, exceeds
 //            every admissible (t - b64) - lane, so whether the request is blocked does not depend
-//            on those limits: acc = max(max over rows >= 1 of Q_r + (s - M), min(Q_0 + (s - M), 0)),
+//            on those limits: acc = max(max over rows >= 1 of Q_r, min(Q_0, M - s)) - (M - s),
 //            one v_max3 per two rows, and the request is blocked iff acc > (t - b64) - lane in some
 //            lane.  Most requests are not, and are admitted after this pass alone;
 //   bounds   if acc <= 64 in every lane no limit of a row >= 1 was reached and acc already holds
@@ -189,7 +191,7 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 //
 // Wait states (gfx950 does not interlock these; the distances below are by construction):
 //   a VALU instruction that reads an SGPR or VCC written by a VALU instruction (v_readlane, v_cmp)
-//   needs two instructions in between: sb is read by vector instructions only behind a computed
+//   needs two instructions in between: M - s is read by vector instructions only behind a computed
 //   jump (at least five scalar instructions later); oj, vcc and the DPP result are read by scalar
 //   instructions, which need none;
 //   DPP reads of a VGPR written by the previous VALU instruction, and v_readlane of one: s_nop 1.
@@ -218,10 +220,10 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 #define KVS_SLOT_PAD(bytes) "  .fill (" #bytes "-(.-7b))/4, 4, 0xbf800000\n"
 
 template <int NR>
-__device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, int vmin, int M, int &t, int &b64)
+__device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, int vmin, int M, int &t, int &b64)
 {
     int cv, acc, y, z, tl, vw;
-    int sb, oj, x64, off, u64, w, rs, ta, tb, tc, ql, qh, cl, ch, ul, uh, rl, rh;
+    int ns, oj, x64, off, u64, w, rs, ta, tb, tc, ql, qh, cl, ch, ul, uh, rl, rh;
     long long mk, m2;
 #define KVS_STMT(CLOB, ASC, DESC)                                                                       \
     asm volatile(                                                                                       \
@@ -235,7 +237,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_addc_u32 %[ch], s73, 0\n"                                                                    \
         "s_add_u32 %[ul], s72, 62f-60b-64\n"                                                            \
         "s_addc_u32 %[uh], s73, 0\n"                                                                    \
-        "s_add_u32 %[rl], s72, 63f-60b\n"                                                               \
+        "s_add_u32 %[rl], s72, 63f-60b-32\n"                                                             \
         "s_addc_u32 %[rh], s73, 0\n"                                                                    \
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n" /* (t - b64) - lane */                                     \
@@ -243,10 +245,10 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_sub_u32 %[w], %[M], %[u64]\n"                                                                \
         "v_add_u32 %[vw], %[w], %[lane]\n"   /* ramp in lane l of the window's last row: vw + (s - M) + 64 (re + 1) */ \
         "v_mov_b32 %[cv], 0\n"                                                                          \
-        "s_mov_b32 m0, 0\n"                                                                             \
-        /* ---- next request: is it blocked at all? */                                                  \
+        "s_sub_u32 m0, %[cnt], 1\n"                                                                     \
+        /* ---- next request (lane m0, counting down): is it blocked at all? */                         \
         "40:\n"                                                                                         \
-        "v_readlane_b32 %[sb], %[vsb], m0\n"                                                            \
+        "v_readlane_b32 %[ns], %[vns], m0\n"                                                            \
         "v_readlane_b32 %[oj], %[vo], m0\n"                                                             \
         "s_add_u32 %[x64], %[oj], %[u64]\n" /* (t + o - b64) + 64: row and lane of the window's last round */ \
         "s_lshl_b64 %[mk], -2, %[x64]\n"    /* the lanes behind it (the shift uses x64 mod 64) */       \
@@ -258,42 +260,43 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
         "  .if \\r == 0\n"                                                                              \
-        "    v_add_u32 %[y], %[sb], v[" KVS_PB "]\n"                                                    \
-        "    v_min_i32 %[y], 0, %[y]\n"                                                                 \
+        "    v_min_i32 %[y], %[ns], v[" KVS_PB "]\n"                                                    \
         "    v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                          \
-        "    s_branch 41f\n"                                                                            \
+        "    s_branch 26f\n"                                                                            \
         "  .else\n"                                                                                     \
         "    v_cndmask_b32_e64 %[acc], v[" KVS_PB "+\\r], %[vmin], %[mk]\n"                             \
         "    .if \\r == 1\n"                                                                            \
+        "      v_min_i32 %[y], %[ns], v[" KVS_PB "]\n"                                                  \
+        "      v_max_i32 %[acc], %[acc], %[y]\n"                                                        \
         "      s_branch 26f\n"                                                                          \
         "    .else\n"                                                                                   \
-        "      .if (\\r & 1) == 0\n"                                                                    \
+        "      .if (\\r & 1) == 1\n"                                                                    \
         "        v_max_i32 %[acc], %[acc], v[" KVS_PB "+\\r-1]\n"                                       \
         "      .endif\n"                                                                                \
         "      s_branch 25\\r\\()f\n"                                                                   \
         "    .endif\n"                                                                                  \
         "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
         ".endr\n"                                                                                       \
-        /* entry 25r: the rows below stub r's, two per instruction, down to row 1 */                    \
+        /* entry 25r: the rows below those of stub r, two per instruction; y stands for row 0 */       \
         ".irp r," DESC "\n"                                                                             \
         "25\\r:\n"                                                                                      \
-        "  .if (\\r & 1) == 1\n"                                                                        \
-        "    .if \\r >= 3\n"                                                                             \
+        "  .if (\\r & 1) == 0\n"                                                                        \
+        "    .if \\r == 2\n"                                                                            \
+        "      v_min_i32 %[y], %[ns], v[" KVS_PB "]\n"                                                  \
+        "      v_max3_i32 %[acc], %[acc], v[" KVS_PB "+1], %[y]\n"                                      \
+        "    .else\n"                                                                                   \
         "      v_max3_i32 %[acc], %[acc], v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-2]\n"                   \
         "    .endif\n"                                                                                  \
         "  .endif\n"                                                                                    \
         ".endr\n"                                                                                       \
         "26:\n"                                                                                         \
-        "v_add_u32 %[acc], %[sb], %[acc]\n"                                                             \
-        "v_add_u32 %[y], %[sb], v[" KVS_PB "]\n"                                                        \
-        "v_min_i32 %[y], 0, %[y]\n"                                                                     \
-        "v_max_i32 %[acc], %[acc], %[y]\n"                                                              \
+        "v_subrev_u32 %[acc], %[ns], %[acc]\n"                                                          \
         "41:\n"                                                                                         \
         "v_cmp_gt_i32 vcc, %[acc], %[tl]\n"                                                             \
         "s_cbranch_vccnz 52f\n"                                                                         \
         /* ---- admit at round t */                                                                     \
         "42:\n"                                                                                         \
-        "s_add_u32 %[rs], %[sb], %[off]\n"                                                              \
+        "s_sub_u32 %[rs], %[off], %[ns]\n"                                                              \
         "s_add_u32 s72, %[ul], %[off]\n"                                                                \
         "s_addc_u32 s73, %[uh], 0\n"                                                                    \
         "s_setpc_b64 s[72:73]\n"                                                                        \
@@ -331,9 +334,8 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "43:\n"                                                                                         \
         "s_add_u32 %[ta], %[t], %[oj]\n"                                                                \
         "v_writelane_b32 %[cv], %[ta], m0\n"                                                            \
-        "s_add_u32 m0, m0, 1\n"                                                                         \
-        "s_cmp_lt_u32 m0, %[cnt]\n"                                                                     \
-        "s_cbranch_scc1 40b\n"                                                                          \
+        "s_sub_u32 m0, m0, 1\n"             /* borrows behind lane 0 */                                 \
+        "s_cbranch_scc0 40b\n"                                                                          \
         "s_branch 50f\n"                                                                                \
         /* ---- blocked.  The bounds found are exact unless one exceeds 64 in some lane (only then */   \
         /* can a row's limit 64 r, r >= 1, have mattered): then the pass with the limits */             \
@@ -346,7 +348,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "61:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
-        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_subrev_u32 %[y], %[ns], v[" KVS_PB "+\\r]\n"                                                  \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
         "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
         "  .if \\r == 0\n"                                                                              \
@@ -361,10 +363,10 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         ".irp r," DESC "\n"                                                                             \
         "20\\r:\n"                                                                                      \
         "  .if ((\\r-1) & 1) == 1\n"                                                                    \
-        "    v_add_u32 %[z], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
+        "    v_subrev_u32 %[z], %[ns], v[" KVS_PB "+\\r-1]\n"                                              \
         "    v_min_i32 %[z], 64*(\\r-1), %[z]\n"                                                        \
         "  .else\n"                                                                                     \
-        "    v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r-1]\n"                                              \
+        "    v_subrev_u32 %[y], %[ns], v[" KVS_PB "+\\r-1]\n"                                              \
         "    v_min_i32 %[y], 64*(\\r-1), %[y]\n"                                                        \
         "    v_max3_i32 %[acc], %[acc], %[y], %[z]\n"                                                   \
         "  .endif\n"                                                                                    \
@@ -373,16 +375,12 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "44:\n"                                                                                         \
         "v_add_u32 %[y], %[acc], %[lane]\n"                                                             \
         KVS_WAVE_MAX                                                                                    \
-        "s_sub_u32 %[tb], %[x64], 63\n"                                                                 \
-        "s_lshr_b32 %[tb], %[tb], 6\n"       /* row of the first round not looked at yet */             \
         "s_add_u32 %[t], %[tc], %[b64]\n"                                                               \
-        "s_add_u32 %[tc], %[t], 1\n"                                                                    \
-        "s_andn2_b32 %[tc], %[tc], 63\n"     /* row 0 starts at 64 floor((t + 1) / 64) */               \
-        "s_sub_u32 %[rs], %[tc], %[b64]\n"                                                              \
-        "s_lshr_b32 %[rs], %[rs], 6\n"       /* rows to move down */                                    \
-        "s_mov_b32 %[b64], %[tc]\n"                                                                     \
-        "s_sub_u32 %[tb], %[tb], %[rs]\n"    /* ... in the moved file */                                \
-        "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
+        "s_add_u32 %[ta], %[tc], 1\n"                                                                   \
+        "s_andn2_b32 %[rs], %[ta], 63\n"     /* row 0 starts at 64 floor((t + 1) / 64): 64 x rows to move down */ \
+        "s_add_u32 %[b64], %[b64], %[rs]\n"                                                             \
+        "s_sub_u32 %[tb], %[x64], %[rs]\n"   /* the last round looked at, as x64 counts in the moved file */ \
+        "s_sub_u32 %[u64], %[tc], %[rs]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n"                                                            \
         "s_add_u32 %[u64], %[u64], 64\n"                                                                \
         "s_sub_u32 %[w], %[M], %[u64]\n"                                                                \
@@ -390,8 +388,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_add_u32 %[x64], %[oj], %[u64]\n"                                                             \
         "s_lshl_b64 %[mk], -2, %[x64]\n"                                                                \
         "s_andn2_b32 %[off], %[x64], 63\n"                                                              \
-        "s_lshr_b32 %[tc], %[x64], 6\n"                                                                 \
-        "s_sub_u32 %[tc], %[tc], 1\n"        /* last row of the window */                               \
+        "s_lshr_b32 %[rs], %[rs], 6\n"                                                                  \
         "s_cmp_eq_u32 %[rs], 0\n"                                                                       \
         "s_cbranch_scc1 46f\n"                                                                          \
         "s_cmp_ge_u32 %[rs], %c[nr]\n"                                                                  \
@@ -414,23 +411,29 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "  .set kvs_r, kvs_r+1\n"                                                                       \
         ".endr\n"                                                                                       \
         "46:\n"                                                                                         \
-        "s_cmp_lt_u32 %[tb], %[tc]\n"                                                                   \
-        "s_cbranch_scc1 48f\n"                                                                          \
+        "s_add_u32 %[tb], %[tb], 1\n"        /* the first round not looked at yet */                    \
+        "s_xor_b32 %[ta], %[tb], %[x64]\n"                                                              \
+        "s_cmp_lt_u32 %[ta], 64\n"           /* in the window's last row? */                            \
+        "s_cbranch_scc0 48f\n"                                                                          \
         /* only the window's last row is new */                                                         \
-        "s_lshl_b32 %[ta], %[tc], 5\n"                                                                  \
+        "s_lshr_b32 %[ta], %[off], 1\n"      /* 32 (re + 1) */                                          \
         "s_add_u32 s72, %[rl], %[ta]\n"                                                                 \
         "s_addc_u32 s73, %[rh], 0\n"                                                                    \
         "s_setpc_b64 s[72:73]\n"                                                                        \
         "63:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
-        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_subrev_u32 %[y], %[ns], v[" KVS_PB "+\\r]\n"                                                  \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
         "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
         "  s_branch 53f\n" KVS_SLOT_PAD(32)                                                             \
         ".endr\n"                                                                                       \
         /* rows tb..tc, the last of them masked */                                                      \
         "48:\n"                                                                                         \
+        "s_lshr_b32 %[tb], %[tb], 6\n"                                                                  \
+        "s_sub_u32 %[tb], %[tb], 1\n"                                                                   \
+        "s_lshr_b32 %[tc], %[x64], 6\n"                                                                 \
+        "s_sub_u32 %[tc], %[tc], 1\n"                                                                   \
         "v_mov_b32 %[acc], %[vmin]\n"                                                                   \
         "51:\n"                                                                                         \
         "s_cmp_eq_u32 %[tb], %[tc]\n"                                                                   \
@@ -444,7 +447,7 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         ".fill 1, 4, 0xbf800000\n"                                                                      \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
-        "  v_add_u32 %[y], %[sb], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_subrev_u32 %[y], %[ns], v[" KVS_PB "+\\r]\n"                                                  \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
         "  s_branch 49f\n" KVS_SLOT_PAD(16)                                                             \
         ".endr\n"                                                                                       \
@@ -461,11 +464,11 @@ __device__ __forceinline__ int place_block(int cnt, int vsb, int vo, int lane, i
         "s_branch 44b\n"                                                                                \
         "50:\n"                                                                                         \
         : [cv] "=&v"(cv), [acc] "=&v"(acc), [y] "=&v"(y), [z] "=&v"(z), [tl] "=&v"(tl), [vw] "=&v"(vw), \
-          [sb] "=&s"(sb), [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64),         \
+          [ns] "=&s"(ns), [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64),         \
           [w] "=&s"(w), [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [ql] "=&s"(ql), \
           [qh] "=&s"(qh), [cl] "=&s"(cl), [ch] "=&s"(ch), [ul] "=&s"(ul), [uh] "=&s"(uh), [rl] "=&s"(rl), \
           [rh] "=&s"(rh), [mk] "=&s"(mk), [m2] "=&s"(m2), [t] "+s"(t), [b64] "+s"(b64)                  \
-        : [cnt] "s"(cnt), [vsb] "v"(vsb), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
+        : [cnt] "s"(cnt), [vns] "v"(vns), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
           [M] "s"(M), [nr] "n"(NR)                                                                      \
         : "scc", "vcc", "s72", "s73", CLOB)
     KVS_FOR_NR(KVS_STMT);
@@ -681,12 +684,16 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     const int vmin = -(1 << 30);  // below every bound (s - M > -2^30), and s - M may still be added to it
 
     // 64 positions of the order at a time: ids read coalesced, lengths gathered; the next
-    // block is fetched while the current one is being placed
+    // block is fetched while the current one is being placed.  Within a block of cnt positions
+    // lane cnt - 1 holds the first and lane 0 the last (place_block counts its lane number down).
     int rq_n = 0, sv_n = 1, ov_n = 1;
-    if (k_first + lane < n) {
-        rq_n = min(max(rd.at(k_first + lane), 0), n_all - 1);
-        sv_n = p.s[rq_n];
-        ov_n = p.o[rq_n];
+    {
+        const int k = k_first + min(WAVE, n - k_first) - 1 - lane;
+        if (k >= k_first) {
+            rq_n = min(max(rd.at(k), 0), n_all - 1);
+            sv_n = p.s[rq_n];
+            ov_n = p.o[rq_n];
+        }
     }
     for (int k0 = k_first; k0 < n; k0 += WAVE) {
         if (takes_snapshots && k0 > 0 && (k0 >> 6) <= p.snap_blocks) {  // the state after k0 positions
@@ -695,13 +702,18 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             prof_store<NR>(snap + KVS_STATE_HEAD_WORDS, lane);
             if (ONE) snapshot_publish<NR>(p.snap_flags, k0 >> 6, lane);
         }
-        const int k = k0 + lane;
+        const int cnt = __builtin_amdgcn_readfirstlane(min(WAVE, n - k0));
+        const int k = k0 + cnt - 1 - lane;  // this lane's position (none if k < k0)
         const int rq = rq_n, sv = sv_n, ov = ov_n;
         rq_n = 0, sv_n = 1, ov_n = 1;
-        if (k + WAVE < n) {
-            rq_n = min(max(rd.at(k + WAVE), 0), n_all - 1);
-            sv_n = p.s[rq_n];
-            ov_n = p.o[rq_n];
+        {
+            const int k1 = k0 + WAVE;
+            const int kn = k1 + min(WAVE, n - k1) - 1 - lane;
+            if (kn >= k1) {
+                rq_n = min(max(rd.at(kn), 0), n_all - 1);
+                sv_n = p.s[rq_n];
+                ov_n = p.o[rq_n];
+            }
         }
         const bool bad = (sv < 1) | (ov < 1) | (ov > p.o_bound) | ((long long)sv + (long long)ov > (long long)M);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever
@@ -713,11 +725,10 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
                 snapshot_progress_set<NR>(p.snap_flags, ~(k0 >> 6), lane);
             return;  // (snapshots not taken stay marked unusable, as the host left them)
         }
-        const int cnt = min(WAVE, n - k0);
-        // the up to 64 requests of this block, one after the other; cv: completion round of position k0 + lane
-        const int cv = place_block<NR>(cnt, sv - M, ov, lane, vmin, M, t, b64);
+        // the up to 64 requests of this block, one after the other; cv: completion round of this lane's position
+        const int cv = place_block<NR>(cnt, M - sv, ov, lane, vmin, M, t, b64);
         tel_lane += cv;
-        if (crow && k < n) crow[p.completion_by_position ? k : rq] = cv;
+        if (crow && k >= k0) crow[p.completion_by_position ? k : rq] = cv;
     }
     if (p.state_out) {
         state_head_store<NR>(p.state_out, b64, t, tel_lane, lane);
