@@ -178,8 +178,8 @@ __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 //            looked at: nearly always the window's last row alone (one computed jump to a stub of
 //            that row), otherwise rows rs..re one by one (a computed jump per row: the row number is
 //            not known at compile time and VGPR index mode is avoided); blocked again: repeat;
-//   admit    rows 0..re get the ramp s + (tau - t) (by value zero beyond the window); the completion
-//            round t + o goes to lane j of cv.
+//   admit    rows 0..re get the ramp s + (tau - t) (by value zero beyond the window); the start
+//            round t goes to the request's lane of cv.
 // A pass over rows 0..re is entered by one computed jump (table base + 64 (re + 1), s_setpc) to a
 // 64-byte stub that handles the masked last row with constant register numbers and branches into a
 // descending chain of full rows re-1..0, which runs to its end without a compare or a branch.
@@ -332,8 +332,7 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "  .endif\n"                                                                                    \
         ".endr\n"                                                                                       \
         "43:\n"                                                                                         \
-        "s_add_u32 %[ta], %[t], %[oj]\n"                                                                \
-        "v_writelane_b32 %[cv], %[ta], m0\n"                                                            \
+        "v_writelane_b32 %[cv], %[t], m0\n"  /* the start round; the caller adds the lane's decode length */ \
         "s_sub_u32 m0, m0, 1\n"             /* borrows behind lane 0 */                                 \
         "s_cbranch_scc0 40b\n"                                                                          \
         "s_branch 50f\n"                                                                                \
@@ -725,8 +724,9 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
                 snapshot_progress_set<NR>(p.snap_flags, ~(k0 >> 6), lane);
             return;  // (snapshots not taken stay marked unusable, as the host left them)
         }
-        // the up to 64 requests of this block, one after the other; cv: completion round of this lane's position
-        const int cv = place_block<NR>(cnt, M - sv, ov, lane, vmin, M, t, b64);
+        // the up to 64 requests of this block, one after the other (place_block returns the lanes' start
+        // rounds); cv: completion round of this lane's position
+        const int cv = (k >= k0 ? ov : 0) + place_block<NR>(cnt, M - sv, ov, lane, vmin, M, t, b64);
         tel_lane += cv;
         if (crow && k >= k0) crow[p.completion_by_position ? k : rq] = cv;
     }
