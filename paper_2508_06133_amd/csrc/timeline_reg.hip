@@ -224,26 +224,26 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
 {
     int cv, acc, y, z, tl, vw;
     int ns, oj, x64, off, u64, w, rs, ta, tb, tc, ql, qh, cl, ch, ul, uh, rl, rh;
-    long long mk, m2;
+    long long mk;
 #define KVS_STMT(CLOB, ASC, DESC)                                                                       \
     asm volatile(                                                                                       \
         /* table addresses: slot of row r at base + 64 (r + 1) for the stubs of a whole pass, */       \
-        /* at base + 32 r for the stubs of a single row */                                              \
-        "s_getpc_b64 s[72:73]\n"                                                                        \
+        /* whole passes and single rows alike */                                                    \
+        "s_getpc_b64 s[66:67]\n"                                                                        \
         "60:\n"                                                                                         \
-        "s_add_u32 %[ql], s72, 64f-60b-64\n"                                                            \
-        "s_addc_u32 %[qh], s73, 0\n"                                                                    \
-        "s_add_u32 %[cl], s72, 61f-60b-64\n"                                                            \
-        "s_addc_u32 %[ch], s73, 0\n"                                                                    \
-        "s_add_u32 %[ul], s72, 62f-60b-64\n"                                                            \
-        "s_addc_u32 %[uh], s73, 0\n"                                                                    \
-        "s_add_u32 %[rl], s72, 63f-60b-32\n"                                                             \
-        "s_addc_u32 %[rh], s73, 0\n"                                                                    \
+        "s_add_u32 %[ql], s66, 64f-60b-64\n"                                                            \
+        "s_addc_u32 %[qh], s67, 0\n"                                                                    \
+        "s_add_u32 %[cl], s66, 61f-60b-64\n"                                                            \
+        "s_addc_u32 %[ch], s67, 0\n"                                                                    \
+        "s_add_u32 %[ul], s66, 62f-60b-64\n"                                                            \
+        "s_addc_u32 %[uh], s67, 0\n"                                                                    \
+        "s_add_u32 %[rl], s66, 63f-60b-64\n"                                                            \
+        "s_addc_u32 %[rh], s67, 0\n"                                                                    \
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n" /* (t - b64) - lane */                                     \
         "s_add_u32 %[u64], %[u64], 64\n"     /* x64 of a request is its decode length plus this */      \
-        "s_sub_u32 %[w], %[M], %[u64]\n"                                                                \
-        "v_add_u32 %[vw], %[w], %[lane]\n"   /* ramp in lane l of the window's last row: vw + (s - M) + 64 (re + 1) */ \
+        "s_sub_u32 %[w], %[M], 64\n"                                                                    \
+        "v_sub_u32 %[vw], %[w], %[tl]\n"    /* ramp in lane l of the window's last row: vw + (s - M) + 64 (re + 1) */ \
         "v_mov_b32 %[cv], 0\n"                                                                          \
         "s_sub_u32 m0, %[cnt], 1\n"                                                                     \
         /* ---- next request (lane m0, counting down): is it blocked at all? */                         \
@@ -253,9 +253,9 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "s_add_u32 %[x64], %[oj], %[u64]\n" /* (t + o - b64) + 64: row and lane of the window's last round */ \
         "s_lshl_b64 %[mk], -2, %[x64]\n"    /* the lanes behind it (the shift uses x64 mod 64) */       \
         "s_andn2_b32 %[off], %[x64], 63\n"  /* 64 (re + 1) */                                           \
-        "s_add_u32 s72, %[ql], %[off]\n"                                                                \
-        "s_addc_u32 s73, %[qh], 0\n"                                                                    \
-        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "s_add_u32 s66, %[ql], %[off]\n"                                                                \
+        "s_addc_u32 s67, %[qh], 0\n"                                                                    \
+        "s_setpc_b64 s[66:67]\n"                                                                        \
         "64:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
@@ -297,9 +297,9 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         /* ---- admit at round t */                                                                     \
         "42:\n"                                                                                         \
         "s_sub_u32 %[rs], %[off], %[ns]\n"                                                              \
-        "s_add_u32 s72, %[ul], %[off]\n"                                                                \
-        "s_addc_u32 s73, %[uh], 0\n"                                                                    \
-        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "s_add_u32 s66, %[ul], %[off]\n"                                                                \
+        "s_addc_u32 s67, %[uh], 0\n"                                                                    \
+        "s_setpc_b64 s[66:67]\n"                                                                        \
         "62:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
@@ -341,9 +341,9 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "52:\n"                                                                                         \
         "v_cmp_lt_i32 vcc, 64, %[acc]\n"                                                                \
         "s_cbranch_vccz 44f\n"                                                                          \
-        "s_add_u32 s72, %[cl], %[off]\n"                                                                \
-        "s_addc_u32 s73, %[ch], 0\n"                                                                    \
-        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "s_add_u32 s66, %[cl], %[off]\n"                                                                \
+        "s_addc_u32 s67, %[ch], 0\n"                                                                    \
+        "s_setpc_b64 s[66:67]\n"                                                                        \
         "61:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
@@ -382,14 +382,12 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "s_sub_u32 %[u64], %[tc], %[rs]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n"                                                            \
         "s_add_u32 %[u64], %[u64], 64\n"                                                                \
-        "s_sub_u32 %[w], %[M], %[u64]\n"                                                                \
-        "v_add_u32 %[vw], %[w], %[lane]\n"                                                              \
+        "v_sub_u32 %[vw], %[w], %[tl]\n"                                                                \
         "s_add_u32 %[x64], %[oj], %[u64]\n"                                                             \
         "s_lshl_b64 %[mk], -2, %[x64]\n"                                                                \
         "s_andn2_b32 %[off], %[x64], 63\n"                                                              \
-        "s_lshr_b32 %[rs], %[rs], 6\n"                                                                  \
-        "s_cmp_eq_u32 %[rs], 0\n"                                                                       \
-        "s_cbranch_scc1 46f\n"                                                                          \
+        "s_lshr_b32 %[rs], %[rs], 6\n"       /* rows to move down; SCC: any */                          \
+        "s_cbranch_scc0 46f\n"                                                                          \
         "s_cmp_ge_u32 %[rs], %c[nr]\n"                                                                  \
         "s_cbranch_scc1 47f\n"                                                                          \
         "45:\n"                                                                                         \
@@ -410,25 +408,24 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "  .set kvs_r, kvs_r+1\n"                                                                       \
         ".endr\n"                                                                                       \
         "46:\n"                                                                                         \
-        "s_add_u32 %[tb], %[tb], 1\n"        /* the first round not looked at yet */                    \
-        "s_xor_b32 %[ta], %[tb], %[x64]\n"                                                              \
-        "s_cmp_lt_u32 %[ta], 64\n"           /* in the window's last row? */                            \
+        "s_cmp_ge_u32 %[tb], %[off]\n"       /* are all rounds not looked at yet in the window's last row? */ \
         "s_cbranch_scc0 48f\n"                                                                          \
-        /* only the window's last row is new */                                                         \
-        "s_lshr_b32 %[ta], %[off], 1\n"      /* 32 (re + 1) */                                          \
-        "s_add_u32 s72, %[rl], %[ta]\n"                                                                 \
-        "s_addc_u32 s73, %[rh], 0\n"                                                                    \
-        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "s_add_u32 s66, %[rl], %[off]\n"                                                                \
+        "s_addc_u32 s67, %[rh], 0\n"                                                                    \
+        "s_setpc_b64 s[66:67]\n"                                                                        \
         "63:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
-        "  v_subrev_u32 %[y], %[ns], v[" KVS_PB "+\\r]\n"                                                  \
+        "  v_subrev_u32 %[y], %[ns], v[" KVS_PB "+\\r]\n"                                               \
         "  v_min_i32 %[y], 64*\\r, %[y]\n"                                                              \
         "  v_cndmask_b32_e64 %[acc], %[y], %[vmin], %[mk]\n"                                            \
-        "  s_branch 53f\n" KVS_SLOT_PAD(32)                                                             \
+        "  v_cmp_gt_i32 vcc, %[acc], %[tl]\n"                                                           \
+        "  s_cbranch_vccz 42b\n"                                                                        \
+        "  s_branch 44b\n" KVS_SLOT_PAD(64)                                                             \
         ".endr\n"                                                                                       \
         /* rows tb..tc, the last of them masked */                                                      \
         "48:\n"                                                                                         \
+        "s_add_u32 %[tb], %[tb], 1\n"                                                                   \
         "s_lshr_b32 %[tb], %[tb], 6\n"                                                                  \
         "s_sub_u32 %[tb], %[tb], 1\n"                                                                   \
         "s_lshr_b32 %[tc], %[x64], 6\n"                                                                 \
@@ -436,13 +433,13 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "v_mov_b32 %[acc], %[vmin]\n"                                                                   \
         "51:\n"                                                                                         \
         "s_cmp_eq_u32 %[tb], %[tc]\n"                                                                   \
-        "s_cselect_b64 %[m2], %[mk], 0\n"                                                               \
+        "s_cselect_b64 vcc, %[mk], 0\n"                                                                \
         "s_add_u32 %[ta], %[tb], 1\n"                                                                   \
         "s_lshl_b32 %[ta], %[ta], 4\n"       /* 16-byte slots, the first 16 bytes behind s_getpc's successor */ \
-        "s_getpc_b64 s[72:73]\n"                                                                        \
-        "s_add_u32 s72, s72, %[ta]\n"                                                                   \
-        "s_addc_u32 s73, s73, 0\n"                                                                      \
-        "s_setpc_b64 s[72:73]\n"                                                                        \
+        "s_getpc_b64 s[66:67]\n"                                                                        \
+        "s_add_u32 s66, s66, %[ta]\n"                                                                   \
+        "s_addc_u32 s67, s67, 0\n"                                                                      \
+        "s_setpc_b64 s[66:67]\n"                                                                        \
         ".fill 1, 4, 0xbf800000\n"                                                                      \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
@@ -451,7 +448,7 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "  s_branch 49f\n" KVS_SLOT_PAD(16)                                                             \
         ".endr\n"                                                                                       \
         "49:\n"                                                                                         \
-        "v_cndmask_b32_e64 %[y], %[y], %[vmin], %[m2]\n"                                                \
+        "v_cndmask_b32_e32 %[y], %[y], %[vmin], vcc\n"                                                 \
         "v_max_i32 %[acc], %[acc], %[y]\n"                                                              \
         "s_add_u32 %[tb], %[tb], 1\n"                                                                   \
         "s_cmp_le_u32 %[tb], %[tc]\n"                                                                   \
@@ -466,10 +463,10 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
           [ns] "=&s"(ns), [oj] "=&s"(oj), [x64] "=&s"(x64), [off] "=&s"(off), [u64] "=&s"(u64),         \
           [w] "=&s"(w), [rs] "=&s"(rs), [ta] "=&s"(ta), [tb] "=&s"(tb), [tc] "=&s"(tc), [ql] "=&s"(ql), \
           [qh] "=&s"(qh), [cl] "=&s"(cl), [ch] "=&s"(ch), [ul] "=&s"(ul), [uh] "=&s"(uh), [rl] "=&s"(rl), \
-          [rh] "=&s"(rh), [mk] "=&s"(mk), [m2] "=&s"(m2), [t] "+s"(t), [b64] "+s"(b64)                  \
+          [rh] "=&s"(rh), [mk] "=&s"(mk), [t] "+s"(t), [b64] "+s"(b64)                  \
         : [cnt] "s"(cnt), [vns] "v"(vns), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
           [M] "s"(M), [nr] "n"(NR)                                                                      \
-        : "scc", "vcc", "s72", "s73", CLOB)
+        : "scc", "vcc", "s66", "s67", CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
     return cv;
