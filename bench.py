@@ -35,13 +35,22 @@ if ROOT not in sys.path:
 # lane per clock (the fp32 vector peak of 157.3 TFLOP/s counts an FMA as two and packs two).
 PEAK_INT32_LANE_OPS = 256 * 4 * 16 * 2.4e9
 PEAK_HBM_BYTES = 8.0e12
-# Lane-ops the exact algorithm needs per slot visit (one future round inspected or updated for one
-# request) on a dense profile: the check of two rows (128 visits) is add, min, add, min and one
-# three-way max = 5 wave instructions, the update of two rows is two adds and one step of the shared
-# ramp = 3; (5 + 3) x 64 lanes / 256 visits = 2.  Everything else the kernel issues (masked last
-# rows, dead lanes of partial rows, per-request bookkeeping, moving the register file) is overhead
-# and is not credited, so the fraction below cannot exceed the share of issue slots the kernel uses.
-OPS_PER_VISIT = 2
+# Lane-ops no dense-profile kernel on this instruction set can do without.  A visit is one future
+# round of one request's window, inspected (the admission check, including the rounds that enter the
+# window while the request waits) or updated (the admitted request's memory added to the profile).
+#   * an inspected round has to be an operand of some vector instruction at least once, and an
+#     instruction takes at most two new operands next to its accumulator (v_max3_i32): 1/2 lane-op;
+#   * an updated round has to be written back by some vector instruction: 1 lane-op.
+# The kernel's row chains come to 1/2 and 3/2 (the ramp shared by two rows costs a step).  Everything
+# else it issues (the masked last row, dead lanes of partial rows, per-request bookkeeping, the second
+# pass with the rows' limits, moving the register file) is overhead and is not credited, so the
+# fraction below cannot exceed the share of issue slots the kernel uses.
+OPS_PER_INSPECTED = 0.5
+OPS_PER_UPDATED = 1.0
+# The credit in use before the admission check became a plain maximum over the rows (add, min per row
+# and a three-way maximum per two rows, two adds and a ramp step per two rows: 2 per visit); kept as
+# a second figure so that the kernels can be compared across that change.
+OPS_PER_VISIT_BEFORE = 2
 CFG = 3
 
 # What rocprofv3 counters measured for the dominant kernel of a workload (summaries and commands in
@@ -51,20 +60,21 @@ CFG = 3
 # null once those change.
 PROFILED = {
     # profiles/timeline_kernel_config3_traffic.md, timeline_kernel_config3_counters.md
-    "config3": {"traffic_bytes": int((47114.8 * 1.99974 + 89414.8 * 1.0) * 1024),
-                "issue": {"valu": 0.937, "scalar_and_branch": 0.828, "lane_slots_per_visit": 3.88,
+    "config3": {"traffic_bytes": int((47186.3 * 1.99974 + 89430.0 * 1.0) * 1024),
+                "issue": {"valu": 0.988, "scalar_and_branch": 0.823, "lane_slots_per_visit": 3.20,
                           "source": "profiles/timeline_kernel_config3_counters.md"}},
     # profiles/timeline_kernel_config5_rows65.md (one wavefront per SIMD)
     "config5": {"traffic_bytes": None,
-                "issue": {"valu": 0.415, "scalar_and_branch": 0.062, "lane_slots_per_visit": 2.25,
+                "issue": {"valu": 0.380, "scalar_and_branch": 0.080, "lane_slots_per_visit": 1.27,
                           "source": "profiles/timeline_kernel_config5_rows65.md"}},
-    # profiles/timeline_kernel_config4_moves.md (candidates' launches; saturated, the clock a little above nominal)
+    # profiles/timeline_kernel_config4_moves.md (candidates' launches; the counters give 1.07 vector
+    # instructions per SIMD and four nominal clocks: saturated)
     "config4": {"traffic_bytes": None,
-                "issue": {"valu": 1.0, "scalar_and_branch": 0.92, "lane_slots_per_visit": 3.65,
+                "issue": {"valu": 1.0, "scalar_and_branch": 0.91, "lane_slots_per_visit": 2.84,
                           "source": "profiles/timeline_kernel_config4_moves.md"}},
 }
 PROFILED_SOURCES = ("timeline_reg.hip", "device_util.h")
-PROFILED_SOURCES_SHA256 = "c8a5df4a44bc73d6"
+PROFILED_SOURCES_SHA256 = "a6f2bf669acd57b6"
 
 
 def _kernel_sources_hash() -> str:
@@ -145,11 +155,13 @@ def cpu_baseline_rows(inst, make_rows, C: int, tel_gpu, what: str):
     }
 
 
-def roofline_object(kernel: str, visits: int, kernel_ms_total: float, launches: int, workload: str, hbm_bytes: int,
-                    extra: dict | None = None):
-    """Integer-VALU roofline of the timeline kernel: credited lane-ops = OPS_PER_VISIT x visits."""
+def roofline_object(kernel: str, inspected: int, updated: int, kernel_ms_total: float, launches: int, workload: str,
+                    hbm_bytes: int, extra: dict | None = None):
+    """Integer-VALU roofline of the timeline kernel: credited lane-ops = inspected / 2 + updated."""
     secs = kernel_ms_total * 1e-3
-    achieved = OPS_PER_VISIT * visits / secs
+    visits = inspected + updated
+    ops = OPS_PER_INSPECTED * inspected + OPS_PER_UPDATED * updated
+    achieved = ops / secs
     traffic, issue = profiled(workload)
     obj = {
         "bound": "alu",
@@ -162,7 +174,10 @@ def roofline_object(kernel: str, visits: int, kernel_ms_total: float, launches: 
         "frac": achieved / PEAK_INT32_LANE_OPS,
         "traffic": traffic,
         "visits": visits,
-        "ops_per_visit": OPS_PER_VISIT,
+        "inspected": inspected,
+        "updated": updated,
+        "ops_per_visit": ops / visits,
+        "frac_at_two_ops_per_visit": OPS_PER_VISIT_BEFORE * visits / secs / PEAK_INT32_LANE_OPS,
         "issue_measured": issue,
         "hbm": {"algorithmic_bytes": hbm_bytes, "achieved_GBps": hbm_bytes / secs / 1e9,
                 "frac_of_8TBps": hbm_bytes / secs / PEAK_HBM_BYTES},
@@ -501,7 +516,8 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
     start0 = comp[0].to(torch.int64)[order0] - o_row0  # start rounds of row 0 by position
     cum0 = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev), torch.cumsum(o_row0, 0)])
     t_res = torch.where(resume > 0, start0[(resume - 1).clamp(min=0)], torch.zeros_like(resume))
-    visits = int(((p_last - t_res) + 2 * (sum_o - cum0[resume])).sum().item())
+    updated = int((sum_o - cum0[resume]).sum().item())
+    inspected = int((p_last - t_res).sum().item()) + updated
     visits_from_scratch = int((p_last + 2 * sum_o).sum().item())
     resumed_rows = int((resume > 0).sum().item())
     hbm_bytes = int((8 * (n - resume) + 8).sum().item()) + 8 * n  # order entries read, completion rounds written, from the resume point on
@@ -532,7 +548,8 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
         "gpu_ms_per_step": gpu_ms / args.steps,
         "timeline_kernel_ms": float(np.mean(kernel_ms)),
         "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
-        "roofline": roofline_object(kernel, visits * args.steps, float(np.sum(kernel_ms)), args.steps, f"config{cfg}",
+        "roofline": roofline_object(kernel, inspected * args.steps, updated * args.steps, float(np.sum(kernel_ms)), args.steps,
+                                    f"config{cfg}",
                                     hbm_bytes * args.steps,
                                     {"resumed_rows": resumed_rows, "visits_without_resume": visits_from_scratch}),
     }
@@ -609,7 +626,8 @@ def bench_horizon(args, ctx, dev) -> int:
     o_h = inst.o.astype(np.int64)
     rng = np.random.default_rng(4)
     order = order_d.cpu().numpy()
-    visits = 0
+    waited = 0   # rounds that entered a window while its request waited
+    window = 0   # rounds of the windows themselves: each inspected once and updated once
     hbm_bytes = 0
     for rec in log:
         moves = workloads.window_moves(rng, K, rec["lo"], rec["hi"])
@@ -621,13 +639,14 @@ def bench_horizon(args, ctx, dev) -> int:
         lowest = int(touched[~ident].min()) if (~ident).any() else n
         if lowest >= 64:  # common prefix placed once, every candidate starts behind it
             first = np.full(K + 1, lowest, dtype=np.int64)
-            visits += int(start[lowest - 1] + 2 * cum[lowest])  # the prefix itself
+            waited += int(start[lowest - 1])  # the prefix itself
+            window += int(cum[lowest])
         else:  # from the saved state of the move's block (identity moves: of the last block)
             first = np.where(ident, (n - 1) // 64 * 64, touched // 64 * 64).astype(np.int64)
             first = np.concatenate([first, [0]])  # the order as it stands runs from the start and saves the states
         t_first = np.where(first > 0, start[np.maximum(first - 1, 0)], 0)
-        visits += int(((start[-1] - t_first) + 2 * (cum[n] - cum[first])).sum())
-        visits += int(start[-1] + 2 * cum[n])  # the chosen order once more
+        waited += int((start[-1] - t_first).sum()) + int(start[-1])  # ... and the chosen order once more
+        window += int((cum[n] - cum[first]).sum()) + int(cum[n])
         hbm_bytes += 12 * K + 8 * (K + 1) + 12 * n
     kernel_ms_total = float(np.sum(timed.ms))
     launches = len(timed.ms)
@@ -653,7 +672,8 @@ def bench_horizon(args, ctx, dev) -> int:
         "candidate_launch_ms_per_replan": kernel_ms_total / launches,
         "final_tel": int(log[-1]["best_tel"]), "start_tel": int(log[0]["base_tel"]),
         "roofline": roofline_object(f"timeline_reg_kernel<{reg_rows(o_max)},4,true,...> (the candidates' launch of each re-plan)",
-                                    visits * args.steps, kernel_ms_total, launches, "config4", hbm_bytes * args.steps,
+                                    (waited + window) * args.steps, window * args.steps, kernel_ms_total, launches,
+                                    "config4", hbm_bytes * args.steps,
                                     {"note": "visits credited from each candidate's start point (common prefix or saved "
                                              "state of its block) on; the chosen timeline's start rounds stand in for the "
                                              "candidates' own"}),
