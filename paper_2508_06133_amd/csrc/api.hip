@@ -904,10 +904,13 @@ int kvsched_simulate_predicted(kvsched_ctx *ctx, const int32_t *orders, int32_t 
     if (bound > KVSCHED_MAX_O) return KVSCHED_ERANGE;
     const int32_t H = ring_slots_for(bound < 1 ? 1 : bound);
     if (kvs_predicted_lds_bytes(n, H) > KVS_PREDICTED_MAX_LDS) return KVSCHED_ERANGE;
-    rc = ensure_scratch(ctx, sizeof(int32_t) * (size_t)C);  // which candidates need the second launch
+    // which candidates need the second launch; the estimates that stopped requests keep (written before read)
+    const size_t retry_bytes = align256(sizeof(int32_t) * (size_t)C);
+    rc = ensure_scratch(ctx, retry_bytes + sizeof(uint16_t) * (size_t)C * (size_t)n);
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_predicted(orders, C, n, s, o, est0, E, (int32_t)M, H, 1 << 26, tel_out, completion_out,
-                              evictions_out, (int32_t *)ctx->d_scratch, ctx->d_words, st);
+                              evictions_out, (int32_t *)ctx->d_scratch, (uint16_t *)((char *)ctx->d_scratch + retry_bytes),
+                              ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
     return kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
 }

@@ -166,7 +166,7 @@ size_t kvs_predicted_lds_bytes(int32_t n, int32_t H);
 int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int32_t *s, const int32_t *o,
                          const int32_t *est0, int32_t E, int32_t M, int32_t H, int32_t round_limit, int64_t *tel_out,
                          int32_t *completion_out, int32_t *evictions_out, int32_t *retry /*[C] scratch*/,
-                         int32_t *d_words, hipStream_t st);
+                         uint16_t *est_stopped /*[C][n] scratch*/, int32_t *d_words, hipStream_t st);
 
 // prefix.hip
 int kvs_launch_moves_min_position(const int32_t *moves, int32_t K, int32_t n, int32_t *d_words, hipStream_t st);

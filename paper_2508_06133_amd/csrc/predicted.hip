@@ -17,23 +17,27 @@
 //   * the requests that have outrun their estimate are not in the ring: each of them reserves
 //     exactly the next round, s_j + (t + 1 - p_j), so two scalars (their count and the sum of
 //     s_j - p_j) give their share of round t + 1, and a round costs nothing per such request;
-//   * per position of the order only what changes and must outlive a stop: the current estimate
-//     (16 bits) and one bit "waits"; every position from `frontier` on waits (none of them was
-//     ever started), so the bits are looked at only after a request was stopped;
+//   * per position of the order only what changes and must outlive a stop: one bit "waits" (every
+//     position from `frontier` on waits and none of them was ever started, so the bits are looked
+//     at only after a request was stopped).  The estimate a stopped request keeps is needed twice
+//     per stop (written when it is stopped, read when it is looked at again), so it lives in
+//     global memory, 16 bits per position and candidate, written and read by the same wavefront;
+//     a position that was never started takes its estimate from est0;
 //   * the RUNNING requests as a compact unordered list of complete entries: three words
 //     {s, position | id, o | estimate} side by side (a stride of three words is free of bank
-//     conflicts) and, in arrays of their own, the low 16 bits of the start round (a running request
-//     started at most o <= 16384 rounds ago, so the round itself follows from the current one) and of
-//     the round at which the entry next matters (it reaches its estimate or its true length).  The
-//     pass that finds the due entries and the next due round reads that last array alone; an entry
-//     that finishes leaves a hole that the list's last entry fills.
+//     conflicts) and, in an array of its own, the low 16 bits of the round at which the entry next
+//     matters: it reaches its estimate or its true length, start + min(estimate, o), or start + o
+//     once it has outrun its estimate.  The start round follows from that (a running request
+//     started at most o <= 16384 rounds ago, so 16 bits and the current round give the round
+//     itself).  The pass that finds the due entries and the next due round reads that array alone;
+//     an entry that finishes leaves a hole that the list's last entry fills.
 // Lengths and ids of the waiting positions are not kept at all: admission walks the order from the
 // front, so the 64 positions around the first waiting one sit in registers (one position per lane,
 // fetched from the order row and the length tables when the walk leaves the window).
 // The list is what decides how many candidates fit a compute unit, and a wavefront here spends
 // most of its time waiting on its own dependent instructions, so twice the wavefronts per SIMD
 // is nearly twice the rate: a first launch runs every candidate with a list of at most `cap`
-// entries, sized so that eight candidates share a compute unit (two wavefronts per SIMD); a
+// entries, sized so that eight candidates share a compute unit (two wavefronts per SIMD: 20 KB each); a
 // candidate whose list overflows gives up and is run again by a second launch whose list holds
 // all n positions (three to four candidates per compute unit).
 // A blocked request is not re-examined round by round: the search over the ring gives the earliest
@@ -60,6 +64,7 @@ struct PredParams {
     int32_t cap;          // entries of the running list (even)
     int32_t second;       // 0: every candidate, overflow sets retry[c]; 1: only candidates with retry[c] != 0
     int32_t *retry;       // [C]
+    unsigned short *est_stopped;  // [C][n]: estimate kept by a stopped request, by position
     int32_t round_limit;  // a run that lasts longer is reported, not continued
     int64_t *tel_out;         // [C]
     int32_t *completion_out;  // [C][n] by request id, or NULL
@@ -95,13 +100,12 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     const int cand = blockIdx.x;
     if (p.second && p.retry[cand] == 0) return;
     const int n = p.n, M = p.M, H = p.H, HM = H - 1, cap = p.cap;
-    const int n2 = (n + 1) & ~1, stw = (n + 31) >> 5;
+    const int stw = (n + 31) >> 5;
     int *ring = lds;
     unsigned *WAIT = (unsigned *)(ring + H);           // bit k & 31 of word k >> 5: position k waits (below the frontier)
     int *LE = (int *)(WAIT + stw);                     // the running list, three words an entry: s, position | id << 16, o | estimate << 16
-    unsigned short *EST = (unsigned short *)(LE + 3 * cap);  // current estimate of every position
-    unsigned short *LPS = EST + n2;                    // start round of an entry, low 16 bits
-    unsigned short *LDUE = LPS + cap;                  // round it next matters at, low 16 bits
+    unsigned short *LDUE = (unsigned short *)(LE + 3 * cap);  // round an entry next matters at, low 16 bits
+    unsigned short *est_stopped = p.est_stopped + (size_t)cand * (size_t)n;
 
     const int32_t *row = p.orders + (size_t)cand * (size_t)n;
     const int32_t *est0 = p.est0 + (p.E > 1 ? (size_t)cand * (size_t)n : 0);
@@ -116,7 +120,6 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         if (sv < 1 || ov < 1 || ev < 1 || ov > H || ev > H || (long long)sv + ov > (long long)M ||
             (long long)sv + ev > (long long)M)
             bad = 1;
-        EST[k] = (unsigned short)ev;
     }
     if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // cannot be scheduled: report, do not loop forever
         if (lane == 0) {
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     p_sync();
 
     // the 64 positions [w_base, w_base + 64) of the order: lane l holds id, s, o of position w_base + l
-    int w_base = -PW, w_id = 0, w_s = 1, w_o = 1;
-    int x_base = -PW, x_id = 0, x_s = 1, x_o = 1;  // ... and the 64 behind them, fetched ahead of need
+    int w_base = -PW, w_id = 0, w_s = 1, w_o = 1, w_e = 1;
+    int x_base = -PW, x_id = 0, x_s = 1, x_o = 1, x_e = 1;  // ... and the 64 behind them, fetched ahead of need
     int frontier = 0;  // every position from here on waits and was never started
 
     int t = 0;
@@ -175,10 +178,11 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 while (m != 0) {
                     const int e = a0 + __builtin_ctzll(m);  // the entry
                     m &= m - 1;
-                    const int ps16 = LPS[e], s_r = LE[3 * e], oe_r = LE[3 * e + 2];  // three reads in flight
-                    const int ps_l = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(ps16));
+                    const int s_r = LE[3 * e], oe_r = LE[3 * e + 2];  // two reads in flight
                     const int oe_l = p_uni(oe_r), sv_l = p_uni(s_r);
                     const int ov_l = oe_l & 0xffff, ev_l = (int)((unsigned)oe_l >> 16);
+                    // due now: it started min(estimate, o) rounds ago, o rounds ago if it had outrun its estimate
+                    const int ps_l = t - (ev_l == EST_OVERRUN ? ov_l : min(ev_l, ov_l));
                     if (t - ps_l == ov_l) {  // finished
                         if (crow && lane == 0) crow[(unsigned)LE[3 * e + 1] >> 16] = t;
                         ++done;
@@ -215,7 +219,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                         --nact;
                         if (at != nact && lane == 0) {
                             LE[3 * at] = LE[3 * nact], LE[3 * at + 1] = LE[3 * nact + 1], LE[3 * at + 2] = LE[3 * nact + 2];
-                            LPS[at] = LPS[nact], LDUE[at] = LDUE[nact];
+                            LDUE[at] = LDUE[nact];
                         }
                         p_sync();
                     }
@@ -225,17 +229,19 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                         const int a = a0 + lane;
                         const bool in = a < nact;
                         const int e0 = in ? LE[3 * a] : 0, e1 = in ? LE[3 * a + 1] : 0, e2 = in ? LE[3 * a + 2] : 0;
-                        const int ps = in ? LPS[a] : 0, due = in ? LDUE[a] : 0;
-                        // finished: due now, and the start lies the true length back
+                        const int due = in ? LDUE[a] : 0;
+                        // finished: due now, and what it was due for is its true length (the entries that
+                        // went on past their estimate at this round were given a later due round above)
+                        const int ev = (int)((unsigned)e2 >> 16);
                         const bool fin = in && (unsigned short)due == (unsigned short)t &&
-                                         (unsigned short)((unsigned short)t - (unsigned short)ps) == (unsigned short)(e2 & 0xffff);
+                                         (ev == EST_OVERRUN || ev >= (e2 & 0xffff));
                         const bool keep = in && !fin;
                         const unsigned long long km = __builtin_amdgcn_ballot_w64(keep);
                         p_sync();
                         if (keep) {
                             const int to = kept + __popcll(km & ((1ull << lane) - 1ull));
                             LE[3 * to] = e0, LE[3 * to + 1] = e1, LE[3 * to + 2] = e2;
-                            LPS[to] = (unsigned short)ps, LDUE[to] = (unsigned short)due;
+                            LDUE[to] = (unsigned short)due;
                         }
                         kept += __popcll(km);
                         p_sync();
@@ -271,30 +277,33 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 if (hpos < w_base || hpos >= w_base + PW) {  // the 64 positions around it
                     const int base = hpos & ~(PW - 1);
                     if (base == x_base) {  // fetched ahead
-                        w_id = x_id, w_s = x_s, w_o = x_o;
+                        w_id = x_id, w_s = x_s, w_o = x_o, w_e = x_e;
                     } else {
                         const int k = base + lane;
-                        w_id = 0, w_s = 1, w_o = 1;
+                        w_id = 0, w_s = 1, w_o = 1, w_e = 1;
                         if (k < n) {
                             w_id = min(max(row[k], 0), n - 1);
                             w_s = p.s[w_id];
                             w_o = p.o[w_id];
+                            w_e = est0[w_id];
                         }
                     }
                     w_base = base;
                     x_base = base + PW;  // the loads for the next 64 are issued now and waited for when used
                     const int k = x_base + lane;
-                    x_id = 0, x_s = 1, x_o = 1;
+                    x_id = 0, x_s = 1, x_o = 1, x_e = 1;
                     if (k < n) {
                         x_id = min(max(row[k], 0), n - 1);
                         x_s = p.s[x_id];
                         x_o = p.o[x_id];
+                        x_e = est0[x_id];
                     }
                 }
                 hs = __builtin_amdgcn_readlane(w_s, hpos - w_base);
                 ho = __builtin_amdgcn_readlane(w_o, hpos - w_base);
                 hid = __builtin_amdgcn_readlane(w_id, hpos - w_base);
-                he = p_uni(EST[hpos]);
+                // a stopped request kept its estimate; one that never ran starts from est0
+                he = hpos < frontier ? p_uni((int)est_stopped[hpos]) : __builtin_amdgcn_readlane(w_e, hpos - w_base);
                 ring_start = 0;
             }
             if (t < ring_start) {  // the ring rules this round out (nothing was released since that was found)
@@ -339,7 +348,6 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
             if (lane == 0) {
                 if (hpos < frontier) WAIT[hpos >> 5] &= ~(1u << (hpos & 31));  // a stopped one starts again
                 LE[3 * nact] = hs, LE[3 * nact + 1] = hpos | (hid << 16), LE[3 * nact + 2] = ho | (he << 16);
-                LPS[nact] = (unsigned short)t;
                 LDUE[nact] = (unsigned short)(t + min(he, ho));
             }
             if (hpos >= frontier) frontier = hpos + 1;
@@ -360,8 +368,10 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 for (int a0 = 0; a0 < nact; a0 += PW) {
                     const int a = a0 + lane;
                     if (a < nact) {
-                        const int ev = (int)((unsigned)LE[3 * a + 2] >> 16);
-                        const int cur = ev == EST_OVERRUN ? (int)(unsigned short)((unsigned short)t - LPS[a]) + 1 : ev;
+                        const int oe = LE[3 * a + 2];
+                        const int ev = (int)((unsigned)oe >> 16);
+                        // past its estimate: it has run o - (due - t) rounds and needs one more
+                        const int cur = ev == EST_OVERRUN ? (oe & 0xffff) - (int)(unsigned short)(LDUE[a] - (unsigned short)t) + 1 : ev;
                         best = min(best, (cur << 16) | (int)((unsigned)LE[3 * a + 1] >> 16));
                     }
                 }
@@ -376,10 +386,11 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                     if (m != 0) slot = a0 + __builtin_ctzll(m);
                 }
                 if (slot < 0) break;
-                const int s_r = LE[3 * slot], pi_r = LE[3 * slot + 1], oe_r = LE[3 * slot + 2], ps16 = LPS[slot];
+                const int s_r = LE[3 * slot], pi_r = LE[3 * slot + 1], oe_r = LE[3 * slot + 2], due16 = LDUE[slot];
                 const int vpos = p_uni(pi_r) & 0xffff;
-                const int ps = t - (int)(unsigned short)((unsigned short)t - (unsigned short)p_uni(ps16));
-                const int ev = (int)((unsigned)p_uni(oe_r) >> 16), sv = p_uni(s_r);
+                const int ev = (int)((unsigned)p_uni(oe_r) >> 16), sv = p_uni(s_r), ov = p_uni(oe_r) & 0xffff;
+                const int due = t + (int)(unsigned short)((unsigned short)p_uni(due16) - (unsigned short)t);
+                const int ps = due - (ev == EST_OVERRUN ? ov : min(ev, ov));
                 if (ev == EST_OVERRUN) {
                     --ov_cnt;
                     ov_sp -= (long long)sv - ps;
@@ -389,11 +400,11 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 }
                 p_sync();
                 if (lane == 0) {
-                    EST[vpos] = (unsigned short)(ev == EST_OVERRUN ? t - ps + 1 : ev);  // what it is known to need
+                    est_stopped[vpos] = (unsigned short)(ev == EST_OVERRUN ? t - ps + 1 : ev);  // what it is known to need
                     WAIT[vpos >> 5] |= 1u << (vpos & 31);  // waits again
                     const int last = nact - 1;
                     LE[3 * slot] = LE[3 * last], LE[3 * slot + 1] = LE[3 * last + 1], LE[3 * slot + 2] = LE[3 * last + 2];
-                    LPS[slot] = LPS[last], LDUE[slot] = LDUE[last];
+                    LDUE[slot] = LDUE[last];
                 }
                 --nact;
                 if (vpos < head) { head = vpos; hpos = -1; }
@@ -479,8 +490,8 @@ int kvs_launch_scan_estimates(const int32_t *est, size_t count, int32_t *d_words
 // LDS of one candidate whose running list has `cap` entries.
 static size_t predicted_lds_bytes(int32_t n, int32_t H, int32_t cap)
 {
-    const size_t n2 = ((size_t)n + 1) & ~(size_t)1, stw = ((size_t)n + 31) >> 5;
-    return sizeof(int) * ((size_t)H + stw + 3 * (size_t)cap) + sizeof(unsigned short) * (n2 + 2 * (size_t)cap);
+    const size_t stw = ((size_t)n + 31) >> 5;
+    return sizeof(int) * ((size_t)H + stw + 3 * (size_t)cap) + sizeof(unsigned short) * (size_t)cap;
 }
 
 // ... with a list that holds every position: what a candidate may need at worst.
@@ -488,8 +499,8 @@ size_t kvs_predicted_lds_bytes(int32_t n, int32_t H) { return predicted_lds_byte
 
 int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int32_t *s, const int32_t *o,
                          const int32_t *est0, int32_t E, int32_t M, int32_t H, int32_t round_limit, int64_t *tel_out,
-                         int32_t *completion_out, int32_t *evictions_out, int32_t *retry, int32_t *d_words,
-                         hipStream_t st)
+                         int32_t *completion_out, int32_t *evictions_out, int32_t *retry, uint16_t *est_stopped,
+                         int32_t *d_words, hipStream_t st)
 {
     const int32_t cap_all = (n + 1) & ~1;
     const size_t bytes_all = predicted_lds_bytes(n, H, cap_all);
@@ -502,11 +513,11 @@ int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int3
             return KVSCHED_EHIP;
         lds_limit = bytes_all;
     }
-    // First launch: the longest list with which eight candidates share a compute unit's 160 KB; worth it
-    // when that is at least 128 entries and fewer than all.
-    const size_t budget = 26 * 1024;  // six to a compute unit: LDS is handed out in whole KB (measured: 26.5 KB each gives five)
+    // First launch: the longest list with which eight candidates share a compute unit's 160 KB (LDS is
+    // handed out in whole KB); worth it when that is at least 128 entries and fewer than all.
+    const size_t budget = 20 * 1024;
     const size_t fixed = predicted_lds_bytes(n, H, 0);
-    int32_t cap_first = fixed < budget ? (int32_t)((budget - fixed) / 16) & ~1 : 0;
+    int32_t cap_first = fixed < budget ? (int32_t)((budget - fixed) / 14) & ~1 : 0;
     PredParams p;
     p.orders = orders;
     p.C = C;
@@ -518,6 +529,7 @@ int kvs_launch_predicted(const int32_t *orders, int32_t C, int32_t n, const int3
     p.M = M;
     p.H = H;
     p.retry = retry;
+    p.est_stopped = est_stopped;
     p.round_limit = round_limit;
     p.tel_out = tel_out;
     p.completion_out = completion_out;

@@ -122,7 +122,7 @@ def test_faults(ctx):
         ctx.simulate_predicted(_to_dev([[0, 1, 2]] * 3), _to_dev(s), _to_dev(o), _to_dev([[2, 2, 2]] * 2), M)
     assert e.value.code == -1
     with pytest.raises(kvsched.KvschedError) as e:  # per-candidate state beyond the LDS of a workgroup
-        n = 11000
+        n = 12000
         ctx.simulate_predicted(_to_dev(np.arange(n)[None, :]), _to_dev(np.ones(n)), _to_dev(np.ones(n)),
                                _to_dev(np.ones(n)), 100)
     assert e.value.code == -2
