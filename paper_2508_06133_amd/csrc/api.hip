@@ -178,8 +178,11 @@ size_t state_bytes() { return align256(sizeof(int32_t) * KVS_STATE_MAX_WORDS); }
 
 // Run positions [0, cp) of `row0` once and leave the timeline state in `state`;
 // completion rounds of those positions (position order) go to prefix_completion if not NULL.
+// prefix_completion: completion rounds of the prefix, by position (by_id = 0: an array of cp entries) or by
+// request id (by_id = 1: a row of n entries of which the prefix's requests are written), or null.
 int run_shared_prefix(const int32_t *row0, int32_t cp, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
-                      int32_t o_bound, int32_t *d_words, int32_t *state, int32_t *prefix_completion, hipStream_t st)
+                      int32_t o_bound, int32_t *d_words, int32_t *state, int32_t *prefix_completion, hipStream_t st,
+                      int by_id = 0)
 {
     SimParams q;
     q.src.orders = row0;
@@ -192,7 +195,7 @@ int run_shared_prefix(const int32_t *row0, int32_t cp, int32_t n, const int32_t 
     q.M = (int32_t)M;
     q.tel_out = nullptr;
     q.completion_out = prefix_completion;
-    q.completion_by_position = 1;
+    q.completion_by_position = by_id ? 0 : 1;
     q.d_words = d_words;
     q.o_bound = o_bound;
     q.k_begin = 0;
@@ -672,9 +675,13 @@ size_t neighbor_scratch_bytes(int32_t K, int32_t n, int32_t o_bound)
 // o_bound_known > 0: the caller's bound on the decode lengths; nothing is read back from the device
 // (so the lowest position the moves touch is not known either and no common prefix is placed ahead:
 // moves far into the order start from the base order's saved states instead).
+// prefix_completion_by_id (with prefix_len_out, both optional): when a common prefix is placed ahead, its
+// requests' completion rounds go there (by request id) and its length is returned; the prefix's state stays
+// in the work area behind the latencies for the caller to resume from.
 static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known, const int32_t *base_order, int32_t n,
                             const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o, int64_t M,
-                            int64_t *tel_out, int64_t *result_out, hipStream_t st)
+                            int64_t *tel_out, int64_t *result_out, hipStream_t st,
+                            int32_t *prefix_completion_by_id = nullptr, int32_t *prefix_len_out = nullptr)
 {
     // work: [K+1] latencies (neighbours, then the base order) | state of the shared prefix | resume plan
     const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1));
@@ -708,10 +715,11 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
     // No move touches a position before min_pos: that prefix of the base order is common to
     // every neighbour, so it is placed once and all timelines resume from its state.
     if (min_pos >= kMinSharedPrefix && o_bound <= KVS_REG_MAX_O) {
-        rc = run_shared_prefix(base_order, min_pos, n, s, o, M, o_bound, ctx->d_words, state, nullptr, st);
+        rc = run_shared_prefix(base_order, min_pos, n, s, o, M, o_bound, ctx->d_words, state, prefix_completion_by_id, st, 1);
         if (rc != KVSCHED_OK) return rc;
         p.k_begin = min_pos;
         p.state_in = state;
+        if (prefix_len_out) *prefix_len_out = min_pos;
     }
     if (!p.state_in && ctx->resume_wait_polls > 0 && resume_pays(ctx, K + 1, n, o_bound)) {
         // Moves anywhere in the order (no prefix common to all): a move at positions i, j leaves the
@@ -795,21 +803,26 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
                          const int32_t *s, const int32_t *o, int64_t M, int64_t completed_in, int32_t complete_every,
                          int64_t *tel_out, int32_t *completion_out, int64_t *result_out, void *stream)
 {
-    if (!order || !result_out || completed_in < 0 || complete_every < 1) return KVSCHED_EINVAL;
-    if (K < 1 || K == INT32_MAX || n < 1) return KVSCHED_EINVAL;
+    int rc = check_common(ctx, n, s, o, M);
+    if (rc != KVSCHED_OK) return rc;
+    if (!order || !moves || !result_out || completed_in < 0 || complete_every < 1) return KVSCHED_EINVAL;
+    if (K < 1 || K == INT32_MAX) return KVSCHED_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     // scratch: [K+1] latencies of best_neighbor | new order [n] | completion rounds [n] | one latency
-    const size_t tel_bytes = neighbor_scratch_bytes(K, n, ctx ? ctx->o_max_bound : 0);  // best_neighbor's part
+    const size_t tel_bytes = neighbor_scratch_bytes(K, n, ctx->o_max_bound);  // best_neighbor's part
     const size_t row_bytes = align256(sizeof(int32_t) * (size_t)n);
-    int rc = ctx ? ensure_scratch(ctx, tel_bytes + 2 * row_bytes + 256) : KVSCHED_EINVAL;
-    if (rc != KVSCHED_OK) return rc;
-    // 1. best move of the window (result_out[0..2])
-    rc = kvsched_best_neighbor(ctx, order, n, moves, K, s, o, M, tel_out, result_out, stream);
+    rc = ensure_scratch(ctx, tel_bytes + 2 * row_bytes + 256);
     if (rc != KVSCHED_OK) return rc;
     char *base = (char *)ctx->d_scratch;
     int32_t *new_order = (int32_t *)(base + tel_bytes);
     int32_t *comp = completion_out ? completion_out : (int32_t *)(base + tel_bytes + row_bytes);
     int64_t *tel1 = (int64_t *)(base + tel_bytes + 2 * row_bytes);
+    // 1. best move of the window (result_out[0..2]).  When the positions before the window are placed once for
+    //    all moves, their completion rounds are kept and the state behind them serves the chosen order too.
+    int32_t prefix_len = 0;
+    rc = best_neighbor_on(ctx, ctx->d_scratch, ctx->o_max_bound, order, n, moves, K, s, o, M, tel_out, result_out, st,
+                          comp, &prefix_len);
+    if (rc != KVSCHED_OK) return rc;
     // 2. take it
     rc = kvs_launch_apply_best_move(order, n, moves, result_out, new_order, st);
     if (rc != KVSCHED_OK) return rc;
@@ -832,6 +845,10 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     p.completion_by_position = 0;
     p.d_words = ctx->d_words;
     p.o_bound = o_bound;
+    if (prefix_len > 0) {  // (only with the register kernel) no move touches these positions: the new order shares them
+        p.k_begin = prefix_len;
+        p.state_in = (const int32_t *)(base + align256(sizeof(int64_t) * ((size_t)K + 1)));
+    }
     rc = p.o_bound <= KVS_REG_MAX_O ? kvs_launch_simulate_reg(p, st)
                                     : kvs_launch_simulate(p, ring_slots_for(o_bound), st);
     if (rc != KVSCHED_OK) return rc;
