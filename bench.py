@@ -645,8 +645,12 @@ def bench_horizon(args, ctx, dev) -> int:
             first = np.where(ident, (n - 1) // 64 * 64, touched // 64 * 64).astype(np.int64)
             first = np.concatenate([first, [0]])  # the order as it stands runs from the start and saves the states
         t_first = np.where(first > 0, start[np.maximum(first - 1, 0)], 0)
-        waited += int((start[-1] - t_first).sum()) + int(start[-1])  # ... and the chosen order once more
-        window += int((cum[n] - cum[first]).sum()) + int(cum[n])
+        waited += int((start[-1] - t_first).sum())
+        window += int((cum[n] - cum[first]).sum())
+        # ... and the chosen order once more, from the common prefix's state on where there is one
+        chosen_first = lowest if lowest >= 64 else 0
+        waited += int(start[-1] - (start[chosen_first - 1] if chosen_first > 0 else 0))
+        window += int(cum[n] - cum[chosen_first])
         hbm_bytes += 12 * K + 8 * (K + 1) + 12 * n
     kernel_ms_total = float(np.sum(timed.ms))
     launches = len(timed.ms)
