@@ -19,6 +19,7 @@ a sample of the same candidates on this host, on one thread and on all cores.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -441,6 +442,10 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
     from paper_2508_06133_amd import workloads
 
     inst = workloads.instance(cfg)
+    scale = int(args.decode_scale)
+    if scale > 1:  # the same instance with decode lengths and budget scaled: the larger register files
+        inst = dataclasses.replace(inst, o=np.minimum(inst.o.astype(np.int64) * scale, 14336).astype(np.int32),
+                                   M=int(inst.M) * scale)
     n, M = inst.n, inst.M
     s = torch.from_numpy(inst.s).to(dev)
     o = torch.from_numpy(inst.o).to(dev)
@@ -529,7 +534,8 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
              5: "config 5: adversarial bimodal, n=100000, M=2097152, Sorted-F order (prefix scoring of every batch) "
                 "+ 1024 rows of 64 random swaps"}
     result = {
-        "metric": "candidate schedules evaluated/s (n=2000 mixed)" if cfg == 3
+        "metric": f"candidate schedules evaluated/s (config {cfg}, n={n}, decode lengths x {scale})" if scale > 1
+                  else "candidate schedules evaluated/s (n=2000 mixed)" if cfg == 3
                   else f"candidate schedules evaluated/s (config {cfg}, n={n})",
         "value": C * args.steps / wall,
         "unit": "candidates/s",
@@ -542,14 +548,14 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
         "vs_baseline": None,
         "dtype": "int32",
         "data": "synthetic",
-        "config": {"workload": names[cfg], "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item()),
-                   "phase1": args.phase1},
+        "config": {"workload": names[cfg] + (f"; decode lengths and budget x {scale} (o_max {o_max})" if scale > 1 else ""),
+                   "n": n, "M": M, "C": C, "sortedF_batches": int(nb_d.item()), "phase1": args.phase1},
         "request_rounds_per_s": C * sum_o * args.steps / wall,
         "gpu_ms_per_step": gpu_ms / args.steps,
         "timeline_kernel_ms": float(np.mean(kernel_ms)),
         "best_candidate": {"index": int(best[0].item()), "tel": int(best[1].item()), "base_tel": int(tel_h[0])},
         "roofline": roofline_object(kernel, inspected * args.steps, updated * args.steps, float(np.sum(kernel_ms)), args.steps,
-                                    f"config{cfg}",
+                                    f"config{cfg}" if scale == 1 else "scaled",
                                     hbm_bytes * args.steps,
                                     {"resumed_rows": resumed_rows, "visits_without_resume": visits_from_scratch}),
     }
@@ -716,6 +722,8 @@ def main() -> int:
                          "config-3 candidates run under interval predictions of the decode lengths "
                          "(kvsched_simulate_predicted, estimates started from the lower bounds); phase1: the "
                          "Phase-1 constructions (sorted prefix, Local Swap Search, exact batches) on configs 3, 4, 5")
+    ap.add_argument("--decode-scale", type=int, default=1,
+                    help="configs 1, 2, 3, 5: multiply decode lengths (capped at 14336) and the budget by this factor")
     ap.add_argument("--gamma", type=float, default=0.6, help="prediction confidence inf l_i / u_i of --workload predicted")
     ap.add_argument("--online-seeds", type=int, default=200,
                     help="arrival sequences per load level of the online workload (10 loads x 3 policies each)")
