@@ -74,6 +74,12 @@ struct PredParams {
 
 __device__ __forceinline__ int p_uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+__device__ __forceinline__ long long p_uni64(long long v)
+{
+    const int lo = __builtin_amdgcn_readfirstlane((int)v), hi = __builtin_amdgcn_readfirstlane((int)(v >> 32));
+    return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+
 __device__ __forceinline__ void p_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -135,6 +141,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     int w_base = -PW, w_id = 0, w_s = 1, w_o = 1, w_e = 1;
     int x_base = -PW, x_id = 0, x_s = 1, x_o = 1, x_e = 1;  // ... and the 64 behind them, fetched ahead of need
     int frontier = 0;  // every position from here on waits and was never started
+    int c_pos = -1, c_s = 0, c_o = 0, c_id = 0, c_e = 0;  // the request stopped last: position, lengths, id, estimate kept
 
     int t = 0;
     int head = 0;      // no waiting position lies before it
@@ -150,6 +157,14 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
     bool over_limit = false, overflow = false;
 
     while (done < n) {
+        // Everything the loop carries is the same in all lanes; saying so keeps it in scalar registers and the
+        // control flow on the scalar unit (left to itself the compiler treats much of it as per-lane data:
+        // copies of a dozen vector registers and an EXEC mask at every branch).
+        t = p_uni(t), head = p_uni(head), hpos = p_uni(hpos), hs = p_uni(hs), he = p_uni(he), ho = p_uni(ho), hid = p_uni(hid);
+        ring_start = p_uni(ring_start), nact = p_uni(nact), done = p_uni(done), ov_cnt = p_uni(ov_cnt), ov_sp = p_uni64(ov_sp);
+        next_due = p_uni(next_due), evictions = p_uni(evictions), tel = p_uni64(tel), frontier = p_uni(frontier);
+        c_pos = p_uni(c_pos), c_s = p_uni(c_s), c_o = p_uni(c_o), c_id = p_uni(c_id), c_e = p_uni(c_e);
+        w_base = p_uni(w_base), x_base = p_uni(x_base);
         if (t >= p.round_limit) { over_limit = true; break; }
         // nothing waits, nobody outruns an estimate: nothing can happen before the next due round
         if (head >= n && ov_cnt == 0 && next_due > t) {
@@ -176,7 +191,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 if (in && !now) wait_min = min(wait_min, wait);
                 unsigned long long m = __builtin_amdgcn_ballot_w64(now);
                 while (m != 0) {
-                    const int e = a0 + __builtin_ctzll(m);  // the entry
+                    const int e = p_uni(a0 + __builtin_ctzll(m));  // the entry
                     m &= m - 1;
                     const int s_r = LE[3 * e], oe_r = LE[3 * e + 2];  // two reads in flight
                     const int oe_l = p_uni(oe_r), sv_l = p_uni(s_r);
@@ -256,6 +271,8 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         const int ov_next = (int)(ov_sp + (long long)ov_cnt * (t + 1));  // the overrunners' share of round t + 1
         int t_skip = t + 1;  // the next round at which anything can happen
         while (head < n) {
+            head = p_uni(head), hpos = p_uni(hpos), frontier = p_uni(frontier), nact = p_uni(nact), next_due = p_uni(next_due);
+            ring_start = p_uni(ring_start), t_skip = p_uni(t_skip);
             if (hpos < 0) {  // first waiting position at or after head; kept while it stays blocked
                 if (head < frontier) {  // among the stopped ones: 32 positions a lane, 2048 a turn
                     for (int w0 = head >> 5; w0 < stw && hpos < 0; w0 += PW) {
@@ -272,38 +289,49 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 } else {
                     hpos = head;
                 }
+                hpos = p_uni(hpos);
                 if (hpos >= n) { hpos = -1; head = n; break; }
                 head = hpos;
-                if (hpos < w_base || hpos >= w_base + PW) {  // the 64 positions around it
-                    const int base = hpos & ~(PW - 1);
-                    if (base == x_base) {  // fetched ahead
-                        w_id = x_id, w_s = x_s, w_o = x_o, w_e = x_e;
-                    } else {
-                        const int k = base + lane;
-                        w_id = 0, w_s = 1, w_o = 1, w_e = 1;
+                if (hpos == c_pos) {
+                    // the request stopped last: what admission needs of it was at hand when it was stopped
+                    hs = c_s, ho = c_o, hid = c_id, he = c_e;
+                } else if (hpos < frontier) {
+                    // an older stopped one: fetched alone (two dependent loads), the window stays at the frontier
+                    hid = p_uni(min(max(row[hpos], 0), n - 1));
+                    hs = p_uni(p.s[hid]);
+                    ho = p_uni(p.o[hid]);
+                    he = p_uni((int)est_stopped[hpos]);  // a stopped request kept its estimate
+                } else {
+                    if (hpos < w_base || hpos >= w_base + PW) {  // the 64 positions around it
+                        const int base = hpos & ~(PW - 1);
+                        if (base == x_base) {  // fetched ahead
+                            w_id = x_id, w_s = x_s, w_o = x_o, w_e = x_e;
+                        } else {
+                            const int k = base + lane;
+                            w_id = 0, w_s = 1, w_o = 1, w_e = 1;
+                            if (k < n) {
+                                w_id = min(max(row[k], 0), n - 1);
+                                w_s = p.s[w_id];
+                                w_o = p.o[w_id];
+                                w_e = est0[w_id];
+                            }
+                        }
+                        w_base = base;
+                        x_base = base + PW;  // the loads for the next 64 are issued now and waited for when used
+                        const int k = x_base + lane;
+                        x_id = 0, x_s = 1, x_o = 1, x_e = 1;
                         if (k < n) {
-                            w_id = min(max(row[k], 0), n - 1);
-                            w_s = p.s[w_id];
-                            w_o = p.o[w_id];
-                            w_e = est0[w_id];
+                            x_id = min(max(row[k], 0), n - 1);
+                            x_s = p.s[x_id];
+                            x_o = p.o[x_id];
+                            x_e = est0[x_id];
                         }
                     }
-                    w_base = base;
-                    x_base = base + PW;  // the loads for the next 64 are issued now and waited for when used
-                    const int k = x_base + lane;
-                    x_id = 0, x_s = 1, x_o = 1, x_e = 1;
-                    if (k < n) {
-                        x_id = min(max(row[k], 0), n - 1);
-                        x_s = p.s[x_id];
-                        x_o = p.o[x_id];
-                        x_e = est0[x_id];
-                    }
+                    hs = __builtin_amdgcn_readlane(w_s, hpos - w_base);
+                    ho = __builtin_amdgcn_readlane(w_o, hpos - w_base);
+                    hid = __builtin_amdgcn_readlane(w_id, hpos - w_base);
+                    he = __builtin_amdgcn_readlane(w_e, hpos - w_base);  // one that never ran starts from est0
                 }
-                hs = __builtin_amdgcn_readlane(w_s, hpos - w_base);
-                ho = __builtin_amdgcn_readlane(w_o, hpos - w_base);
-                hid = __builtin_amdgcn_readlane(w_id, hpos - w_base);
-                // a stopped request kept its estimate; one that never ran starts from est0
-                he = hpos < frontier ? p_uni((int)est_stopped[hpos]) : __builtin_amdgcn_readlane(w_e, hpos - w_base);
                 ring_start = 0;
             }
             if (t < ring_start) {  // the ring rules this round out (nothing was released since that was found)
@@ -399,8 +427,10 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                     ring_start = 0;  // memory released
                 }
                 p_sync();
+                c_pos = vpos, c_s = sv, c_o = ov, c_id = (int)((unsigned)p_uni(pi_r) >> 16);
+                c_e = ev == EST_OVERRUN ? t - ps + 1 : ev;  // what it is known to need
                 if (lane == 0) {
-                    est_stopped[vpos] = (unsigned short)(ev == EST_OVERRUN ? t - ps + 1 : ev);  // what it is known to need
+                    est_stopped[vpos] = (unsigned short)c_e;
                     WAIT[vpos >> 5] |= 1u << (vpos & 31);  // waits again
                     const int last = nact - 1;
                     LE[3 * slot] = LE[3 * last], LE[3 * slot + 1] = LE[3 * last + 1], LE[3 * slot + 2] = LE[3 * last + 2];
