@@ -193,13 +193,13 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 while (m != 0) {
                     const int e = p_uni(a0 + __builtin_ctzll(m));  // the entry
                     m &= m - 1;
-                    const int s_r = LE[3 * e], oe_r = LE[3 * e + 2];  // two reads in flight
+                    const int s_r = LE[3 * e], pi_r = LE[3 * e + 1], oe_r = LE[3 * e + 2];  // three reads in flight
                     const int oe_l = p_uni(oe_r), sv_l = p_uni(s_r);
                     const int ov_l = oe_l & 0xffff, ev_l = (int)((unsigned)oe_l >> 16);
                     // due now: it started min(estimate, o) rounds ago, o rounds ago if it had outrun its estimate
                     const int ps_l = t - (ev_l == EST_OVERRUN ? ov_l : min(ev_l, ov_l));
                     if (t - ps_l == ov_l) {  // finished
-                        if (crow && lane == 0) crow[(unsigned)LE[3 * e + 1] >> 16] = t;
+                        if (crow && lane == 0) crow[(unsigned)pi_r >> 16] = t;
                         ++done;
                         tel += t;
                         if (holes < MAX_HOLES) hole_at = lane == holes ? e : hole_at;
@@ -229,15 +229,19 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 if (holes <= MAX_HOLES) {
                     // fill each hole with the list's last entry, the hole furthest back first: the last
                     // entry is then never a hole that is still to be filled
+                    // (lane 0 alone moves the entries: its reads and writes stay in order; the four reads
+                    // of a move go out together)
                     for (int h = holes - 1; h >= 0; --h) {
                         const int at = __builtin_amdgcn_readlane(hole_at, h);
                         --nact;
                         if (at != nact && lane == 0) {
-                            LE[3 * at] = LE[3 * nact], LE[3 * at + 1] = LE[3 * nact + 1], LE[3 * at + 2] = LE[3 * nact + 2];
-                            LDUE[at] = LDUE[nact];
+                            const int e0 = LE[3 * nact], e1 = LE[3 * nact + 1], e2 = LE[3 * nact + 2];
+                            const unsigned short due = LDUE[nact];
+                            LE[3 * at] = e0, LE[3 * at + 1] = e1, LE[3 * at + 2] = e2;
+                            LDUE[at] = due;
                         }
-                        p_sync();
                     }
+                    p_sync();
                 } else {  // (more than a tile of requests finishing in one round) close the list up: the due ones that have finished go
                     int kept = 0;
                     for (int a0 = 0; a0 < nact; a0 += PW) {
@@ -433,8 +437,10 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                     est_stopped[vpos] = (unsigned short)c_e;
                     WAIT[vpos >> 5] |= 1u << (vpos & 31);  // waits again
                     const int last = nact - 1;
-                    LE[3 * slot] = LE[3 * last], LE[3 * slot + 1] = LE[3 * last + 1], LE[3 * slot + 2] = LE[3 * last + 2];
-                    LDUE[slot] = LDUE[last];
+                    const int e0 = LE[3 * last], e1 = LE[3 * last + 1], e2 = LE[3 * last + 2];
+                    const unsigned short due_last = LDUE[last];
+                    LE[3 * slot] = e0, LE[3 * slot + 1] = e1, LE[3 * slot + 2] = e2;
+                    LDUE[slot] = due_last;
                 }
                 --nact;
                 if (vpos < head) { head = vpos; hpos = -1; }
