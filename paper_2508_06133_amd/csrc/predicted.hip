@@ -342,6 +342,9 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 if (ov_cnt == 0) t_skip = min(ring_start, next_due);
                 break;
             }
+            // The requests past their estimate hold round t + 1 as well; that test is one slot of the ring, so it
+            // goes first (when it fails no request starts this round, whatever the ring's reservations say).
+            if (ov_cnt > 0 && p_uni(ring[(t + 1) & HM]) + ov_next + hs + 1 > M) break;
             // a start at t against the reservations in the ring
             // (two tiles of 64 rounds a turn, their reads in flight together; a slot behind the window is read and ignored)
             bool viol = false;
@@ -372,9 +375,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 if (ov_cnt == 0) t_skip = min(start, next_due);  // nothing happens before
                 break;
             }
-            ring_start = t;
-            // the ring allows a start now; the requests past their estimate also hold round t + 1
-            if (ov_cnt > 0 && p_uni(ring[(t + 1) & HM]) + ov_next + hs + 1 > M) break;
+            ring_start = t;  // the ring allows a start now
             if (nact == cap) { overflow = true; break; }  // (first launch only: the second one's list holds every position)
             for (int j = lane + 1; j <= he; j += PW) ring[(t + j) & HM] += hs + j;
             if (lane == 0) {
