@@ -397,7 +397,7 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
         if (ov_cnt > 0) {
             p_sync();
             while (p_uni(ring[(t + 1) & HM]) + (int)(ov_sp + (long long)ov_cnt * (t + 1)) > M) {
-                int best = INT_MAX;  // (current estimate, id) of the running requests, least first
+                int best = INT_MAX, best_at = -1;  // (current estimate, id) of the running requests, least first, and its place
                 for (int a0 = 0; a0 < nact; a0 += PW) {
                     const int a = a0 + lane;
                     if (a < nact) {
@@ -405,19 +405,15 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                         const int ev = (int)((unsigned)oe >> 16);
                         // past its estimate: it has run o - (due - t) rounds and needs one more
                         const int cur = ev == EST_OVERRUN ? (oe & 0xffff) - (int)(unsigned short)(LDUE[a] - (unsigned short)t) + 1 : ev;
-                        best = min(best, (cur << 16) | (int)((unsigned)LE[3 * a + 1] >> 16));
+                        const int key = (cur << 16) | (int)((unsigned)LE[3 * a + 1] >> 16);
+                        if (key < best) best = key, best_at = a;
                     }
                 }
-                best = p_wave_min(best);
-                if (best == INT_MAX) break;  // cannot happen: an empty system holds nothing
-                // find it in the list again (ids of a permutation are distinct)
-                int slot = -1;
-                for (int a0 = 0; a0 < nact && slot < 0; a0 += PW) {
-                    const int a = a0 + lane;
-                    const unsigned long long m =
-                        __builtin_amdgcn_ballot_w64(a < nact && (int)((unsigned)LE[3 * a + 1] >> 16) == (best & 0xffff));
-                    if (m != 0) slot = a0 + __builtin_ctzll(m);
-                }
+                const int least = p_wave_min(best);
+                if (least == INT_MAX) break;  // cannot happen: an empty system holds nothing
+                // ids of a permutation are distinct: one lane holds it
+                const unsigned long long holder = __builtin_amdgcn_ballot_w64(best == least);
+                const int slot = __builtin_amdgcn_readlane(best_at, __builtin_ctzll(holder));
                 if (slot < 0) break;
                 const int s_r = LE[3 * slot], pi_r = LE[3 * slot + 1], oe_r = LE[3 * slot + 2], due16 = LDUE[slot];
                 const int vpos = p_uni(pi_r) & 0xffff;
