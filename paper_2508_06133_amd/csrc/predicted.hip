@@ -345,15 +345,24 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
             // The requests past their estimate hold round t + 1 as well; that test is one slot of the ring, so it
             // goes first (when it fails no request starts this round, whatever the ring's reservations say).
             if (ov_cnt > 0 && p_uni(ring[(t + 1) & HM]) + ov_next + hs + 1 > M) break;
-            // a start at t against the reservations in the ring
-            // (two tiles of 64 rounds a turn, their reads in flight together; a slot behind the window is read and ignored)
+            if (nact == cap) { overflow = true; break; }  // (first launch only: the second one's list holds every position)
+            // A start at t against the reservations in the ring, the request's own entered in the same pass and
+            // taken back if some round cannot hold them (rare: the ring's verdict is known for a blocked request).
+            // Two tiles of 64 rounds a turn, their reads in flight together; a slot behind the window is read
+            // and left alone.  Every lane touches only its own slots until the wavefront meets again.
             bool viol = false;
             for (int j = lane + 1; j <= he; j += 2 * PW) {
-                const int r0 = ring[(t + j) & HM], r1 = ring[(t + j + PW) & HM];
-                viol |= r0 + hs + j > M;
-                viol |= j + PW <= he && r1 + hs + j + PW > M;
+                const int i0 = (t + j) & HM, i1 = (t + j + PW) & HM;
+                const int r0 = ring[i0] + hs + j, r1 = ring[i1] + hs + j + PW;
+                const bool in1 = j + PW <= he;
+                viol |= r0 > M;
+                viol |= in1 && r1 > M;
+                ring[i0] = r0;
+                if (in1) ring[i1] = r1;
             }
             if (__builtin_amdgcn_ballot_w64(viol) != 0) {
+                for (int j = lane + 1; j <= he; j += PW) ring[(t + j) & HM] -= hs + j;
+                p_sync();
                 // Blocked by them.  They change only by admissions (none while this request is blocked)
                 // and releases, so they are searched once for the earliest start they allow: round tq
                 // rules out the starts t' < tq with t' < ring(tq) + s + tq - M; rounds more than H ahead
@@ -376,8 +385,6 @@ __global__ __launch_bounds__(PW) void predicted_kernel(PredParams p)
                 break;
             }
             ring_start = t;  // the ring allows a start now
-            if (nact == cap) { overflow = true; break; }  // (first launch only: the second one's list holds every position)
-            for (int j = lane + 1; j <= he; j += PW) ring[(t + j) & HM] += hs + j;
             if (lane == 0) {
                 if (hpos < frontier) WAIT[hpos >> 5] &= ~(1u << (hpos & 31));  // a stopped one starts again
                 LE[3 * nact] = hs, LE[3 * nact + 1] = hpos | (hid << 16), LE[3 * nact + 2] = ho | (he << 16);
