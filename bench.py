@@ -635,6 +635,7 @@ def bench_horizon(args, ctx, dev) -> int:
     waited = 0   # rounds that entered a window while its request waited
     window = 0   # rounds of the windows themselves: each inspected once and updated once
     hbm_bytes = 0
+    kept_prefix = 0
     for rec in log:
         moves = workloads.window_moves(rng, K, rec["lo"], rec["hi"])
         touched = np.minimum(moves[:, 1], moves[:, 2])
@@ -645,9 +646,13 @@ def bench_horizon(args, ctx, dev) -> int:
         lowest = int(touched[~ident].min()) if (~ident).any() else n
         if lowest >= 64:  # common prefix placed once, every candidate starts behind it
             first = np.full(K + 1, lowest, dtype=np.int64)
-            waited += int(start[lowest - 1])  # the prefix itself
-            window += int(cum[lowest])
+            # the prefix itself: continued from the state the step before left behind its own prefix
+            kept = kept_prefix if 64 <= kept_prefix <= lowest else 0
+            waited += int(start[lowest - 1] - (start[kept - 1] if kept > 0 else 0))
+            window += int(cum[lowest] - cum[kept])
+            kept_prefix = lowest
         else:  # from the saved state of the move's block (identity moves: of the last block)
+            kept_prefix = 0
             first = np.where(ident, (n - 1) // 64 * 64, touched // 64 * 64).astype(np.int64)
             first = np.concatenate([first, [0]])  # the order as it stands runs from the start and saves the states
         t_first = np.where(first > 0, start[np.maximum(first - 1, 0)], 0)

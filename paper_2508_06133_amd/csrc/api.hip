@@ -176,13 +176,53 @@ __global__ void kvs_fill_zero_i32(int32_t *dst, int32_t n)
 }
 size_t state_bytes() { return align256(sizeof(int32_t) * KVS_STATE_MAX_WORDS); }
 
+// The horizon step's own buffer (kept between steps): state | order copy | s copy | o copy | completion by position | flag.
+struct HorizonBuffers {
+    int32_t *state, *order, *s, *o, *comp_pos, *ok;
+};
+
+size_t horizon_row_bytes(int32_t n) { return align256(sizeof(int32_t) * (size_t)n); }
+
+HorizonBuffers horizon_buffers(kvsched_ctx *ctx, int32_t n)
+{
+    char *b = (char *)ctx->d_horizon;
+    const size_t row = horizon_row_bytes(n);
+    HorizonBuffers h;
+    h.state = (int32_t *)b;
+    h.order = (int32_t *)(b + state_bytes());
+    h.s = (int32_t *)(b + state_bytes() + row);
+    h.o = (int32_t *)(b + state_bytes() + 2 * row);
+    h.comp_pos = (int32_t *)(b + state_bytes() + 3 * row);
+    h.ok = (int32_t *)(b + state_bytes() + 4 * row);
+    return h;
+}
+
+// (growing it forgets what was kept)
+int ensure_horizon(kvsched_ctx *ctx, int32_t n)
+{
+    const size_t bytes = state_bytes() + 4 * horizon_row_bytes(n) + 256;
+    if (bytes <= ctx->horizon_bytes) return KVSCHED_OK;
+    ctx->hz_len = 0;
+    if (ctx->d_horizon) {
+        if (hipDeviceSynchronize() != hipSuccess) return KVSCHED_EHIP;
+        (void)hipFree(ctx->d_horizon);
+        ctx->d_horizon = nullptr;
+        ctx->horizon_bytes = 0;
+    }
+    if (hipMalloc(&ctx->d_horizon, bytes) != hipSuccess) return KVSCHED_ENOMEM;
+    ctx->horizon_bytes = bytes;
+    return KVSCHED_OK;
+}
+
+
 // Run positions [0, cp) of `row0` once and leave the timeline state in `state`;
 // completion rounds of those positions (position order) go to prefix_completion if not NULL.
 // prefix_completion: completion rounds of the prefix, by position (by_id = 0: an array of cp entries) or by
 // request id (by_id = 1: a row of n entries of which the prefix's requests are written), or null.
+// from_len > 0: state holds the timeline after the first from_len positions; they are skipped if *resume_ok != 0.
 int run_shared_prefix(const int32_t *row0, int32_t cp, int32_t n, const int32_t *s, const int32_t *o, int64_t M,
                       int32_t o_bound, int32_t *d_words, int32_t *state, int32_t *prefix_completion, hipStream_t st,
-                      int by_id = 0)
+                      int by_id = 0, int32_t from_len = 0, const int32_t *resume_ok = nullptr)
 {
     SimParams q;
     q.src.orders = row0;
@@ -201,6 +241,11 @@ int run_shared_prefix(const int32_t *row0, int32_t cp, int32_t n, const int32_t 
     q.k_begin = 0;
     q.k_end = cp;
     q.state_out = state;
+    if (from_len > 0 && resume_ok) {
+        q.k_begin = from_len;
+        q.state_in = state;
+        q.resume_ok = resume_ok;
+    }
     return kvs_launch_simulate_reg(q, st);
 }
 
@@ -235,6 +280,10 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->static_scratch = nullptr;
     ctx->d_tables = nullptr;
     ctx->tables_bytes = 0;
+    ctx->d_horizon = nullptr;
+    ctx->horizon_bytes = 0;
+    ctx->hz_n = ctx->hz_len = ctx->hz_o_bound = 0;
+    ctx->hz_M = 0;
     ctx->timing = 0;
     ctx->timed = 0;
     ctx->resume_rows = 0;
@@ -270,6 +319,7 @@ void kvsched_destroy(kvsched_ctx *ctx)
     if (ctx->h_words) (void)hipHostFree(ctx->h_words);
     if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
     if (ctx->d_tables) (void)hipFree(ctx->d_tables);
+    if (ctx->d_horizon) (void)hipFree(ctx->d_horizon);
     if (ctx->ev0) (void)hipEventDestroy(ctx->ev0);
     if (ctx->ev1) (void)hipEventDestroy(ctx->ev1);
     delete ctx;
@@ -675,13 +725,16 @@ size_t neighbor_scratch_bytes(int32_t K, int32_t n, int32_t o_bound)
 // o_bound_known > 0: the caller's bound on the decode lengths; nothing is read back from the device
 // (so the lowest position the moves touch is not known either and no common prefix is placed ahead:
 // moves far into the order start from the base order's saved states instead).
-// prefix_completion_by_id (with prefix_len_out, both optional): when a common prefix is placed ahead, its
-// requests' completion rounds go there (by request id) and its length is returned; the prefix's state stays
-// in the work area behind the latencies for the caller to resume from.
+// For kvsched_horizon_step (keep != nullptr, with prefix_completion_by_id and prefix_len_out): when a common
+// prefix is placed ahead, its state is left in the horizon buffers, its requests' completion rounds go to
+// prefix_completion_by_id and its length is returned.  If the buffers hold the state of a shorter prefix from
+// the step before (ctx->hz_len positions, same n, M and decode bound), the prefix run starts there, provided the
+// order up to there and the lengths still equal the copies kept with it (compared on the device).
 static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known, const int32_t *base_order, int32_t n,
                             const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o, int64_t M,
                             int64_t *tel_out, int64_t *result_out, hipStream_t st,
-                            int32_t *prefix_completion_by_id = nullptr, int32_t *prefix_len_out = nullptr)
+                            const HorizonBuffers *keep = nullptr, int32_t *prefix_completion_by_id = nullptr,
+                            int32_t *prefix_len_out = nullptr)
 {
     // work: [K+1] latencies (neighbours, then the base order) | state of the shared prefix | resume plan
     const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1));
@@ -715,11 +768,30 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
     // No move touches a position before min_pos: that prefix of the base order is common to
     // every neighbour, so it is placed once and all timelines resume from its state.
     if (min_pos >= kMinSharedPrefix && o_bound <= KVS_REG_MAX_O) {
-        rc = run_shared_prefix(base_order, min_pos, n, s, o, M, o_bound, ctx->d_words, state, prefix_completion_by_id, st, 1);
-        if (rc != KVSCHED_OK) return rc;
+        if (keep) {
+            int32_t from = 0;
+            if (ctx->hz_len >= kMinSharedPrefix && ctx->hz_len <= min_pos && ctx->hz_n == n && ctx->hz_M == M &&
+                ctx->hz_o_bound == o_bound)
+                from = ctx->hz_len;
+            ctx->hz_len = 0;  // (until this step has left its own)
+            rc = kvs_launch_horizon_verify(base_order, s, o, n, from, min_pos, keep->order, keep->s, keep->o, keep->ok, st);
+            if (rc != KVSCHED_OK) return rc;
+            state = keep->state;
+            rc = run_shared_prefix(base_order, min_pos, n, s, o, M, o_bound, ctx->d_words, state, keep->comp_pos, st, 0,
+                                   from, keep->ok);
+            if (rc != KVSCHED_OK) return rc;
+            rc = kvs_launch_scatter_prefix(base_order, keep->comp_pos, min_pos, n, prefix_completion_by_id, st);
+            if (rc != KVSCHED_OK) return rc;
+            ctx->hz_len = min_pos, ctx->hz_n = n, ctx->hz_M = M, ctx->hz_o_bound = o_bound;
+        } else {
+            rc = run_shared_prefix(base_order, min_pos, n, s, o, M, o_bound, ctx->d_words, state, nullptr, st);
+            if (rc != KVSCHED_OK) return rc;
+        }
         p.k_begin = min_pos;
         p.state_in = state;
         if (prefix_len_out) *prefix_len_out = min_pos;
+    } else if (keep) {
+        ctx->hz_len = 0;
     }
     if (!p.state_in && ctx->resume_wait_polls > 0 && resume_pays(ctx, K + 1, n, o_bound)) {
         // Moves anywhere in the order (no prefix common to all): a move at positions i, j leaves the
@@ -819,10 +891,16 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     int64_t *tel1 = (int64_t *)(base + tel_bytes + 2 * row_bytes);
     // 1. best move of the window (result_out[0..2]).  When the positions before the window are placed once for
     //    all moves, their completion rounds are kept and the state behind them serves the chosen order too.
+    rc = ensure_horizon(ctx, n);
+    if (rc != KVSCHED_OK) return rc;
+    const HorizonBuffers keep = horizon_buffers(ctx, n);
     int32_t prefix_len = 0;
     rc = best_neighbor_on(ctx, ctx->d_scratch, ctx->o_max_bound, order, n, moves, K, s, o, M, tel_out, result_out, st,
-                          comp, &prefix_len);
-    if (rc != KVSCHED_OK) return rc;
+                          &keep, comp, &prefix_len);
+    if (rc != KVSCHED_OK) {
+        ctx->hz_len = 0;
+        return rc;
+    }
     // 2. take it
     rc = kvs_launch_apply_best_move(order, n, moves, result_out, new_order, st);
     if (rc != KVSCHED_OK) return rc;
@@ -847,7 +925,7 @@ int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int3
     p.o_bound = o_bound;
     if (prefix_len > 0) {  // (only with the register kernel) no move touches these positions: the new order shares them
         p.k_begin = prefix_len;
-        p.state_in = (const int32_t *)(base + align256(sizeof(int64_t) * ((size_t)K + 1)));
+        p.state_in = keep.state;
     }
     rc = p.o_bound <= KVS_REG_MAX_O ? kvs_launch_simulate_reg(p, st)
                                     : kvs_launch_simulate(p, ring_slots_for(o_bound), st);

@@ -87,6 +87,40 @@ __global__ __launch_bounds__(1024) void horizon_advance_kernel(const int32_t *or
     }
 }
 
+
+// One workgroup.  ok[0] = 1 iff the first old_len entries of the order and all lengths equal their copies;
+// afterwards the copies hold order[0 .. new_len), s and o.
+__global__ __launch_bounds__(1024) void horizon_verify_kernel(const int32_t *order, const int32_t *s, const int32_t *o,
+                                                              int32_t n, int32_t old_len, int32_t new_len,
+                                                              int32_t *order_copy, int32_t *s_copy, int32_t *o_copy,
+                                                              int32_t *ok)
+{
+    int same = 1;
+    for (int i = threadIdx.x; i < n; i += 1024) {
+        const int sv = s[i], ov = o[i];
+        same &= (sv == s_copy[i]) & (ov == o_copy[i]);
+        s_copy[i] = sv;
+        o_copy[i] = ov;
+    }
+    for (int k = threadIdx.x; k < new_len; k += 1024) {
+        const int id = order[k];
+        if (k < old_len) same &= id == order_copy[k];
+        order_copy[k] = id;
+    }
+    const int all = __syncthreads_and(same);
+    if (threadIdx.x == 0) ok[0] = all ? 1 : 0;
+}
+
+__global__ void scatter_prefix_kernel(const int32_t *order, const int32_t *by_position, int32_t len, int32_t n,
+                                      int32_t *completion_by_id)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < len) {
+        const int id = order[k];
+        if (id >= 0 && id < n) completion_by_id[id] = by_position[k];
+    }
+}
+
 }  // namespace
 
 int kvs_launch_apply_best_move(const int32_t *order, int32_t n, const int32_t *moves, const int64_t *result,
@@ -102,5 +136,23 @@ int kvs_launch_horizon_advance(const int32_t *order, const int32_t *completion, 
 {
     hipLaunchKernelGGL(horizon_advance_kernel, dim3(1), dim3(1024), 0, st, order, completion, o, n,
                        (long long)completed_in, complete_every, result_out);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_horizon_verify(const int32_t *order, const int32_t *s, const int32_t *o, int32_t n, int32_t old_len,
+                              int32_t new_len, int32_t *order_copy, int32_t *s_copy, int32_t *o_copy, int32_t *ok,
+                              hipStream_t st)
+{
+    hipLaunchKernelGGL(horizon_verify_kernel, dim3(1), dim3(1024), 0, st, order, s, o, n, old_len, new_len, order_copy,
+                       s_copy, o_copy, ok);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_scatter_prefix(const int32_t *order, const int32_t *by_position, int32_t len, int32_t n,
+                              int32_t *completion_by_id, hipStream_t st)
+{
+    if (len < 1) return KVSCHED_OK;
+    hipLaunchKernelGGL(scatter_prefix_kernel, dim3((unsigned)((len + 255) / 256)), dim3(256), 0, st, order, by_position,
+                       len, n, completion_by_id);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }

@@ -36,6 +36,12 @@ struct kvsched_ctx {
     int32_t resume_min_rows;  // kvsched_simulate resumes rows from row 0's snapshots from this many rows on
     int32_t resume_wait_polls;  // ... in one launch, a row waiting at most so many polls for its snapshot; 0: in two launches
     hipEvent_t ev0, ev1;
+    // kvsched_horizon_step: the state behind the positions no move touched at the last step, with what it was
+    // computed from (copies of the order's prefix and of the lengths, compared on the device before use)
+    void *d_horizon;          // state | order copy [n] | s copy [n] | o copy [n] | completion rounds by position [n] | flag
+    size_t horizon_bytes;
+    int32_t hz_n, hz_len, hz_o_bound;  // hz_len = 0: nothing kept
+    int64_t hz_M;
 };
 
 // How a candidate's order is presented to the timeline kernel.
@@ -65,6 +71,8 @@ struct SimParams {
     int32_t k_end = 0;
     const int32_t *state_in = nullptr;
     int32_t *state_out = nullptr;
+    // ... unless *resume_ok == 0 (when set): then from position 0 and an empty timeline after all
+    const int32_t *resume_ok = nullptr;
     // Register kernel, explicit rows only: resuming rows from snapshots of row 0.  When cand_list is
     // set, wave w of the launch runs candidate cand_list[w].  Snapshot j (j >= 1) is the timeline
     // state of row 0 after 64 j positions, at snapshots + (j - 1) * snap_stride.  The wave that runs
@@ -103,6 +111,14 @@ int32_t kvs_reg_state_words(int32_t o_bound);  // words of one snapshot for this
 
 int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t *tel_out, int32_t *d_words,
                             hipStream_t st);
+// horizon.hip: ok = (order[0 .. old_len) and the lengths equal their copies); the copies are then brought up to
+// date (order[0 .. new_len), s, o)
+int kvs_launch_horizon_verify(const int32_t *order, const int32_t *s, const int32_t *o, int32_t n, int32_t old_len,
+                              int32_t new_len, int32_t *order_copy, int32_t *s_copy, int32_t *o_copy, int32_t *ok,
+                              hipStream_t st);
+// completion_by_id[order[k]] = by_position[k], k < len
+int kvs_launch_scatter_prefix(const int32_t *order, const int32_t *by_position, int32_t len, int32_t n,
+                              int32_t *completion_by_id, hipStream_t st);
 int kvs_launch_check_moves(const int32_t *moves, int32_t K, int32_t n, int64_t *tel_out, int32_t *d_words,
                            hipStream_t st);
 int kvs_launch_argmin(const int64_t *tel, int32_t K, int64_t *result_out, int32_t with_base, hipStream_t st);

@@ -650,6 +650,10 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     // (a prefix shared by all candidates) comes from memory when there is one
     int k_first = p.k_begin;
     const int32_t *state_in = p.state_in;
+    if (p.resume_ok && scalar_read(p.resume_ok, 0) == 0) {  // what the state was computed from has changed since
+        k_first = 0;
+        state_in = nullptr;
+    }
     if (RES && p.resume_block) {
         const int planned = scalar_read(p.resume_block, cand);
         // ONE: taken in this very launch: wait for it, within bounds

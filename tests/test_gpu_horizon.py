@@ -94,3 +94,46 @@ def test_hand_worked_example_on_gpu(ctx, golden_dir):
         assert order.cpu().tolist() == ints(g[f"step{k}_order"]) and comp.cpu().tolist() == ints(g[f"step{k}_completion"])
         completed = done
     assert ctx.device_status() == 0
+
+
+def test_state_kept_between_steps_is_checked_before_use(ctx):
+    # kvsched_horizon_step keeps the timeline state behind the positions no move touched and starts the next
+    # step's common prefix there -- provided the order up to there and the lengths are still what they were.
+    # Steps on an unchanged prefix, then with two prefix positions exchanged behind the library's back, then
+    # with a length changed, then with the window moved back: each against the oracle.
+    import torch
+
+    inst = workloads.instance(4, n=600)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    s_h, o_h = inst.s.copy(), inst.o.copy()
+    order_h = np.array(base, dtype=np.int32)
+    s, o, order = _dev(s_h), _dev(o_h), _dev(order_h)
+    comp = torch.empty(inst.n, dtype=torch.int32, device="cuda:0")
+    rng = np.random.default_rng(11)
+
+    def step(lo, hi, what):
+        nonlocal order_h
+        print(f"horizon step, window [{lo}, {hi}): {what}", flush=True)
+        moves = workloads.window_moves(rng, 300, lo, hi)
+        order_o, comp_o, tel_o, res_o = ohorizon.horizon_step(s_h, o_h, inst.M, order_h, moves, 0, 40)
+        tel, res = ctx.horizon_step(order, _dev(moves), s, o, inst.M, 0, 40, want_tel=True, completion_out=comp)
+        torch.cuda.synchronize()
+        assert tuple(int(x) for x in res.cpu().numpy()) == res_o, what
+        assert (tel.cpu().numpy() == tel_o).all() and (order.cpu().numpy() == order_o).all(), what
+        assert (comp.cpu().numpy() == comp_o).all(), what
+        order_h = order_o
+
+    step(100, 140, "first step")
+    step(150, 190, "prefix unchanged: continues from position 100")
+    step(200, 240, "again")
+    order_h[[3, 70]] = order_h[[70, 3]]  # the caller rearranges the kept prefix
+    order.copy_(_dev(order_h))
+    step(250, 290, "order changed below the kept prefix")
+    step(300, 340, "continues again")
+    j = int(order_h[10])
+    s_h[j] += 1  # ... and changes a length
+    s.copy_(_dev(s_h))
+    step(350, 390, "a prompt length changed")
+    step(120, 160, "window further back than the kept prefix")
+    step(400, 440, "and forward again")
+    assert ctx.device_status() == 0
