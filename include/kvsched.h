@@ -351,6 +351,13 @@ int kvsched_best_neighbor_static(kvsched_ctx *ctx, const int32_t *base_order, in
  *   completion_out  [n]    int32 or NULL: completion rounds of the new order, by request id
  *   result_out      [6]    int64: {best move, its total latency, latency of the order before
  *                   the move, committed positions, requests completed by T, T}
+ *
+ * Between steps the context keeps the timeline state behind the positions that no move of the last
+ * step touched (with copies of that part of the order and of s and o, in a buffer of its own of
+ * about 20 n bytes + 60 KB): the next step places only what lies between there and its own moves.
+ * The copies are compared with `order`, s and o on the device at every step; when the caller has
+ * changed any of them (or n, M, or moved the window back) the step starts from position 0 as if
+ * nothing had been kept.  Results never depend on it.
  */
 int kvsched_horizon_step(kvsched_ctx *ctx, int32_t *order, int32_t n, const int32_t *moves, int32_t K,
                          const int32_t *s, const int32_t *o, int64_t M, int64_t completed_in,
