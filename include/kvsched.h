@@ -354,7 +354,7 @@ int kvsched_best_neighbor_static(kvsched_ctx *ctx, const int32_t *base_order, in
  *
  * Between steps the context keeps the timeline state behind the positions that no move of the last
  * step touched (with copies of that part of the order and of s and o, in a buffer of its own of
- * about 20 n bytes + 60 KB): the next step places only what lies between there and its own moves.
+ * about 16 n bytes + 60 KB): the next step places only what lies between there and its own moves.
  * The copies are compared with `order`, s and o on the device at every step; when the caller has
  * changed any of them (or n, M, or moved the window back) the step starts from position 0 as if
  * nothing had been kept.  Results never depend on it.
