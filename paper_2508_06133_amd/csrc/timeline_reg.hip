@@ -67,6 +67,11 @@ namespace {
     "v233", "v234", "v235", "v236", "v237", "v238", "v239", "v240", "v241", "v242", "v243", "v244", "v245", \
     "v246", "v247", "v248", "v249", "v250", "v251", "v252", "v253", "v254"
 
+// Scalar registers of place_block: the pair it jumps through and, for the 65-row file, the row offsets 192 k.
+#define KVS_SCLOB_PLAIN "s66", "s67"
+#define KVS_SCLOB_65 "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", \
+    "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88"
+
 // Row numbers as the assembler's .irp wants them: all rows ascending (one stub each), and the
 // rows that can be the last row of a window with at least one full row below, descending.
 #define KVS_ASC_9 "0,1,2,3,4,5,6,7,8"
@@ -80,22 +85,23 @@ namespace {
 #define KVS_ASC_225 "0,1,2,3,4,5,6,7,8,9,10,11,12,13,14,15,16,17,18,19,20,21,22,23,24,25,26,27,28,29,30,31,32,33,34,35,36,37,38,39,40,41,42,43,44,45,46,47,48,49,50,51,52,53,54,55,56,57,58,59,60,61,62,63,64,65,66,67,68,69,70,71,72,73,74,75,76,77,78,79,80,81,82,83,84,85,86,87,88,89,90,91,92,93,94,95,96,97,98,99,100,101,102,103,104,105,106,107,108,109,110,111,112,113,114,115,116,117,118,119,120,121,122,123,124,125,126,127,128,129,130,131,132,133,134,135,136,137,138,139,140,141,142,143,144,145,146,147,148,149,150,151,152,153,154,155,156,157,158,159,160,161,162,163,164,165,166,167,168,169,170,171,172,173,174,175,176,177,178,179,180,181,182,183,184,185,186,187,188,189,190,191,192,193,194,195,196,197,198,199,200,201,202,203,204,205,206,207,208,209,210,211,212,213,214,215,216,217,218,219,220,221,222,223,224"
 #define KVS_DESC_225 "224,223,222,221,220,219,218,217,216,215,214,213,212,211,210,209,208,207,206,205,204,203,202,201,200,199,198,197,196,195,194,193,192,191,190,189,188,187,186,185,184,183,182,181,180,179,178,177,176,175,174,173,172,171,170,169,168,167,166,165,164,163,162,161,160,159,158,157,156,155,154,153,152,151,150,149,148,147,146,145,144,143,142,141,140,139,138,137,136,135,134,133,132,131,130,129,128,127,126,125,124,123,122,121,120,119,118,117,116,115,114,113,112,111,110,109,108,107,106,105,104,103,102,101,100,99,98,97,96,95,94,93,92,91,90,89,88,87,86,85,84,83,82,81,80,79,78,77,76,75,74,73,72,71,70,69,68,67,66,65,64,63,62,61,60,59,58,57,56,55,54,53,52,51,50,49,48,47,46,45,44,43,42,41,40,39,38,37,36,35,34,33,32,31,30,29,28,27,26,25,24,23,22,21,20,19,18,17,16,15,14,13,12,11,10,9,8,7,6,5,4,3,2,1"
 
-// Expands STMT(clobber-list, rows ascending, rows descending) for the instantiated file size
+// Expands STMT(clobber-list, rows ascending, rows descending, place_block's scalar clobbers) for the
+// instantiated file size
 // (NR - 1 must be even: the row chains process rows in pairs).
 #define KVS_FOR_NR(STMT)                                                                         \
     do {                                                                                         \
         static_assert(NR == 9 || NR == 33 || NR == 65 || NR == 129 || NR == 225,                 \
                       "profile file sizes: 9, 33, 65, 129 or 225 rows");                         \
         if constexpr (NR == 9) {                                                                 \
-            STMT(KVS_CLOB_9, KVS_ASC_9, KVS_DESC_9);                                             \
+            STMT(KVS_CLOB_9, KVS_ASC_9, KVS_DESC_9, KVS_SCLOB_PLAIN);                                             \
         } else if constexpr (NR == 33) {                                                         \
-            STMT(KVS_CLOB_33, KVS_ASC_33, KVS_DESC_33);                                          \
+            STMT(KVS_CLOB_33, KVS_ASC_33, KVS_DESC_33, KVS_SCLOB_PLAIN);                                          \
         } else if constexpr (NR == 65) {                                                         \
-            STMT(KVS_CLOB_65, KVS_ASC_65, KVS_DESC_65);                                          \
+            STMT(KVS_CLOB_65, KVS_ASC_65, KVS_DESC_65, KVS_SCLOB_65);                                          \
         } else if constexpr (NR == 129) {                                                        \
-            STMT(KVS_CLOB_129, KVS_ASC_129, KVS_DESC_129);                                       \
+            STMT(KVS_CLOB_129, KVS_ASC_129, KVS_DESC_129, KVS_SCLOB_PLAIN);                                       \
         } else {                                                                                 \
-            STMT(KVS_CLOB_225, KVS_ASC_225, KVS_DESC_225);                                       \
+            STMT(KVS_CLOB_225, KVS_ASC_225, KVS_DESC_225, KVS_SCLOB_PLAIN);                                       \
         }                                                                                        \
     } while (0)
 
@@ -103,7 +109,7 @@ namespace {
 template <int NR>
 __device__ __forceinline__ void prof_init()
 {
-#define KVS_STMT(CLOB, ASC, DESC)                                        \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                        \
     asm volatile(".set kvs_r, 0\n"                             \
                  ".rept %c[nr]\n"                              \
                  "  v_mov_b32 v[" KVS_PB "+kvs_r], 64*kvs_r\n" \
@@ -122,7 +128,7 @@ template <int NR>
 __device__ __forceinline__ void prof_store(int32_t *rows, int lane)
 {
     int voff = lane * 4;
-#define KVS_STMT(CLOB, ASC, DESC)                                                           \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                           \
     asm volatile(".set kvs_r, 0\n"                                                \
                  ".rept %c[nr]\n"                                                 \
                  "  global_store_dword %[voff], v[" KVS_PB "+kvs_r], %[base]\n"   \
@@ -141,7 +147,7 @@ template <int NR>
 __device__ __forceinline__ void prof_load(const int32_t *rows, int lane)
 {
     int voff = lane * 4;
-#define KVS_STMT(CLOB, ASC, DESC)                                                           \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                           \
     asm volatile(".set kvs_r, 0\n"                                                \
                  ".rept %c[nr]\n"                                                 \
                  "  global_load_dword v[" KVS_PB "+kvs_r], %[voff], %[base]\n"    \
@@ -225,7 +231,7 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
     int cv, acc, y, z, tl, vw;
     int ns, oj, x64, off, u64, w, rs, ta, tb, tc, ql, qh, cl, ch, ul, uh, rl, rh;
     long long mk;
-#define KVS_STMT(CLOB, ASC, DESC)                                                                       \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                                       \
     asm volatile(                                                                                       \
         /* table addresses: slot of row r at base + 64 (r + 1) for the stubs of a whole pass, */       \
         /* whole passes and single rows alike */                                                    \
@@ -242,7 +248,21 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "s_sub_u32 %[u64], %[t], %[b64]\n"                                                              \
         "v_sub_u32 %[tl], %[u64], %[lane]\n" /* (t - b64) - lane */                                     \
         "s_add_u32 %[u64], %[u64], 64\n"     /* x64 of a request is its decode length plus this */      \
-        "s_sub_u32 %[w], %[M], 64\n"                                                                    \
+        /* The 65-row file (long decodes, few wavefronts per SIMD) updates a row in one instruction: the */ \
+        /* ramp of row r is that of row r mod 3 (three vectors) plus 192 floor(r / 3) from a scalar */    \
+        /* register (s[67 + k] = 192 k); vw = M - (t - b64) + lane there, the ramp of row 0 is vw - (M - s). */ \
+        /* The other files take rows in pairs from the ramp of the window's last row, */                  \
+        /* vw + 64 (re + 1) - (M - s) with vw = M - 64 - (t - b64) + lane. */                             \
+        ".if %c[nr] == 65\n"                                                                            \
+        "  .set kvs_r, 1\n"                                                                             \
+        "  .rept 21\n"                                                                                  \
+        "    s_movk_i32 s[67+kvs_r], 192*kvs_r\n"                                                       \
+        "    .set kvs_r, kvs_r+1\n"                                                                     \
+        "  .endr\n"                                                                                     \
+        "  s_mov_b32 %[w], %[M]\n"                                                                      \
+        ".else\n"                                                                                       \
+        "  s_sub_u32 %[w], %[M], 64\n"                                                                  \
+        ".endif\n"                                                                                      \
         "v_sub_u32 %[vw], %[w], %[tl]\n"    /* ramp in lane l of the window's last row: vw + (s - M) + 64 (re + 1) */ \
         "v_mov_b32 %[cv], 0\n"                                                                          \
         "s_sub_u32 m0, %[cnt], 1\n"                                                                     \
@@ -296,38 +316,77 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
         "s_cbranch_vccnz 52f\n"                                                                         \
         /* ---- admit at round t */                                                                     \
         "42:\n"                                                                                         \
-        "s_sub_u32 %[rs], %[off], %[ns]\n"                                                              \
+        ".if %c[nr] != 65\n"                                                                            \
+        "  s_sub_u32 %[rs], %[off], %[ns]\n"                                                            \
+        ".endif\n"                                                                                      \
         "s_add_u32 s66, %[ul], %[off]\n"                                                                \
         "s_addc_u32 s67, %[uh], 0\n"                                                                    \
         "s_setpc_b64 s[66:67]\n"                                                                        \
         "62:\n"                                                                                         \
         ".irp r," ASC "\n"                                                                              \
         "7:\n"                                                                                          \
-        "  v_add_u32 %[y], %[rs], %[vw]\n"                                                              \
-        "  .if \\r == 0\n"                                                                              \
-        "    v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                  \
-        "    v_add_u32 v[" KVS_PB "], %[y], v[" KVS_PB "]\n"                                            \
-        "    s_branch 43f\n"                                                                            \
-        "  .else\n"                                                                                     \
-        /*   z: ramp of the even row of the pair that holds row r - 1 */                                \
-        "    .if (\\r & 1) == 1\n"                                                                      \
-        "      v_subrev_u32 %[z], 64, %[y]\n"                                                           \
+        "  .if %c[nr] == 65\n"                                                                          \
+        /*   z, acc, y (once the masked row is done): the ramps of rows 0, 1, 2 */                      \
+        "    v_subrev_u32 %[z], %[ns], %[vw]\n"                                                         \
+        "    .if \\r == 0\n"                                                                            \
+        "      v_cndmask_b32_e64 %[y], %[z], 0, %[mk]\n"                                                \
+        "      v_add_u32 v[" KVS_PB "], %[y], v[" KVS_PB "]\n"                                          \
+        "      s_branch 43f\n"                                                                          \
         "    .else\n"                                                                                   \
-        "      v_add_u32 %[z], 0xffffff80, %[y]\n"                                                      \
+        "      v_add_u32 %[y], 64*\\r, %[z]\n"                                                          \
+        "      v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                \
+        "      v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                  \
+        "      .if \\r >= 2\n"                                                                          \
+        "        v_add_u32 %[acc], 64, %[z]\n"                                                          \
+        "      .endif\n"                                                                                \
+        "      .if \\r >= 3\n"                                                                          \
+        "        v_add_u32 %[y], 0x80, %[z]\n"                                                          \
+        "      .endif\n"                                                                                \
+        "      s_branch 30\\r\\()f\n"                                                                   \
         "    .endif\n"                                                                                  \
-        "    v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                  \
-        "    v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                    \
-        "    s_branch 30\\r\\()f\n"                                                                     \
+        "  .else\n"                                                                                     \
+        "    v_add_u32 %[y], %[rs], %[vw]\n"                                                            \
+        "    .if \\r == 0\n"                                                                            \
+        "      v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                \
+        "      v_add_u32 v[" KVS_PB "], %[y], v[" KVS_PB "]\n"                                          \
+        "      s_branch 43f\n"                                                                          \
+        "    .else\n"                                                                                   \
+        /*     z: ramp of the even row of the pair that holds row r - 1 */                              \
+        "      .if (\\r & 1) == 1\n"                                                                    \
+        "        v_subrev_u32 %[z], 64, %[y]\n"                                                         \
+        "      .else\n"                                                                                 \
+        "        v_add_u32 %[z], 0xffffff80, %[y]\n"                                                    \
+        "      .endif\n"                                                                                \
+        "      v_cndmask_b32_e64 %[y], %[y], 0, %[mk]\n"                                                \
+        "      v_add_u32 v[" KVS_PB "+\\r], %[y], v[" KVS_PB "+\\r]\n"                                  \
+        "      s_branch 30\\r\\()f\n"                                                                   \
+        "    .endif\n"                                                                                  \
         "  .endif\n" KVS_SLOT_PAD(64)                                                                   \
         ".endr\n"                                                                                       \
         ".irp r," DESC "\n"                                                                             \
         "30\\r:\n"                                                                                      \
-        "  .if ((\\r-1) & 1) == 1\n"                                                                    \
-        "    v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[z], 64\n"                           \
+        "  .if %c[nr] == 65\n"                                                                          \
+        "    .if (\\r-1) == 0\n"                                                                        \
+        "      v_add_u32 v[" KVS_PB "], %[z], v[" KVS_PB "]\n"                                          \
+        "    .elseif (\\r-1) == 1\n"                                                                    \
+        "      v_add_u32 v[" KVS_PB "+1], %[acc], v[" KVS_PB "+1]\n"                                    \
+        "    .elseif (\\r-1) == 2\n"                                                                    \
+        "      v_add_u32 v[" KVS_PB "+2], %[y], v[" KVS_PB "+2]\n"                                      \
+        "    .elseif ((\\r-1) - 3*((\\r-1)/3)) == 0\n"                                                  \
+        "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[z], s[67+(\\r-1)/3]\n"            \
+        "    .elseif ((\\r-1) - 3*((\\r-1)/3)) == 1\n"                                                  \
+        "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[acc], s[67+(\\r-1)/3]\n"          \
+        "    .else\n"                                                                                   \
+        "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[y], s[67+(\\r-1)/3]\n"            \
+        "    .endif\n"                                                                                  \
         "  .else\n"                                                                                     \
-        "    v_add_u32 v[" KVS_PB "+\\r-1], %[z], v[" KVS_PB "+\\r-1]\n"                                \
-        "    .if (\\r-1) >= 2\n"                                                                        \
-        "      v_add_u32 %[z], 0xffffff80, %[z]\n"                                                      \
+        "    .if ((\\r-1) & 1) == 1\n"                                                                  \
+        "      v_add3_u32 v[" KVS_PB "+\\r-1], v[" KVS_PB "+\\r-1], %[z], 64\n"                         \
+        "    .else\n"                                                                                   \
+        "      v_add_u32 v[" KVS_PB "+\\r-1], %[z], v[" KVS_PB "+\\r-1]\n"                              \
+        "      .if (\\r-1) >= 2\n"                                                                      \
+        "        v_add_u32 %[z], 0xffffff80, %[z]\n"                                                    \
+        "      .endif\n"                                                                                \
         "    .endif\n"                                                                                  \
         "  .endif\n"                                                                                    \
         ".endr\n"                                                                                       \
@@ -466,7 +525,7 @@ __device__ __forceinline__ int place_block(int cnt, int vns, int vo, int lane, i
           [rh] "=&s"(rh), [mk] "=&s"(mk), [t] "+s"(t), [b64] "+s"(b64)                  \
         : [cnt] "s"(cnt), [vns] "v"(vns), [vo] "v"(vo), [lane] "v"(lane), [vmin] "v"(vmin),             \
           [M] "s"(M), [nr] "n"(NR)                                                                      \
-        : "scc", "vcc", "s66", "s67", CLOB)
+        : "scc", "vcc", SCLOB, CLOB)
     KVS_FOR_NR(KVS_STMT);
 #undef KVS_STMT
     return cv;
@@ -491,7 +550,7 @@ template <int NR>
 __device__ __forceinline__ void state_head_store(int32_t *snap, int b64, int t, long long tel_lane, int lane)
 {
     int a, b, off;
-#define KVS_STMT(CLOB, ASC, DESC)                                                                        \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                                        \
     asm volatile("v_mov_b32 %[a], %[b64]\n"                                                              \
                  "v_mov_b32 %[b], %[t]\n"                                                                \
                  "v_mov_b32 %[off], 0\n"                                                                 \
@@ -529,7 +588,7 @@ __device__ __forceinline__ void snapshot_progress_set(int32_t *progress, int val
 {
     static_assert(KVS_PROGRESS_COPIES == 64 && KVS_PROGRESS_STRIDE_WORDS == 16, "one copy per lane, 64 bytes apart");
     int off, v;
-#define KVS_STMT(CLOB, ASC, DESC)                                                       \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                       \
     asm volatile("v_lshlrev_b32 %[off], 6, %[lane]\n"                                   \
                  "v_mov_b32 %[v], %[val]\n"                                             \
                  "global_store_dword %[off], %[v], %[base] sc1\n"                       \
@@ -556,7 +615,7 @@ template <int NR>
 __device__ __forceinline__ int snapshot_wait(const int32_t *progress, int rb, int polls, int copy)
 {
     int f, cnt, last, voff, v;
-#define KVS_STMT(CLOB, ASC, DESC)                                                                                 \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                                                 \
     asm volatile("s_cmp_eq_u32 %[rb], 0\n"                                                                        \
                  "s_cbranch_scc1 4f\n"                                                                            \
                  "s_max_i32 %[cnt], %[polls], 1\n"                                                                \
@@ -605,7 +664,7 @@ template <int NR>
 __device__ __forceinline__ int snapshot_word(const int32_t *snap, int index)
 {
     int off, v;
-#define KVS_STMT(CLOB, ASC, DESC)                              \
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                              \
     asm volatile("v_mov_b32 %[off], %[idx]\n"                  \
                  "global_load_dword %[v], %[off], %[base]\n"   \
                  "s_waitcnt vmcnt(0)\n"                        \
