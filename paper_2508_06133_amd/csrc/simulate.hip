@@ -171,6 +171,33 @@ __global__ __launch_bounds__(WAVE *WPB) void check_orders_kernel(const int32_t *
     }
 }
 
+// The same for long rows: one workgroup of 1024 threads per row (a single wavefront would walk a row of
+// 100000 entries in 1563 dependent turns).
+__global__ __launch_bounds__(1024) void check_orders_wide_kernel(const int32_t *orders, int32_t C, int32_t n,
+                                                                 int64_t *tel_out, int32_t *words)
+{
+    extern __shared__ unsigned int bitmap_all[];
+    const int cand = blockIdx.x;
+    const int nw = (n + 31) >> 5;
+    for (int i = threadIdx.x; i < nw; i += 1024) bitmap_all[i] = 0;
+    __syncthreads();
+    const int32_t *row = orders + (size_t)cand * (size_t)n;
+    int bad = 0;
+    for (int k = threadIdx.x; k < n; k += 1024) {
+        const int r = row[k];
+        if (r < 0 || r >= n) {
+            bad = 1;
+        } else {
+            const unsigned int bit = 1u << (r & 31);
+            if (atomicOr(&bitmap_all[r >> 5], bit) & bit) bad = 1;
+        }
+    }
+    if (__syncthreads_or(bad) && threadIdx.x == 0) {
+        tel_out[cand] = -1;
+        atomicOr(&words[KVS_W_STATUS], KVSCHED_DEV_BAD_ORDER);
+    }
+}
+
 __global__ __launch_bounds__(256) void check_moves_kernel(const int32_t *moves, int32_t K, int32_t n,
                                                           int64_t *tel_out, int32_t *words)
 {
@@ -280,7 +307,10 @@ int kvs_launch_check_orders(const int32_t *orders, int32_t C, int32_t n, int64_t
 {
     const size_t per_wave = (size_t)((n + 31) >> 5) * sizeof(unsigned int);
     if (per_wave > 65536) return KVSCHED_ERANGE;
-    if (per_wave * 4 <= 65536) {
+    if (n >= 16384 && C <= 8192) {  // long rows, not enough of them to fill the chip with a wavefront each
+        hipLaunchKernelGGL(check_orders_wide_kernel, dim3((unsigned)C), dim3(1024), per_wave, st, orders, C, n, tel_out,
+                           d_words);
+    } else if (per_wave * 4 <= 65536) {
         hipLaunchKernelGGL((check_orders_kernel<4>), dim3((unsigned)((C + 3) / 4)), dim3(256), per_wave * 4, st,
                            orders, C, n, tel_out, d_words);
     } else {

@@ -447,3 +447,22 @@ def test_resume_is_chosen_by_size_unless_told_otherwise(ctx):
     assert (_resume_positions(ctx, 4000) == 0).all() and (tel_h == tel_g[:4000]).all()
     with pytest.raises(Exception):
         ctx.set_resume_min_rows(-2)
+
+
+def test_long_rows_that_are_no_permutation_are_reported(ctx):
+    # rows of 20000 positions go through the one-workgroup-per-row permutation check
+    from paper_2508_06133_amd import kvsched
+
+    n = 20000
+    rng = np.random.default_rng(5)
+    s = rng.integers(1, 40, n).astype(np.int32)
+    o = rng.integers(1, 30, n).astype(np.int32)
+    M = 4096
+    rows = np.stack([rng.permutation(n) for _ in range(4)]).astype(np.int32)
+    rows[1, 19999] = rows[1, 0]      # an id twice, far apart
+    rows[3, 12345] = n               # an id out of range
+    tel_g, comp_g, status = _gpu_simulate(ctx, s, o, M, rows)
+    assert status == kvsched.DEV_BAD_ORDER
+    assert tel_g[1] == -1 and tel_g[3] == -1
+    tel_o, comp_o = oracle.simulate_many(s, o, M, rows[[0, 2]], literal=False)
+    assert (tel_g[[0, 2]] == tel_o).all() and (comp_g[[0, 2]] == comp_o).all()
