@@ -7,6 +7,10 @@
 //   2. when a refresh is due the planner re-orders the whole backlog into a new cached list;
 //   3. list entries are admitted from the front while Eq. (1) holds beside the running requests,
 //      stopping at the first that does not fit.
+// Iterations that cannot change anything are not executed one by one: with an empty backlog the
+// stream moves to the next arrival, and when the head of the list does not fit, to the earliest of
+// the first round at which it might, the next arrival and the next refresh that could change the
+// list (refreshes of an unchanged backlog reproduce the list and are only counted).
 //
 // A stream is a chain of small dependent steps (a refresh of the paper's setting is some
 // twenty batches and a hundred exchanges on fifty requests), so nothing is gained by putting
@@ -124,6 +128,7 @@ constexpr int DPP_BCAST15 = 0x142, DPP_BCAST31 = 0x143;  // last lane of a row -
 
 __device__ __forceinline__ int op_add(int a, int b) { return a + b; }
 __device__ __forceinline__ int op_min(int a, int b) { return min(a, b); }
+__device__ __forceinline__ int op_max(int a, int b) { return max(a, b); }
 
 __device__ __forceinline__ int wave_sum(int v)
 {
@@ -143,6 +148,13 @@ __device__ __forceinline__ int wave_min(int v)
     KVS_ROW_BUTTERFLY(v, op_min)
     return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
                min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+
+__device__ __forceinline__ int wave_max(int v)
+{
+    KVS_ROW_BUTTERFLY(v, op_max)
+    return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 // Inclusive prefix scans over the 64 lanes: within rows by shifts of 1, 2, 4, 8, then the last
@@ -542,12 +554,13 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
         max_backlog = max(max_backlog, q);
 
         // ---- 2. refresh of the cached order
+        bool refreshed = false;
+        int wn = 0;
         if (q > 0) {
             const long long newly = q - planned_left;
             const bool due = planned_left == 0 || t - t_plan >= period ||
                              (rden > 0 && newly * rden >= (long long)rnum * backlog_at_plan);
             if (due) {
-                int wn = 0;
                 if (planner == KVSCHED_PLANNER_SORTED_F && window > 0) {
                     wn = min(window, q);
                     plan_window<Lds::WCAP>(cur, wn, M, L.wk, oth, L.list);
@@ -558,6 +571,7 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
                 t_plan = t;
                 backlog_at_plan = q;
                 ++refreshes;
+                refreshed = true;
                 wave_sync();
             }
         }
@@ -566,13 +580,19 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
         if (lane == 0) L.ring[t & HM] = 0;  // round t is behind every check from now on
         wave_sync();
         int adm = 0;
+        int wait_to = t + 1;  // when the loop stops at a request: a round before which it cannot start
         while (adm < q) {
             const u64 key = uni64(L.list[(head + adm) & QM]);
             const int oo = codec.decode(key), id = codec.id(key);
             const int sr = codec.size(key) - oo;
-            bool viol = false;
-            for (int j = lane + 1; j <= oo; j += 64) viol |= L.ring[(t + j) & HM] + sr + j > M;
-            if (__builtin_amdgcn_ballot_w64(viol) != 0) break;
+            // round t + j rules out every start before t + min(excess, j): started later the request is
+            // smaller at that round by as much, or no longer overlaps it
+            int excess = 0;
+            for (int j = lane + 1; j <= oo; j += 64) excess = max(excess, min(L.ring[(t + j) & HM] + sr + j - M, j));
+            if (__builtin_amdgcn_ballot_w64(excess > 0) != 0) {
+                wait_to = t + wave_max(excess);
+                break;
+            }
             for (int j = lane + 1; j <= oo; j += 64) L.ring[(t + j) & HM] += sr + j;
             if (lane == 0) cout[id] = t + oo;
             sum_c += t + oo;
@@ -606,7 +626,31 @@ __global__ __launch_bounds__(64) void online_kernel(OnlineParams p)
             started += adm;
             planned_left = max(planned_left - adm, 0);
         }
-        ++t;
+        // ---- the rounds at which nothing can happen are passed in one step.  Until the request at
+        // the head of the list can start (wait_to at the earliest), an iteration changes something
+        // only if requests arrive or the list is re-planned.  Re-planning an unchanged backlog gives
+        // the same list, so where the list is the plan of the present backlog (a refresh in this
+        // iteration, and nothing admitted since unless the planner is a plain sort) the refreshes
+        // of the rounds passed are only counted; otherwise the step ends at the next refresh due.
+        int t_next = t + 1;
+        if (q > 0) {
+            t_next = min(wait_to, next_a);
+            if (refreshed && (wn == 0 || adm == 0)) {
+                const int every = (rden > 0 && rnum == 0) ? 1 : period;
+                const int passed = (t_next - 1 - t) / every;
+                if (passed > 0) {
+                    refreshes += passed;
+                    t_plan = t + passed * every;
+                    backlog_at_plan = q;
+                }
+            } else {
+                const bool grown = rden > 0 && (long long)(q - planned_left) * rden >= (long long)rnum * backlog_at_plan;
+                const long long due_at = (planned_left == 0 || grown) ? t + 1 : max((long long)t + 1, (long long)t_plan + period);
+                t_next = (int)min((long long)t_next, due_at);
+            }
+            for (int u = t + 1 + lane; u < t_next; u += 64) L.ring[u & HM] = 0;
+        }
+        t = t_next;
     }
 
     const long long sa = wave_sum64(sum_a);

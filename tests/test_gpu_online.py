@@ -203,6 +203,34 @@ def test_longest_decode_and_idle_gaps(ctx):
     b.check(ctx, 4100, "decode length = ring size", cap=16)
 
 
+def test_long_waits_of_the_head_request(ctx):
+    # the kernel passes the rounds at which the head of the list cannot start in one step: here the
+    # head waits for hundreds of rounds behind a few long requests that nearly fill the budget, while
+    # requests keep arriving, under every refresh rule (periods shorter and longer than the waits,
+    # growth triggers that never / always / sometimes fire) -- refresh counts included
+    rng = np.random.default_rng(77)
+    for M, o_hi, n in ((600, 400, 60), (2000, 1500, 120), (300, 40, 200)):
+        b = Batch()
+        for rep in range(3):
+            s = rng.integers(1, M // 4, n)
+            o = rng.integers(max(1, o_hi // 3), o_hi + 1, n)
+            short = rng.random(n) < 0.3
+            o[short] = rng.integers(1, 6, int(short.sum()))
+            a = np.sort(rng.integers(0, n * o_hi // 8, n))
+            ok = s + o <= M
+            s, o, a = s[ok], o[ok], a[ok]
+            r = b.add_requests(a, s, o)
+            for planner in (FCFS, MCSF, FOOT):
+                for period in (1, 3, 1000):
+                    for refresh in ((1, 2), (0, 0), (0, 1), (3, 1)):
+                        b.add_stream(r, planner, period, 0, refresh)
+            for period in (1, 7, 50, 1000):
+                for window in (0, 2, 300):
+                    for refresh in ((1, 2), (0, 0), (0, 3), (1, 10)):
+                        b.add_stream(r, SORTF, period, window, refresh)
+        b.check(ctx, M, f"long waits, M={M}", cap=256)
+
+
 def test_all_present_at_round_zero_equals_offline(ctx):
     # arrivals all at round 0, one refresh, window over everything: the offline Sorted-F order
     # with Local Swap Search batches run through Phase 2
