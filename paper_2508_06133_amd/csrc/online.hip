@@ -118,6 +118,7 @@ __device__ __forceinline__ int dpp(int idle, int v)
 constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
 constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
 constexpr int DPP_BCAST15 = 0x142, DPP_BCAST31 = 0x143;  // last lane of a row -> the next row(s)
+constexpr int DPP_WAVE_SHR1 = 0x138;                      // every lane from the lane below, across rows
 
 // After these four steps every lane of a 16-lane row holds the row's total.
 #define KVS_ROW_BUTTERFLY(v, OP)                      \
@@ -127,7 +128,6 @@ constexpr int DPP_BCAST15 = 0x142, DPP_BCAST31 = 0x143;  // last lane of a row -
     v = OP(v, dpp<DPP_MIRROR>(v, v));
 
 __device__ __forceinline__ int op_add(int a, int b) { return a + b; }
-__device__ __forceinline__ int op_min(int a, int b) { return min(a, b); }
 __device__ __forceinline__ int op_max(int a, int b) { return max(a, b); }
 
 __device__ __forceinline__ int wave_sum(int v)
@@ -141,13 +141,6 @@ __device__ __forceinline__ long long wave_sum64(long long v)
 {
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
     return (long long)uni64((u64)v);
-}
-
-__device__ __forceinline__ int wave_min(int v)
-{
-    KVS_ROW_BUTTERFLY(v, op_min)
-    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
-               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 __device__ __forceinline__ int wave_max(int v)
@@ -172,8 +165,8 @@ __device__ __forceinline__ unsigned wave_incl_add_sat(unsigned v, unsigned cap)
     return v;
 }
 
-// exclusive prefix minimum (INT_MAX for lane 0)
-__device__ __forceinline__ int wave_excl_min(int v)
+// inclusive prefix minimum
+__device__ __forceinline__ int wave_incl_min(int v)
 {
     v = min(v, dpp<DPP_ROW_SHR1>(INT_MAX, v));
     v = min(v, dpp<DPP_ROW_SHR2>(INT_MAX, v));
@@ -181,10 +174,7 @@ __device__ __forceinline__ int wave_excl_min(int v)
     v = min(v, dpp<DPP_ROW_SHR8>(INT_MAX, v));
     v = min(v, dpp<DPP_BCAST15, 0xa>(INT_MAX, v));
     v = min(v, dpp<DPP_BCAST31, 0xc>(INT_MAX, v));
-    // one lane down: inside a row by a shift, across a row boundary from the row below's last lane
-    const int within = dpp<DPP_ROW_SHR1>(INT_MAX, v);
-    const int across = dpp<DPP_BCAST15, 0xe>(INT_MAX, v);
-    return (lane_id() & 15) ? within : across;
+    return v;
 }
 
 __device__ __forceinline__ int first_lane(u64 ballot) { return __ffsll((long long)ballot) - 1; }
@@ -304,14 +294,14 @@ __device__ void plan_window(const u64 *src, int wn, int M, u64 *wk, u64 *tmp, u6
                 }
                 if (astar < 0) break;
             } else {
-                int run = INT_MAX;
+                int run = INT_MAX, oa = 0;
 #pragma unroll
                 for (int r = 0; r < RMAX; ++r) {
                     if (r < R) {
                         const bool out = ((valid >> r) & 1u) && !((mem >> r) & 1u);
-                        const int v = out ? oreg[r] : INT_MAX;
-                        pm[64 * r + lane] = min(wave_excl_min(v), run);
-                        run = min(run, wave_min(v));
+                        const int upto = wave_incl_min(out ? oreg[r] : INT_MAX);
+                        pm[64 * r + lane] = min(dpp<DPP_WAVE_SHR1>(INT_MAX, upto), run);  // lane 0: run alone
+                        run = min(run, __builtin_amdgcn_readlane(upto, 63));
                     }
                 }
                 if (lane == 0) pm[m] = run;
@@ -329,25 +319,28 @@ __device__ void plan_window(const u64 *src, int wn, int M, u64 *wk, u64 *tmp, u6
                                 has = pm[ub] < oreg[r];
                             }
                             const u64 bal = __builtin_amdgcn_ballot_w64(has);
-                            if (bal != 0) astar = 64 * r + first_lane(bal);
+                            if (bal != 0) {
+                                astar = 64 * r + first_lane(bal);
+                                wa = __builtin_amdgcn_readlane(wreg[r], first_lane(bal));
+                                oa = __builtin_amdgcn_readlane(oreg[r], first_lane(bal));
+                            }
                         }
                     }
                 }
                 wave_sync();
                 if (astar < 0) break;
-                const u64 ka = uni64(wk[astar]);
-                const int oa = (int)((ka >> 20) & 0x3fffu);
 #pragma unroll
                 for (int r = 0; r < RMAX; ++r) {
                     if (r < R && bstar < 0) {
                         const bool ok = ((valid >> r) & 1u) && !((mem >> r) & 1u) && oreg[r] < oa;
                         const u64 bal = __builtin_amdgcn_ballot_w64(ok);
-                        if (bal != 0) bstar = 64 * r + first_lane(bal);
+                        if (bal != 0) {
+                            bstar = 64 * r + first_lane(bal);
+                            wb = __builtin_amdgcn_readlane(wreg[r], first_lane(bal));
+                        }
                     }
                 }
                 if (bstar < 0) break;  // cannot happen: pm[] promised a partner before the bound
-                wa = (int)(ka >> 34);
-                wb = (int)(uni64(wk[bstar]) >> 34);
             }
             memsum += wb - wa;
             if (lane == (astar & 63)) mem &= ~(1u << (astar >> 6));
