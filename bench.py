@@ -521,12 +521,17 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
     start0 = comp[0].to(torch.int64)[order0] - o_row0  # start rounds of row 0 by position
     cum0 = torch.cat([torch.zeros(1, dtype=torch.int64, device=dev), torch.cumsum(o_row0, 0)])
     t_res = torch.where(resume > 0, start0[(resume - 1).clamp(min=0)], torch.zeros_like(resume))
-    updated = int((sum_o - cum0[resume]).sum().item())
-    inspected = int((p_last - t_res).sum().item()) + updated
+    # ... and a row whose timeline became row 0's again stopped placing there: positions [resume, stop)
+    stop = torch.maximum(ctx.simulate_stop_positions(C, n).to(torch.int64), resume)
+    rejoined = stop < n
+    p_end = torch.where(rejoined, torch.where(stop > resume, start0[(stop - 1).clamp(min=0)], t_res), p_last)
+    updated = int((cum0[stop] - cum0[resume]).sum().item())
+    inspected = int((p_end - t_res).sum().item()) + updated
     visits_from_scratch = int((p_last + 2 * sum_o).sum().item())
     resumed_rows = int((resume > 0).sum().item())
-    hbm_bytes = int((8 * (n - resume) + 8).sum().item()) + 8 * n  # order entries read, completion rounds written, from the resume point on
-    kernel = f"timeline_reg_kernel<{reg_rows(o_max)},4,false,{'true,true' if resumed_rows else 'false,false'}>"
+    rejoined_rows = int(rejoined.sum().item())
+    hbm_bytes = int((8 * (stop - resume) + 8).sum().item()) + 8 * n  # order entries read, completion rounds written, for the positions placed
+    kernel = f"timeline_reg_kernel<{reg_rows(o_max)},{'1,false,true,true' if resumed_rows else '4,false,false,false'}>"
     names = {1: "config 1: tiny exact, n=8, M=48, all 8! orders + the Sorted-F order",
              2: "config 2: short conversation, n=200, M=16384, Sorted-F order + 4095 random pairwise swaps",
              3: "config 3: mixed chat+summarization, n=2000, M=131072, C=16384 "
@@ -557,7 +562,8 @@ def bench_rows(args, ctx, dev, cfg: int) -> int:
         "roofline": roofline_object(kernel, inspected * args.steps, updated * args.steps, float(np.sum(kernel_ms)), args.steps,
                                     f"config{cfg}" if scale == 1 else "scaled",
                                     hbm_bytes * args.steps,
-                                    {"resumed_rows": resumed_rows, "visits_without_resume": visits_from_scratch}),
+                                    {"resumed_rows": resumed_rows, "rejoined_rows": rejoined_rows,
+                                     "visits_without_resume": visits_from_scratch}),
     }
     if not args.no_cpu_baseline:
         base_line = cpu_baseline_rows(inst, lambda lo, hi: rows_h[lo:hi], C, tel_h, "candidate rows")

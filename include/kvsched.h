@@ -143,7 +143,13 @@ int kvsched_device_status(kvsched_ctx *ctx, void *stream, int32_t *status_out);
  * kvsched_set_resume_min_rows) and no declared prefix, row 0's timeline state is saved every 64
  * positions and every row that shares at least 64 leading positions with row 0 starts from the
  * last such state it shares (see kvsched_set_resume_one_launch for how the states are handed
- * over).  Results are the same; kvsched_simulate_resume_positions() tells which rows did so.
+ * over).  Such a row may also stop before its end: if it differs from row 0 only at positions
+ * i..j (the same requests in another order) and row 0 starts the requests of positions i-1..j in
+ * one round (round 0 for i = 0), the row starts them in that round too and its timeline is row 0's
+ * from position j+1 on (Algorithm 1, Phase 2: admission in order, Eq. (1) holds for every part of
+ * a set it holds for); what row 0 places behind the next 64-position boundary is then taken from
+ * row 0.  Results are the same; kvsched_simulate_resume_positions() and
+ * kvsched_simulate_stop_positions() tell which positions each row placed itself.
  * ERANGE: n * (ring size) >= 2^31 (round counters are int32), M >= 2^30, o_max bound too large.
  */
 int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n,
@@ -202,6 +208,11 @@ int kvsched_simulate_predicted(kvsched_ctx *ctx, const int32_t *orders, int32_t 
  * resumed from row 0's state after 64 b positions).  C must be that call's C; valid until the next
  * call on the context that is not kvsched_argmin / kvsched_device_status. */
 int kvsched_simulate_resume_positions(kvsched_ctx *ctx, int32_t C, int32_t *resume_pos_out, void *stream);
+
+/* Its counterpart: stop_pos_out[c] (device, [C] int32) = the position before which row c of that call
+ * stopped placing, its timeline having become row 0's again (n = it placed its last position itself;
+ * 0 = it placed nothing: the whole timeline is row 0's).  C and n must be that call's; same validity. */
+int kvsched_simulate_stop_positions(kvsched_ctx *ctx, int32_t C, int32_t n, int32_t *stop_pos_out, void *stream);
 
 /*
  * Phase 1 of Algorithm 1 ("Batch Construction") with the batch chosen among the feasible

@@ -47,7 +47,7 @@ def timeline_reg_instantiations() -> int:
     """Kernel instantiations kvs_launch_simulate_reg can reach: one per launch statement of launch_reg
     and profile-file size."""
     src = open(os.path.join(CSRC, "timeline_reg.hip")).read()
-    launches = len(re.findall(r"hipLaunchKernelGGL\(\(timeline_reg_kernel<NR, WPB,", src))
+    launches = len(re.findall(r"hipLaunchKernelGGL\(\(timeline_reg_kernel<NR, (?:WPB|1),", src))
     sizes = len(re.findall(r"return launch_reg<\d+, \d+>\(p, st\);", src))
     return launches * sizes
 

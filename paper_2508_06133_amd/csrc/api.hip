@@ -40,6 +40,7 @@ constexpr size_t kMaxExactTableBytes = (size_t)16 << 30;  // tables + records of
 int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
 {
     ctx->resume_rows = 0;  // whoever asks for scratch overwrites the last resume plan
+    ctx->rejoin_offset = 0;
     if (bytes <= ctx->scratch_bytes) return KVSCHED_OK;
     if (ctx->d_scratch) {
         // kernels of earlier calls may still be reading the old buffer
@@ -287,6 +288,7 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->timing = 0;
     ctx->timed = 0;
     ctx->resume_rows = 0;
+    ctx->rejoin_offset = 0;
     ctx->resume_first = 0;
     ctx->resume_min_rows = KVSCHED_RESUME_AUTO;
     ctx->resume_wait_polls = kResumeWaitPollsDefault;
@@ -348,9 +350,9 @@ int kvsched_reserve(kvsched_ctx *ctx, int32_t rows, int32_t n, int32_t moves)
     const size_t swap = kvs_local_swap_scratch_bytes(n);
     if (swap > need) need = swap;
     if (rows > 0) {
-        const size_t sim = 3 * align256(sizeof(int32_t) * (size_t)rows) +
+        const size_t sim = 6 * align256(sizeof(int32_t) * (size_t)rows) +
                            align256(sizeof(int32_t) * nblk * KVS_STATE_MAX_WORDS) +
-                           align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) + row_bytes;
+                           align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) + 2 * row_bytes;
         const size_t pre = state_bytes() + row_bytes;  // a declared common prefix
         if (sim > need) need = sim;
         if (pre > need) need = pre;
@@ -360,9 +362,10 @@ int kvsched_reserve(kvsched_ctx *ctx, int32_t rows, int32_t n, int32_t moves)
         if (hor > need) need = hor;
     }
     const int32_t keep = ctx->resume_rows;  // reserving is no call: the last resume plan stays readable unless the buffer moves
+    const size_t keep_rejoin = ctx->rejoin_offset;
     const bool grows = need > ctx->scratch_bytes;
     const int rc = ensure_scratch(ctx, need);
-    if (!grows) ctx->resume_rows = keep;
+    if (!grows) ctx->resume_rows = keep, ctx->rejoin_offset = keep_rejoin;
     return rc;
 }
 
@@ -469,14 +472,16 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
     // No declared prefix: rows that agree with row 0 on their leading 64-position blocks resume
     // from snapshots of row 0's timeline, taken by row 0's own wave.
     ctx->resume_rows = 0;
-    const int32_t *resumed_blocks = nullptr, *resumed_row0 = nullptr;
+    ctx->rejoin_offset = 0;
+    const int32_t *resumed_blocks = nullptr, *resumed_row0 = nullptr, *rejoined = nullptr;
     if (cp == 0 && resume_pays(ctx, C, n, o_bound)) {
         const int32_t nblk = (n - 1) / WAVE_POSITIONS;
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
         const size_t snap_bytes = align256(sizeof(int32_t) * (size_t)nblk * (size_t)stride);
         const size_t flag_bytes = align256(sizeof(int32_t) * KVS_PROGRESS_WORDS);  // the progress word of row 0's wave
-        rc = ensure_scratch(ctx, 3 * list_bytes + snap_bytes + flag_bytes + align256(sizeof(int32_t) * (size_t)n));
+        const size_t row_bytes = align256(sizeof(int32_t) * (size_t)n);
+        rc = ensure_scratch(ctx, 6 * list_bytes + snap_bytes + flag_bytes + 2 * row_bytes);
         if (rc != KVSCHED_OK) return rc;
         int32_t *blocks = (int32_t *)ctx->d_scratch;
         int32_t *sorted = (int32_t *)((char *)ctx->d_scratch + list_bytes);
@@ -484,8 +489,21 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         int32_t *snaps = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes);
         int32_t *flags = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes);
         int32_t *row0 = (int32_t *)((char *)ctx->d_scratch + 3 * list_bytes + snap_bytes + flag_bytes);
-        rc = kvs_launch_shared_blocks(orders, C, n, blocks, st);
+        // A row may also stop before its end, where its timeline has become row 0's again (see SimParams);
+        // not when the timeline kernel itself scatters the completion rounds by request id.
+        const bool rejoin = !completion_out || p.completion_by_position;
+        char *more = (char *)ctx->d_scratch + 3 * list_bytes + snap_bytes + flag_bytes + row_bytes;
+        int32_t *diff_first = (int32_t *)more, *diff_last = (int32_t *)(more + list_bytes);
+        int32_t *rejoin_block = (int32_t *)(more + 2 * list_bytes);
+        int32_t *start0 = (int32_t *)(more + 3 * list_bytes);
+        rc = kvs_launch_shared_blocks(orders, C, n, blocks, rejoin ? diff_first : nullptr, diff_last, st);
         if (rc != KVSCHED_OK) return rc;
+        if (rejoin) {
+            p.diff_first = diff_first;
+            p.diff_last = diff_last;
+            p.rejoin_block = rejoin_block;
+            p.start0 = start0;
+        }
         rc = kvs_launch_sort_by_blocks(blocks, C, 0, tmp, sorted, flags, KVS_PROGRESS_WORDS, st);  // (clears the progress word too)
         if (rc != KVSCHED_OK) return rc;
         int32_t first = 0;
@@ -501,6 +519,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
             a.snap_blocks = nblk;
             a.snap_flags = flags;
             a.snap_wait_polls = ctx->resume_wait_polls;
+            a.rejoin_blocks = rejoin ? nblk : 0;
             rc = kvs_launch_simulate_reg(a, st);
             if (rc != KVSCHED_OK) return rc;
         } else {
@@ -523,8 +542,15 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
             b.snapshots = snaps;
             b.snap_stride = stride;
             b.snap_blocks = 0;
+            b.rejoin_blocks = rejoin ? nblk : 0;  // (the first launch has left every state and start round of row 0)
             rc = kvs_launch_simulate_reg(b, st);
             if (rc != KVSCHED_OK) return rc;
+        }
+        if (rejoin) {
+            rc = kvs_launch_rejoin_finish(rejoin_block, C, tel_out, st);
+            if (rc != KVSCHED_OK) return rc;
+            rejoined = rejoin_block;
+            ctx->rejoin_offset = (size_t)((char *)rejoin_block - (char *)ctx->d_scratch);
         }
         if (ctx->timing) {
             if (hipEventRecord(ctx->ev1, st) != hipSuccess) return KVSCHED_EHIP;
@@ -552,7 +578,8 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
         if (rc != KVSCHED_OK) return rc;
     }
     if (p.completion_by_position) {  // this pass over the rows checks them as well
-        rc = kvs_launch_permute_rows(orders, C, n, completion_out, tel_out, ctx->d_words, resumed_blocks, resumed_row0, st);
+        rc = kvs_launch_permute_rows(orders, C, n, completion_out, tel_out, ctx->d_words, resumed_blocks, resumed_row0,
+                                     resumed_row0 ? rejoined : nullptr, st);
     } else {
         rc = kvs_launch_check_orders(orders, C, n, tel_out, ctx->d_words, st);
     }
@@ -974,6 +1001,16 @@ int kvsched_simulate_resume_positions(kvsched_ctx *ctx, int32_t C, int32_t *resu
     const int32_t *blocks = (const int32_t *)ctx->d_scratch;
     const int32_t *sorted = (const int32_t *)((const char *)ctx->d_scratch + list_bytes);
     return kvs_launch_resume_plan(sorted, C, ctx->resume_first, blocks, resume_pos_out, st);
+}
+
+int kvsched_simulate_stop_positions(kvsched_ctx *ctx, int32_t C, int32_t n, int32_t *stop_pos_out, void *stream)
+{
+    if (!ctx || !stop_pos_out || C < 1 || n < 1) return KVSCHED_EINVAL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    if (ctx->rejoin_offset != 0 && C != ctx->resume_rows) return KVSCHED_EINVAL;
+    const int32_t *rejoin =
+        ctx->rejoin_offset != 0 ? (const int32_t *)((const char *)ctx->d_scratch + ctx->rejoin_offset) : nullptr;
+    return kvs_launch_stop_positions(rejoin, C, n, stop_pos_out, (hipStream_t)stream);
 }
 
 int kvsched_simulate_predicted(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n, const int32_t *s,

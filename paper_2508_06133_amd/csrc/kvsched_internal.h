@@ -33,6 +33,7 @@ struct kvsched_ctx {
     int timed;             // a pair of events has been recorded
     int32_t resume_rows;   // rows of the last kvsched_simulate call if it resumed rows from snapshots, else 0
     int32_t resume_first;  // ... and how many of them (in sorted order) ran from the start
+    size_t rejoin_offset;  // ... and where in the scratch buffer the blocks at which rows stopped early are (0: nowhere)
     int32_t resume_min_rows;  // kvsched_simulate resumes rows from row 0's snapshots from this many rows on
     int32_t resume_wait_polls;  // ... in one launch, a row waiting at most so many polls for its snapshot; 0: in two launches
     hipEvent_t ev0, ev1;
@@ -92,6 +93,17 @@ struct SimParams {
     int32_t *snap_flags = nullptr;
     int32_t snap_wait_polls = 0;  // polls (about 3 us each) a candidate waits for its snapshot at most
     int32_t snap_cand = 0;        // the candidate whose wave writes the snapshots (row 0; the base order among moves)
+    // Explicit rows resumed from row 0 may also stop early: a row that differs from row 0 at positions
+    // diff_first[c] .. diff_last[c] only, and whose timeline is row 0's again behind them, stops at the
+    // 64-position boundary b behind diff_last[c] (b <= rejoin_blocks, the boundaries row 0 saves a state at) and
+    // writes b to rejoin_block[c] (INT_MAX: placed everything itself; 0: placed nothing); its tel_out is then
+    // relative to row 0's and its completion rounds from position 64 b on are row 0's.  The test needs row 0's
+    // start rounds by position, which the wave of row 0 stores in start0.
+    const int32_t *diff_first = nullptr;
+    const int32_t *diff_last = nullptr;
+    int32_t *rejoin_block = nullptr;
+    int32_t *start0 = nullptr;
+    int32_t rejoin_blocks = 0;
 };
 constexpr int KVS_STATE_HEAD_WORDS = 192;
 // the progress word of the snapshot hand-over: this many copies, this far apart (SimParams::snap_flags)
@@ -162,7 +174,8 @@ constexpr int32_t KVS_PERMUTE_MAX_N = 15872;  // one row and its bitmap must fit
 // resume_block / row0 (or NULL): row c placed only the positions from 64 resume_block[c] on; the
 // completion rounds before them are row0[k], row 0's in position order
 int kvs_launch_permute_rows(const int32_t *orders, int32_t C, int32_t n, int32_t *completion, int64_t *tel_out,
-                            int32_t *d_words, const int32_t *resume_block, const int32_t *row0, hipStream_t st);
+                            int32_t *d_words, const int32_t *resume_block, const int32_t *row0,
+                            const int32_t *rejoin_block, hipStream_t st);
 
 // horizon.hip
 int kvs_launch_apply_best_move(const int32_t *order, int32_t n, const int32_t *moves, const int64_t *result,
@@ -191,7 +204,10 @@ int kvs_launch_check_prefix(const int32_t *orders, int32_t C, int32_t n, int32_t
 int kvs_launch_broadcast_prefix(const int32_t *prefix, int32_t cp, int32_t C, int32_t n, int32_t *completion,
                                 hipStream_t st);
 // rows resumed from snapshots of row 0 (see SimParams)
-int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, hipStream_t st);
+int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, int32_t *diff_first,
+                             int32_t *diff_last, hipStream_t st);
+int kvs_launch_rejoin_finish(const int32_t *rejoin, int32_t C, int64_t *tel, hipStream_t st);
+int kvs_launch_stop_positions(const int32_t *rejoin, int32_t C, int32_t n, int32_t *stop_pos_out, hipStream_t st);
 // flags / nflags: words to clear on the way (the snapshot flags of the launch that follows), or NULL
 int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t first_row, int32_t *tmp, int32_t *sorted,
                               int32_t *flags, int32_t nflags, hipStream_t st);

@@ -52,7 +52,11 @@ __global__ __launch_bounds__(256) void broadcast_prefix_kernel(const int32_t *pr
 // timeline.  blocks[c] = number of leading 64-position blocks on which row c equals row 0, at
 // most (n - 1) / 64 so that something is left to place; 0 for row 0 itself, which is the row
 // that takes the snapshots.  One wavefront per row, reading stops at the first difference.
-__global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks)
+// With diff_first / diff_last the first and the last position at which the row differs from row 0
+// are found as well (the row is read from its end down to the last difference); both are -1 when
+// the row equals row 0 or the first difference was not looked for (it lies in the last block).
+__global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks,
+                                                            int32_t *diff_first, int32_t *diff_last)
 {
     const int lane = threadIdx.x & 63;
     const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -81,6 +85,43 @@ __global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *order
     }
 done:
     if (lane == 0) blocks[c] = nb;
+    if (!diff_first) return;
+    int first = -1, last = -1;
+    if (c > 0 && nb < cap) {
+        const int k = 64 * nb + lane;
+        const unsigned long long d = __builtin_amdgcn_ballot_w64(a[k] != b[k]);  // not zero: the scan stopped here
+        first = 64 * nb + (__ffsll((long long)d) - 1);
+        for (int top = (n - 1) >> 6; top >= nb; --top) {  // ends at block nb at the latest
+            const int kk = 64 * top + lane;
+            const unsigned long long e = __builtin_amdgcn_ballot_w64(kk < n && a[kk] != b[kk]);
+            if (e != 0) {
+                last = 64 * top + (63 - __clzll((long long)e));
+                break;
+            }
+        }
+    }
+    if (lane == 0) {
+        diff_first[c] = first;
+        diff_last[c] = last;
+    }
+}
+
+// Rows that stopped where their timeline had become row 0's again (rejoin[c] != INT_MAX) hold their
+// sum of completion rounds relative to row 0's: add row 0's (or pass on that row 0 could not be scheduled).
+__global__ __launch_bounds__(256) void rejoin_finish_kernel(const int32_t *rejoin, int32_t C, int64_t *tel)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C || c == 0 || rejoin[c] == INT_MAX) return;
+    const long long t0 = tel[0];
+    tel[c] = t0 < 0 ? -1 : tel[c] + t0;
+}
+
+// stop_pos_out[c] = position at which row c stopped placing (n: it placed its last position itself).
+__global__ __launch_bounds__(256) void stop_positions_kernel(const int32_t *rejoin, int32_t C, int32_t n, int32_t *stop_pos_out)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    stop_pos_out[c] = (rejoin && rejoin[c] != INT_MAX) ? 64 * rejoin[c] : n;
 }
 
 // The same count for the neighbours of a base order given as moves: a swap or an insertion of
@@ -207,9 +248,24 @@ __global__ __launch_bounds__(256) void resume_plan_kernel(const int32_t *sorted,
 
 }  // namespace
 
-int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, hipStream_t st)
+int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, int32_t *diff_first,
+                             int32_t *diff_last, hipStream_t st)
 {
-    hipLaunchKernelGGL(shared_blocks_kernel, dim3((unsigned)((C + 3) / 4)), dim3(256), 0, st, orders, C, n, blocks);
+    hipLaunchKernelGGL(shared_blocks_kernel, dim3((unsigned)((C + 3) / 4)), dim3(256), 0, st, orders, C, n, blocks,
+                       diff_first, diff_first ? diff_last : nullptr);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_rejoin_finish(const int32_t *rejoin, int32_t C, int64_t *tel, hipStream_t st)
+{
+    hipLaunchKernelGGL(rejoin_finish_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, rejoin, C, tel);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_stop_positions(const int32_t *rejoin, int32_t C, int32_t n, int32_t *stop_pos_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(stop_positions_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, rejoin, C, n,
+                       stop_pos_out);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 

@@ -658,6 +658,31 @@ __device__ __forceinline__ int snapshot_wait(const int32_t *progress, int rb, in
     return rb;
 }
 
+// The number of snapshots published so far, read once without waiting (the reader's side of the same
+// hand-over: what the writer stored before publishing them may be loaded afterwards).
+template <int NR>
+__device__ __forceinline__ int progress_peek(const int32_t *progress, int copy)
+{
+    int f, voff, v;
+#define KVS_STMT(CLOB, ASC, DESC, SCLOB)                                                                                 \
+    asm volatile("s_lshl_b32 %[f], %[copy], 6\n"                                                                  \
+                 "v_mov_b32 %[voff], %[f]\n"                                                                      \
+                 "global_load_dword %[v], %[voff], %[base] sc1\n"                                                 \
+                 "s_waitcnt vmcnt(0)\n"                                                                           \
+                 "v_readfirstlane_b32 %[f], %[v]\n"                                                               \
+                 "s_cmp_lt_i32 %[f], 0\n"                                                                         \
+                 "s_cbranch_scc0 1f\n"                                                                            \
+                 "s_not_b32 %[f], %[f]\n" /* the writer has stopped: what it published before */                  \
+                 "1:\n"                                                                                           \
+                 "buffer_inv sc1\n"                                                                               \
+                 : [f] "=&s"(f), [voff] "=&v"(voff), [v] "=&v"(v)                                                 \
+                 : [base] "s"(progress), [copy] "s"(copy)                                                         \
+                 : "scc", "memory", CLOB)
+    KVS_FOR_NR(KVS_STMT);
+#undef KVS_STMT
+    return f;
+}
+
 // One int32 of a snapshot's head through the vector unit (the scalar cache takes no part in the
 // hand-over above).
 template <int NR>
@@ -713,6 +738,41 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         k_first = 0;
         state_in = nullptr;
     }
+    const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
+    // Rejoining row 0.  A row that differs from row 0 only at positions i..j holds the same requests
+    // there in another order.  If row 0 starts the requests of positions i - 1 .. j in one and the same
+    // round (start rounds never decrease along the order, so the two ends tell; for i = 0: in round 0),
+    // then so does this row: none of them can start before the request at position i - 1, and each fits
+    // that round beside any part of the others, since all of them do.  From position j + 1 on the two
+    // timelines are the same, and this row need not place what row 0 places anyway: it stops at the
+    // 64-position boundary behind j (or does not start at all, when row 0 is already past it), reports
+    // the boundary, and leaves its sum of completion rounds relative to row 0's; a later pass adds row
+    // 0's sum and takes the completion rounds from there on from row 0.
+    int rejoin_k = -1;  // the boundary, as a position
+    if (RES && !MOVES && p.rejoin_block) {
+        if (lane == 0) p.rejoin_block[cand] = INT_MAX;
+        if (cand != p.snap_cand && p.k_end == 0) {
+            const int j = scalar_read(p.diff_last, cand);
+            if (j >= 0 && (j >> 6) + 1 <= p.rejoin_blocks) rejoin_k = 64 * ((j >> 6) + 1);
+        }
+    }
+    const int peek_copy = wave_no & (KVS_PROGRESS_COPIES - 1);
+    // (row 0 has published the boundary's snapshot, hence its start rounds before the boundary too)
+    auto rest_is_row0 = [&](int boundary_block) __attribute__((always_inline)) -> bool {  // (a call would not know of the register block)
+        const int avail = ONE ? progress_peek<NR>(p.snap_flags, peek_copy) : p.rejoin_blocks;
+        if (avail < boundary_block) return false;
+        const int i = scalar_read(p.diff_first, cand), j = scalar_read(p.diff_last, cand);
+        const int at_j = snapshot_word<NR>(p.start0, j);
+        const int before_i = i > 0 ? snapshot_word<NR>(p.start0, i - 1) : 0;
+        return at_j == before_i;
+    };
+    if (rejoin_k >= 0 && rest_is_row0(rejoin_k >> 6)) {  // nothing to place at all
+        if (lane == 0) {
+            p.rejoin_block[cand] = 0;
+            if (p.tel_out) p.tel_out[cand] = 0;
+        }
+        return;
+    }
     if (RES && p.resume_block) {
         const int planned = scalar_read(p.resume_block, cand);
         // ONE: taken in this very launch: wait for it, within bounds
@@ -724,7 +784,6 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         }
     }
     const bool takes_snapshots = RES && p.snap_blocks > 0 && cand == p.snap_cand;
-    const int n = p.k_end > 0 ? p.k_end : n_all;  // one past the last position placed here
     int b64 = 0;             // round of lane 0 of register 0: 64 * floor((t + 1) / 64)
     int t = 0;               // start round of the previous request in the order
     long long tel_lane = 0;  // completion rounds summed per lane; added up over the lanes at the end
@@ -754,7 +813,15 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
             ov_n = p.o[rq_n];
         }
     }
-    for (int k0 = k_first; k0 < n; k0 += WAVE) {
+    int n_stop = n;  // (the loop has one way out: the kernel's assembly operands stay scalar that way)
+    for (int k0 = k_first; k0 < n_stop; k0 += WAVE) {
+        if (RES && !MOVES && k0 == rejoin_k && rest_is_row0(k0 >> 6)) {  // the state is row 0's after k0 positions
+            const int32_t *snap = p.snapshots + (size_t)((k0 >> 6) - 1) * (size_t)p.snap_stride;
+            tel_lane -= ((const long long *)(snap + 64))[lane];
+            if (lane == 0) p.rejoin_block[cand] = k0 >> 6;
+            n_stop = 0;
+            continue;
+        }
         if (takes_snapshots && k0 > 0 && (k0 >> 6) <= p.snap_blocks) {  // the state after k0 positions
             int32_t *snap = p.snapshots + (size_t)((k0 >> 6) - 1) * (size_t)p.snap_stride;
             state_head_store<NR>(snap, b64, t, tel_lane, lane);
@@ -786,9 +853,11 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         }
         // the up to 64 requests of this block, one after the other (place_block returns the lanes' start
         // rounds); cv: completion round of this lane's position
-        const int cv = (k >= k0 ? ov : 0) + place_block<NR>(cnt, M - sv, ov, lane, vmin, M, t, b64);
+        const int pv = place_block<NR>(cnt, M - sv, ov, lane, vmin, M, t, b64);
+        const int cv = (k >= k0 ? ov : 0) + pv;
         tel_lane += cv;
         if (crow && k >= k0) crow[p.completion_by_position ? k : rq] = cv;
+        if (RES && !MOVES && takes_snapshots && p.start0 && k >= k0) p.start0[k] = pv;  // (published with the next snapshot)
     }
     if (p.state_out) {
         state_head_store<NR>(p.state_out, b64, t, tel_lane, lane);
@@ -806,7 +875,9 @@ int launch_reg(const SimParams &p, hipStream_t st)
     if (p.src.moves && p.cand_list && p.snap_flags)  // moves against a base order, resumed from the base order's states
         hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true, true, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     else if (p.src.orders && p.cand_list && p.snap_flags)
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+        // (rows of very different length, many of which stop early: a workgroup of one wavefront gives its
+        // place to the next as soon as it ends)
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, 1, false, true, true>), dim3((unsigned)p.C), dim3(WAVE), 0, st, p);
     else if (p.src.orders && p.cand_list)
         hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
     else if (p.src.orders)

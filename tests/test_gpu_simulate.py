@@ -350,6 +350,66 @@ def test_rows_resumed_from_row0_snapshots(ctx, resume_from_2048_rows, cfg, n, C,
     _assert_equal(tel_p, comp_p, tel_g, comp_g, "with and without resuming")
 
 
+def _stop_positions(ctx, C, n):
+    import torch
+
+    pos = ctx.simulate_stop_positions(C, n)
+    torch.cuda.synchronize()
+    return pos.cpu().numpy()
+
+
+@pytest.mark.parametrize("cfg,n,C,completions", [(3, 1500, 4000, True), (3, 900, 2500, False), (2, 700, 3000, True),
+                                                 (5, 1300, 2600, True)])
+def test_rows_that_rejoin_row0_stop_early(ctx, resume_from_2048_rows, cfg, n, C, completions):
+    # Rows that differ from row 0 inside a short stretch i..j only (a swap, an insertion, a shuffled
+    # segment).  Where row 0 starts the requests of positions i-1..j in one round, such a row's timeline
+    # is row 0's again behind j and the library stops placing it there; everywhere else it must not.
+    # Either way results equal the oracle's, which places every position of every row.
+    inst = workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    rng = np.random.default_rng(500 + cfg + n)
+    rows = np.broadcast_to(base, (C, n)).copy()
+    for c in range(1, C):
+        kind = c % 6
+        i = int(rng.integers(0, n - 1)) if kind else 0
+        j = min(n - 1, i + int(rng.integers(1, 250)))
+        if kind in (0, 1, 2):
+            rows[c, i], rows[c, j] = rows[c, j], rows[c, i]
+        elif kind == 3:
+            rows[c, i:j + 1] = np.roll(rows[c, i:j + 1], 1)  # position j inserted before position i
+        elif kind == 4:
+            rows[c, i:j + 1] = rng.permutation(rows[c, i:j + 1])
+        else:
+            rows[c, i:j + 1] = rows[c, i:j + 1][::-1]
+    print(f"rejoin: config {cfg} n={n} C={C}", flush=True)
+    tel_o, comp_o = oracle.simulate_many(inst.s, inst.o, inst.M, rows, literal=False)
+    p0, _, _ = oracle.simulate(inst.s, inst.o, inst.M, base, literal=False)
+    start0 = p0[base]  # row 0's start rounds by position
+    differs = rows != base[None, :]
+    first = np.where(differs.any(axis=1), differs.argmax(axis=1), n)
+    last = np.where(differs.any(axis=1), n - 1 - differs[:, ::-1].argmax(axis=1), -1)
+    stopped_any = 0
+    for polls in (4096, 1, 0):  # one launch; rows that do not wait for row 0; two launches
+        ctx.set_resume_one_launch(polls)
+        tel_g, comp_g, status = _gpu_simulate(ctx, inst.s, inst.o, inst.M, rows, completions=completions)
+        stop = _stop_positions(ctx, C, n)
+        pos = _resume_positions(ctx, C)
+        assert status == 0
+        _assert_equal(tel_g, comp_g, tel_o, comp_o if completions else None, f"rejoin config {cfg}, wait_polls={polls}")
+        early = stop < n
+        # a row stops only on a 64-position boundary behind its last difference (or places nothing at all),
+        # and only where the condition on row 0's start rounds holds
+        assert (stop[early] % 64 == 0).all() and ((stop[early] > last[early]) | (stop[early] == 0)).all()
+        assert (last[early] >= 0).all() and not early[0]
+        before = np.where(first[early] > 0, start0[np.maximum(first[early] - 1, 0)], 0)
+        assert (start0[last[early]] == before).all()
+        assert (pos[early & (stop > 0)] <= first[early & (stop > 0)]).all()
+        stopped_any = max(stopped_any, int(early.sum()))
+    ctx.set_resume_one_launch(4096)
+    assert stopped_any >= 50, stopped_any  # (the case is there: config 3 and 5 stop hundreds of rows, config 2 some tens)
+
+
+
 def test_resume_with_short_decode_lengths(ctx, resume_from_2048_rows):
     # decode lengths up to 200: the smallest register file of the timeline kernel (the other
     # resume cases run the two larger ones), under the three hand-over settings
