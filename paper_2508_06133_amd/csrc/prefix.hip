@@ -64,34 +64,30 @@ __global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *order
     const int32_t *a = orders;
     const int32_t *b = orders + (size_t)c * (size_t)n;
     const int cap = (n - 1) >> 6;
-    int nb = 0;
+    int nb = 0, first = -1, last = -1;
     if (c > 0) {
         // four blocks a turn: the loads of a turn are in flight together, the turns are a dependent chain
-        for (; nb + 4 <= cap; nb += 4) {
-            const int k = 64 * nb + lane;  // < n: blocks below cap are complete
-            const bool d0 = a[k] != b[k], d1 = a[k + 64] != b[k + 64], d2 = a[k + 128] != b[k + 128],
-                       d3 = a[k + 192] != b[k + 192];
-            const bool e0 = __builtin_amdgcn_ballot_w64(d0) != 0, e1 = __builtin_amdgcn_ballot_w64(d1) != 0,
-                       e2 = __builtin_amdgcn_ballot_w64(d2) != 0, e3 = __builtin_amdgcn_ballot_w64(d3) != 0;
-            if (e0 | e1 | e2 | e3) {
-                nb += e0 ? 0 : e1 ? 1 : e2 ? 2 : 3;
-                goto done;
+        while (nb < cap && first < 0) {
+            unsigned long long d[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = 64 * (nb + u) + lane;  // < n where nb + u < cap: blocks below cap are complete
+                d[u] = __builtin_amdgcn_ballot_w64(nb + u < cap && a[k] != b[k]);
             }
-        }
-        for (; nb < cap; ++nb) {
-            const int k = 64 * nb + lane;
-            if (__builtin_amdgcn_ballot_w64(a[k] != b[k]) != 0) break;
+            int same = min(4, cap - nb);
+#pragma unroll
+            for (int u = 3; u >= 0; --u)
+                if (d[u] != 0) same = u;
+            if (same < 4 && nb + same < cap) first = 64 * (nb + same) + (__ffsll((long long)d[same & 3]) - 1);
+            nb += same;
         }
     }
-done:
     if (lane == 0) blocks[c] = nb;
     if (!diff_first) return;
-    int first = -1, last = -1;
-    if (c > 0 && nb < cap) {
-        const int k = 64 * nb + lane;
-        const unsigned long long d = __builtin_amdgcn_ballot_w64(a[k] != b[k]);  // not zero: the scan stopped here
-        first = 64 * nb + (__ffsll((long long)d) - 1);
-        for (int top = (n - 1) >> 6; top >= nb; --top) {  // ends at block nb at the latest
+    if (first >= 0) {
+        // from the end down (block by block: what is read beyond the last difference is read for nothing,
+        // and this kernel is bound by what it reads); ends at block nb at the latest
+        for (int top = (n - 1) >> 6; top >= nb; --top) {
             const int kk = 64 * top + lane;
             const unsigned long long e = __builtin_amdgcn_ballot_w64(kk < n && a[kk] != b[kk]);
             if (e != 0) {
