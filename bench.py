@@ -621,7 +621,18 @@ def bench_horizon(args, ctx, dev) -> int:
         order_g, comp_g, log = run(timed=timed)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    _, _, log = run(keep_completion=True)  # the same run once more, untimed, keeping every chosen timeline for the accounts
+
+    class Accounted:  # the context, recording where the library stopped placing each move's timeline
+        def __init__(self):
+            self.stops = []
+
+        def horizon_step(self, *a, **kw):
+            out = ctx.horizon_step(*a, **kw)
+            self.stops.append(ctx.neighbor_stop_positions(K, n).cpu().numpy().astype(np.int64))
+            return out
+
+    accounted = Accounted()
+    _, _, log = run(keep_completion=True, timed=accounted)  # the same run once more, untimed, keeping every chosen timeline for the accounts
     status = ctx.device_status()
     if status != 0:
         print(f"bench.py: device status {status}", file=sys.stderr)
@@ -642,6 +653,7 @@ def bench_horizon(args, ctx, dev) -> int:
     window = 0   # rounds of the windows themselves: each inspected once and updated once
     hbm_bytes = 0
     kept_prefix = 0
+    stops_seen = []  # per re-plan: moves not placed to their end
     for rec in log:
         moves = workloads.window_moves(rng, K, rec["lo"], rec["hi"])
         touched = np.minimum(moves[:, 1], moves[:, 2])
@@ -662,8 +674,12 @@ def bench_horizon(args, ctx, dev) -> int:
             first = np.where(ident, (n - 1) // 64 * 64, touched // 64 * 64).astype(np.int64)
             first = np.concatenate([first, [0]])  # the order as it stands runs from the start and saves the states
         t_first = np.where(first > 0, start[np.maximum(first - 1, 0)], 0)
-        waited += int((start[-1] - t_first).sum())
-        window += int((cum[n] - cum[first]).sum())
+        # a move whose timeline became the order's own again was placed up to there only, or not at all
+        stop = np.maximum(np.concatenate([accounted.stops[len(stops_seen)], [n]]), first)
+        stops_seen.append(int((stop < n).sum()))
+        t_end = np.where(stop < n, np.where(stop > first, start[np.maximum(stop - 1, 0)], t_first), start[-1])
+        waited += int((t_end - t_first).sum())
+        window += int((cum[stop] - cum[first]).sum())
         # ... and the chosen order once more, from the common prefix's state on where there is one
         chosen_first = lowest if lowest >= 64 else 0
         waited += int(start[-1] - (start[chosen_first - 1] if chosen_first > 0 else 0))
@@ -695,7 +711,8 @@ def bench_horizon(args, ctx, dev) -> int:
         "roofline": roofline_object(f"timeline_reg_kernel<{reg_rows(o_max)},4,true,...> (the candidates' launch of each re-plan)",
                                     (waited + window) * args.steps, window * args.steps, kernel_ms_total, launches,
                                     "config4", hbm_bytes * args.steps,
-                                    {"note": "visits credited from each candidate's start point (common prefix or saved "
+                                    {"moves_stopped_early": int(sum(stops_seen)),
+                                     "note": "visits credited from each candidate's start point (common prefix or saved "
                                              "state of its block) on; the chosen timeline's start rounds stand in for the "
                                              "candidates' own"}),
     }

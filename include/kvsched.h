@@ -214,6 +214,13 @@ int kvsched_simulate_resume_positions(kvsched_ctx *ctx, int32_t C, int32_t *resu
  * 0 = it placed nothing: the whole timeline is row 0's).  C and n must be that call's; same validity. */
 int kvsched_simulate_stop_positions(kvsched_ctx *ctx, int32_t C, int32_t n, int32_t *stop_pos_out, void *stream);
 
+/* The same for the moves of the LAST kvsched_best_neighbor / kvsched_horizon_step call on this context
+ * (not kvsched_best_neighbor_static): stop_pos_out[m] (device, [K] int32) = the position before which the
+ * timeline of move m stopped being placed because it had become the base order's again (n = placed to its
+ * end; 0 = not placed at all: the move only reorders requests the base order starts in one round, or
+ * changes nothing).  K and n must be that call's; same validity. */
+int kvsched_neighbor_stop_positions(kvsched_ctx *ctx, int32_t K, int32_t n, int32_t *stop_pos_out, void *stream);
+
 /*
  * Phase 1 of Algorithm 1 ("Batch Construction") with the batch chosen among the feasible
  * prefixes of the remaining requests sorted by (s_i + o_i, o_i, i): for every feasible prefix
@@ -311,7 +318,12 @@ int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t 
  * there; otherwise, with enough moves and positions (kvsched_set_resume_min_rows, with the moves
  * counted as rows), the base order's timeline saves its state every 64 positions and a move on
  * positions i, j starts from the last state before min(i, j) (handed over within the launch, see
- * kvsched_set_resume_one_launch).  Results are the same.
+ * kvsched_set_resume_one_launch).  And a move that only reorders requests which the base order
+ * starts in one and the same round (see kvsched_simulate) gives the base order's timeline: behind
+ * a common prefix the base order is placed once more through the last position any move touches and
+ * such moves are not run at all; a timeline started from a saved state stops at the 64-position
+ * boundary behind max(i, j) once the base order's timeline has got there.  Results are the same;
+ * kvsched_neighbor_stop_positions() tells which moves were cut short.
  */
 int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n,
                           const int32_t *moves, int32_t K, const int32_t *s, const int32_t *o,
@@ -329,7 +341,7 @@ int kvsched_best_neighbor(kvsched_ctx *ctx, const int32_t *base_order, int32_t n
  *   - o_max_bound (1..KVSCHED_MAX_O) is the caller's bound on the decode lengths, as for
  *     kvsched_set_o_max (a longer one is reported as KVSCHED_DEV_O_MAX, tel = -1), in place of the
  *     length scan's read-back;
- *   - ERANGE when the working memory needed, about 20 (K + 1) + (768 + 256 R) floor((n - 1) / 64) +
+ *   - ERANGE when the working memory needed, about 24 (K + 1) + 4 n + (768 + 256 R) floor((n - 1) / 64) +
  *     64 KiB bytes with R = 9 / 33 / 65 / 129 / 225 for o_max_bound up to 512 / 2048 / 4096 / 8192 /
  *     14336, exceeds the array (K = 65536 moves with o_max_bound <= 4096 fit up to n = 16384
  *     positions), or the context's device number is 64 or more.

@@ -41,6 +41,7 @@ int ensure_scratch(kvsched_ctx *ctx, size_t bytes)
 {
     ctx->resume_rows = 0;  // whoever asks for scratch overwrites the last resume plan
     ctx->rejoin_offset = 0;
+    ctx->neighbor_stop_offset = 0;
     if (bytes <= ctx->scratch_bytes) return KVSCHED_OK;
     if (ctx->d_scratch) {
         // kernels of earlier calls may still be reading the old buffer
@@ -104,8 +105,9 @@ int32_t ring_slots_for(int32_t o_max)
 // length.  *o_bound_out is what the timeline kernels size their ring from.
 int scan_and_bound(kvsched_ctx *ctx, const int32_t *s, const int32_t *o, int32_t n, int64_t M, hipStream_t st,
                    int32_t *o_bound_out, const int32_t *moves = nullptr, int32_t K = 0,
-                   int32_t *min_position_out = nullptr)
+                   int32_t *min_position_out = nullptr, int32_t *max_position_out = nullptr)
 {
+    if (max_position_out) *max_position_out = n - 1;
     int rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, ctx->o_max_bound, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
     if (min_position_out) *min_position_out = 0;
@@ -128,6 +130,10 @@ int scan_and_bound(kvsched_ctx *ctx, const int32_t *s, const int32_t *o, int32_t
         const int32_t mp = ctx->h_words[KVS_W_MINPOS];
         *min_position_out = (mp < 0 || mp > n) ? 0 : mp;  // INT_MAX: no move changes the order
         if (mp == INT32_MAX) *min_position_out = n;
+        if (max_position_out) {
+            const int32_t top = ctx->h_words[KVS_W_MAXPOS];
+            *max_position_out = (top < 0 || top >= n) ? n - 1 : top;
+        }
     }
     return KVSCHED_OK;
 }
@@ -289,6 +295,8 @@ int kvsched_create(kvsched_ctx **out, int device_id)
     ctx->timed = 0;
     ctx->resume_rows = 0;
     ctx->rejoin_offset = 0;
+    ctx->neighbor_stop_offset = 0;
+    ctx->neighbor_moves = 0;
     ctx->resume_first = 0;
     ctx->resume_min_rows = KVSCHED_RESUME_AUTO;
     ctx->resume_wait_polls = kResumeWaitPollsDefault;
@@ -547,7 +555,7 @@ int kvsched_simulate(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t
             if (rc != KVSCHED_OK) return rc;
         }
         if (rejoin) {
-            rc = kvs_launch_rejoin_finish(rejoin_block, C, tel_out, st);
+            rc = kvs_launch_rejoin_finish(rejoin_block, C, 0, tel_out, st);
             if (rc != KVSCHED_OK) return rc;
             rejoined = rejoin_block;
             ctx->rejoin_offset = (size_t)((char *)rejoin_block - (char *)ctx->d_scratch);
@@ -731,9 +739,10 @@ int kvsched_phase1_G(kvsched_ctx *ctx, int32_t solver, int32_t n, const int32_t 
     }
 }
 
-// Scratch of kvsched_best_neighbor: K + 1 latencies, the state of a shared prefix, and the plan for
-// resuming each move's timeline from the base order's (three lists of K + 1 entries, a flag and a saved
-// state of the largest kind per 64 positions).
+// Scratch of kvsched_best_neighbor: K + 1 latencies, the state of a shared prefix, where each move's timeline
+// stopped because it had become the base order's again (K + 1 entries) with the base order's start rounds (n),
+// and the plan for resuming each move's timeline from the base order's (three lists of K + 1 entries, a flag
+// and a saved state of the largest kind per 64 positions).
 namespace {
 // o_bound: the caller's bound on the decode lengths if there is one (it fixes the size of a saved state), else 0.
 size_t neighbor_scratch_bytes(int32_t K, int32_t n, int32_t o_bound)
@@ -743,8 +752,8 @@ size_t neighbor_scratch_bytes(int32_t K, int32_t n, int32_t o_bound)
                          : o_bound > 0           ? (size_t)kvs_reg_state_words(o_bound)
                                                  : KVS_STATE_MAX_WORDS;
     return align256(sizeof(int64_t) * ((size_t)K + 1)) + state_bytes() +
-           3 * align256(sizeof(int32_t) * ((size_t)K + 1)) + align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) +
-           align256(sizeof(int32_t) * nblk * words);
+           4 * align256(sizeof(int32_t) * ((size_t)K + 1)) + align256(sizeof(int32_t) * (size_t)n) +
+           align256(sizeof(int32_t) * KVS_PROGRESS_WORDS) + align256(sizeof(int32_t) * nblk * words);
 }
 }  // namespace
 
@@ -767,13 +776,19 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
     const size_t tel_bytes = align256(sizeof(int64_t) * ((size_t)K + 1));
     int64_t *tel = (int64_t *)work;
     int32_t *state = (int32_t *)((char *)work + tel_bytes);
-    int32_t o_bound = 0, min_pos = 0;
+    const size_t list_bytes_all = align256(sizeof(int32_t) * ((size_t)K + 1));
+    int32_t *rejoin_block = (int32_t *)((char *)work + tel_bytes + state_bytes());
+    int32_t *start0 = (int32_t *)((char *)work + tel_bytes + state_bytes() + list_bytes_all);
+    const size_t plan_offset = tel_bytes + state_bytes() + list_bytes_all + align256(sizeof(int32_t) * (size_t)n);
+    int32_t o_bound = 0, min_pos = 0, max_pos = n - 1;
+    bool stops_early = false;
+    ctx->neighbor_stop_offset = 0;
     int rc;
     if (o_bound_known > 0) {
         rc = kvs_launch_scan_lengths(s, o, n, (int32_t)M, o_bound_known, ctx->d_words, st);
         o_bound = o_bound_known;
     } else {
-        rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound, moves, K, &min_pos);
+        rc = scan_and_bound(ctx, s, o, n, M, st, &o_bound, moves, K, &min_pos, &max_pos);
     }
     if (rc != KVSCHED_OK) return rc;
     const int32_t H = ring_slots_for(o_bound);
@@ -817,6 +832,26 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
         p.k_begin = min_pos;
         p.state_in = state;
         if (prefix_len_out) *prefix_len_out = min_pos;
+        // A move that only reorders requests the base order starts in one and the same round changes no
+        // completion round (see the timeline kernel): the base order is placed once more, alone, through the last
+        // position any move touches, and the moves found to be of that kind are not run at all.
+        if (min_pos < n && max_pos >= min_pos) {
+            SimParams q = p;
+            q.src.orders = base_order;
+            q.src.base = nullptr;
+            q.src.moves = nullptr;
+            q.C = 1;
+            q.tel_out = nullptr;
+            q.k_end = max_pos + 1;
+            q.start0 = start0;  // (by position)
+            rc = kvs_launch_simulate_reg(q, st);
+            if (rc != KVSCHED_OK) return rc;
+            rc = kvs_launch_mark_noop_moves(moves, K, n, min_pos, max_pos + 1 - min_pos, start0 + min_pos, state,
+                                            rejoin_block, st);
+            if (rc != KVSCHED_OK) return rc;
+            p.skip = rejoin_block;
+            stops_early = true;
+        }
     } else if (keep) {
         ctx->hz_len = 0;
     }
@@ -828,7 +863,7 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
         const int32_t nblk = (n - 1) / WAVE_POSITIONS;
         const int32_t stride = kvs_reg_state_words(o_bound);
         const size_t list_bytes = align256(sizeof(int32_t) * (size_t)C);
-        char *plan = (char *)work + tel_bytes + state_bytes();
+        char *plan = (char *)work + plan_offset;
         int32_t *blocks = (int32_t *)plan;
         int32_t *sorted = (int32_t *)(plan + list_bytes);
         int32_t *tmp = (int32_t *)(plan + 2 * list_bytes);
@@ -846,6 +881,10 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
         p.snap_flags = flags;
         p.snap_wait_polls = ctx->resume_wait_polls;
         p.snap_cand = K;
+        p.rejoin_block = rejoin_block;  // a move's timeline stops where it has become the base order's again
+        p.start0 = start0;
+        p.rejoin_blocks = nblk;
+        stops_early = true;
         if (ctx->timing && hipEventRecord(ctx->ev0, st) != hipSuccess) return KVSCHED_EHIP;
         rc = kvs_launch_simulate_reg(p, st);
         if (rc == KVSCHED_OK && ctx->timing) {
@@ -856,6 +895,14 @@ static int best_neighbor_on(kvsched_ctx *ctx, void *work, int32_t o_bound_known,
         rc = run_timelines(ctx, p, H, st);
     }
     if (rc != KVSCHED_OK) return rc;
+    if (stops_early) {
+        rc = kvs_launch_rejoin_finish(rejoin_block, K + 1, K, tel, st);
+        if (rc != KVSCHED_OK) return rc;
+        if (work == ctx->d_scratch) {
+            ctx->neighbor_stop_offset = (size_t)((char *)rejoin_block - (char *)work);
+            ctx->neighbor_moves = K;
+        }
+    }
     rc = kvs_launch_check_moves(moves, K, n, tel, ctx->d_words, st);
     if (rc != KVSCHED_OK) return rc;
     rc = kvs_launch_check_orders(base_order, 1, n, tel + K, ctx->d_words, st);
@@ -1011,6 +1058,17 @@ int kvsched_simulate_stop_positions(kvsched_ctx *ctx, int32_t C, int32_t n, int3
     const int32_t *rejoin =
         ctx->rejoin_offset != 0 ? (const int32_t *)((const char *)ctx->d_scratch + ctx->rejoin_offset) : nullptr;
     return kvs_launch_stop_positions(rejoin, C, n, stop_pos_out, (hipStream_t)stream);
+}
+
+int kvsched_neighbor_stop_positions(kvsched_ctx *ctx, int32_t K, int32_t n, int32_t *stop_pos_out, void *stream)
+{
+    if (!ctx || !stop_pos_out || K < 1 || n < 1) return KVSCHED_EINVAL;
+    if (hipSetDevice(ctx->device) != hipSuccess) return KVSCHED_EHIP;
+    if (ctx->neighbor_stop_offset != 0 && K != ctx->neighbor_moves) return KVSCHED_EINVAL;
+    const int32_t *rejoin = ctx->neighbor_stop_offset != 0
+                                ? (const int32_t *)((const char *)ctx->d_scratch + ctx->neighbor_stop_offset)
+                                : nullptr;
+    return kvs_launch_stop_positions(rejoin, K, n, stop_pos_out, (hipStream_t)stream);
 }
 
 int kvsched_simulate_predicted(kvsched_ctx *ctx, const int32_t *orders, int32_t C, int32_t n, const int32_t *s,

@@ -16,7 +16,8 @@ enum {
     KVS_W_BESTK = 5,   // exact DP: best state of the batch in hand
     KVS_W_BESTM = 6,
     KVS_W_ESTMAX = 7,  // largest initial estimate (kvsched_simulate_predicted)
-    KVS_W_COUNT = 8
+    KVS_W_MAXPOS = 8,  // largest position any move touches (best_neighbor), -1: none
+    KVS_W_COUNT = 16
 };
 
 struct kvsched_ctx {
@@ -34,6 +35,8 @@ struct kvsched_ctx {
     int32_t resume_rows;   // rows of the last kvsched_simulate call if it resumed rows from snapshots, else 0
     int32_t resume_first;  // ... and how many of them (in sorted order) ran from the start
     size_t rejoin_offset;  // ... and where in the scratch buffer the blocks at which rows stopped early are (0: nowhere)
+    size_t neighbor_stop_offset;  // the same for the moves of the last kvsched_best_neighbor / kvsched_horizon_step call
+    int32_t neighbor_moves;       // ... and how many moves that call had
     int32_t resume_min_rows;  // kvsched_simulate resumes rows from row 0's snapshots from this many rows on
     int32_t resume_wait_polls;  // ... in one launch, a row waiting at most so many polls for its snapshot; 0: in two launches
     hipEvent_t ev0, ev1;
@@ -99,11 +102,16 @@ struct SimParams {
     // writes b to rejoin_block[c] (INT_MAX: placed everything itself; 0: placed nothing); its tel_out is then
     // relative to row 0's and its completion rounds from position 64 b on are row 0's.  The test needs row 0's
     // start rounds by position, which the wave of row 0 stores in start0.
+    // With moves the stretch is the move's own (positions min(i, j) .. max(i, j)) and diff_first / diff_last stay
+    // unset; the candidate whose timeline the others rejoin is snap_cand, the base order.
     const int32_t *diff_first = nullptr;
     const int32_t *diff_last = nullptr;
     int32_t *rejoin_block = nullptr;
-    int32_t *start0 = nullptr;
+    int32_t *start0 = nullptr;  // (a launch of one timeline that takes no snapshots stores its start rounds here too)
     int32_t rejoin_blocks = 0;
+    // Candidates with skip[c] != INT_MAX are not run at all: they are known to stop at block skip[c] (the
+    // encoding of rejoin_block; in practice 0, nothing to place); their tel_out is set to 0.
+    const int32_t *skip = nullptr;
 };
 constexpr int KVS_STATE_HEAD_WORDS = 192;
 // the progress word of the snapshot hand-over: this many copies, this far apart (SimParams::snap_flags)
@@ -206,8 +214,16 @@ int kvs_launch_broadcast_prefix(const int32_t *prefix, int32_t cp, int32_t C, in
 // rows resumed from snapshots of row 0 (see SimParams)
 int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_t *blocks, int32_t *diff_first,
                              int32_t *diff_last, hipStream_t st);
-int kvs_launch_rejoin_finish(const int32_t *rejoin, int32_t C, int64_t *tel, hipStream_t st);
+// tel[c] += tel[base] for the candidates that stopped early (rejoin[c] != INT_MAX), c != base
+int kvs_launch_rejoin_finish(const int32_t *rejoin, int32_t C, int32_t base, int64_t *tel, hipStream_t st);
 int kvs_launch_stop_positions(const int32_t *rejoin, int32_t C, int32_t n, int32_t *stop_pos_out, hipStream_t st);
+// Moves behind a common prefix of `first` positions whose timeline is the base order's: the move only reorders
+// requests that the base order starts in one round (start rounds of positions first .. first + count - 1 in
+// window_start, that of position first - 1 in word 1 of the prefix's state).  rejoin[m] = 0 for those (and for
+// moves that change nothing), INT_MAX for the others and for the base order itself (entry K).
+int kvs_launch_mark_noop_moves(const int32_t *moves, int32_t K, int32_t n, int32_t first, int32_t count,
+                               const int32_t *window_start, const int32_t *prefix_state, int32_t *rejoin,
+                               hipStream_t st);
 // flags / nflags: words to clear on the way (the snapshot flags of the launch that follows), or NULL
 int kvs_launch_sort_by_blocks(const int32_t *blocks, int32_t C, int32_t first_row, int32_t *tmp, int32_t *sorted,
                               int32_t *flags, int32_t nflags, hipStream_t st);

@@ -21,8 +21,34 @@ __global__ __launch_bounds__(256) void moves_min_position_kernel(const int32_t *
         if (ok && i != j) pos = min(i, j);
         if (!ok) pos = 0;  // malformed moves are clamped by the timeline kernel: no shared prefix
     }
-    for (int d = 32; d > 0; d >>= 1) pos = min(pos, __shfl_down(pos, d));
+    int top = -1;
+    if (m < K) top = min(max(max(moves[3 * (size_t)m + 1], moves[3 * (size_t)m + 2]), 0), n - 1);  // (as the timeline kernel clamps)
+    for (int d = 32; d > 0; d >>= 1) {
+        pos = min(pos, __shfl_down(pos, d));
+        top = max(top, __shfl_down(top, d));
+    }
     if ((threadIdx.x & 63) == 0 && pos != INT_MAX) atomicMin(&words[KVS_W_MINPOS], pos);
+    if ((threadIdx.x & 63) == 0 && top >= 0) atomicMax(&words[KVS_W_MAXPOS], top);
+}
+
+__global__ __launch_bounds__(256) void mark_noop_moves_kernel(const int32_t *moves, int32_t K, int32_t n, int32_t first,
+                                                              int32_t count, const int32_t *window_start,
+                                                              const int32_t *prefix_state, int32_t *rejoin)
+{
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m > K) return;
+    int r = INT_MAX;
+    if (m < K) {
+        const int i0 = min(max(moves[3 * (size_t)m + 1], 0), n - 1), j0 = min(max(moves[3 * (size_t)m + 2], 0), n - 1);
+        const int i = min(i0, j0), j = max(i0, j0);
+        if (i == j) {
+            r = 0;  // the base order itself
+        } else if (i >= first && j < first + count) {
+            const int before = i > first ? window_start[i - 1 - first] : (first > 0 ? prefix_state[1] : 0);
+            if (window_start[j - first] == before && (i > 0 || before == 0)) r = 0;
+        }
+    }
+    rejoin[m] = r;
 }
 
 // Rows that differ from row 0 inside the declared common prefix are faulty.
@@ -103,12 +129,13 @@ __global__ __launch_bounds__(256) void shared_blocks_kernel(const int32_t *order
 }
 
 // Rows that stopped where their timeline had become row 0's again (rejoin[c] != INT_MAX) hold their
-// sum of completion rounds relative to row 0's: add row 0's (or pass on that row 0 could not be scheduled).
-__global__ __launch_bounds__(256) void rejoin_finish_kernel(const int32_t *rejoin, int32_t C, int64_t *tel)
+// sum of completion rounds relative to row 0's (the base order's, among moves): add that (or pass on that it
+// could not be scheduled).
+__global__ __launch_bounds__(256) void rejoin_finish_kernel(const int32_t *rejoin, int32_t C, int32_t base, int64_t *tel)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C || c == 0 || rejoin[c] == INT_MAX) return;
-    const long long t0 = tel[0];
+    if (c >= C || c == base || rejoin[c] == INT_MAX) return;
+    const long long t0 = tel[base];
     tel[c] = t0 < 0 ? -1 : tel[c] + t0;
 }
 
@@ -252,9 +279,18 @@ int kvs_launch_shared_blocks(const int32_t *orders, int32_t C, int32_t n, int32_
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 
-int kvs_launch_rejoin_finish(const int32_t *rejoin, int32_t C, int64_t *tel, hipStream_t st)
+int kvs_launch_rejoin_finish(const int32_t *rejoin, int32_t C, int32_t base, int64_t *tel, hipStream_t st)
 {
-    hipLaunchKernelGGL(rejoin_finish_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, rejoin, C, tel);
+    hipLaunchKernelGGL(rejoin_finish_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, rejoin, C, base, tel);
+    return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
+}
+
+int kvs_launch_mark_noop_moves(const int32_t *moves, int32_t K, int32_t n, int32_t first, int32_t count,
+                               const int32_t *window_start, const int32_t *prefix_state, int32_t *rejoin,
+                               hipStream_t st)
+{
+    hipLaunchKernelGGL(mark_noop_moves_kernel, dim3((unsigned)(K / 256 + 1)), dim3(256), 0, st, moves, K, n, first, count,
+                       window_start, prefix_state, rejoin);
     return hipGetLastError() == hipSuccess ? KVSCHED_OK : KVSCHED_EHIP;
 }
 

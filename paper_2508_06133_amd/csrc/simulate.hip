@@ -138,6 +138,7 @@ __global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t *s, co
         words[KVS_W_STATUS] = flag;
         words[KVS_W_OMAX] = mx;
         words[KVS_W_MINPOS] = INT_MAX;
+        words[KVS_W_MAXPOS] = -1;
     }
 }
 

@@ -711,6 +711,10 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     const int wave_no = __builtin_amdgcn_readfirstlane(blockIdx.x * WPB + (threadIdx.x >> 6));
     if (wave_no >= p.C) return;
     const int cand = RES ? scalar_read(p.cand_list, wave_no) : wave_no;
+    if (p.skip && scalar_read(p.skip, cand) != INT_MAX) {  // known to be another candidate's timeline
+        if (threadIdx.x % WAVE == 0 && p.tel_out) p.tel_out[cand] = 0;  // (relative to that one's, as for a row that stops early)
+        return;
+    }
 
     const int n_all = p.n;
     const int M = p.M;
@@ -728,6 +732,9 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         rd.row = p.src.orders + (size_t)cand * (size_t)n_all;
         rd.mt = rd.mi = rd.mj = 0;
     }
+    // the stretch of positions a move changes (through the scalar unit, like everything the rows' control flow uses)
+    const int move_lo = MOVES ? __builtin_amdgcn_readfirstlane(min(rd.mi, rd.mj)) : 0;
+    const int move_hi = MOVES ? __builtin_amdgcn_readfirstlane(max(rd.mi, rd.mj)) : 0;
     int32_t *crow = p.completion_out ? p.completion_out + (size_t)cand * (size_t)n_all : nullptr;
 
     // positions [k_first, n) of the order are placed; the state after the first k_first ones
@@ -748,11 +755,12 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     // 64-position boundary behind j (or does not start at all, when row 0 is already past it), reports
     // the boundary, and leaves its sum of completion rounds relative to row 0's; a later pass adds row
     // 0's sum and takes the completion rounds from there on from row 0.
+    // (Among moves the stretch is the move's own, and row 0 stands for the base order.)
     int rejoin_k = -1;  // the boundary, as a position
-    if (RES && !MOVES && p.rejoin_block) {
+    if (RES && p.rejoin_block) {
         if (lane == 0) p.rejoin_block[cand] = INT_MAX;
         if (cand != p.snap_cand && p.k_end == 0) {
-            const int j = scalar_read(p.diff_last, cand);
+            const int j = MOVES ? move_hi : scalar_read(p.diff_last, cand);
             if (j >= 0 && (j >> 6) + 1 <= p.rejoin_blocks) rejoin_k = 64 * ((j >> 6) + 1);
         }
     }
@@ -761,7 +769,8 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     auto rest_is_row0 = [&](int boundary_block) __attribute__((always_inline)) -> bool {  // (a call would not know of the register block)
         const int avail = ONE ? progress_peek<NR>(p.snap_flags, peek_copy) : p.rejoin_blocks;
         if (avail < boundary_block) return false;
-        const int i = scalar_read(p.diff_first, cand), j = scalar_read(p.diff_last, cand);
+        const int i = MOVES ? move_lo : scalar_read(p.diff_first, cand);
+        const int j = MOVES ? move_hi : scalar_read(p.diff_last, cand);
         const int at_j = snapshot_word<NR>(p.start0, j);
         const int before_i = i > 0 ? snapshot_word<NR>(p.start0, i - 1) : 0;
         return at_j == before_i;
@@ -815,7 +824,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
     }
     int n_stop = n;  // (the loop has one way out: the kernel's assembly operands stay scalar that way)
     for (int k0 = k_first; k0 < n_stop; k0 += WAVE) {
-        if (RES && !MOVES && k0 == rejoin_k && rest_is_row0(k0 >> 6)) {  // the state is row 0's after k0 positions
+        if (RES && k0 == rejoin_k && rest_is_row0(k0 >> 6)) {  // the state is row 0's after k0 positions
             const int32_t *snap = p.snapshots + (size_t)((k0 >> 6) - 1) * (size_t)p.snap_stride;
             tel_lane -= ((const long long *)(snap + 64))[lane];
             if (lane == 0) p.rejoin_block[cand] = k0 >> 6;
@@ -857,7 +866,7 @@ __global__ __launch_bounds__(WAVE *WPB) void timeline_reg_kernel(SimParams p)
         const int cv = (k >= k0 ? ov : 0) + pv;
         tel_lane += cv;
         if (crow && k >= k0) crow[p.completion_by_position ? k : rq] = cv;
-        if (RES && !MOVES && takes_snapshots && p.start0 && k >= k0) p.start0[k] = pv;  // (published with the next snapshot)
+        if ((RES ? takes_snapshots : p.C == 1) && p.start0 && k >= k0) p.start0[k] = pv;  // (published with the next snapshot)
     }
     if (p.state_out) {
         state_head_store<NR>(p.state_out, b64, t, tel_lane, lane);
@@ -872,11 +881,11 @@ template <int NR, int WPB>
 int launch_reg(const SimParams &p, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((p.C + WPB - 1) / WPB);
+    // (Resumed timelines are of very different length and many stop early: a workgroup of one wavefront gives
+    // its place to the next as soon as it ends.)
     if (p.src.moves && p.cand_list && p.snap_flags)  // moves against a base order, resumed from the base order's states
-        hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, true, true, true>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);
+        hipLaunchKernelGGL((timeline_reg_kernel<NR, 1, true, true, true>), dim3((unsigned)p.C), dim3(WAVE), 0, st, p);
     else if (p.src.orders && p.cand_list && p.snap_flags)
-        // (rows of very different length, many of which stop early: a workgroup of one wavefront gives its
-        // place to the next as soon as it ends)
         hipLaunchKernelGGL((timeline_reg_kernel<NR, 1, false, true, true>), dim3((unsigned)p.C), dim3(WAVE), 0, st, p);
     else if (p.src.orders && p.cand_list)
         hipLaunchKernelGGL((timeline_reg_kernel<NR, WPB, false, true, false>), dim3(blocks), dim3(WAVE * WPB), 0, st, p);

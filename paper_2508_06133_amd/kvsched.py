@@ -56,6 +56,7 @@ def _load() -> ctypes.CDLL:
     lib.kvsched_simulate.argtypes = [vp, vp, i32, i32, vp, vp, i64, vp, vp, i32, vp]
     lib.kvsched_simulate_resume_positions.argtypes = [vp, i32, vp, vp]
     lib.kvsched_simulate_stop_positions.argtypes = [vp, i32, i32, vp, vp]
+    lib.kvsched_neighbor_stop_positions.argtypes = [vp, i32, i32, vp, vp]
     lib.kvsched_set_resume_min_rows.argtypes = [vp, i32]
     lib.kvsched_set_resume_one_launch.argtypes = [vp, i32]
     lib.kvsched_sortedF.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
@@ -189,6 +190,15 @@ class Context:
         rc = _lib.kvsched_simulate_stop_positions(self._h, int(C), int(n), out.data_ptr(), _stream())
         if rc != OK:
             raise KvschedError(rc, "kvsched_simulate_stop_positions")
+        return out
+
+    def neighbor_stop_positions(self, K: int, n: int, device="cuda:0"):
+        """-> [K] int32: position before which the timeline of each move of the last best_neighbor() /
+        horizon_step() call stopped being placed (n: placed to its end, 0: not placed at all)."""
+        out = torch.empty(int(K), dtype=torch.int32, device=device)
+        rc = _lib.kvsched_neighbor_stop_positions(self._h, int(K), int(n), out.data_ptr(), _stream())
+        if rc != OK:
+            raise KvschedError(rc, "kvsched_neighbor_stop_positions")
         return out
 
     def sortedF(self, s, o, M, tie_rule: int = TIE_LARGER, feas_mode: int = FEAS_SUM_OF_PEAKS, out=None):

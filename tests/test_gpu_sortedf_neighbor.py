@@ -219,6 +219,51 @@ def test_best_neighbor_moves_anywhere_resume_from_the_base_order(ctx, cfg, n, K,
         ctx.set_resume_one_launch(4096)
 
 
+@pytest.mark.parametrize("cfg,n", [(3, 1500), (4, 3000), (5, 1300)])
+def test_moves_that_only_reorder_requests_started_together_are_not_placed(ctx, cfg, n):
+    # A move that only reorders requests which the base order starts in one round changes no completion
+    # round, and the library does not place such a move's timeline (at all, or beyond the 64-position
+    # boundary behind the move): windows inside the base order's initial fill, across its end and behind
+    # it, behind a common prefix (first position >= 64: the base order is placed once more through the
+    # window to find its start rounds) and not (the moves' timelines start from the base order's saved
+    # states and look at its start rounds as it goes).  Latencies and the best move as the oracle's,
+    # which places every timeline in full; a timeline is cut short only where the condition holds.
+    inst = workloads.instance(cfg, n=n)
+    base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
+    p0, _, _ = oracle.simulate(inst.s, inst.o, inst.M, base, literal=False)
+    start0 = p0[base]
+    fill = int((start0 == 0).sum())  # positions of the initial fill
+    assert 200 < fill < n - 200, fill
+    K = 700
+    cut_short = placed_nothing = 0
+    try:
+        ctx.set_resume_min_rows(256)
+        for lo, hi in ((0, 300), (80, fill - 20), (fill - 150, fill + 150), (fill + 100, min(n, fill + 500)), (64, n)):
+            moves = workloads.window_moves(np.random.default_rng(cfg * 100 + lo), K, lo, hi)
+            print(f"moves among requests started together: config {cfg} n={n} fill={fill} window [{lo},{hi})", flush=True)
+            tel_o, res_o = oracle.best_neighbor(inst.s, inst.o, inst.M, base, moves, literal=False)
+            tel_g, res_g = _gpu_best(ctx, inst.s, inst.o, inst.M, base, moves)
+            assert (tel_g == tel_o).all() and res_g == res_o, (lo, hi)
+            assert ctx.device_status() == 0
+            import torch
+
+            stop = ctx.neighbor_stop_positions(K, n).cpu().numpy()
+            torch.cuda.synchronize()
+            i = np.minimum(moves[:, 1], moves[:, 2])
+            j = np.maximum(moves[:, 1], moves[:, 2])
+            together = start0[j] == np.where(i > 0, start0[np.maximum(i - 1, 0)], 0)
+            early = stop < n
+            assert (together | (i == j))[early].all(), (lo, hi)
+            assert ((stop[early] == 0) | ((stop[early] % 64 == 0) & (stop[early] > j[early]))).all()
+            if lo >= 64 and hi <= fill:
+                assert early.all(), (lo, hi)  # every move of a window inside the fill (behind a common prefix this does not depend on timing)
+            cut_short += int(early.sum())
+            placed_nothing += int((stop == 0).sum())
+    finally:
+        ctx.set_resume_min_rows(-1)
+    assert cut_short > K and placed_nothing > K // 2, (cut_short, placed_nothing)
+
+
 def test_best_neighbor_only_identity_moves(ctx):
     inst = workloads.instance(2, n=130)
     base, _, _ = oracle.sortedF(inst.s, inst.o, inst.M)
